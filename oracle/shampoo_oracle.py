@@ -1,0 +1,211 @@
+"""fp64 CPU oracle for the per-block Shampoo optimizer step.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+HIP path is checked against.  Only the test-suite, the smoke check and the
+benchmark's CPU-baseline leg may import it; the product path never does, and
+this module imports nothing from the product package.  It shares no code,
+tables or helpers with the HIP kernels.
+
+Everything is numpy float64.  Inputs given as float32 (or bf16 bits decoded
+to float32 by the caller) are widened exactly.  No blocking, fusion or
+reordering beyond what the paper's algorithm states.
+
+What is computed (paper: "Complete Distributed Shampoo Pseudocode", restricted
+to beta1 = 0, no weight decay, no Nesterov, AdaGrad grafting; identical to
+"Shampoo Pseudocode (with AdaGrad Grafting)" when beta2 = 1):
+
+  for every block (m x n) of every 2-D parameter, at iteration t (0-based):
+    1. L <- beta2 L + (1-beta2) G G^T,  R <- beta2 R + (1-beta2) G^T G
+       (plain sums when beta2 == 1; L = R = 0 initially)      [Sec. 3.1.1 EMA eqs]
+    2. A <- A + G*G elementwise (AdaGrad grafting state)       [Sec. 2.4]
+    3. if t >= start and t % f == 0:
+         Lbar <- rootinv(L), Rbar <- rootinv(R)                [Sec. 3.2.1 framed box]
+    4. P_graft = G / (sqrt(A) + eps_graft)                     [Sec. 2.4]
+    5. if t >= start: P = -||P_graft||_F * Lbar G Rbar / ||Lbar G Rbar||_F
+       else:          P = -P_graft                             [Sec. 2.4 grafting eq.]
+    6. M <- mu M + P ; P <- M   (only when mu > 0)             [Sec. 3.1.3 momentum eqs]
+    7. W <- W + lr * P
+  1-D parameters take steps 2, 4, P = -P_graft, 6, 7 (diagonal AdaGrad,
+  Sec. 2.2 / Sec. 4.2.2).
+
+Readings of the paper taken here (each also listed in the design notes):
+  * Factors start at zero and epsilon enters only inside the root-inverse
+    routine (the complete pseudocode + framed box), not as L_{-1} = eps*I.
+  * The EMA weight in the factor update is beta2 (the complete pseudocode
+    prints beta1 there while guarding on beta2 < 1; the text equations use
+    beta2).
+  * No bias correction.
+  * Grafting norms are taken per block (each block owns its grafting object,
+    App. E class structure).
+  * The grafting branch before start_preconditioning_step uses P = -P_graft
+    (sign consistent with W <- W + lr P).
+  * Momentum recursion is M_t = mu M_{t-1} + P_t.
+  * If ||P_shampoo||_F == 0 or ||P_graft||_F == 0 the block's P is zero.
+
+Pins: see tests/test_oracle_pins.py (Kronecker brute force, X^4 (L+eps I) = I,
+diagonal closed forms, polar factor at t = 0, textbook AdaGrad, geometric
+momentum, trace identities, independent Jacobi eigensolver).
+"""
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# Blocking (Sec. 4.2.1 "Merging and Blocking": k_m = ceil(m/b), k_n = ceil(n/b),
+# full b x b blocks except the last block row / column, which hold the rest).
+# ----------------------------------------------------------------------------
+def block_partition(rows, cols, b):
+    """Return the list of (row0, col0, m, n) blocks of a rows x cols matrix."""
+    if rows <= 0 or cols <= 0 or b <= 0:
+        raise ValueError("bad shape or block size")
+    km = -(-rows // b)
+    kn = -(-cols // b)
+    blocks = []
+    for i in range(km):
+        for j in range(kn):
+            r0 = i * b
+            c0 = j * b
+            blocks.append((r0, c0, min(b, rows - r0), min(b, cols - c0)))
+    return blocks
+
+
+# ----------------------------------------------------------------------------
+# Stage functions
+# ----------------------------------------------------------------------------
+def factor_update(L, R, G, beta2):
+    """Kronecker factor accumulation, Sec. 3.1.1 EMA equations / pseudocode."""
+    G = np.asarray(G, dtype=np.float64)
+    GGt = G @ G.T
+    GtG = G.T @ G
+    if beta2 < 1.0:
+        return beta2 * L + (1.0 - beta2) * GGt, beta2 * R + (1.0 - beta2) * GtG
+    return L + GGt, R + GtG
+
+
+def graft_state_update(A, G):
+    """AdaGrad grafting state: running sum of squared gradients (Sec. 2.4)."""
+    G = np.asarray(G, dtype=np.float64)
+    return A + G * G
+
+
+def graft_direction(G, A, eps_graft):
+    """P_graft = G / (A^{1/2} + eps_graft), elementwise (Sec. 2.4)."""
+    G = np.asarray(G, dtype=np.float64)
+    return G / (np.sqrt(A) + eps_graft)
+
+
+def root_inverse(F, epsilon, r):
+    """Framed box "Symmetric Eigendecomposition Approach for Computing Root
+    Inverse" (Sec. 3.2.1):
+        lambda, Q = eigh(F)
+        lambda_new = lambda - min(lambda_min, 0) + epsilon
+        return Q diag(lambda_new^{-r}) Q^T
+    Returns (root inverse, lambda).  numpy's LAPACK eigh is the library step.
+    """
+    F = np.asarray(F, dtype=np.float64)
+    lam, Q = np.linalg.eigh(F)
+    lam_min = lam.min()
+    lam_new = lam - min(lam_min, 0.0) + epsilon
+    X = (Q * lam_new ** (-r)) @ Q.T
+    return X, lam
+
+
+def shampoo_direction(Lbar, G, Rbar):
+    """P_shampoo = Lbar G Rbar (Sec. 2.3 Shampoo update)."""
+    return Lbar @ np.asarray(G, dtype=np.float64) @ Rbar
+
+
+def grafted_direction(P_sh, P_graft):
+    """P = -||P_graft||_F P_sh / ||P_sh||_F (Sec. 2.4); zero if either norm is zero."""
+    n_sh = np.sqrt(np.sum(P_sh * P_sh))
+    n_g = np.sqrt(np.sum(P_graft * P_graft))
+    if n_sh == 0.0 or n_g == 0.0:
+        return np.zeros_like(P_sh)
+    return -(n_g / n_sh) * P_sh
+
+
+# ----------------------------------------------------------------------------
+# Whole optimizer
+# ----------------------------------------------------------------------------
+class ShampooOracle:
+    """State and step of the optimizer for a list of 1-D / 2-D parameters.
+
+    shapes: list of tuples, (len,) or (rows, cols).
+    State per 2-D block: L, R, Lbar, Rbar; per element: A, M.  All float64.
+    """
+
+    def __init__(self, shapes, block_size, beta2, epsilon, root_exponent,
+                 precondition_frequency, start_preconditioning_step=0,
+                 graft_epsilon=1e-10, momentum=0.0):
+        self.shapes = [tuple(int(x) for x in s) for s in shapes]
+        self.b = int(block_size)
+        self.beta2 = float(beta2)
+        self.epsilon = float(epsilon)
+        self.r = float(root_exponent)
+        self.f = int(precondition_frequency)
+        self.start = int(start_preconditioning_step)
+        self.eps_g = float(graft_epsilon)
+        self.mu = float(momentum)
+        self.blocks = []      # per param: list of (r0, c0, m, n) (empty for 1-D)
+        self.L, self.R, self.Lbar, self.Rbar = [], [], [], []
+        self.A, self.M = [], []
+        self.P_sh = []        # last Shampoo direction per block (for inspection)
+        self.s_g, self.s_sh = [], []   # last squared norms per block
+        for s in self.shapes:
+            self.A.append(np.zeros(s))
+            self.M.append(np.zeros(s))
+            if len(s) == 2:
+                blks = block_partition(s[0], s[1], self.b)
+                self.blocks.append(blks)
+                self.L.append([np.zeros((m, m)) for (_, _, m, n) in blks])
+                self.R.append([np.zeros((n, n)) for (_, _, m, n) in blks])
+                # before the first refresh the previous root is the identity
+                self.Lbar.append([np.eye(m) for (_, _, m, n) in blks])
+                self.Rbar.append([np.eye(n) for (_, _, m, n) in blks])
+                self.P_sh.append([None] * len(blks))
+                self.s_g.append([0.0] * len(blks))
+                self.s_sh.append([0.0] * len(blks))
+            elif len(s) == 1:
+                self.blocks.append([])
+                for lst in (self.L, self.R, self.Lbar, self.Rbar, self.P_sh,
+                            self.s_g, self.s_sh):
+                    lst.append([])
+            else:
+                raise ValueError("only 1-D and 2-D parameters")
+
+    def step(self, params, grads, lr, t):
+        """One iteration t.  params: list of float64 arrays, updated in place.
+        grads: list of arrays (any float dtype; widened exactly)."""
+        refresh = (t >= self.start) and (t % self.f == 0)
+        for i, s in enumerate(self.shapes):
+            G = np.asarray(grads[i], dtype=np.float64)
+            W = params[i]
+            if len(s) == 1:
+                self.A[i] = graft_state_update(self.A[i], G)
+                P = -graft_direction(G, self.A[i], self.eps_g)
+                if self.mu > 0.0:
+                    self.M[i] = self.mu * self.M[i] + P
+                    P = self.M[i]
+                W += lr * P
+                continue
+            for k, (r0, c0, m, n) in enumerate(self.blocks[i]):
+                sl = (slice(r0, r0 + m), slice(c0, c0 + n))
+                Gb = G[sl]
+                self.L[i][k], self.R[i][k] = factor_update(
+                    self.L[i][k], self.R[i][k], Gb, self.beta2)
+                self.A[i][sl] = graft_state_update(self.A[i][sl], Gb)
+                if refresh:
+                    self.Lbar[i][k], _ = root_inverse(self.L[i][k], self.epsilon, self.r)
+                    self.Rbar[i][k], _ = root_inverse(self.R[i][k], self.epsilon, self.r)
+                Pg = graft_direction(Gb, self.A[i][sl], self.eps_g)
+                self.s_g[i][k] = float(np.sum(Pg * Pg))
+                if t >= self.start:
+                    Psh = shampoo_direction(self.Lbar[i][k], Gb, self.Rbar[i][k])
+                    self.P_sh[i][k] = Psh
+                    self.s_sh[i][k] = float(np.sum(Psh * Psh))
+                    P = grafted_direction(Psh, Pg)
+                else:
+                    P = -Pg
+                if self.mu > 0.0:
+                    self.M[i][sl] = self.mu * self.M[i][sl] + P
+                    P = self.M[i][sl]
+                W[sl] += lr * P

@@ -1,0 +1,378 @@
+"""Pins for the fp64 oracle: each test ties one part of oracle/shampoo_oracle.py
+to something fixed by the paper or by mathematics, written independently of the
+oracle's own formulae.  CPU only."""
+import numpy as np
+import pytest
+
+from oracle import shampoo_oracle as so
+from paper_2309_06497_amd import workloads as wl
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------------------
+# an eigensolver that is not LAPACK: cyclic Jacobi, plain loops (tiny n only)
+# ---------------------------------------------------------------------------
+def jacobi_eigh(A, sweeps=30):
+    A = np.array(A, dtype=np.float64)
+    n = A.shape[0]
+    V = np.eye(n)
+    for _ in range(sweeps):
+        off = 0.0
+        for p in range(n - 1):
+            for q in range(p + 1, n):
+                if abs(A[p, q]) < 1e-150:
+                    continue
+                off += A[p, q] ** 2
+                tau = (A[q, q] - A[p, p]) / (2.0 * A[p, q])
+                t = (1.0 if tau >= 0 else -1.0) / (abs(tau) + np.sqrt(1.0 + tau * tau))
+                c = 1.0 / np.sqrt(1.0 + t * t)
+                s = t * c
+                Rm = np.eye(n)
+                Rm[p, p] = c; Rm[q, q] = c; Rm[p, q] = s; Rm[q, p] = -s
+                A = Rm.T @ A @ Rm
+                V = V @ Rm
+        if off < 1e-300:
+            break
+    return np.diag(A).copy(), V
+
+
+# ---------------------------------------------------------------------------
+# Blocking  (Sec. 4.2.1)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,cols,b", [(256, 128, 64), (64, 147, 128), (2048, 1000, 128),
+                                         (5, 7, 3), (1, 1, 4), (130, 130, 128)])
+def test_block_partition_covers_once(rows, cols, b):
+    blks = so.block_partition(rows, cols, b)
+    assert len(blks) == -(-rows // b) * -(-cols // b)
+    cover = np.zeros((rows, cols), dtype=np.int32)
+    for (r0, c0, m, n) in blks:
+        assert 1 <= m <= b and 1 <= n <= b
+        # full blocks except in the last block row / column
+        if r0 + m < rows:
+            assert m == b
+        if c0 + n < cols:
+            assert n == b
+        cover[r0:r0 + m, c0:c0 + n] += 1
+    assert (cover == 1).all()
+
+
+def test_resnet50_block_histogram():
+    shapes = wl.resnet50_shapes()
+    two_d = [s for s in shapes if len(s) == 2]
+    one_d = [s for s in shapes if len(s) == 1]
+    assert len(two_d) == 54 and len(one_d) == 107
+    assert sum(wl.numel(s) for s in shapes) == 25_557_032
+    hist = {}
+    for (r, c) in two_d:
+        for (_, _, m, n) in so.block_partition(r, c, 128):
+            hist[(m, n)] = hist.get((m, n), 0) + 1
+    assert hist == {(128, 128): 1530, (64, 128): 17, (128, 104): 16, (128, 64): 8,
+                    (64, 64): 4, (64, 19): 1}
+
+
+def test_transformer_shapes():
+    shapes = wl.transformer_shapes()
+    two_d = [s for s in shapes if len(s) == 2]
+    assert sum(wl.numel(s) for s in two_d) == 1_207_959_552
+    nblk = sum(len(so.block_partition(r, c, 1024)) for (r, c) in two_d)
+    assert nblk == 1152
+    assert sum(wl.numel(s) for s in shapes if len(s) == 1) == 98 * 2048
+
+
+# ---------------------------------------------------------------------------
+# Root inverse  (Sec. 2.2 definition via eigendecomposition; Sec. 3.2.1 box)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,r", [(1, 0.25), (2, 0.25), (7, 0.25), (33, 0.25), (12, 0.5)])
+def test_root_inverse_power_identity(n, r):
+    g = rng(n).standard_normal((n, n + 3))
+    F = g @ g.T
+    eps = 1e-12
+    X, lam = so.root_inverse(F, eps, r)
+    assert np.allclose(X, X.T, rtol=0, atol=1e-12 * np.abs(X).max())
+    assert np.linalg.eigvalsh(X).min() > 0
+    p = int(round(1.0 / r))
+    Xp = np.linalg.matrix_power(X, p)
+    err = np.linalg.norm(Xp @ (F + eps * np.eye(n)) - np.eye(n)) / np.sqrt(n)
+    assert err < 1e-9
+    assert np.all(np.diff(lam) >= 0)
+
+
+def test_root_inverse_diagonal_closed_form():
+    d = np.array([4.0, 0.25, 9.0, 1e-3, 0.0])
+    eps = 1e-12
+    X, _ = so.root_inverse(np.diag(d), eps, 0.25)
+    assert np.allclose(X, np.diag((d + eps) ** -0.25), rtol=1e-13, atol=0)
+
+
+def test_root_inverse_negative_eigenvalue_shift():
+    # the box shifts by -min(lambda_min, 0): diag(-1, 3) -> lambda_new = (eps, 4 + eps)
+    eps = 1e-6
+    X, lam = so.root_inverse(np.diag([-1.0, 3.0]), eps, 0.25)
+    assert np.allclose(lam, [-1.0, 3.0])
+    assert np.allclose(X, np.diag([eps ** -0.25, (4.0 + eps) ** -0.25]), rtol=1e-12)
+    # and a non-negative spectrum is not shifted at all
+    X2, _ = so.root_inverse(np.diag([1.0, 3.0]), eps, 0.25)
+    assert np.allclose(X2, np.diag([(1 + eps) ** -0.25, (3 + eps) ** -0.25]), rtol=1e-12)
+
+
+def test_root_inverse_matches_independent_jacobi():
+    g = rng(5).standard_normal((9, 11))
+    F = g @ g.T
+    eps = 1e-9
+    X, lam = so.root_inverse(F, eps, 0.25)
+    lam_j, V = jacobi_eigh(F)
+    Xj = (V * (lam_j + eps) ** -0.25) @ V.T
+    assert np.allclose(np.sort(lam_j), lam, rtol=1e-11)
+    assert np.allclose(X, Xj, rtol=1e-9, atol=1e-12)
+
+
+def test_root_inverse_orthogonal_equivariance():
+    g = rng(6).standard_normal((8, 8))
+    F = g @ g.T
+    U, _ = np.linalg.qr(rng(7).standard_normal((8, 8)))
+    X, _ = so.root_inverse(F, 1e-9, 0.25)
+    XU, _ = so.root_inverse(U @ F @ U.T, 1e-9, 0.25)
+    assert np.allclose(XU, U @ X @ U.T, rtol=1e-9, atol=1e-11)
+
+
+# ---------------------------------------------------------------------------
+# Two-sided preconditioning vs the explicit Kronecker product (Sec. 1.2 vec
+# identities, Sec. 2.3): (L (x) R)^(-1/4) vec(G) = vec(L^(-1/4) G R^(-1/4)),
+# vec taken row-wise.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("m,n", [(3, 4), (5, 5), (4, 2), (1, 6)])
+def test_kronecker_brute_force(m, n):
+    r = rng(100 * m + n)
+    eps = 1e-3
+    L = np.zeros((m, m)); R = np.zeros((n, n))
+    for _ in range(3):
+        G = r.standard_normal((m, n))
+        L, R = so.factor_update(L, R, G, 1.0)
+    Lbar, _ = so.root_inverse(L, eps, 0.25)
+    Rbar, _ = so.root_inverse(R, eps, 0.25)
+    P = so.shampoo_direction(Lbar, G, Rbar)
+    # brute force with an eigensolver that is not LAPACK, on the mn x mn matrix
+    K = np.kron(L + eps * np.eye(m), R + eps * np.eye(n))
+    lam, V = jacobi_eigh(K)
+    Kroot = (V * lam ** -0.25) @ V.T
+    assert np.allclose(Kroot @ G.reshape(-1), P.reshape(-1), rtol=1e-8, atol=1e-10)
+
+
+def test_factor_update_definition_and_trace():
+    r = rng(3)
+    m, n = 6, 9
+    beta2 = 0.9
+    L = np.zeros((m, m)); R = np.zeros((n, n))
+    Ls = np.zeros((m, m)); Rs = np.zeros((n, n))
+    tr = 0.0; trs = 0.0
+    for t in range(5):
+        G = r.standard_normal((m, n)).astype(np.float32)
+        L, R = so.factor_update(L, R, G, beta2)
+        Ls, Rs = so.factor_update(Ls, Rs, G, 1.0)
+        g2 = float(np.sum(G.astype(np.float64) ** 2))
+        tr = beta2 * tr + (1 - beta2) * g2
+        trs += g2
+        # elementwise definition: L_ij = sum_k G_ik G_jk, R_ij = sum_k G_ki G_kj
+        assert np.isclose(np.trace(L), tr, rtol=1e-13)
+        assert np.isclose(np.trace(R), tr, rtol=1e-13)
+        assert np.isclose(np.trace(Ls), trs, rtol=1e-13)
+        assert np.isclose(np.trace(Rs), trs, rtol=1e-13)
+    assert L.shape == (m, m) and R.shape == (n, n)
+    assert np.allclose(L, L.T) and np.allclose(R, R.T)
+    assert np.linalg.eigvalsh(L).min() > -1e-12 * np.linalg.eigvalsh(L).max()
+    Gd = G.astype(np.float64)
+    L1, R1 = so.factor_update(np.zeros((m, m)), np.zeros((n, n)), G, 1.0)
+    ref_L = np.array([[sum(Gd[i, k] * Gd[j, k] for k in range(n)) for j in range(m)] for i in range(m)])
+    ref_R = np.array([[sum(Gd[k, i] * Gd[k, j] for k in range(m)) for j in range(n)] for i in range(n)])
+    assert np.allclose(L1, ref_L, rtol=1e-13) and np.allclose(R1, ref_R, rtol=1e-13)
+
+
+# ---------------------------------------------------------------------------
+# Whole-step closed forms
+# ---------------------------------------------------------------------------
+def make_opt(shapes, **kw):
+    args = dict(block_size=64, beta2=1.0, epsilon=1e-12, root_exponent=0.25,
+                precondition_frequency=1, start_preconditioning_step=0,
+                graft_epsilon=1e-10, momentum=0.0)
+    args.update(kw)
+    return so.ShampooOracle(shapes, **args)
+
+
+@pytest.mark.parametrize("m,n", [(6, 4), (4, 6), (5, 5)])
+def test_first_step_is_polar_factor(m, n):
+    """beta2 = 1, t = 0, full-rank G = U S V^T: L^(-1/4) G R^(-1/4) = U V^T, the
+    AdaGrad graft is sign(G), so W_1 = W_0 - lr sqrt(max(m, n)) U V^T."""
+    G = rng(m * 10 + n).standard_normal((m, n))
+    U, S, Vt = np.linalg.svd(G, full_matrices=False)
+    # rank-deficient side: the null space gets eps^(-1/4) but G has no component there
+    opt = make_opt([(m, n)], epsilon=1e-14)
+    W = [np.zeros((m, n))]
+    lr = 0.1
+    opt.step(W, [G], lr, 0)
+    expect = -lr * np.sqrt(max(m, n)) * (U @ Vt)
+    assert np.allclose(W[0], expect, rtol=1e-6, atol=1e-8)
+    assert np.isclose(opt.s_g[0][0], m * n, rtol=1e-8)
+    assert np.isclose(opt.s_sh[0][0], min(m, n), rtol=1e-6)
+
+
+def test_diagonal_gradients_reduce_to_adagrad():
+    """If every G_s is diagonal, L = R = diag(sum d^2) and Shampoo's direction is
+    d / sqrt(sum d^2), i.e. diagonal AdaGrad (App. B algebra)."""
+    n = 6
+    r = rng(11)
+    opt = make_opt([(n, n)], epsilon=1e-30, graft_epsilon=1e-30)
+    W = [np.zeros((n, n))]
+    w_ref = np.zeros(n); acc = np.zeros(n)
+    lr = 0.05
+    for t in range(6):
+        d = r.standard_normal(n) + 0.1
+        opt.step(W, [np.diag(d)], lr, t)
+        acc += d * d
+        w_ref -= lr * d / np.sqrt(acc)
+        assert np.allclose(np.diag(W[0]), w_ref, rtol=1e-9, atol=1e-12)
+        assert np.allclose(W[0] - np.diag(np.diag(W[0])), 0.0, atol=1e-12)
+
+
+def test_one_d_path_is_textbook_adagrad_with_momentum():
+    n = 37
+    r = rng(12)
+    mu, lr, eg = 0.9, 0.01, 1e-10
+    opt = make_opt([(n,)], momentum=mu, graft_epsilon=eg, precondition_frequency=10)
+    W = [r.standard_normal(n)]
+    w = W[0].copy(); a = np.zeros(n); mom = np.zeros(n)
+    for t in range(12):
+        g = (r.standard_normal(n) * 0.01).astype(np.float32)
+        opt.step(W, [g], lr, t)
+        for i in range(n):          # textbook loop, scalar by scalar
+            gi = float(g[i])
+            a[i] += gi * gi
+            mom[i] = mu * mom[i] - gi / (np.sqrt(a[i]) + eg)
+            w[i] += lr * mom[i]
+        assert np.array_equal(W[0], w)
+
+
+def test_grafting_norm_and_block_independence():
+    """||P||_F equals the AdaGrad direction's norm per block; blocks of one
+    parameter behave exactly like separate parameters."""
+    r = rng(13)
+    shape = (10, 7); b = 4
+    G_seq = [r.standard_normal(shape) * 0.01 for _ in range(4)]
+    lr = 0.3
+    opt = make_opt([shape], block_size=b, beta2=0.9, precondition_frequency=2)
+    W = [np.zeros(shape)]
+    blks = so.block_partition(*shape, b)
+    subs = [make_opt([(m, n)], block_size=b, beta2=0.9, precondition_frequency=2) for (_, _, m, n) in blks]
+    Wsub = [[np.zeros((m, n))] for (_, _, m, n) in blks]
+    acc = np.zeros(shape)
+    for t, G in enumerate(G_seq):
+        before = W[0].copy()
+        opt.step(W, [G], lr, t)
+        acc += G * G
+        for k, (r0, c0, m, n) in enumerate(blks):
+            sl = (slice(r0, r0 + m), slice(c0, c0 + n))
+            delta = (W[0] - before)[sl]
+            pg = G[sl] / (np.sqrt(acc[sl]) + 1e-10)
+            assert np.isclose(np.linalg.norm(delta), lr * np.linalg.norm(pg), rtol=1e-10)
+            subs[k].step(Wsub[k], [G[sl]], lr, t)
+            assert np.allclose(W[0][sl], Wsub[k][0], rtol=1e-12, atol=1e-15)
+
+
+def test_momentum_is_geometric_sum_of_directions():
+    """Gradients do not depend on W here, so the directions P_s are the same with
+    and without momentum and W_T = W_0 + lr sum_t sum_{s<=t} mu^(t-s) P_s."""
+    r = rng(14)
+    shapes = [(6, 5), (9,)]
+    grads = [[r.standard_normal(s) * 0.1 for s in shapes] for _ in range(7)]
+    lr, mu = 0.02, 0.8
+    plain = make_opt(shapes, precondition_frequency=3)
+    W = [np.zeros(s) for s in shapes]
+    P = []
+    for t, g in enumerate(grads):
+        before = [w.copy() for w in W]
+        plain.step(W, g, lr, t)
+        P.append([(w - b0) / lr for w, b0 in zip(W, before)])
+    mom = make_opt(shapes, precondition_frequency=3, momentum=mu)
+    Wm = [np.zeros(s) for s in shapes]
+    for t, g in enumerate(grads):
+        mom.step(Wm, g, lr, t)
+    for i in range(len(shapes)):
+        expect = np.zeros(shapes[i])
+        for t in range(len(grads)):
+            for s_ in range(t + 1):
+                expect += lr * mu ** (t - s_) * P[s_][i]
+        assert np.allclose(Wm[i], expect, rtol=1e-10, atol=1e-14)
+
+
+def test_refresh_schedule_and_warmup_branch():
+    r = rng(15)
+    shape = (5, 4)
+    opt = make_opt([shape], precondition_frequency=3, start_preconditioning_step=2)
+    W = [np.zeros(shape)]
+    acc = np.zeros(shape)
+    roots = []
+    for t in range(8):
+        G = r.standard_normal(shape)
+        before = W[0].copy()
+        opt.step(W, [G], 0.1, t)
+        acc += G * G
+        roots.append(opt.Lbar[0][0].copy())
+        if t < 2:   # grafting direction only, with a minus sign
+            assert np.allclose(W[0] - before, -0.1 * G / (np.sqrt(acc) + 1e-10), rtol=1e-12)
+            assert np.array_equal(opt.Lbar[0][0], np.eye(5))
+    # refresh at t = 3 and t = 6 only (t >= start and t % f == 0); stale otherwise
+    assert np.array_equal(roots[2], np.eye(5))
+    assert not np.array_equal(roots[3], roots[2])
+    assert np.array_equal(roots[4], roots[3]) and np.array_equal(roots[5], roots[3])
+    assert not np.array_equal(roots[6], roots[5])
+    assert np.array_equal(roots[7], roots[6])
+    # the refreshed root uses the factor that already contains G_t
+    X, _ = so.root_inverse(opt.L[0][0], 1e-12, 0.25)
+    assert not np.allclose(roots[6], X)   # L has moved on at t = 7 ...
+    opt2 = make_opt([shape], precondition_frequency=1)
+    W2 = [np.zeros(shape)]
+    G = r.standard_normal(shape)
+    opt2.step(W2, [G], 0.1, 0)
+    X0, _ = so.root_inverse(G @ G.T, 1e-12, 0.25)
+    assert np.allclose(opt2.Lbar[0][0], X0, rtol=1e-12)   # ... and at t = 0 it is rootinv(G0 G0^T)
+
+
+def test_gradient_scale_invariance():
+    """Scaling every gradient by c leaves the trajectory unchanged (grafting
+    normalises the direction, AdaGrad's direction is scale-free) up to epsilon
+    effects.  Roots are refreshed every step so that each G_t lies in the range
+    of its own factors and epsilon (which does not scale) stays negligible."""
+    r = rng(16)
+    shapes = [(12, 9), (5,)]
+    grads = [[r.standard_normal(s) for s in shapes] for _ in range(5)]
+    outs = []
+    for c in (1.0, 64.0):
+        opt = make_opt(shapes, block_size=8, beta2=0.99, precondition_frequency=1, momentum=0.9,
+                       epsilon=1e-20, graft_epsilon=1e-20)
+        W = [np.zeros(s) for s in shapes]
+        for t, g in enumerate(grads):
+            opt.step(W, [c * x for x in g], 0.01, t)
+        outs.append(W)
+    for a, b in zip(*outs):
+        assert np.allclose(a, b, rtol=1e-7, atol=1e-12)
+
+
+def test_zero_gradient_block_is_safe():
+    opt = make_opt([(4, 4)], momentum=0.9)
+    W = [np.ones((4, 4))]
+    opt.step(W, [np.zeros((4, 4))], 0.1, 0)
+    assert np.array_equal(W[0], np.ones((4, 4)))
+    assert np.all(np.isfinite(opt.Lbar[0][0]))
+
+
+def test_bf16_helpers_roundtrip():
+    x = rng(17).standard_normal(1000).astype(np.float32)
+    bits = wl.f32_to_bf16_bits(x)
+    y = wl.bf16_bits_to_f32(bits)
+    assert np.all(np.abs(y - x) <= np.abs(x) * 2.0 ** -8)
+    assert np.array_equal(wl.f32_to_bf16_bits(y), bits)
+    # ties to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> rounds to 1
+    assert wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.array([1.0 + 2.0 ** -8], np.float32)))[0] == 1.0
+    assert wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.array([1.0 + 3 * 2.0 ** -8], np.float32)))[0] == 1.0 + 2.0 ** -6
