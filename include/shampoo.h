@@ -1,0 +1,192 @@
+/*
+ * shampoo.h -- C ABI of the MI355X (gfx950) per-block Shampoo optimizer step.
+ *
+ * The library computes, entirely in hand-written HIP kernels, the optimizer
+ * step of Shi et al., "A Distributed Data-Parallel PyTorch Implementation of
+ * the Distributed Shampoo Optimizer for Training Neural Networks At-Scale"
+ * (arXiv 2309.06497), restricted to one GPU: blocked Kronecker-factor
+ * accumulation, periodic inverse-root refresh by batched symmetric
+ * eigendecomposition, two-sided preconditioning, AdaGrad grafting, momentum
+ * and the parameter update.  The multi-GPU distribution of the paper (Sec. 4.1)
+ * is not part of this library.
+ *
+ * Conventions for every entry point
+ *   - "device pointer": memory of the GPU the optimizer was created on,
+ *     owned by the caller and never freed by the library.
+ *   - "host pointer": ordinary process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; calls return without waiting unless stated.
+ *   - Return value: 0 on success, negative error code otherwise (see
+ *     shampoo_strerror).  On a negative return nothing has been modified.
+ *   - No entry point throws; none is safe to call concurrently on the same
+ *     shampoo_opt from several threads.
+ */
+#ifndef SHAMPOO_H
+#define SHAMPOO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct shampoo_opt shampoo_opt; /* opaque, owned by the library */
+
+enum {
+  SHAMPOO_OK = 0,
+  SHAMPOO_ERR_NULL = -1,      /* a required pointer is NULL                      */
+  SHAMPOO_ERR_SHAPE = -2,     /* bad n_params / ndim / shape / block_size / index */
+  SHAMPOO_ERR_HYPER = -3,     /* hyper-parameter out of range                     */
+  SHAMPOO_ERR_WORKSPACE = -4, /* workspace NULL, misaligned or too small          */
+  SHAMPOO_ERR_STEP = -5,      /* step not strictly increasing                     */
+  SHAMPOO_ERR_HIP = -6,       /* a HIP runtime call failed                        */
+  SHAMPOO_ERR_UNSUPPORTED = -7 /* size outside what the kernels support           */
+};
+
+enum { SHAMPOO_GRAD_F32 = 0, SHAMPOO_GRAD_BF16 = 1 };
+
+/*
+ * Optimizer configuration (copied at create; the arrays need not outlive the call).
+ * Hyper-parameters are those of the paper's complete pseudocode (Sec. 3,
+ * "Complete Distributed Shampoo Pseudocode") with beta1 = 0, no weight decay,
+ * no Nesterov, no bias correction, AdaGrad grafting.
+ */
+typedef struct {
+  int32_t n_params;       /* number of parameters (tensors), >= 1                          */
+  const int32_t *ndim;    /* host [n_params]: 1 (diagonal AdaGrad path, Sec. 4.2.2) or 2    */
+  const int64_t *shape;   /* host [2*n_params]: rows, cols (cols ignored when ndim == 1)    */
+  int32_t block_size;     /* b: max_preconditioner_dim of Sec. 4.2.1, >= 1                  */
+  float beta2;            /* in (0,1]; 1 = plain sum of G G^T, < 1 = EMA (Sec. 3.1.1)       */
+  float epsilon;          /* > 0: added to the eigenvalues in the root inverse (Sec. 3.2.1) */
+  float root_exponent;    /* r > 0: factors are raised to the power -r (0.25 for matrices)  */
+  int32_t precondition_frequency;     /* f >= 1: roots refreshed when step % f == 0 (Sec. 4.3) */
+  int32_t start_preconditioning_step; /* >= 0: before it the grafted direction is used alone   */
+  float graft_epsilon;    /* >= 0: P_graft = G / (sqrt(A) + graft_epsilon) (Sec. 2.4)        */
+  float momentum;         /* mu in [0,1): 0 disables the momentum state (Sec. 3.1.3)         */
+  int32_t grad_dtype;     /* SHAMPOO_GRAD_F32 or SHAMPOO_GRAD_BF16; parameters are float32   */
+  int32_t device;         /* HIP device ordinal                                              */
+} shampoo_config;
+
+/*
+ * Block planner (host only, touches no GPU).  Sec. 4.2.1: a rows x cols
+ * parameter is cut into ceil(rows/b) x ceil(cols/b) blocks, all b x b except
+ * in the last block row / column.  Blocks of equal (m, n) form a bucket and
+ * are numbered (slot) in parameter order, row-major inside a parameter.
+ * Writes up to `cap` rows of 8 int64 {param, row0, col0, m, n, bucket, slot, 0}
+ * into `table` (host, may be NULL when cap == 0) and the total number of
+ * blocks / buckets into *n_blocks / *n_buckets (host, may be NULL).
+ */
+int shampoo_plan(const shampoo_config *cfg, int64_t *table, int64_t cap,
+                 int64_t *n_blocks, int64_t *n_buckets);
+
+/* Bytes of device workspace shampoo_create needs for cfg; 0 if cfg is invalid. */
+size_t shampoo_workspace_bytes(const shampoo_config *cfg);
+
+/*
+ * Create an optimizer.  `workspace` is a device pointer, 256-byte aligned, of
+ * at least shampoo_workspace_bytes(cfg) bytes; it holds all optimizer state
+ * (factors L, R, roots, grafting state A, momentum M) and scratch, and must
+ * stay allocated until shampoo_destroy.  State is initialised (L = R = 0,
+ * roots = I, A = M = 0) on `stream`, which is synchronised before returning.
+ * *out (host) receives the handle.
+ */
+int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_bytes,
+                   void *stream, shampoo_opt **out);
+
+/*
+ * One optimizer iteration t = `step` (0-based, strictly increasing between
+ * calls) of the complete pseudocode for every block of every parameter:
+ *   L <- beta2 L + (1-beta2) G G^T, R likewise          (Sec. 3.1.1)
+ *   A <- A + G.^2                                        (Sec. 2.4)
+ *   if step >= start and step % f == 0: roots refreshed  (Sec. 3.2.1 box, 4.3)
+ *   P = -||G/(sqrt(A)+eps_g)||_F * Lbar G Rbar / ||Lbar G Rbar||_F   (Sec. 2.4)
+ *       (P = -G/(sqrt(A)+eps_g) while step < start, and for 1-D parameters)
+ *   M <- mu M + P ; W <- W + lr M                        (Sec. 3.1.3)
+ * params: host array [n_params] of device pointers, float32, contiguous
+ *         row-major with the shapes given at create; updated in place.
+ * grads:  host array [n_params] of device pointers, float32 or bfloat16 per
+ *         grad_dtype, same shapes; read only.
+ * Asynchronous on `stream`.  A factor whose eigendecomposition is not finite
+ * keeps its previous root (Sec. 3.2.3); such events are counted, see
+ * shampoo_status.
+ */
+int shampoo_step(shampoo_opt *opt, void *const *params, const void *const *grads,
+                 float lr, int64_t step, void *stream);
+
+/* State selectors for shampoo_get. */
+enum {
+  SHAMPOO_GET_L = 0,      /* m x m float32   */
+  SHAMPOO_GET_R = 1,      /* n x n           */
+  SHAMPOO_GET_LINV = 2,   /* m x m           */
+  SHAMPOO_GET_RINV = 3,   /* n x n           */
+  SHAMPOO_GET_A = 4,      /* m x n (block) or len (1-D parameter, block = 0) */
+  SHAMPOO_GET_M = 5,      /* same shape as A; error if momentum == 0         */
+  SHAMPOO_GET_PSH = 6,    /* m x n: last Lbar G Rbar                         */
+  SHAMPOO_GET_NORMS = 7   /* 2 floats: ||P_graft||_F^2, ||P_shampoo||_F^2 of the last step */
+};
+
+/*
+ * Copy one piece of state of block `block` (row-major index inside parameter
+ * `param`) into dst (device pointer, dense row-major float32, `bytes` must
+ * equal the size listed above).  Asynchronous on `stream`.
+ */
+int shampoo_get(shampoo_opt *opt, int32_t param, int32_t block, int32_t which,
+                void *dst, size_t bytes, void *stream);
+
+/*
+ * Synchronises `stream` and reports (host pointers, each may be NULL):
+ * the number of root refreshes performed, and the total number of factors
+ * whose refresh was skipped because the factor or its spectrum was not finite.
+ */
+int shampoo_status(shampoo_opt *opt, void *stream, int64_t *n_refreshes,
+                   int64_t *n_failed_roots);
+
+/* Per-stage device timing (HIP events on the step's stream). */
+enum {
+  SHAMPOO_STAGE_FACTOR = 0,   /* both symmetric rank-k factor updates       */
+  SHAMPOO_STAGE_GRAFT = 1,    /* grafting state + graft norm                */
+  SHAMPOO_STAGE_ROOT = 2,     /* root-inverse refresh                       */
+  SHAMPOO_STAGE_PRECOND = 3,  /* both GEMMs of Lbar G Rbar                  */
+  SHAMPOO_STAGE_UPDATE = 4,   /* rescale + momentum + parameter update      */
+  SHAMPOO_STAGE_DIAG = 5,     /* 1-D parameters                             */
+  SHAMPOO_STAGE_COUNT = 6
+};
+/* enable != 0: later steps record events around each stage (small overhead). */
+int shampoo_set_timing(shampoo_opt *opt, int32_t enable);
+/*
+ * Synchronises the recorded events and returns, for `stage`, the summed
+ * milliseconds and the number of timed intervals since the last call for that
+ * stage (host pointers).  Resets that stage's record.
+ */
+int shampoo_get_timing(shampoo_opt *opt, int32_t stage, double *ms_total, int64_t *intervals);
+
+/* Frees the host-side handle only (the workspace belongs to the caller). */
+int shampoo_destroy(shampoo_opt *opt);
+
+/*
+ * Stand-alone batched root inverse (the framed box of Sec. 3.2.1):
+ *   lambda, Q = eigh(A_i);  lambda' = lambda - min(lambda_min, 0) + epsilon;
+ *   X_i = Q diag(lambda'^(-r)) Q^T               for i = 0 .. batch-1.
+ * a:      device, batch dense row-major symmetric n x n float32 matrices (read only)
+ * x:      device, batch n x n float32 outputs (may not alias a)
+ * lambda: device, batch x n float32 eigenvalues in the solver's order
+ *         (unsorted), or NULL
+ * workspace: device, 256-byte aligned, at least
+ *         shampoo_root_inverse_workspace_bytes(n, batch) bytes
+ * failed: device int32[batch] set to 1 where A_i or its spectrum is not
+ *         finite (X_i is then left untouched), else 0; or NULL
+ * Asynchronous on `stream`.
+ */
+size_t shampoo_root_inverse_workspace_bytes(int32_t n, int32_t batch);
+int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon, float r,
+                         float *x, float *lambda, int32_t *failed,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static, NUL-terminated description of a return code. */
+const char *shampoo_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHAMPOO_H */

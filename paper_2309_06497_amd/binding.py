@@ -1,0 +1,241 @@
+"""ctypes binding of libshampoo.so: the same entry points as include/shampoo.h.
+
+Argument marshalling only -- every step of the optimizer runs in the HIP
+kernels of the library.  PyTorch is used for device memory and streams.
+The library is loaded on first use and a missing library is an error: there
+is no fallback path.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libshampoo.so")
+
+GRAD_F32, GRAD_BF16 = 0, 1
+GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS = range(8)
+STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG = range(6)
+STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag")
+
+EXPORTS = (
+    "shampoo_plan", "shampoo_workspace_bytes", "shampoo_create", "shampoo_step", "shampoo_get",
+    "shampoo_status", "shampoo_set_timing", "shampoo_get_timing", "shampoo_destroy",
+    "shampoo_root_inverse_workspace_bytes", "shampoo_root_inverse", "shampoo_strerror",
+)
+
+
+class ShampooConfig(ctypes.Structure):
+    _fields_ = [
+        ("n_params", ctypes.c_int32),
+        ("ndim", ctypes.POINTER(ctypes.c_int32)),
+        ("shape", ctypes.POINTER(ctypes.c_int64)),
+        ("block_size", ctypes.c_int32),
+        ("beta2", ctypes.c_float),
+        ("epsilon", ctypes.c_float),
+        ("root_exponent", ctypes.c_float),
+        ("precondition_frequency", ctypes.c_int32),
+        ("start_preconditioning_step", ctypes.c_int32),
+        ("graft_epsilon", ctypes.c_float),
+        ("momentum", ctypes.c_float),
+        ("grad_dtype", ctypes.c_int32),
+        ("device", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library (raises OSError if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise OSError(f"{LIB_PATH} not found: build it with `python -m paper_2309_06497_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    cfgp = ctypes.POINTER(ShampooConfig)
+    L.shampoo_plan.argtypes = [cfgp, ctypes.POINTER(i64), i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.shampoo_plan.restype = ctypes.c_int
+    L.shampoo_workspace_bytes.argtypes = [cfgp]
+    L.shampoo_workspace_bytes.restype = sz
+    L.shampoo_create.argtypes = [cfgp, vp, sz, vp, ctypes.POINTER(vp)]
+    L.shampoo_create.restype = ctypes.c_int
+    L.shampoo_step.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), f32, i64, vp]
+    L.shampoo_step.restype = ctypes.c_int
+    L.shampoo_get.argtypes = [vp, i32, i32, i32, vp, sz, vp]
+    L.shampoo_get.restype = ctypes.c_int
+    L.shampoo_status.argtypes = [vp, vp, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    L.shampoo_status.restype = ctypes.c_int
+    L.shampoo_set_timing.argtypes = [vp, i32]
+    L.shampoo_set_timing.restype = ctypes.c_int
+    L.shampoo_get_timing.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    L.shampoo_get_timing.restype = ctypes.c_int
+    L.shampoo_destroy.argtypes = [vp]
+    L.shampoo_destroy.restype = ctypes.c_int
+    L.shampoo_root_inverse_workspace_bytes.argtypes = [i32, i32]
+    L.shampoo_root_inverse_workspace_bytes.restype = sz
+    L.shampoo_root_inverse.argtypes = [vp, i32, i32, f32, f32, vp, vp, vp, vp, sz, vp]
+    L.shampoo_root_inverse.restype = ctypes.c_int
+    L.shampoo_strerror.argtypes = [ctypes.c_int]
+    L.shampoo_strerror.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+class ShampooError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__(f"libshampoo error {code}: {lib().shampoo_strerror(code).decode()}")
+
+
+def _check(code):
+    if code != 0:
+        raise ShampooError(code)
+
+
+def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_frequency,
+                start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
+                grad_dtype=GRAD_F32, device=0):
+    """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
+    n = len(shapes)
+    ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
+    flat = []
+    for s in shapes:
+        flat += [int(s[0]), int(s[1]) if len(s) > 1 else 1]
+    shape = (ctypes.c_int64 * max(2 * n, 1))(*flat)
+    cfg = ShampooConfig(n, ndim, shape, block_size, beta2, epsilon, root_exponent,
+                        precondition_frequency, start_preconditioning_step, graft_epsilon,
+                        momentum, grad_dtype, device)
+    cfg._keep = (ndim, shape)
+    return cfg
+
+
+def shampoo_plan(cfg):
+    """Returns (table int64 [n_blocks, 8], n_buckets); rows are
+    {param, row0, col0, m, n, bucket, slot, 0}.  Host only."""
+    nb, nk = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().shampoo_plan(ctypes.byref(cfg), None, 0, ctypes.byref(nb), ctypes.byref(nk)))
+    table = np.zeros((max(nb.value, 1), 8), dtype=np.int64)
+    _check(lib().shampoo_plan(ctypes.byref(cfg), table.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                              nb.value, ctypes.byref(nb), ctypes.byref(nk)))
+    return table[:nb.value], nk.value
+
+
+def shampoo_workspace_bytes(cfg):
+    return lib().shampoo_workspace_bytes(ctypes.byref(cfg))
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class Shampoo:
+    """Owns the workspace tensor and the library handle for one parameter list."""
+
+    def __init__(self, shapes, block_size, beta2, epsilon, root_exponent, precondition_frequency,
+                 start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
+                 grad_dtype=GRAD_F32, device=0):
+        import torch
+        self.shapes = [tuple(s) for s in shapes]
+        self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
+                               precondition_frequency, start_preconditioning_step, graft_epsilon,
+                               momentum, grad_dtype, device)
+        self.device = torch.device("cuda", device)
+        nbytes = shampoo_workspace_bytes(self.cfg)
+        if nbytes == 0:
+            raise ShampooError(lib().shampoo_plan(ctypes.byref(self.cfg), None, 0, None, None) or -2)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.handle = ctypes.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(lib().shampoo_create(ctypes.byref(self.cfg), ctypes.c_void_p(self.workspace.data_ptr()),
+                                        nbytes, _stream_ptr(), ctypes.byref(self.handle)))
+        self._n = len(self.shapes)
+        self._pw = (ctypes.c_void_p * self._n)()
+        self._pg = (ctypes.c_void_p * self._n)()
+
+    def step(self, params, grads, lr, step):
+        """params / grads: lists of contiguous CUDA tensors (float32 / float32-or-bfloat16)."""
+        for i in range(self._n):
+            self._pw[i] = params[i].data_ptr()
+            self._pg[i] = grads[i].data_ptr()
+        _check(lib().shampoo_step(self.handle, self._pw, self._pg, lr, step, _stream_ptr()))
+
+    def get(self, param, block, which):
+        import torch
+        s = self.shapes[param]
+        if len(s) == 1:
+            shape = (s[0],)
+        else:
+            table = self.plan()[0]
+            rows = table[table[:, 0] == param]
+            m, n = int(rows[block, 3]), int(rows[block, 4])
+            shape = {GET_L: (m, m), GET_LINV: (m, m), GET_R: (n, n), GET_RINV: (n, n),
+                     GET_A: (m, n), GET_M: (m, n), GET_PSH: (m, n), GET_NORMS: (2,)}[which]
+        out = torch.empty(shape, dtype=torch.float32, device=self.device)
+        _check(lib().shampoo_get(self.handle, param, block, which, ctypes.c_void_p(out.data_ptr()),
+                                 out.numel() * 4, _stream_ptr()))
+        return out
+
+    def plan(self):
+        if not hasattr(self, "_plan"):
+            self._plan = shampoo_plan(self.cfg)
+        return self._plan
+
+    def status(self):
+        a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(lib().shampoo_status(self.handle, _stream_ptr(), ctypes.byref(a), ctypes.byref(b)))
+        return {"refreshes": a.value, "failed_roots": b.value}
+
+    def set_timing(self, enable):
+        _check(lib().shampoo_set_timing(self.handle, 1 if enable else 0))
+
+    def get_timing(self):
+        """{stage name: (total ms, intervals)} since the last call."""
+        out = {}
+        for st, name in enumerate(STAGE_NAMES):
+            ms, cnt = ctypes.c_double(0), ctypes.c_int64(0)
+            _check(lib().shampoo_get_timing(self.handle, st, ctypes.byref(ms), ctypes.byref(cnt)))
+            out[name] = (ms.value, cnt.value)
+        return out
+
+    def destroy(self):
+        if self.handle:
+            lib().shampoo_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def shampoo_root_inverse(a, epsilon, r, want_lambda=False, want_failed=False):
+    """a: CUDA float32 tensor [batch, n, n] (symmetric).  Returns X [batch, n, n]
+    (and eigenvalues [batch, n], failure flags [batch] on request)."""
+    import torch
+    assert a.is_cuda and a.dtype == torch.float32 and a.dim() == 3 and a.shape[1] == a.shape[2]
+    a = a.contiguous()
+    batch, n = a.shape[0], a.shape[1]
+    x = torch.empty_like(a)
+    lam = torch.empty((batch, n), dtype=torch.float32, device=a.device) if want_lambda else None
+    failed = torch.zeros((batch,), dtype=torch.int32, device=a.device) if want_failed else None
+    nbytes = lib().shampoo_root_inverse_workspace_bytes(n, batch)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=a.device)
+    with torch.cuda.device(a.device):
+        _check(lib().shampoo_root_inverse(
+            ctypes.c_void_p(a.data_ptr()), n, batch, epsilon, r, ctypes.c_void_p(x.data_ptr()),
+            ctypes.c_void_p(lam.data_ptr()) if lam is not None else None,
+            ctypes.c_void_p(failed.data_ptr()) if failed is not None else None,
+            ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream_ptr()))
+        torch.cuda.current_stream().synchronize()   # ws is released on return
+    res = [x]
+    if want_lambda:
+        res.append(lam)
+    if want_failed:
+        res.append(failed)
+    return res[0] if len(res) == 1 else tuple(res)

@@ -1,0 +1,213 @@
+// Coalesced elementwise stages of the step (HBM-bandwidth bound):
+//   graft_kernel      A <- A + G.^2 ; partial sums of ||G / (sqrt(A) + eps_g)||_F^2   (Sec. 2.4)
+//   scale_kernel      per block: -||P_graft||_F / ||P_shampoo||_F from the partial sums
+//   update_kernel     P = scale * P_shampoo (or -P_graft) ; M <- mu M + P ; W <- W + lr M (Sec. 3.1.3)
+//   diag_kernel       1-D parameters: diagonal AdaGrad + momentum in one pass (Sec. 4.2.2)
+// A block is addressed inside the caller's row-major tensors through its
+// BlockDesc; rows of a block are contiguous runs, read as 4-element vectors
+// when the block's origin and leading dimension allow it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "gemm_mfma.h"
+
+namespace shampoo {
+
+constexpr int EW_THREADS = 256;
+
+struct EwGeom {        // how 256 threads tile a block of m x n
+  int32_t lanes_x_log2;   // threads along columns = 1 << lanes_x_log2 (each owns 4 columns per pass)
+  int32_t rows_per_wg;
+  int32_t chunks;         // workgroups per block = ceil(m / rows_per_wg)
+};
+
+struct EwArgs {
+  const BlockDesc *desc;
+  void *const *w_table;          // parameter pointers (float32)
+  const void *const *g_table;    // gradient pointers
+  float *a_state;                // grafting state, parameter layout, all parameters concatenated
+  float *m_state;                // momentum state, same layout (nullptr when mu == 0)
+  const float *p;                // [slot][m][n] Shampoo directions
+  float *sg_partial;             // [slot][chunks]
+  const float *scale;            // [slot]
+  int32_t m, n;
+  EwGeom geom;
+  float graft_eps, mu, lr;
+  int32_t graft_only;            // update_kernel: use -P_graft instead of scale * P
+};
+
+template <typename GT>
+__device__ __forceinline__ void load_g4(const GT *g, bool vec, int valid, float v[4]) {
+  if (vec) { Elem<GT>::load4(g, v); return; }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = e < valid ? Elem<GT>::load1(g + e) : 0.f;
+}
+__device__ __forceinline__ void load_f4(const float *p, bool vec, int valid, float v[4]) {
+  if (vec) { Elem<float>::load4(p, v); return; }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = e < valid ? p[e] : 0.f;
+}
+__device__ __forceinline__ void store_f4(float *p, bool vec, int valid, const float v[4]) {
+  if (vec) { *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]); return; }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) if (e < valid) p[e] = v[e];
+}
+
+// grid: chunks * (blocks of the bucket) workgroups, chunk index fastest
+template <typename GT>
+__global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
+  __shared__ float red[EW_THREADS / 64];
+  const int slot = blockIdx.x / g.geom.chunks, chunk = blockIdx.x - slot * g.geom.chunks, tid = threadIdx.x;
+  const BlockDesc d = g.desc[slot];
+  const GT *gp = reinterpret_cast<const GT *>(g.g_table[d.param]) + d.offset;
+  float *ap = g.a_state + d.state_offset;
+  const int ld = d.ld, n = g.n;
+  const bool vec = ((ld & 3) == 0) && ((n & 3) == 0) && ((d.offset & 3) == 0) && ((d.state_offset & 3) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(g.g_table[d.param]) & 15) == 0);
+  const int lx = g.geom.lanes_x_log2;
+  const int tx = tid & ((1 << lx) - 1), ty = tid >> lx, ny = EW_THREADS >> lx;
+  const int r0 = chunk * g.geom.rows_per_wg;
+  const int r1 = min(r0 + g.geom.rows_per_wg, g.m);
+  float ss = 0.f;
+  for (int i = r0 + ty; i < r1; i += ny)
+    for (int j = tx * 4; j < n; j += 4 << lx) {
+      const int valid = min(4, n - j);
+      float gv[4], av[4];
+      load_g4<GT>(gp + (int64_t)i * ld + j, vec, valid, gv);
+      load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        av[e] += gv[e] * gv[e];
+        const float pg = gv[e] / (sqrtf(av[e]) + g.graft_eps);
+        if (e < valid) ss += pg * pg;
+      }
+      store_f4(ap + (int64_t)i * ld + j, vec, valid, av);
+    }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  if (tid == 0) g.sg_partial[(int64_t)slot * g.geom.chunks + chunk] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+struct ScaleArgs {
+  const float *sg_partial; int32_t sg_count;   // per block
+  const float *ssh_partial; int32_t ssh_count; // per block
+  float *scale;    // [blocks]
+  float *norms;    // [blocks][2]
+};
+
+// One wavefront per block; fixed summation order, so results are reproducible.
+__global__ __launch_bounds__(64) void scale_kernel(const ScaleArgs g) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  double sg = 0.0, ssh = 0.0;
+  for (int i = lane; i < g.sg_count; i += 64) sg += (double)g.sg_partial[(int64_t)b * g.sg_count + i];
+  for (int i = lane; i < g.ssh_count; i += 64) ssh += (double)g.ssh_partial[(int64_t)b * g.ssh_count + i];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    sg += __shfl_xor(sg, off, 64);
+    ssh += __shfl_xor(ssh, off, 64);
+  }
+  if (lane == 0) {
+    // zero (or non-finite) norms give a zero step for the block instead of NaN
+    const bool ok = (sg > 0.0) && (ssh > 0.0) && (sg <= 1.0e300) && (ssh <= 1.0e300);
+    g.scale[b] = ok ? (float)(-sqrt(sg / ssh)) : 0.f;
+    g.norms[2 * b] = (float)sg;
+    g.norms[2 * b + 1] = (float)ssh;
+  }
+}
+
+template <typename GT>
+__global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
+  const int slot = blockIdx.x / g.geom.chunks, chunk = blockIdx.x - slot * g.geom.chunks, tid = threadIdx.x;
+  const BlockDesc d = g.desc[slot];
+  float *wp = reinterpret_cast<float *>(g.w_table[d.param]) + d.offset;
+  const GT *gp = reinterpret_cast<const GT *>(g.g_table[d.param]) + d.offset;
+  float *ap = g.a_state + d.state_offset;
+  float *mp = g.m_state ? g.m_state + d.state_offset : nullptr;
+  const int ld = d.ld, n = g.n;
+  const float *pp = g.p + (int64_t)slot * g.m * n;
+  const bool vec = ((ld & 3) == 0) && ((n & 3) == 0) && ((d.offset & 3) == 0) && ((d.state_offset & 3) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(g.w_table[d.param]) & 15) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(g.g_table[d.param]) & 15) == 0);
+  const int lx = g.geom.lanes_x_log2;
+  const int tx = tid & ((1 << lx) - 1), ty = tid >> lx, ny = EW_THREADS >> lx;
+  const int r0 = chunk * g.geom.rows_per_wg;
+  const int r1 = min(r0 + g.geom.rows_per_wg, g.m);
+  const float sc = g.graft_only ? 0.f : g.scale[slot];
+  for (int i = r0 + ty; i < r1; i += ny)
+    for (int j = tx * 4; j < n; j += 4 << lx) {
+      const int valid = min(4, n - j);
+      float pv[4], wv[4], mv[4];
+      if (g.graft_only) {
+        float gv[4], av[4];
+        load_g4<GT>(gp + (int64_t)i * ld + j, vec, valid, gv);
+        load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pv[e] = -gv[e] / (sqrtf(av[e]) + g.graft_eps);
+      } else {
+        load_f4(pp + (int64_t)i * n + j, vec, valid, pv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pv[e] *= sc;
+      }
+      load_f4(wp + (int64_t)i * ld + j, vec, valid, wv);
+      if (mp) {
+        load_f4(mp + (int64_t)i * ld + j, vec, valid, mv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { mv[e] = g.mu * mv[e] + pv[e]; wv[e] += g.lr * mv[e]; }
+        store_f4(mp + (int64_t)i * ld + j, vec, valid, mv);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wv[e] += g.lr * pv[e];
+      }
+      store_f4(wp + (int64_t)i * ld + j, vec, valid, wv);
+    }
+}
+
+// 1-D parameters, cut into chunks of at most DIAG_CHUNK elements.
+constexpr int DIAG_CHUNK = 4096;
+struct DiagChunk {
+  int32_t param;
+  int32_t len;
+  int64_t start;         // first element inside the parameter
+  int64_t state_offset;  // offset of that element in the A / M state arrays
+};
+struct DiagArgs {
+  const DiagChunk *chunks;
+  void *const *w_table;
+  const void *const *g_table;
+  float *a_state, *m_state;
+  float graft_eps, mu, lr;
+};
+
+template <typename GT>
+__global__ __launch_bounds__(EW_THREADS) void diag_kernel(const DiagArgs g) {
+  const DiagChunk c = g.chunks[blockIdx.x];
+  float *w = reinterpret_cast<float *>(g.w_table[c.param]) + c.start;
+  const GT *gp = reinterpret_cast<const GT *>(g.g_table[c.param]) + c.start;
+  float *a = g.a_state + c.state_offset;
+  float *m = g.m_state ? g.m_state + c.state_offset : nullptr;
+  for (int i = threadIdx.x; i < c.len; i += EW_THREADS) {
+    const float gv = Elem<GT>::load1(gp + i);
+    const float av = a[i] + gv * gv;
+    a[i] = av;
+    float p = -gv / (sqrtf(av) + g.graft_eps);
+    if (m) { p = g.mu * m[i] + p; m[i] = p; }
+    w[i] += g.lr * p;
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(float *p, float v, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// roots start as the identity: count matrices of n x n
+__global__ __launch_bounds__(256) void eye_kernel(float *p, int32_t n, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t e = i % ((int64_t)n * n);
+  p[i] = (e / n == e % n) ? 1.f : 0.f;
+}
+
+}  // namespace shampoo

@@ -1,0 +1,727 @@
+// Host side of libshampoo: configuration checks, block planner, workspace
+// layout, kernel launches and the extern "C" boundary declared in shampoo.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <new>
+#include <utility>
+#include <vector>
+
+#include "../../include/shampoo.h"
+#include "eigh_jacobi.h"
+#include "elementwise.h"
+#include "gemm_mfma.h"
+
+using namespace shampoo;
+
+namespace {
+
+constexpr int64_t MAX_BLOCK_SIZE = 8192;
+constexpr size_t ALIGN = 256;
+constexpr size_t EIG_CHUNK_BYTES = (size_t)2 << 30;   // W + Qt of one chunk of the block solver
+
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+#define HIP_TRY(expr)                          \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) return SHAMPOO_ERR_HIP; \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// Planner (Sec. 4.2.1 blocking)
+// ---------------------------------------------------------------------------
+struct Block {
+  int32_t param;
+  int64_t row0, col0;
+  int32_t m, n;
+  int32_t bucket, slot;
+};
+struct Bucket {
+  int32_t m, n, count;
+  // byte offsets into the workspace
+  size_t off_L, off_R, off_Linv, off_Rinv, off_P, off_desc, off_sgp, off_sshp, off_scale, off_norms;
+  EwGeom geom;
+  int32_t tiles_m, tiles_n;
+};
+struct Plan {
+  std::vector<Block> blocks;
+  std::vector<Bucket> buckets;
+  std::vector<std::vector<int32_t>> param_blocks;  // per parameter: indices into blocks (row-major)
+  std::vector<int64_t> param_state_offset;         // element offset of each parameter in A / M
+  std::vector<DiagChunk> diag_chunks;
+  int64_t total_elems = 0;
+};
+
+int check_config(const shampoo_config *c) {
+  if (!c || !c->ndim || !c->shape) return SHAMPOO_ERR_NULL;
+  if (c->n_params < 1) return SHAMPOO_ERR_SHAPE;
+  if (c->block_size < 1) return SHAMPOO_ERR_SHAPE;
+  if (c->block_size > MAX_BLOCK_SIZE) return SHAMPOO_ERR_UNSUPPORTED;
+  for (int i = 0; i < c->n_params; ++i) {
+    if (c->ndim[i] != 1 && c->ndim[i] != 2) return SHAMPOO_ERR_SHAPE;
+    if (c->shape[2 * i] < 1) return SHAMPOO_ERR_SHAPE;
+    if (c->ndim[i] == 2 && c->shape[2 * i + 1] < 1) return SHAMPOO_ERR_SHAPE;
+    if (c->shape[2 * i] > (int64_t)1 << 30) return SHAMPOO_ERR_UNSUPPORTED;
+    if (c->ndim[i] == 2 && c->shape[2 * i + 1] > (int64_t)1 << 30) return SHAMPOO_ERR_UNSUPPORTED;
+  }
+  if (!(c->beta2 > 0.f && c->beta2 <= 1.f)) return SHAMPOO_ERR_HYPER;
+  if (!(c->epsilon > 0.f) || !std::isfinite(c->epsilon)) return SHAMPOO_ERR_HYPER;
+  if (!(c->root_exponent > 0.f) || !std::isfinite(c->root_exponent)) return SHAMPOO_ERR_HYPER;
+  if (c->precondition_frequency < 1 || c->start_preconditioning_step < 0) return SHAMPOO_ERR_HYPER;
+  if (!(c->graft_epsilon >= 0.f) || !std::isfinite(c->graft_epsilon)) return SHAMPOO_ERR_HYPER;
+  if (!(c->momentum >= 0.f && c->momentum < 1.f)) return SHAMPOO_ERR_HYPER;
+  if (c->grad_dtype != SHAMPOO_GRAD_F32 && c->grad_dtype != SHAMPOO_GRAD_BF16) return SHAMPOO_ERR_HYPER;
+  return SHAMPOO_OK;
+}
+
+EwGeom make_geom(int m, int n) {
+  EwGeom g;
+  const int vecs = (n + 3) / 4;
+  int lx = 0;
+  while ((1 << lx) < vecs && lx < 6) ++lx;
+  g.lanes_x_log2 = lx;
+  const int ny = EW_THREADS >> lx;
+  const int cols_per_pass = 4 << lx;
+  const int passes = (n + cols_per_pass - 1) / cols_per_pass;
+  // about 8192 elements per workgroup, a whole number of thread rows
+  int rows = std::max(1, 8192 / (cols_per_pass * passes));
+  rows = (rows + ny - 1) / ny * ny;
+  g.rows_per_wg = rows;
+  g.chunks = (m + rows - 1) / rows;
+  return g;
+}
+
+void make_plan(const shampoo_config *c, Plan &p) {
+  const int64_t b = c->block_size;
+  std::map<std::pair<int, int>, int> bucket_of;
+  p.param_blocks.assign(c->n_params, {});
+  p.param_state_offset.assign(c->n_params, 0);
+  int64_t off = 0;
+  for (int i = 0; i < c->n_params; ++i) {
+    p.param_state_offset[i] = off;
+    const int64_t rows = c->shape[2 * i];
+    if (c->ndim[i] == 1) {
+      for (int64_t s = 0; s < rows; s += DIAG_CHUNK) {
+        DiagChunk dc;
+        dc.param = i;
+        dc.len = (int32_t)std::min<int64_t>(DIAG_CHUNK, rows - s);
+        dc.start = s;
+        dc.state_offset = off + s;
+        p.diag_chunks.push_back(dc);
+      }
+      off += (rows + 3) / 4 * 4;
+      continue;
+    }
+    const int64_t cols = c->shape[2 * i + 1];
+    const int64_t km = (rows + b - 1) / b, kn = (cols + b - 1) / b;
+    for (int64_t bi = 0; bi < km; ++bi)
+      for (int64_t bj = 0; bj < kn; ++bj) {
+        Block blk;
+        blk.param = i;
+        blk.row0 = bi * b;
+        blk.col0 = bj * b;
+        blk.m = (int32_t)std::min<int64_t>(b, rows - blk.row0);
+        blk.n = (int32_t)std::min<int64_t>(b, cols - blk.col0);
+        auto key = std::make_pair(blk.m, blk.n);
+        auto it = bucket_of.find(key);
+        if (it == bucket_of.end()) {
+          Bucket bk{};
+          bk.m = blk.m; bk.n = blk.n; bk.count = 0;
+          bucket_of[key] = (int)p.buckets.size();
+          p.buckets.push_back(bk);
+          it = bucket_of.find(key);
+        }
+        blk.bucket = it->second;
+        blk.slot = p.buckets[it->second].count++;
+        p.param_blocks[i].push_back((int32_t)p.blocks.size());
+        p.blocks.push_back(blk);
+      }
+    off += (rows * cols + 3) / 4 * 4;
+  }
+  p.total_elems = off;
+  for (auto &bk : p.buckets) {
+    bk.geom = make_geom(bk.m, bk.n);
+    bk.tiles_m = (bk.m + BM - 1) / BM;
+    bk.tiles_n = (bk.n + BN - 1) / BN;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Root-inverse workspace (shared by the optimizer and the stand-alone call)
+// ---------------------------------------------------------------------------
+struct EigLayout {
+  int32_t np = 0, chunk = 0;
+  size_t off_w = 0, off_qt = 0, off_j = 0, off_ident = 0, off_rot = 0, off_dmax = 0, off_failed = 0, off_f = 0;
+  size_t bytes = 0;
+};
+
+EigLayout eig_layout(int n, int batch) {
+  EigLayout e;
+  if (n <= JAC_SMALL_MAX) {     // LDS solver: only the per-matrix failure flags
+    e.chunk = batch;
+    e.off_failed = 0;
+    e.bytes = align_up((size_t)std::max(batch, 1) * sizeof(int32_t));
+    return e;
+  }
+  e.np = (n + JAC_PIV - 1) / JAC_PIV * JAC_PIV;
+  const size_t mat = (size_t)e.np * e.np * sizeof(float);
+  e.chunk = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)batch, 32768), EIG_CHUNK_BYTES / (2 * mat)));
+  size_t off = 0;
+  e.off_w = off; off += align_up(mat * e.chunk);
+  e.off_qt = off; off += align_up(mat * e.chunk);
+  const int hp = e.np / JAC_PIV;
+  e.off_j = off; off += align_up((size_t)e.chunk * hp * JAC_PIV * JAC_PIV * sizeof(float));
+  e.off_ident = off; off += align_up((size_t)e.chunk * hp * sizeof(int32_t));
+  e.off_rot = off; off += align_up((size_t)e.chunk * JAC_OUTER_SWEEPS * sizeof(int32_t));
+  e.off_dmax = off; off += align_up((size_t)e.chunk * sizeof(float));
+  e.off_failed = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
+  e.off_f = off; off += align_up((size_t)e.chunk * e.np * sizeof(float));
+  e.bytes = off;
+  return e;
+}
+
+template <int AO, int BO, typename TA, typename TB, int EPI, bool KS>
+int launch_gemm(GemmArgs &g, hipStream_t s) {
+  const int64_t total = (int64_t)g.tiles * g.batch;
+  if (total <= 0) return SHAMPOO_OK;
+  if (total > (int64_t)1 << 30) return SHAMPOO_ERR_UNSUPPORTED;
+  const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
+  hipLaunchKernelGGL((gemm_mfma_kernel<AO, BO, TA, TB, EPI, KS>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, g);
+  HIP_TRY(hipGetLastError());
+  return SHAMPOO_OK;
+}
+
+int launch_fill(float *p, float v, int64_t n, hipStream_t s) {
+  if (n <= 0) return SHAMPOO_OK;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, v, n);
+  HIP_TRY(hipGetLastError());
+  return SHAMPOO_OK;
+}
+
+// X_i = rootinv(A_i) for a batch of dense n x n matrices.  ws: eig_layout(n, >= chunk) region.
+int root_inverse_batched(const float *a, int n, int batch, float eps, float r, float *x, float *lambda,
+                         int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
+                         const EigLayout &e, hipStream_t s) {
+  if (batch <= 0) return SHAMPOO_OK;
+  if (n <= JAC_SMALL_MAX) {
+    SmallRootArgs g;
+    g.a = a; g.a_stride = (int64_t)n * n;
+    g.x = x; g.x_stride = (int64_t)n * n;
+    g.lambda = lambda; g.failed = failed_user; g.fail_count = fail_count;
+    g.n = n; g.epsilon = eps; g.r = r;
+    const size_t lds = rootinv_small_lds_bytes(n);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rootinv_small_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(rootinv_small_kernel, dim3(batch), dim3(JAC_THREADS), lds, s, g);
+    HIP_TRY(hipGetLastError());
+    return SHAMPOO_OK;
+  }
+  const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
+  float *w = reinterpret_cast<float *>(ws + e.off_w);
+  float *qt = reinterpret_cast<float *>(ws + e.off_qt);
+  float *jbuf = reinterpret_cast<float *>(ws + e.off_j);
+  int32_t *ident = reinterpret_cast<int32_t *>(ws + e.off_ident);
+  int32_t *rot = reinterpret_cast<int32_t *>(ws + e.off_rot);
+  float *dmax = reinterpret_cast<float *>(ws + e.off_dmax);
+  int32_t *failed = reinterpret_cast<int32_t *>(ws + e.off_failed);
+  float *fv = reinterpret_cast<float *>(ws + e.off_f);
+  for (int b0 = 0; b0 < batch; b0 += e.chunk) {
+    const int cb = std::min(e.chunk, batch - b0);
+    // dmax and failed are adjacent 4-byte arrays of `chunk` entries each: clear both
+    int rc = launch_fill(dmax, 0.f, cb, s);
+    if (rc) return rc;
+    rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, cb, s);
+    if (rc) return rc;
+    BlockInitArgs ia;
+    ia.a = a + (int64_t)b0 * n * n; ia.a_stride = (int64_t)n * n; ia.n = n;
+    ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot;
+    hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cb), dim3(256), 0, s, ia);
+    HIP_TRY(hipGetLastError());
+    BlockJacArgs ja;
+    ja.w = w; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
+    ja.np = np;
+    for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
+      for (int rd = 0; rd < nblk - 1; ++rd) {
+        ja.round = rd; ja.sweep = sw;
+        hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cb), dim3(JAC_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_kernel, dim3(hp * hp + hp * (np / JAC_PIV), cb), dim3(JAC_THREADS), 0, s, ja);
+      }
+    HIP_TRY(hipGetLastError());
+    BlockFinalArgs fa;
+    fa.w = w; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.fvals = fv;
+    fa.lambda = lambda ? lambda + (int64_t)b0 * n : nullptr;
+    fa.failed = failed; fa.failed_out = failed_user ? failed_user + b0 : nullptr; fa.fail_count = fail_count;
+    hipLaunchKernelGGL(blockjac_final_kernel, dim3(cb), dim3(256), 0, s, fa);
+    HIP_TRY(hipGetLastError());
+    GemmArgs g{};
+    g.a.base = qt; g.a.batch_stride = (int64_t)np * np; g.a.ld = np; g.a.from_table = 0;
+    g.b = g.a;
+    g.c = x + (int64_t)b0 * n * n; g.c_batch_stride = (int64_t)n * n; g.ldc = n;
+    g.M = n; g.N = n; g.K = np; g.alpha = 1.f; g.beta = 0.f;
+    g.kscale = fv; g.kscale_stride = np; g.skip = failed;
+    g.tiles_m = g.tiles_n = (n + BM - 1) / BM;
+    g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
+    g.batch = cb;
+    rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_SYRK, true>(g, s);
+    if (rc) return rc;
+  }
+  return SHAMPOO_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// The optimizer object
+// ---------------------------------------------------------------------------
+struct shampoo_opt {
+  shampoo_config cfg;
+  std::vector<int32_t> ndim;
+  std::vector<int64_t> shape;
+  Plan plan;
+  unsigned char *ws = nullptr;
+  size_t ws_bytes = 0;
+  // workspace offsets
+  size_t off_A = 0, off_M = 0, off_T = 0, off_wtab = 0, off_gtab = 0, off_diag = 0, off_count = 0, off_eig = 0;
+  std::vector<EigLayout> eig_L, eig_R;   // per bucket
+  std::vector<void *> last_w, last_g;    // pointer tables currently on the device
+  int64_t last_step = -1;
+  int64_t n_refresh = 0;
+  bool timing = false;
+  struct Interval { hipEvent_t a, b; };
+  std::vector<Interval> intervals[SHAMPOO_STAGE_COUNT];
+};
+
+namespace {
+
+size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
+  const size_t offA = take((size_t)p.total_elems * 4);
+  const size_t offM = c->momentum > 0.f ? take((size_t)p.total_elems * 4) : 0;
+  size_t t_elems = 0, eig_bytes = 0;
+  std::vector<EigLayout> eL, eR;
+  for (auto &b : p.buckets) {
+    const size_t B = b.count, m = b.m, n = b.n;
+    b.off_L = take(B * m * m * 4);
+    b.off_R = take(B * n * n * 4);
+    b.off_Linv = take(B * m * m * 4);
+    b.off_Rinv = take(B * n * n * 4);
+    b.off_P = take(B * m * n * 4);
+    b.off_desc = take(B * sizeof(BlockDesc));
+    b.off_sgp = take(B * b.geom.chunks * 4);
+    b.off_sshp = take(B * b.tiles_m * b.tiles_n * 4);
+    b.off_scale = take(B * 4);
+    b.off_norms = take(B * 8);
+    t_elems = std::max(t_elems, B * m * n);
+    eL.push_back(eig_layout(b.m, b.count));
+    eR.push_back(eig_layout(b.n, b.count));
+    eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
+  }
+  const size_t offT = take(t_elems * 4);
+  const size_t offW = take((size_t)c->n_params * sizeof(void *));
+  const size_t offG = take((size_t)c->n_params * sizeof(void *));
+  const size_t offD = take(std::max<size_t>(1, p.diag_chunks.size()) * sizeof(DiagChunk));
+  const size_t offC = take(64);
+  const size_t offE = take(eig_bytes);
+  if (o) {
+    o->off_A = offA; o->off_M = offM; o->off_T = offT; o->off_wtab = offW; o->off_gtab = offG;
+    o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
+    o->eig_L = eL; o->eig_R = eR;
+  }
+  return off;
+}
+
+struct StageTimer {
+  shampoo_opt *o; int stage; hipStream_t s; bool on; hipEvent_t a{};
+  StageTimer(shampoo_opt *o_, int st, hipStream_t s_) : o(o_), stage(st), s(s_), on(o_->timing) {
+    if (on) { if (hipEventCreate(&a) != hipSuccess) { on = false; return; } (void)hipEventRecord(a, s); }
+  }
+  ~StageTimer() {
+    if (!on) return;
+    hipEvent_t b;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+    (void)hipEventRecord(b, s);
+    o->intervals[stage].push_back({a, b});
+  }
+};
+
+template <typename GT>
+int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
+  const shampoo_config &c = o->cfg;
+  Plan &p = o->plan;
+  unsigned char *ws = o->ws;
+  float *A = reinterpret_cast<float *>(ws + o->off_A);
+  float *M = c.momentum > 0.f ? reinterpret_cast<float *>(ws + o->off_M) : nullptr;
+  float *T = reinterpret_cast<float *>(ws + o->off_T);
+  void *const *wtab = reinterpret_cast<void *const *>(ws + o->off_wtab);
+  const void *const *gtab = reinterpret_cast<const void *const *>(ws + o->off_gtab);
+  unsigned long long *fail_count = reinterpret_cast<unsigned long long *>(ws + o->off_count);
+  const bool use_shampoo = step >= c.start_preconditioning_step;
+  const bool refresh = use_shampoo && (step % c.precondition_frequency == 0);
+  const float alpha = c.beta2 < 1.f ? 1.f - c.beta2 : 1.f;
+  const float beta = c.beta2 < 1.f ? c.beta2 : 1.f;
+  int rc;
+
+  for (auto &b : p.buckets) {
+    const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
+    {
+      StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
+      GemmArgs g{};
+      g.a.from_table = 1; g.b.from_table = 1;
+      g.desc = desc; g.ptr_table = gtab;
+      g.alpha = alpha; g.beta = beta; g.batch = b.count;
+      // L <- beta L + alpha G G^T
+      g.c = reinterpret_cast<float *>(ws + b.off_L); g.c_batch_stride = (int64_t)b.m * b.m; g.ldc = b.m;
+      g.M = b.m; g.N = b.m; g.K = b.n;
+      g.tiles_m = g.tiles_n = b.tiles_m; g.tiles = b.tiles_m * (b.tiles_m + 1) / 2;
+      rc = launch_gemm<K_CONTIG, K_CONTIG, GT, GT, EPI_SYRK, false>(g, s);
+      if (rc) return rc;
+      // R <- beta R + alpha G^T G
+      g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.n * b.n; g.ldc = b.n;
+      g.M = b.n; g.N = b.n; g.K = b.m;
+      g.tiles_m = g.tiles_n = b.tiles_n; g.tiles = b.tiles_n * (b.tiles_n + 1) / 2;
+      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GT, GT, EPI_SYRK, false>(g, s);
+      if (rc) return rc;
+    }
+    {
+      StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
+      EwArgs e{};
+      e.desc = desc; e.w_table = wtab; e.g_table = gtab; e.a_state = A; e.m_state = M;
+      e.sg_partial = reinterpret_cast<float *>(ws + b.off_sgp);
+      e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
+      hipLaunchKernelGGL(graft_kernel<GT>, dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+  if (refresh) {
+    StageTimer t(o, SHAMPOO_STAGE_ROOT, s);
+    for (size_t i = 0; i < p.buckets.size(); ++i) {
+      auto &b = p.buckets[i];
+      rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, c.root_exponent,
+                                reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
+                                ws + o->off_eig, o->eig_L[i], s);
+      if (rc) return rc;
+      rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, c.root_exponent,
+                                reinterpret_cast<float *>(ws + b.off_Rinv), nullptr, nullptr, fail_count,
+                                ws + o->off_eig, o->eig_R[i], s);
+      if (rc) return rc;
+    }
+    o->n_refresh++;
+  }
+  for (auto &b : p.buckets) {
+    const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
+    float *P = reinterpret_cast<float *>(ws + b.off_P);
+    float *scale = reinterpret_cast<float *>(ws + b.off_scale);
+    if (use_shampoo) {
+      StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
+      GemmArgs g{};
+      // T = Lbar G   (Lbar symmetric: A(i,k) read as Lbar[k][i], contiguous in i)
+      g.a.base = ws + b.off_Linv; g.a.batch_stride = (int64_t)b.m * b.m; g.a.ld = b.m;
+      g.b.from_table = 1; g.desc = desc; g.ptr_table = gtab;
+      g.c = T; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
+      g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = 1.f; g.beta = 0.f;
+      g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.tiles = b.tiles_m * b.tiles_n; g.batch = b.count;
+      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GT, EPI_STORE, false>(g, s);
+      if (rc) return rc;
+      // P = T Rbar, with per-tile sums of squares
+      GemmArgs h{};
+      h.a.base = T; h.a.batch_stride = (int64_t)b.m * b.n; h.a.ld = b.n;
+      h.b.base = ws + b.off_Rinv; h.b.batch_stride = (int64_t)b.n * b.n; h.b.ld = b.n;
+      h.c = P; h.c_batch_stride = (int64_t)b.m * b.n; h.ldc = b.n;
+      h.M = b.m; h.N = b.n; h.K = b.n; h.alpha = 1.f; h.beta = 0.f;
+      h.tiles_m = b.tiles_m; h.tiles_n = b.tiles_n; h.tiles = b.tiles_m * b.tiles_n; h.batch = b.count;
+      h.norm_partial = reinterpret_cast<float *>(ws + b.off_sshp);
+      rc = launch_gemm<K_CONTIG, ROW_CONTIG, float, float, EPI_STORE_NORM, false>(h, s);
+      if (rc) return rc;
+    }
+    {
+      StageTimer t(o, SHAMPOO_STAGE_UPDATE, s);
+      if (use_shampoo) {
+        ScaleArgs sa;
+        sa.sg_partial = reinterpret_cast<const float *>(ws + b.off_sgp); sa.sg_count = b.geom.chunks;
+        sa.ssh_partial = reinterpret_cast<const float *>(ws + b.off_sshp); sa.ssh_count = b.tiles_m * b.tiles_n;
+        sa.scale = scale; sa.norms = reinterpret_cast<float *>(ws + b.off_norms);
+        hipLaunchKernelGGL(scale_kernel, dim3(b.count), dim3(64), 0, s, sa);
+      }
+      EwArgs e{};
+      e.desc = desc; e.w_table = wtab; e.g_table = gtab; e.a_state = A; e.m_state = M;
+      e.p = P; e.scale = scale;
+      e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
+      e.graft_only = use_shampoo ? 0 : 1;
+      hipLaunchKernelGGL(update_kernel<GT>, dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+  if (!p.diag_chunks.empty()) {
+    StageTimer t(o, SHAMPOO_STAGE_DIAG, s);
+    DiagArgs d;
+    d.chunks = reinterpret_cast<const DiagChunk *>(ws + o->off_diag);
+    d.w_table = wtab; d.g_table = gtab; d.a_state = A; d.m_state = M;
+    d.graft_eps = c.graft_epsilon; d.mu = c.momentum; d.lr = lr;
+    hipLaunchKernelGGL(diag_kernel<GT>, dim3((unsigned)p.diag_chunks.size()), dim3(EW_THREADS), 0, s, d);
+    HIP_TRY(hipGetLastError());
+  }
+  return SHAMPOO_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// extern "C" boundary
+// ---------------------------------------------------------------------------
+extern "C" {
+
+int shampoo_plan(const shampoo_config *cfg, int64_t *table, int64_t cap, int64_t *n_blocks, int64_t *n_buckets) {
+  const int rc = check_config(cfg);
+  if (rc) return rc;
+  if (cap < 0 || (cap > 0 && !table)) return SHAMPOO_ERR_NULL;
+  Plan p;
+  make_plan(cfg, p);
+  if (n_blocks) *n_blocks = (int64_t)p.blocks.size();
+  if (n_buckets) *n_buckets = (int64_t)p.buckets.size();
+  const int64_t cnt = std::min<int64_t>(cap, (int64_t)p.blocks.size());
+  for (int64_t i = 0; i < cnt; ++i) {
+    const Block &b = p.blocks[i];
+    int64_t *row = table + 8 * i;
+    row[0] = b.param; row[1] = b.row0; row[2] = b.col0; row[3] = b.m; row[4] = b.n;
+    row[5] = b.bucket; row[6] = b.slot; row[7] = 0;
+  }
+  return SHAMPOO_OK;
+}
+
+size_t shampoo_workspace_bytes(const shampoo_config *cfg) {
+  if (check_config(cfg)) return 0;
+  Plan p;
+  make_plan(cfg, p);
+  return layout(cfg, p, nullptr);
+}
+
+int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_bytes, void *stream,
+                   shampoo_opt **out) {
+  if (!out) return SHAMPOO_ERR_NULL;
+  *out = nullptr;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  shampoo_opt *o = new (std::nothrow) shampoo_opt();
+  if (!o) return SHAMPOO_ERR_HIP;
+  o->cfg = *cfg;
+  o->ndim.assign(cfg->ndim, cfg->ndim + cfg->n_params);
+  o->shape.assign(cfg->shape, cfg->shape + 2 * (size_t)cfg->n_params);
+  o->cfg.ndim = o->ndim.data();
+  o->cfg.shape = o->shape.data();
+  make_plan(&o->cfg, o->plan);
+  const size_t need = layout(&o->cfg, o->plan, o);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % ALIGN) != 0 || workspace_bytes < need) {
+    delete o;
+    return SHAMPOO_ERR_WORKSPACE;
+  }
+  o->ws = static_cast<unsigned char *>(workspace);
+  o->ws_bytes = workspace_bytes;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  auto fail = [&](int code) { delete o; return code; };
+  if (hipSetDevice(cfg->device) != hipSuccess) return fail(SHAMPOO_ERR_HIP);
+  Plan &p = o->plan;
+  // state: A = M = 0, L = R = 0, roots = I
+  if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + o->off_A), 0.f, p.total_elems, s))) return fail(rc);
+  if (cfg->momentum > 0.f)
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + o->off_M), 0.f, p.total_elems, s))) return fail(rc);
+  if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + o->off_count), 0.f, 16, s))) return fail(rc);
+  std::vector<std::vector<BlockDesc>> descs(p.buckets.size());
+  for (size_t i = 0; i < p.buckets.size(); ++i) descs[i].resize(p.buckets[i].count);
+  for (const Block &b : p.blocks) {
+    BlockDesc d;
+    d.param = b.param;
+    d.ld = (int32_t)o->shape[2 * b.param + 1];
+    d.offset = b.row0 * d.ld + b.col0;
+    d.state_offset = p.param_state_offset[b.param] + d.offset;
+    descs[b.bucket][b.slot] = d;
+  }
+  for (size_t i = 0; i < p.buckets.size(); ++i) {
+    Bucket &b = p.buckets[i];
+    const int64_t B = b.count;
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_L), 0.f, B * b.m * b.m, s))) return fail(rc);
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_R), 0.f, B * b.n * b.n, s))) return fail(rc);
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_P), 0.f, B * b.m * b.n, s))) return fail(rc);
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_norms), 0.f, B * 2, s))) return fail(rc);
+    const int64_t tl = B * b.m * b.m, tr = B * b.n * b.n;
+    hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tl + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<float *>(o->ws + b.off_Linv), b.m, tl);
+    hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tr + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<float *>(o->ws + b.off_Rinv), b.n, tr);
+    if (hipGetLastError() != hipSuccess) return fail(SHAMPOO_ERR_HIP);
+    if (hipMemcpyAsync(o->ws + b.off_desc, descs[i].data(), descs[i].size() * sizeof(BlockDesc),
+                       hipMemcpyHostToDevice, s) != hipSuccess)
+      return fail(SHAMPOO_ERR_HIP);
+  }
+  if (!p.diag_chunks.empty())
+    if (hipMemcpyAsync(o->ws + o->off_diag, p.diag_chunks.data(), p.diag_chunks.size() * sizeof(DiagChunk),
+                       hipMemcpyHostToDevice, s) != hipSuccess)
+      return fail(SHAMPOO_ERR_HIP);
+  if (hipStreamSynchronize(s) != hipSuccess) return fail(SHAMPOO_ERR_HIP);
+  *out = o;
+  return SHAMPOO_OK;
+}
+
+int shampoo_step(shampoo_opt *o, void *const *params, const void *const *grads, float lr, int64_t step,
+                 void *stream) {
+  if (!o || !params || !grads) return SHAMPOO_ERR_NULL;
+  const int np = o->cfg.n_params;
+  for (int i = 0; i < np; ++i)
+    if (!params[i] || !grads[i]) return SHAMPOO_ERR_NULL;
+  if (step < 0 || step <= o->last_step) return SHAMPOO_ERR_STEP;
+  if (!std::isfinite(lr)) return SHAMPOO_ERR_HYPER;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipSetDevice(o->cfg.device));
+  // pointer tables: re-sent only when they change; the copy from pageable
+  // memory is staged before hipMemcpyAsync returns, so the vectors may be reused
+  bool same = (int)o->last_w.size() == np;
+  for (int i = 0; same && i < np; ++i) same = o->last_w[i] == params[i] && o->last_g[i] == grads[i];
+  if (!same) {
+    o->last_w.assign(params, params + np);
+    o->last_g.resize(np);
+    for (int i = 0; i < np; ++i) o->last_g[i] = const_cast<void *>(grads[i]);
+    HIP_TRY(hipMemcpyAsync(o->ws + o->off_wtab, o->last_w.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(o->ws + o->off_gtab, o->last_g.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
+  }
+  o->last_step = step;
+  if (o->cfg.grad_dtype == SHAMPOO_GRAD_BF16) return step_impl<uint16_t>(o, lr, step, s);
+  return step_impl<float>(o, lr, step, s);
+}
+
+int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, void *dst, size_t bytes,
+                void *stream) {
+  if (!o || !dst) return SHAMPOO_ERR_NULL;
+  if (param < 0 || param >= o->cfg.n_params) return SHAMPOO_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipSetDevice(o->cfg.device));
+  Plan &p = o->plan;
+  unsigned char *ws = o->ws;
+  if (o->ndim[param] == 1) {
+    if (block != 0 || (which != SHAMPOO_GET_A && which != SHAMPOO_GET_M)) return SHAMPOO_ERR_SHAPE;
+    if (which == SHAMPOO_GET_M && !(o->cfg.momentum > 0.f)) return SHAMPOO_ERR_SHAPE;
+    const size_t len = (size_t)o->shape[2 * param];
+    if (bytes != len * 4) return SHAMPOO_ERR_SHAPE;
+    const float *src = reinterpret_cast<const float *>(ws + (which == SHAMPOO_GET_A ? o->off_A : o->off_M)) +
+                       p.param_state_offset[param];
+    HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
+    return SHAMPOO_OK;
+  }
+  if (block < 0 || block >= (int32_t)p.param_blocks[param].size()) return SHAMPOO_ERR_SHAPE;
+  const Block &b = p.blocks[p.param_blocks[param][block]];
+  const Bucket &bk = p.buckets[b.bucket];
+  const size_t m = b.m, n = b.n;
+  const unsigned char *src = nullptr;
+  size_t need = 0;
+  switch (which) {
+    case SHAMPOO_GET_L: src = ws + bk.off_L + (size_t)b.slot * m * m * 4; need = m * m * 4; break;
+    case SHAMPOO_GET_R: src = ws + bk.off_R + (size_t)b.slot * n * n * 4; need = n * n * 4; break;
+    case SHAMPOO_GET_LINV: src = ws + bk.off_Linv + (size_t)b.slot * m * m * 4; need = m * m * 4; break;
+    case SHAMPOO_GET_RINV: src = ws + bk.off_Rinv + (size_t)b.slot * n * n * 4; need = n * n * 4; break;
+    case SHAMPOO_GET_PSH: src = ws + bk.off_P + (size_t)b.slot * m * n * 4; need = m * n * 4; break;
+    case SHAMPOO_GET_NORMS: src = ws + bk.off_norms + (size_t)b.slot * 8; need = 8; break;
+    case SHAMPOO_GET_A:
+    case SHAMPOO_GET_M: {
+      if (which == SHAMPOO_GET_M && !(o->cfg.momentum > 0.f)) return SHAMPOO_ERR_SHAPE;
+      if (bytes != m * n * 4) return SHAMPOO_ERR_SHAPE;
+      const int64_t ld = o->shape[2 * param + 1];
+      const float *base = reinterpret_cast<const float *>(ws + (which == SHAMPOO_GET_A ? o->off_A : o->off_M)) +
+                          p.param_state_offset[param] + b.row0 * ld + b.col0;
+      HIP_TRY(hipMemcpy2DAsync(dst, n * 4, base, (size_t)ld * 4, n * 4, m, hipMemcpyDeviceToDevice, s));
+      return SHAMPOO_OK;
+    }
+    default: return SHAMPOO_ERR_SHAPE;
+  }
+  if (bytes != need) return SHAMPOO_ERR_SHAPE;
+  HIP_TRY(hipMemcpyAsync(dst, src, need, hipMemcpyDeviceToDevice, s));
+  return SHAMPOO_OK;
+}
+
+int shampoo_status(shampoo_opt *o, void *stream, int64_t *n_refreshes, int64_t *n_failed_roots) {
+  if (!o) return SHAMPOO_ERR_NULL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipSetDevice(o->cfg.device));
+  unsigned long long cnt = 0;
+  HIP_TRY(hipMemcpyAsync(&cnt, o->ws + o->off_count, sizeof(cnt), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (n_refreshes) *n_refreshes = o->n_refresh;
+  if (n_failed_roots) *n_failed_roots = (int64_t)cnt;
+  return SHAMPOO_OK;
+}
+
+int shampoo_set_timing(shampoo_opt *o, int32_t enable) {
+  if (!o) return SHAMPOO_ERR_NULL;
+  o->timing = enable != 0;
+  return SHAMPOO_OK;
+}
+
+int shampoo_get_timing(shampoo_opt *o, int32_t stage, double *ms_total, int64_t *intervals) {
+  if (!o || !ms_total || !intervals) return SHAMPOO_ERR_NULL;
+  if (stage < 0 || stage >= SHAMPOO_STAGE_COUNT) return SHAMPOO_ERR_SHAPE;
+  double total = 0.0;
+  int64_t cnt = 0;
+  int rc = SHAMPOO_OK;
+  for (auto &iv : o->intervals[stage]) {
+    float ms = 0.f;
+    if (hipEventSynchronize(iv.b) != hipSuccess || hipEventElapsedTime(&ms, iv.a, iv.b) != hipSuccess)
+      rc = SHAMPOO_ERR_HIP;
+    else { total += ms; ++cnt; }
+    (void)hipEventDestroy(iv.a);
+    (void)hipEventDestroy(iv.b);
+  }
+  o->intervals[stage].clear();
+  *ms_total = total;
+  *intervals = cnt;
+  return rc;
+}
+
+int shampoo_destroy(shampoo_opt *o) {
+  if (!o) return SHAMPOO_ERR_NULL;
+  for (auto &v : o->intervals)
+    for (auto &iv : v) { (void)hipEventDestroy(iv.a); (void)hipEventDestroy(iv.b); }
+  delete o;
+  return SHAMPOO_OK;
+}
+
+size_t shampoo_root_inverse_workspace_bytes(int32_t n, int32_t batch) {
+  if (n < 1 || batch < 1 || n > MAX_BLOCK_SIZE) return 0;
+  return eig_layout(n, batch).bytes;
+}
+
+int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon, float r, float *x,
+                         float *lambda, int32_t *failed, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!a || !x) return SHAMPOO_ERR_NULL;
+  if (n < 1 || batch < 1) return SHAMPOO_ERR_SHAPE;
+  if (n > MAX_BLOCK_SIZE) return SHAMPOO_ERR_UNSUPPORTED;
+  if (!(epsilon > 0.f) || !std::isfinite(epsilon) || !(r > 0.f) || !std::isfinite(r)) return SHAMPOO_ERR_HYPER;
+  const EigLayout e = eig_layout(n, batch);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % ALIGN) != 0 || workspace_bytes < e.bytes)
+    return SHAMPOO_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (failed) {
+    const int rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, batch, s);
+    if (rc) return rc;
+  }
+  return root_inverse_batched(a, n, batch, epsilon, r, x, lambda, failed, nullptr,
+                              static_cast<unsigned char *>(workspace), e, s);
+}
+
+const char *shampoo_strerror(int code) {
+  switch (code) {
+    case SHAMPOO_OK: return "success";
+    case SHAMPOO_ERR_NULL: return "a required pointer is NULL";
+    case SHAMPOO_ERR_SHAPE: return "bad shape, dimension count, block size, index or byte count";
+    case SHAMPOO_ERR_HYPER: return "hyper-parameter out of range";
+    case SHAMPOO_ERR_WORKSPACE: return "workspace NULL, misaligned or too small";
+    case SHAMPOO_ERR_STEP: return "step must be non-negative and strictly increasing";
+    case SHAMPOO_ERR_HIP: return "a HIP runtime call failed";
+    case SHAMPOO_ERR_UNSUPPORTED: return "size outside the supported range";
+    default: return "unknown error code";
+  }
+}
+
+}  // extern "C"

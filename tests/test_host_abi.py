@@ -1,0 +1,124 @@
+"""Host-side tests of libshampoo (no GPU): the library loads, exports every
+symbol the header declares, validates configurations, and its block planner
+agrees with the blocking rule of Sec. 4.2.1 as written out in the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import shampoo_oracle as so
+from paper_2309_06497_amd import binding as B
+from paper_2309_06497_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def cfg_for(shapes, b, **kw):
+    args = dict(beta2=0.999, epsilon=1e-12, root_exponent=0.25, precondition_frequency=10)
+    args.update(kw)
+    return B.make_config(shapes, b, **args)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "shampoo.h")).read()
+    declared = set(re.findall(r"\b(shampoo_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.shampoo_strerror(0) == b"success"
+    assert L.shampoo_strerror(-4).startswith(b"workspace")
+
+
+@pytest.mark.parametrize("name,shapes,b", [
+    ("tiny", wl.tiny_shapes(), 64),
+    ("uniform", wl.uniform_shapes(), 128),
+    ("resnet50", wl.resnet50_shapes(), 128),
+    ("transformer", wl.transformer_shapes(), 1024),
+    ("ragged", [(5, 7), (3,), (130, 257), (1, 1)], 128),
+])
+def test_planner_matches_blocking_rule(name, shapes, b):
+    cfg = cfg_for(shapes, b)
+    table, n_buckets = B.shampoo_plan(cfg)
+    expect = []
+    for i, s in enumerate(shapes):
+        if len(s) == 2:
+            expect += [(i, r0, c0, m, n) for (r0, c0, m, n) in so.block_partition(s[0], s[1], b)]
+    assert [tuple(int(x) for x in row[:5]) for row in table] == expect
+    # buckets: equal (m, n) share a bucket, slots count up inside it in table order
+    seen = {}
+    for row in table:
+        key = (int(row[3]), int(row[4]))
+        bucket, slot = int(row[5]), int(row[6])
+        if key not in seen:
+            seen[key] = [bucket, 0]
+        assert seen[key][0] == bucket and seen[key][1] == slot
+        seen[key][1] += 1
+    assert len(seen) == n_buckets
+    assert len({v[0] for v in seen.values()}) == n_buckets
+
+
+def test_planner_histograms_of_the_named_workloads():
+    t, nb = B.shampoo_plan(cfg_for(wl.tiny_shapes(), 64))
+    assert len(t) == 8 and nb == 1 and set(map(tuple, t[:, 3:5])) == {(64, 64)}
+    t, nb = B.shampoo_plan(cfg_for(wl.uniform_shapes(), 128))
+    assert len(t) == 512 and nb == 1
+    t, nb = B.shampoo_plan(cfg_for(wl.resnet50_shapes(), 128))
+    assert len(t) == 1576 and nb == 6
+    t, nb = B.shampoo_plan(cfg_for(wl.transformer_shapes(), 1024))
+    assert len(t) == 1152 and nb == 1
+
+
+def test_workspace_holds_the_state_of_the_memory_rule():
+    """Sec. 4.2.1: blocked Shampoo on a matrix stores 4 d1 d2 numbers (factors and
+    roots) when b divides both dimensions; plus A, M, the direction scratch."""
+    d1, d2, b = 512, 384, 128
+    cfg = cfg_for([(d1, d2)], b, momentum=0.9)
+    nbytes = B.shampoo_workspace_bytes(cfg)
+    state = 4 * d1 * d2 + 2 * d1 * d2      # factors + roots, A + M
+    scratch = 2 * d1 * d2                   # P and T
+    assert nbytes >= 4 * (state + scratch)
+    assert nbytes < 4 * (state + scratch) * 1.02 + (1 << 16)
+    # the transformer workload fits one MI355X (288 GB) with room to spare
+    big = B.shampoo_workspace_bytes(cfg_for(wl.transformer_shapes(), 1024, momentum=0.9))
+    assert 35e9 < big < 60e9
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(beta2=0.0), -3), (dict(beta2=1.5), -3), (dict(epsilon=0.0), -3), (dict(epsilon=-1.0), -3),
+    (dict(root_exponent=0.0), -3), (dict(precondition_frequency=0), -3),
+    (dict(start_preconditioning_step=-1), -3), (dict(graft_epsilon=-1.0), -3),
+    (dict(momentum=1.0), -3), (dict(momentum=-0.1), -3), (dict(grad_dtype=7), -3),
+])
+def test_bad_hyperparameters_are_rejected(kw, code):
+    cfg = cfg_for([(8, 8)], 4, **kw)
+    assert B.lib().shampoo_plan(ctypes.byref(cfg), None, 0, None, None) == code
+    assert B.shampoo_workspace_bytes(cfg) == 0
+
+
+def test_bad_shapes_are_rejected():
+    L = B.lib()
+    assert L.shampoo_plan(None, None, 0, None, None) == -1
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 0)], 4)), None, 0, None, None) == -2
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(0,)], 4)), None, 0, None, None) == -2
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8)], 0)), None, 0, None, None) == -2
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8)], 100000)), None, 0, None, None) == -7
+    cfg = cfg_for([(8, 8)], 4)
+    cfg.n_params = 0
+    assert L.shampoo_plan(ctypes.byref(cfg), None, 0, None, None) == -2
+    cfg = cfg_for([(8, 8, 8)], 4)   # ndim 3
+    assert L.shampoo_plan(ctypes.byref(cfg), None, 0, None, None) == -2
+    # a table pointer is required when cap > 0
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8)], 4)), None, 3, None, None) == -1
+    # null handles
+    assert L.shampoo_step(None, None, None, 0.1, 0, None) == -1
+    assert L.shampoo_destroy(None) == -1
+    assert L.shampoo_get(None, 0, 0, 0, None, 0, None) == -1
+    assert L.shampoo_root_inverse_workspace_bytes(0, 1) == 0
+    assert L.shampoo_root_inverse_workspace_bytes(1024, 4) > 2 * 4 * 1024 * 1024 * 4
+    out = ctypes.c_void_p()
+    # create checks the workspace before touching any device
+    assert L.shampoo_create(ctypes.byref(cfg_for([(8, 8)], 4)), None, 0, None, ctypes.byref(out)) == -4
+    assert L.shampoo_create(ctypes.byref(cfg_for([(8, 8)], 4)), None, 0, None, None) == -1
