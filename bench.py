@@ -1,0 +1,225 @@
+"""Benchmark of the per-block Shampoo step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload transformer|resnet50|uniform]
+
+Workload (default): the transformer-shaped parameter set -- 24 layers at d = 2048
+(QKV 2048x6144, attention out 2048x2048, MLP up 2048x8192, MLP down 8192x2048,
+LayerNorm vectors), block size 1024 -> 1152 blocks of 1024x1024, 1.21e9 parameters,
+bf16 gradients N(0, 1e-3^2), float32 factors / roots / state, beta2 = 0.999,
+epsilon = 1e-12, root exponent 1/4, precondition_frequency = 100, AdaGrad grafting
+(eps 1e-10), momentum 0.9, lr 0.01.  Everything is synthetic and seeded; gradients are
+resident in HBM before the timed region (a pool of two pre-generated sets is cycled).
+
+A "step" is one whole shampoo_step: factor updates, grafting pass, two-sided
+preconditioning, rescale + momentum + parameter update, 1-D parameters.  Step 0 holds
+the root-inverse refresh; it runs in the warm-up and its time is reported separately
+(`refresh_ms`).  The K timed steps are non-refresh steps.
+
+One JSON line is printed:
+  metric/value        milliseconds per (non-refresh) step, whole job, one GPU
+  roofline            the dominant kernel (the float32-MFMA GEMM of the two-sided
+                      preconditioning): algorithmic flops per launch / average launch
+                      duration from HIP events recorded by the library on the step's stream
+  cpu_baseline        the fp64 numpy oracle timed on the host on a sample of blocks
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+TILE = 128
+
+
+def workload(name):
+    from paper_2309_06497_amd import workloads as wl
+    from paper_2309_06497_amd import binding as B
+    if name == "transformer":
+        return dict(shapes=wl.transformer_shapes(), block=1024, sigma=1e-3, f=100, bf16=True,
+                    label="transformer 24 x d2048, block 1024, 1152 blocks, bf16 gradients")
+    if name == "resnet50":
+        return dict(shapes=wl.resnet50_shapes(), block=128, sigma=1e-3, f=50, bf16=False,
+                    label="ResNet-50 shapes, block 128, 1576 blocks, fp32 gradients")
+    if name == "uniform":
+        return dict(shapes=wl.uniform_shapes(), block=128, sigma=1e-3, f=100, bf16=False,
+                    label="512 blocks of 128x128, fp32 gradients")
+    raise SystemExit(f"unknown workload {name}")
+
+
+def flop_counts(table):
+    """Algorithmic flops per step (symmetric updates at triangular cost) and the flops the
+    128 x 128-tiled kernels execute (whole diagonal tiles)."""
+    alg_factor = alg_precond = exe_factor = exe_precond = 0.0
+    for row in table:
+        m, n = float(row[3]), float(row[4])
+        alg_factor += m * n * (m + n)
+        alg_precond += 2 * m * n * (m + n)
+        tm, tn = -(-int(m) // TILE), -(-int(n) // TILE)
+        exe_factor += 2.0 * TILE * TILE * (tm * (tm + 1) / 2 * n + tn * (tn + 1) / 2 * m)
+        exe_precond += 2.0 * TILE * TILE * tm * tn * (m + n)
+    return alg_factor, alg_precond, exe_factor, exe_precond
+
+
+def cpu_baseline(wk, table, rng_seed=0):
+    """The oracle, untuned, on the host cores: a bounded sample of blocks of the largest
+    bucket for one non-refresh step, and a few factors for the refresh; scaled linearly to
+    the whole block set (blocks are independent)."""
+    from oracle import shampoo_oracle as so
+    rng = np.random.default_rng(rng_seed)
+    sizes = {}
+    for row in table:
+        sizes[(int(row[3]), int(row[4]))] = sizes.get((int(row[3]), int(row[4])), 0) + 1
+    (m, n), _ = max(sizes.items(), key=lambda kv: kv[1] * kv[0][0] * kv[0][1])
+    elems_total = sum(float(r[3]) * float(r[4]) for r in table)
+    n_step = 8 if m * n >= 512 * 512 else 64
+    n_root = 4 if m >= 512 else 32
+    f32 = lambda v: float(np.float32(v))
+    state = []
+    for _ in range(n_step):
+        G = (rng.standard_normal((m, n)) * wk["sigma"]).astype(np.float32)
+        L, R = so.factor_update(np.zeros((m, m)), np.zeros((n, n)), G, f32(0.999))
+        state.append([L, R, np.eye(m), np.eye(n), np.zeros((m, n)), np.zeros((m, n)), np.zeros((m, n))])
+    t0 = time.perf_counter()
+    for st in state:
+        G = (rng.standard_normal((m, n)) * wk["sigma"]).astype(np.float32)
+        st[0], st[1] = so.factor_update(st[0], st[1], G, f32(0.999))
+        st[4] = so.graft_state_update(st[4], G)
+        Pg = so.graft_direction(G, st[4], f32(1e-10))
+        P = so.grafted_direction(so.shampoo_direction(st[2], G, st[3]), Pg)
+        st[5] = f32(0.9) * st[5] + P
+        st[6] += f32(0.01) * st[5]
+    t_step = (time.perf_counter() - t0) / (n_step * m * n) * elems_total
+    t0 = time.perf_counter()
+    for st in state[:n_root]:
+        so.root_inverse(st[0], f32(1e-12), 0.25)
+        so.root_inverse(st[1], f32(1e-12), 0.25)
+    t_root = (time.perf_counter() - t0) / (n_root * (m * m + n * n)) * sum(
+        float(r[3]) ** 2 + float(r[4]) ** 2 for r in table)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": t_step * 1e3, "unit": "ms/step", "cores": cores, "kind": "oracle",
+            "refresh_ms": t_root * 1e3,
+            "sample": f"{n_step} of {len(table)} blocks ({m}x{n}) for one non-refresh step and "
+                      f"{2 * n_root} factors for the refresh, numpy float64 (LAPACK eigh), "
+                      f"scaled linearly to the whole block set (extrapolated)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="transformer")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the multi-GPU distribution of the "
+              "paper is out of scope); rerun with --gpus 1", file=sys.stderr)
+        return 2
+    import torch
+    from paper_2309_06497_amd import binding as B
+
+    wk = workload(args.workload)
+    shapes = wk["shapes"]
+    f = wk["f"]
+    warm = max(args.warmup, 1)
+    if warm + args.steps > f:
+        print(f"bench.py: warmup + steps must stay below precondition_frequency = {f}", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    gdt = torch.bfloat16 if wk["bf16"] else torch.float32
+    params = [torch.randn(s, generator=gen, device=dev, dtype=torch.float32) * 0.02 for s in shapes]
+    pool = [[(torch.randn(s, generator=gen, device=dev, dtype=torch.float32) * wk["sigma"]).to(gdt)
+             for s in shapes] for _ in range(2)]
+    opt = B.Shampoo(shapes, wk["block"], 0.999, 1e-12, 0.25, f, 0, 1e-10, 0.9,
+                    B.GRAD_BF16 if wk["bf16"] else B.GRAD_F32)
+    table, n_buckets = opt.plan()
+    n_elems = sum(int(np.prod(s)) for s in shapes)
+
+    # warm-up: step 0 carries the root-inverse refresh
+    opt.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    opt.step(params, pool[0], 0.01, 0)
+    torch.cuda.synchronize()
+    first_step_ms = (time.perf_counter() - t0) * 1e3
+    refresh_ms = opt.get_timing()["root"][0]
+    for t in range(1, warm):
+        opt.step(params, pool[t % 2], 0.01, t)
+    torch.cuda.synchronize()
+    opt.get_timing()
+
+    t0 = time.perf_counter()
+    for t in range(warm, warm + args.steps):
+        opt.step(params, pool[t % 2], 0.01, t)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    stages = opt.get_timing()
+    status = opt.status()
+
+    alg_f, alg_p, exe_f, exe_p = flop_counts(table)
+    st_ms = {k: v[0] / args.steps for k, v in stages.items()}
+    # two launches of the same GEMM kernel per bucket in the preconditioning stage
+    n_launch = stages["precond"][1] * 2
+    launch_ms = stages["precond"][0] / max(n_launch, 1)
+    gemm_flops_per_launch = alg_p * args.steps / max(n_launch, 1)
+    achieved = gemm_flops_per_launch / (launch_ms * 1e-3) / 1e12 if launch_ms > 0 else 0.0
+    gsz = 2 if wk["bf16"] else 4
+    ew_bytes = {"graft": (gsz + 8.0) * n_elems, "update": 20.0 * n_elems}
+    out = {
+        "metric": "shampoo_step_ms",
+        "value": ms_per_step,
+        "unit": "ms/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": warm,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wk["label"], "params": n_elems, "blocks": int(len(table)),
+                   "buckets": int(n_buckets), "block_size": wk["block"], "precondition_frequency": f,
+                   "grad_dtype": "bf16" if wk["bf16"] else "f32"},
+        "refresh_ms": refresh_ms,
+        "first_step_ms": first_step_ms,
+        "amortized_ms_per_step": ms_per_step + refresh_ms / f,
+        "tflops_algorithmic": (alg_f + alg_p) / (ms_per_step * 1e-3) / 1e12,
+        "tflops_executed": (exe_f + exe_p) / (ms_per_step * 1e-3) / 1e12,
+        "stage_ms_per_step": st_ms,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "kernel": "gemm_mfma_kernel (two-sided preconditioning, fp32 MFMA)",
+                     "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch},
+        "stage_roofline": {
+            "factor": {"bound": "mfma", "tflops_algorithmic": alg_f / (st_ms["factor"] * 1e-3) / 1e12 if st_ms["factor"] else 0,
+                       "tflops_executed": exe_f / (st_ms["factor"] * 1e-3) / 1e12 if st_ms["factor"] else 0},
+            "precond": {"bound": "mfma", "tflops": alg_p / (st_ms["precond"] * 1e-3) / 1e12 if st_ms["precond"] else 0},
+            "graft": {"bound": "hbm", "GBps": ew_bytes["graft"] / (st_ms["graft"] * 1e-3) / 1e9 if st_ms["graft"] else 0},
+            "update": {"bound": "hbm", "GBps": ew_bytes["update"] / (st_ms["update"] * 1e-3) / 1e9 if st_ms["update"] else 0},
+        },
+        "status": status,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wk, table)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

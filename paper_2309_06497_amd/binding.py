@@ -172,6 +172,8 @@ class Shampoo:
         else:
             table = self.plan()[0]
             rows = table[table[:, 0] == param]
+            if not 0 <= block < len(rows):
+                raise ShampooError(-2)
             m, n = int(rows[block, 3]), int(rows[block, 4])
             shape = {GET_L: (m, m), GET_LINV: (m, m), GET_R: (n, n), GET_RINV: (n, n),
                      GET_A: (m, n), GET_M: (m, n), GET_PSH: (m, n), GET_NORMS: (2,)}[which]

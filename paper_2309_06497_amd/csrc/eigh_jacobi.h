@@ -3,8 +3,9 @@
 // + eps; return Q diag(lambda'^-r) Q^T).  The paper calls a library eigh; this is
 // a Jacobi solver laid out for CDNA4:
 //
-//  * n <= 128: one workgroup per matrix, the matrix A and the accumulated
-//    rotations J both resident in LDS.  Rounds of n/2 disjoint rotations
+//  * n <= 128: one workgroup per matrix, the matrix A (float64, packed lower
+//    triangle) and the accumulated rotations J (float32) both resident in LDS
+//    (132 KB at n = 128).  Rounds of n/2 disjoint rotations
 //    (round-robin tournament ordering); in a round every thread updates whole
 //    2 x 2 blocks  R_k^T [a b; c d] R_l  so rows and columns are rotated in one
 //    pass with no intermediate barrier.  The root inverse is formed in the
@@ -12,13 +13,13 @@
 //  * n > 128: two-sided block Jacobi.  The matrix (padded to a multiple of 64)
 //    is cut into 32-wide block columns; a round pairs them up, each 64 x 64
 //    pivot is diagonalised by the LDS solver above, and the 64 x 64 rotation
-//    blocks are applied to A (both sides, A_kl <- J_k^T A_kl J_l) and to Q^T
-//    (rows) with fp32 MFMA.  The reconstruction Q f(Lambda) Q^T reuses the
-//    batched SYRK kernel.
+//    blocks are applied to A (both sides, A_kl <- J_k^T A_kl J_l, float64 MFMA)
+//    and to Q^T (rows, float32 MFMA).  The reconstruction Q f(Lambda) Q^T reuses
+//    the batched SYRK kernel.
 //
 // Rotations are applied in the form x' = x - s (y + tau x), y' = y + s (x - tau y)
-// with tau = s / (1 + c): for small angles the float32 cosine rounds to 1 and
-// the plain form c x - s y would let the columns of Q grow by t^2 per rotation.
+// with tau = s / (1 + c): for small angles the cosine rounds to 1 and the plain
+// form c x - s y would let the columns of Q grow by t^2 per rotation.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -30,15 +31,16 @@ constexpr int JAC_THREADS = 256;
 constexpr int JAC_NB = 32;            // block-column width of the block solver
 constexpr int JAC_PIV = 2 * JAC_NB;   // pivot size
 constexpr int JAC_SMALL_MAX = 128;    // largest n solved entirely in LDS
-constexpr int JAC_SMALL_SWEEPS = 16;
-constexpr int JAC_OUTER_SWEEPS = 12;
+constexpr int JAC_SMALL_SWEEPS = 20;
+constexpr int JAC_OUTER_SWEEPS = 16;
 constexpr int JAC_INNER_SWEEPS = 2;
-constexpr float JAC_TOL_REL = 5.9604645e-8f;   // 2^-24
-constexpr float JAC_TOL_ABS = 9.3132257e-10f;  // 2^-30, times the largest |diagonal| of the input
+// rotation thresholds |a_pq| > rel * sqrt(|a_pp a_qq|) and > abs * max|diag(input)|
+constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver on a float64 copy of the factor
+constexpr double JAC_SMALL_TOL_ABS = 1e-15;
 
 struct JacScratch {      // small per-workgroup LDS arrays
-  float s[JAC_SMALL_MAX / 2];
-  float t[JAC_SMALL_MAX / 2];
+  double s[JAC_SMALL_MAX / 2];
+  double t[JAC_SMALL_MAX / 2];
   int p[JAC_SMALL_MAX / 2];
   int q[JAC_SMALL_MAX / 2];
   int flag;
@@ -55,11 +57,21 @@ __device__ __host__ __forceinline__ void rr_pair(int cnt, int r, int k, int &p, 
   if (p > q) { const int t = p; p = q; q = t; }
 }
 
+// index of element (i, j) of a symmetric matrix stored as its packed lower triangle
+__device__ __forceinline__ int tri(int i, int j) {
+  return i >= j ? i * (i + 1) / 2 + j : j * (j + 1) / 2 + i;
+}
+
 // Up to max_sweeps sweeps of parallel two-sided Jacobi on the s x s (s even)
-// symmetric matrix As, accumulating J <- J R.  LD = LDS row stride (odd, so that
-// column walks are bank-conflict free).  Returns nonzero if any rotation was
-// applied.  All threads must call it.
-__device__ int jacobi_sweeps(float *As, float *Js, int s, const int LD, int max_sweeps, float tol_abs, JacScratch *sc) {
+// symmetric matrix At (float64, packed lower triangle), accumulating the
+// rotations into the float32 matrix J <- J R (row stride LD, odd).  Keeping A in
+// float64 makes the small eigenvalues of an ill-conditioned factor (a single
+// G G^T at the first refresh) as accurate as the stored factor allows; the
+// rotations themselves only need float32.  Because A is symmetric only the
+// 2 x 2 blocks (rows of pair k, columns of pair l) with l <= k are updated.
+// Returns nonzero if any rotation was applied.  All threads must call it.
+__device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, int max_sweeps, double tol_rel,
+                             double tol_abs, JacScratch *sc) {
   const int tid = threadIdx.x;
   const int half = s >> 1;
   int any = 0;
@@ -69,48 +81,50 @@ __device__ int jacobi_sweeps(float *As, float *Js, int s, const int LD, int max_
     for (int r = 0; r < s - 1; ++r) {
       if (tid < half) {
         int p, q;
-        rr_pair(s, r, tid, p, q);
-        const float app = As[p * LD + p], aqq = As[q * LD + q], apq = As[p * LD + q];
-        float sn = 0.f, tp = 0.f;
-        const float aa = fabsf(apq);
-        if (aa > tol_abs && aa > JAC_TOL_REL * sqrtf(fabsf(app * aqq))) {
-          const float tau = (aqq - app) / (2.f * apq);
-          const float t = copysignf(1.f, tau) / (fabsf(tau) + sqrtf(1.f + tau * tau));
-          const float c = 1.f / sqrtf(1.f + t * t);
+        rr_pair(s, r, tid, p, q);   // p < q
+        const double app = At[tri(p, p)], aqq = At[tri(q, q)], apq = At[tri(q, p)];
+        double sn = 0.0, tp = 0.0;
+        const double aa = fabs(apq);
+        if (aa > tol_abs && aa > tol_rel * sqrt(fabs(app * aqq))) {
+          const double tau = (aqq - app) / (2.0 * apq);
+          const double t = copysign(1.0, tau) / (fabs(tau) + sqrt(1.0 + tau * tau));
+          const double c = 1.0 / sqrt(1.0 + t * t);
           sn = t * c;
-          tp = sn / (1.f + c);
-          if (sn != 0.f) sc->flag = 1;
+          tp = sn / (1.0 + c);
+          if (sn != 0.0) sc->flag = 1;
         }
         sc->s[tid] = sn; sc->t[tid] = tp; sc->p[tid] = p; sc->q[tid] = q;
       }
       __syncthreads();
-      // A <- R^T A R, one 2 x 2 block (rows of pair k, columns of pair l) per step
+      // A <- R^T A R on the blocks with l <= k
       for (int k = tid >> 5; k < half; k += JAC_THREADS / 32) {
         const int pk = sc->p[k], qk = sc->q[k];
-        const float sk = sc->s[k], tk = sc->t[k];
-        for (int l = tid & 31; l < half; l += 32) {
+        const double sk = sc->s[k], tk = sc->t[k];
+        for (int l = tid & 31; l <= k; l += 32) {
           const int pl = sc->p[l], ql = sc->q[l];
-          const float sl = sc->s[l], tl = sc->t[l];
-          if (sk == 0.f && sl == 0.f) continue;
-          float a = As[pk * LD + pl], b = As[pk * LD + ql];
-          float c = As[qk * LD + pl], d = As[qk * LD + ql];
+          const double sl = sc->s[l], tl = sc->t[l];
+          if (sk == 0.0 && sl == 0.0) continue;
+          const int ia = tri(pk, pl), ib = tri(pk, ql), ic = tri(qk, pl), id = tri(qk, ql);
+          double a = At[ia], b = At[ib], c = At[ic], d = At[id];
           // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
-          float a1 = a - sk * (c + tk * a), c1 = c + sk * (a - tk * c);
-          float b1 = b - sk * (d + tk * b), d1 = d + sk * (b - tk * d);
+          const double a1 = a - sk * (c + tk * a), c1 = c + sk * (a - tk * c);
+          const double b1 = b - sk * (d + tk * b), d1 = d + sk * (b - tk * d);
           // columns: (a1, b1) and (c1, d1) are (x, y) pairs of rotation l
           a = a1 - sl * (b1 + tl * a1); b = b1 + sl * (a1 - tl * b1);
           c = c1 - sl * (d1 + tl * c1); d = d1 + sl * (c1 - tl * d1);
-          if (k == l) { b = 0.f; c = 0.f; }   // the annihilated pivot element
-          As[pk * LD + pl] = a; As[pk * LD + ql] = b;
-          As[qk * LD + pl] = c; As[qk * LD + ql] = d;
+          if (k == l) {   // pivot block: ib == ic is the annihilated element
+            At[ia] = a; At[ib] = 0.0; At[id] = d;
+          } else {
+            At[ia] = a; At[ib] = b; At[ic] = c; At[id] = d;
+          }
         }
       }
       // J <- J R (columns)
       for (int i = tid >> 5; i < s; i += JAC_THREADS / 32) {
         for (int l = tid & 31; l < half; l += 32) {
-          const float sl = sc->s[l];
+          const float sl = (float)sc->s[l];
           if (sl == 0.f) continue;
-          const float tl = sc->t[l];
+          const float tl = (float)sc->t[l];
           const int pl = sc->p[l], ql = sc->q[l];
           const float x = Js[i * LD + pl], y = Js[i * LD + ql];
           Js[i * LD + pl] = x - sl * (y + tl * x);
@@ -141,7 +155,6 @@ struct SmallRootArgs {
   float epsilon, r;
 };
 
-
 __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallRootArgs g) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ float redf[JAC_THREADS / 64];
@@ -153,24 +166,28 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
   const int b = blockIdx.x;
   const int n = g.n;
   const int s = (n + 1) & ~1;
-  const int SMALL_LD = s + 1;
-  float *As = reinterpret_cast<float *>(smem);
-  float *Js = As + s * SMALL_LD;
-  float *fv = Js + s * SMALL_LD;            // [s]
+  const int LD = s + 1;
+  double *At = reinterpret_cast<double *>(smem);            // s (s + 1) / 2
+  float *Js = reinterpret_cast<float *>(At + s * (s + 1) / 2);
+  float *fv = Js + s * LD;                                  // [s]
   const float *a = g.a + (int64_t)b * g.a_stride;
 
+  // load (symmetrising: a no-op for exactly symmetric input), padding decoupled zeros
   int bad = 0;
   float dmax = 0.f;
   for (int i = tid >> 6; i < s; i += JAC_THREADS / 64)
     for (int j = lane; j < s; j += 64) {
-      float v = 0.f;
-      if (i < n && j < n) {
-        v = a[(int64_t)i * n + j];
-        if (!(fabsf(v) <= 3.0e38f)) bad = 1;
-        if (i == j) dmax = fmaxf(dmax, fabsf(v));
+      if (j <= i) {
+        double v = 0.0;
+        if (i < n) {
+          const float lo = a[(int64_t)i * n + j], up = a[(int64_t)j * n + i];
+          if (!(fabsf(lo) <= 3.0e38f) || !(fabsf(up) <= 3.0e38f)) bad = 1;
+          v = 0.5 * ((double)lo + (double)up);
+          if (i == j) dmax = fmaxf(dmax, fabsf(lo));
+        }
+        At[i * (i + 1) / 2 + j] = v;
       }
-      As[i * SMALL_LD + j] = v;
-      Js[i * SMALL_LD + j] = (i == j) ? 1.f : 0.f;
+      Js[i * LD + j] = (i == j) ? 1.f : 0.f;
     }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
@@ -188,36 +205,28 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
     }
     return;
   }
-  // symmetrise (a no-op for exactly symmetric input)
-  for (int i = tid >> 6; i < s; i += JAC_THREADS / 64)
-    for (int j = lane; j < i; j += 64) {
-      const float v = 0.5f * (As[i * SMALL_LD + j] + As[j * SMALL_LD + i]);
-      As[i * SMALL_LD + j] = v;
-      As[j * SMALL_LD + i] = v;
-    }
-  __syncthreads();
 
-  jacobi_sweeps(As, Js, s, SMALL_LD, JAC_SMALL_SWEEPS, JAC_TOL_ABS * dmax, sc);
+  jacobi_sweeps(At, Js, s, LD, JAC_SMALL_SWEEPS, JAC_SMALL_TOL_REL, JAC_SMALL_TOL_ABS * (double)dmax, sc);
   __syncthreads();
 
   // lambda_min over the true eigenvalues, then f = (lambda - min(lambda_min, 0) + eps)^-r
-  float lmin = 3.0e38f;
-  for (int i = tid; i < n; i += JAC_THREADS) lmin = fminf(lmin, As[i * SMALL_LD + i]);
+  double lmin = 1.0e300;
+  for (int i = tid; i < n; i += JAC_THREADS) lmin = fmin(lmin, At[i * (i + 1) / 2 + i]);
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) lmin = fminf(lmin, __shfl_xor(lmin, off, 64));
-  if (lane == 0) redf[wave] = lmin;
+  for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   __syncthreads();
-  lmin = fminf(fminf(redf[0], redf[1]), fminf(redf[2], redf[3]));
-  const float shift = fminf(lmin, 0.f);
+  if (lane == 0) reinterpret_cast<double *>(sc->s)[wave] = lmin;   // rotation scratch is free now
+  __syncthreads();
+  lmin = fmin(fmin(sc->s[0], sc->s[1]), fmin(sc->s[2], sc->s[3]));
+  const double shift = fmin(lmin, 0.0);
   int badf = 0;
   for (int i = tid; i < s; i += JAC_THREADS) {
     float f = 0.f;
     if (i < n) {
-      const float lam = As[i * SMALL_LD + i];
-      const double ln = (double)(lam - shift) + (double)g.epsilon;
-      f = (float)pow(ln, -(double)g.r);
+      const double lam = At[i * (i + 1) / 2 + i];
+      f = (float)pow(lam - shift + (double)g.epsilon, -(double)g.r);
       if (!(f <= 3.0e38f) || !(f >= 0.f)) badf = 1;
-      if (g.lambda) g.lambda[(int64_t)b * n + i] = lam;
+      if (g.lambda) g.lambda[(int64_t)b * n + i] = (float)lam;
     }
     fv[i] = sqrtf(f);
   }
@@ -233,13 +242,13 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
   }
   // J <- J diag(sqrt f); X = J J^T, lower triangle computed and mirrored
   for (int i = tid >> 6; i < n; i += JAC_THREADS / 64)
-    for (int k = lane; k < s; k += 64) Js[i * SMALL_LD + k] *= fv[k];
+    for (int k = lane; k < s; k += 64) Js[i * LD + k] *= fv[k];
   __syncthreads();
   float *x = g.x + (int64_t)b * g.x_stride;
   for (int i = tid >> 6; i < n; i += JAC_THREADS / 64)
     for (int j = lane; j <= i; j += 64) {
       float acc = 0.f;
-      for (int k = 0; k < n; ++k) acc += Js[i * SMALL_LD + k] * Js[j * SMALL_LD + k];
+      for (int k = 0; k < n; ++k) acc += Js[i * LD + k] * Js[j * LD + k];
       x[(int64_t)i * n + j] = acc;
       x[(int64_t)j * n + i] = acc;
     }
@@ -247,17 +256,25 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
 
 inline size_t rootinv_small_lds_bytes(int n) {
   const int s = (n + 1) & ~1;
-  return (size_t)(2 * s * (s + 1) + s) * sizeof(float);
+  return (size_t)(s * (s + 1) / 2) * sizeof(double) + (size_t)(s * (s + 1) + s) * sizeof(float);
 }
 
 // ---------------------------------------------------------------------------
 // n > 128: block Jacobi.  Work arrays per matrix (np = n rounded up to 64):
-//   W  [np][np]  the matrix being diagonalised (padding: zero, decoupled)
-//   Qt [np][np]  accumulated rotations, transposed (rows are eigenvectors)
-//   J  [np/64][64][64] rotation blocks of the current round
+//   W  [np][np] float64  the matrix being diagonalised (padding: zero, decoupled);
+//                        kept exactly symmetric (mirrored writes)
+//   Qt [np][np] float32  accumulated rotations, transposed (rows are eigenvectors)
+//   J  [np/64][64][64] float32 rotation blocks of the current round
+// W is float64 for the same reason as in the LDS solver: the update
+// A_kl <- J_k^T A_kl J_l runs on the float64 matrix cores (v_mfma_f64_16x16x4_f64),
+// so eigenvalues far below 2^-24 lambda_max survive the ~400 updates of a solve.
+// J is only orthogonal to float32 accuracy; applied as a congruence this moves
+// every eigenvalue by a *relative* 1e-7 per round, which is harmless.
 // ---------------------------------------------------------------------------
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
 struct BlockJacArgs {
-  float *w;
+  double *w;
   float *qt;
   float *jbuf;
   int32_t *ident;        // [batch][np/64]: pivot of the current round needed no rotation
@@ -270,29 +287,30 @@ struct BlockJacArgs {
 
 struct BlockInitArgs {
   const float *a; int64_t a_stride; int32_t n;
-  float *w; float *qt; int32_t np;
+  double *w; float *qt; int32_t np;
   float *dmax; int32_t *failed; int32_t *rot;
 };
 
-// W = pad(A), Qt = I, dmax, failed, rot = 0.  grid (np, batch), 256 threads.
+// W = pad(sym(A)), Qt = I, dmax, failed, rot = 0.  grid (np, batch), 256 threads.
 __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs g) {
   const int b = blockIdx.y, i = blockIdx.x, np = g.np, n = g.n;
-  float *w = g.w + (int64_t)b * np * np + (int64_t)i * np;
+  double *w = g.w + (int64_t)b * np * np + (int64_t)i * np;
   float *qt = g.qt + (int64_t)b * np * np + (int64_t)i * np;
-  const float *a = g.a + (int64_t)b * g.a_stride + (int64_t)i * n;
+  const float *a = g.a + (int64_t)b * g.a_stride;
   int bad = 0;
   for (int j = threadIdx.x; j < np; j += 256) {
-    float v = 0.f;
+    double v = 0.0;
     if (i < n && j < n) {
-      v = a[j];
-      if (!(fabsf(v) <= 3.0e38f)) bad = 1;
+      const float lo = a[(int64_t)i * n + j], up = a[(int64_t)j * n + i];
+      if (!(fabsf(lo) <= 3.0e38f) || !(fabsf(up) <= 3.0e38f)) bad = 1;
+      v = 0.5 * ((double)lo + (double)up);
     }
     w[j] = v;
     qt[j] = (i == j) ? 1.f : 0.f;
   }
   if (bad) g.failed[b] = 1;
   if (i < n && threadIdx.x == 0) {
-    const float d = fabsf(a[i]);
+    const float d = fabsf(a[(int64_t)i * n + i]);
     if (d <= 3.0e38f) atomicMax(reinterpret_cast<int *>(g.dmax + b), __float_as_int(d));  // d >= 0: int order = float order
   }
   if (i == 0 && threadIdx.x < JAC_OUTER_SWEEPS) g.rot[b * JAC_OUTER_SWEEPS + threadIdx.x] = 0;
@@ -302,7 +320,7 @@ constexpr int PIV_LD = JAC_PIV + 1;
 
 // One workgroup per (pair, matrix): diagonalise the 64 x 64 pivot.
 __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const BlockJacArgs g) {
-  __shared__ float As[JAC_PIV * PIV_LD];
+  __shared__ double At[JAC_PIV * (JAC_PIV + 1) / 2];
   __shared__ float Js[JAC_PIV * PIV_LD];
   __shared__ JacScratch sc;
   const int b = blockIdx.y, pair = blockIdx.x;
@@ -311,26 +329,18 @@ __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const Block
   const int np = g.np, nblk = np / JAC_NB;
   int pb, qb;
   rr_pair(nblk, g.round, pair, pb, qb);
-  const float *w = g.w + (int64_t)b * np * np;
+  const double *w = g.w + (int64_t)b * np * np;
   const int tid = threadIdx.x;
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
     const int j = tid & 63;
     const int gi = (i < JAC_NB ? pb * JAC_NB + i : qb * JAC_NB + i - JAC_NB);
     const int gj = (j < JAC_NB ? pb * JAC_NB + j : qb * JAC_NB + j - JAC_NB);
-    As[i * PIV_LD + j] = w[(int64_t)gi * np + gj];
+    if (j <= i) At[i * (i + 1) / 2 + j] = w[(int64_t)gi * np + gj];
     Js[i * PIV_LD + j] = (i == j) ? 1.f : 0.f;
   }
   __syncthreads();
-  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
-    const int j = tid & 63;
-    if (j < i) {
-      const float v = 0.5f * (As[i * PIV_LD + j] + As[j * PIV_LD + i]);
-      As[i * PIV_LD + j] = v;
-      As[j * PIV_LD + i] = v;
-    }
-  }
-  __syncthreads();
-  const int any = jacobi_sweeps(As, Js, JAC_PIV, PIV_LD, JAC_INNER_SWEEPS, JAC_TOL_ABS * g.dmax[b], &sc);
+  const double dm = (double)g.dmax[b];
+  const int any = jacobi_sweeps(At, Js, JAC_PIV, PIV_LD, JAC_INNER_SWEEPS, JAC_SMALL_TOL_REL, JAC_SMALL_TOL_ABS * dm, &sc);
   __syncthreads();
   if (tid == 0) {
     g.ident[b * (nblk / 2) + pair] = any ? 0 : 1;
@@ -343,7 +353,115 @@ __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const Block
 
 constexpr int APP_LD = JAC_PIV + 4;
 
-// 64 x 64 x 64 product on one workgroup: wavefront (wi, wj) computes the 32 x 32
+// Loads rotation block `idx` of this matrix into LDS (identity if that pivot did not rotate).
+__device__ __forceinline__ void load_rotation(float *dst, const float *jb, int idx, bool ident, int tid) {
+  const int c = tid & 63;
+  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64)
+    dst[i * APP_LD + c] = ident ? (i == c ? 1.f : 0.f) : jb[((int64_t)idx * JAC_PIV + i) * JAC_PIV + c];
+}
+
+// W_kl <- J_k^T W_kl J_l for the pair-blocks l <= k of one matrix, in float64 on the
+// matrix cores; the transposed result is written to W_lk.  grid (hp (hp + 1) / 2, batch).
+// Wavefront (wi, wj) owns the 32 x 32 quadrant as 2 x 2 tiles of 16 x 16; a 16x16x4
+// MFMA takes A(i, k) from lane (i = lane % 16, k = lane / 16), B(k, j) likewise, and
+// leaves D(4 (lane / 16) + v, lane % 16) in element v of the lane's result.
+__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const BlockJacArgs g) {
+  __shared__ __align__(16) float Jk[JAC_PIV * APP_LD];
+  __shared__ __align__(16) float Jl[JAC_PIV * APP_LD];
+  __shared__ __align__(32) double X[JAC_PIV * APP_LD];   // W_kl, then (J_k^T W_kl)^T
+  const int b = blockIdx.y;
+  if (g.failed[b]) return;
+  if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;
+  const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wi = wave >> 1, wj = wave & 1;
+  const int32_t *ident = g.ident + b * hp;
+  const float *jb = g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV;
+  // lower-triangular pair-block index: blockIdx.x = k (k + 1) / 2 + l, l <= k
+  int k = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
+  while ((k + 1) * (k + 2) / 2 <= (int)blockIdx.x) ++k;
+  while (k * (k + 1) / 2 > (int)blockIdx.x) --k;
+  const int l = blockIdx.x - k * (k + 1) / 2;
+  if (ident[k] && ident[l]) return;
+  double *w = g.w + (int64_t)b * np * np;
+  int pk, qk, pl, ql;
+  rr_pair(nblk, g.round, k, pk, qk);
+  rr_pair(nblk, g.round, l, pl, ql);
+
+  const int c = tid & 63;
+  const int gcol = (c < JAC_NB ? pl * JAC_NB + c : ql * JAC_NB + c - JAC_NB);
+  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
+    const int grow = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
+    X[i * APP_LD + c] = w[(int64_t)grow * np + gcol];
+  }
+  load_rotation(Jk, jb, k, ident[k] != 0, tid);
+  load_rotation(Jl, jb, l, ident[l] != 0, tid);
+  __syncthreads();
+
+  const int li = lane & 15, lk = lane >> 4;
+  doublex4 acc[2][2];
+  // T = J_k^T X :  A(i, kk) = Jk[kk][i], B(kk, j) = X[kk][j]
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll 4
+  for (int kk = 0; kk < JAC_PIV; kk += 4) {
+    const int row = (kk + lk) * APP_LD;
+    const double a0 = (double)Jk[row + wi * 32 + li], a1 = (double)Jk[row + wi * 32 + 16 + li];
+    const double b0 = X[row + wj * 32 + li], b1 = X[row + wj * 32 + 16 + li];
+    acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+  }
+  __syncthreads();   // all reads of X done
+  // X <- T^T : lane holds T(i0 .. i0+3, j)
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const int i0 = wi * 32 + a * 16 + 4 * lk, j = wj * 32 + e * 16 + li;
+      *reinterpret_cast<doublex4 *>(&X[j * APP_LD + i0]) = acc[a][e];
+    }
+  __syncthreads();
+  // C = T J_l :  A(i, kk) = X[kk][i] (= T[i][kk]), B(kk, j) = Jl[kk][j]
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll 4
+  for (int kk = 0; kk < JAC_PIV; kk += 4) {
+    const int row = (kk + lk) * APP_LD;
+    const double a0 = X[row + wi * 32 + li], a1 = X[row + wi * 32 + 16 + li];
+    const double b0 = (double)Jl[row + wj * 32 + li], b1 = (double)Jl[row + wj * 32 + 16 + li];
+    acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+    acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+    acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+    acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+  }
+  // write C to block (k, l) and C^T to block (l, k); on the diagonal (k == l) only the
+  // lower half is kept and mirrored, so W stays exactly symmetric
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const int j = wj * 32 + e * 16 + li;
+      const int gc = (j < JAC_NB ? pl * JAC_NB + j : ql * JAC_NB + j - JAC_NB);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int i = wi * 32 + a * 16 + 4 * lk + v;
+        const int gr = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
+        if (k != l || j <= i) {
+          const double val = (k == l && i == j) ? acc[a][e][v] : acc[a][e][v];
+          w[(int64_t)gr * np + gc] = val;
+          if (gr != gc) w[(int64_t)gc * np + gr] = val;
+        }
+      }
+    }
+}
+
+// 64 x 64 x 64 float32 product on one workgroup: wavefront (wi, wj) computes the 32 x 32
 // tile  C[i][j] = sum_k At[k][i] * B[k][j]  from LDS (both operands k-major).
 __device__ __forceinline__ floatx16 mfma_64(const float *At, const float *B, int wi, int wj, int lane) {
   floatx16 acc;
@@ -356,79 +474,43 @@ __device__ __forceinline__ floatx16 mfma_64(const float *At, const float *B, int
   return acc;
 }
 
-// Applies the round's rotations.  blockIdx.x < hp*hp: A_kl <- J_k^T A_kl J_l for
-// the pair-block (k, l); otherwise Qt rows of pair k, one 64-column tile.
-__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_kernel(const BlockJacArgs g) {
+// Qt rows of pair k <- J_k^T (those rows), one 64-column tile per workgroup, float32 MFMA.
+// grid (hp * np / 64, batch).
+__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const BlockJacArgs g) {
   __shared__ __align__(16) float Jk[JAC_PIV * APP_LD];
-  __shared__ __align__(16) float Jl[JAC_PIV * APP_LD];
   __shared__ __align__(16) float X[JAC_PIV * APP_LD];
-  __shared__ __align__(16) float Tt[JAC_PIV * APP_LD];
   const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;
-  const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
+  const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2, ctiles = np / JAC_PIV;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wi = wave >> 1, wj = wave & 1;
-  const int32_t *ident = g.ident + b * hp;
-  const float *jb = g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV;
-
-  const bool two_sided = (int)blockIdx.x < hp * hp;
-  int k, l = 0, ctile = 0;
-  float *mat;
-  if (two_sided) {
-    k = blockIdx.x / hp; l = blockIdx.x - k * hp;
-    if (ident[k] && ident[l]) return;
-    mat = g.w + (int64_t)b * np * np;
-  } else {
-    const int rest = blockIdx.x - hp * hp;
-    const int ctiles = np / JAC_PIV;
-    k = rest / ctiles; ctile = rest - k * ctiles;
-    if (ident[k]) return;
-    mat = g.qt + (int64_t)b * np * np;
-  }
-  int pk, qk, pl = 0, ql = 0;
+  const int k = blockIdx.x / ctiles, ctile = blockIdx.x - k * ctiles;
+  if (g.ident[b * hp + k]) return;
+  float *qt = g.qt + (int64_t)b * np * np;
+  int pk, qk;
   rr_pair(nblk, g.round, k, pk, qk);
-  if (two_sided) rr_pair(nblk, g.round, l, pl, ql);
-
-  // global row / column of local index (one 64-float row per 64 consecutive threads)
   const int c = tid & 63;
-  const int gcol = two_sided ? (c < JAC_NB ? pl * JAC_NB + c : ql * JAC_NB + c - JAC_NB) : ctile * JAC_PIV + c;
-  const bool idk = ident[k] != 0;
-  const bool idl = two_sided ? (ident[l] != 0) : true;
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
     const int grow = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
-    X[i * APP_LD + c] = mat[(int64_t)grow * np + gcol];
-    Jk[i * APP_LD + c] = idk ? (i == c ? 1.f : 0.f) : jb[((int64_t)k * JAC_PIV + i) * JAC_PIV + c];
-    if (two_sided) Jl[i * APP_LD + c] = idl ? (i == c ? 1.f : 0.f) : jb[((int64_t)l * JAC_PIV + i) * JAC_PIV + c];
+    X[i * APP_LD + c] = qt[(int64_t)grow * np + ctile * JAC_PIV + c];
   }
+  load_rotation(Jk, g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV, k, false, tid);
   __syncthreads();
-  // T = J_k^T X
-  floatx16 acc = mfma_64(Jk, X, wi, wj, lane);
-  const int j = wj * 32 + (lane & 31);
-  if (two_sided) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int i0 = wi * 32 + 8 * q + 4 * (lane >> 5);
-      *reinterpret_cast<float4 *>(&Tt[j * APP_LD + i0]) =
-          make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-    }
-    __syncthreads();
-    // C = T J_l   (A-operand (i, k) = Tt[k][i])
-    acc = mfma_64(Tt, Jl, wi, wj, lane);
-  }
-  const int gc = two_sided ? (j < JAC_NB ? pl * JAC_NB + j : ql * JAC_NB + j - JAC_NB) : ctile * JAC_PIV + j;
+  const floatx16 acc = mfma_64(Jk, X, wi, wj, lane);
+  const int gc = ctile * JAC_PIV + wj * 32 + (lane & 31);
 #pragma unroll
   for (int q = 0; q < 4; ++q)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int i = wi * 32 + 8 * q + 4 * (lane >> 5) + e;
       const int grow = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
-      mat[(int64_t)grow * np + gc] = acc[4 * q + e];
+      qt[(int64_t)grow * np + gc] = acc[4 * q + e];
     }
 }
 
 struct BlockFinalArgs {
-  const float *w; int32_t np; int32_t n;
+  const double *w; int32_t np; int32_t n;
   float epsilon, r;
   float *fvals;          // [batch][np]: lambda'^-r (0 on padding)
   float *lambda;         // optional [batch][n]
@@ -439,31 +521,30 @@ struct BlockFinalArgs {
 
 // One workgroup per matrix: eigenvalues = diag(W); shift; f(lambda).
 __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArgs g) {
-  __shared__ float redf[4];
+  __shared__ double redf[4];
   __shared__ int redi[4];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int np = g.np, n = g.n;
-  const float *w = g.w + (int64_t)b * np * np;
+  const double *w = g.w + (int64_t)b * np * np;
   float *fv = g.fvals + (int64_t)b * np;
-  int bad = g.failed[b];
-  float lmin = 3.0e38f;
+  const int bad = g.failed[b];
+  double lmin = 1.0e300;
   if (!bad)
-    for (int i = tid; i < n; i += 256) lmin = fminf(lmin, w[(int64_t)i * np + i]);
+    for (int i = tid; i < n; i += 256) lmin = fmin(lmin, w[(int64_t)i * np + i]);
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) lmin = fminf(lmin, __shfl_xor(lmin, off, 64));
+  for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   if (lane == 0) redf[wave] = lmin;
   __syncthreads();
-  lmin = fminf(fminf(redf[0], redf[1]), fminf(redf[2], redf[3]));
-  const float shift = fminf(lmin, 0.f);
+  lmin = fmin(fmin(redf[0], redf[1]), fmin(redf[2], redf[3]));
+  const double shift = fmin(lmin, 0.0);
   int badf = bad;
   for (int i = tid; i < np; i += 256) {
     float f = 0.f;
     if (i < n && !bad) {
-      const float lam = w[(int64_t)i * np + i];
-      const double ln = (double)(lam - shift) + (double)g.epsilon;
-      f = (float)pow(ln, -(double)g.r);
+      const double lam = w[(int64_t)i * np + i];
+      f = (float)pow(lam - shift + (double)g.epsilon, -(double)g.r);
       if (!(f <= 3.0e38f) || !(f >= 0.f)) badf = 1;
-      if (g.lambda) g.lambda[(int64_t)b * n + i] = lam;
+      if (g.lambda) g.lambda[(int64_t)b * n + i] = (float)lam;
     }
     fv[i] = f;
   }

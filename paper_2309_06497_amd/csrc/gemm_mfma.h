@@ -60,6 +60,7 @@ struct GemmArgs {
   int32_t ldc;
   int32_t M, N, K;
   float alpha, beta;
+  double alpha_d, beta_d;       // used instead of alpha, beta by the ACC64 kernels
   const BlockDesc *desc;
   const void *const *ptr_table;
   const float *kscale;          // per-k multiplier of A (length K per batch entry), or nullptr
@@ -197,7 +198,13 @@ __device__ __forceinline__ const T *operand_ptr(const Operand &o, const BlockDes
   return reinterpret_cast<const T *>(o.base) + (int64_t)b * o.batch_stride;
 }
 
-template <int AO, int BO, typename TA, typename TB, int EPI, bool KSCALE>
+// ACC64: after every k-slab of 16 the float32 MFMA accumulators are added into
+// float64 registers and cleared, and the epilogue (alpha * acc + beta * C) is
+// evaluated in float64 before the single rounding to float32.  Used for the
+// factor updates: the first root refresh sees L = G G^T of a single gradient,
+// whose condition number is the square of G's, and a plain float32 running sum
+// over k would perturb its small eigenvalues by more than the parity budget.
+template <int AO, int BO, typename TA, typename TB, int EPI, bool KSCALE, bool ACC64 = false>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmArgs g) {
   __shared__ __align__(16) float As[2][BK][BM + LDS_PAD];
   __shared__ __align__(16) float Bs[2][BK][BN + LDS_PAD];
@@ -244,6 +251,16 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmAr
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  double acc64[ACC64 ? 2 : 1][ACC64 ? 2 : 1][ACC64 ? 16 : 1];
+  if (ACC64) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc64[ACC64 ? i : 0][ACC64 ? j : 0][ACC64 ? v : 0] = 0.0;
+  }
+
   const int nk = (g.K + BK - 1) / BK;
   la.fetch(0, tid);
   lb.fetch(0, tid);
@@ -271,6 +288,17 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmAr
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    if (ACC64) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            acc64[ACC64 ? i : 0][ACC64 ? j : 0][ACC64 ? v : 0] += (double)acc[i][j][v];
+            acc[i][j][v] = 0.f;
+          }
     }
     if (kt + 1 < nk) {
       if (KSCALE) la.scale(ks, (kt + 1) * BK, tid);
@@ -302,7 +330,11 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmAr
               // only the lower triangle is computed; its mirror image is written with the
               // same bits so the factor stays exactly symmetric
               if (j <= i) {
-                if (g.beta != 0.f) v += g.beta * c[(int64_t)i * ldc + j];
+                if (ACC64) {
+                  double vd = g.alpha_d * acc64[ACC64 ? mi : 0][ACC64 ? ni : 0][ACC64 ? 4 * q + e : 0];
+                  if (g.beta_d != 0.0) vd += g.beta_d * (double)c[(int64_t)i * ldc + j];
+                  v = (float)vd;
+                } else if (g.beta != 0.f) v += g.beta * c[(int64_t)i * ldc + j];
                 c[(int64_t)i * ldc + j] = v;
                 if (j < i) c[(int64_t)j * ldc + i] = v;
               }

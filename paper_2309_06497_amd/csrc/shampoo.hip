@@ -22,7 +22,7 @@ namespace {
 
 constexpr int64_t MAX_BLOCK_SIZE = 8192;
 constexpr size_t ALIGN = 256;
-constexpr size_t EIG_CHUNK_BYTES = (size_t)2 << 30;   // W + Qt of one chunk of the block solver
+constexpr size_t EIG_CHUNK_BYTES = (size_t)3 << 30;   // W + Qt of one chunk of the block solver
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -170,9 +170,10 @@ EigLayout eig_layout(int n, int batch) {
   }
   e.np = (n + JAC_PIV - 1) / JAC_PIV * JAC_PIV;
   const size_t mat = (size_t)e.np * e.np * sizeof(float);
-  e.chunk = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)batch, 32768), EIG_CHUNK_BYTES / (2 * mat)));
+  // W is float64, Qt float32: 3 float-sized matrices per solve
+  e.chunk = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)batch, 32768), EIG_CHUNK_BYTES / (3 * mat)));
   size_t off = 0;
-  e.off_w = off; off += align_up(mat * e.chunk);
+  e.off_w = off; off += align_up(2 * mat * e.chunk);
   e.off_qt = off; off += align_up(mat * e.chunk);
   const int hp = e.np / JAC_PIV;
   e.off_j = off; off += align_up((size_t)e.chunk * hp * JAC_PIV * JAC_PIV * sizeof(float));
@@ -185,13 +186,13 @@ EigLayout eig_layout(int n, int batch) {
   return e;
 }
 
-template <int AO, int BO, typename TA, typename TB, int EPI, bool KS>
+template <int AO, int BO, typename TA, typename TB, int EPI, bool KS, bool ACC64 = false>
 int launch_gemm(GemmArgs &g, hipStream_t s) {
   const int64_t total = (int64_t)g.tiles * g.batch;
   if (total <= 0) return SHAMPOO_OK;
   if (total > (int64_t)1 << 30) return SHAMPOO_ERR_UNSUPPORTED;
   const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
-  hipLaunchKernelGGL((gemm_mfma_kernel<AO, BO, TA, TB, EPI, KS>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, g);
+  hipLaunchKernelGGL((gemm_mfma_kernel<AO, BO, TA, TB, EPI, KS, ACC64>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, g);
   HIP_TRY(hipGetLastError());
   return SHAMPOO_OK;
 }
@@ -222,7 +223,7 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
     return SHAMPOO_OK;
   }
   const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
-  float *w = reinterpret_cast<float *>(ws + e.off_w);
+  double *w = reinterpret_cast<double *>(ws + e.off_w);
   float *qt = reinterpret_cast<float *>(ws + e.off_qt);
   float *jbuf = reinterpret_cast<float *>(ws + e.off_j);
   int32_t *ident = reinterpret_cast<int32_t *>(ws + e.off_ident);
@@ -249,7 +250,8 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
       for (int rd = 0; rd < nblk - 1; ++rd) {
         ja.round = rd; ja.sweep = sw;
         hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cb), dim3(JAC_THREADS), 0, s, ja);
-        hipLaunchKernelGGL(blockjac_apply_kernel, dim3(hp * hp + hp * (np / JAC_PIV), cb), dim3(JAC_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(hp * (hp + 1) / 2, cb), dim3(JAC_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * (np / JAC_PIV), cb), dim3(JAC_THREADS), 0, s, ja);
       }
     HIP_TRY(hipGetLastError());
     BlockFinalArgs fa;
@@ -363,8 +365,9 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   unsigned long long *fail_count = reinterpret_cast<unsigned long long *>(ws + o->off_count);
   const bool use_shampoo = step >= c.start_preconditioning_step;
   const bool refresh = use_shampoo && (step % c.precondition_frequency == 0);
-  const float alpha = c.beta2 < 1.f ? 1.f - c.beta2 : 1.f;
-  const float beta = c.beta2 < 1.f ? c.beta2 : 1.f;
+  // EMA weights from the float32 beta2 the caller gave, evaluated in float64
+  const double alpha = c.beta2 < 1.f ? 1.0 - (double)c.beta2 : 1.0;
+  const double beta = c.beta2 < 1.f ? (double)c.beta2 : 1.0;
   int rc;
 
   for (auto &b : p.buckets) {
@@ -374,18 +377,18 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       GemmArgs g{};
       g.a.from_table = 1; g.b.from_table = 1;
       g.desc = desc; g.ptr_table = gtab;
-      g.alpha = alpha; g.beta = beta; g.batch = b.count;
+      g.alpha = (float)alpha; g.beta = (float)beta; g.alpha_d = alpha; g.beta_d = beta; g.batch = b.count;
       // L <- beta L + alpha G G^T
       g.c = reinterpret_cast<float *>(ws + b.off_L); g.c_batch_stride = (int64_t)b.m * b.m; g.ldc = b.m;
       g.M = b.m; g.N = b.m; g.K = b.n;
       g.tiles_m = g.tiles_n = b.tiles_m; g.tiles = b.tiles_m * (b.tiles_m + 1) / 2;
-      rc = launch_gemm<K_CONTIG, K_CONTIG, GT, GT, EPI_SYRK, false>(g, s);
+      rc = launch_gemm<K_CONTIG, K_CONTIG, GT, GT, EPI_SYRK, false, true>(g, s);
       if (rc) return rc;
       // R <- beta R + alpha G^T G
       g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.n * b.n; g.ldc = b.n;
       g.M = b.n; g.N = b.n; g.K = b.m;
       g.tiles_m = g.tiles_n = b.tiles_n; g.tiles = b.tiles_n * (b.tiles_n + 1) / 2;
-      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GT, GT, EPI_SYRK, false>(g, s);
+      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GT, GT, EPI_SYRK, false, true>(g, s);
       if (rc) return rc;
     }
     {
