@@ -69,11 +69,16 @@ __device__ __forceinline__ int tri(int i, int j) {
 // G G^T at the first refresh) as accurate as the stored factor allows; the
 // rotations themselves only need float32.  Because A is symmetric only the
 // 2 x 2 blocks (rows of pair k, columns of pair l) with l <= k are updated.
+// SQUARE: At is instead a full square array with row stride LDA (odd): every
+// LDS access of a round is then bank-conflict free, at twice the footprint; the
+// mirror image of each updated block is written as well.
 // Returns nonzero if any rotation was applied.  All threads must call it.
-__device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, int max_sweeps, double tol_rel,
-                             double tol_abs, JacScratch *sc) {
+template <bool SQUARE>
+__device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const int LDA, int max_sweeps,
+                             double tol_rel, double tol_abs, JacScratch *sc) {
   const int tid = threadIdx.x;
   const int half = s >> 1;
+  auto at = [LDA](int i, int j) { return SQUARE ? i * LDA + j : tri(i, j); };
   int any = 0;
   for (int sw = 0; sw < max_sweeps; ++sw) {
     if (tid == 0) sc->flag = 0;
@@ -82,53 +87,90 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, int max
       if (tid < half) {
         int p, q;
         rr_pair(s, r, tid, p, q);   // p < q
-        const double app = At[tri(p, p)], aqq = At[tri(q, q)], apq = At[tri(q, p)];
+        const double app = At[at(p, p)], aqq = At[at(q, q)], apq = At[at(q, p)];
         double sn = 0.0, tp = 0.0;
         const double aa = fabs(apq);
         if (aa > tol_abs && aa > tol_rel * sqrt(fabs(app * aqq))) {
-          const double tau = (aqq - app) / (2.0 * apq);
-          const double t = copysign(1.0, tau) / (fabs(tau) + sqrt(1.0 + tau * tau));
-          const double c = 1.0 / sqrt(1.0 + t * t);
-          sn = t * c;
-          tp = sn / (1.0 + c);
+          // t = tan of the rotation angle, the smaller root of t^2 + 2 zeta t - 1 = 0 with
+          // zeta = (a_qq - a_pp) / (2 a_pq), written so that it costs one division
+          const double d = aqq - app, h = 2.0 * apq;
+          const double t = h / (d + copysign(sqrt(d * d + h * h), d));
+          const double w = sqrt(1.0 + t * t);   // 1 / cos
+          sn = t / w;
+          tp = t / (1.0 + w);                   // sin / (1 + cos)
+          if (!(fabs(sn) <= 1.0)) { sn = 0.0; tp = 0.0; }   // non-finite: leave the pair alone
           if (sn != 0.0) sc->flag = 1;
         }
         sc->s[tid] = sn; sc->t[tid] = tp; sc->p[tid] = p; sc->q[tid] = q;
       }
       __syncthreads();
-      // A <- R^T A R on the blocks with l <= k
-      for (int k = tid >> 5; k < half; k += JAC_THREADS / 32) {
-        const int pk = sc->p[k], qk = sc->q[k];
-        const double sk = sc->s[k], tk = sc->t[k];
-        for (int l = tid & 31; l <= k; l += 32) {
-          const int pl = sc->p[l], ql = sc->q[l];
-          const double sl = sc->s[l], tl = sc->t[l];
-          if (sk == 0.0 && sl == 0.0) continue;
-          const int ia = tri(pk, pl), ib = tri(pk, ql), ic = tri(qk, pl), id = tri(qk, ql);
-          double a = At[ia], b = At[ib], c = At[ic], d = At[id];
-          // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
-          const double a1 = a - sk * (c + tk * a), c1 = c + sk * (a - tk * c);
-          const double b1 = b - sk * (d + tk * b), d1 = d + sk * (b - tk * d);
-          // columns: (a1, b1) and (c1, d1) are (x, y) pairs of rotation l
-          a = a1 - sl * (b1 + tl * a1); b = b1 + sl * (a1 - tl * b1);
-          c = c1 - sl * (d1 + tl * c1); d = d1 + sl * (c1 - tl * d1);
-          if (k == l) {   // pivot block: ib == ic is the annihilated element
-            At[ia] = a; At[ib] = 0.0; At[id] = d;
-          } else {
-            At[ia] = a; At[ib] = b; At[ic] = c; At[id] = d;
+      // A <- R^T A R on the blocks with l <= k.  Blocks are independent, so a thread first
+      // loads all of its blocks of a pass, then rotates, then stores (the loads overlap).
+      constexpr int U = 4;
+      for (int l = tid & 31; l < half; l += 32) {
+        const int pl = sc->p[l], ql = sc->q[l];
+        const double sl = sc->s[l], tl = sc->t[l];
+        for (int k0 = tid >> 5; k0 < half; k0 += (JAC_THREADS / 32) * U) {
+          double a[U], b[U], c[U], d[U], sk[U], tk[U];
+          int ia[U], ib[U], ic[U], id[U], pk[U], qk[U];
+          bool act[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int k = k0 + (JAC_THREADS / 32) * u;
+            act[u] = k < half && l <= k;
+            if (act[u]) {
+              pk[u] = sc->p[k]; qk[u] = sc->q[k]; sk[u] = sc->s[k]; tk[u] = sc->t[k];
+              act[u] = !(sk[u] == 0.0 && sl == 0.0);
+            }
+            if (act[u]) {
+              ia[u] = at(pk[u], pl); ib[u] = at(pk[u], ql); ic[u] = at(qk[u], pl); id[u] = at(qk[u], ql);
+              a[u] = At[ia[u]]; b[u] = At[ib[u]]; c[u] = At[ic[u]]; d[u] = At[id[u]];
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            if (!act[u]) continue;
+            const int k = k0 + (JAC_THREADS / 32) * u;
+            // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
+            const double a1 = a[u] - sk[u] * (c[u] + tk[u] * a[u]), c1 = c[u] + sk[u] * (a[u] - tk[u] * c[u]);
+            const double b1 = b[u] - sk[u] * (d[u] + tk[u] * b[u]), d1 = d[u] + sk[u] * (b[u] - tk[u] * d[u]);
+            // columns: (a1, b1) and (c1, d1) are (x, y) pairs of rotation l
+            const double a2 = a1 - sl * (b1 + tl * a1), b2 = b1 + sl * (a1 - tl * b1);
+            const double c2 = c1 - sl * (d1 + tl * c1), d2 = d1 + sl * (c1 - tl * d1);
+            if (k == l) {   // pivot block: (p, q) and (q, p) are the annihilated element
+              At[ia[u]] = a2; At[ib[u]] = 0.0; At[id[u]] = d2;
+              if (SQUARE) At[ic[u]] = 0.0;
+            } else {
+              At[ia[u]] = a2; At[ib[u]] = b2; At[ic[u]] = c2; At[id[u]] = d2;
+              if (SQUARE) {
+                At[at(pl, pk[u])] = a2; At[at(ql, pk[u])] = b2; At[at(pl, qk[u])] = c2; At[at(ql, qk[u])] = d2;
+              }
+            }
           }
         }
       }
-      // J <- J R (columns)
-      for (int i = tid >> 5; i < s; i += JAC_THREADS / 32) {
-        for (int l = tid & 31; l < half; l += 32) {
-          const float sl = (float)sc->s[l];
-          if (sl == 0.f) continue;
-          const float tl = (float)sc->t[l];
-          const int pl = sc->p[l], ql = sc->q[l];
-          const float x = Js[i * LD + pl], y = Js[i * LD + ql];
-          Js[i * LD + pl] = x - sl * (y + tl * x);
-          Js[i * LD + ql] = y + sl * (x - tl * y);
+      // J <- J R (columns), same load / rotate / store batching over rows
+      constexpr int V = 8;
+      for (int l = tid & 31; l < half; l += 32) {
+        const float sl = (float)sc->s[l];
+        if (sl == 0.f) continue;
+        const float tl = (float)sc->t[l];
+        const int pl = sc->p[l], ql = sc->q[l];
+        for (int i0 = tid >> 5; i0 < s; i0 += (JAC_THREADS / 32) * V) {
+          float x[V], y[V];
+#pragma unroll
+          for (int u = 0; u < V; ++u) {
+            const int i = i0 + (JAC_THREADS / 32) * u;
+            if (i < s) { x[u] = Js[i * LD + pl]; y[u] = Js[i * LD + ql]; }
+          }
+#pragma unroll
+          for (int u = 0; u < V; ++u) {
+            const int i = i0 + (JAC_THREADS / 32) * u;
+            if (i < s) {
+              Js[i * LD + pl] = x[u] - sl * (y[u] + tl * x[u]);
+              Js[i * LD + ql] = y[u] + sl * (x[u] - tl * y[u]);
+            }
+          }
         }
       }
       __syncthreads();
@@ -206,7 +248,7 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
     return;
   }
 
-  jacobi_sweeps(At, Js, s, LD, JAC_SMALL_SWEEPS, JAC_SMALL_TOL_REL, JAC_SMALL_TOL_ABS * (double)dmax, sc);
+  jacobi_sweeps<false>(At, Js, s, LD, 0, JAC_SMALL_SWEEPS, JAC_SMALL_TOL_REL, JAC_SMALL_TOL_ABS * (double)dmax, sc);
   __syncthreads();
 
   // lambda_min over the true eigenvalues, then f = (lambda - min(lambda_min, 0) + eps)^-r
@@ -283,6 +325,8 @@ struct BlockJacArgs {
   const int32_t *failed; // [batch]
   int32_t np;            // padded size
   int32_t round, sweep;
+  int32_t inner_sweeps;  // Jacobi sweeps per pivot
+  double tol_rel;        // rotation threshold relative to sqrt(|a_pp a_qq|)
 };
 
 struct BlockInitArgs {
@@ -318,9 +362,14 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
 
 constexpr int PIV_LD = JAC_PIV + 1;
 
+// Only the lower triangle of W is kept up to date, as 32 x 32 sub-blocks (a, b)
+// with a >= b (the strictly-lower ones full, the diagonal ones symmetric): every
+// sub-block is then read and written by exactly one workgroup per round, along
+// its rows.  A sub-block needed "the other way round" is read transposed.
+
 // One workgroup per (pair, matrix): diagonalise the 64 x 64 pivot.
 __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const BlockJacArgs g) {
-  __shared__ double At[JAC_PIV * (JAC_PIV + 1) / 2];
+  __shared__ double At[JAC_PIV * PIV_LD];
   __shared__ float Js[JAC_PIV * PIV_LD];
   __shared__ JacScratch sc;
   const int b = blockIdx.y, pair = blockIdx.x;
@@ -328,19 +377,22 @@ __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const Block
   if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;   // converged
   const int np = g.np, nblk = np / JAC_NB;
   int pb, qb;
-  rr_pair(nblk, g.round, pair, pb, qb);
+  rr_pair(nblk, g.round, pair, pb, qb);   // pb < qb
   const double *w = g.w + (int64_t)b * np * np;
   const int tid = threadIdx.x;
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
     const int j = tid & 63;
     const int gi = (i < JAC_NB ? pb * JAC_NB + i : qb * JAC_NB + i - JAC_NB);
     const int gj = (j < JAC_NB ? pb * JAC_NB + j : qb * JAC_NB + j - JAC_NB);
-    if (j <= i) At[i * (i + 1) / 2 + j] = w[(int64_t)gi * np + gj];
+    // lower triangle of W (gi >= gj when j <= i, because pb < qb), mirrored into LDS
+    const double v = (j <= i) ? w[(int64_t)gi * np + gj] : w[(int64_t)gj * np + gi];
+    At[i * PIV_LD + j] = v;
     Js[i * PIV_LD + j] = (i == j) ? 1.f : 0.f;
   }
   __syncthreads();
   const double dm = (double)g.dmax[b];
-  const int any = jacobi_sweeps(At, Js, JAC_PIV, PIV_LD, JAC_INNER_SWEEPS, JAC_SMALL_TOL_REL, JAC_SMALL_TOL_ABS * dm, &sc);
+  const int any = jacobi_sweeps<true>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, g.tol_rel,
+                                      JAC_SMALL_TOL_ABS * dm, &sc);
   __syncthreads();
   if (tid == 0) {
     g.ident[b * (nblk / 2) + pair] = any ? 0 : 1;
@@ -355,20 +407,59 @@ constexpr int APP_LD = JAC_PIV + 4;
 
 // Loads rotation block `idx` of this matrix into LDS (identity if that pivot did not rotate).
 __device__ __forceinline__ void load_rotation(float *dst, const float *jb, int idx, bool ident, int tid) {
-  const int c = tid & 63;
-  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64)
-    dst[i * APP_LD + c] = ident ? (i == c ? 1.f : 0.f) : jb[((int64_t)idx * JAC_PIV + i) * JAC_PIV + c];
+  const int r = tid >> 4, c4 = (tid & 15) * 4;
+#pragma unroll
+  for (int h = 0; h < 4; ++h) {
+    const int i = r + 16 * h;
+    float4 v;
+    if (ident) v = make_float4(i == c4 ? 1.f : 0.f, i == c4 + 1 ? 1.f : 0.f, i == c4 + 2 ? 1.f : 0.f, i == c4 + 3 ? 1.f : 0.f);
+    else v = *reinterpret_cast<const float4 *>(jb + ((int64_t)idx * JAC_PIV + i) * JAC_PIV + c4);
+    *reinterpret_cast<float4 *>(dst + i * APP_LD + c4) = v;
+  }
+}
+
+// Copies one 32 x 32 sub-block between W and the LDS tile X (64 x 64, stride APP_LD).
+// (ra, cb): block row / column of the quadrant as the product sees it; (xi, xj): its
+// origin inside X.  The sub-block lives in W at (max, min); when ra < cb it is accessed
+// transposed.  TO_LDS: W -> X, else X -> W.  Rows of W are always walked contiguously.
+template <bool TO_LDS>
+__device__ __forceinline__ void copy_subblock(double *w, int np, double *X, int ra, int cb, int xi, int xj, int tid) {
+  const bool tr = ra < cb;
+  const int gr0 = (tr ? cb : ra) * JAC_NB, gc0 = (tr ? ra : cb) * JAC_NB;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int idx = tid + JAC_THREADS * e;
+    const int ii = idx >> 5, jj = idx & 31;          // position inside the stored sub-block
+    double *gp = w + (int64_t)(gr0 + ii) * np + gc0 + jj;
+    double *lp = tr ? &X[(xi + jj) * APP_LD + xj + ii] : &X[(xi + ii) * APP_LD + xj + jj];
+    if (TO_LDS) *lp = *gp; else *gp = *lp;
+  }
+}
+
+// The MFMA operand registers of a rotation block for one wavefront quadrant: element
+// [2 * (kk / 4) + h] = J[kk + lane / 16][off + 16 h + lane % 16], read straight from global
+// memory (the 16 KB block is shared by every pair-block of its row and column, so it
+// stays in L2); the identity if that pivot did not rotate.
+__device__ __forceinline__ void load_rotation_regs(float (&jr)[32], const float *jb, int idx, bool ident, int off,
+                                                   int lane) {
+  const int li = lane & 15, lk = lane >> 4;
+#pragma unroll
+  for (int q = 0; q < 16; ++q)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int row = 4 * q + lk, col = off + 16 * h + li;
+      jr[2 * q + h] = ident ? (row == col ? 1.f : 0.f) : jb[((int64_t)idx * JAC_PIV + row) * JAC_PIV + col];
+    }
 }
 
 // W_kl <- J_k^T W_kl J_l for the pair-blocks l <= k of one matrix, in float64 on the
-// matrix cores; the transposed result is written to W_lk.  grid (hp (hp + 1) / 2, batch).
-// Wavefront (wi, wj) owns the 32 x 32 quadrant as 2 x 2 tiles of 16 x 16; a 16x16x4
-// MFMA takes A(i, k) from lane (i = lane % 16, k = lane / 16), B(k, j) likewise, and
-// leaves D(4 (lane / 16) + v, lane % 16) in element v of the lane's result.
-__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const BlockJacArgs g) {
-  __shared__ __align__(16) float Jk[JAC_PIV * APP_LD];
-  __shared__ __align__(16) float Jl[JAC_PIV * APP_LD];
-  __shared__ __align__(32) double X[JAC_PIV * APP_LD];   // W_kl, then (J_k^T W_kl)^T
+// matrix cores.  grid (hp (hp + 1) / 2, batch).  Wavefront (wi, wj) owns the 32 x 32
+// quadrant as 2 x 2 tiles of 16 x 16; a 16x16x4 MFMA takes A(i, k) from lane
+// (i = lane % 16, k = lane / 16), B(k, j) likewise, and leaves D(4 (lane / 16) + v, lane % 16)
+// in element v of the lane's result.  Only the W tile lives in LDS (35 KB, 3 workgroups
+// per CU); the rotation operands sit in registers.
+__global__ __launch_bounds__(JAC_THREADS, 3) void blockjac_apply_w_kernel(const BlockJacArgs g) {
+  __shared__ __align__(32) double X[JAC_PIV * APP_LD];   // W_kl, then (J_k^T W_kl)^T, then the result
   const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;
@@ -388,14 +479,12 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
   rr_pair(nblk, g.round, k, pk, qk);
   rr_pair(nblk, g.round, l, pl, ql);
 
-  const int c = tid & 63;
-  const int gcol = (c < JAC_NB ? pl * JAC_NB + c : ql * JAC_NB + c - JAC_NB);
-  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
-    const int grow = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
-    X[i * APP_LD + c] = w[(int64_t)grow * np + gcol];
-  }
-  load_rotation(Jk, jb, k, ident[k] != 0, tid);
-  load_rotation(Jl, jb, l, ident[l] != 0, tid);
+  float jr[32];
+  load_rotation_regs(jr, jb, k, ident[k] != 0, wi * 32, lane);
+  copy_subblock<true>(w, np, X, pk, pl, 0, 0, tid);
+  copy_subblock<true>(w, np, X, pk, ql, 0, JAC_NB, tid);
+  copy_subblock<true>(w, np, X, qk, pl, JAC_NB, 0, tid);
+  copy_subblock<true>(w, np, X, qk, ql, JAC_NB, JAC_NB, tid);
   __syncthreads();
 
   const int li = lane & 15, lk = lane >> 4;
@@ -405,16 +494,17 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
-  for (int kk = 0; kk < JAC_PIV; kk += 4) {
-    const int row = (kk + lk) * APP_LD;
-    const double a0 = (double)Jk[row + wi * 32 + li], a1 = (double)Jk[row + wi * 32 + 16 + li];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int row = (4 * q + lk) * APP_LD;
+    const double a0 = (double)jr[2 * q], a1 = (double)jr[2 * q + 1];
     const double b0 = X[row + wj * 32 + li], b1 = X[row + wj * 32 + 16 + li];
     acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
     acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
     acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
     acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
   }
+  load_rotation_regs(jr, jb, l, ident[l] != 0, wj * 32, lane);   // in flight during the LDS exchange
   __syncthreads();   // all reads of X done
   // X <- T^T : lane holds T(i0 .. i0+3, j)
 #pragma unroll
@@ -430,35 +520,36 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
-  for (int kk = 0; kk < JAC_PIV; kk += 4) {
-    const int row = (kk + lk) * APP_LD;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int row = (4 * q + lk) * APP_LD;
     const double a0 = X[row + wi * 32 + li], a1 = X[row + wi * 32 + 16 + li];
-    const double b0 = (double)Jl[row + wj * 32 + li], b1 = (double)Jl[row + wj * 32 + 16 + li];
+    const double b0 = (double)jr[2 * q], b1 = (double)jr[2 * q + 1];
     acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
     acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
     acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
     acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
   }
-  // write C to block (k, l) and C^T to block (l, k); on the diagonal (k == l) only the
-  // lower half is kept and mirrored, so W stays exactly symmetric
+  __syncthreads();   // all reads of X (= T^T) done
+  // X <- C.  On the diagonal pair-block (k == l) only the lower half of C is kept and
+  // mirrored, so that the diagonal sub-blocks stay exactly symmetric.
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       const int j = wj * 32 + e * 16 + li;
-      const int gc = (j < JAC_NB ? pl * JAC_NB + j : ql * JAC_NB + j - JAC_NB);
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int i = wi * 32 + a * 16 + 4 * lk + v;
-        const int gr = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
-        if (k != l || j <= i) {
-          const double val = (k == l && i == j) ? acc[a][e][v] : acc[a][e][v];
-          w[(int64_t)gr * np + gc] = val;
-          if (gr != gc) w[(int64_t)gc * np + gr] = val;
-        }
+        if (k != l) X[i * APP_LD + j] = acc[a][e][v];
+        else if (j <= i) { X[i * APP_LD + j] = acc[a][e][v]; X[j * APP_LD + i] = acc[a][e][v]; }
       }
     }
+  __syncthreads();
+  copy_subblock<false>(w, np, X, pk, pl, 0, 0, tid);
+  copy_subblock<false>(w, np, X, qk, pl, JAC_NB, 0, tid);
+  copy_subblock<false>(w, np, X, qk, ql, JAC_NB, JAC_NB, tid);
+  if (k != l) copy_subblock<false>(w, np, X, pk, ql, 0, JAC_NB, tid);   // (pk, qk) is the mirror of (qk, pk)
 }
 
 // 64 x 64 x 64 float32 product on one workgroup: wavefront (wi, wj) computes the 32 x 32
@@ -474,39 +565,65 @@ __device__ __forceinline__ floatx16 mfma_64(const float *At, const float *B, int
   return acc;
 }
 
-// Qt rows of pair k <- J_k^T (those rows), one 64-column tile per workgroup, float32 MFMA.
-// grid (hp * np / 64, batch).
+constexpr int APPQ_TILES = 4;   // 64-column tiles of Qt handled by one workgroup
+
+// Qt rows of pair k <- J_k^T (those rows), APPQ_TILES 64-column tiles per workgroup,
+// float32 MFMA.  grid (hp * ceil(np / 256), batch).
 __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const BlockJacArgs g) {
   __shared__ __align__(16) float Jk[JAC_PIV * APP_LD];
-  __shared__ __align__(16) float X[JAC_PIV * APP_LD];
+  __shared__ __align__(16) float X[2][JAC_PIV * APP_LD];
   const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2, ctiles = np / JAC_PIV;
+  const int groups = (ctiles + APPQ_TILES - 1) / APPQ_TILES;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wi = wave >> 1, wj = wave & 1;
-  const int k = blockIdx.x / ctiles, ctile = blockIdx.x - k * ctiles;
+  const int k = blockIdx.x / groups, grp = blockIdx.x - k * groups;
   if (g.ident[b * hp + k]) return;
   float *qt = g.qt + (int64_t)b * np * np;
   int pk, qk;
   rr_pair(nblk, g.round, k, pk, qk);
-  const int c = tid & 63;
-  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
-    const int grow = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
-    X[i * APP_LD + c] = qt[(int64_t)grow * np + ctile * JAC_PIV + c];
-  }
+  const int r = tid >> 4, c4 = (tid & 15) * 4;
+  const int t0 = grp * APPQ_TILES, t1 = min(t0 + APPQ_TILES, ctiles);
+  float4 pre0, pre1, pre2, pre3;
+  // thread (r, c4) moves rows r, r+16, r+32, r+48 of the 64-row strip, 4 columns each
+  const float *src0 = qt + (int64_t)(pk * JAC_NB + r) * np + c4;
+  const float *src1 = qt + (int64_t)(pk * JAC_NB + r + 16) * np + c4;
+  const float *src2 = qt + (int64_t)(qk * JAC_NB + r) * np + c4;
+  const float *src3 = qt + (int64_t)(qk * JAC_NB + r + 16) * np + c4;
+#define APPQ_FETCH(ct)                                                        \
+  pre0 = *reinterpret_cast<const float4 *>(src0 + (ct) * JAC_PIV);            \
+  pre1 = *reinterpret_cast<const float4 *>(src1 + (ct) * JAC_PIV);            \
+  pre2 = *reinterpret_cast<const float4 *>(src2 + (ct) * JAC_PIV);            \
+  pre3 = *reinterpret_cast<const float4 *>(src3 + (ct) * JAC_PIV)
+#define APPQ_STASH(dst)                                                       \
+  *reinterpret_cast<float4 *>((dst) + (r) * APP_LD + c4) = pre0;              \
+  *reinterpret_cast<float4 *>((dst) + (r + 16) * APP_LD + c4) = pre1;         \
+  *reinterpret_cast<float4 *>((dst) + (r + 32) * APP_LD + c4) = pre2;         \
+  *reinterpret_cast<float4 *>((dst) + (r + 48) * APP_LD + c4) = pre3
+  APPQ_FETCH(t0);
   load_rotation(Jk, g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV, k, false, tid);
+  APPQ_STASH(X[0]);
   __syncthreads();
-  const floatx16 acc = mfma_64(Jk, X, wi, wj, lane);
-  const int gc = ctile * JAC_PIV + wj * 32 + (lane & 31);
+  for (int t = t0; t < t1; ++t) {
+    const int cur = (t - t0) & 1;
+    if (t + 1 < t1) { APPQ_FETCH(t + 1); }
+    const floatx16 acc = mfma_64(Jk, X[cur], wi, wj, lane);
+    const int gc = t * JAC_PIV + wj * 32 + (lane & 31);
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < 4; ++q)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int i = wi * 32 + 8 * q + 4 * (lane >> 5) + e;
-      const int grow = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
-      qt[(int64_t)grow * np + gc] = acc[4 * q + e];
-    }
+      for (int e = 0; e < 4; ++e) {
+        const int i = wi * 32 + 8 * q + 4 * (lane >> 5) + e;
+        const int grow = (i < JAC_NB ? pk * JAC_NB + i : qk * JAC_NB + i - JAC_NB);
+        qt[(int64_t)grow * np + gc] = acc[4 * q + e];
+      }
+    if (t + 1 < t1) { APPQ_STASH(X[cur ^ 1]); }
+    __syncthreads();
+  }
+#undef APPQ_FETCH
+#undef APPQ_STASH
 }
 
 struct BlockFinalArgs {

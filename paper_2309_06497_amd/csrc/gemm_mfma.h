@@ -198,13 +198,13 @@ __device__ __forceinline__ const T *operand_ptr(const Operand &o, const BlockDes
   return reinterpret_cast<const T *>(o.base) + (int64_t)b * o.batch_stride;
 }
 
-// ACC64: after every k-slab of 16 the float32 MFMA accumulators are added into
-// float64 registers and cleared, and the epilogue (alpha * acc + beta * C) is
+// ACC64 = N > 0: after every N k-slabs of 16 the float32 MFMA accumulators are added
+// into float64 registers and cleared, and the epilogue (alpha * acc + beta * C) is
 // evaluated in float64 before the single rounding to float32.  Used for the
 // factor updates: the first root refresh sees L = G G^T of a single gradient,
 // whose condition number is the square of G's, and a plain float32 running sum
 // over k would perturb its small eigenvalues by more than the parity budget.
-template <int AO, int BO, typename TA, typename TB, int EPI, bool KSCALE, bool ACC64 = false>
+template <int AO, int BO, typename TA, typename TB, int EPI, bool KSCALE, int ACC64 = 0>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmArgs g) {
   __shared__ __align__(16) float As[2][BK][BM + LDS_PAD];
   __shared__ __align__(16) float Bs[2][BK][BN + LDS_PAD];
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmAr
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
     }
-    if (ACC64) {
+    if (ACC64 && ((kt + 1) % (ACC64 ? ACC64 : 1) == 0 || kt + 1 == nk)) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll

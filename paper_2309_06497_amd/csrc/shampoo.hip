@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <new>
@@ -15,6 +16,7 @@
 #include "eigh_jacobi.h"
 #include "elementwise.h"
 #include "gemm_mfma.h"
+#include "syrk_bf16.h"
 
 using namespace shampoo;
 
@@ -47,6 +49,7 @@ struct Bucket {
   size_t off_L, off_R, off_Linv, off_Rinv, off_P, off_desc, off_sgp, off_sshp, off_scale, off_norms;
   EwGeom geom;
   int32_t tiles_m, tiles_n;
+  bool bf16_mfma;   // shapes, offsets and leading dimensions allow the bf16 matrix-core factor update
 };
 struct Plan {
   std::vector<Block> blocks;
@@ -144,6 +147,11 @@ void make_plan(const shampoo_config *c, Plan &p) {
     off += (rows * cols + 3) / 4 * 4;
   }
   p.total_elems = off;
+  for (auto &bk : p.buckets) bk.bf16_mfma = (bk.m % 8 == 0) && (bk.n % 8 == 0) && bk.count <= 65535;
+  for (const Block &blk : p.blocks) {
+    const int64_t ld = c->shape[2 * blk.param + 1];
+    if (ld % 8 != 0 || (blk.row0 * ld + blk.col0) % 8 != 0) p.buckets[blk.bucket].bf16_mfma = false;
+  }
   for (auto &bk : p.buckets) {
     bk.geom = make_geom(bk.m, bk.n);
     bk.tiles_m = (bk.m + BM - 1) / BM;
@@ -186,7 +194,7 @@ EigLayout eig_layout(int n, int batch) {
   return e;
 }
 
-template <int AO, int BO, typename TA, typename TB, int EPI, bool KS, bool ACC64 = false>
+template <int AO, int BO, typename TA, typename TB, int EPI, bool KS, int ACC64 = 0>
 int launch_gemm(GemmArgs &g, hipStream_t s) {
   const int64_t total = (int64_t)g.tiles * g.batch;
   if (total <= 0) return SHAMPOO_OK;
@@ -246,12 +254,16 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
     BlockJacArgs ja;
     ja.w = w; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
     ja.np = np;
+    ja.inner_sweeps = JAC_INNER_SWEEPS;
+    ja.tol_rel = JAC_SMALL_TOL_REL;
+    if (const char *e1 = getenv("SHAMPOO_JAC_INNER")) ja.inner_sweeps = std::max(1, atoi(e1));
+    if (const char *e2 = getenv("SHAMPOO_JAC_TOL")) ja.tol_rel = atof(e2);
     for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
       for (int rd = 0; rd < nblk - 1; ++rd) {
         ja.round = rd; ja.sweep = sw;
         hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cb), dim3(JAC_THREADS), 0, s, ja);
         hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(hp * (hp + 1) / 2, cb), dim3(JAC_THREADS), 0, s, ja);
-        hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * (np / JAC_PIV), cb), dim3(JAC_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES), cb), dim3(JAC_THREADS), 0, s, ja);
       }
     HIP_TRY(hipGetLastError());
     BlockFinalArgs fa;
@@ -288,9 +300,11 @@ struct shampoo_opt {
   unsigned char *ws = nullptr;
   size_t ws_bytes = 0;
   // workspace offsets
+  size_t off_Gt = 0;
   size_t off_A = 0, off_M = 0, off_T = 0, off_wtab = 0, off_gtab = 0, off_diag = 0, off_count = 0, off_eig = 0;
   std::vector<EigLayout> eig_L, eig_R;   // per bucket
   std::vector<void *> last_w, last_g;    // pointer tables currently on the device
+  bool ptrs_aligned16 = false;           // every gradient pointer is 16-byte aligned
   int64_t last_step = -1;
   int64_t n_refresh = 0;
   bool timing = false;
@@ -305,7 +319,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
   const size_t offA = take((size_t)p.total_elems * 4);
   const size_t offM = c->momentum > 0.f ? take((size_t)p.total_elems * 4) : 0;
-  size_t t_elems = 0, eig_bytes = 0;
+  size_t t_elems = 0, gt_elems = 0, eig_bytes = 0;
   std::vector<EigLayout> eL, eR;
   for (auto &b : p.buckets) {
     const size_t B = b.count, m = b.m, n = b.n;
@@ -320,18 +334,20 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     b.off_scale = take(B * 4);
     b.off_norms = take(B * 8);
     t_elems = std::max(t_elems, B * m * n);
+    if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma) gt_elems = std::max(gt_elems, B * m * n);
     eL.push_back(eig_layout(b.m, b.count));
     eR.push_back(eig_layout(b.n, b.count));
     eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
   }
   const size_t offT = take(t_elems * 4);
+  const size_t offGt = take(gt_elems * 2);
   const size_t offW = take((size_t)c->n_params * sizeof(void *));
   const size_t offG = take((size_t)c->n_params * sizeof(void *));
   const size_t offD = take(std::max<size_t>(1, p.diag_chunks.size()) * sizeof(DiagChunk));
   const size_t offC = take(64);
   const size_t offE = take(eig_bytes);
   if (o) {
-    o->off_A = offA; o->off_M = offM; o->off_T = offT; o->off_wtab = offW; o->off_gtab = offG;
+    o->off_A = offA; o->off_M = offM; o->off_T = offT; o->off_Gt = offGt; o->off_wtab = offW; o->off_gtab = offG;
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
     o->eig_L = eL; o->eig_R = eR;
   }
@@ -368,11 +384,41 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   // EMA weights from the float32 beta2 the caller gave, evaluated in float64
   const double alpha = c.beta2 < 1.f ? 1.0 - (double)c.beta2 : 1.0;
   const double beta = c.beta2 < 1.f ? (double)c.beta2 : 1.0;
+  // k-slabs between float64 flushes of the factor accumulators (flushing every 4 slabs
+  // measured 3x larger errors in the stale-root directions, for a 5 % gain)
+  constexpr int FLUSH = 1;
   int rc;
 
   for (auto &b : p.buckets) {
     const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
-    {
+    if (sizeof(GT) == 2 && b.bf16_mfma && o->ptrs_aligned16) {
+      StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
+      uint16_t *Gt = reinterpret_cast<uint16_t *>(ws + o->off_Gt);
+      TransposeArgs ta;
+      ta.desc = desc; ta.g_table = gtab; ta.out = Gt; ta.m = b.m; ta.n = b.n;
+      hipLaunchKernelGGL(transpose_bf16_kernel, dim3((b.n + 63) / 64, (b.m + 63) / 64, b.count), dim3(256), 0, s, ta);
+      SyrkBf16Args sa{};
+      sa.desc = desc; sa.ptr_table = gtab; sa.alpha = alpha; sa.beta = beta; sa.batch = b.count;
+      // L <- beta L + alpha G G^T
+      sa.a.from_table = 1;
+      sa.c = reinterpret_cast<float *>(ws + b.off_L); sa.c_batch_stride = (int64_t)b.m * b.m; sa.ldc = b.m;
+      sa.M = b.m; sa.K = b.n; sa.tiles = b.tiles_m * (b.tiles_m + 1) / 2;
+      {
+        const int64_t total = (int64_t)sa.tiles * sa.batch;
+        const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
+        hipLaunchKernelGGL(syrk_bf16_kernel, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+      }
+      // R <- beta R + alpha (G^T)(G^T)^T
+      sa.a.from_table = 0; sa.a.base = Gt; sa.a.batch_stride = (int64_t)b.m * b.n; sa.a.ld = b.m;
+      sa.c = reinterpret_cast<float *>(ws + b.off_R); sa.c_batch_stride = (int64_t)b.n * b.n; sa.ldc = b.n;
+      sa.M = b.n; sa.K = b.m; sa.tiles = b.tiles_n * (b.tiles_n + 1) / 2;
+      {
+        const int64_t total = (int64_t)sa.tiles * sa.batch;
+        const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
+        hipLaunchKernelGGL(syrk_bf16_kernel, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+      }
+      HIP_TRY(hipGetLastError());
+    } else {
       StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
       GemmArgs g{};
       g.a.from_table = 1; g.b.from_table = 1;
@@ -382,13 +428,13 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       g.c = reinterpret_cast<float *>(ws + b.off_L); g.c_batch_stride = (int64_t)b.m * b.m; g.ldc = b.m;
       g.M = b.m; g.N = b.m; g.K = b.n;
       g.tiles_m = g.tiles_n = b.tiles_m; g.tiles = b.tiles_m * (b.tiles_m + 1) / 2;
-      rc = launch_gemm<K_CONTIG, K_CONTIG, GT, GT, EPI_SYRK, false, true>(g, s);
+      rc = launch_gemm<K_CONTIG, K_CONTIG, GT, GT, EPI_SYRK, false, FLUSH>(g, s);
       if (rc) return rc;
       // R <- beta R + alpha G^T G
       g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.n * b.n; g.ldc = b.n;
       g.M = b.n; g.N = b.n; g.K = b.m;
       g.tiles_m = g.tiles_n = b.tiles_n; g.tiles = b.tiles_n * (b.tiles_n + 1) / 2;
-      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GT, GT, EPI_SYRK, false, true>(g, s);
+      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GT, GT, EPI_SYRK, false, FLUSH>(g, s);
       if (rc) return rc;
     }
     {
@@ -586,6 +632,9 @@ int shampoo_step(shampoo_opt *o, void *const *params, const void *const *grads, 
   for (int i = 0; same && i < np; ++i) same = o->last_w[i] == params[i] && o->last_g[i] == grads[i];
   if (!same) {
     o->last_w.assign(params, params + np);
+    o->ptrs_aligned16 = true;
+    for (int i = 0; i < np; ++i)
+      if (reinterpret_cast<uintptr_t>(grads[i]) % 16 != 0) o->ptrs_aligned16 = false;
     o->last_g.resize(np);
     for (int i = 0; i < np; ++i) o->last_g[i] = const_cast<void *>(grads[i]);
     HIP_TRY(hipMemcpyAsync(o->ws + o->off_wtab, o->last_w.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
