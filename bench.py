@@ -35,6 +35,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
+# HBM bytes per launch of the dominant kernel (P = T Rbar) on the transformer workload, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (x2.0 / x1.0):
+# profiles/transformer_b1024_hbm_traffic_pmc.md
+TRAFFIC_BYTES = {"transformer": 14.43e9 + 4.83e9}
 PEAK_HBM_GBS = 8000.0
 TILE = 128
 
@@ -122,6 +126,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="transformer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-refresh", action="store_true",
+                    help="number the steps from 1 so that no root refresh runs (roots stay the identity); "
+                         "for counter runs of the per-step kernels only")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, the reference for scaling HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the multi-GPU distribution of the "
@@ -154,18 +163,23 @@ def main():
     opt.set_timing(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    opt.step(params, pool[0], 0.01, 0)
+    base = 1 if args.skip_refresh else 0
+    if args.copy_ref:
+        ref_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_(generator=gen)
+        ref_dst = torch.empty_like(ref_src)
+        ref_dst.copy_(ref_src)
+    opt.step(params, pool[0], 0.01, base)
     torch.cuda.synchronize()
     first_step_ms = (time.perf_counter() - t0) * 1e3
     refresh_ms = opt.get_timing()["root"][0]
     for t in range(1, warm):
-        opt.step(params, pool[t % 2], 0.01, t)
+        opt.step(params, pool[t % 2], 0.01, base + t)
     torch.cuda.synchronize()
     opt.get_timing()
 
     t0 = time.perf_counter()
     for t in range(warm, warm + args.steps):
-        opt.step(params, pool[t % 2], 0.01, t)
+        opt.step(params, pool[t % 2], 0.01, base + t)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     stages = opt.get_timing()
@@ -203,11 +217,15 @@ def main():
         "tflops_executed": (exe_f + exe_p) / (ms_per_step * 1e-3) / 1e12,
         "stage_ms_per_step": st_ms,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                     "traffic": TRAFFIC_BYTES.get(args.workload),
                      "kernel": "gemm_mfma_kernel (two-sided preconditioning, fp32 MFMA)",
                      "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch},
         "stage_roofline": {
-            "factor": {"bound": "mfma", "tflops_algorithmic": alg_f / (st_ms["factor"] * 1e-3) / 1e12 if st_ms["factor"] else 0,
+            # bf16 gradients: G G^T runs on the bf16 matrix cores (exact products, float32 / float64
+            # accumulation); the figure is algorithmic flops per second, comparable to the float32 peak
+            "factor": {"bound": "mfma", "matrix_core_dtype": "bf16" if wk["bf16"] else "f32",
+                       "tflops_algorithmic": alg_f / (st_ms["factor"] * 1e-3) / 1e12 if st_ms["factor"] else 0,
                        "tflops_executed": exe_f / (st_ms["factor"] * 1e-3) / 1e12 if st_ms["factor"] else 0},
             "precond": {"bound": "mfma", "tflops": alg_p / (st_ms["precond"] * 1e-3) / 1e12 if st_ms["precond"] else 0},
             "graft": {"bound": "hbm", "GBps": ew_bytes["graft"] / (st_ms["graft"] * 1e-3) / 1e9 if st_ms["graft"] else 0},

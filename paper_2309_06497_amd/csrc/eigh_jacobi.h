@@ -33,7 +33,7 @@ constexpr int JAC_PIV = 2 * JAC_NB;   // pivot size
 constexpr int JAC_SMALL_MAX = 128;    // largest n solved entirely in LDS
 constexpr int JAC_SMALL_SWEEPS = 20;
 constexpr int JAC_OUTER_SWEEPS = 16;
-constexpr int JAC_INNER_SWEEPS = 2;
+constexpr int JAC_INNER_SWEEPS = 1;
 // rotation thresholds |a_pq| > rel * sqrt(|a_pp a_qq|) and > abs * max|diag(input)|
 constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver on a float64 copy of the factor
 constexpr double JAC_SMALL_TOL_ABS = 1e-15;
@@ -55,6 +55,21 @@ __device__ __host__ __forceinline__ void rr_pair(int cnt, int r, int k, int &p, 
     q = r - k; if (q < 0) q += m1;
   }
   if (p > q) { const int t = p; p = q; q = t; }
+}
+
+// 1 / sqrt(x) and 1 / x for finite x > 0 (x != 0 for the reciprocal) to float64 accuracy:
+// hardware estimate + three Newton steps (each squares the relative error)
+__device__ __forceinline__ double rsqrt_newton(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+#pragma unroll
+  for (int it = 0; it < 3; ++it) y = y * (1.5 - 0.5 * x * y * y);
+  return y;
+}
+__device__ __forceinline__ double rcp_newton(double x) {
+  double y = __builtin_amdgcn_rcp(x);
+#pragma unroll
+  for (int it = 0; it < 3; ++it) y = y * (2.0 - x * y);
+  return y;
 }
 
 // index of element (i, j) of a symmetric matrix stored as its packed lower triangle
@@ -90,14 +105,19 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
         const double app = At[at(p, p)], aqq = At[at(q, q)], apq = At[at(q, p)];
         double sn = 0.0, tp = 0.0;
         const double aa = fabs(apq);
-        if (aa > tol_abs && aa > tol_rel * sqrt(fabs(app * aqq))) {
+        if (aa > tol_abs && aa * aa > tol_rel * tol_rel * fabs(app * aqq)) {
           // t = tan of the rotation angle, the smaller root of t^2 + 2 zeta t - 1 = 0 with
-          // zeta = (a_qq - a_pp) / (2 a_pq), written so that it costs one division
+          // zeta = (a_qq - a_pp) / (2 a_pq):  t = h / (d + sign(d) sqrt(d^2 + h^2)).
+          // This chain is the serial part of every round (32 lanes work, 224 wait), so the
+          // square root and the reciprocals start from the hardware estimates and are
+          // polished by Newton steps instead of going through the full library routines.
           const double d = aqq - app, h = 2.0 * apq;
-          const double t = h / (d + copysign(sqrt(d * d + h * h), d));
-          const double w = sqrt(1.0 + t * t);   // 1 / cos
-          sn = t / w;
-          tp = t / (1.0 + w);                   // sin / (1 + cos)
+          const double x = d * d + h * h;
+          const double hyp = x * rsqrt_newton(x);
+          const double t = h * rcp_newton(d + copysign(hyp, d));
+          const double c = rsqrt_newton(1.0 + t * t);   // cos
+          sn = t * c;
+          tp = sn * rcp_newton(1.0 + c);                 // sin / (1 + cos)
           if (!(fabs(sn) <= 1.0)) { sn = 0.0; tp = 0.0; }   // non-finite: leave the pair alone
           if (sn != 0.0) sc->flag = 1;
         }

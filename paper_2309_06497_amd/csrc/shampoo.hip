@@ -212,6 +212,85 @@ int launch_fill(float *p, float v, int64_t n, hipStream_t s) {
   return SHAMPOO_OK;
 }
 
+constexpr int JAC_STREAMS = 3;   // sub-chunks of the block solver that run concurrently
+
+struct AuxStreams {
+  hipStream_t stream[JAC_STREAMS - 1];
+  hipEvent_t fork, join[JAC_STREAMS - 1];
+};
+
+// Lazily created helper streams (default priority) and fork / join events; nullptr if
+// the runtime refuses, in which case everything runs on the caller's stream.
+AuxStreams *aux_streams() {
+  static AuxStreams a;
+  static int state = 0;   // 0 = not tried, 1 = ready, -1 = unavailable
+  if (state == 0) {
+    state = 1;
+    if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess) state = -1;
+    for (int i = 0; i < JAC_STREAMS - 1 && state == 1; ++i) {
+      if (hipStreamCreateWithFlags(&a.stream[i], hipStreamNonBlocking) != hipSuccess) state = -1;
+      else if (hipEventCreateWithFlags(&a.join[i], hipEventDisableTiming) != hipSuccess) state = -1;
+    }
+  }
+  return state == 1 ? &a : nullptr;
+}
+
+// Block-Jacobi root inverse of `cnt` matrices, using workspace slots [slot0, slot0 + cnt).
+int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float *x, float *lambda,
+                       int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
+                       const EigLayout &e, int slot0, hipStream_t s) {
+  const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
+  double *w = reinterpret_cast<double *>(ws + e.off_w) + (int64_t)slot0 * np * np;
+  float *qt = reinterpret_cast<float *>(ws + e.off_qt) + (int64_t)slot0 * np * np;
+  float *jbuf = reinterpret_cast<float *>(ws + e.off_j) + (int64_t)slot0 * hp * JAC_PIV * JAC_PIV;
+  int32_t *ident = reinterpret_cast<int32_t *>(ws + e.off_ident) + (int64_t)slot0 * hp;
+  int32_t *rot = reinterpret_cast<int32_t *>(ws + e.off_rot) + (int64_t)slot0 * JAC_OUTER_SWEEPS;
+  float *dmax = reinterpret_cast<float *>(ws + e.off_dmax) + slot0;
+  int32_t *failed = reinterpret_cast<int32_t *>(ws + e.off_failed) + slot0;
+  float *fv = reinterpret_cast<float *>(ws + e.off_f) + (int64_t)slot0 * np;
+  int rc = launch_fill(dmax, 0.f, cnt, s);
+  if (rc) return rc;
+  rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, cnt, s);
+  if (rc) return rc;
+  BlockInitArgs ia;
+  ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
+  ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot;
+  hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cnt), dim3(256), 0, s, ia);
+  HIP_TRY(hipGetLastError());
+  BlockJacArgs ja;
+  ja.w = w; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
+  ja.np = np;
+  ja.inner_sweeps = JAC_INNER_SWEEPS;
+  ja.tol_rel = JAC_SMALL_TOL_REL;
+  if (const char *e1 = getenv("SHAMPOO_JAC_INNER")) ja.inner_sweeps = std::max(1, atoi(e1));
+  if (const char *e2 = getenv("SHAMPOO_JAC_TOL")) ja.tol_rel = atof(e2);
+  for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
+    for (int rd = 0; rd < nblk - 1; ++rd) {
+      ja.round = rd; ja.sweep = sw;
+      hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cnt), dim3(JAC_THREADS), 0, s, ja);
+      hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(hp * (hp + 1) / 2, cnt), dim3(JAC_THREADS), 0, s, ja);
+      hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES), cnt),
+                         dim3(JAC_THREADS), 0, s, ja);
+    }
+  HIP_TRY(hipGetLastError());
+  BlockFinalArgs fa;
+  fa.w = w; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.fvals = fv;
+  fa.lambda = lambda;
+  fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
+  hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);
+  HIP_TRY(hipGetLastError());
+  GemmArgs g{};
+  g.a.base = qt; g.a.batch_stride = (int64_t)np * np; g.a.ld = np; g.a.from_table = 0;
+  g.b = g.a;
+  g.c = x; g.c_batch_stride = (int64_t)n * n; g.ldc = n;
+  g.M = n; g.N = n; g.K = np; g.alpha = 1.f; g.beta = 0.f;
+  g.kscale = fv; g.kscale_stride = np; g.skip = failed;
+  g.tiles_m = g.tiles_n = (n + BM - 1) / BM;
+  g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
+  g.batch = cnt;
+  return launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_SYRK, true>(g, s);
+}
+
 // X_i = rootinv(A_i) for a batch of dense n x n matrices.  ws: eig_layout(n, >= chunk) region.
 int root_inverse_batched(const float *a, int n, int batch, float eps, float r, float *x, float *lambda,
                          int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
@@ -230,59 +309,36 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
     HIP_TRY(hipGetLastError());
     return SHAMPOO_OK;
   }
-  const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
-  double *w = reinterpret_cast<double *>(ws + e.off_w);
-  float *qt = reinterpret_cast<float *>(ws + e.off_qt);
-  float *jbuf = reinterpret_cast<float *>(ws + e.off_j);
-  int32_t *ident = reinterpret_cast<int32_t *>(ws + e.off_ident);
-  int32_t *rot = reinterpret_cast<int32_t *>(ws + e.off_rot);
-  float *dmax = reinterpret_cast<float *>(ws + e.off_dmax);
-  int32_t *failed = reinterpret_cast<int32_t *>(ws + e.off_failed);
-  float *fv = reinterpret_cast<float *>(ws + e.off_f);
+  // Large matrices: block Jacobi.  A chunk of matrices is cut into a few sub-chunks
+  // that run on separate streams: the pivot kernel is bound by LDS, the W update by
+  // the float64 matrix cores and the Q update by HBM, so sub-chunks that are in
+  // different phases overlap on the same CUs.
+  AuxStreams *aux = aux_streams();
+  int n_sub = aux ? JAC_STREAMS : 1;
+  if (const char *e0 = getenv("SHAMPOO_JAC_STREAMS")) n_sub = std::max(1, std::min(aux ? JAC_STREAMS : 1, atoi(e0)));
   for (int b0 = 0; b0 < batch; b0 += e.chunk) {
     const int cb = std::min(e.chunk, batch - b0);
-    // dmax and failed are adjacent 4-byte arrays of `chunk` entries each: clear both
-    int rc = launch_fill(dmax, 0.f, cb, s);
-    if (rc) return rc;
-    rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, cb, s);
-    if (rc) return rc;
-    BlockInitArgs ia;
-    ia.a = a + (int64_t)b0 * n * n; ia.a_stride = (int64_t)n * n; ia.n = n;
-    ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot;
-    hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cb), dim3(256), 0, s, ia);
-    HIP_TRY(hipGetLastError());
-    BlockJacArgs ja;
-    ja.w = w; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
-    ja.np = np;
-    ja.inner_sweeps = JAC_INNER_SWEEPS;
-    ja.tol_rel = JAC_SMALL_TOL_REL;
-    if (const char *e1 = getenv("SHAMPOO_JAC_INNER")) ja.inner_sweeps = std::max(1, atoi(e1));
-    if (const char *e2 = getenv("SHAMPOO_JAC_TOL")) ja.tol_rel = atof(e2);
-    for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
-      for (int rd = 0; rd < nblk - 1; ++rd) {
-        ja.round = rd; ja.sweep = sw;
-        hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cb), dim3(JAC_THREADS), 0, s, ja);
-        hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(hp * (hp + 1) / 2, cb), dim3(JAC_THREADS), 0, s, ja);
-        hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES), cb), dim3(JAC_THREADS), 0, s, ja);
+    const int subs = std::min(n_sub, cb);
+    if (subs > 1) {
+      HIP_TRY(hipEventRecord(aux->fork, s));
+      for (int k = 1; k < subs; ++k) HIP_TRY(hipStreamWaitEvent(aux->stream[k - 1], aux->fork, 0));
+    }
+    int first = 0;
+    for (int k = 0; k < subs; ++k) {
+      const int cnt = cb / subs + (k < cb % subs ? 1 : 0);
+      hipStream_t sk = k == 0 ? s : aux->stream[k - 1];
+      const int rc = block_jacobi_solve(a + (int64_t)(b0 + first) * n * n, n, cnt, eps, r,
+                                        x + (int64_t)(b0 + first) * n * n,
+                                        lambda ? lambda + (int64_t)(b0 + first) * n : nullptr,
+                                        failed_user ? failed_user + b0 + first : nullptr, fail_count, ws, e, first, sk);
+      if (rc) return rc;
+      first += cnt;
+    }
+    if (subs > 1)
+      for (int k = 1; k < subs; ++k) {
+        HIP_TRY(hipEventRecord(aux->join[k - 1], aux->stream[k - 1]));
+        HIP_TRY(hipStreamWaitEvent(s, aux->join[k - 1], 0));
       }
-    HIP_TRY(hipGetLastError());
-    BlockFinalArgs fa;
-    fa.w = w; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.fvals = fv;
-    fa.lambda = lambda ? lambda + (int64_t)b0 * n : nullptr;
-    fa.failed = failed; fa.failed_out = failed_user ? failed_user + b0 : nullptr; fa.fail_count = fail_count;
-    hipLaunchKernelGGL(blockjac_final_kernel, dim3(cb), dim3(256), 0, s, fa);
-    HIP_TRY(hipGetLastError());
-    GemmArgs g{};
-    g.a.base = qt; g.a.batch_stride = (int64_t)np * np; g.a.ld = np; g.a.from_table = 0;
-    g.b = g.a;
-    g.c = x + (int64_t)b0 * n * n; g.c_batch_stride = (int64_t)n * n; g.ldc = n;
-    g.M = n; g.N = n; g.K = np; g.alpha = 1.f; g.beta = 0.f;
-    g.kscale = fv; g.kscale_stride = np; g.skip = failed;
-    g.tiles_m = g.tiles_n = (n + BM - 1) / BM;
-    g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
-    g.batch = cb;
-    rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_SYRK, true>(g, s);
-    if (rc) return rc;
   }
   return SHAMPOO_OK;
 }

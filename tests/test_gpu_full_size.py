@@ -154,3 +154,20 @@ def test_root_inverse_stress_2048():
         assert e_range <= 2e-3
         assert e_x4 <= 2e-3
         assert e_full <= 0.5
+
+
+@pytest.mark.timeout(900)
+def test_resnet50_shapes_every_block():
+    """The ResNet-50 parameter set (54 weights -> 1576 blocks in 6 buckets at block 128, 107
+    vectors, 25.6e6 parameters), per-tensor sigma log-uniform in [1e-4, 1e-2]: the oracle runs
+    the whole set; every block and vector is compared (see Pair.check for the bars)."""
+    from test_gpu_parity import Pair
+    say("case resnet50 shapes")
+    shapes = wl.resnet50_shapes()
+    sig = wl.per_tensor_sigmas(shapes, 21)
+    p = Pair(shapes, 128, 0.999, 3)
+    for t in range(5):
+        p.step(wl.gaussian_grads(shapes, 21, t, sig), 0.01, t)
+        if t in (0, 1, 3, 4):
+            p.check(t)
+    assert p.gpu.status() == {"refreshes": 2, "failed_roots": 0}
