@@ -17,7 +17,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on it; calls return without waiting unless stated.
  *   - Return value: 0 on success, negative error code otherwise (see
- *     shampoo_strerror).  On a negative return nothing has been modified.
+ *     shampoo_strerror).  Argument errors (every code except SHAMPOO_ERR_HIP)
+ *     are detected before any work is enqueued: nothing has been modified.
  *   - No entry point throws; none is safe to call concurrently on the same
  *     shampoo_opt from several threads.
  */

@@ -262,8 +262,6 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   ja.np = np;
   ja.inner_sweeps = JAC_INNER_SWEEPS;
   ja.tol_rel = JAC_SMALL_TOL_REL;
-  if (const char *e1 = getenv("SHAMPOO_JAC_INNER")) ja.inner_sweeps = std::max(1, atoi(e1));
-  if (const char *e2 = getenv("SHAMPOO_JAC_TOL")) ja.tol_rel = atof(e2);
   for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
     for (int rd = 0; rd < nblk - 1; ++rd) {
       ja.round = rd; ja.sweep = sw;
@@ -314,8 +312,7 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
   // the float64 matrix cores and the Q update by HBM, so sub-chunks that are in
   // different phases overlap on the same CUs.
   AuxStreams *aux = aux_streams();
-  int n_sub = aux ? JAC_STREAMS : 1;
-  if (const char *e0 = getenv("SHAMPOO_JAC_STREAMS")) n_sub = std::max(1, std::min(aux ? JAC_STREAMS : 1, atoi(e0)));
+  const int n_sub = aux ? JAC_STREAMS : 1;
   for (int b0 = 0; b0 < batch; b0 += e.chunk) {
     const int cb = std::min(e.chunk, batch - b0);
     const int subs = std::min(n_sub, cb);
