@@ -19,7 +19,8 @@ FLAGS = [
 
 def build(verbose=True):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + SOURCES + ["-o", LIB]
+    extra = os.environ.get("SHAMPOO_EXTRA_FLAGS", "").split()   # e.g. -DSHAMPOO_GEMM_BK=32
+    cmd = [hipcc] + FLAGS + extra + SOURCES + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -24,8 +24,18 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 128;
 constexpr int BN = 128;
-constexpr int BK = 16;
-constexpr int LDS_PAD = 4;
+#ifndef SHAMPOO_GEMM_BK
+#define SHAMPOO_GEMM_BK 16
+#endif
+#ifndef SHAMPOO_GEMM_PAD
+#define SHAMPOO_GEMM_PAD 4
+#endif
+#ifndef SHAMPOO_GEMM_MINBLOCKS
+#define SHAMPOO_GEMM_MINBLOCKS 2
+#endif
+constexpr int BK = SHAMPOO_GEMM_BK;          // k-slab depth (multiple of 8)
+constexpr int LDS_PAD = SHAMPOO_GEMM_PAD;
+constexpr int LOAD_PASSES = BK / 8;          // 128 x BK floats = 256 threads x LOAD_PASSES float4
 constexpr int GEMM_THREADS = 256;
 constexpr int NUM_XCD = 8;
 
@@ -94,8 +104,8 @@ template <> struct Elem<uint16_t> {
   static __device__ __forceinline__ float load1(const uint16_t *p) { return bf16_to_f32(*p); }
 };
 
-// Fetches one 128 x BK operand slab into registers (8 floats per thread) and
-// later writes it into LDS in [k][row] order.
+// Fetches one 128 x BK operand slab into registers (4 * LOAD_PASSES floats per thread)
+// and later writes it into LDS in [k][row] order.
 template <int ORIENT, typename T>
 struct TileLoader {
   const T *ptr;     // operand origin for this batch entry, already offset to the tile's first row
@@ -103,7 +113,7 @@ struct TileLoader {
   int rows_left;    // valid rows from the tile's first row
   int K;
   bool fast;        // whole tile in range and 4-element vectors aligned
-  float r[2][4];
+  float r[LOAD_PASSES][4];
 
   __device__ __forceinline__ void init(const T *p, int ld_, int rows_left_, int K_) {
     ptr = p; ld = ld_; rows_left = rows_left_; K = K_;
@@ -113,10 +123,11 @@ struct TileLoader {
 
   __device__ __forceinline__ void fetch(int k0, int tid) {
     if (ORIENT == K_CONTIG) {
-      const int row = tid >> 2, kq = (tid & 3) * 4;
+      constexpr int TPR = BK / 4, RPP = GEMM_THREADS / TPR;   // threads per row, rows per pass
+      const int row = tid / TPR, kq = (tid % TPR) * 4;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int rr = row + 64 * h;
+      for (int h = 0; h < LOAD_PASSES; ++h) {
+        const int rr = row + RPP * h;
         if (fast) {
           Elem<T>::load4(ptr + (int64_t)rr * ld + k0 + kq, r[h]);
         } else {
@@ -128,7 +139,7 @@ struct TileLoader {
     } else {
       const int kk = tid >> 5, r4 = (tid & 31) * 4;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
+      for (int h = 0; h < LOAD_PASSES; ++h) {
         const int k = k0 + kk + 8 * h;
         if (fast) {
           Elem<T>::load4(ptr + (int64_t)k * ld + r4, r[h]);
@@ -144,16 +155,17 @@ struct TileLoader {
   // kscale: optional per-k multiplier (already offset to this batch entry), k0 = slab origin
   __device__ __forceinline__ void scale(const float *kscale, int k0, int tid) {
     if (ORIENT == K_CONTIG) {
-      const int kq = (tid & 3) * 4;
+      const int kq = (tid % (BK / 4)) * 4;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float s = (k0 + kq + j < K) ? kscale[k0 + kq + j] : 0.f;
-        r[0][j] *= s; r[1][j] *= s;
+#pragma unroll
+        for (int h = 0; h < LOAD_PASSES; ++h) r[h][j] *= s;
       }
     } else {
       const int kk = tid >> 5;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
+      for (int h = 0; h < LOAD_PASSES; ++h) {
         const int k = k0 + kk + 8 * h;
         const float s = (k < K) ? kscale[k] : 0.f;
 #pragma unroll
@@ -164,15 +176,16 @@ struct TileLoader {
 
   __device__ __forceinline__ void store(float (*lds)[BM + LDS_PAD], int tid) const {
     if (ORIENT == K_CONTIG) {
-      const int row = tid >> 2, kq = (tid & 3) * 4;
+      constexpr int TPR = BK / 4, RPP = GEMM_THREADS / TPR;
+      const int row = tid / TPR, kq = (tid % TPR) * 4;
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+      for (int h = 0; h < LOAD_PASSES; ++h)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) lds[kq + j][row + 64 * h] = r[h][j];
+        for (int j = 0; j < 4; ++j) lds[kq + j][row + RPP * h] = r[h][j];
     } else {
       const int kk = tid >> 5, r4 = (tid & 31) * 4;
 #pragma unroll
-      for (int h = 0; h < 2; ++h)
+      for (int h = 0; h < LOAD_PASSES; ++h)
         *reinterpret_cast<float4 *>(&lds[kk + 8 * h][r4]) = make_float4(r[h][0], r[h][1], r[h][2], r[h][3]);
     }
   }
@@ -205,7 +218,7 @@ __device__ __forceinline__ const T *operand_ptr(const Operand &o, const BlockDes
 // whose condition number is the square of G's, and a plain float32 running sum
 // over k would perturb its small eigenvalues by more than the parity budget.
 template <int AO, int BO, typename TA, typename TB, int EPI, bool KSCALE, int ACC64 = 0>
-__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(GEMM_THREADS, SHAMPOO_GEMM_MINBLOCKS) void gemm_mfma_kernel(const GemmArgs g) {
   __shared__ __align__(16) float As[2][BK][BM + LDS_PAD];
   __shared__ __align__(16) float Bs[2][BK][BN + LDS_PAD];
   __shared__ float red[4];
