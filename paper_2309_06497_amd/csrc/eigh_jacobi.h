@@ -35,7 +35,12 @@ constexpr int JAC_SMALL_SWEEPS = 20;
 constexpr int JAC_OUTER_SWEEPS = 16;
 constexpr int JAC_INNER_SWEEPS = 1;
 // rotation thresholds |a_pq| > rel * sqrt(|a_pp a_qq|) and > abs * max|diag(input)|
-constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver on a float64 copy of the factor
+constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver (n <= 128), float64 copy of the factor
+// Block solver: an off-diagonal element left at tau sqrt(a_ii a_jj) tilts the two
+// eigenvectors by a_ij / (lambda_i - lambda_j) and changes f(A) by about |f'| |a_ij|
+// <= tau f / 4, i.e. sqrt(n) tau / 4 ~ 1e-6 over a 1024-matrix: below the float32
+// accuracy of the accumulated Q, and one sweep cheaper than 1e-11.
+constexpr double JAC_BLOCK_TOL_REL = 1e-7;
 constexpr double JAC_SMALL_TOL_ABS = 1e-15;
 
 struct JacScratch {      // small per-workgroup LDS arrays
@@ -647,27 +652,46 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const 
 }
 
 struct BlockFinalArgs {
-  const double *w; int32_t np; int32_t n;
+  const double *w; const float *qt; int32_t np; int32_t n;
   float epsilon, r;
-  float *fvals;          // [batch][np]: lambda'^-r (0 on padding)
+  float *fvals;          // [batch][np]: lambda'^-r / ||q||^2 (0 on padding)
   float *lambda;         // optional [batch][n]
   int32_t *failed;       // [batch] in/out
   int32_t *failed_out;   // optional user-visible copy
   unsigned long long *fail_count;
 };
 
-// One workgroup per matrix: eigenvalues = diag(W); shift; f(lambda).
+// One workgroup per matrix: eigenvalues, shift, f(lambda).
+// The rotation blocks are orthogonal to float32 accuracy only, so after a few
+// hundred rounds the accumulated columns q_i have drifted off unit length by ~1e-5
+// (and the diagonal of W, q_i^T A q_i, with them).  Both are put right here: the
+// eigenvalue is the Rayleigh quotient W_ii / ||q_i||^2 and the weight handed to the
+// reconstruction sum_i f_i q_i q_i^T is f_i / ||q_i||^2.
 __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArgs g) {
   __shared__ double redf[4];
   __shared__ int redi[4];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int np = g.np, n = g.n;
   const double *w = g.w + (int64_t)b * np * np;
+  const float *qt = g.qt + (int64_t)b * np * np;
   float *fv = g.fvals + (int64_t)b * np;
   const int bad = g.failed[b];
+  // pass 1: fv[i] <- ||row i of Qt||^2, one wavefront per row
+  if (!bad)
+    for (int i = wave; i < n; i += 4) {
+      double ss = 0.0;
+      for (int j = lane; j < np; j += 64) {
+        const double v = (double)qt[(int64_t)i * np + j];
+        ss += v * v;
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+      if (lane == 0) fv[i] = (float)ss;
+    }
+  __syncthreads();
   double lmin = 1.0e300;
   if (!bad)
-    for (int i = tid; i < n; i += 256) lmin = fmin(lmin, w[(int64_t)i * np + i]);
+    for (int i = tid; i < n; i += 256) lmin = fmin(lmin, w[(int64_t)i * np + i] / (double)fv[i]);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   if (lane == 0) redf[wave] = lmin;
@@ -678,8 +702,9 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
   for (int i = tid; i < np; i += 256) {
     float f = 0.f;
     if (i < n && !bad) {
-      const double lam = w[(int64_t)i * np + i];
-      f = (float)pow(lam - shift + (double)g.epsilon, -(double)g.r);
+      const double nrm2 = (double)fv[i];
+      const double lam = w[(int64_t)i * np + i] / nrm2;
+      f = (float)(pow(lam - shift + (double)g.epsilon, -(double)g.r) / nrm2);
       if (!(f <= 3.0e38f) || !(f >= 0.f)) badf = 1;
       if (g.lambda) g.lambda[(int64_t)b * n + i] = (float)lam;
     }

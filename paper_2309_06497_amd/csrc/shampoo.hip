@@ -261,7 +261,7 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   ja.w = w; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
   ja.np = np;
   ja.inner_sweeps = JAC_INNER_SWEEPS;
-  ja.tol_rel = JAC_SMALL_TOL_REL;
+  ja.tol_rel = JAC_BLOCK_TOL_REL;
   for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
     for (int rd = 0; rd < nblk - 1; ++rd) {
       ja.round = rd; ja.sweep = sw;
@@ -272,7 +272,7 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
     }
   HIP_TRY(hipGetLastError());
   BlockFinalArgs fa;
-  fa.w = w; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.fvals = fv;
+  fa.w = w; fa.qt = qt; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.fvals = fv;
   fa.lambda = lambda;
   fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
   hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);

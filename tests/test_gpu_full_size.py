@@ -127,7 +127,7 @@ def test_root_inverse_stress_2048():
     eps = f32(1e-12)
     x, lam, failed = B.shampoo_root_inverse(torch.from_numpy(a).cuda(), 1e-12, 0.25, True, True)
     x = x.cpu().numpy(); lam = lam.cpu().numpy()
-    assert not failed.cpu().numpy().any()
+    assert not failed.cpu().numpy().any(), (failed.cpu().numpy(), np.isnan(lam).sum(axis=1))
     for i in range(batch):
         assert np.array_equal(x[i], x[i].T)
         assert np.isfinite(x[i]).all()

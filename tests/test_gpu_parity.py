@@ -270,10 +270,7 @@ def test_root_inverse_standalone(n):
         e_lam = np.abs(np.sort(lam[i]) - lo).max() / lo.max()
         e_x = rel(x[i], xo)
         say(f"    n={n} i={i} eig err {e_lam:.2e} X err {e_x:.2e}")
-        # n > 128: the rotation blocks are orthogonal to float32 accuracy only; applied as
-        # congruences they scale all eigenvalues by a common 1 + O(1e-5), which moves the
-        # root by a quarter of that
-        assert e_lam <= (1e-6 if n <= 128 else 5e-5)
+        assert e_lam <= 2e-6
         assert e_x <= 1e-4
 
 
