@@ -10,23 +10,27 @@ Everything is numpy float64.  Inputs given as float32 (or bf16 bits decoded
 to float32 by the caller) are widened exactly.  No blocking, fusion or
 reordering beyond what the paper's algorithm states.
 
-What is computed (paper: "Complete Distributed Shampoo Pseudocode", restricted
-to beta1 = 0, no weight decay, no Nesterov, AdaGrad grafting; identical to
-"Shampoo Pseudocode (with AdaGrad Grafting)" when beta2 = 1):
+What is computed (paper: "Complete Distributed Shampoo Pseudocode" without bias
+correction; identical to "Shampoo Pseudocode (with AdaGrad Grafting)" when
+beta2 = 1, beta1 = 0, no weight decay, no momentum):
 
   for every block (m x n) of every 2-D parameter, at iteration t (0-based):
+    0. if weight_decay > 0 and not decoupled: G <- G + weight_decay * W   [Sec. 3.1.2]
     1. L <- beta2 L + (1-beta2) G G^T,  R <- beta2 R + (1-beta2) G^T G
        (plain sums when beta2 == 1; L = R = 0 initially)      [Sec. 3.1.1 EMA eqs]
-    2. A <- A + G*G elementwise (AdaGrad grafting state)       [Sec. 2.4]
+    2. AdaGrad grafting: A <- A + G*G elementwise (SGD grafting has no state)  [Sec. 2.4]
     3. if t >= start and t % f == 0:
          Lbar <- rootinv(L), Rbar <- rootinv(R)                [Sec. 3.2.1 framed box]
-    4. P_graft = G / (sqrt(A) + eps_graft)                     [Sec. 2.4]
-    5. if t >= start: P = -||P_graft||_F * Lbar G Rbar / ||Lbar G Rbar||_F
+    4. if beta1 > 0: Gf <- beta1 Gf + (1-beta1) G (Gf = 0 initially), else Gf = G.
+       The grafting state above uses G, every direction below uses Gf.   [Sec. 3.1.1]
+    5. P_graft = Gf / (sqrt(A) + eps_graft)  (AdaGrad)  or  Gf  (SGD)    [Sec. 2.4]
+    6. if t >= start: P = -||P_graft||_F * Lbar Gf Rbar / ||Lbar Gf Rbar||_F
        else:          P = -P_graft                             [Sec. 2.4 grafting eq.]
-    6. M <- mu M + P ; P <- M   (only when mu > 0)             [Sec. 3.1.3 momentum eqs]
-    7. W <- W + lr * P
-  1-D parameters take steps 2, 4, P = -P_graft, 6, 7 (diagonal AdaGrad,
-  Sec. 2.2 / Sec. 4.2.2).
+    7. if weight_decay > 0 and decoupled: P <- P - weight_decay * W      [Sec. 3.1.2 eqs]
+    8. if mu > 0: M <- mu M + P ; P <- mu M + P (Nesterov) or P <- M     [Sec. 3.1.3 eqs]
+    9. W <- W + lr * P
+  1-D parameters take steps 0, 2 (always AdaGrad), 4, P = -Gf / (sqrt(A) + eps_graft),
+  7, 8, 9 (diagonal AdaGrad, Sec. 2.2 / Sec. 4.2.2).
 
 Readings of the paper taken here (each also listed in the design notes):
   * Factors start at zero and epsilon enters only inside the root-inverse
@@ -41,10 +45,16 @@ Readings of the paper taken here (each also listed in the design notes):
     (sign consistent with W <- W + lr P).
   * Momentum recursion is M_t = mu M_{t-1} + P_t.
   * If ||P_shampoo||_F == 0 or ||P_graft||_F == 0 the block's P is zero.
+  * Decoupled weight decay enters as P <- P - weight_decay * W: the complete
+    pseudocode prints a plus sign, but its P already carries the minus sign of the
+    step (W <- W + lr P), and the text equations give W_{t+1} = (1 - lr wd) W_t - ....
+  * 1-D parameters keep diagonal AdaGrad whatever the grafting type of the blocks.
 
 Pins: see tests/test_oracle_pins.py (Kronecker brute force, X^4 (L+eps I) = I,
 diagonal closed forms, polar factor at t = 0, textbook AdaGrad, geometric
-momentum, trace identities, independent Jacobi eigensolver).
+momentum and Nesterov sums, trace identities, independent Jacobi eigensolver,
+geometric weight decay, l2 as a shifted gradient, constant-gradient filtering,
+SGD-graft step length).
 """
 import numpy as np
 
@@ -135,7 +145,8 @@ class ShampooOracle:
 
     def __init__(self, shapes, block_size, beta2, epsilon, root_exponent,
                  precondition_frequency, start_preconditioning_step=0,
-                 graft_epsilon=1e-10, momentum=0.0):
+                 graft_epsilon=1e-10, momentum=0.0, beta1=0.0, weight_decay=0.0,
+                 use_decoupled_weight_decay=True, use_nesterov=False, grafting="adagrad"):
         self.shapes = [tuple(int(x) for x in s) for s in shapes]
         self.b = int(block_size)
         self.beta2 = float(beta2)
@@ -145,14 +156,22 @@ class ShampooOracle:
         self.start = int(start_preconditioning_step)
         self.eps_g = float(graft_epsilon)
         self.mu = float(momentum)
+        self.beta1 = float(beta1)
+        self.wd = float(weight_decay)
+        self.decoupled = bool(use_decoupled_weight_decay)
+        self.nesterov = bool(use_nesterov)
+        if grafting not in ("adagrad", "sgd"):
+            raise ValueError("grafting must be 'adagrad' or 'sgd'")
+        self.grafting = grafting
         self.blocks = []      # per param: list of (r0, c0, m, n) (empty for 1-D)
         self.L, self.R, self.Lbar, self.Rbar = [], [], [], []
-        self.A, self.M = [], []
+        self.A, self.M, self.Gf = [], [], []
         self.P_sh = []        # last Shampoo direction per block (for inspection)
         self.s_g, self.s_sh = [], []   # last squared norms per block
         for s in self.shapes:
             self.A.append(np.zeros(s))
             self.M.append(np.zeros(s))
+            self.Gf.append(np.zeros(s))
             if len(s) == 2:
                 blks = block_partition(s[0], s[1], self.b)
                 self.blocks.append(blks)
@@ -172,6 +191,15 @@ class ShampooOracle:
             else:
                 raise ValueError("only 1-D and 2-D parameters")
 
+    def _finish(self, i, sl, P, W, lr):
+        """Steps 7-9 on one block / vector: decoupled decay, momentum, update."""
+        if self.wd > 0.0 and self.decoupled:
+            P = P - self.wd * W[sl]
+        if self.mu > 0.0:
+            self.M[i][sl] = self.mu * self.M[i][sl] + P
+            P = self.mu * self.M[i][sl] + P if self.nesterov else self.M[i][sl]
+        W[sl] += lr * P
+
     def step(self, params, grads, lr, t):
         """One iteration t.  params: list of float64 arrays, updated in place.
         grads: list of arrays (any float dtype; widened exactly)."""
@@ -179,33 +207,38 @@ class ShampooOracle:
         for i, s in enumerate(self.shapes):
             G = np.asarray(grads[i], dtype=np.float64)
             W = params[i]
+            if self.wd > 0.0 and not self.decoupled:
+                G = G + self.wd * W
+            if self.beta1 > 0.0:
+                self.Gf[i] = self.beta1 * self.Gf[i] + (1.0 - self.beta1) * G
+                Gf = self.Gf[i]
+            else:
+                Gf = G
             if len(s) == 1:
                 self.A[i] = graft_state_update(self.A[i], G)
-                P = -graft_direction(G, self.A[i], self.eps_g)
-                if self.mu > 0.0:
-                    self.M[i] = self.mu * self.M[i] + P
-                    P = self.M[i]
-                W += lr * P
+                P = -graft_direction(Gf, self.A[i], self.eps_g)
+                self._finish(i, slice(None), P, W, lr)
                 continue
             for k, (r0, c0, m, n) in enumerate(self.blocks[i]):
                 sl = (slice(r0, r0 + m), slice(c0, c0 + n))
-                Gb = G[sl]
+                Gb, Gfb = G[sl], Gf[sl]
                 self.L[i][k], self.R[i][k] = factor_update(
                     self.L[i][k], self.R[i][k], Gb, self.beta2)
-                self.A[i][sl] = graft_state_update(self.A[i][sl], Gb)
+                if self.grafting == "adagrad":
+                    self.A[i][sl] = graft_state_update(self.A[i][sl], Gb)
                 if refresh:
                     self.Lbar[i][k], _ = root_inverse(self.L[i][k], self.epsilon, self.r)
                     self.Rbar[i][k], _ = root_inverse(self.R[i][k], self.epsilon, self.r)
-                Pg = graft_direction(Gb, self.A[i][sl], self.eps_g)
+                if self.grafting == "adagrad":
+                    Pg = graft_direction(Gfb, self.A[i][sl], self.eps_g)
+                else:
+                    Pg = Gfb.copy()
                 self.s_g[i][k] = float(np.sum(Pg * Pg))
                 if t >= self.start:
-                    Psh = shampoo_direction(self.Lbar[i][k], Gb, self.Rbar[i][k])
+                    Psh = shampoo_direction(self.Lbar[i][k], Gfb, self.Rbar[i][k])
                     self.P_sh[i][k] = Psh
                     self.s_sh[i][k] = float(np.sum(Psh * Psh))
                     P = grafted_direction(Psh, Pg)
                 else:
                     P = -Pg
-                if self.mu > 0.0:
-                    self.M[i][sl] = self.mu * self.M[i][sl] + P
-                    P = self.M[i][sl]
-                W[sl] += lr * P
+                self._finish(i, sl, P, W, lr)

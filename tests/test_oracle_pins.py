@@ -376,3 +376,138 @@ def test_bf16_helpers_roundtrip():
     # ties to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> rounds to 1
     assert wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.array([1.0 + 2.0 ** -8], np.float32)))[0] == 1.0
     assert wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(np.array([1.0 + 3 * 2.0 ** -8], np.float32)))[0] == 1.0 + 2.0 ** -6
+
+
+# ---------------------------------------------------------------------------
+# Heuristics of the complete pseudocode (Sec. 3.1): weight decay, gradient
+# filtering, Nesterov, SGD grafting
+# ---------------------------------------------------------------------------
+def test_decoupled_weight_decay_is_geometric_shrink():
+    """Zero gradients: W_{t+1} = (1 - lr wd) W_t (Sec. 3.1.2 decoupled equations)."""
+    shapes = [(6, 5), (7,)]
+    opt = make_opt(shapes, weight_decay=0.1, use_decoupled_weight_decay=True)
+    r = rng(20)
+    W0 = [r.standard_normal(s) for s in shapes]
+    W = [w.copy() for w in W0]
+    lr = 0.05
+    for t in range(6):
+        opt.step(W, [np.zeros(s) for s in shapes], lr, t)
+    for w, w0 in zip(W, W0):
+        assert np.allclose(w, w0 * (1 - lr * 0.1) ** 6, rtol=1e-13)
+
+
+def test_decoupled_weight_decay_adds_to_the_grafted_step():
+    """W_{t+1} = (1 - lr wd) W_t + lr P_t with P_t the step of the undecayed optimizer
+    (weight decay sits outside the preconditioner and the grafting, Sec. 3.1.2)."""
+    r = rng(21)
+    shapes = [(8, 6)]
+    grads = [[r.standard_normal(s) for s in shapes] for _ in range(4)]
+    lr, wd = 0.1, 0.3
+    plain = make_opt(shapes, precondition_frequency=2)
+    Wp = [np.zeros(s) for s in shapes]
+    P = []
+    for t, g in enumerate(grads):
+        before = Wp[0].copy()
+        plain.step(Wp, g, lr, t)
+        P.append((Wp[0] - before) / lr)
+    dec = make_opt(shapes, precondition_frequency=2, weight_decay=wd)
+    W = [r.standard_normal(shapes[0])]
+    w_ref = W[0].copy()
+    for t, g in enumerate(grads):
+        dec.step(W, g, lr, t)
+        w_ref = (1 - lr * wd) * w_ref + lr * P[t]
+        assert np.allclose(W[0], w_ref, rtol=1e-12, atol=1e-14)
+
+
+def test_l2_regularisation_is_a_shifted_gradient():
+    """l2: the optimizer sees G + wd W everywhere (Sec. 3.1.2): same trajectory as the
+    plain optimizer fed those gradients by hand."""
+    r = rng(22)
+    shapes = [(9, 7), (5,)]
+    grads = [[r.standard_normal(s) * 0.1 for s in shapes] for _ in range(5)]
+    wd, lr = 0.2, 0.05
+    a = make_opt(shapes, block_size=4, beta2=0.9, precondition_frequency=2, momentum=0.5,
+                 weight_decay=wd, use_decoupled_weight_decay=False)
+    b = make_opt(shapes, block_size=4, beta2=0.9, precondition_frequency=2, momentum=0.5)
+    Wa = [r.standard_normal(s) for s in shapes]
+    Wb = [w.copy() for w in Wa]
+    for t, g in enumerate(grads):
+        a.step(Wa, g, lr, t)
+        b.step(Wb, [gi + wd * wi for gi, wi in zip(g, Wb)], lr, t)
+        for x, y in zip(Wa, Wb):
+            assert np.allclose(x, y, rtol=1e-12, atol=1e-14)
+
+
+def test_nesterov_is_geometric_sum_plus_current_direction():
+    """W_{t+1} = W_t + lr (mu M_t + P_t), M_t = sum_{s<=t} mu^(t-s) P_s (Sec. 3.1.3)."""
+    r = rng(23)
+    shapes = [(6, 5), (9,)]
+    grads = [[r.standard_normal(s) * 0.1 for s in shapes] for _ in range(6)]
+    lr, mu = 0.02, 0.7
+    plain = make_opt(shapes, precondition_frequency=3)
+    W = [np.zeros(s) for s in shapes]
+    P = []
+    for t, g in enumerate(grads):
+        before = [w.copy() for w in W]
+        plain.step(W, g, lr, t)
+        P.append([(w - b0) / lr for w, b0 in zip(W, before)])
+    nes = make_opt(shapes, precondition_frequency=3, momentum=mu, use_nesterov=True)
+    Wn = [np.zeros(s) for s in shapes]
+    for t, g in enumerate(grads):
+        nes.step(Wn, g, lr, t)
+    for i in range(len(shapes)):
+        expect = np.zeros(shapes[i])
+        for t in range(len(grads)):
+            M = sum(mu ** (t - s_) * P[s_][i] for s_ in range(t + 1))
+            expect += lr * (mu * M + P[t][i])
+        assert np.allclose(Wn[i], expect, rtol=1e-10, atol=1e-14)
+
+
+def test_gradient_filtering_with_a_constant_gradient():
+    """Constant full-rank G, beta2 = 1, roots refreshed every step: the filtered gradient is
+    (1 - beta1^(t+1)) G, the Shampoo direction of any multiple of G is U V^T, the AdaGrad state
+    is (t+1) G^2, so W_T = -lr sqrt(max(m,n)) U V^T sum_t (1 - beta1^(t+1)) / sqrt(t+1)."""
+    m, n, b1, lr = 5, 4, 0.8, 0.1
+    G = rng(24).standard_normal((m, n))
+    U, S, Vt = np.linalg.svd(G, full_matrices=False)
+    opt = make_opt([(m, n)], epsilon=1e-14, graft_epsilon=0.0, beta1=b1)
+    W = [np.zeros((m, n))]
+    coeff = 0.0
+    for t in range(5):
+        opt.step(W, [G], lr, t)
+        coeff += (1 - b1 ** (t + 1)) / np.sqrt(t + 1)
+        assert np.allclose(W[0], -lr * np.sqrt(max(m, n)) * coeff * (U @ Vt), rtol=1e-6, atol=1e-9)
+
+
+def test_gradient_filtering_one_d_textbook():
+    """1-D: A from the raw gradient, direction from the filtered one (Sec. 3.1.1)."""
+    n, b1, lr, eg = 11, 0.9, 0.01, 1e-10
+    r = rng(25)
+    opt = make_opt([(n,)], beta1=b1, graft_epsilon=eg)
+    W = [np.zeros(n)]
+    w = np.zeros(n); a = np.zeros(n); gf = np.zeros(n)
+    for t in range(7):
+        g = r.standard_normal(n)
+        opt.step(W, [g], lr, t)
+        for i in range(n):
+            a[i] += g[i] * g[i]
+            gf[i] = b1 * gf[i] + (1 - b1) * g[i]
+            w[i] -= lr * gf[i] / (np.sqrt(a[i]) + eg)
+        assert np.allclose(W[0], w, rtol=1e-13, atol=1e-16)
+
+
+def test_sgd_grafting_step_length_and_polar_first_step():
+    """SGD grafting: ||P||_F = ||G||_F per block (Sec. 2.4); at t = 0 with beta2 = 1 the step is
+    -lr ||G||_F U V^T / sqrt(min(m, n))."""
+    m, n, lr = 6, 4, 0.2
+    G = rng(26).standard_normal((m, n))
+    U, S, Vt = np.linalg.svd(G, full_matrices=False)
+    opt = make_opt([(m, n)], epsilon=1e-14, grafting="sgd")
+    W = [np.zeros((m, n))]
+    opt.step(W, [G], lr, 0)
+    assert np.allclose(W[0], -lr * np.linalg.norm(G) / np.sqrt(min(m, n)) * (U @ Vt), rtol=1e-6, atol=1e-9)
+    G2 = rng(27).standard_normal((m, n))
+    before = W[0].copy()
+    opt.step(W, [G2], lr, 1)
+    assert np.isclose(np.linalg.norm(W[0] - before), lr * np.linalg.norm(G2), rtol=1e-10)
+    assert np.array_equal(opt.A[0], np.zeros((m, n)))     # no grafting state
