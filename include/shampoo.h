@@ -6,8 +6,9 @@
  * the Distributed Shampoo Optimizer for Training Neural Networks At-Scale"
  * (arXiv 2309.06497), restricted to one GPU: blocked Kronecker-factor
  * accumulation, periodic inverse-root refresh by batched symmetric
- * eigendecomposition, two-sided preconditioning, AdaGrad grafting, momentum
- * and the parameter update.  The multi-GPU distribution of the paper (Sec. 4.1)
+ * eigendecomposition, two-sided preconditioning, AdaGrad or SGD grafting,
+ * gradient filtering, weight decay, (Nesterov) momentum and the parameter
+ * update.  The multi-GPU distribution of the paper (Sec. 4.1)
  * is not part of this library.
  *
  * Conventions for every entry point
@@ -46,12 +47,12 @@ enum {
 };
 
 enum { SHAMPOO_GRAD_F32 = 0, SHAMPOO_GRAD_BF16 = 1 };
+enum { SHAMPOO_GRAFT_ADAGRAD = 0, SHAMPOO_GRAFT_SGD = 1 };
 
 /*
  * Optimizer configuration (copied at create; the arrays need not outlive the call).
  * Hyper-parameters are those of the paper's complete pseudocode (Sec. 3,
- * "Complete Distributed Shampoo Pseudocode") with beta1 = 0, no weight decay,
- * no Nesterov, no bias correction, AdaGrad grafting.
+ * "Complete Distributed Shampoo Pseudocode"), without bias correction.
  */
 typedef struct {
   int32_t n_params;       /* number of parameters (tensors), >= 1                          */
@@ -65,6 +66,13 @@ typedef struct {
   int32_t start_preconditioning_step; /* >= 0: before it the grafted direction is used alone   */
   float graft_epsilon;    /* >= 0: P_graft = G / (sqrt(A) + graft_epsilon) (Sec. 2.4)        */
   float momentum;         /* mu in [0,1): 0 disables the momentum state (Sec. 3.1.3)         */
+  float beta1;            /* in [0,1): > 0 filters the gradient, Gf <- beta1 Gf + (1-beta1) G;
+                             grafting state and factors use G, directions use Gf (Sec. 3.1.1) */
+  float weight_decay;     /* >= 0 (Sec. 3.1.2)                                               */
+  int32_t use_decoupled_weight_decay; /* != 0: P <- P - wd W after grafting; 0: G <- G + wd W  */
+  int32_t use_nesterov;   /* != 0: W += lr (mu M + P) instead of lr M (Sec. 3.1.3)            */
+  int32_t grafting_type;  /* SHAMPOO_GRAFT_ADAGRAD or SHAMPOO_GRAFT_SGD (P_graft = G) for the
+                             blocks; 1-D parameters always use diagonal AdaGrad              */
   int32_t grad_dtype;     /* SHAMPOO_GRAD_F32 or SHAMPOO_GRAD_BF16; parameters are float32   */
   int32_t device;         /* HIP device ordinal                                              */
 } shampoo_config;
@@ -98,12 +106,16 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
 /*
  * One optimizer iteration t = `step` (0-based, strictly increasing between
  * calls) of the complete pseudocode for every block of every parameter:
+ *   G <- G + wd W   (l2 weight decay only)               (Sec. 3.1.2)
  *   L <- beta2 L + (1-beta2) G G^T, R likewise          (Sec. 3.1.1)
- *   A <- A + G.^2                                        (Sec. 2.4)
+ *   A <- A + G.^2   (AdaGrad grafting)                   (Sec. 2.4)
  *   if step >= start and step % f == 0: roots refreshed  (Sec. 3.2.1 box, 4.3)
- *   P = -||G/(sqrt(A)+eps_g)||_F * Lbar G Rbar / ||Lbar G Rbar||_F   (Sec. 2.4)
- *       (P = -G/(sqrt(A)+eps_g) while step < start, and for 1-D parameters)
- *   M <- mu M + P ; W <- W + lr M                        (Sec. 3.1.3)
+ *   Gf <- beta1 Gf + (1-beta1) G  (Gf = G when beta1 = 0) (Sec. 3.1.1)
+ *   P_graft = Gf/(sqrt(A)+eps_g)  or  Gf (SGD grafting)
+ *   P = -||P_graft||_F * Lbar Gf Rbar / ||Lbar Gf Rbar||_F           (Sec. 2.4)
+ *       (P = -P_graft while step < start; 1-D parameters: -Gf/(sqrt(A)+eps_g))
+ *   P <- P - wd W   (decoupled weight decay only)        (Sec. 3.1.2)
+ *   M <- mu M + P ; W <- W + lr M  (Nesterov: lr (mu M + P))          (Sec. 3.1.3)
  * params: host array [n_params] of device pointers, float32, contiguous
  *         row-major with the shapes given at create; updated in place.
  * grads:  host array [n_params] of device pointers, float32 or bfloat16 per
@@ -124,7 +136,8 @@ enum {
   SHAMPOO_GET_A = 4,      /* m x n (block) or len (1-D parameter, block = 0) */
   SHAMPOO_GET_M = 5,      /* same shape as A; error if momentum == 0         */
   SHAMPOO_GET_PSH = 6,    /* m x n: last Lbar G Rbar                         */
-  SHAMPOO_GET_NORMS = 7   /* 2 floats: ||P_graft||_F^2, ||P_shampoo||_F^2 of the last step */
+  SHAMPOO_GET_NORMS = 7,  /* 2 floats: ||P_graft||_F^2, ||P_shampoo||_F^2 of the last step */
+  SHAMPOO_GET_GF = 8      /* same shape as A: filtered gradient; error if beta1 == 0       */
 };
 
 /*

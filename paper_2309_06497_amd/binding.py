@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshampoo.so")
 
 GRAD_F32, GRAD_BF16 = 0, 1
-GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS = range(8)
+GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF = range(9)
+GRAFT_ADAGRAD, GRAFT_SGD = 0, 1
 STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG = range(6)
 STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag")
 
@@ -38,6 +39,11 @@ class ShampooConfig(ctypes.Structure):
         ("start_preconditioning_step", ctypes.c_int32),
         ("graft_epsilon", ctypes.c_float),
         ("momentum", ctypes.c_float),
+        ("beta1", ctypes.c_float),
+        ("weight_decay", ctypes.c_float),
+        ("use_decoupled_weight_decay", ctypes.c_int32),
+        ("use_nesterov", ctypes.c_int32),
+        ("grafting_type", ctypes.c_int32),
         ("grad_dtype", ctypes.c_int32),
         ("device", ctypes.c_int32),
     ]
@@ -97,7 +103,8 @@ def _check(code):
 
 def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_frequency,
                 start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
-                grad_dtype=GRAD_F32, device=0):
+                grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
+                use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD):
     """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
     n = len(shapes)
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
@@ -107,7 +114,8 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
     shape = (ctypes.c_int64 * max(2 * n, 1))(*flat)
     cfg = ShampooConfig(n, ndim, shape, block_size, beta2, epsilon, root_exponent,
                         precondition_frequency, start_preconditioning_step, graft_epsilon,
-                        momentum, grad_dtype, device)
+                        momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
+                        1 if use_nesterov else 0, grafting_type, grad_dtype, device)
     cfg._keep = (ndim, shape)
     return cfg
 
@@ -138,12 +146,14 @@ class Shampoo:
 
     def __init__(self, shapes, block_size, beta2, epsilon, root_exponent, precondition_frequency,
                  start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
-                 grad_dtype=GRAD_F32, device=0):
+                 grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
+                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD):
         import torch
         self.shapes = [tuple(s) for s in shapes]
         self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
                                precondition_frequency, start_preconditioning_step, graft_epsilon,
-                               momentum, grad_dtype, device)
+                               momentum, grad_dtype, device, beta1, weight_decay,
+                               use_decoupled_weight_decay, use_nesterov, grafting_type)
         self.device = torch.device("cuda", device)
         nbytes = shampoo_workspace_bytes(self.cfg)
         if nbytes == 0:
@@ -176,7 +186,7 @@ class Shampoo:
                 raise ShampooError(-2)
             m, n = int(rows[block, 3]), int(rows[block, 4])
             shape = {GET_L: (m, m), GET_LINV: (m, m), GET_R: (n, n), GET_RINV: (n, n),
-                     GET_A: (m, n), GET_M: (m, n), GET_PSH: (m, n), GET_NORMS: (2,)}[which]
+                     GET_A: (m, n), GET_M: (m, n), GET_PSH: (m, n), GET_NORMS: (2,), GET_GF: (m, n)}[which]
         out = torch.empty(shape, dtype=torch.float32, device=self.device)
         _check(lib().shampoo_get(self.handle, param, block, which, ctypes.c_void_p(out.data_ptr()),
                                  out.numel() * 4, _stream_ptr()))

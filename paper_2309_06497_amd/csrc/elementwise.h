@@ -1,5 +1,6 @@
 // Coalesced elementwise stages of the step (HBM-bandwidth bound):
-//   graft_kernel      A <- A + G.^2 ; partial sums of ||G / (sqrt(A) + eps_g)||_F^2   (Sec. 2.4)
+//   prep_kernel       G1 = G + wd W (l2 weight decay), Gf <- beta1 Gf + (1-beta1) G1   (Sec. 3.1.1, 3.1.2)
+//   graft_kernel      A <- A + G.^2 ; partial sums of ||Gf / (sqrt(A) + eps_g)||_F^2  (Sec. 2.4)
 //   scale_kernel      per block: -||P_graft||_F / ||P_shampoo||_F from the partial sums
 //   update_kernel     P = scale * P_shampoo (or -P_graft) ; M <- mu M + P ; W <- W + lr M (Sec. 3.1.3)
 //   diag_kernel       1-D parameters: diagonal AdaGrad + momentum in one pass (Sec. 4.2.2)
@@ -24,7 +25,8 @@ struct EwGeom {        // how 256 threads tile a block of m x n
 struct EwArgs {
   const BlockDesc *desc;
   void *const *w_table;          // parameter pointers (float32)
-  const void *const *g_table;    // gradient pointers
+  const void *const *g_table;    // gradients that feed the grafting state (G, or G + wd W)
+  const void *const *gd_table;   // gradients that feed the directions (filtered gradient if beta1 > 0)
   float *a_state;                // grafting state, parameter layout, all parameters concatenated
   float *m_state;                // momentum state, same layout (nullptr when mu == 0)
   const float *p;                // [slot][m][n] Shampoo directions
@@ -33,6 +35,10 @@ struct EwArgs {
   int32_t m, n;
   EwGeom geom;
   float graft_eps, mu, lr;
+  float wd_decoupled;            // update_kernel: P <- P - wd_decoupled * W (0 = off)
+  int32_t nesterov;              // update_kernel: step with mu M + P instead of M
+  int32_t sgd_graft;             // P_graft = G (no grafting state) instead of AdaGrad
+  int32_t same_src;              // g_table and gd_table are the same tensors
   int32_t graft_only;            // update_kernel: use -P_graft instead of scale * P
 };
 
@@ -53,17 +59,20 @@ __device__ __forceinline__ void store_f4(float *p, bool vec, int valid, const fl
   for (int e = 0; e < 4; ++e) if (e < valid) p[e] = v[e];
 }
 
-// grid: chunks * (blocks of the bucket) workgroups, chunk index fastest
-template <typename GT>
+// grid: chunks * (blocks of the bucket) workgroups, chunk index fastest.
+// GS / GD: element types of the state-source and direction-source gradients.
+template <typename GS, typename GD>
 __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
   __shared__ float red[EW_THREADS / 64];
   const int slot = blockIdx.x / g.geom.chunks, chunk = blockIdx.x - slot * g.geom.chunks, tid = threadIdx.x;
   const BlockDesc d = g.desc[slot];
-  const GT *gp = reinterpret_cast<const GT *>(g.g_table[d.param]) + d.offset;
+  const GS *gp = reinterpret_cast<const GS *>(g.g_table[d.param]) + d.offset;
+  const GD *dp = reinterpret_cast<const GD *>(g.gd_table[d.param]) + d.offset;
   float *ap = g.a_state + d.state_offset;
   const int ld = d.ld, n = g.n;
   const bool vec = ((ld & 3) == 0) && ((n & 3) == 0) && ((d.offset & 3) == 0) && ((d.state_offset & 3) == 0) &&
-                   ((reinterpret_cast<uintptr_t>(g.g_table[d.param]) & 15) == 0);
+                   ((reinterpret_cast<uintptr_t>(g.g_table[d.param]) & 15) == 0) &&
+                   ((reinterpret_cast<uintptr_t>(g.gd_table[d.param]) & 15) == 0);
   const int lx = g.geom.lanes_x_log2;
   const int tx = tid & ((1 << lx) - 1), ty = tid >> lx, ny = EW_THREADS >> lx;
   const int r0 = chunk * g.geom.rows_per_wg;
@@ -72,13 +81,24 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
   for (int i = r0 + ty; i < r1; i += ny)
     for (int j = tx * 4; j < n; j += 4 << lx) {
       const int valid = min(4, n - j);
-      float gv[4], av[4];
-      load_g4<GT>(gp + (int64_t)i * ld + j, vec, valid, gv);
+      float gv[4], dv[4], av[4];
+      load_g4<GD>(dp + (int64_t)i * ld + j, vec, valid, dv);
+      if (g.sgd_graft) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (e < valid) ss += dv[e] * dv[e];
+        continue;
+      }
+      if (g.same_src) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gv[e] = dv[e];
+      } else {
+        load_g4<GS>(gp + (int64_t)i * ld + j, vec, valid, gv);
+      }
       load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         av[e] += gv[e] * gv[e];
-        const float pg = gv[e] / (sqrtf(av[e]) + g.graft_eps);
+        const float pg = dv[e] / (sqrtf(av[e]) + g.graft_eps);
         if (e < valid) ss += pg * pg;
       }
       store_f4(ap + (int64_t)i * ld + j, vec, valid, av);
@@ -117,19 +137,20 @@ __global__ __launch_bounds__(64) void scale_kernel(const ScaleArgs g) {
   }
 }
 
-template <typename GT>
+// GD: element type of the direction-source gradients (read only in the grafting-only phase).
+template <typename GD>
 __global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
   const int slot = blockIdx.x / g.geom.chunks, chunk = blockIdx.x - slot * g.geom.chunks, tid = threadIdx.x;
   const BlockDesc d = g.desc[slot];
   float *wp = reinterpret_cast<float *>(g.w_table[d.param]) + d.offset;
-  const GT *gp = reinterpret_cast<const GT *>(g.g_table[d.param]) + d.offset;
+  const GD *gp = reinterpret_cast<const GD *>(g.gd_table[d.param]) + d.offset;
   float *ap = g.a_state + d.state_offset;
   float *mp = g.m_state ? g.m_state + d.state_offset : nullptr;
   const int ld = d.ld, n = g.n;
   const float *pp = g.p + (int64_t)slot * g.m * n;
   const bool vec = ((ld & 3) == 0) && ((n & 3) == 0) && ((d.offset & 3) == 0) && ((d.state_offset & 3) == 0) &&
                    ((reinterpret_cast<uintptr_t>(g.w_table[d.param]) & 15) == 0) &&
-                   ((reinterpret_cast<uintptr_t>(g.g_table[d.param]) & 15) == 0);
+                   ((reinterpret_cast<uintptr_t>(g.gd_table[d.param]) & 15) == 0);
   const int lx = g.geom.lanes_x_log2;
   const int tx = tid & ((1 << lx) - 1), ty = tid >> lx, ny = EW_THREADS >> lx;
   const int r0 = chunk * g.geom.rows_per_wg;
@@ -141,20 +162,32 @@ __global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
       float pv[4], wv[4], mv[4];
       if (g.graft_only) {
         float gv[4], av[4];
-        load_g4<GT>(gp + (int64_t)i * ld + j, vec, valid, gv);
-        load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
+        load_g4<GD>(gp + (int64_t)i * ld + j, vec, valid, gv);
+        if (g.sgd_graft) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pv[e] = -gv[e] / (sqrtf(av[e]) + g.graft_eps);
+          for (int e = 0; e < 4; ++e) pv[e] = -gv[e];
+        } else {
+          load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pv[e] = -gv[e] / (sqrtf(av[e]) + g.graft_eps);
+        }
       } else {
         load_f4(pp + (int64_t)i * n + j, vec, valid, pv);
 #pragma unroll
         for (int e = 0; e < 4; ++e) pv[e] *= sc;
       }
       load_f4(wp + (int64_t)i * ld + j, vec, valid, wv);
+      if (g.wd_decoupled != 0.f) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pv[e] -= g.wd_decoupled * wv[e];
+      }
       if (mp) {
         load_f4(mp + (int64_t)i * ld + j, vec, valid, mv);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { mv[e] = g.mu * mv[e] + pv[e]; wv[e] += g.lr * mv[e]; }
+        for (int e = 0; e < 4; ++e) {
+          mv[e] = g.mu * mv[e] + pv[e];
+          wv[e] += g.lr * (g.nesterov ? g.mu * mv[e] + pv[e] : mv[e]);
+        }
         store_f4(mp + (int64_t)i * ld + j, vec, valid, mv);
       } else {
 #pragma unroll
@@ -176,8 +209,10 @@ struct DiagArgs {
   const DiagChunk *chunks;
   void *const *w_table;
   const void *const *g_table;
-  float *a_state, *m_state;
+  float *a_state, *m_state, *gf_state;   // gf_state: filtered gradient (nullptr when beta1 == 0)
   float graft_eps, mu, lr;
+  float beta1, wd_l2, wd_decoupled;
+  int32_t nesterov;
 };
 
 template <typename GT>
@@ -187,13 +222,48 @@ __global__ __launch_bounds__(EW_THREADS) void diag_kernel(const DiagArgs g) {
   const GT *gp = reinterpret_cast<const GT *>(g.g_table[c.param]) + c.start;
   float *a = g.a_state + c.state_offset;
   float *m = g.m_state ? g.m_state + c.state_offset : nullptr;
+  float *gf = g.gf_state ? g.gf_state + c.state_offset : nullptr;
   for (int i = threadIdx.x; i < c.len; i += EW_THREADS) {
-    const float gv = Elem<GT>::load1(gp + i);
+    float wv = w[i];
+    float gv = Elem<GT>::load1(gp + i);
+    if (g.wd_l2 != 0.f) gv += g.wd_l2 * wv;
     const float av = a[i] + gv * gv;
     a[i] = av;
-    float p = -gv / (sqrtf(av) + g.graft_eps);
-    if (m) { p = g.mu * m[i] + p; m[i] = p; }
-    w[i] += g.lr * p;
+    float dv = gv;
+    if (gf) { dv = g.beta1 * gf[i] + (1.f - g.beta1) * gv; gf[i] = dv; }
+    float p = -dv / (sqrtf(av) + g.graft_eps);
+    if (g.wd_decoupled != 0.f) p -= g.wd_decoupled * wv;
+    if (m) {
+      const float mv = g.mu * m[i] + p;
+      m[i] = mv;
+      p = g.nesterov ? g.mu * mv + p : mv;
+    }
+    w[i] = wv + g.lr * p;
+  }
+}
+
+// 2-D parameters, flat chunks: G1 = G + wd W (if g1 != nullptr) and
+// Gf <- beta1 Gf + (1 - beta1) G1 (if gf != nullptr); both in the A / M state layout.
+struct PrepArgs {
+  const DiagChunk *chunks;
+  void *const *w_table;
+  const void *const *g_table;
+  float *g1, *gf;
+  float wd_l2, beta1;
+};
+
+template <typename GT>
+__global__ __launch_bounds__(EW_THREADS) void prep_kernel(const PrepArgs g) {
+  const DiagChunk c = g.chunks[blockIdx.x];
+  const float *w = reinterpret_cast<const float *>(g.w_table[c.param]) + c.start;
+  const GT *gp = reinterpret_cast<const GT *>(g.g_table[c.param]) + c.start;
+  for (int i = threadIdx.x; i < c.len; i += EW_THREADS) {
+    float gv = Elem<GT>::load1(gp + i);
+    if (g.g1) { gv += g.wd_l2 * w[i]; g.g1[c.state_offset + i] = gv; }
+    if (g.gf) {
+      const float f = g.beta1 * g.gf[c.state_offset + i] + (1.f - g.beta1) * gv;
+      g.gf[c.state_offset + i] = f;
+    }
   }
 }
 

@@ -56,7 +56,8 @@ struct Plan {
   std::vector<Bucket> buckets;
   std::vector<std::vector<int32_t>> param_blocks;  // per parameter: indices into blocks (row-major)
   std::vector<int64_t> param_state_offset;         // element offset of each parameter in A / M
-  std::vector<DiagChunk> diag_chunks;
+  std::vector<DiagChunk> diag_chunks;   // 1-D parameters
+  std::vector<DiagChunk> prep_chunks;   // 2-D parameters, flat (used by the l2 / filtering pre-pass)
   int64_t total_elems = 0;
 };
 
@@ -79,6 +80,9 @@ int check_config(const shampoo_config *c) {
   if (!(c->graft_epsilon >= 0.f) || !std::isfinite(c->graft_epsilon)) return SHAMPOO_ERR_HYPER;
   if (!(c->momentum >= 0.f && c->momentum < 1.f)) return SHAMPOO_ERR_HYPER;
   if (c->grad_dtype != SHAMPOO_GRAD_F32 && c->grad_dtype != SHAMPOO_GRAD_BF16) return SHAMPOO_ERR_HYPER;
+  if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return SHAMPOO_ERR_HYPER;
+  if (!(c->weight_decay >= 0.f) || !std::isfinite(c->weight_decay)) return SHAMPOO_ERR_HYPER;
+  if (c->grafting_type != SHAMPOO_GRAFT_ADAGRAD && c->grafting_type != SHAMPOO_GRAFT_SGD) return SHAMPOO_ERR_HYPER;
   return SHAMPOO_OK;
 }
 
@@ -121,6 +125,14 @@ void make_plan(const shampoo_config *c, Plan &p) {
       continue;
     }
     const int64_t cols = c->shape[2 * i + 1];
+    for (int64_t st = 0; st < rows * cols; st += DIAG_CHUNK) {
+      DiagChunk dc;
+      dc.param = i;
+      dc.len = (int32_t)std::min<int64_t>(DIAG_CHUNK, rows * cols - st);
+      dc.start = st;
+      dc.state_offset = off + st;
+      p.prep_chunks.push_back(dc);
+    }
     const int64_t km = (rows + b - 1) / b, kn = (cols + b - 1) / b;
     for (int64_t bi = 0; bi < km; ++bi)
       for (int64_t bj = 0; bj < kn; ++bj) {
@@ -353,7 +365,8 @@ struct shampoo_opt {
   unsigned char *ws = nullptr;
   size_t ws_bytes = 0;
   // workspace offsets
-  size_t off_Gt = 0;
+  size_t off_Gt = 0, off_G1 = 0, off_Gf = 0, off_g1tab = 0, off_gftab = 0, off_prep = 0;
+  bool use_l2 = false, use_b1 = false;
   size_t off_A = 0, off_M = 0, off_T = 0, off_wtab = 0, off_gtab = 0, off_diag = 0, off_count = 0, off_eig = 0;
   std::vector<EigLayout> eig_L, eig_R;   // per bucket
   std::vector<void *> last_w, last_g;    // pointer tables currently on the device
@@ -372,6 +385,13 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   auto take = [&](size_t bytes) { size_t r = off; off += align_up(bytes); return r; };
   const size_t offA = take((size_t)p.total_elems * 4);
   const size_t offM = c->momentum > 0.f ? take((size_t)p.total_elems * 4) : 0;
+  const bool use_l2 = c->weight_decay > 0.f && !c->use_decoupled_weight_decay;
+  const bool use_b1 = c->beta1 > 0.f;
+  const size_t offG1 = use_l2 ? take((size_t)p.total_elems * 4) : 0;
+  const size_t offGf = use_b1 ? take((size_t)p.total_elems * 4) : 0;
+  const size_t offG1tab = take((size_t)c->n_params * sizeof(void *));
+  const size_t offGftab = take((size_t)c->n_params * sizeof(void *));
+  const size_t offPrep = (use_l2 || use_b1) ? take(std::max<size_t>(1, p.prep_chunks.size()) * sizeof(DiagChunk)) : 0;
   size_t t_elems = 0, gt_elems = 0, eig_bytes = 0;
   std::vector<EigLayout> eL, eR;
   for (auto &b : p.buckets) {
@@ -387,7 +407,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     b.off_scale = take(B * 4);
     b.off_norms = take(B * 8);
     t_elems = std::max(t_elems, B * m * n);
-    if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma) gt_elems = std::max(gt_elems, B * m * n);
+    if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) gt_elems = std::max(gt_elems, B * m * n);
     eL.push_back(eig_layout(b.m, b.count));
     eR.push_back(eig_layout(b.n, b.count));
     eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
@@ -400,7 +420,9 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offC = take(64);
   const size_t offE = take(eig_bytes);
   if (o) {
-    o->off_A = offA; o->off_M = offM; o->off_T = offT; o->off_Gt = offGt; o->off_wtab = offW; o->off_gtab = offG;
+    o->off_A = offA; o->off_M = offM; o->off_T = offT; o->off_Gt = offGt;
+    o->off_G1 = offG1; o->off_Gf = offGf; o->off_g1tab = offG1tab; o->off_gftab = offGftab; o->off_prep = offPrep;
+    o->use_l2 = use_l2; o->use_b1 = use_b1; o->off_wtab = offW; o->off_gtab = offG;
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
     o->eig_L = eL; o->eig_R = eR;
   }
@@ -421,7 +443,10 @@ struct StageTimer {
   }
 };
 
-template <typename GT>
+// GT: element type of the caller's gradients.  GS: of the gradients that feed the factors and
+// the grafting state (GT, or float when l2 weight decay materialises G + wd W).  GD: of the
+// gradients that feed the directions (float when filtered or shifted, else GT).
+template <typename GT, typename GS, typename GD>
 int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   const shampoo_config &c = o->cfg;
   Plan &p = o->plan;
@@ -429,8 +454,13 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   float *A = reinterpret_cast<float *>(ws + o->off_A);
   float *M = c.momentum > 0.f ? reinterpret_cast<float *>(ws + o->off_M) : nullptr;
   float *T = reinterpret_cast<float *>(ws + o->off_T);
+  float *G1 = o->use_l2 ? reinterpret_cast<float *>(ws + o->off_G1) : nullptr;
+  float *Gf = o->use_b1 ? reinterpret_cast<float *>(ws + o->off_Gf) : nullptr;
   void *const *wtab = reinterpret_cast<void *const *>(ws + o->off_wtab);
   const void *const *gtab = reinterpret_cast<const void *const *>(ws + o->off_gtab);
+  // gradients feeding factors + grafting state / feeding the directions
+  const void *const *gs_tab = o->use_l2 ? reinterpret_cast<const void *const *>(ws + o->off_g1tab) : gtab;
+  const void *const *gd_tab = o->use_b1 ? reinterpret_cast<const void *const *>(ws + o->off_gftab) : gs_tab;
   unsigned long long *fail_count = reinterpret_cast<unsigned long long *>(ws + o->off_count);
   const bool use_shampoo = step >= c.start_preconditioning_step;
   const bool refresh = use_shampoo && (step % c.precondition_frequency == 0);
@@ -440,18 +470,29 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   // k-slabs between float64 flushes of the factor accumulators (flushing every 4 slabs
   // measured 3x larger errors in the stale-root directions, for a 5 % gain)
   constexpr int FLUSH = 1;
+  const float wd_l2 = o->use_l2 ? c.weight_decay : 0.f;
+  const float wd_dec = (c.weight_decay > 0.f && c.use_decoupled_weight_decay) ? c.weight_decay : 0.f;
+  const int sgd = c.grafting_type == SHAMPOO_GRAFT_SGD ? 1 : 0;
   int rc;
 
+  if ((o->use_l2 || o->use_b1) && !p.prep_chunks.empty()) {
+    StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
+    PrepArgs pa;
+    pa.chunks = reinterpret_cast<const DiagChunk *>(ws + o->off_prep);
+    pa.w_table = wtab; pa.g_table = gtab; pa.g1 = G1; pa.gf = Gf; pa.wd_l2 = wd_l2; pa.beta1 = c.beta1;
+    hipLaunchKernelGGL(prep_kernel<GT>, dim3((unsigned)p.prep_chunks.size()), dim3(EW_THREADS), 0, s, pa);
+    HIP_TRY(hipGetLastError());
+  }
   for (auto &b : p.buckets) {
     const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
-    if (sizeof(GT) == 2 && b.bf16_mfma && o->ptrs_aligned16) {
+    if (sizeof(GS) == 2 && b.bf16_mfma && o->ptrs_aligned16) {
       StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
       uint16_t *Gt = reinterpret_cast<uint16_t *>(ws + o->off_Gt);
       TransposeArgs ta;
-      ta.desc = desc; ta.g_table = gtab; ta.out = Gt; ta.m = b.m; ta.n = b.n;
+      ta.desc = desc; ta.g_table = gs_tab; ta.out = Gt; ta.m = b.m; ta.n = b.n;
       hipLaunchKernelGGL(transpose_bf16_kernel, dim3((b.n + 63) / 64, (b.m + 63) / 64, b.count), dim3(256), 0, s, ta);
       SyrkBf16Args sa{};
-      sa.desc = desc; sa.ptr_table = gtab; sa.alpha = alpha; sa.beta = beta; sa.batch = b.count;
+      sa.desc = desc; sa.ptr_table = gs_tab; sa.alpha = alpha; sa.beta = beta; sa.batch = b.count;
       // L <- beta L + alpha G G^T
       sa.a.from_table = 1;
       sa.c = reinterpret_cast<float *>(ws + b.off_L); sa.c_batch_stride = (int64_t)b.m * b.m; sa.ldc = b.m;
@@ -475,28 +516,29 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
       GemmArgs g{};
       g.a.from_table = 1; g.b.from_table = 1;
-      g.desc = desc; g.ptr_table = gtab;
+      g.desc = desc; g.ptr_table = gs_tab;
       g.alpha = (float)alpha; g.beta = (float)beta; g.alpha_d = alpha; g.beta_d = beta; g.batch = b.count;
       // L <- beta L + alpha G G^T
       g.c = reinterpret_cast<float *>(ws + b.off_L); g.c_batch_stride = (int64_t)b.m * b.m; g.ldc = b.m;
       g.M = b.m; g.N = b.m; g.K = b.n;
       g.tiles_m = g.tiles_n = b.tiles_m; g.tiles = b.tiles_m * (b.tiles_m + 1) / 2;
-      rc = launch_gemm<K_CONTIG, K_CONTIG, GT, GT, EPI_SYRK, false, FLUSH>(g, s);
+      rc = launch_gemm<K_CONTIG, K_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
       if (rc) return rc;
       // R <- beta R + alpha G^T G
       g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.n * b.n; g.ldc = b.n;
       g.M = b.n; g.N = b.n; g.K = b.m;
       g.tiles_m = g.tiles_n = b.tiles_n; g.tiles = b.tiles_n * (b.tiles_n + 1) / 2;
-      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GT, GT, EPI_SYRK, false, FLUSH>(g, s);
+      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
       if (rc) return rc;
     }
     {
       StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
       EwArgs e{};
-      e.desc = desc; e.w_table = wtab; e.g_table = gtab; e.a_state = A; e.m_state = M;
+      e.desc = desc; e.w_table = wtab; e.g_table = gs_tab; e.gd_table = gd_tab; e.a_state = A; e.m_state = M;
       e.sg_partial = reinterpret_cast<float *>(ws + b.off_sgp);
       e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
-      hipLaunchKernelGGL(graft_kernel<GT>, dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
+      e.sgd_graft = sgd; e.same_src = (gs_tab == gd_tab) ? 1 : 0;
+      hipLaunchKernelGGL((graft_kernel<GS, GD>), dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
       HIP_TRY(hipGetLastError());
     }
   }
@@ -524,11 +566,11 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       GemmArgs g{};
       // T = Lbar G   (Lbar symmetric: A(i,k) read as Lbar[k][i], contiguous in i)
       g.a.base = ws + b.off_Linv; g.a.batch_stride = (int64_t)b.m * b.m; g.a.ld = b.m;
-      g.b.from_table = 1; g.desc = desc; g.ptr_table = gtab;
+      g.b.from_table = 1; g.desc = desc; g.ptr_table = gd_tab;
       g.c = T; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
       g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = 1.f; g.beta = 0.f;
       g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.tiles = b.tiles_m * b.tiles_n; g.batch = b.count;
-      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GT, EPI_STORE, false>(g, s);
+      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE, false>(g, s);
       if (rc) return rc;
       // P = T Rbar, with per-tile sums of squares
       GemmArgs h{};
@@ -551,11 +593,12 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         hipLaunchKernelGGL(scale_kernel, dim3(b.count), dim3(64), 0, s, sa);
       }
       EwArgs e{};
-      e.desc = desc; e.w_table = wtab; e.g_table = gtab; e.a_state = A; e.m_state = M;
+      e.desc = desc; e.w_table = wtab; e.g_table = gs_tab; e.gd_table = gd_tab; e.a_state = A; e.m_state = M;
       e.p = P; e.scale = scale;
       e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
+      e.wd_decoupled = wd_dec; e.nesterov = c.use_nesterov ? 1 : 0; e.sgd_graft = sgd;
       e.graft_only = use_shampoo ? 0 : 1;
-      hipLaunchKernelGGL(update_kernel<GT>, dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
+      hipLaunchKernelGGL(update_kernel<GD>, dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
       HIP_TRY(hipGetLastError());
     }
   }
@@ -563,8 +606,9 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     StageTimer t(o, SHAMPOO_STAGE_DIAG, s);
     DiagArgs d;
     d.chunks = reinterpret_cast<const DiagChunk *>(ws + o->off_diag);
-    d.w_table = wtab; d.g_table = gtab; d.a_state = A; d.m_state = M;
+    d.w_table = wtab; d.g_table = gtab; d.a_state = A; d.m_state = M; d.gf_state = Gf;
     d.graft_eps = c.graft_epsilon; d.mu = c.momentum; d.lr = lr;
+    d.beta1 = c.beta1; d.wd_l2 = wd_l2; d.wd_decoupled = wd_dec; d.nesterov = c.use_nesterov ? 1 : 0;
     hipLaunchKernelGGL(diag_kernel<GT>, dim3((unsigned)p.diag_chunks.size()), dim3(EW_THREADS), 0, s, d);
     HIP_TRY(hipGetLastError());
   }
@@ -633,6 +677,24 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
   if (cfg->momentum > 0.f)
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + o->off_M), 0.f, p.total_elems, s))) return fail(rc);
   if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + o->off_count), 0.f, 16, s))) return fail(rc);
+  if (o->use_b1)
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + o->off_Gf), 0.f, p.total_elems, s))) return fail(rc);
+  {
+    // pointer tables of the library-owned gradient buffers (same layout as A / M)
+    std::vector<void *> t1(cfg->n_params), t2(cfg->n_params);
+    for (int i = 0; i < cfg->n_params; ++i) {
+      t1[i] = o->use_l2 ? reinterpret_cast<float *>(o->ws + o->off_G1) + p.param_state_offset[i] : nullptr;
+      t2[i] = o->use_b1 ? reinterpret_cast<float *>(o->ws + o->off_Gf) + p.param_state_offset[i] : nullptr;
+    }
+    if (hipMemcpyAsync(o->ws + o->off_g1tab, t1.data(), t1.size() * sizeof(void *), hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(o->ws + o->off_gftab, t2.data(), t2.size() * sizeof(void *), hipMemcpyHostToDevice, s) != hipSuccess)
+      return fail(SHAMPOO_ERR_HIP);
+    if ((o->use_l2 || o->use_b1) && !p.prep_chunks.empty())
+      if (hipMemcpyAsync(o->ws + o->off_prep, p.prep_chunks.data(), p.prep_chunks.size() * sizeof(DiagChunk),
+                         hipMemcpyHostToDevice, s) != hipSuccess)
+        return fail(SHAMPOO_ERR_HIP);
+    if (hipStreamSynchronize(s) != hipSuccess) return fail(SHAMPOO_ERR_HIP);   // t1, t2 go out of scope
+  }
   std::vector<std::vector<BlockDesc>> descs(p.buckets.size());
   for (size_t i = 0; i < p.buckets.size(); ++i) descs[i].resize(p.buckets[i].count);
   for (const Block &b : p.blocks) {
@@ -694,8 +756,12 @@ int shampoo_step(shampoo_opt *o, void *const *params, const void *const *grads, 
     HIP_TRY(hipMemcpyAsync(o->ws + o->off_gtab, o->last_g.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
   }
   o->last_step = step;
-  if (o->cfg.grad_dtype == SHAMPOO_GRAD_BF16) return step_impl<uint16_t>(o, lr, step, s);
-  return step_impl<float>(o, lr, step, s);
+  if (o->cfg.grad_dtype == SHAMPOO_GRAD_BF16) {
+    if (o->use_l2) return step_impl<uint16_t, float, float>(o, lr, step, s);
+    if (o->use_b1) return step_impl<uint16_t, uint16_t, float>(o, lr, step, s);
+    return step_impl<uint16_t, uint16_t, uint16_t>(o, lr, step, s);
+  }
+  return step_impl<float, float, float>(o, lr, step, s);
 }
 
 int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, void *dst, size_t bytes,
@@ -707,12 +773,13 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
   Plan &p = o->plan;
   unsigned char *ws = o->ws;
   if (o->ndim[param] == 1) {
-    if (block != 0 || (which != SHAMPOO_GET_A && which != SHAMPOO_GET_M)) return SHAMPOO_ERR_SHAPE;
+    if (block != 0 || (which != SHAMPOO_GET_A && which != SHAMPOO_GET_M && which != SHAMPOO_GET_GF)) return SHAMPOO_ERR_SHAPE;
     if (which == SHAMPOO_GET_M && !(o->cfg.momentum > 0.f)) return SHAMPOO_ERR_SHAPE;
+    if (which == SHAMPOO_GET_GF && !o->use_b1) return SHAMPOO_ERR_SHAPE;
     const size_t len = (size_t)o->shape[2 * param];
     if (bytes != len * 4) return SHAMPOO_ERR_SHAPE;
-    const float *src = reinterpret_cast<const float *>(ws + (which == SHAMPOO_GET_A ? o->off_A : o->off_M)) +
-                       p.param_state_offset[param];
+    const size_t off_state = which == SHAMPOO_GET_A ? o->off_A : (which == SHAMPOO_GET_M ? o->off_M : o->off_Gf);
+    const float *src = reinterpret_cast<const float *>(ws + off_state) + p.param_state_offset[param];
     HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
     return SHAMPOO_OK;
   }
@@ -730,11 +797,14 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
     case SHAMPOO_GET_PSH: src = ws + bk.off_P + (size_t)b.slot * m * n * 4; need = m * n * 4; break;
     case SHAMPOO_GET_NORMS: src = ws + bk.off_norms + (size_t)b.slot * 8; need = 8; break;
     case SHAMPOO_GET_A:
-    case SHAMPOO_GET_M: {
+    case SHAMPOO_GET_M:
+    case SHAMPOO_GET_GF: {
       if (which == SHAMPOO_GET_M && !(o->cfg.momentum > 0.f)) return SHAMPOO_ERR_SHAPE;
+      if (which == SHAMPOO_GET_GF && !o->use_b1) return SHAMPOO_ERR_SHAPE;
       if (bytes != m * n * 4) return SHAMPOO_ERR_SHAPE;
       const int64_t ld = o->shape[2 * param + 1];
-      const float *base = reinterpret_cast<const float *>(ws + (which == SHAMPOO_GET_A ? o->off_A : o->off_M)) +
+      const size_t off_state = which == SHAMPOO_GET_A ? o->off_A : (which == SHAMPOO_GET_M ? o->off_M : o->off_Gf);
+      const float *base = reinterpret_cast<const float *>(ws + off_state) +
                           p.param_state_offset[param] + b.row0 * ld + b.col0;
       HIP_TRY(hipMemcpy2DAsync(dst, n * 4, base, (size_t)ld * 4, n * 4, m, hipMemcpyDeviceToDevice, s));
       return SHAMPOO_OK;

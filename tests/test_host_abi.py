@@ -91,6 +91,7 @@ def test_workspace_holds_the_state_of_the_memory_rule():
     (dict(root_exponent=0.0), -3), (dict(precondition_frequency=0), -3),
     (dict(start_preconditioning_step=-1), -3), (dict(graft_epsilon=-1.0), -3),
     (dict(momentum=1.0), -3), (dict(momentum=-0.1), -3), (dict(grad_dtype=7), -3),
+    (dict(beta1=1.0), -3), (dict(beta1=-0.5), -3), (dict(weight_decay=-1.0), -3), (dict(grafting_type=5), -3),
 ])
 def test_bad_hyperparameters_are_rejected(kw, code):
     cfg = cfg_for([(8, 8)], 4, **kw)
