@@ -10,9 +10,9 @@ Everything is numpy float64.  Inputs given as float32 (or bf16 bits decoded
 to float32 by the caller) are widened exactly.  No blocking, fusion or
 reordering beyond what the paper's algorithm states.
 
-What is computed (paper: "Complete Distributed Shampoo Pseudocode" without bias
-correction; identical to "Shampoo Pseudocode (with AdaGrad Grafting)" when
-beta2 = 1, beta1 = 0, no weight decay, no momentum):
+What is computed (paper: "Complete Distributed Shampoo Pseudocode"; identical to
+"Shampoo Pseudocode (with AdaGrad Grafting)" when beta2 = 1, beta1 = 0, no
+weight decay, no momentum):
 
   for every block (m x n) of every 2-D parameter, at iteration t (0-based):
     0. if weight_decay > 0 and not decoupled: G <- G + weight_decay * W   [Sec. 3.1.2]
@@ -21,8 +21,10 @@ beta2 = 1, beta1 = 0, no weight decay, no momentum):
     2. AdaGrad grafting: A <- A + G*G elementwise (SGD grafting has no state)  [Sec. 2.4]
     3. if t >= start and t % f == 0:
          Lbar <- rootinv(L), Rbar <- rootinv(R)                [Sec. 3.2.1 framed box]
+         (with bias correction and beta2 < 1: of L / (1 - beta2^(t+1)), likewise R)
     4. if beta1 > 0: Gf <- beta1 Gf + (1-beta1) G (Gf = 0 initially), else Gf = G.
-       The grafting state above uses G, every direction below uses Gf.   [Sec. 3.1.1]
+       The grafting state above uses G, every direction below uses Gf
+       (with bias correction and beta1 > 0: Gf / (1 - beta1^(t+1)))      [Sec. 3.1.1]
     5. P_graft = Gf / (sqrt(A) + eps_graft)  (AdaGrad)  or  Gf  (SGD)    [Sec. 2.4]
     6. if t >= start: P = -||P_graft||_F * Lbar Gf Rbar / ||Lbar Gf Rbar||_F
        else:          P = -P_graft                             [Sec. 2.4 grafting eq.]
@@ -38,7 +40,10 @@ Readings of the paper taken here (each also listed in the design notes):
   * The EMA weight in the factor update is beta2 (the complete pseudocode
     prints beta1 there while guarding on beta2 < 1; the text equations use
     beta2).
-  * No bias correction.
+  * Bias correction is optional and off by default (the workloads do not list it).
+    When on, the corrected factor is what the root routine receives, so epsilon is
+    added after the division; the stored factors and the filtered gradient stay
+    uncorrected, as in Adam.
   * Grafting norms are taken per block (each block owns its grafting object,
     App. E class structure).
   * The grafting branch before start_preconditioning_step uses P = -P_graft
@@ -54,7 +59,7 @@ Pins: see tests/test_oracle_pins.py (Kronecker brute force, X^4 (L+eps I) = I,
 diagonal closed forms, polar factor at t = 0, textbook AdaGrad, geometric
 momentum and Nesterov sums, trace identities, independent Jacobi eigensolver,
 geometric weight decay, l2 as a shifted gradient, constant-gradient filtering,
-SGD-graft step length).
+SGD-graft step length, bias correction under a constant gradient).
 """
 import numpy as np
 
@@ -146,7 +151,8 @@ class ShampooOracle:
     def __init__(self, shapes, block_size, beta2, epsilon, root_exponent,
                  precondition_frequency, start_preconditioning_step=0,
                  graft_epsilon=1e-10, momentum=0.0, beta1=0.0, weight_decay=0.0,
-                 use_decoupled_weight_decay=True, use_nesterov=False, grafting="adagrad"):
+                 use_decoupled_weight_decay=True, use_nesterov=False, grafting="adagrad",
+                 use_bias_correction=False):
         self.shapes = [tuple(int(x) for x in s) for s in shapes]
         self.b = int(block_size)
         self.beta2 = float(beta2)
@@ -160,6 +166,7 @@ class ShampooOracle:
         self.wd = float(weight_decay)
         self.decoupled = bool(use_decoupled_weight_decay)
         self.nesterov = bool(use_nesterov)
+        self.bias_correction = bool(use_bias_correction)
         if grafting not in ("adagrad", "sgd"):
             raise ValueError("grafting must be 'adagrad' or 'sgd'")
         self.grafting = grafting
@@ -204,6 +211,12 @@ class ShampooOracle:
         """One iteration t.  params: list of float64 arrays, updated in place.
         grads: list of arrays (any float dtype; widened exactly)."""
         refresh = (t >= self.start) and (t % self.f == 0)
+        # Sec. 3.1.1 bias correction: G^ = Gf / (1 - beta1^(t+1)), L^ = L / (1 - beta2^(t+1))
+        c1 = c2 = 1.0
+        if self.bias_correction and self.beta1 > 0.0:
+            c1 = 1.0 / (1.0 - self.beta1 ** (t + 1))
+        if self.bias_correction and self.beta2 < 1.0:
+            c2 = 1.0 / (1.0 - self.beta2 ** (t + 1))
         for i, s in enumerate(self.shapes):
             G = np.asarray(grads[i], dtype=np.float64)
             W = params[i]
@@ -211,7 +224,7 @@ class ShampooOracle:
                 G = G + self.wd * W
             if self.beta1 > 0.0:
                 self.Gf[i] = self.beta1 * self.Gf[i] + (1.0 - self.beta1) * G
-                Gf = self.Gf[i]
+                Gf = c1 * self.Gf[i]
             else:
                 Gf = G
             if len(s) == 1:
@@ -227,8 +240,8 @@ class ShampooOracle:
                 if self.grafting == "adagrad":
                     self.A[i][sl] = graft_state_update(self.A[i][sl], Gb)
                 if refresh:
-                    self.Lbar[i][k], _ = root_inverse(self.L[i][k], self.epsilon, self.r)
-                    self.Rbar[i][k], _ = root_inverse(self.R[i][k], self.epsilon, self.r)
+                    self.Lbar[i][k], _ = root_inverse(c2 * self.L[i][k], self.epsilon, self.r)
+                    self.Rbar[i][k], _ = root_inverse(c2 * self.R[i][k], self.epsilon, self.r)
                 if self.grafting == "adagrad":
                     Pg = graft_direction(Gfb, self.A[i][sl], self.eps_g)
                 else:

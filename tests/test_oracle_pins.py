@@ -511,3 +511,52 @@ def test_sgd_grafting_step_length_and_polar_first_step():
     opt.step(W, [G2], lr, 1)
     assert np.isclose(np.linalg.norm(W[0] - before), lr * np.linalg.norm(G2), rtol=1e-10)
     assert np.array_equal(opt.A[0], np.zeros((m, n)))     # no grafting state
+
+
+def test_bias_correction_undoes_filtering_of_a_constant_gradient():
+    """Sec. 3.1.1: Gf / (1 - beta1^(t+1)) of a constant gradient is that gradient, so the
+    closed form of the filtering pin loses its (1 - beta1^(t+1)) weights."""
+    m, n, b1, lr = 5, 4, 0.8, 0.1
+    G = rng(28).standard_normal((m, n))
+    U, S, Vt = np.linalg.svd(G, full_matrices=False)
+    opt = make_opt([(m, n)], epsilon=1e-14, graft_epsilon=0.0, beta1=b1, use_bias_correction=True)
+    W = [np.zeros((m, n))]
+    coeff = 0.0
+    for t in range(5):
+        opt.step(W, [G], lr, t)
+        coeff += 1.0 / np.sqrt(t + 1)
+        assert np.allclose(W[0], -lr * np.sqrt(max(m, n)) * coeff * (U @ Vt), rtol=1e-6, atol=1e-9)
+
+
+@pytest.mark.parametrize("bc", [False, True])
+def test_bias_correction_of_the_factors_diagonal_closed_form(bc):
+    """Constant diagonal G = diag(d), beta2 < 1: L_t = (1 - beta2^(t+1)) diag(d^2).  With bias
+    correction the root routine sees diag(d^2) at every t, and epsilon (large here, so that the
+    order matters) is added after the division."""
+    d = np.array([0.5, 1.0, 2.0, 3.0])
+    b2, eps = 0.9, 0.5
+    opt = make_opt([(4, 4)], beta2=b2, epsilon=eps, use_bias_correction=bc)
+    W = [np.zeros((4, 4))]
+    for t in range(4):
+        opt.step(W, [np.diag(d)], 0.1, t)
+        scale = 1.0 if bc else 1.0 - b2 ** (t + 1)
+        expect = np.diag((scale * d * d + eps) ** -0.25)
+        assert np.allclose(opt.Lbar[0][0], expect, rtol=1e-12, atol=1e-14)
+        assert np.allclose(opt.Rbar[0][0], expect, rtol=1e-12, atol=1e-14)
+        assert np.allclose(np.diag(opt.L[0][0]), (1.0 - b2 ** (t + 1)) * d * d, rtol=1e-12)   # stored uncorrected
+
+
+def test_bias_correction_one_d_textbook():
+    n, b1, lr, eg = 9, 0.9, 0.01, 1e-10
+    r = rng(29)
+    opt = make_opt([(n,)], beta1=b1, graft_epsilon=eg, use_bias_correction=True)
+    W = [np.zeros(n)]
+    w = np.zeros(n); a = np.zeros(n); gf = np.zeros(n)
+    for t in range(6):
+        g = r.standard_normal(n)
+        opt.step(W, [g], lr, t)
+        for i in range(n):
+            a[i] += g[i] * g[i]
+            gf[i] = b1 * gf[i] + (1 - b1) * g[i]
+            w[i] -= lr * (gf[i] / (1 - b1 ** (t + 1))) / (np.sqrt(a[i]) + eg)
+        assert np.allclose(W[0], w, rtol=1e-13, atol=1e-16)
