@@ -73,6 +73,9 @@ typedef struct {
   int32_t use_nesterov;   /* != 0: W += lr (mu M + P) instead of lr M (Sec. 3.1.3)            */
   int32_t grafting_type;  /* SHAMPOO_GRAFT_ADAGRAD or SHAMPOO_GRAFT_SGD (P_graft = G) for the
                              blocks; 1-D parameters always use diagonal AdaGrad              */
+  int32_t use_bias_correction; /* != 0: directions use Gf / (1 - beta1^(step+1)) and roots are
+                             taken of L / (1 - beta2^(step+1)) (beta2 < 1), epsilon added after
+                             the division; stored state stays uncorrected (Sec. 3.1.1)        */
   int32_t grad_dtype;     /* SHAMPOO_GRAD_F32 or SHAMPOO_GRAD_BF16; parameters are float32   */
   int32_t device;         /* HIP device ordinal                                              */
 } shampoo_config;
@@ -111,6 +114,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
  *   A <- A + G.^2   (AdaGrad grafting)                   (Sec. 2.4)
  *   if step >= start and step % f == 0: roots refreshed  (Sec. 3.2.1 box, 4.3)
  *   Gf <- beta1 Gf + (1-beta1) G  (Gf = G when beta1 = 0) (Sec. 3.1.1)
+ *       (with bias correction the lines below read Gf / (1 - beta1^(step+1)))
  *   P_graft = Gf/(sqrt(A)+eps_g)  or  Gf (SGD grafting)
  *   P = -||P_graft||_F * Lbar Gf Rbar / ||Lbar Gf Rbar||_F           (Sec. 2.4)
  *       (P = -P_graft while step < start; 1-D parameters: -Gf/(sqrt(A)+eps_g))

@@ -44,6 +44,7 @@ class ShampooConfig(ctypes.Structure):
         ("use_decoupled_weight_decay", ctypes.c_int32),
         ("use_nesterov", ctypes.c_int32),
         ("grafting_type", ctypes.c_int32),
+        ("use_bias_correction", ctypes.c_int32),
         ("grad_dtype", ctypes.c_int32),
         ("device", ctypes.c_int32),
     ]
@@ -104,7 +105,8 @@ def _check(code):
 def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_frequency,
                 start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
                 grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
-                use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD):
+                use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
+                use_bias_correction=False):
     """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
     n = len(shapes)
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
@@ -115,7 +117,8 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
     cfg = ShampooConfig(n, ndim, shape, block_size, beta2, epsilon, root_exponent,
                         precondition_frequency, start_preconditioning_step, graft_epsilon,
                         momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
-                        1 if use_nesterov else 0, grafting_type, grad_dtype, device)
+                        1 if use_nesterov else 0, grafting_type, 1 if use_bias_correction else 0,
+                        grad_dtype, device)
     cfg._keep = (ndim, shape)
     return cfg
 
@@ -147,13 +150,15 @@ class Shampoo:
     def __init__(self, shapes, block_size, beta2, epsilon, root_exponent, precondition_frequency,
                  start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
                  grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
-                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD):
+                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
+                use_bias_correction=False):
         import torch
         self.shapes = [tuple(s) for s in shapes]
         self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
                                precondition_frequency, start_preconditioning_step, graft_epsilon,
                                momentum, grad_dtype, device, beta1, weight_decay,
-                               use_decoupled_weight_decay, use_nesterov, grafting_type)
+                               use_decoupled_weight_decay, use_nesterov, grafting_type,
+                               use_bias_correction)
         self.device = torch.device("cuda", device)
         nbytes = shampoo_workspace_bytes(self.cfg)
         if nbytes == 0:

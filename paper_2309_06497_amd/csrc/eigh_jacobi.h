@@ -220,6 +220,7 @@ struct SmallRootArgs {
   unsigned long long *fail_count;  // optional global counter
   int32_t n;
   float epsilon, r;
+  float scale;           // the root is taken of scale * A (bias correction, Sec. 3.1.1); 1 = off
 };
 
 __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallRootArgs g) {
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
 
   // lambda_min over the true eigenvalues, then f = (lambda - min(lambda_min, 0) + eps)^-r
   double lmin = 1.0e300;
-  for (int i = tid; i < n; i += JAC_THREADS) lmin = fmin(lmin, At[i * (i + 1) / 2 + i]);
+  for (int i = tid; i < n; i += JAC_THREADS) lmin = fmin(lmin, (double)g.scale * At[i * (i + 1) / 2 + i]);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   __syncthreads();
@@ -290,7 +291,7 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
   for (int i = tid; i < s; i += JAC_THREADS) {
     float f = 0.f;
     if (i < n) {
-      const double lam = At[i * (i + 1) / 2 + i];
+      const double lam = (double)g.scale * At[i * (i + 1) / 2 + i];
       f = (float)pow(lam - shift + (double)g.epsilon, -(double)g.r);
       if (!(f <= 3.0e38f) || !(f >= 0.f)) badf = 1;
       if (g.lambda) g.lambda[(int64_t)b * n + i] = (float)lam;
@@ -654,6 +655,7 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const 
 struct BlockFinalArgs {
   const double *w; const float *qt; int32_t np; int32_t n;
   float epsilon, r;
+  float scale;           // the root is taken of scale * A; 1 = off
   float *fvals;          // [batch][np]: lambda'^-r / ||q||^2 (0 on padding)
   float *lambda;         // optional [batch][n]
   int32_t *failed;       // [batch] in/out
@@ -691,7 +693,7 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
   __syncthreads();
   double lmin = 1.0e300;
   if (!bad)
-    for (int i = tid; i < n; i += 256) lmin = fmin(lmin, w[(int64_t)i * np + i] / (double)fv[i]);
+    for (int i = tid; i < n; i += 256) lmin = fmin(lmin, (double)g.scale * w[(int64_t)i * np + i] / (double)fv[i]);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   if (lane == 0) redf[wave] = lmin;
@@ -703,7 +705,7 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
     float f = 0.f;
     if (i < n && !bad) {
       const double nrm2 = (double)fv[i];
-      const double lam = w[(int64_t)i * np + i] / nrm2;
+      const double lam = (double)g.scale * w[(int64_t)i * np + i] / nrm2;
       f = (float)(pow(lam - shift + (double)g.epsilon, -(double)g.r) / nrm2);
       if (!(f <= 3.0e38f) || !(f >= 0.f)) badf = 1;
       if (g.lambda) g.lambda[(int64_t)b * n + i] = (float)lam;

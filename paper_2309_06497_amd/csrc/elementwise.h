@@ -35,6 +35,7 @@ struct EwArgs {
   int32_t m, n;
   EwGeom geom;
   float graft_eps, mu, lr;
+  float gd_scale;                // direction gradients are multiplied by this (bias correction, 1 = off)
   float wd_decoupled;            // update_kernel: P <- P - wd_decoupled * W (0 = off)
   int32_t nesterov;              // update_kernel: step with mu M + P instead of M
   int32_t sgd_graft;             // P_graft = G (no grafting state) instead of AdaGrad
@@ -83,17 +84,18 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
       const int valid = min(4, n - j);
       float gv[4], dv[4], av[4];
       load_g4<GD>(dp + (int64_t)i * ld + j, vec, valid, dv);
+      if (g.same_src) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gv[e] = dv[e];
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dv[e] *= g.gd_scale;
       if (g.sgd_graft) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) if (e < valid) ss += dv[e] * dv[e];
         continue;
       }
-      if (g.same_src) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) gv[e] = dv[e];
-      } else {
-        load_g4<GS>(gp + (int64_t)i * ld + j, vec, valid, gv);
-      }
+      if (!g.same_src) load_g4<GS>(gp + (int64_t)i * ld + j, vec, valid, gv);
       load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -163,6 +165,8 @@ __global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
       if (g.graft_only) {
         float gv[4], av[4];
         load_g4<GD>(gp + (int64_t)i * ld + j, vec, valid, gv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gv[e] *= g.gd_scale;
         if (g.sgd_graft) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) pv[e] = -gv[e];
@@ -212,6 +216,7 @@ struct DiagArgs {
   float *a_state, *m_state, *gf_state;   // gf_state: filtered gradient (nullptr when beta1 == 0)
   float graft_eps, mu, lr;
   float beta1, wd_l2, wd_decoupled;
+  float gd_scale;        // bias correction of the filtered gradient (1 = off)
   int32_t nesterov;
 };
 
@@ -231,7 +236,7 @@ __global__ __launch_bounds__(EW_THREADS) void diag_kernel(const DiagArgs g) {
     a[i] = av;
     float dv = gv;
     if (gf) { dv = g.beta1 * gf[i] + (1.f - g.beta1) * gv; gf[i] = dv; }
-    float p = -dv / (sqrtf(av) + g.graft_eps);
+    float p = -(g.gd_scale * dv) / (sqrtf(av) + g.graft_eps);
     if (g.wd_decoupled != 0.f) p -= g.wd_decoupled * wv;
     if (m) {
       const float mv = g.mu * m[i] + p;

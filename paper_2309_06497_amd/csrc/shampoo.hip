@@ -248,7 +248,7 @@ AuxStreams *aux_streams() {
 }
 
 // Block-Jacobi root inverse of `cnt` matrices, using workspace slots [slot0, slot0 + cnt).
-int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float *x, float *lambda,
+int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float scale, float *x, float *lambda,
                        int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
                        const EigLayout &e, int slot0, hipStream_t s) {
   const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
@@ -284,7 +284,7 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
     }
   HIP_TRY(hipGetLastError());
   BlockFinalArgs fa;
-  fa.w = w; fa.qt = qt; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.fvals = fv;
+  fa.w = w; fa.qt = qt; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.scale = scale; fa.fvals = fv;
   fa.lambda = lambda;
   fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
   hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);
@@ -301,8 +301,8 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   return launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_SYRK, true>(g, s);
 }
 
-// X_i = rootinv(A_i) for a batch of dense n x n matrices.  ws: eig_layout(n, >= chunk) region.
-int root_inverse_batched(const float *a, int n, int batch, float eps, float r, float *x, float *lambda,
+// X_i = rootinv(scale * A_i) for a batch of dense n x n matrices.  ws: eig_layout(n, >= chunk) region.
+int root_inverse_batched(const float *a, int n, int batch, float eps, float r, float scale, float *x, float *lambda,
                          int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
                          const EigLayout &e, hipStream_t s) {
   if (batch <= 0) return SHAMPOO_OK;
@@ -311,7 +311,7 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
     g.a = a; g.a_stride = (int64_t)n * n;
     g.x = x; g.x_stride = (int64_t)n * n;
     g.lambda = lambda; g.failed = failed_user; g.fail_count = fail_count;
-    g.n = n; g.epsilon = eps; g.r = r;
+    g.n = n; g.epsilon = eps; g.r = r; g.scale = scale;
     const size_t lds = rootinv_small_lds_bytes(n);
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rootinv_small_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -336,7 +336,7 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
     for (int k = 0; k < subs; ++k) {
       const int cnt = cb / subs + (k < cb % subs ? 1 : 0);
       hipStream_t sk = k == 0 ? s : aux->stream[k - 1];
-      const int rc = block_jacobi_solve(a + (int64_t)(b0 + first) * n * n, n, cnt, eps, r,
+      const int rc = block_jacobi_solve(a + (int64_t)(b0 + first) * n * n, n, cnt, eps, r, scale,
                                         x + (int64_t)(b0 + first) * n * n,
                                         lambda ? lambda + (int64_t)(b0 + first) * n : nullptr,
                                         failed_user ? failed_user + b0 + first : nullptr, fail_count, ws, e, first, sk);
@@ -473,6 +473,11 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   const float wd_l2 = o->use_l2 ? c.weight_decay : 0.f;
   const float wd_dec = (c.weight_decay > 0.f && c.use_decoupled_weight_decay) ? c.weight_decay : 0.f;
   const int sgd = c.grafting_type == SHAMPOO_GRAFT_SGD ? 1 : 0;
+  // bias correction (Sec. 3.1.1): directions use Gf / (1 - beta1^(t+1)), roots are taken of
+  // L / (1 - beta2^(t+1)); the stored state stays uncorrected
+  const bool bc = c.use_bias_correction != 0;
+  const float c1 = (bc && c.beta1 > 0.f) ? (float)(1.0 / (1.0 - std::pow((double)c.beta1, (double)(step + 1)))) : 1.f;
+  const float c2 = (bc && c.beta2 < 1.f) ? (float)(1.0 / (1.0 - std::pow((double)c.beta2, (double)(step + 1)))) : 1.f;
   int rc;
 
   if ((o->use_l2 || o->use_b1) && !p.prep_chunks.empty()) {
@@ -537,7 +542,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       e.desc = desc; e.w_table = wtab; e.g_table = gs_tab; e.gd_table = gd_tab; e.a_state = A; e.m_state = M;
       e.sg_partial = reinterpret_cast<float *>(ws + b.off_sgp);
       e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
-      e.sgd_graft = sgd; e.same_src = (gs_tab == gd_tab) ? 1 : 0;
+      e.sgd_graft = sgd; e.same_src = (gs_tab == gd_tab) ? 1 : 0; e.gd_scale = c1;
       hipLaunchKernelGGL((graft_kernel<GS, GD>), dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
       HIP_TRY(hipGetLastError());
     }
@@ -546,11 +551,11 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     StageTimer t(o, SHAMPOO_STAGE_ROOT, s);
     for (size_t i = 0; i < p.buckets.size(); ++i) {
       auto &b = p.buckets[i];
-      rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, c.root_exponent,
+      rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
                                 ws + o->off_eig, o->eig_L[i], s);
       if (rc) return rc;
-      rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, c.root_exponent,
+      rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Rinv), nullptr, nullptr, fail_count,
                                 ws + o->off_eig, o->eig_R[i], s);
       if (rc) return rc;
@@ -568,7 +573,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       g.a.base = ws + b.off_Linv; g.a.batch_stride = (int64_t)b.m * b.m; g.a.ld = b.m;
       g.b.from_table = 1; g.desc = desc; g.ptr_table = gd_tab;
       g.c = T; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
-      g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = 1.f; g.beta = 0.f;
+      g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1; g.beta = 0.f;
       g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.tiles = b.tiles_m * b.tiles_n; g.batch = b.count;
       rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE, false>(g, s);
       if (rc) return rc;
@@ -596,7 +601,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       e.desc = desc; e.w_table = wtab; e.g_table = gs_tab; e.gd_table = gd_tab; e.a_state = A; e.m_state = M;
       e.p = P; e.scale = scale;
       e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
-      e.wd_decoupled = wd_dec; e.nesterov = c.use_nesterov ? 1 : 0; e.sgd_graft = sgd;
+      e.wd_decoupled = wd_dec; e.nesterov = c.use_nesterov ? 1 : 0; e.sgd_graft = sgd; e.gd_scale = c1;
       e.graft_only = use_shampoo ? 0 : 1;
       hipLaunchKernelGGL(update_kernel<GD>, dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
       HIP_TRY(hipGetLastError());
@@ -609,6 +614,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     d.w_table = wtab; d.g_table = gtab; d.a_state = A; d.m_state = M; d.gf_state = Gf;
     d.graft_eps = c.graft_epsilon; d.mu = c.momentum; d.lr = lr;
     d.beta1 = c.beta1; d.wd_l2 = wd_l2; d.wd_decoupled = wd_dec; d.nesterov = c.use_nesterov ? 1 : 0;
+    d.gd_scale = c1;
     hipLaunchKernelGGL(diag_kernel<GT>, dim3((unsigned)p.diag_chunks.size()), dim3(EW_THREADS), 0, s, d);
     HIP_TRY(hipGetLastError());
   }
@@ -881,7 +887,7 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
     const int rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, batch, s);
     if (rc) return rc;
   }
-  return root_inverse_batched(a, n, batch, epsilon, r, x, lambda, failed, nullptr,
+  return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
                               static_cast<unsigned char *>(workspace), e, s);
 }
 

@@ -76,15 +76,17 @@ class Pair:
     THETA = 1e-7
 
     def __init__(self, shapes, b, beta2, f, start=0, mu=0.9, eps=1e-12, eps_g=1e-10, bf16=False, seed=0,
-                 beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad"):
+                 beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad",
+                 bias_correction=False):
         self.shapes = shapes
         self.bf16 = bf16
         self.f, self.start, self.eps = f, start, f32(eps)
         self.gpu = B.Shampoo(shapes, b, beta2, eps, 0.25, f, start, eps_g, mu,
                              B.GRAD_BF16 if bf16 else B.GRAD_F32, 0, beta1, weight_decay, decoupled, nesterov,
-                             B.GRAFT_SGD if grafting == "sgd" else B.GRAFT_ADAGRAD)
+                             B.GRAFT_SGD if grafting == "sgd" else B.GRAFT_ADAGRAD, bias_correction)
         self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, start, f32(eps_g), f32(mu),
-                                    f32(beta1), f32(weight_decay), decoupled, nesterov, grafting)
+                                    f32(beta1), f32(weight_decay), decoupled, nesterov, grafting,
+                                    bias_correction)
         w0 = wl.init_params(shapes, seed)
         self.w0 = [w.astype(np.float64) for w in w0]
         self.w_ora = [w.astype(np.float64) for w in w0]
@@ -164,10 +166,17 @@ class Pair:
                     Ri = self.gpu.get(i, k, B.GET_RINV).cpu().numpy()
                     assert np.array_equal(Li, Li.T) and np.array_equal(Ri, Ri.T)
                     if refresh:
-                        worst["root"] = max(worst["root"], rel(Li, so.root_inverse(L, self.eps, 0.25)[0]),
-                                            rel(Ri, so.root_inverse(R, self.eps, 0.25)[0]))
+                        c2 = 1.0
+                        if self.ora.bias_correction and self.ora.beta2 < 1.0:
+                            c2 = 1.0 / (1.0 - self.ora.beta2 ** (t + 1))
+                        worst["root"] = max(worst["root"],
+                                            rel(Li, so.root_inverse(c2 * L.astype(np.float64), self.eps, 0.25)[0]),
+                                            rel(Ri, so.root_inverse(c2 * R.astype(np.float64), self.eps, 0.25)[0]))
                     P = self.gpu.get(i, k, B.GET_PSH).cpu().numpy()
-                    g_dir = self.ora.Gf[i][sl] if self.ora.beta1 > 0 else (
+                    c1 = 1.0
+                    if self.ora.bias_correction and self.ora.beta1 > 0:
+                        c1 = 1.0 / (1.0 - self.ora.beta1 ** (t + 1))
+                    g_dir = c1 * self.ora.Gf[i][sl] if self.ora.beta1 > 0 else (
                         self.g_last[i][sl] + (self.ora.wd * self.w_prev[i][sl]
                                               if self.ora.wd > 0 and not self.ora.decoupled else 0.0))
                     worst["gemm"] = max(worst["gemm"], rel(P, so.shampoo_direction(
@@ -395,3 +404,12 @@ def test_sgd_grafting_and_warmup():
     for t in range(5):
         p.step(wl.gaussian_grads(shapes, 35, t, 1e-2), 0.01, t)
         p.check(t, use_shampoo=(t >= 2))
+
+
+def test_bias_correction_of_gradient_and_factors():
+    say("case bias correction")
+    shapes = [(96, 80), (33,), (64, 64)]
+    p = Pair(shapes, 64, 0.99, 2, beta1=0.9, bias_correction=True, eps=1e-6)
+    for t in range(5):
+        p.step(wl.gaussian_grads(shapes, 36, t, 1e-2), 0.01, t)
+        p.check(t)
