@@ -17,9 +17,12 @@ the root-inverse refresh; it runs in the warm-up and its time is reported separa
 
 One JSON line is printed:
   metric/value        milliseconds per (non-refresh) step, whole job, one GPU
-  roofline            the dominant kernel (the float32-MFMA GEMM of the two-sided
-                      preconditioning): algorithmic flops per launch / average launch
-                      duration from HIP events recorded by the library on the step's stream
+  roofline            the dominant kernel: for blocks above 128 the float32-MFMA GEMM of the
+                      two-sided preconditioning (algorithmic flops per launch / average launch
+                      duration); for workloads whose blocks are at most 128 x 128 the
+                      single-workgroup block-step kernel, which is bound by HBM (algorithmic
+                      bytes per launch / average launch duration).  Durations come from HIP
+                      events recorded by the library on the step's stream
   cpu_baseline        the fp64 numpy oracle timed on the host on a sample of blocks
 """
 import argparse
@@ -70,6 +73,17 @@ def flop_counts(table):
         exe_factor += 2.0 * TILE * TILE * (tm * (tm + 1) / 2 * n + tn * (tn + 1) / 2 * m)
         exe_precond += 2.0 * TILE * TILE * tm * tn * (m + n)
     return alg_factor, alg_precond, exe_factor, exe_precond
+
+
+def fused_bytes(table, gsz):
+    """Algorithmic HBM bytes per step of the blocks that take the single-workgroup kernel
+    (m, n <= 128): G once, L and R read + written, Lbar and Rbar read, A, M, W read + written."""
+    total = 0.0
+    for row in table:
+        m, n = float(row[3]), float(row[4])
+        if m <= 128 and n <= 128:
+            total += (gsz + 24.0) * m * n + 12.0 * (m * m + n * n)
+    return total
 
 
 def cpu_baseline(wk, table, rng_seed=0):
@@ -194,6 +208,20 @@ def main():
     achieved = gemm_flops_per_launch / (launch_ms * 1e-3) / 1e12 if launch_ms > 0 else 0.0
     gsz = 2 if wk["bf16"] else 4
     ew_bytes = {"graft": (gsz + 8.0) * n_elems, "update": 20.0 * n_elems}
+    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                "traffic": TRAFFIC_BYTES.get(args.workload),
+                "kernel": "gemm_mfma_kernel (two-sided preconditioning, fp32 MFMA)",
+                "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch}
+    fused_ms, fused_launches = stages["fused"]
+    if fused_launches > 0 and fused_ms >= stages["precond"][0]:
+        bytes_per_launch = fused_bytes(table, gsz) * args.steps / fused_launches
+        f_launch_ms = fused_ms / fused_launches
+        gbs = bytes_per_launch / (f_launch_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": gbs / PEAK_HBM_GBS, "traffic": None,
+                    "kernel": "block_step_small_kernel (whole step of a block <= 128 x 128 in one workgroup)",
+                    "launch_ms": f_launch_ms, "bytes_per_launch": bytes_per_launch}
     out = {
         "metric": "shampoo_step_ms",
         "value": ms_per_step,
@@ -216,11 +244,7 @@ def main():
         "tflops_algorithmic": (alg_f + alg_p) / (ms_per_step * 1e-3) / 1e12,
         "tflops_executed": (exe_f + exe_p) / (ms_per_step * 1e-3) / 1e12,
         "stage_ms_per_step": st_ms,
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                     "traffic": TRAFFIC_BYTES.get(args.workload),
-                     "kernel": "gemm_mfma_kernel (two-sided preconditioning, fp32 MFMA)",
-                     "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch},
+        "roofline": roofline,
         "stage_roofline": {
             # bf16 gradients: G G^T runs on the bf16 matrix cores (exact products, float32 / float64
             # accumulation); the figure is algorithmic flops per second, comparable to the float32 peak

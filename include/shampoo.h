@@ -168,7 +168,9 @@ enum {
   SHAMPOO_STAGE_PRECOND = 3,  /* both GEMMs of Lbar G Rbar                  */
   SHAMPOO_STAGE_UPDATE = 4,   /* rescale + momentum + parameter update      */
   SHAMPOO_STAGE_DIAG = 5,     /* 1-D parameters                             */
-  SHAMPOO_STAGE_COUNT = 6
+  SHAMPOO_STAGE_FUSED = 6,    /* blocks <= 128 x 128 on steps without refresh: factor update,
+                                 grafting, preconditioning and update in one kernel */
+  SHAMPOO_STAGE_COUNT = 7
 };
 /* enable != 0: later steps record events around each stage (small overhead). */
 int shampoo_set_timing(shampoo_opt *opt, int32_t enable);

@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libshampoo.so")
 GRAD_F32, GRAD_BF16 = 0, 1
 GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF = range(9)
 GRAFT_ADAGRAD, GRAFT_SGD = 0, 1
-STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG = range(6)
-STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag")
+STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG, STAGE_FUSED = range(7)
+STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag", "fused")
 
 EXPORTS = (
     "shampoo_plan", "shampoo_workspace_bytes", "shampoo_create", "shampoo_step", "shampoo_get",

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "../../include/shampoo.h"
+#include "block_step_small.h"
 #include "eigh_jacobi.h"
 #include "elementwise.h"
 #include "gemm_mfma.h"
@@ -365,7 +366,8 @@ struct shampoo_opt {
   unsigned char *ws = nullptr;
   size_t ws_bytes = 0;
   // workspace offsets
-  size_t off_Gt = 0, off_G1 = 0, off_Gf = 0, off_g1tab = 0, off_gftab = 0, off_prep = 0;
+  size_t off_Gt = 0, off_G1 = 0, off_Gf = 0, off_g1tab = 0, off_gftab = 0, off_prep = 0, off_small = 0;
+  int64_t n_small = 0;     // blocks of at most 128 x 128 (single-workgroup step kernel)
   bool use_l2 = false, use_b1 = false;
   size_t off_A = 0, off_M = 0, off_T = 0, off_wtab = 0, off_gtab = 0, off_diag = 0, off_count = 0, off_eig = 0;
   std::vector<EigLayout> eig_L, eig_R;   // per bucket
@@ -417,6 +419,9 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offW = take((size_t)c->n_params * sizeof(void *));
   const size_t offG = take((size_t)c->n_params * sizeof(void *));
   const size_t offD = take(std::max<size_t>(1, p.diag_chunks.size()) * sizeof(DiagChunk));
+  int64_t n_small = 0;
+  for (auto &b : p.buckets) if (b.m <= SB && b.n <= SB) n_small += b.count;
+  const size_t offSmall = take(std::max<size_t>(1, (size_t)n_small) * sizeof(SmallBlock));
   const size_t offC = take(64);
   const size_t offE = take(eig_bytes);
   if (o) {
@@ -424,6 +429,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     o->off_G1 = offG1; o->off_Gf = offGf; o->off_g1tab = offG1tab; o->off_gftab = offGftab; o->off_prep = offPrep;
     o->use_l2 = use_l2; o->use_b1 = use_b1; o->off_wtab = offW; o->off_gtab = offG;
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
+    o->off_small = offSmall; o->n_small = n_small;
     o->eig_L = eL; o->eig_R = eR;
   }
   return off;
@@ -488,7 +494,24 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     hipLaunchKernelGGL(prep_kernel<GT>, dim3((unsigned)p.prep_chunks.size()), dim3(EW_THREADS), 0, s, pa);
     HIP_TRY(hipGetLastError());
   }
+  // Blocks of at most 128 x 128 take the whole step in one workgroup (gradient block
+  // resident in LDS) whenever no refresh separates the factor update from the
+  // preconditioning and the default heuristics are in force.
+  const bool small_ok = use_shampoo && !refresh && !o->use_l2 && !o->use_b1 && !sgd;
+  auto fused = [&](const Bucket &b) { return small_ok && b.m <= SB && b.n <= SB; };
+  if (small_ok && o->n_small > 0) {
+    StageTimer t(o, SHAMPOO_STAGE_FUSED, s);
+    SmallStepArgs f;
+    f.blocks = reinterpret_cast<const SmallBlock *>(ws + o->off_small); f.ws = ws;
+    f.w_table = wtab; f.g_table = gtab; f.a_state = A; f.m_state = M;
+    f.alpha_d = alpha; f.beta_d = beta;
+    f.graft_eps = c.graft_epsilon; f.mu = c.momentum; f.lr = lr; f.wd_decoupled = wd_dec;
+    f.nesterov = c.use_nesterov ? 1 : 0;
+    hipLaunchKernelGGL(block_step_small_kernel<GT>, dim3((unsigned)o->n_small), dim3(SB_THREADS), 0, s, f);
+    HIP_TRY(hipGetLastError());
+  }
   for (auto &b : p.buckets) {
+    if (fused(b)) continue;
     const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
     if (sizeof(GS) == 2 && b.bf16_mfma && o->ptrs_aligned16) {
       StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
@@ -566,6 +589,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
     float *P = reinterpret_cast<float *>(ws + b.off_P);
     float *scale = reinterpret_cast<float *>(ws + b.off_scale);
+    if (fused(b)) continue;
     if (use_shampoo) {
       StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
       GemmArgs g{};
@@ -726,6 +750,28 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
     if (hipGetLastError() != hipSuccess) return fail(SHAMPOO_ERR_HIP);
     if (hipMemcpyAsync(o->ws + b.off_desc, descs[i].data(), descs[i].size() * sizeof(BlockDesc),
                        hipMemcpyHostToDevice, s) != hipSuccess)
+      return fail(SHAMPOO_ERR_HIP);
+  }
+  if (o->n_small > 0) {
+    // largest blocks first, so that the tail of the launch is made of the cheapest workgroups
+    std::vector<SmallBlock> small;
+    for (size_t i = 0; i < p.buckets.size(); ++i) {
+      const Bucket &b = p.buckets[i];
+      if (b.m > SB || b.n > SB) continue;
+      for (int64_t k = 0; k < b.count; ++k) {
+        SmallBlock sb;
+        sb.d = descs[i][k]; sb.m = b.m; sb.n = b.n;
+        sb.off_L = (int64_t)(b.off_L + (size_t)k * b.m * b.m * 4); sb.off_R = (int64_t)(b.off_R + (size_t)k * b.n * b.n * 4);
+        sb.off_Linv = (int64_t)(b.off_Linv + (size_t)k * b.m * b.m * 4);
+        sb.off_Rinv = (int64_t)(b.off_Rinv + (size_t)k * b.n * b.n * 4);
+        sb.off_P = (int64_t)(b.off_P + (size_t)k * b.m * b.n * 4); sb.off_norms = (int64_t)(b.off_norms + (size_t)k * 8);
+        small.push_back(sb);
+      }
+    }
+    std::stable_sort(small.begin(), small.end(), [](const SmallBlock &x, const SmallBlock &y) {
+      return (int64_t)x.m * x.n > (int64_t)y.m * y.n;
+    });
+    if (hipMemcpy(o->ws + o->off_small, small.data(), small.size() * sizeof(SmallBlock), hipMemcpyHostToDevice) != hipSuccess)
       return fail(SHAMPOO_ERR_HIP);
   }
   if (!p.diag_chunks.empty())

@@ -413,3 +413,18 @@ def test_bias_correction_of_gradient_and_factors():
     for t in range(5):
         p.step(wl.gaussian_grads(shapes, 36, t, 1e-2), 0.01, t)
         p.check(t)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("b", [128, 48])
+def test_small_blocks_between_refreshes(b, bf16):
+    """Steps without refresh take blocks of at most 128 x 128 through the single-workgroup
+    kernel: ragged edge blocks, unaligned leading dimensions, momentum, decoupled decay.  A
+    larger epsilon keeps the stale roots of rank-deficient edge blocks well-posed."""
+    say(f"case small blocks fused b={b} bf16={bf16}")
+    shapes = [(130, 257), (64, 148), (64, 147), (7,), (64, 19), (5, 7), (1, 1), (257, 3), (128, 128)]
+    sig = wl.per_tensor_sigmas(shapes, 5)
+    p = Pair(shapes, b, 0.99, 3, eps=1e-5, bf16=bf16, weight_decay=0.01, nesterov=True)
+    for t in range(6):
+        p.step(wl.gaussian_grads(shapes, 37, t, sig), 0.01, t)
+        p.check(t)
