@@ -28,6 +28,10 @@
 namespace shampoo {
 
 constexpr int JAC_THREADS = 256;
+#ifndef SHAMPOO_PIV_THREADS
+#define SHAMPOO_PIV_THREADS 256
+#endif
+constexpr int JAC_PIV_THREADS = SHAMPOO_PIV_THREADS;   // workgroup of the 64 x 64 pivot solver
 constexpr int JAC_NB = 32;            // block-column width of the block solver
 constexpr int JAC_PIV = 2 * JAC_NB;   // pivot size
 constexpr int JAC_SMALL_MAX = 128;    // largest n solved entirely in LDS
@@ -92,8 +96,8 @@ __device__ __forceinline__ int tri(int i, int j) {
 // SQUARE: At is instead a full square array with row stride LDA (odd): every
 // LDS access of a round is then bank-conflict free, at twice the footprint; the
 // mirror image of each updated block is written as well.
-// Returns nonzero if any rotation was applied.  All threads must call it.
-template <bool SQUARE>
+// Returns nonzero if any rotation was applied.  All NT threads of the workgroup must call it.
+template <bool SQUARE, int NT>
 __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const int LDA, int max_sweeps,
                              double tol_rel, double tol_abs, JacScratch *sc) {
   const int tid = threadIdx.x;
@@ -131,17 +135,17 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
       __syncthreads();
       // A <- R^T A R on the blocks with l <= k.  Blocks are independent, so a thread first
       // loads all of its blocks of a pass, then rotates, then stores (the loads overlap).
-      constexpr int U = 4;
+      constexpr int U = NT >= 1024 ? 2 : 4;
       for (int l = tid & 31; l < half; l += 32) {
         const int pl = sc->p[l], ql = sc->q[l];
         const double sl = sc->s[l], tl = sc->t[l];
-        for (int k0 = tid >> 5; k0 < half; k0 += (JAC_THREADS / 32) * U) {
+        for (int k0 = tid >> 5; k0 < half; k0 += (NT / 32) * U) {
           double a[U], b[U], c[U], d[U], sk[U], tk[U];
           int ia[U], ib[U], ic[U], id[U], pk[U], qk[U];
           bool act[U];
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            const int k = k0 + (JAC_THREADS / 32) * u;
+            const int k = k0 + (NT / 32) * u;
             act[u] = k < half && l <= k;
             if (act[u]) {
               pk[u] = sc->p[k]; qk[u] = sc->q[k]; sk[u] = sc->s[k]; tk[u] = sc->t[k];
@@ -155,7 +159,7 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             if (!act[u]) continue;
-            const int k = k0 + (JAC_THREADS / 32) * u;
+            const int k = k0 + (NT / 32) * u;
             // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
             const double a1 = a[u] - sk[u] * (c[u] + tk[u] * a[u]), c1 = c[u] + sk[u] * (a[u] - tk[u] * c[u]);
             const double b1 = b[u] - sk[u] * (d[u] + tk[u] * b[u]), d1 = d[u] + sk[u] * (b[u] - tk[u] * d[u]);
@@ -175,22 +179,22 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
         }
       }
       // J <- J R (columns), same load / rotate / store batching over rows
-      constexpr int V = 8;
+      constexpr int V = NT >= 1024 ? 4 : 8;
       for (int l = tid & 31; l < half; l += 32) {
         const float sl = (float)sc->s[l];
         if (sl == 0.f) continue;
         const float tl = (float)sc->t[l];
         const int pl = sc->p[l], ql = sc->q[l];
-        for (int i0 = tid >> 5; i0 < s; i0 += (JAC_THREADS / 32) * V) {
+        for (int i0 = tid >> 5; i0 < s; i0 += (NT / 32) * V) {
           float x[V], y[V];
 #pragma unroll
           for (int u = 0; u < V; ++u) {
-            const int i = i0 + (JAC_THREADS / 32) * u;
+            const int i = i0 + (NT / 32) * u;
             if (i < s) { x[u] = Js[i * LD + pl]; y[u] = Js[i * LD + ql]; }
           }
 #pragma unroll
           for (int u = 0; u < V; ++u) {
-            const int i = i0 + (JAC_THREADS / 32) * u;
+            const int i = i0 + (NT / 32) * u;
             if (i < s) {
               Js[i * LD + pl] = x[u] - sl * (y[u] + tl * x[u]);
               Js[i * LD + ql] = y[u] + sl * (x[u] - tl * y[u]);
@@ -223,10 +227,14 @@ struct SmallRootArgs {
   float scale;           // the root is taken of scale * A (bias correction, Sec. 3.1.1); 1 = off
 };
 
-__global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallRootArgs g) {
+// NT threads per workgroup: 256 while several matrices fit the LDS of a CU (n <= 64); 1024
+// above, where only one or two do and more wavefronts are the only way to hide LDS latency.
+template <int NT>
+__global__ __launch_bounds__(NT) void rootinv_small_kernel(const SmallRootArgs g) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ float redf[JAC_THREADS / 64];
-  __shared__ int redi[JAC_THREADS / 64];
+  constexpr int NW = NT / 64;
+  __shared__ float redf[NW];
+  __shared__ int redi[NW];
   __shared__ JacScratch scratch;
   JacScratch *sc = &scratch;
 
@@ -243,7 +251,7 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
   // load (symmetrising: a no-op for exactly symmetric input), padding decoupled zeros
   int bad = 0;
   float dmax = 0.f;
-  for (int i = tid >> 6; i < s; i += JAC_THREADS / 64)
+  for (int i = tid >> 6; i < s; i += NW)
     for (int j = lane; j < s; j += 64) {
       if (j <= i) {
         double v = 0.0;
@@ -264,8 +272,9 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
   }
   if (lane == 0) { redf[wave] = dmax; redi[wave] = bad; }
   __syncthreads();
-  dmax = fmaxf(fmaxf(redf[0], redf[1]), fmaxf(redf[2], redf[3]));
-  bad = redi[0] | redi[1] | redi[2] | redi[3];
+  dmax = redf[0]; bad = redi[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) { dmax = fmaxf(dmax, redf[w]); bad |= redi[w]; }
   if (bad) {   // uniform: Sec. 3.2.3, keep the previous root
     if (tid == 0) {
       if (g.failed) g.failed[b] = 1;
@@ -274,21 +283,23 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
     return;
   }
 
-  jacobi_sweeps<false>(At, Js, s, LD, 0, JAC_SMALL_SWEEPS, JAC_SMALL_TOL_REL, JAC_SMALL_TOL_ABS * (double)dmax, sc);
+  jacobi_sweeps<false, NT>(At, Js, s, LD, 0, JAC_SMALL_SWEEPS, JAC_SMALL_TOL_REL, JAC_SMALL_TOL_ABS * (double)dmax, sc);
   __syncthreads();
 
   // lambda_min over the true eigenvalues, then f = (lambda - min(lambda_min, 0) + eps)^-r
   double lmin = 1.0e300;
-  for (int i = tid; i < n; i += JAC_THREADS) lmin = fmin(lmin, (double)g.scale * At[i * (i + 1) / 2 + i]);
+  for (int i = tid; i < n; i += NT) lmin = fmin(lmin, (double)g.scale * At[i * (i + 1) / 2 + i]);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   __syncthreads();
   if (lane == 0) reinterpret_cast<double *>(sc->s)[wave] = lmin;   // rotation scratch is free now
   __syncthreads();
-  lmin = fmin(fmin(sc->s[0], sc->s[1]), fmin(sc->s[2], sc->s[3]));
+  lmin = sc->s[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) lmin = fmin(lmin, sc->s[w]);
   const double shift = fmin(lmin, 0.0);
   int badf = 0;
-  for (int i = tid; i < s; i += JAC_THREADS) {
+  for (int i = tid; i < s; i += NT) {
     float f = 0.f;
     if (i < n) {
       const double lam = (double)g.scale * At[i * (i + 1) / 2 + i];
@@ -302,18 +313,20 @@ __global__ __launch_bounds__(JAC_THREADS) void rootinv_small_kernel(const SmallR
   for (int off = 32; off > 0; off >>= 1) badf |= __shfl_xor(badf, off, 64);
   if (lane == 0) redi[wave] = badf;
   __syncthreads();
-  badf = redi[0] | redi[1] | redi[2] | redi[3];
+  badf = redi[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) badf |= redi[w];
   if (tid == 0 && g.failed) g.failed[b] = badf ? 1 : 0;
   if (badf) {
     if (tid == 0 && g.fail_count) atomicAdd(g.fail_count, 1ull);
     return;
   }
   // J <- J diag(sqrt f); X = J J^T, lower triangle computed and mirrored
-  for (int i = tid >> 6; i < n; i += JAC_THREADS / 64)
+  for (int i = tid >> 6; i < n; i += NW)
     for (int k = lane; k < s; k += 64) Js[i * LD + k] *= fv[k];
   __syncthreads();
   float *x = g.x + (int64_t)b * g.x_stride;
-  for (int i = tid >> 6; i < n; i += JAC_THREADS / 64)
+  for (int i = tid >> 6; i < n; i += NW)
     for (int j = lane; j <= i; j += 64) {
       float acc = 0.f;
       for (int k = 0; k < n; ++k) acc += Js[i * LD + k] * Js[j * LD + k];
@@ -394,7 +407,7 @@ constexpr int PIV_LD = JAC_PIV + 1;
 // its rows.  A sub-block needed "the other way round" is read transposed.
 
 // One workgroup per (pair, matrix): diagonalise the 64 x 64 pivot.
-__global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const BlockJacArgs g) {
+__global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const BlockJacArgs g) {
   __shared__ double At[JAC_PIV * PIV_LD];
   __shared__ float Js[JAC_PIV * PIV_LD];
   __shared__ JacScratch sc;
@@ -406,7 +419,7 @@ __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const Block
   rr_pair(nblk, g.round, pair, pb, qb);   // pb < qb
   const double *w = g.w + (int64_t)b * np * np;
   const int tid = threadIdx.x;
-  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) {
+  for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) {
     const int j = tid & 63;
     const int gi = (i < JAC_NB ? pb * JAC_NB + i : qb * JAC_NB + i - JAC_NB);
     const int gj = (j < JAC_NB ? pb * JAC_NB + j : qb * JAC_NB + j - JAC_NB);
@@ -417,7 +430,7 @@ __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const Block
   }
   __syncthreads();
   const double dm = (double)g.dmax[b];
-  const int any = jacobi_sweeps<true>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, g.tol_rel,
+  const int any = jacobi_sweeps<true, JAC_PIV_THREADS>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, g.tol_rel,
                                       JAC_SMALL_TOL_ABS * dm, &sc);
   __syncthreads();
   if (tid == 0) {
@@ -426,7 +439,7 @@ __global__ __launch_bounds__(JAC_THREADS) void blockjac_pivot_kernel(const Block
   }
   if (!any) return;
   float *jout = g.jbuf + ((int64_t)b * (nblk / 2) + pair) * JAC_PIV * JAC_PIV;
-  for (int i = tid >> 6; i < JAC_PIV; i += JAC_THREADS / 64) jout[i * JAC_PIV + (tid & 63)] = Js[i * PIV_LD + (tid & 63)];
+  for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) jout[i * JAC_PIV + (tid & 63)] = Js[i * PIV_LD + (tid & 63)];
 }
 
 constexpr int APP_LD = JAC_PIV + 4;

@@ -278,7 +278,7 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
     for (int rd = 0; rd < nblk - 1; ++rd) {
       ja.round = rd; ja.sweep = sw;
-      hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cnt), dim3(JAC_THREADS), 0, s, ja);
+      hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
       hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(hp * (hp + 1) / 2, cnt), dim3(JAC_THREADS), 0, s, ja);
       hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES), cnt),
                          dim3(JAC_THREADS), 0, s, ja);
@@ -314,9 +314,15 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
     g.lambda = lambda; g.failed = failed_user; g.fail_count = fail_count;
     g.n = n; g.epsilon = eps; g.r = r; g.scale = scale;
     const size_t lds = rootinv_small_lds_bytes(n);
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rootinv_small_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(rootinv_small_kernel, dim3(batch), dim3(JAC_THREADS), lds, s, g);
+    if (n <= 64) {
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rootinv_small_kernel<256>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      hipLaunchKernelGGL(rootinv_small_kernel<256>, dim3(batch), dim3(256), lds, s, g);
+    } else {
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rootinv_small_kernel<1024>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      hipLaunchKernelGGL(rootinv_small_kernel<1024>, dim3(batch), dim3(1024), lds, s, g);
+    }
     HIP_TRY(hipGetLastError());
     return SHAMPOO_OK;
   }
