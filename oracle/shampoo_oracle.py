@@ -20,7 +20,8 @@ weight decay, no momentum):
        (plain sums when beta2 == 1; L = R = 0 initially)      [Sec. 3.1.1 EMA eqs]
     2. AdaGrad grafting: A <- A + G*G elementwise (SGD grafting has no state)  [Sec. 2.4]
     3. if t >= start and t % f == 0:
-         Lbar <- rootinv(L), Rbar <- rootinv(R)                [Sec. 3.2.1 framed box]
+         Lbar <- rootinv(L), Rbar <- rootinv(R)                [Sec. 3.2.1 framed box;
+         or, on request, the coupled inverse Newton iteration of the same section]
          (with bias correction and beta2 < 1: of L / (1 - beta2^(t+1)), likewise R)
     4. if beta1 > 0: Gf <- beta1 Gf + (1-beta1) G (Gf = 0 initially), else Gf = G.
        The grafting state above uses G, every direction below uses Gf
@@ -59,7 +60,8 @@ Pins: see tests/test_oracle_pins.py (Kronecker brute force, X^4 (L+eps I) = I,
 diagonal closed forms, polar factor at t = 0, textbook AdaGrad, geometric
 momentum and Nesterov sums, trace identities, independent Jacobi eigensolver,
 geometric weight decay, l2 as a shifted gradient, constant-gradient filtering,
-SGD-graft step length, bias correction under a constant gradient).
+SGD-graft step length, bias correction under a constant gradient, coupled Newton against
+the spectral definition and scalar closed forms).
 """
 import numpy as np
 
@@ -124,6 +126,33 @@ def root_inverse(F, epsilon, r):
     return X, lam
 
 
+def root_inverse_newton(F, epsilon, p, tol=1e-6, max_iterations=100):
+    """Coupled inverse Newton iteration of Sec. 3.2.1 (item 2) for (F + epsilon I)^(-1/p):
+        c   = (2 ||A||_F / (p + 1))^(1/p),  A = F + epsilon I
+        X_0 = I / c,   M_0 = A / c^p
+        X_{k+1} = X_k T_k,   M_{k+1} = T_k^p M_k,   T_k = ((p + 1) I - M_k) / p
+    stopped at the first k with ||M_k - I||_inf < tol (maximum absolute row sum), or after
+    max_iterations steps.  Returns (X_k, k, ||M_k - I||_inf).  The paper leaves open how
+    epsilon enters this variant and the iteration cap; the readings taken are: epsilon is
+    added to the matrix before the iteration, and the cap is a parameter."""
+    F = np.asarray(F, dtype=np.float64)
+    n = F.shape[0]
+    I = np.eye(n)
+    A = F + epsilon * I
+    c = (2.0 * np.sqrt(np.sum(A * A)) / (p + 1.0)) ** (1.0 / p)
+    X = I / c
+    M = A / c ** p
+    k = 0
+    while True:
+        err = np.max(np.sum(np.abs(M - I), axis=1))
+        if err < tol or k >= max_iterations:
+            return X, k, err
+        T = ((p + 1.0) * I - M) / p
+        X = X @ T
+        M = np.linalg.matrix_power(T, p) @ M
+        k += 1
+
+
 def shampoo_direction(Lbar, G, Rbar):
     """P_shampoo = Lbar G Rbar (Sec. 2.3 Shampoo update)."""
     return Lbar @ np.asarray(G, dtype=np.float64) @ Rbar
@@ -152,7 +181,8 @@ class ShampooOracle:
                  precondition_frequency, start_preconditioning_step=0,
                  graft_epsilon=1e-10, momentum=0.0, beta1=0.0, weight_decay=0.0,
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting="adagrad",
-                 use_bias_correction=False):
+                 use_bias_correction=False, root_method="eigh", newton_tolerance=1e-6,
+                 newton_max_iterations=100):
         self.shapes = [tuple(int(x) for x in s) for s in shapes]
         self.b = int(block_size)
         self.beta2 = float(beta2)
@@ -167,6 +197,11 @@ class ShampooOracle:
         self.decoupled = bool(use_decoupled_weight_decay)
         self.nesterov = bool(use_nesterov)
         self.bias_correction = bool(use_bias_correction)
+        if root_method not in ("eigh", "newton"):
+            raise ValueError("root_method must be 'eigh' or 'newton'")
+        self.root_method = root_method
+        self.newton_tol = float(newton_tolerance)
+        self.newton_max_iter = int(newton_max_iterations)
         if grafting not in ("adagrad", "sgd"):
             raise ValueError("grafting must be 'adagrad' or 'sgd'")
         self.grafting = grafting
@@ -197,6 +232,12 @@ class ShampooOracle:
                     lst.append([])
             else:
                 raise ValueError("only 1-D and 2-D parameters")
+
+    def _root(self, F):
+        if self.root_method == "newton":
+            return root_inverse_newton(F, self.epsilon, int(round(1.0 / self.r)), self.newton_tol,
+                                       self.newton_max_iter)[0]
+        return root_inverse(F, self.epsilon, self.r)[0]
 
     def _finish(self, i, sl, P, W, lr):
         """Steps 7-9 on one block / vector: decoupled decay, momentum, update."""
@@ -240,8 +281,8 @@ class ShampooOracle:
                 if self.grafting == "adagrad":
                     self.A[i][sl] = graft_state_update(self.A[i][sl], Gb)
                 if refresh:
-                    self.Lbar[i][k], _ = root_inverse(c2 * self.L[i][k], self.epsilon, self.r)
-                    self.Rbar[i][k], _ = root_inverse(c2 * self.R[i][k], self.epsilon, self.r)
+                    self.Lbar[i][k] = self._root(c2 * self.L[i][k])
+                    self.Rbar[i][k] = self._root(c2 * self.R[i][k])
                 if self.grafting == "adagrad":
                     Pg = graft_direction(Gfb, self.A[i][sl], self.eps_g)
                 else:

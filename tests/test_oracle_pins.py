@@ -560,3 +560,75 @@ def test_bias_correction_one_d_textbook():
             gf[i] = b1 * gf[i] + (1 - b1) * g[i]
             w[i] -= lr * (gf[i] / (1 - b1 ** (t + 1))) / (np.sqrt(a[i]) + eg)
         assert np.allclose(W[0], w, rtol=1e-13, atol=1e-16)
+
+
+# ---------------------------------------------------------------------------
+# Coupled inverse Newton iteration (Sec. 3.2.1, item 2)
+# ---------------------------------------------------------------------------
+def wishart(n, k, seed):
+    g = rng(seed).standard_normal((n, k))
+    return g @ g.T / k
+
+
+@pytest.mark.parametrize("p", [1, 2, 4])
+def test_newton_converges_to_the_spectral_root_inverse(p):
+    """On a well-conditioned SPD matrix the iteration ends below its tolerance and X equals
+    (A + eps I)^(-1/p) from the eigendecomposition to about tol / p."""
+    A = wishart(24, 96, 40 + p)
+    eps = 1e-3
+    X, k, err = so.root_inverse_newton(A, eps, p, tol=1e-10, max_iterations=200)
+    lam, Q = np.linalg.eigh(A)
+    exact = (Q * (lam + eps) ** (-1.0 / p)) @ Q.T
+    assert err < 1e-10 and 0 < k < 60
+    assert np.linalg.norm(X - exact) <= 1e-9 * np.linalg.norm(exact)
+    # X^p (A + eps I) = I
+    assert np.allclose(np.linalg.matrix_power(X, p) @ (A + eps * np.eye(24)), np.eye(24), atol=1e-8)
+
+
+def test_newton_scalar_recursion_by_hand():
+    """n = 1: c = (2 a / (p + 1))^(1/p), m_0 = (p + 1) / 2 ... the scalar recursion written out."""
+    a, p, eps = 3.7, 4, 0.05
+    X, k, err = so.root_inverse_newton(np.array([[a]]), eps, p, tol=1e-12, max_iterations=50)
+    A = a + eps
+    c = (2 * A / (p + 1)) ** (1 / p)
+    x, m = 1 / c, A / c ** p
+    assert np.isclose(m, (p + 1) / 2)
+    steps = 0
+    while abs(m - 1) >= 1e-12:
+        t = ((p + 1) - m) / p
+        x, m = x * t, t ** p * m
+        steps += 1
+    assert steps == k and np.isclose(X[0, 0], x, rtol=1e-14) and np.isclose(x, A ** (-1 / p), rtol=1e-11)
+
+
+def test_newton_iteration_cap_and_diagonal_input():
+    """A diagonal matrix stays diagonal and every entry follows its own scalar recursion from the
+    common c; with a cap of 3 steps exactly 3 are taken."""
+    d = np.array([0.2, 1.0, 5.0])
+    p = 2
+    X, k, err = so.root_inverse_newton(np.diag(d), 0.0, p, tol=1e-30, max_iterations=3)
+    assert k == 3
+    c = (2 * np.sqrt(np.sum(d * d)) / (p + 1)) ** (1 / p)
+    x, m = np.full(3, 1 / c), d / c ** p
+    for _ in range(3):
+        t = ((p + 1) - m) / p
+        x, m = x * t, t ** p * m
+    assert np.allclose(X, np.diag(x), rtol=1e-14, atol=1e-300)
+    assert np.isclose(err, np.max(np.abs(m - 1)))
+
+
+def test_optimizer_with_newton_roots_matches_eigh_roots_when_well_conditioned():
+    """Same optimizer, two root routines: on well-conditioned factors (wide blocks, visible
+    epsilon) the trajectories agree to the Newton tolerance."""
+    shapes = [(8, 40), (12,)]
+    kw = dict(block_size=64, beta2=0.99, epsilon=1e-3, precondition_frequency=2, momentum=0.9)
+    a = make_opt(shapes, **kw)
+    b = make_opt(shapes, root_method="newton", newton_tolerance=1e-10, **kw)
+    Wa = [np.zeros(s) for s in shapes]
+    Wb = [np.zeros(s) for s in shapes]
+    for t in range(5):
+        g = [rng(50 + t).standard_normal(s) for s in shapes]
+        a.step(Wa, g, 0.1, t)
+        b.step(Wb, g, 0.1, t)
+    assert np.allclose(Wa[0], Wb[0], rtol=1e-7, atol=1e-10)
+    assert np.allclose(a.Rbar[0][0], b.Rbar[0][0], rtol=1e-7, atol=1e-9)
