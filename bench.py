@@ -143,6 +143,13 @@ def main():
     ap.add_argument("--skip-refresh", action="store_true",
                     help="number the steps from 1 so that no root refresh runs (roots stay the identity); "
                          "for counter runs of the per-step kernels only")
+    ap.add_argument("--root-method", default="eigh", choices=["eigh", "newton"],
+                    help="root-inverse routine of the refresh: eigendecomposition (default) or the coupled "
+                         "inverse Newton iteration (float32; meant for well-conditioned factors)")
+    ap.add_argument("--first-refresh-at", type=int, default=0,
+                    help="run this many untimed grafting-only steps first (start_preconditioning_step), so that "
+                         "the timed refresh sees factors accumulated over that many gradients; must be a "
+                         "multiple of the workload's precondition_frequency")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the reference for scaling HBM counters")
     args = ap.parse_args()
@@ -157,6 +164,10 @@ def main():
     shapes = wk["shapes"]
     f = wk["f"]
     warm = max(args.warmup, 1)
+    t_first = args.first_refresh_at
+    if t_first % f != 0 or t_first < 0 or (t_first and args.skip_refresh):
+        print(f"bench.py: --first-refresh-at must be a non-negative multiple of {f}", file=sys.stderr)
+        return 2
     if warm + args.steps > f:
         print(f"bench.py: warmup + steps must stay below precondition_frequency = {f}", file=sys.stderr)
         return 2
@@ -168,8 +179,9 @@ def main():
     params = [torch.randn(s, generator=gen, device=dev, dtype=torch.float32) * 0.02 for s in shapes]
     pool = [[(torch.randn(s, generator=gen, device=dev, dtype=torch.float32) * wk["sigma"]).to(gdt)
              for s in shapes] for _ in range(2)]
-    opt = B.Shampoo(shapes, wk["block"], 0.999, 1e-12, 0.25, f, 0, 1e-10, 0.9,
-                    B.GRAD_BF16 if wk["bf16"] else B.GRAD_F32)
+    opt = B.Shampoo(shapes, wk["block"], 0.999, 1e-12, 0.25, f, t_first, 1e-10, 0.9,
+                    B.GRAD_BF16 if wk["bf16"] else B.GRAD_F32,
+                    root_method=B.ROOT_NEWTON if args.root_method == "newton" else B.ROOT_EIGH)
     table, n_buckets = opt.plan()
     n_elems = sum(int(np.prod(s)) for s in shapes)
 
@@ -177,7 +189,11 @@ def main():
     opt.set_timing(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    base = 1 if args.skip_refresh else 0
+    base = 1 if args.skip_refresh else t_first
+    for t in range(t_first):          # untimed: factors accumulate, the step is the grafted one
+        opt.step(params, pool[t % 2], 0.01, t)
+    torch.cuda.synchronize()
+    opt.get_timing()
     if args.copy_ref:
         ref_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_(generator=gen)
         ref_dst = torch.empty_like(ref_src)
@@ -237,7 +253,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": wk["label"], "params": n_elems, "blocks": int(len(table)),
                    "buckets": int(n_buckets), "block_size": wk["block"], "precondition_frequency": f,
-                   "grad_dtype": "bf16" if wk["bf16"] else "f32"},
+                   "grad_dtype": "bf16" if wk["bf16"] else "f32", "root_method": args.root_method,
+                   "first_refresh_at_step": t_first},
         "refresh_ms": refresh_ms,
         "first_step_ms": first_step_ms,
         "amortized_ms_per_step": ms_per_step + refresh_ms / f,

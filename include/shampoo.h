@@ -48,6 +48,7 @@ enum {
 
 enum { SHAMPOO_GRAD_F32 = 0, SHAMPOO_GRAD_BF16 = 1 };
 enum { SHAMPOO_GRAFT_ADAGRAD = 0, SHAMPOO_GRAFT_SGD = 1 };
+enum { SHAMPOO_ROOT_EIGH = 0, SHAMPOO_ROOT_NEWTON = 1 };
 
 /*
  * Optimizer configuration (copied at create; the arrays need not outlive the call).
@@ -76,6 +77,13 @@ typedef struct {
   int32_t use_bias_correction; /* != 0: directions use Gf / (1 - beta1^(step+1)) and roots are
                              taken of L / (1 - beta2^(step+1)) (beta2 < 1), epsilon added after
                              the division; stored state stays uncorrected (Sec. 3.1.1)        */
+  int32_t root_method;    /* SHAMPOO_ROOT_EIGH: eigendecomposition (framed box of Sec. 3.2.1, default);
+                             SHAMPOO_ROOT_NEWTON: coupled inverse Newton iteration of the same
+                             section on L + epsilon I, in float32; needs 1/root_exponent in
+                             {1, 2, 4, 8} (else SHAMPOO_ERR_UNSUPPORTED) and factors whose
+                             condition number float32 can resolve                            */
+  float newton_tolerance; /* stop when ||M_k - I||_inf < this; 0 selects 1e-6 (Sec. 3.2.1)     */
+  int32_t newton_max_iterations; /* iteration cap, <= 1000; 0 selects 100                     */
   int32_t grad_dtype;     /* SHAMPOO_GRAD_F32 or SHAMPOO_GRAD_BF16; parameters are float32   */
   int32_t device;         /* HIP device ordinal                                              */
 } shampoo_config;
@@ -202,6 +210,29 @@ size_t shampoo_root_inverse_workspace_bytes(int32_t n, int32_t batch);
 int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon, float r,
                          float *x, float *lambda, int32_t *failed,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Stand-alone batched coupled inverse Newton iteration (Sec. 3.2.1, item 2):
+ *   A_i = a_i + epsilon I,  c = (2 ||A_i||_F / (p + 1))^(1/p),  X_0 = I / c,  M_0 = A_i / c^p,
+ *   X_{k+1} = X_k T_k,  M_{k+1} = T_k^p M_k,  T_k = ((p + 1) I - M_k) / p,
+ * ended per matrix at the first k with ||M_k - I||_inf < tolerance, at k = max_iterations,
+ * or when the norm has reached the floor of float32 arithmetic (below 0.1 and no longer
+ * halving).  x_i = X_k approximates A_i^(-1/p).
+ * a:          device, batch dense row-major symmetric n x n float32 matrices (read only)
+ * p:          1, 2, 4 or 8 (else SHAMPOO_ERR_UNSUPPORTED)
+ * x:          device, batch n x n float32 outputs (may not alias a)
+ * iterations: device int32[batch], the k at which each matrix ended, or NULL
+ * failed:     device int32[batch] set to 1 where A_i or an iterate is not finite (x_i is
+ *             then left untouched), else 0; or NULL
+ * workspace:  device, 256-byte aligned, at least
+ *             shampoo_root_inverse_newton_workspace_bytes(n, batch) bytes
+ * Asynchronous on `stream`; no host synchronisation inside.
+ */
+size_t shampoo_root_inverse_newton_workspace_bytes(int32_t n, int32_t batch);
+int shampoo_root_inverse_newton(const float *a, int32_t n, int32_t batch, float epsilon, int32_t p,
+                                float tolerance, int32_t max_iterations, float *x,
+                                int32_t *iterations, int32_t *failed,
+                                void *workspace, size_t workspace_bytes, void *stream);
 
 /* Static, NUL-terminated description of a return code. */
 const char *shampoo_strerror(int code);

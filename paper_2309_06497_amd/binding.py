@@ -16,13 +16,15 @@ LIB_PATH = os.path.join(_HERE, "libshampoo.so")
 GRAD_F32, GRAD_BF16 = 0, 1
 GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF = range(9)
 GRAFT_ADAGRAD, GRAFT_SGD = 0, 1
+ROOT_EIGH, ROOT_NEWTON = 0, 1
 STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG, STAGE_FUSED = range(7)
 STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag", "fused")
 
 EXPORTS = (
     "shampoo_plan", "shampoo_workspace_bytes", "shampoo_create", "shampoo_step", "shampoo_get",
     "shampoo_status", "shampoo_set_timing", "shampoo_get_timing", "shampoo_destroy",
-    "shampoo_root_inverse_workspace_bytes", "shampoo_root_inverse", "shampoo_strerror",
+    "shampoo_root_inverse_workspace_bytes", "shampoo_root_inverse",
+    "shampoo_root_inverse_newton_workspace_bytes", "shampoo_root_inverse_newton", "shampoo_strerror",
 )
 
 
@@ -45,6 +47,9 @@ class ShampooConfig(ctypes.Structure):
         ("use_nesterov", ctypes.c_int32),
         ("grafting_type", ctypes.c_int32),
         ("use_bias_correction", ctypes.c_int32),
+        ("root_method", ctypes.c_int32),
+        ("newton_tolerance", ctypes.c_float),
+        ("newton_max_iterations", ctypes.c_int32),
         ("grad_dtype", ctypes.c_int32),
         ("device", ctypes.c_int32),
     ]
@@ -85,6 +90,10 @@ def lib():
     L.shampoo_root_inverse_workspace_bytes.restype = sz
     L.shampoo_root_inverse.argtypes = [vp, i32, i32, f32, f32, vp, vp, vp, vp, sz, vp]
     L.shampoo_root_inverse.restype = ctypes.c_int
+    L.shampoo_root_inverse_newton_workspace_bytes.argtypes = [i32, i32]
+    L.shampoo_root_inverse_newton_workspace_bytes.restype = sz
+    L.shampoo_root_inverse_newton.argtypes = [vp, i32, i32, f32, i32, f32, i32, vp, vp, vp, vp, sz, vp]
+    L.shampoo_root_inverse_newton.restype = ctypes.c_int
     L.shampoo_strerror.argtypes = [ctypes.c_int]
     L.shampoo_strerror.restype = ctypes.c_char_p
     _lib = L
@@ -106,7 +115,8 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                 start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
                 grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
-                use_bias_correction=False):
+                use_bias_correction=False, root_method=ROOT_EIGH,
+                newton_tolerance=1e-6, newton_max_iterations=100):
     """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
     n = len(shapes)
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
@@ -118,7 +128,7 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                         precondition_frequency, start_preconditioning_step, graft_epsilon,
                         momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
                         1 if use_nesterov else 0, grafting_type, 1 if use_bias_correction else 0,
-                        grad_dtype, device)
+                        root_method, newton_tolerance, newton_max_iterations, grad_dtype, device)
     cfg._keep = (ndim, shape)
     return cfg
 
@@ -151,14 +161,15 @@ class Shampoo:
                  start_preconditioning_step=0, graft_epsilon=1e-10, momentum=0.0,
                  grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
-                use_bias_correction=False):
+                use_bias_correction=False, root_method=ROOT_EIGH,
+                newton_tolerance=1e-6, newton_max_iterations=100):
         import torch
         self.shapes = [tuple(s) for s in shapes]
         self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
                                precondition_frequency, start_preconditioning_step, graft_epsilon,
                                momentum, grad_dtype, device, beta1, weight_decay,
                                use_decoupled_weight_decay, use_nesterov, grafting_type,
-                               use_bias_correction)
+                               use_bias_correction, root_method, newton_tolerance, newton_max_iterations)
         self.device = torch.device("cuda", device)
         nbytes = shampoo_workspace_bytes(self.cfg)
         if nbytes == 0:
@@ -253,6 +264,36 @@ def shampoo_root_inverse(a, epsilon, r, want_lambda=False, want_failed=False):
     res = [x]
     if want_lambda:
         res.append(lam)
+    if want_failed:
+        res.append(failed)
+    return res[0] if len(res) == 1 else tuple(res)
+
+
+def shampoo_root_inverse_newton(a, epsilon, p, tolerance=1e-6, max_iterations=100, want_iterations=False,
+                                want_failed=False):
+    """a: CUDA float32 tensor [batch, n, n] (symmetric).  Returns X [batch, n, n], the coupled
+    inverse Newton approximation of (a + epsilon I)^(-1/p) (and the iteration counts [batch],
+    failure flags [batch] on request)."""
+    import torch
+    assert a.is_cuda and a.dtype == torch.float32 and a.dim() == 3 and a.shape[1] == a.shape[2]
+    a = a.contiguous()
+    batch, n = a.shape[0], a.shape[1]
+    x = torch.empty_like(a)
+    iters = torch.zeros((batch,), dtype=torch.int32, device=a.device) if want_iterations else None
+    failed = torch.zeros((batch,), dtype=torch.int32, device=a.device) if want_failed else None
+    nbytes = lib().shampoo_root_inverse_newton_workspace_bytes(n, batch)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=a.device)
+    with torch.cuda.device(a.device):
+        _check(lib().shampoo_root_inverse_newton(
+            ctypes.c_void_p(a.data_ptr()), n, batch, epsilon, p, tolerance, max_iterations,
+            ctypes.c_void_p(x.data_ptr()),
+            ctypes.c_void_p(iters.data_ptr()) if iters is not None else None,
+            ctypes.c_void_p(failed.data_ptr()) if failed is not None else None,
+            ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream_ptr()))
+        torch.cuda.current_stream().synchronize()   # ws is released on return
+    res = [x]
+    if want_iterations:
+        res.append(iters)
     if want_failed:
         res.append(failed)
     return res[0] if len(res) == 1 else tuple(res)

@@ -17,6 +17,7 @@
 #include "eigh_jacobi.h"
 #include "elementwise.h"
 #include "gemm_mfma.h"
+#include "newton_root.h"
 #include "syrk_bf16.h"
 
 using namespace shampoo;
@@ -62,6 +63,14 @@ struct Plan {
   int64_t total_elems = 0;
 };
 
+// p = 1 / r when that is 1, 2, 4 or 8 (the powers the coupled Newton iteration forms by
+// repeated squaring), else 0
+int newton_p_of(float r) {
+  for (int p : {1, 2, 4, 8})
+    if (std::fabs(1.0 / (double)r - (double)p) <= 1e-4 * p) return p;
+  return 0;
+}
+
 int check_config(const shampoo_config *c) {
   if (!c || !c->ndim || !c->shape) return SHAMPOO_ERR_NULL;
   if (c->n_params < 1) return SHAMPOO_ERR_SHAPE;
@@ -84,6 +93,12 @@ int check_config(const shampoo_config *c) {
   if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return SHAMPOO_ERR_HYPER;
   if (!(c->weight_decay >= 0.f) || !std::isfinite(c->weight_decay)) return SHAMPOO_ERR_HYPER;
   if (c->grafting_type != SHAMPOO_GRAFT_ADAGRAD && c->grafting_type != SHAMPOO_GRAFT_SGD) return SHAMPOO_ERR_HYPER;
+  if (c->root_method != SHAMPOO_ROOT_EIGH && c->root_method != SHAMPOO_ROOT_NEWTON) return SHAMPOO_ERR_HYPER;
+  if (c->root_method == SHAMPOO_ROOT_NEWTON) {
+    if (c->newton_tolerance < 0.f || !std::isfinite(c->newton_tolerance)) return SHAMPOO_ERR_HYPER;
+    if (c->newton_max_iterations < 0 || c->newton_max_iterations > 1000) return SHAMPOO_ERR_HYPER;
+    if (newton_p_of(c->root_exponent) == 0) return SHAMPOO_ERR_UNSUPPORTED;
+  }
   return SHAMPOO_OK;
 }
 
@@ -359,6 +374,106 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
   return SHAMPOO_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Coupled inverse Newton iteration (Sec. 3.2.1, item 2): workspace and driver
+// ---------------------------------------------------------------------------
+struct NewtonLayout {
+  int32_t chunk = 0;
+  size_t mat = 0;          // bytes of one n x n float32 matrix (aligned)
+  size_t off_mats = 0, off_rowpart = 0, off_err = 0, off_prev = 0, off_done = 0, off_failed = 0, off_iters = 0;
+  size_t bytes = 0;
+};
+constexpr int NEWTON_MATS = 7;   // M, M', X, X', T and two buffers for the powers of T
+
+NewtonLayout newton_layout(int n, int batch) {
+  NewtonLayout e;
+  e.mat = align_up((size_t)n * n * sizeof(float));
+  e.chunk = (int)std::max<size_t>(1, std::min<size_t>((size_t)std::max(batch, 1), EIG_CHUNK_BYTES / (NEWTON_MATS * e.mat)));
+  size_t off = 0;
+  e.off_mats = off; off += (size_t)NEWTON_MATS * e.chunk * e.mat;
+  e.off_rowpart = off; off += align_up((size_t)e.chunk * n * sizeof(double));
+  e.off_err = off; off += align_up((size_t)e.chunk * sizeof(float));
+  e.off_prev = off; off += align_up((size_t)e.chunk * sizeof(float));
+  e.off_done = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
+  e.off_failed = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
+  e.off_iters = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
+  e.bytes = off;
+  return e;
+}
+
+// p must be 1, 2, 4 or 8: T^p is formed by repeated squaring
+inline bool newton_p_supported(int p) { return p == 1 || p == 2 || p == 4 || p == 8; }
+
+// C = A B on the lower tiles, mirrored (A, B symmetric and commuting), for the matrices not yet done
+int newton_product(const float *A, const float *B, float *C, int n, int cnt, const int32_t *done, hipStream_t s) {
+  GemmArgs g{};
+  g.a.base = A; g.a.batch_stride = (int64_t)n * n; g.a.ld = n; g.a.from_table = 0;
+  g.b.base = B; g.b.batch_stride = (int64_t)n * n; g.b.ld = n; g.b.from_table = 0;
+  g.c = C; g.c_batch_stride = (int64_t)n * n; g.ldc = n;
+  g.M = n; g.N = n; g.K = n; g.alpha = 1.f; g.beta = 0.f;
+  g.skip = done;
+  g.tiles_m = g.tiles_n = (n + BM - 1) / BM;
+  g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
+  g.batch = cnt;
+  return launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_SYRK, false>(g, s);
+}
+
+// X_i = (scale * A_i + eps I)^(-1/p) for a batch of dense n x n matrices.
+int newton_root_batched(const float *a, int n, int batch, float eps, int p, float scale, float tol, int max_iter,
+                        float *x, int32_t *iters_user, int32_t *failed_user, unsigned long long *fail_count,
+                        unsigned char *ws, const NewtonLayout &e, hipStream_t s) {
+  if (batch <= 0) return SHAMPOO_OK;
+  const size_t mat_elems = e.mat / sizeof(float);
+  for (int b0 = 0; b0 < batch; b0 += e.chunk) {
+    const int cb = std::min(e.chunk, batch - b0);
+    float *buf[NEWTON_MATS];
+    for (int i = 0; i < NEWTON_MATS; ++i) buf[i] = reinterpret_cast<float *>(ws + e.off_mats) + (size_t)i * e.chunk * mat_elems;
+    // matrices of a chunk are stored back to back with stride n * n inside each buffer
+    float *M = buf[0], *M2 = buf[1], *X = buf[2], *X2 = buf[3], *T = buf[4], *Pa = buf[5], *Pb = buf[6];
+    NewtonArgs g{};
+    g.a = a + (int64_t)b0 * n * n; g.a_stride = (int64_t)n * n;
+    g.rowpart = reinterpret_cast<double *>(ws + e.off_rowpart);
+    g.err = reinterpret_cast<float *>(ws + e.off_err); g.prev = reinterpret_cast<float *>(ws + e.off_prev);
+    g.done = reinterpret_cast<int32_t *>(ws + e.off_done); g.failed = reinterpret_cast<int32_t *>(ws + e.off_failed);
+    g.iters = reinterpret_cast<int32_t *>(ws + e.off_iters);
+    g.n = n; g.p = p; g.max_iter = max_iter; g.epsilon = eps; g.scale = scale; g.tol = tol;
+    int rc = launch_fill(reinterpret_cast<float *>(g.failed), 0.f, cb, s);
+    if (rc) return rc;
+    g.M = M; g.X = X; g.T = T;
+    hipLaunchKernelGGL(newton_rownorm_kernel, dim3(n, cb), dim3(256), 0, s, g);
+    hipLaunchKernelGGL(newton_init_kernel, dim3(n, cb), dim3(256), 0, s, g);
+    HIP_TRY(hipGetLastError());
+    for (int k = 0; k <= max_iter; ++k) {
+      g.k = k; g.M = M; g.X = X; g.T = T;
+      hipLaunchKernelGGL(newton_prep_kernel, dim3(n, cb), dim3(256), 0, s, g);
+      hipLaunchKernelGGL(newton_check_kernel, dim3((cb + 255) / 256), dim3(256), 0, s, g, cb);
+      HIP_TRY(hipGetLastError());
+      // matrices whose iteration ended at this k hand their X over now: afterwards the X / M
+      // buffers swap roles, and a finished matrix is no longer written by the products
+      NewtonFinishArgs fa;
+      fa.X = X; fa.x = x + (int64_t)b0 * n * n; fa.x_stride = (int64_t)n * n;
+      fa.done = g.done; fa.failed = g.failed; fa.failed_out = failed_user ? failed_user + b0 : nullptr;
+      fa.fail_count = fail_count;
+      fa.iters = g.iters; fa.iters_out = iters_user ? iters_user + b0 : nullptr; fa.n = n; fa.k = k;
+      hipLaunchKernelGGL(newton_finish_kernel, dim3(n, cb), dim3(256), 0, s, fa);
+      HIP_TRY(hipGetLastError());
+      if (k == max_iter) break;
+      // T^p by repeated squaring, X' = X T, M' = T^p M
+      const float *Tp = T;
+      float *sq[2] = {Pa, Pb};
+      int w = 0;
+      for (int q = 1; q < p; q *= 2) {
+        if ((rc = newton_product(Tp, Tp, sq[w], n, cb, g.done, s))) return rc;
+        Tp = sq[w]; w ^= 1;
+      }
+      if ((rc = newton_product(X, T, X2, n, cb, g.done, s))) return rc;
+      if ((rc = newton_product(Tp, M, M2, n, cb, g.done, s))) return rc;
+      std::swap(M, M2); std::swap(X, X2);
+    }
+  }
+  return SHAMPOO_OK;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -418,7 +533,10 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) gt_elems = std::max(gt_elems, B * m * n);
     eL.push_back(eig_layout(b.m, b.count));
     eR.push_back(eig_layout(b.n, b.count));
-    eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
+    if (c->root_method == SHAMPOO_ROOT_NEWTON)
+      eig_bytes = std::max(eig_bytes, std::max(newton_layout(b.m, b.count).bytes, newton_layout(b.n, b.count).bytes));
+    else
+      eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
   }
   const size_t offT = take(t_elems * 4);
   const size_t offGt = take(gt_elems * 2);
@@ -580,6 +698,20 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     StageTimer t(o, SHAMPOO_STAGE_ROOT, s);
     for (size_t i = 0; i < p.buckets.size(); ++i) {
       auto &b = p.buckets[i];
+      if (c.root_method == SHAMPOO_ROOT_NEWTON) {
+        const int pw = newton_p_of(c.root_exponent);
+        const float tol = c.newton_tolerance > 0.f ? c.newton_tolerance : 1e-6f;
+        const int cap = c.newton_max_iterations > 0 ? c.newton_max_iterations : 100;
+        rc = newton_root_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, pw, c2, tol, cap,
+                                 reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
+                                 ws + o->off_eig, newton_layout(b.m, b.count), s);
+        if (rc) return rc;
+        rc = newton_root_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, pw, c2, tol, cap,
+                                 reinterpret_cast<float *>(ws + b.off_Rinv), nullptr, nullptr, fail_count,
+                                 ws + o->off_eig, newton_layout(b.n, b.count), s);
+        if (rc) return rc;
+        continue;
+      }
       rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
                                 ws + o->off_eig, o->eig_L[i], s);
@@ -941,6 +1073,27 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
   }
   return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
                               static_cast<unsigned char *>(workspace), e, s);
+}
+
+size_t shampoo_root_inverse_newton_workspace_bytes(int32_t n, int32_t batch) {
+  if (n < 1 || batch < 1 || n > MAX_BLOCK_SIZE) return 0;
+  return newton_layout(n, batch).bytes;
+}
+
+int shampoo_root_inverse_newton(const float *a, int32_t n, int32_t batch, float epsilon, int32_t p, float tolerance,
+                                int32_t max_iterations, float *x, int32_t *iterations, int32_t *failed,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+  if (!a || !x) return SHAMPOO_ERR_NULL;
+  if (n < 1 || batch < 1) return SHAMPOO_ERR_SHAPE;
+  if (n > MAX_BLOCK_SIZE || !newton_p_supported(p)) return SHAMPOO_ERR_UNSUPPORTED;
+  if (!(epsilon >= 0.f) || !std::isfinite(epsilon) || !(tolerance > 0.f) || !std::isfinite(tolerance) ||
+      max_iterations < 1 || max_iterations > 1000)
+    return SHAMPOO_ERR_HYPER;
+  const NewtonLayout e = newton_layout(n, batch);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % ALIGN) != 0 || workspace_bytes < e.bytes)
+    return SHAMPOO_ERR_WORKSPACE;
+  return newton_root_batched(a, n, batch, epsilon, p, 1.f, tolerance, max_iterations, x, iterations, failed, nullptr,
+                             static_cast<unsigned char *>(workspace), e, static_cast<hipStream_t>(stream));
 }
 
 const char *shampoo_strerror(int code) {

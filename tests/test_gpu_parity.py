@@ -77,16 +77,19 @@ class Pair:
 
     def __init__(self, shapes, b, beta2, f, start=0, mu=0.9, eps=1e-12, eps_g=1e-10, bf16=False, seed=0,
                  beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad",
-                 bias_correction=False):
+                 bias_correction=False, newton=None):
         self.shapes = shapes
         self.bf16 = bf16
         self.f, self.start, self.eps = f, start, f32(eps)
         self.gpu = B.Shampoo(shapes, b, beta2, eps, 0.25, f, start, eps_g, mu,
                              B.GRAD_BF16 if bf16 else B.GRAD_F32, 0, beta1, weight_decay, decoupled, nesterov,
-                             B.GRAFT_SGD if grafting == "sgd" else B.GRAFT_ADAGRAD, bias_correction)
+                             B.GRAFT_SGD if grafting == "sgd" else B.GRAFT_ADAGRAD, bias_correction,
+                             B.ROOT_NEWTON if newton else B.ROOT_EIGH, *(newton or (1e-6, 100)))
         self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, start, f32(eps_g), f32(mu),
                                     f32(beta1), f32(weight_decay), decoupled, nesterov, grafting,
-                                    bias_correction)
+                                    bias_correction, "newton" if newton else "eigh",
+                                    *((f32(newton[0]), newton[1]) if newton else (1e-6, 100)))
+        self.newton = newton
         w0 = wl.init_params(shapes, seed)
         self.w0 = [w.astype(np.float64) for w in w0]
         self.w_ora = [w.astype(np.float64) for w in w0]
@@ -169,9 +172,12 @@ class Pair:
                         c2 = 1.0
                         if self.ora.bias_correction and self.ora.beta2 < 1.0:
                             c2 = 1.0 / (1.0 - self.ora.beta2 ** (t + 1))
-                        worst["root"] = max(worst["root"],
-                                            rel(Li, so.root_inverse(c2 * L.astype(np.float64), self.eps, 0.25)[0]),
-                                            rel(Ri, so.root_inverse(c2 * R.astype(np.float64), self.eps, 0.25)[0]))
+                        if self.newton:
+                            root = lambda F: so.root_inverse_newton(c2 * F.astype(np.float64), self.eps, 4,
+                                                                    f32(self.newton[0]), self.newton[1])[0]
+                        else:
+                            root = lambda F: so.root_inverse(c2 * F.astype(np.float64), self.eps, 0.25)[0]
+                        worst["root"] = max(worst["root"], rel(Li, root(L)), rel(Ri, root(R)))
                     P = self.gpu.get(i, k, B.GET_PSH).cpu().numpy()
                     c1 = 1.0
                     if self.ora.bias_correction and self.ora.beta1 > 0:
@@ -428,3 +434,92 @@ def test_small_blocks_between_refreshes(b, bf16):
     for t in range(6):
         p.step(wl.gaussian_grads(shapes, 37, t, sig), 0.01, t)
         p.check(t)
+
+
+# ---------------------------------------------------------------------------
+# Coupled inverse Newton iteration (Sec. 3.2.1, item 2)
+# ---------------------------------------------------------------------------
+def wishart_batch(n, batch, seed, samples_per_dim=4):
+    r = np.random.default_rng(seed)
+    out = np.empty((batch, n, n), np.float32)
+    for b in range(batch):
+        g = r.standard_normal((n, samples_per_dim * n + 1))
+        out[b] = (g @ g.T / g.shape[1]).astype(np.float32)
+        out[b] = 0.5 * (out[b] + out[b].T)
+    return out
+
+
+# float32 products of n-long sums, 6-10 iterations, condition number ~10: measured 2e-7 ... 1.3e-6
+TOL_NEWTON_X = 2e-5
+
+
+@pytest.mark.parametrize("n,p", [(1, 4), (5, 2), (64, 4), (100, 4), (128, 2), (200, 4), (300, 4), (96, 1), (96, 8)])
+def test_newton_root_inverse_standalone(n, p):
+    import torch
+    say(f"case newton n={n} p={p}")
+    a = wishart_batch(n, 3, 60 + n + p)
+    eps, tol = 1e-3, 1e-6
+    x, iters, failed = B.shampoo_root_inverse_newton(torch.from_numpy(a).cuda(), eps, p, tol, 100, True, True)
+    x, iters, failed = x.cpu().numpy(), iters.cpu().numpy(), failed.cpu().numpy()
+    assert not failed.any()
+    worst = 0.0
+    for b in range(a.shape[0]):
+        X, k, err = so.root_inverse_newton(a[b], f32(eps), p, f32(tol), 100)
+        lam, Q = np.linalg.eigh(a[b].astype(np.float64))
+        exact = (Q * (lam + f32(eps)) ** (-1.0 / p)) @ Q.T
+        worst = max(worst, rel(x[b], X), rel(x[b], exact))
+        # the float32 iteration may end one step early (its norm reaches the float32 floor)
+        assert k - 2 <= iters[b] <= k, (iters[b], k)
+        assert np.array_equal(x[b], x[b].T)
+    say(f"    worst rel error {worst:.1e}, iterations {iters.tolist()}")
+    assert worst <= TOL_NEWTON_X
+
+
+def test_newton_iteration_cap_and_loose_tolerance():
+    """With a loose tolerance both sides stop by the paper's criterion at the same k; with a
+    cap of 3 both return X_3."""
+    import torch
+    a = wishart_batch(80, 4, 77)
+    dev = torch.from_numpy(a).cuda()
+    x, iters = B.shampoo_root_inverse_newton(dev, 1e-3, 4, 1e-2, 100, True)
+    for b in range(4):
+        X, k, _ = so.root_inverse_newton(a[b], f32(1e-3), 4, f32(1e-2), 100)
+        assert int(iters[b]) == k
+        assert rel(x[b].cpu().numpy(), X) <= 1e-5
+    x, iters = B.shampoo_root_inverse_newton(dev, 1e-3, 4, 1e-6, 3, True)
+    for b in range(4):
+        X, k, _ = so.root_inverse_newton(a[b], f32(1e-3), 4, f32(1e-6), 3)
+        assert int(iters[b]) == 3 == k
+        assert rel(x[b].cpu().numpy(), X) <= 1e-5
+
+
+def test_newton_non_finite_input_keeps_output():
+    import torch
+    a = wishart_batch(40, 3, 78)
+    a[1, 3, 4] = a[1, 4, 3] = np.nan
+    dev = torch.from_numpy(a).cuda()
+    import ctypes
+    x = torch.full_like(dev, 7.0)
+    iters = torch.zeros(3, dtype=torch.int32, device="cuda")
+    failed = torch.zeros(3, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.lib().shampoo_root_inverse_newton_workspace_bytes(40, 3), dtype=torch.uint8, device="cuda")
+    rc = B.lib().shampoo_root_inverse_newton(ctypes.c_void_p(dev.data_ptr()), 40, 3, 1e-3, 4, 1e-6, 50,
+                                             ctypes.c_void_p(x.data_ptr()), ctypes.c_void_p(iters.data_ptr()),
+                                             ctypes.c_void_p(failed.data_ptr()), ctypes.c_void_p(ws.data_ptr()),
+                                             ws.numel(), None)
+    torch.cuda.synchronize()
+    assert rc == 0
+    assert failed.cpu().tolist() == [0, 1, 0]
+    assert bool((x[1] == 7.0).all()) and not bool((x[0] == 7.0).any())
+
+
+def test_optimizer_with_newton_roots():
+    """Wide blocks and a visible epsilon keep the factors within what a float32 iteration
+    resolves; every stage against the oracle running the same iteration in float64."""
+    say("case optimizer newton")
+    shapes = [(32, 256), (20,), (64, 192)]
+    p = Pair(shapes, 64, 0.99, 2, eps=1e-6, newton=(1e-6, 60))
+    for t in range(5):
+        p.step(wl.gaussian_grads(shapes, 61, t, 1e-2), 0.01, t)
+        p.check(t)
+    assert p.gpu.status()["failed_roots"] == 0

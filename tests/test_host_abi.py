@@ -92,6 +92,9 @@ def test_workspace_holds_the_state_of_the_memory_rule():
     (dict(start_preconditioning_step=-1), -3), (dict(graft_epsilon=-1.0), -3),
     (dict(momentum=1.0), -3), (dict(momentum=-0.1), -3), (dict(grad_dtype=7), -3),
     (dict(beta1=1.0), -3), (dict(beta1=-0.5), -3), (dict(weight_decay=-1.0), -3), (dict(grafting_type=5), -3),
+    (dict(root_method=3), -3), (dict(root_method=B.ROOT_NEWTON, newton_tolerance=-1.0), -3),
+    (dict(root_method=B.ROOT_NEWTON, newton_max_iterations=5000), -3),
+    (dict(root_method=B.ROOT_NEWTON, root_exponent=1.0 / 3.0), -7),
 ])
 def test_bad_hyperparameters_are_rejected(kw, code):
     cfg = cfg_for([(8, 8)], 4, **kw)
@@ -119,6 +122,9 @@ def test_bad_shapes_are_rejected():
     assert L.shampoo_get(None, 0, 0, 0, None, 0, None) == -1
     assert L.shampoo_root_inverse_workspace_bytes(0, 1) == 0
     assert L.shampoo_root_inverse_workspace_bytes(1024, 4) > 2 * 4 * 1024 * 1024 * 4
+    assert L.shampoo_root_inverse_newton_workspace_bytes(0, 1) == 0
+    assert L.shampoo_root_inverse_newton_workspace_bytes(1024, 4) >= 7 * 4 * 1024 * 1024 * 4
+    assert L.shampoo_root_inverse_newton(None, 8, 1, 1e-6, 4, 1e-6, 10, None, None, None, None, 0, None) == -1
     out = ctypes.c_void_p()
     # create checks the workspace before touching any device
     assert L.shampoo_create(ctypes.byref(cfg_for([(8, 8)], 4)), None, 0, None, ctypes.byref(out)) == -4
