@@ -42,6 +42,9 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (x2.0 / x1.0):
 # profiles/transformer_b1024_hbm_traffic_pmc.md
 TRAFFIC_BYTES = {"transformer": 14.43e9 + 4.83e9}
+# the same for the single-workgroup block-step kernel on the ResNet-50 shapes:
+# profiles/resnet50_b128_hbm_traffic_pmc.md
+FUSED_TRAFFIC_BYTES = {"resnet50": 0.849e9 + 0.631e9}
 PEAK_HBM_GBS = 8000.0
 TILE = 128
 
@@ -235,7 +238,7 @@ def main():
         f_launch_ms = fused_ms / fused_launches
         gbs = bytes_per_launch / (f_launch_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": gbs / PEAK_HBM_GBS, "traffic": None,
+                    "frac": gbs / PEAK_HBM_GBS, "traffic": FUSED_TRAFFIC_BYTES.get(args.workload),
                     "kernel": "block_step_small_kernel (whole step of a block <= 128 x 128 in one workgroup)",
                     "launch_ms": f_launch_ms, "bytes_per_launch": bytes_per_launch}
     out = {

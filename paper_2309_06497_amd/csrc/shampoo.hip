@@ -240,7 +240,10 @@ int launch_fill(float *p, float v, int64_t n, hipStream_t s) {
   return SHAMPOO_OK;
 }
 
-constexpr int JAC_STREAMS = 3;   // sub-chunks of the block solver that run concurrently
+#ifndef SHAMPOO_JAC_STREAMS
+#define SHAMPOO_JAC_STREAMS 4
+#endif
+constexpr int JAC_STREAMS = SHAMPOO_JAC_STREAMS;   // sub-chunks of the block solver that run concurrently
 
 struct AuxStreams {
   hipStream_t stream[JAC_STREAMS - 1];
