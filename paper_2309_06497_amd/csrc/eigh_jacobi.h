@@ -491,13 +491,51 @@ __device__ __forceinline__ void load_rotation_regs(float (&jr)[32], const float 
     }
 }
 
+// One 32 x 32 sub-block of W on its way to / from the LDS tile X (64 x 64, stride APP_LD),
+// split into a global -> register half and a register -> LDS half so that the global loads
+// of the next pair-block can be in flight while the current one is multiplied.
+// (ra, cb): block row / column of the quadrant as the product sees it; (xi, xj): its origin
+// inside X.  The sub-block lives in W at (max, min); when ra < cb it is used transposed.
+__device__ __forceinline__ void sub_fetch(const double *w, int np, int ra, int cb, int tid, double r[4]) {
+  const bool tr = ra < cb;
+  const int gr0 = (tr ? cb : ra) * JAC_NB, gc0 = (tr ? ra : cb) * JAC_NB;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int idx = tid + JAC_THREADS * e;
+    r[e] = w[(int64_t)(gr0 + (idx >> 5)) * np + gc0 + (idx & 31)];
+  }
+}
+__device__ __forceinline__ void sub_stash(double *X, int ra, int cb, int xi, int xj, int tid, const double r[4]) {
+  const bool tr = ra < cb;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int idx = tid + JAC_THREADS * e;
+    const int ii = idx >> 5, jj = idx & 31;
+    if (tr) X[(xi + jj) * APP_LD + xj + ii] = r[e]; else X[(xi + ii) * APP_LD + xj + jj] = r[e];
+  }
+}
+
+#ifndef SHAMPOO_APPW_SEG
+#define SHAMPOO_APPW_SEG 4
+#endif
+constexpr int APPW_SEG = SHAMPOO_APPW_SEG;   // pair-blocks of one block row handled by one workgroup
+
+// number of workgroups per matrix: row k of the lower triangle has k + 1 pair-blocks
+inline int appw_segments(int hp) {
+  int s = 0;
+  for (int k = 0; k < hp; ++k) s += (k + 1 + APPW_SEG - 1) / APPW_SEG;
+  return s;
+}
+
 // W_kl <- J_k^T W_kl J_l for the pair-blocks l <= k of one matrix, in float64 on the
-// matrix cores.  grid (hp (hp + 1) / 2, batch).  Wavefront (wi, wj) owns the 32 x 32
-// quadrant as 2 x 2 tiles of 16 x 16; a 16x16x4 MFMA takes A(i, k) from lane
-// (i = lane % 16, k = lane / 16), B(k, j) likewise, and leaves D(4 (lane / 16) + v, lane % 16)
-// in element v of the lane's result.  Only the W tile lives in LDS (35 KB, 3 workgroups
-// per CU); the rotation operands sit in registers.
-__global__ __launch_bounds__(JAC_THREADS, 3) void blockjac_apply_w_kernel(const BlockJacArgs g) {
+// matrix cores.  grid (appw_segments(hp), batch): a workgroup walks up to APPW_SEG
+// consecutive pair-blocks of block row k.  J_k stays in registers for the whole walk, and
+// while one pair-block is multiplied the W tile of the next one is already being fetched
+// into registers (its J_l follows as soon as the current one has been consumed), so the HBM latency is paid once per workgroup rather than
+// once per pair-block.  Wavefront (wi, wj) owns the 32 x 32 quadrant as 2 x 2 tiles of
+// 16 x 16; a 16x16x4 MFMA takes A(i, k) from lane (i = lane % 16, k = lane / 16), B(k, j)
+// likewise, and leaves D(4 (lane / 16) + v, lane % 16) in element v of the lane's result.
+__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const BlockJacArgs g) {
   __shared__ __align__(32) double X[JAC_PIV * APP_LD];   // W_kl, then (J_k^T W_kl)^T, then the result
   const int b = blockIdx.y;
   if (g.failed[b]) return;
@@ -507,88 +545,128 @@ __global__ __launch_bounds__(JAC_THREADS, 3) void blockjac_apply_w_kernel(const 
   const int wi = wave >> 1, wj = wave & 1;
   const int32_t *ident = g.ident + b * hp;
   const float *jb = g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV;
-  // lower-triangular pair-block index: blockIdx.x = k (k + 1) / 2 + l, l <= k
-  int k = (int)((sqrtf(8.f * (float)blockIdx.x + 1.f) - 1.f) * 0.5f);
-  while ((k + 1) * (k + 2) / 2 <= (int)blockIdx.x) ++k;
-  while (k * (k + 1) / 2 > (int)blockIdx.x) --k;
-  const int l = blockIdx.x - k * (k + 1) / 2;
-  if (ident[k] && ident[l]) return;
+  // segment -> (k, first l)
+  int seg = blockIdx.x, k = 0;
+  for (;;) {
+    const int ns = (k + 1 + APPW_SEG - 1) / APPW_SEG;
+    if (seg < ns) break;
+    seg -= ns; ++k;
+  }
+  const int l_first = seg * APPW_SEG, l_end = min(l_first + APPW_SEG, k + 1);
+  const bool idk = ident[k] != 0;
+  // the pair-blocks of this walk that rotate at all, in order (uniform across the workgroup)
+  auto next_active = [&](int from) {
+    int l = from;
+    while (l < l_end && idk && ident[l] != 0) ++l;
+    return l;
+  };
+  int l = next_active(l_first);
+  if (l >= l_end) return;
   double *w = g.w + (int64_t)b * np * np;
-  int pk, qk, pl, ql;
+  int pk, qk;
   rr_pair(nblk, g.round, k, pk, qk);
-  rr_pair(nblk, g.round, l, pl, ql);
 
-  float jr[32];
-  load_rotation_regs(jr, jb, k, ident[k] != 0, wi * 32, lane);
-  copy_subblock<true>(w, np, X, pk, pl, 0, 0, tid);
-  copy_subblock<true>(w, np, X, pk, ql, 0, JAC_NB, tid);
-  copy_subblock<true>(w, np, X, qk, pl, JAC_NB, 0, tid);
-  copy_subblock<true>(w, np, X, qk, ql, JAC_NB, JAC_NB, tid);
-  __syncthreads();
-
+  float jk[32], jl[32];
+  double wt[4][4];
   const int li = lane & 15, lk = lane >> 4;
-  doublex4 acc[2][2];
-  // T = J_k^T X :  A(i, kk) = Jk[kk][i], B(kk, j) = X[kk][j]
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    const int row = (4 * q + lk) * APP_LD;
-    const double a0 = (double)jr[2 * q], a1 = (double)jr[2 * q + 1];
-    const double b0 = X[row + wj * 32 + li], b1 = X[row + wj * 32 + 16 + li];
-    acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
-    acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
-    acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
-    acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+  load_rotation_regs(jk, jb, k, idk, wi * 32, lane);
+  {
+    int pl, ql;
+    rr_pair(nblk, g.round, l, pl, ql);
+    sub_fetch(w, np, pk, pl, tid, wt[0]);
+    sub_fetch(w, np, pk, ql, tid, wt[1]);
+    sub_fetch(w, np, qk, pl, tid, wt[2]);
+    sub_fetch(w, np, qk, ql, tid, wt[3]);
+    load_rotation_regs(jl, jb, l, ident[l] != 0, wj * 32, lane);
   }
-  load_rotation_regs(jr, jb, l, ident[l] != 0, wj * 32, lane);   // in flight during the LDS exchange
-  __syncthreads();   // all reads of X done
-  // X <- T^T : lane holds T(i0 .. i0+3, j)
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int i0 = wi * 32 + a * 16 + 4 * lk, j = wj * 32 + e * 16 + li;
-      *reinterpret_cast<doublex4 *>(&X[j * APP_LD + i0]) = acc[a][e];
+  for (bool first = true; l < l_end; first = false) {
+    const int ln = next_active(l + 1);   // l_end if this is the last one
+    int pl, ql;
+    rr_pair(nblk, g.round, l, pl, ql);
+    if (!first) __syncthreads();   // the previous result has left X
+    sub_stash(X, pk, pl, 0, 0, tid, wt[0]);
+    sub_stash(X, pk, ql, 0, JAC_NB, tid, wt[1]);
+    sub_stash(X, qk, pl, JAC_NB, 0, tid, wt[2]);
+    sub_stash(X, qk, ql, JAC_NB, JAC_NB, tid, wt[3]);
+    __syncthreads();
+    if (ln < l_end) {               // next W tile: in flight during the products below
+      int pn, qn;
+      rr_pair(nblk, g.round, ln, pn, qn);
+      sub_fetch(w, np, pk, pn, tid, wt[0]);
+      sub_fetch(w, np, pk, qn, tid, wt[1]);
+      sub_fetch(w, np, qk, pn, tid, wt[2]);
+      sub_fetch(w, np, qk, qn, tid, wt[3]);
     }
-  __syncthreads();
-  // C = T J_l :  A(i, kk) = X[kk][i] (= T[i][kk]), B(kk, j) = Jl[kk][j]
+    doublex4 acc[2][2];
+    // T = J_k^T X :  A(i, kk) = Jk[kk][i], B(kk, j) = X[kk][j]
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
+      for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    const int row = (4 * q + lk) * APP_LD;
-    const double a0 = X[row + wi * 32 + li], a1 = X[row + wi * 32 + 16 + li];
-    const double b0 = (double)jr[2 * q], b1 = (double)jr[2 * q + 1];
-    acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
-    acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
-    acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
-    acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
-  }
-  __syncthreads();   // all reads of X (= T^T) done
-  // X <- C.  On the diagonal pair-block (k == l) only the lower half of C is kept and
-  // mirrored, so that the diagonal sub-blocks stay exactly symmetric.
+    for (int q = 0; q < 16; ++q) {
+      const int row = (4 * q + lk) * APP_LD;
+      // widened at the point of use: kept as float64 across the walk, J_k alone would hold 64 registers
+      float f0 = jk[2 * q], f1 = jk[2 * q + 1];
+      asm volatile("" : "+v"(f0), "+v"(f1));
+      const double a0 = (double)f0, a1 = (double)f1;
+      const double b0 = X[row + wj * 32 + li], b1 = X[row + wj * 32 + 16 + li];
+      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+    }
+    __syncthreads();   // all reads of X done
+    // X <- T^T : lane holds T(i0 .. i0+3, j)
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      const int j = wj * 32 + e * 16 + li;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int i = wi * 32 + a * 16 + 4 * lk + v;
-        if (k != l) X[i * APP_LD + j] = acc[a][e][v];
-        else if (j <= i) { X[i * APP_LD + j] = acc[a][e][v]; X[j * APP_LD + i] = acc[a][e][v]; }
+      for (int e = 0; e < 2; ++e) {
+        const int i0 = wi * 32 + a * 16 + 4 * lk, j = wj * 32 + e * 16 + li;
+        *reinterpret_cast<doublex4 *>(&X[j * APP_LD + i0]) = acc[a][e];
       }
+    __syncthreads();
+    // C = T J_l :  A(i, kk) = X[kk][i] (= T[i][kk]), B(kk, j) = Jl[kk][j]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int row = (4 * q + lk) * APP_LD;
+      const double a0 = X[row + wi * 32 + li], a1 = X[row + wi * 32 + 16 + li];
+      float f0 = jl[2 * q], f1 = jl[2 * q + 1];
+      asm volatile("" : "+v"(f0), "+v"(f1));
+      const double b0 = (double)f0, b1 = (double)f1;
+      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
     }
-  __syncthreads();
-  copy_subblock<false>(w, np, X, pk, pl, 0, 0, tid);
-  copy_subblock<false>(w, np, X, qk, pl, JAC_NB, 0, tid);
-  copy_subblock<false>(w, np, X, qk, ql, JAC_NB, JAC_NB, tid);
-  if (k != l) copy_subblock<false>(w, np, X, pk, ql, 0, JAC_NB, tid);   // (pk, qk) is the mirror of (qk, pk)
+    // the next J_l: in flight during the write-back and the first product of the next pair-block
+    if (ln < l_end) load_rotation_regs(jl, jb, ln, ident[ln] != 0, wj * 32, lane);
+    __syncthreads();   // all reads of X (= T^T) done
+    // X <- C.  On the diagonal pair-block (k == l) only the lower half of C is kept and
+    // mirrored, so that the diagonal sub-blocks stay exactly symmetric.
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int j = wj * 32 + e * 16 + li;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int i = wi * 32 + a * 16 + 4 * lk + v;
+          if (k != l) X[i * APP_LD + j] = acc[a][e][v];
+          else if (j <= i) { X[i * APP_LD + j] = acc[a][e][v]; X[j * APP_LD + i] = acc[a][e][v]; }
+        }
+      }
+    __syncthreads();
+    copy_subblock<false>(w, np, X, pk, pl, 0, 0, tid);
+    copy_subblock<false>(w, np, X, qk, pl, JAC_NB, 0, tid);
+    copy_subblock<false>(w, np, X, qk, ql, JAC_NB, JAC_NB, tid);
+    if (k != l) copy_subblock<false>(w, np, X, pk, ql, 0, JAC_NB, tid);   // (pk, qk) is the mirror of (qk, pk)
+    l = ln;
+  }
 }
 
 // 64 x 64 x 64 float32 product on one workgroup: wavefront (wi, wj) computes the 32 x 32

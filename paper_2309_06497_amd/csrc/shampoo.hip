@@ -293,11 +293,12 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   ja.np = np;
   ja.inner_sweeps = JAC_INNER_SWEEPS;
   ja.tol_rel = JAC_BLOCK_TOL_REL;
+  const int appw_seg = appw_segments(hp);
   for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
     for (int rd = 0; rd < nblk - 1; ++rd) {
       ja.round = rd; ja.sweep = sw;
       hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
-      hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(hp * (hp + 1) / 2, cnt), dim3(JAC_THREADS), 0, s, ja);
+      hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
       hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES), cnt),
                          dim3(JAC_THREADS), 0, s, ja);
     }
