@@ -19,6 +19,7 @@ weight decay, no momentum):
     1. L <- beta2 L + (1-beta2) G G^T,  R <- beta2 R + (1-beta2) G^T G
        (plain sums when beta2 == 1; L = R = 0 initially)      [Sec. 3.1.1 EMA eqs]
     2. AdaGrad grafting: A <- A + G*G elementwise (SGD grafting has no state)  [Sec. 2.4]
+       RMSprop / Adam grafting: A <- beta_g A + (1 - beta_g) G*G           [Sec. 2.2 EMA eq.]
     3. if t >= start and t % f == 0:
          Lbar <- rootinv(L), Rbar <- rootinv(R)                [Sec. 3.2.1 framed box;
          or, on request, the coupled inverse Newton iteration of the same section]
@@ -26,7 +27,8 @@ weight decay, no momentum):
     4. if beta1 > 0: Gf <- beta1 Gf + (1-beta1) G (Gf = 0 initially), else Gf = G.
        The grafting state above uses G, every direction below uses Gf
        (with bias correction and beta1 > 0: Gf / (1 - beta1^(t+1)))      [Sec. 3.1.1]
-    5. P_graft = Gf / (sqrt(A) + eps_graft)  (AdaGrad)  or  Gf  (SGD)    [Sec. 2.4]
+    5. P_graft = Gf / (sqrt(A) + eps_graft)  (AdaGrad, RMSprop)  or  Gf  (SGD)    [Sec. 2.4]
+       Adam grafting with bias correction: A / (1 - beta_g^(t+1)) under the root
     6. if t >= start: P = -||P_graft||_F * Lbar Gf Rbar / ||Lbar Gf Rbar||_F
        else:          P = -P_graft                             [Sec. 2.4 grafting eq.]
     7. if weight_decay > 0 and decoupled: P <- P - weight_decay * W      [Sec. 3.1.2 eqs]
@@ -54,14 +56,19 @@ Readings of the paper taken here (each also listed in the design notes):
   * Decoupled weight decay enters as P <- P - weight_decay * W: the complete
     pseudocode prints a plus sign, but its P already carries the minus sign of the
     step (W <- W + lr P), and the text equations give W_{t+1} = (1 - lr wd) W_t - ....
-  * 1-D parameters keep diagonal AdaGrad whatever the grafting type of the blocks.
+  * 1-D parameters run the diagonal method that the blocks graft from (AdaGrad, RMSprop or
+    Adam; Sec. 4.2.2 offers exactly these in place of Shampoo), and AdaGrad under SGD grafting.
+  * RMSprop and Adam grafting differ only in the bias correction of the second moment,
+    which Adam applies when bias correction is on; gradient filtering (beta1) is the
+    optimizer-wide heuristic of Sec. 3.1.1 for every grafting type.
 
 Pins: see tests/test_oracle_pins.py (Kronecker brute force, X^4 (L+eps I) = I,
 diagonal closed forms, polar factor at t = 0, textbook AdaGrad, geometric
 momentum and Nesterov sums, trace identities, independent Jacobi eigensolver,
 geometric weight decay, l2 as a shifted gradient, constant-gradient filtering,
 SGD-graft step length, bias correction under a constant gradient, coupled Newton against
-the spectral definition and scalar closed forms).
+the spectral definition and scalar closed forms, RMSprop / Adam grafting against textbook
+RMSprop and Adam on 1-D parameters).
 """
 import numpy as np
 
@@ -102,6 +109,12 @@ def graft_state_update(A, G):
     """AdaGrad grafting state: running sum of squared gradients (Sec. 2.4)."""
     G = np.asarray(G, dtype=np.float64)
     return A + G * G
+
+
+def graft_state_update_ema(A, G, beta_g):
+    """RMSprop / Adam second moment: exponential moving average of squared gradients (Sec. 2.2)."""
+    G = np.asarray(G, dtype=np.float64)
+    return beta_g * A + (1.0 - beta_g) * G * G
 
 
 def graft_direction(G, A, eps_graft):
@@ -182,7 +195,7 @@ class ShampooOracle:
                  graft_epsilon=1e-10, momentum=0.0, beta1=0.0, weight_decay=0.0,
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting="adagrad",
                  use_bias_correction=False, root_method="eigh", newton_tolerance=1e-6,
-                 newton_max_iterations=100):
+                 newton_max_iterations=100, grafting_beta2=0.999):
         self.shapes = [tuple(int(x) for x in s) for s in shapes]
         self.b = int(block_size)
         self.beta2 = float(beta2)
@@ -202,9 +215,10 @@ class ShampooOracle:
         self.root_method = root_method
         self.newton_tol = float(newton_tolerance)
         self.newton_max_iter = int(newton_max_iterations)
-        if grafting not in ("adagrad", "sgd"):
-            raise ValueError("grafting must be 'adagrad' or 'sgd'")
+        if grafting not in ("adagrad", "sgd", "rmsprop", "adam"):
+            raise ValueError("grafting must be 'adagrad', 'sgd', 'rmsprop' or 'adam'")
         self.grafting = grafting
+        self.beta_g = float(grafting_beta2)
         self.blocks = []      # per param: list of (r0, c0, m, n) (empty for 1-D)
         self.L, self.R, self.Lbar, self.Rbar = [], [], [], []
         self.A, self.M, self.Gf = [], [], []
@@ -239,6 +253,17 @@ class ShampooOracle:
                                        self.newton_max_iter)[0]
         return root_inverse(F, self.epsilon, self.r)[0]
 
+    def _graft_state(self, A, G):
+        if self.grafting in ("rmsprop", "adam"):
+            return graft_state_update_ema(A, G, self.beta_g)
+        return graft_state_update(A, G)
+
+    def _second_moment(self, A, t):
+        """What goes under the square root of the grafted direction."""
+        if self.grafting == "adam" and self.bias_correction and self.beta_g < 1.0:
+            return A / (1.0 - self.beta_g ** (t + 1))
+        return A
+
     def _finish(self, i, sl, P, W, lr):
         """Steps 7-9 on one block / vector: decoupled decay, momentum, update."""
         if self.wd > 0.0 and self.decoupled:
@@ -269,8 +294,8 @@ class ShampooOracle:
             else:
                 Gf = G
             if len(s) == 1:
-                self.A[i] = graft_state_update(self.A[i], G)
-                P = -graft_direction(Gf, self.A[i], self.eps_g)
+                self.A[i] = self._graft_state(self.A[i], G)
+                P = -graft_direction(Gf, self._second_moment(self.A[i], t), self.eps_g)
                 self._finish(i, slice(None), P, W, lr)
                 continue
             for k, (r0, c0, m, n) in enumerate(self.blocks[i]):
@@ -278,13 +303,13 @@ class ShampooOracle:
                 Gb, Gfb = G[sl], Gf[sl]
                 self.L[i][k], self.R[i][k] = factor_update(
                     self.L[i][k], self.R[i][k], Gb, self.beta2)
-                if self.grafting == "adagrad":
-                    self.A[i][sl] = graft_state_update(self.A[i][sl], Gb)
+                if self.grafting != "sgd":
+                    self.A[i][sl] = self._graft_state(self.A[i][sl], Gb)
                 if refresh:
                     self.Lbar[i][k] = self._root(c2 * self.L[i][k])
                     self.Rbar[i][k] = self._root(c2 * self.R[i][k])
-                if self.grafting == "adagrad":
-                    Pg = graft_direction(Gfb, self.A[i][sl], self.eps_g)
+                if self.grafting != "sgd":
+                    Pg = graft_direction(Gfb, self._second_moment(self.A[i][sl], t), self.eps_g)
                 else:
                     Pg = Gfb.copy()
                 self.s_g[i][k] = float(np.sum(Pg * Pg))

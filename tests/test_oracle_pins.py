@@ -632,3 +632,54 @@ def test_optimizer_with_newton_roots_matches_eigh_roots_when_well_conditioned():
         b.step(Wb, g, 0.1, t)
     assert np.allclose(Wa[0], Wb[0], rtol=1e-7, atol=1e-10)
     assert np.allclose(a.Rbar[0][0], b.Rbar[0][0], rtol=1e-7, atol=1e-9)
+
+
+# ---------------------------------------------------------------------------
+# RMSprop / Adam grafting (Sec. 2.2 EMA equation, Sec. 2.4)
+# ---------------------------------------------------------------------------
+def test_adam_grafting_on_a_vector_is_textbook_adam():
+    """1-D parameter, Adam grafting, beta1 filtering, bias correction: the update is Adam's,
+    w -= lr * mhat / (sqrt(vhat) + eps), written out with scalars."""
+    n, b1, b2, lr, eg = 7, 0.9, 0.99, 0.01, 1e-8
+    r = rng(70)
+    opt = make_opt([(n,)], beta1=b1, graft_epsilon=eg, grafting="adam", grafting_beta2=b2,
+                   use_bias_correction=True)
+    W = [np.zeros(n)]
+    w = np.zeros(n); m = np.zeros(n); v = np.zeros(n)
+    for t in range(6):
+        g = r.standard_normal(n)
+        opt.step(W, [g], lr, t)
+        for i in range(n):
+            m[i] = b1 * m[i] + (1 - b1) * g[i]
+            v[i] = b2 * v[i] + (1 - b2) * g[i] * g[i]
+            w[i] -= lr * (m[i] / (1 - b1 ** (t + 1))) / (np.sqrt(v[i] / (1 - b2 ** (t + 1))) + eg)
+        assert np.allclose(W[0], w, rtol=1e-13, atol=1e-16)
+
+
+def test_rmsprop_grafting_on_a_vector_is_textbook_rmsprop():
+    n, b2, lr, eg = 5, 0.9, 0.05, 1e-8
+    r = rng(71)
+    opt = make_opt([(n,)], graft_epsilon=eg, grafting="rmsprop", grafting_beta2=b2, use_bias_correction=True)
+    W = [np.zeros(n)]
+    w = np.zeros(n); v = np.zeros(n)
+    for t in range(5):
+        g = r.standard_normal(n)
+        opt.step(W, [g], lr, t)
+        v = b2 * v + (1 - b2) * g * g          # no bias correction for RMSprop
+        w = w - lr * g / (np.sqrt(v) + eg)
+        assert np.allclose(W[0], w, rtol=1e-13, atol=1e-16)
+
+
+def test_rmsprop_grafting_sets_the_block_step_length():
+    """2-D block: the step has the Frobenius norm of the RMSprop direction of that block and the
+    orientation of the Shampoo direction (Sec. 2.4); at t = 0 with beta2 = 1: U V^T."""
+    m, n, b2, lr = 5, 4, 0.5, 0.3
+    G = rng(72).standard_normal((m, n))
+    U, S, Vt = np.linalg.svd(G, full_matrices=False)
+    opt = make_opt([(m, n)], epsilon=1e-14, graft_epsilon=0.0, grafting="rmsprop", grafting_beta2=b2)
+    W = [np.zeros((m, n))]
+    opt.step(W, [G], lr, 0)
+    # A_0 = (1 - b2) G^2, so P_graft = sign(G) / sqrt(1 - b2) and ||P_graft||_F = sqrt(m n / (1 - b2))
+    expect = -lr * np.sqrt(m * n / (1 - b2)) / np.sqrt(min(m, n)) * (U @ Vt)
+    assert np.allclose(W[0], expect, rtol=1e-6, atol=1e-9)
+    assert np.allclose(opt.A[0], (1 - b2) * G * G)
