@@ -47,7 +47,7 @@ enum {
 };
 
 enum { SHAMPOO_GRAD_F32 = 0, SHAMPOO_GRAD_BF16 = 1 };
-enum { SHAMPOO_GRAFT_ADAGRAD = 0, SHAMPOO_GRAFT_SGD = 1 };
+enum { SHAMPOO_GRAFT_ADAGRAD = 0, SHAMPOO_GRAFT_SGD = 1, SHAMPOO_GRAFT_RMSPROP = 2, SHAMPOO_GRAFT_ADAM = 3 };
 enum { SHAMPOO_ROOT_EIGH = 0, SHAMPOO_ROOT_NEWTON = 1 };
 
 /*
@@ -72,8 +72,11 @@ typedef struct {
   float weight_decay;     /* >= 0 (Sec. 3.1.2)                                               */
   int32_t use_decoupled_weight_decay; /* != 0: P <- P - wd W after grafting; 0: G <- G + wd W  */
   int32_t use_nesterov;   /* != 0: W += lr (mu M + P) instead of lr M (Sec. 3.1.3)            */
-  int32_t grafting_type;  /* SHAMPOO_GRAFT_ADAGRAD or SHAMPOO_GRAFT_SGD (P_graft = G) for the
-                             blocks; 1-D parameters always use diagonal AdaGrad              */
+  int32_t grafting_type;  /* SHAMPOO_GRAFT_ADAGRAD (A <- A + G.^2), SHAMPOO_GRAFT_SGD (P_graft = G, no
+                             state), SHAMPOO_GRAFT_RMSPROP / _ADAM (A <- beta_g A + (1-beta_g) G.^2;
+                             Adam divides A by 1 - beta_g^(step+1) when bias correction is on).
+                             1-D parameters run that diagonal method itself (AdaGrad under SGD) */
+  float grafting_beta2;   /* beta_g in (0,1] of RMSprop / Adam grafting; ignored otherwise   */
   int32_t use_bias_correction; /* != 0: directions use Gf / (1 - beta1^(step+1)) and roots are
                              taken of L / (1 - beta2^(step+1)) (beta2 < 1), epsilon added after
                              the division; stored state stays uncorrected (Sec. 3.1.1)        */
@@ -119,7 +122,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
  * calls) of the complete pseudocode for every block of every parameter:
  *   G <- G + wd W   (l2 weight decay only)               (Sec. 3.1.2)
  *   L <- beta2 L + (1-beta2) G G^T, R likewise          (Sec. 3.1.1)
- *   A <- A + G.^2   (AdaGrad grafting)                   (Sec. 2.4)
+ *   A <- A + G.^2   (AdaGrad grafting; EMA for RMSprop / Adam)   (Sec. 2.4, 2.2)
  *   if step >= start and step % f == 0: roots refreshed  (Sec. 3.2.1 box, 4.3)
  *   Gf <- beta1 Gf + (1-beta1) G  (Gf = G when beta1 = 0) (Sec. 3.1.1)
  *       (with bias correction the lines below read Gf / (1 - beta1^(step+1)))

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libshampoo.so")
 
 GRAD_F32, GRAD_BF16 = 0, 1
 GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF = range(9)
-GRAFT_ADAGRAD, GRAFT_SGD = 0, 1
+GRAFT_ADAGRAD, GRAFT_SGD, GRAFT_RMSPROP, GRAFT_ADAM = 0, 1, 2, 3
 ROOT_EIGH, ROOT_NEWTON = 0, 1
 STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG, STAGE_FUSED = range(7)
 STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag", "fused")
@@ -46,6 +46,7 @@ class ShampooConfig(ctypes.Structure):
         ("use_decoupled_weight_decay", ctypes.c_int32),
         ("use_nesterov", ctypes.c_int32),
         ("grafting_type", ctypes.c_int32),
+        ("grafting_beta2", ctypes.c_float),
         ("use_bias_correction", ctypes.c_int32),
         ("root_method", ctypes.c_int32),
         ("newton_tolerance", ctypes.c_float),
@@ -116,7 +117,7 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                 grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
-                newton_tolerance=1e-6, newton_max_iterations=100):
+                newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999):
     """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
     n = len(shapes)
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
@@ -127,7 +128,7 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
     cfg = ShampooConfig(n, ndim, shape, block_size, beta2, epsilon, root_exponent,
                         precondition_frequency, start_preconditioning_step, graft_epsilon,
                         momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
-                        1 if use_nesterov else 0, grafting_type, 1 if use_bias_correction else 0,
+                        1 if use_nesterov else 0, grafting_type, grafting_beta2, 1 if use_bias_correction else 0,
                         root_method, newton_tolerance, newton_max_iterations, grad_dtype, device)
     cfg._keep = (ndim, shape)
     return cfg
@@ -162,14 +163,15 @@ class Shampoo:
                  grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
-                newton_tolerance=1e-6, newton_max_iterations=100):
+                newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999):
         import torch
         self.shapes = [tuple(s) for s in shapes]
         self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
                                precondition_frequency, start_preconditioning_step, graft_epsilon,
                                momentum, grad_dtype, device, beta1, weight_decay,
                                use_decoupled_weight_decay, use_nesterov, grafting_type,
-                               use_bias_correction, root_method, newton_tolerance, newton_max_iterations)
+                               use_bias_correction, root_method, newton_tolerance, newton_max_iterations,
+                               grafting_beta2)
         self.device = torch.device("cuda", device)
         nbytes = shampoo_workspace_bytes(self.cfg)
         if nbytes == 0:

@@ -47,6 +47,7 @@ struct SmallStepArgs {
   float *a_state, *m_state;      // m_state nullptr when mu == 0
   double alpha_d, beta_d;        // factor update weights
   float graft_eps, mu, lr, wd_decoupled;
+  float a_decay, a_gain, a_bc;   // grafting state A <- a_decay A + a_gain G.^2, root of a_bc A
   int32_t nesterov;
 };
 
@@ -206,8 +207,8 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
           const int valid = min(4, n - j);
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            av[u][e] += gv[u][e] * gv[u][e];
-            const float pg = gv[u][e] / (sqrtf(av[u][e]) + g.graft_eps);
+            av[u][e] = g.a_decay * av[u][e] + g.a_gain * (gv[u][e] * gv[u][e]);
+            const float pg = gv[u][e] / (sqrtf(g.a_bc * av[u][e]) + g.graft_eps);
             if (e < valid) ss += pg * pg;
           }
           store_f4(ap + (int64_t)i * ld + j, vec, valid, av[u]);

@@ -36,6 +36,9 @@ struct EwArgs {
   EwGeom geom;
   float graft_eps, mu, lr;
   float gd_scale;                // direction gradients are multiplied by this (bias correction, 1 = off)
+  // grafting state A <- a_decay A + a_gain G.^2 and P_graft = Gf / (sqrt(a_bc A) + eps):
+  // (1, 1, 1) AdaGrad; (beta_g, 1 - beta_g, 1) RMSprop; Adam adds a_bc = 1 / (1 - beta_g^(t+1))
+  float a_decay, a_gain, a_bc;
   float wd_decoupled;            // update_kernel: P <- P - wd_decoupled * W (0 = off)
   int32_t nesterov;              // update_kernel: step with mu M + P instead of M
   int32_t sgd_graft;             // P_graft = G (no grafting state) instead of AdaGrad
@@ -99,8 +102,8 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
       load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        av[e] += gv[e] * gv[e];
-        const float pg = dv[e] / (sqrtf(av[e]) + g.graft_eps);
+        av[e] = g.a_decay * av[e] + g.a_gain * (gv[e] * gv[e]);
+        const float pg = dv[e] / (sqrtf(g.a_bc * av[e]) + g.graft_eps);
         if (e < valid) ss += pg * pg;
       }
       store_f4(ap + (int64_t)i * ld + j, vec, valid, av);
@@ -173,7 +176,7 @@ __global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
         } else {
           load_f4(ap + (int64_t)i * ld + j, vec, valid, av);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) pv[e] = -gv[e] / (sqrtf(av[e]) + g.graft_eps);
+          for (int e = 0; e < 4; ++e) pv[e] = -gv[e] / (sqrtf(g.a_bc * av[e]) + g.graft_eps);
         }
       } else {
         load_f4(pp + (int64_t)i * n + j, vec, valid, pv);
@@ -217,6 +220,7 @@ struct DiagArgs {
   float graft_eps, mu, lr;
   float beta1, wd_l2, wd_decoupled;
   float gd_scale;        // bias correction of the filtered gradient (1 = off)
+  float a_decay, a_gain, a_bc;   // as in EwArgs
   int32_t nesterov;
 };
 
@@ -232,11 +236,11 @@ __global__ __launch_bounds__(EW_THREADS) void diag_kernel(const DiagArgs g) {
     float wv = w[i];
     float gv = Elem<GT>::load1(gp + i);
     if (g.wd_l2 != 0.f) gv += g.wd_l2 * wv;
-    const float av = a[i] + gv * gv;
+    const float av = g.a_decay * a[i] + g.a_gain * (gv * gv);
     a[i] = av;
     float dv = gv;
     if (gf) { dv = g.beta1 * gf[i] + (1.f - g.beta1) * gv; gf[i] = dv; }
-    float p = -(g.gd_scale * dv) / (sqrtf(av) + g.graft_eps);
+    float p = -(g.gd_scale * dv) / (sqrtf(g.a_bc * av) + g.graft_eps);
     if (g.wd_decoupled != 0.f) p -= g.wd_decoupled * wv;
     if (m) {
       const float mv = g.mu * m[i] + p;

@@ -92,7 +92,10 @@ int check_config(const shampoo_config *c) {
   if (c->grad_dtype != SHAMPOO_GRAD_F32 && c->grad_dtype != SHAMPOO_GRAD_BF16) return SHAMPOO_ERR_HYPER;
   if (!(c->beta1 >= 0.f && c->beta1 < 1.f)) return SHAMPOO_ERR_HYPER;
   if (!(c->weight_decay >= 0.f) || !std::isfinite(c->weight_decay)) return SHAMPOO_ERR_HYPER;
-  if (c->grafting_type != SHAMPOO_GRAFT_ADAGRAD && c->grafting_type != SHAMPOO_GRAFT_SGD) return SHAMPOO_ERR_HYPER;
+  if (c->grafting_type < SHAMPOO_GRAFT_ADAGRAD || c->grafting_type > SHAMPOO_GRAFT_ADAM) return SHAMPOO_ERR_HYPER;
+  if ((c->grafting_type == SHAMPOO_GRAFT_RMSPROP || c->grafting_type == SHAMPOO_GRAFT_ADAM) &&
+      !(c->grafting_beta2 > 0.f && c->grafting_beta2 <= 1.f))
+    return SHAMPOO_ERR_HYPER;
   if (c->root_method != SHAMPOO_ROOT_EIGH && c->root_method != SHAMPOO_ROOT_NEWTON) return SHAMPOO_ERR_HYPER;
   if (c->root_method == SHAMPOO_ROOT_NEWTON) {
     if (c->newton_tolerance < 0.f || !std::isfinite(c->newton_tolerance)) return SHAMPOO_ERR_HYPER;
@@ -612,6 +615,12 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   const bool bc = c.use_bias_correction != 0;
   const float c1 = (bc && c.beta1 > 0.f) ? (float)(1.0 / (1.0 - std::pow((double)c.beta1, (double)(step + 1)))) : 1.f;
   const float c2 = (bc && c.beta2 < 1.f) ? (float)(1.0 / (1.0 - std::pow((double)c.beta2, (double)(step + 1)))) : 1.f;
+  // grafting second moment: sum (AdaGrad) or EMA (RMSprop, Adam; Adam bias-corrected on request)
+  const bool ema = c.grafting_type == SHAMPOO_GRAFT_RMSPROP || c.grafting_type == SHAMPOO_GRAFT_ADAM;
+  const float a_decay = ema ? c.grafting_beta2 : 1.f;
+  const float a_gain = (ema && c.grafting_beta2 < 1.f) ? (float)(1.0 - (double)c.grafting_beta2) : 1.f;
+  const float a_bc = (c.grafting_type == SHAMPOO_GRAFT_ADAM && bc && c.grafting_beta2 < 1.f)
+                         ? (float)(1.0 / (1.0 - std::pow((double)c.grafting_beta2, (double)(step + 1)))) : 1.f;
   int rc;
 
   if ((o->use_l2 || o->use_b1) && !p.prep_chunks.empty()) {
@@ -635,6 +644,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     f.alpha_d = alpha; f.beta_d = beta;
     f.graft_eps = c.graft_epsilon; f.mu = c.momentum; f.lr = lr; f.wd_decoupled = wd_dec;
     f.nesterov = c.use_nesterov ? 1 : 0;
+    f.a_decay = a_decay; f.a_gain = a_gain; f.a_bc = a_bc;
     hipLaunchKernelGGL(block_step_small_kernel<GT>, dim3((unsigned)o->n_small), dim3(SB_THREADS), 0, s, f);
     HIP_TRY(hipGetLastError());
   }
@@ -694,6 +704,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       e.sg_partial = reinterpret_cast<float *>(ws + b.off_sgp);
       e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
       e.sgd_graft = sgd; e.same_src = (gs_tab == gd_tab) ? 1 : 0; e.gd_scale = c1;
+      e.a_decay = a_decay; e.a_gain = a_gain; e.a_bc = a_bc;
       hipLaunchKernelGGL((graft_kernel<GS, GD>), dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
       HIP_TRY(hipGetLastError());
     }
@@ -768,6 +779,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       e.p = P; e.scale = scale;
       e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
       e.wd_decoupled = wd_dec; e.nesterov = c.use_nesterov ? 1 : 0; e.sgd_graft = sgd; e.gd_scale = c1;
+      e.a_decay = a_decay; e.a_gain = a_gain; e.a_bc = a_bc;
       e.graft_only = use_shampoo ? 0 : 1;
       hipLaunchKernelGGL(update_kernel<GD>, dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
       HIP_TRY(hipGetLastError());
@@ -780,7 +792,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     d.w_table = wtab; d.g_table = gtab; d.a_state = A; d.m_state = M; d.gf_state = Gf;
     d.graft_eps = c.graft_epsilon; d.mu = c.momentum; d.lr = lr;
     d.beta1 = c.beta1; d.wd_l2 = wd_l2; d.wd_decoupled = wd_dec; d.nesterov = c.use_nesterov ? 1 : 0;
-    d.gd_scale = c1;
+    d.gd_scale = c1; d.a_decay = a_decay; d.a_gain = a_gain; d.a_bc = a_bc;
     hipLaunchKernelGGL(diag_kernel<GT>, dim3((unsigned)p.diag_chunks.size()), dim3(EW_THREADS), 0, s, d);
     HIP_TRY(hipGetLastError());
   }

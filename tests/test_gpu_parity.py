@@ -77,18 +77,20 @@ class Pair:
 
     def __init__(self, shapes, b, beta2, f, start=0, mu=0.9, eps=1e-12, eps_g=1e-10, bf16=False, seed=0,
                  beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad",
-                 bias_correction=False, newton=None):
+                 bias_correction=False, newton=None, grafting_beta2=0.999):
         self.shapes = shapes
         self.bf16 = bf16
         self.f, self.start, self.eps = f, start, f32(eps)
         self.gpu = B.Shampoo(shapes, b, beta2, eps, 0.25, f, start, eps_g, mu,
                              B.GRAD_BF16 if bf16 else B.GRAD_F32, 0, beta1, weight_decay, decoupled, nesterov,
-                             B.GRAFT_SGD if grafting == "sgd" else B.GRAFT_ADAGRAD, bias_correction,
-                             B.ROOT_NEWTON if newton else B.ROOT_EIGH, *(newton or (1e-6, 100)))
+                             {"adagrad": B.GRAFT_ADAGRAD, "sgd": B.GRAFT_SGD, "rmsprop": B.GRAFT_RMSPROP,
+                              "adam": B.GRAFT_ADAM}[grafting], bias_correction,
+                             B.ROOT_NEWTON if newton else B.ROOT_EIGH, *(newton or (1e-6, 100)), grafting_beta2)
         self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, start, f32(eps_g), f32(mu),
                                     f32(beta1), f32(weight_decay), decoupled, nesterov, grafting,
                                     bias_correction, "newton" if newton else "eigh",
-                                    *((f32(newton[0]), newton[1]) if newton else (1e-6, 100)))
+                                    *((f32(newton[0]), newton[1]) if newton else (1e-6, 100)),
+                                    f32(grafting_beta2))
         self.newton = newton
         w0 = wl.init_params(shapes, seed)
         self.w0 = [w.astype(np.float64) for w in w0]
@@ -523,3 +525,15 @@ def test_optimizer_with_newton_roots():
         p.step(wl.gaussian_grads(shapes, 61, t, 1e-2), 0.01, t)
         p.check(t)
     assert p.gpu.status()["failed_roots"] == 0
+
+
+@pytest.mark.parametrize("grafting,bc", [("rmsprop", False), ("adam", True), ("adam", False)])
+def test_rmsprop_and_adam_grafting(grafting, bc):
+    """EMA second moment (Sec. 2.2) as the grafted method; blocks above 128 take the
+    stage-by-stage kernels, the others the single-workgroup kernel between refreshes."""
+    say(f"case {grafting} grafting bc={bc}")
+    shapes = [(96, 80), (33,), (160, 192)]
+    p = Pair(shapes, 160, 0.999, 2, eps=1e-6, grafting=grafting, grafting_beta2=0.95, bias_correction=bc)
+    for t in range(5):
+        p.step(wl.gaussian_grads(shapes, 80, t, 1e-2), 0.01, t)
+        p.check(t)
