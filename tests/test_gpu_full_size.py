@@ -171,3 +171,17 @@ def test_resnet50_shapes_every_block():
         if t in (0, 1, 3, 4):
             p.check(t)
     assert p.gpu.status() == {"refreshes": 2, "failed_roots": 0}
+
+
+@pytest.mark.gpu
+def test_block_size_2048():
+    """Sec. 4.2.1 / Table 5 use preconditioner blocks up to 8192; one 2048 x 2048 block exercises
+    16 x 16 tiles per GEMM and the blocked eigensolver at n = 2048 inside the optimizer."""
+    from test_gpu_parity import Pair, say
+    say("case block 2048")
+    shapes = [(2048, 2048), (2048,)]
+    p = Pair(shapes, 2048, 0.999, 2, bf16=True)
+    for t in range(3):
+        p.step(wl.gaussian_grads(shapes, 90, t, 1e-3), 0.01, t)
+        p.check(t)
+    assert p.gpu.status() == {"refreshes": 2, "failed_roots": 0}
