@@ -37,6 +37,13 @@ weight decay, no momentum):
   1-D parameters take steps 0, 2 (always AdaGrad), 4, P = -Gf / (sqrt(A) + eps_graft),
   7, 8, 9 (diagonal AdaGrad, Sec. 2.2 / Sec. 4.2.2).
 
+  A 2-D parameter with a dimension above the block size is, by large_dim_method (Sec. 4.2):
+    "blocking"  cut into blocks as above (Sec. 4.2.1);
+    "adagrad"   handled like a 1-D parameter, i.e. by the diagonal method (Sec. 4.2.2);
+    "diagonal"  kept whole, with the factor of every dimension above the block size
+                replaced by its diagonal: l_i <- beta2 l_i + (1-beta2) sum_j G_ij^2 (likewise
+                r_j), root inverse elementwise by the same framed box (Sec. 4.2.3).
+
 Readings of the paper taken here (each also listed in the design notes):
   * Factors start at zero and epsilon enters only inside the root-inverse
     routine (the complete pseudocode + framed box), not as L_{-1} = eps*I.
@@ -195,7 +202,7 @@ class ShampooOracle:
                  graft_epsilon=1e-10, momentum=0.0, beta1=0.0, weight_decay=0.0,
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting="adagrad",
                  use_bias_correction=False, root_method="eigh", newton_tolerance=1e-6,
-                 newton_max_iterations=100, grafting_beta2=0.999):
+                 newton_max_iterations=100, grafting_beta2=0.999, large_dim_method="blocking"):
         self.shapes = [tuple(int(x) for x in s) for s in shapes]
         self.b = int(block_size)
         self.beta2 = float(beta2)
@@ -219,6 +226,11 @@ class ShampooOracle:
             raise ValueError("grafting must be 'adagrad', 'sgd', 'rmsprop' or 'adam'")
         self.grafting = grafting
         self.beta_g = float(grafting_beta2)
+        if large_dim_method not in ("blocking", "adagrad", "diagonal"):
+            raise ValueError("large_dim_method must be 'blocking', 'adagrad' or 'diagonal'")
+        self.large_dim_method = large_dim_method
+        # per 2-D parameter: None (blocked / small), "adagrad", or (L is diagonal, R is diagonal)
+        self.whole = []
         self.blocks = []      # per param: list of (r0, c0, m, n) (empty for 1-D)
         self.L, self.R, self.Lbar, self.Rbar = [], [], [], []
         self.A, self.M, self.Gf = [], [], []
@@ -228,7 +240,26 @@ class ShampooOracle:
             self.A.append(np.zeros(s))
             self.M.append(np.zeros(s))
             self.Gf.append(np.zeros(s))
-            if len(s) == 2:
+            big = len(s) == 2 and (s[0] > self.b or s[1] > self.b)
+            if len(s) == 2 and big and large_dim_method == "adagrad":
+                self.whole.append("adagrad")
+                self.blocks.append([])
+                for lst in (self.L, self.R, self.Lbar, self.Rbar, self.P_sh, self.s_g, self.s_sh):
+                    lst.append([])
+            elif len(s) == 2 and big and large_dim_method == "diagonal":
+                dl, dr = s[0] > self.b, s[1] > self.b
+                self.whole.append((dl, dr))
+                self.blocks.append([(0, 0, s[0], s[1])])
+                # a diagonalised factor is stored as the vector of its diagonal
+                self.L.append([np.zeros(s[0]) if dl else np.zeros((s[0], s[0]))])
+                self.R.append([np.zeros(s[1]) if dr else np.zeros((s[1], s[1]))])
+                self.Lbar.append([np.ones(s[0]) if dl else np.eye(s[0])])
+                self.Rbar.append([np.ones(s[1]) if dr else np.eye(s[1])])
+                self.P_sh.append([None])
+                self.s_g.append([0.0])
+                self.s_sh.append([0.0])
+            elif len(s) == 2:
+                self.whole.append(None)
                 blks = block_partition(s[0], s[1], self.b)
                 self.blocks.append(blks)
                 self.L.append([np.zeros((m, m)) for (_, _, m, n) in blks])
@@ -240,6 +271,7 @@ class ShampooOracle:
                 self.s_g.append([0.0] * len(blks))
                 self.s_sh.append([0.0] * len(blks))
             elif len(s) == 1:
+                self.whole.append(None)
                 self.blocks.append([])
                 for lst in (self.L, self.R, self.Lbar, self.Rbar, self.P_sh,
                             self.s_g, self.s_sh):
@@ -263,6 +295,11 @@ class ShampooOracle:
         if self.grafting == "adam" and self.bias_correction and self.beta_g < 1.0:
             return A / (1.0 - self.beta_g ** (t + 1))
         return A
+
+    def _diag_root(self, d):
+        """The framed box of Sec. 3.2.1 on a diagonal matrix: its eigenvalues are its entries."""
+        lam_new = d - min(d.min(), 0.0) + self.epsilon
+        return lam_new ** (-self.r)
 
     def _finish(self, i, sl, P, W, lr):
         """Steps 7-9 on one block / vector: decoupled decay, momentum, update."""
@@ -293,7 +330,7 @@ class ShampooOracle:
                 Gf = c1 * self.Gf[i]
             else:
                 Gf = G
-            if len(s) == 1:
+            if len(s) == 1 or self.whole[i] == "adagrad":
                 self.A[i] = self._graft_state(self.A[i], G)
                 P = -graft_direction(Gf, self._second_moment(self.A[i], t), self.eps_g)
                 self._finish(i, slice(None), P, W, lr)
@@ -301,6 +338,10 @@ class ShampooOracle:
             for k, (r0, c0, m, n) in enumerate(self.blocks[i]):
                 sl = (slice(r0, r0 + m), slice(c0, c0 + n))
                 Gb, Gfb = G[sl], Gf[sl]
+                if self.whole[i] is not None:
+                    P = self._diagonal_shampoo(i, Gb, Gfb, t, refresh, c2)
+                    self._finish(i, sl, P, W, lr)
+                    continue
                 self.L[i][k], self.R[i][k] = factor_update(
                     self.L[i][k], self.R[i][k], Gb, self.beta2)
                 if self.grafting != "sgd":
@@ -321,3 +362,26 @@ class ShampooOracle:
                 else:
                     P = -Pg
                 self._finish(i, sl, P, W, lr)
+
+    def _diagonal_shampoo(self, i, G, Gf, t, refresh, c2):
+        """Sec. 4.2.3 on a whole parameter: factors of the large dimensions are diagonal."""
+        dl, dr = self.whole[i]
+        a, b = (self.beta2, 1.0 - self.beta2) if self.beta2 < 1.0 else (1.0, 1.0)
+        GGt_diag = np.sum(G * G, axis=1)           # diag(G G^T)
+        GtG_diag = np.sum(G * G, axis=0)           # diag(G^T G)
+        self.L[i][0] = a * self.L[i][0] + b * (GGt_diag if dl else G @ G.T)
+        self.R[i][0] = a * self.R[i][0] + b * (GtG_diag if dr else G.T @ G)
+        if self.grafting != "sgd":
+            self.A[i] = self._graft_state(self.A[i], G)
+        if refresh:
+            self.Lbar[i][0] = self._diag_root(c2 * self.L[i][0]) if dl else self._root(c2 * self.L[i][0])
+            self.Rbar[i][0] = self._diag_root(c2 * self.R[i][0]) if dr else self._root(c2 * self.R[i][0])
+        Pg = graft_direction(Gf, self._second_moment(self.A[i], t), self.eps_g) if self.grafting != "sgd" else Gf.copy()
+        self.s_g[i][0] = float(np.sum(Pg * Pg))
+        if t < self.start:
+            return -Pg
+        T = self.Lbar[i][0][:, None] * Gf if dl else self.Lbar[i][0] @ Gf
+        Psh = T * self.Rbar[i][0][None, :] if dr else T @ self.Rbar[i][0]
+        self.P_sh[i][0] = Psh
+        self.s_sh[i][0] = float(np.sum(Psh * Psh))
+        return grafted_direction(Psh, Pg)

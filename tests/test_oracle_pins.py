@@ -683,3 +683,74 @@ def test_rmsprop_grafting_sets_the_block_step_length():
     expect = -lr * np.sqrt(m * n / (1 - b2)) / np.sqrt(min(m, n)) * (U @ Vt)
     assert np.allclose(W[0], expect, rtol=1e-6, atol=1e-9)
     assert np.allclose(opt.A[0], (1 - b2) * G * G)
+
+
+# ---------------------------------------------------------------------------
+# Large-dimension methods other than blocking (Sec. 4.2.2, 4.2.3)
+# ---------------------------------------------------------------------------
+def test_adagrad_large_dim_method_is_the_flattened_diagonal_method():
+    """A matrix with a dimension above the block size under "adagrad" steps exactly like the
+    1-D parameter made of its entries; a matrix within the block size is untouched by the option."""
+    shapes = [(6, 3), (3, 3)]
+    a = make_opt(shapes, block_size=4, large_dim_method="adagrad", momentum=0.5)
+    b = make_opt([(18,), (3, 3)], block_size=4, momentum=0.5)
+    Wa = [np.zeros(s) for s in shapes]
+    Wb = [np.zeros(18), np.zeros((3, 3))]
+    for t in range(4):
+        g = [rng(90 + t).standard_normal(s) for s in shapes]
+        a.step(Wa, g, 0.1, t)
+        b.step(Wb, [g[0].reshape(-1), g[1]], 0.1, t)
+    assert np.array_equal(Wa[0].reshape(-1), Wb[0]) and np.array_equal(Wa[1], Wb[1])
+
+
+def test_diagonal_shampoo_both_dimensions_by_hand():
+    """Both dimensions above the block size, beta2 = 1, one step: l_i = sum_j G_ij^2,
+    r_j = sum_i G_ij^2, P_sh_ij = (l_i + eps)^(-1/4) G_ij (r_j + eps)^(-1/4); loops written out."""
+    m, n, eps, lr = 5, 6, 1e-3, 0.1
+    G = rng(95).standard_normal((m, n))
+    opt = make_opt([(m, n)], block_size=4, epsilon=eps, large_dim_method="diagonal")
+    W = [np.zeros((m, n))]
+    opt.step(W, [G], lr, 0)
+    l = [sum(G[i, j] ** 2 for j in range(n)) for i in range(m)]
+    r = [sum(G[i, j] ** 2 for i in range(m)) for j in range(n)]
+    P = np.array([[(l[i] + eps) ** -0.25 * G[i, j] * (r[j] + eps) ** -0.25 for j in range(n)] for i in range(m)])
+    graft = np.sqrt(m * n)            # AdaGrad graft of the first step is sign(G) (eps_g tiny)
+    assert np.allclose(W[0], -lr * graft * P / np.linalg.norm(P), rtol=1e-8)
+    assert np.allclose(opt.L[0][0], l) and np.allclose(opt.R[0][0], r)
+
+
+@pytest.mark.parametrize("shape,dl,dr", [((7, 3), True, False), ((3, 7), False, True)])
+def test_diagonal_shampoo_mixed_equals_full_shampoo_on_diagonalised_factor(shape, dl, dr):
+    """One dimension above the block size: the step equals the full two-factor formula with that
+    factor replaced by its diagonal (Sec. 4.2.3), the other factor being the usual full one."""
+    m, n = shape
+    eps = 1e-4
+    opt = make_opt([shape], block_size=4, epsilon=eps, beta2=0.9, large_dim_method="diagonal", precondition_frequency=1)
+    W = [np.zeros(shape)]
+    L = np.zeros((m, m)); R = np.zeros((n, n)); A = np.zeros(shape)
+    for t in range(3):
+        G = rng(96 + t).standard_normal(shape)
+        before = W[0].copy()
+        opt.step(W, [G], 0.1, t)
+        L = 0.9 * L + 0.1 * G @ G.T
+        R = 0.9 * R + 0.1 * G.T @ G
+        A = A + G * G
+        Lm = np.diag(np.diag(L)) if dl else L
+        Rm = np.diag(np.diag(R)) if dr else R
+        lam, Q = np.linalg.eigh(Lm); Li = (Q * (lam + eps) ** -0.25) @ Q.T
+        lam, Q = np.linalg.eigh(Rm); Ri = (Q * (lam + eps) ** -0.25) @ Q.T
+        Psh = Li @ G @ Ri
+        Pg = G / (np.sqrt(A) + 1e-10)
+        expect = -0.1 * np.linalg.norm(Pg) * Psh / np.linalg.norm(Psh)
+        assert np.allclose(W[0] - before, expect, rtol=1e-9, atol=1e-12)
+
+
+def test_diagonal_method_leaves_small_matrices_alone():
+    shapes = [(4, 3)]
+    a = make_opt(shapes, block_size=4, large_dim_method="diagonal")
+    b = make_opt(shapes, block_size=4)
+    Wa, Wb = [np.zeros((4, 3))], [np.zeros((4, 3))]
+    for t in range(3):
+        g = [rng(99 + t).standard_normal((4, 3))]
+        a.step(Wa, g, 0.1, t); b.step(Wb, g, 0.1, t)
+    assert np.array_equal(Wa[0], Wb[0])
