@@ -49,6 +49,7 @@ enum {
 enum { SHAMPOO_GRAD_F32 = 0, SHAMPOO_GRAD_BF16 = 1 };
 enum { SHAMPOO_GRAFT_ADAGRAD = 0, SHAMPOO_GRAFT_SGD = 1, SHAMPOO_GRAFT_RMSPROP = 2, SHAMPOO_GRAFT_ADAM = 3 };
 enum { SHAMPOO_ROOT_EIGH = 0, SHAMPOO_ROOT_NEWTON = 1 };
+enum { SHAMPOO_LARGE_DIM_BLOCKING = 0, SHAMPOO_LARGE_DIM_ADAGRAD = 1, SHAMPOO_LARGE_DIM_DIAGONAL = 2 };
 
 /*
  * Optimizer configuration (copied at create; the arrays need not outlive the call).
@@ -80,6 +81,12 @@ typedef struct {
   int32_t use_bias_correction; /* != 0: directions use Gf / (1 - beta1^(step+1)) and roots are
                              taken of L / (1 - beta2^(step+1)) (beta2 < 1), epsilon added after
                              the division; stored state stays uncorrected (Sec. 3.1.1)        */
+  int32_t large_dim_method; /* what happens to a 2-D parameter with a dimension above block_size (Sec. 4.2):
+                             SHAMPOO_LARGE_DIM_BLOCKING (default): cut into blocks (Sec. 4.2.1);
+                             SHAMPOO_LARGE_DIM_ADAGRAD: the diagonal method on its entries, as for a
+                             1-D parameter (Sec. 4.2.2);
+                             SHAMPOO_LARGE_DIM_DIAGONAL: kept whole, the factor of each such
+                             dimension replaced by its diagonal (Sec. 4.2.3)                  */
   int32_t root_method;    /* SHAMPOO_ROOT_EIGH: eigendecomposition (framed box of Sec. 3.2.1, default);
                              SHAMPOO_ROOT_NEWTON: coupled inverse Newton iteration of the same
                              section on L + epsilon I, in float32; needs 1/root_exponent in
@@ -96,9 +103,13 @@ typedef struct {
  * parameter is cut into ceil(rows/b) x ceil(cols/b) blocks, all b x b except
  * in the last block row / column.  Blocks of equal (m, n) form a bucket and
  * are numbered (slot) in parameter order, row-major inside a parameter.
- * Writes up to `cap` rows of 8 int64 {param, row0, col0, m, n, bucket, slot, 0}
+ * Writes up to `cap` rows of 8 int64 {param, row0, col0, m, n, bucket, slot, flags}
  * into `table` (host, may be NULL when cap == 0) and the total number of
  * blocks / buckets into *n_blocks / *n_buckets (host, may be NULL).
+ * Under SHAMPOO_LARGE_DIM_DIAGONAL a parameter with a dimension above b is one row
+ * (m, n = its shape) with flags bit 0 / bit 1 set where the left / right factor is
+ * diagonal; under SHAMPOO_LARGE_DIM_ADAGRAD such a parameter has no row (it is handled
+ * like a 1-D parameter).
  */
 int shampoo_plan(const shampoo_config *cfg, int64_t *table, int64_t cap,
                  int64_t *n_blocks, int64_t *n_buckets);
@@ -144,10 +155,10 @@ int shampoo_step(shampoo_opt *opt, void *const *params, const void *const *grads
 
 /* State selectors for shampoo_get. */
 enum {
-  SHAMPOO_GET_L = 0,      /* m x m float32   */
-  SHAMPOO_GET_R = 1,      /* n x n           */
-  SHAMPOO_GET_LINV = 2,   /* m x m           */
-  SHAMPOO_GET_RINV = 3,   /* n x n           */
+  SHAMPOO_GET_L = 0,      /* m x m float32 (m floats, the diagonal, where that factor is diagonal) */
+  SHAMPOO_GET_R = 1,      /* n x n (n)       */
+  SHAMPOO_GET_LINV = 2,   /* m x m (m)       */
+  SHAMPOO_GET_RINV = 3,   /* n x n (n)       */
   SHAMPOO_GET_A = 4,      /* m x n (block) or len (1-D parameter, block = 0) */
   SHAMPOO_GET_M = 5,      /* same shape as A; error if momentum == 0         */
   SHAMPOO_GET_PSH = 6,    /* m x n: last Lbar G Rbar                         */

@@ -17,6 +17,7 @@ GRAD_F32, GRAD_BF16 = 0, 1
 GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF = range(9)
 GRAFT_ADAGRAD, GRAFT_SGD, GRAFT_RMSPROP, GRAFT_ADAM = 0, 1, 2, 3
 ROOT_EIGH, ROOT_NEWTON = 0, 1
+LARGE_DIM_BLOCKING, LARGE_DIM_ADAGRAD, LARGE_DIM_DIAGONAL = 0, 1, 2
 STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG, STAGE_FUSED = range(7)
 STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag", "fused")
 
@@ -48,6 +49,7 @@ class ShampooConfig(ctypes.Structure):
         ("grafting_type", ctypes.c_int32),
         ("grafting_beta2", ctypes.c_float),
         ("use_bias_correction", ctypes.c_int32),
+        ("large_dim_method", ctypes.c_int32),
         ("root_method", ctypes.c_int32),
         ("newton_tolerance", ctypes.c_float),
         ("newton_max_iterations", ctypes.c_int32),
@@ -117,7 +119,8 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                 grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
-                newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999):
+                newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999,
+                large_dim_method=LARGE_DIM_BLOCKING):
     """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
     n = len(shapes)
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
@@ -129,7 +132,7 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                         precondition_frequency, start_preconditioning_step, graft_epsilon,
                         momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
                         1 if use_nesterov else 0, grafting_type, grafting_beta2, 1 if use_bias_correction else 0,
-                        root_method, newton_tolerance, newton_max_iterations, grad_dtype, device)
+                        large_dim_method, root_method, newton_tolerance, newton_max_iterations, grad_dtype, device)
     cfg._keep = (ndim, shape)
     return cfg
 
@@ -163,7 +166,8 @@ class Shampoo:
                  grad_dtype=GRAD_F32, device=0, beta1=0.0, weight_decay=0.0,
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
-                newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999):
+                newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999,
+                large_dim_method=LARGE_DIM_BLOCKING):
         import torch
         self.shapes = [tuple(s) for s in shapes]
         self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
@@ -171,7 +175,7 @@ class Shampoo:
                                momentum, grad_dtype, device, beta1, weight_decay,
                                use_decoupled_weight_decay, use_nesterov, grafting_type,
                                use_bias_correction, root_method, newton_tolerance, newton_max_iterations,
-                               grafting_beta2)
+                               grafting_beta2, large_dim_method)
         self.device = torch.device("cuda", device)
         nbytes = shampoo_workspace_bytes(self.cfg)
         if nbytes == 0:
@@ -195,15 +199,17 @@ class Shampoo:
     def get(self, param, block, which):
         import torch
         s = self.shapes[param]
-        if len(s) == 1:
-            shape = (s[0],)
+        table = self.plan()[0]
+        rows = table[table[:, 0] == param] if len(table) else table
+        if len(rows) == 0:      # 1-D, or a matrix on the diagonal-method path
+            shape = tuple(s)
         else:
-            table = self.plan()[0]
-            rows = table[table[:, 0] == param]
             if not 0 <= block < len(rows):
                 raise ShampooError(-2)
-            m, n = int(rows[block, 3]), int(rows[block, 4])
-            shape = {GET_L: (m, m), GET_LINV: (m, m), GET_R: (n, n), GET_RINV: (n, n),
+            m, n, flags = int(rows[block, 3]), int(rows[block, 4]), int(rows[block, 7])
+            lshape = (m,) if flags & 1 else (m, m)
+            rshape = (n,) if flags & 2 else (n, n)
+            shape = {GET_L: lshape, GET_LINV: lshape, GET_R: rshape, GET_RINV: rshape,
                      GET_A: (m, n), GET_M: (m, n), GET_PSH: (m, n), GET_NORMS: (2,), GET_GF: (m, n)}[which]
         out = torch.empty(shape, dtype=torch.float32, device=self.device)
         _check(lib().shampoo_get(self.handle, param, block, which, ctypes.c_void_p(out.data_ptr()),

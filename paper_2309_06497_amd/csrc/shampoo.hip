@@ -8,12 +8,14 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <tuple>
 #include <new>
 #include <utility>
 #include <vector>
 
 #include "../../include/shampoo.h"
 #include "block_step_small.h"
+#include "diag_shampoo.h"
 #include "eigh_jacobi.h"
 #include "elementwise.h"
 #include "gemm_mfma.h"
@@ -52,6 +54,13 @@ struct Bucket {
   EwGeom geom;
   int32_t tiles_m, tiles_n;
   bool bf16_mfma;   // shapes, offsets and leading dimensions allow the bf16 matrix-core factor update
+  // diagonal Shampoo (Sec. 4.2.3): the factor of that side is a vector (its diagonal); such a
+  // bucket holds whole parameters, one per slot
+  bool diagL = false, diagR = false;
+  int32_t col_segs = 1, rows_per_seg = 0;   // row segments of the column-sum reduction
+  bool whole() const { return diagL || diagR; }
+  size_t l_elems() const { return diagL ? (size_t)m : (size_t)m * m; }
+  size_t r_elems() const { return diagR ? (size_t)n : (size_t)n * n; }
 };
 struct Plan {
   std::vector<Block> blocks;
@@ -96,6 +105,12 @@ int check_config(const shampoo_config *c) {
   if ((c->grafting_type == SHAMPOO_GRAFT_RMSPROP || c->grafting_type == SHAMPOO_GRAFT_ADAM) &&
       !(c->grafting_beta2 > 0.f && c->grafting_beta2 <= 1.f))
     return SHAMPOO_ERR_HYPER;
+  if (c->large_dim_method < SHAMPOO_LARGE_DIM_BLOCKING || c->large_dim_method > SHAMPOO_LARGE_DIM_DIAGONAL)
+    return SHAMPOO_ERR_HYPER;
+  if (c->large_dim_method == SHAMPOO_LARGE_DIM_DIAGONAL)
+    for (int i = 0; i < c->n_params; ++i)
+      if (c->ndim[i] == 2 && (c->shape[2 * i] > INT32_MAX / 2 || c->shape[2 * i + 1] > INT32_MAX / 2))
+        return SHAMPOO_ERR_UNSUPPORTED;
   if (c->root_method != SHAMPOO_ROOT_EIGH && c->root_method != SHAMPOO_ROOT_NEWTON) return SHAMPOO_ERR_HYPER;
   if (c->root_method == SHAMPOO_ROOT_NEWTON) {
     if (c->newton_tolerance < 0.f || !std::isfinite(c->newton_tolerance)) return SHAMPOO_ERR_HYPER;
@@ -124,23 +139,27 @@ EwGeom make_geom(int m, int n) {
 
 void make_plan(const shampoo_config *c, Plan &p) {
   const int64_t b = c->block_size;
-  std::map<std::pair<int, int>, int> bucket_of;
+  std::map<std::tuple<int, int, int>, int> bucket_of;   // (m, n, diagonal sides) -> bucket
   p.param_blocks.assign(c->n_params, {});
   p.param_state_offset.assign(c->n_params, 0);
   int64_t off = 0;
   for (int i = 0; i < c->n_params; ++i) {
     p.param_state_offset[i] = off;
     const int64_t rows = c->shape[2 * i];
-    if (c->ndim[i] == 1) {
-      for (int64_t s = 0; s < rows; s += DIAG_CHUNK) {
+    const bool large = c->ndim[i] == 2 && (rows > b || c->shape[2 * i + 1] > b);
+    // 1-D parameters, and under the "adagrad" large-dimension method (Sec. 4.2.2) every
+    // matrix with a dimension above the block size, take the diagonal path on their entries
+    if (c->ndim[i] == 1 || (large && c->large_dim_method == SHAMPOO_LARGE_DIM_ADAGRAD)) {
+      const int64_t len = c->ndim[i] == 1 ? rows : rows * c->shape[2 * i + 1];
+      for (int64_t s = 0; s < len; s += DIAG_CHUNK) {
         DiagChunk dc;
         dc.param = i;
-        dc.len = (int32_t)std::min<int64_t>(DIAG_CHUNK, rows - s);
+        dc.len = (int32_t)std::min<int64_t>(DIAG_CHUNK, len - s);
         dc.start = s;
         dc.state_offset = off + s;
         p.diag_chunks.push_back(dc);
       }
-      off += (rows + 3) / 4 * 4;
+      off += (len + 3) / 4 * 4;
       continue;
     }
     const int64_t cols = c->shape[2 * i + 1];
@@ -152,20 +171,25 @@ void make_plan(const shampoo_config *c, Plan &p) {
       dc.state_offset = off + st;
       p.prep_chunks.push_back(dc);
     }
-    const int64_t km = (rows + b - 1) / b, kn = (cols + b - 1) / b;
+    // diagonal Shampoo (Sec. 4.2.3): the parameter stays whole, one "block"
+    const bool whole = large && c->large_dim_method == SHAMPOO_LARGE_DIM_DIAGONAL;
+    const int64_t bb = whole ? std::max(rows, cols) : b;
+    const int flags = whole ? ((rows > b ? 1 : 0) | (cols > b ? 2 : 0)) : 0;
+    const int64_t km = (rows + bb - 1) / bb, kn = (cols + bb - 1) / bb;
     for (int64_t bi = 0; bi < km; ++bi)
       for (int64_t bj = 0; bj < kn; ++bj) {
         Block blk;
         blk.param = i;
-        blk.row0 = bi * b;
-        blk.col0 = bj * b;
-        blk.m = (int32_t)std::min<int64_t>(b, rows - blk.row0);
-        blk.n = (int32_t)std::min<int64_t>(b, cols - blk.col0);
-        auto key = std::make_pair(blk.m, blk.n);
+        blk.row0 = bi * bb;
+        blk.col0 = bj * bb;
+        blk.m = (int32_t)std::min<int64_t>(bb, rows - blk.row0);
+        blk.n = (int32_t)std::min<int64_t>(bb, cols - blk.col0);
+        auto key = std::make_tuple(blk.m, blk.n, flags);
         auto it = bucket_of.find(key);
         if (it == bucket_of.end()) {
           Bucket bk{};
           bk.m = blk.m; bk.n = blk.n; bk.count = 0;
+          bk.diagL = (flags & 1) != 0; bk.diagR = (flags & 2) != 0;
           bucket_of[key] = (int)p.buckets.size();
           p.buckets.push_back(bk);
           it = bucket_of.find(key);
@@ -178,7 +202,7 @@ void make_plan(const shampoo_config *c, Plan &p) {
     off += (rows * cols + 3) / 4 * 4;
   }
   p.total_elems = off;
-  for (auto &bk : p.buckets) bk.bf16_mfma = (bk.m % 8 == 0) && (bk.n % 8 == 0) && bk.count <= 65535;
+  for (auto &bk : p.buckets) bk.bf16_mfma = (bk.m % 8 == 0) && (bk.n % 8 == 0) && bk.count <= 65535 && !bk.whole();
   for (const Block &blk : p.blocks) {
     const int64_t ld = c->shape[2 * blk.param + 1];
     if (ld % 8 != 0 || (blk.row0 * ld + blk.col0) % 8 != 0) p.buckets[blk.bucket].bf16_mfma = false;
@@ -187,6 +211,8 @@ void make_plan(const shampoo_config *c, Plan &p) {
     bk.geom = make_geom(bk.m, bk.n);
     bk.tiles_m = (bk.m + BM - 1) / BM;
     bk.tiles_n = (bk.n + BN - 1) / BN;
+    bk.col_segs = std::max(1, std::min(64, bk.m / 256));
+    bk.rows_per_seg = (bk.m + bk.col_segs - 1) / bk.col_segs;
   }
 }
 
@@ -526,22 +552,24 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   std::vector<EigLayout> eL, eR;
   for (auto &b : p.buckets) {
     const size_t B = b.count, m = b.m, n = b.n;
-    b.off_L = take(B * m * m * 4);
-    b.off_R = take(B * n * n * 4);
-    b.off_Linv = take(B * m * m * 4);
-    b.off_Rinv = take(B * n * n * 4);
+    b.off_L = take(B * b.l_elems() * 4);
+    b.off_R = take(B * b.r_elems() * 4);
+    b.off_Linv = take(B * b.l_elems() * 4);
+    b.off_Rinv = take(B * b.r_elems() * 4);
     b.off_P = take(B * m * n * 4);
     b.off_desc = take(B * sizeof(BlockDesc));
     b.off_sgp = take(B * b.geom.chunks * 4);
-    b.off_sshp = take(B * b.tiles_m * b.tiles_n * 4);
+    b.off_sshp = take(B * std::max<size_t>((size_t)b.tiles_m * b.tiles_n, (size_t)b.geom.chunks) * 4);
     b.off_scale = take(B * 4);
     b.off_norms = take(B * 8);
     t_elems = std::max(t_elems, B * m * n);
     if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) gt_elems = std::max(gt_elems, B * m * n);
-    eL.push_back(eig_layout(b.m, b.count));
-    eR.push_back(eig_layout(b.n, b.count));
+    // a diagonalised side needs no eigensolver workspace (stand-in layout of a 1 x 1 problem)
+    const int em = b.diagL ? 1 : b.m, en = b.diagR ? 1 : b.n;
+    eL.push_back(eig_layout(em, b.count));
+    eR.push_back(eig_layout(en, b.count));
     if (c->root_method == SHAMPOO_ROOT_NEWTON)
-      eig_bytes = std::max(eig_bytes, std::max(newton_layout(b.m, b.count).bytes, newton_layout(b.n, b.count).bytes));
+      eig_bytes = std::max(eig_bytes, std::max(newton_layout(em, b.count).bytes, newton_layout(en, b.count).bytes));
     else
       eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
   }
@@ -551,7 +579,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offG = take((size_t)c->n_params * sizeof(void *));
   const size_t offD = take(std::max<size_t>(1, p.diag_chunks.size()) * sizeof(DiagChunk));
   int64_t n_small = 0;
-  for (auto &b : p.buckets) if (b.m <= SB && b.n <= SB) n_small += b.count;
+  for (auto &b : p.buckets) if (b.m <= SB && b.n <= SB && !b.whole()) n_small += b.count;
   const size_t offSmall = take(std::max<size_t>(1, (size_t)n_small) * sizeof(SmallBlock));
   const size_t offC = take(64);
   const size_t offE = take(eig_bytes);
@@ -635,7 +663,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   // resident in LDS) whenever no refresh separates the factor update from the
   // preconditioning and the default heuristics are in force.
   const bool small_ok = use_shampoo && !refresh && !o->use_l2 && !o->use_b1 && !sgd;
-  auto fused = [&](const Bucket &b) { return small_ok && b.m <= SB && b.n <= SB; };
+  auto fused = [&](const Bucket &b) { return small_ok && b.m <= SB && b.n <= SB && !b.whole(); };
   if (small_ok && o->n_small > 0) {
     StageTimer t(o, SHAMPOO_STAGE_FUSED, s);
     SmallStepArgs f;
@@ -684,18 +712,36 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       g.a.from_table = 1; g.b.from_table = 1;
       g.desc = desc; g.ptr_table = gs_tab;
       g.alpha = (float)alpha; g.beta = (float)beta; g.alpha_d = alpha; g.beta_d = beta; g.batch = b.count;
-      // L <- beta L + alpha G G^T
-      g.c = reinterpret_cast<float *>(ws + b.off_L); g.c_batch_stride = (int64_t)b.m * b.m; g.ldc = b.m;
-      g.M = b.m; g.N = b.m; g.K = b.n;
-      g.tiles_m = g.tiles_n = b.tiles_m; g.tiles = b.tiles_m * (b.tiles_m + 1) / 2;
-      rc = launch_gemm<K_CONTIG, K_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
-      if (rc) return rc;
-      // R <- beta R + alpha G^T G
-      g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.n * b.n; g.ldc = b.n;
-      g.M = b.n; g.N = b.n; g.K = b.m;
-      g.tiles_m = g.tiles_n = b.tiles_n; g.tiles = b.tiles_n * (b.tiles_n + 1) / 2;
-      rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
-      if (rc) return rc;
+      DiagFactorArgs df{};
+      df.desc = desc; df.g_table = gs_tab; df.a = beta; df.b = alpha; df.m = b.m; df.n = b.n;
+      if (b.diagL) {
+        // l_i <- beta l_i + alpha sum_j G_ij^2 (Sec. 4.2.3)
+        df.vec = reinterpret_cast<float *>(ws + b.off_L);
+        hipLaunchKernelGGL(diag_row_kernel<GS>, dim3((b.m + 3) / 4, b.count), dim3(256), 0, s, df);
+        HIP_TRY(hipGetLastError());
+      } else {
+        // L <- beta L + alpha G G^T
+        g.c = reinterpret_cast<float *>(ws + b.off_L); g.c_batch_stride = (int64_t)b.m * b.m; g.ldc = b.m;
+        g.M = b.m; g.N = b.m; g.K = b.n;
+        g.tiles_m = g.tiles_n = b.tiles_m; g.tiles = b.tiles_m * (b.tiles_m + 1) / 2;
+        rc = launch_gemm<K_CONTIG, K_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
+        if (rc) return rc;
+      }
+      if (b.diagR) {
+        // r_j <- beta r_j + alpha sum_i G_ij^2, rows cut into segments whose partial sums go through T
+        df.vec = reinterpret_cast<float *>(ws + b.off_R);
+        df.partial = T; df.segs = b.col_segs; df.rows_per_seg = b.rows_per_seg;
+        hipLaunchKernelGGL(diag_col_partial_kernel<GS>, dim3((b.n + 255) / 256, b.col_segs, b.count), dim3(256), 0, s, df);
+        hipLaunchKernelGGL(diag_col_reduce_kernel, dim3((b.n + 255) / 256, b.count), dim3(256), 0, s, df);
+        HIP_TRY(hipGetLastError());
+      } else {
+        // R <- beta R + alpha G^T G
+        g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.n * b.n; g.ldc = b.n;
+        g.M = b.n; g.N = b.n; g.K = b.m;
+        g.tiles_m = g.tiles_n = b.tiles_n; g.tiles = b.tiles_n * (b.tiles_n + 1) / 2;
+        rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
+        if (rc) return rc;
+      }
     }
     {
       StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
@@ -713,6 +759,27 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     StageTimer t(o, SHAMPOO_STAGE_ROOT, s);
     for (size_t i = 0; i < p.buckets.size(); ++i) {
       auto &b = p.buckets[i];
+      if (b.whole()) {
+        // diagonal sides: elementwise root; full sides: the eigensolver
+        for (int side = 0; side < 2; ++side) {
+          const bool dg = side == 0 ? b.diagL : b.diagR;
+          const int dim = side == 0 ? b.m : b.n;
+          float *F = reinterpret_cast<float *>(ws + (side == 0 ? b.off_L : b.off_R));
+          float *Fi = reinterpret_cast<float *>(ws + (side == 0 ? b.off_Linv : b.off_Rinv));
+          if (dg) {
+            DiagRootArgs da;
+            da.vec = F; da.out = Fi; da.dim = dim; da.epsilon = c.epsilon; da.r = c.root_exponent; da.scale = c2;
+            da.fail_count = fail_count;
+            hipLaunchKernelGGL(diag_root_kernel, dim3(b.count), dim3(256), 0, s, da);
+            HIP_TRY(hipGetLastError());
+          } else {
+            rc = root_inverse_batched(F, dim, b.count, c.epsilon, c.root_exponent, c2, Fi, nullptr, nullptr, fail_count,
+                                      ws + o->off_eig, side == 0 ? o->eig_L[i] : o->eig_R[i], s);
+            if (rc) return rc;
+          }
+        }
+        continue;
+      }
       if (c.root_method == SHAMPOO_ROOT_NEWTON) {
         const int pw = newton_p_of(c.root_exponent);
         const float tol = c.newton_tolerance > 0.f ? c.newton_tolerance : 1e-6f;
@@ -743,7 +810,50 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     float *P = reinterpret_cast<float *>(ws + b.off_P);
     float *scale = reinterpret_cast<float *>(ws + b.off_scale);
     if (fused(b)) continue;
-    if (use_shampoo) {
+    int ssh_count = b.tiles_m * b.tiles_n;
+    if (use_shampoo && b.whole()) {
+      // diagonal Shampoo: a diagonalised side scales rows / columns instead of multiplying
+      StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
+      DiagScaleArgs ds{};
+      ds.desc = desc; ds.g_table = gd_tab; ds.m = b.m; ds.n = b.n; ds.geom = b.geom;
+      const float *dl = reinterpret_cast<const float *>(ws + b.off_Linv), *dr = reinterpret_cast<const float *>(ws + b.off_Rinv);
+      float *ssh = reinterpret_cast<float *>(ws + b.off_sshp);
+      const unsigned ew_grid = (unsigned)b.geom.chunks * b.count;
+      if (b.diagL && b.diagR) {
+        ds.dl = dl; ds.dr = dr; ds.out = P; ds.norm_partial = ssh; ds.alpha = c1;
+        hipLaunchKernelGGL(diag_scale_kernel<GD>, dim3(ew_grid), dim3(EW_THREADS), 0, s, ds);
+        HIP_TRY(hipGetLastError());
+        ssh_count = b.geom.chunks;
+      } else if (b.diagL) {
+        // T = D_L G, then P = T Rbar with per-tile sums of squares
+        ds.dl = dl; ds.out = T; ds.alpha = c1;
+        hipLaunchKernelGGL(diag_scale_kernel<GD>, dim3(ew_grid), dim3(EW_THREADS), 0, s, ds);
+        HIP_TRY(hipGetLastError());
+        GemmArgs h{};
+        h.a.base = T; h.a.batch_stride = (int64_t)b.m * b.n; h.a.ld = b.n;
+        h.b.base = ws + b.off_Rinv; h.b.batch_stride = (int64_t)b.n * b.n; h.b.ld = b.n;
+        h.c = P; h.c_batch_stride = (int64_t)b.m * b.n; h.ldc = b.n;
+        h.M = b.m; h.N = b.n; h.K = b.n; h.alpha = 1.f; h.beta = 0.f;
+        h.tiles_m = b.tiles_m; h.tiles_n = b.tiles_n; h.tiles = b.tiles_m * b.tiles_n; h.batch = b.count;
+        h.norm_partial = ssh;
+        rc = launch_gemm<K_CONTIG, ROW_CONTIG, float, float, EPI_STORE_NORM, false>(h, s);
+        if (rc) return rc;
+      } else {
+        // T = Lbar G, then P = T D_R
+        GemmArgs g{};
+        g.a.base = ws + b.off_Linv; g.a.batch_stride = (int64_t)b.m * b.m; g.a.ld = b.m;
+        g.b.from_table = 1; g.desc = desc; g.ptr_table = gd_tab;
+        g.c = T; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
+        g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1; g.beta = 0.f;
+        g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.tiles = b.tiles_m * b.tiles_n; g.batch = b.count;
+        rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE, false>(g, s);
+        if (rc) return rc;
+        ds.src = T; ds.dr = dr; ds.out = P; ds.norm_partial = ssh; ds.alpha = 1.f;
+        hipLaunchKernelGGL(diag_scale_kernel<float>, dim3(ew_grid), dim3(EW_THREADS), 0, s, ds);
+        HIP_TRY(hipGetLastError());
+        ssh_count = b.geom.chunks;
+      }
+    } else if (use_shampoo) {
       StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
       GemmArgs g{};
       // T = Lbar G   (Lbar symmetric: A(i,k) read as Lbar[k][i], contiguous in i)
@@ -770,7 +880,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       if (use_shampoo) {
         ScaleArgs sa;
         sa.sg_partial = reinterpret_cast<const float *>(ws + b.off_sgp); sa.sg_count = b.geom.chunks;
-        sa.ssh_partial = reinterpret_cast<const float *>(ws + b.off_sshp); sa.ssh_count = b.tiles_m * b.tiles_n;
+        sa.ssh_partial = reinterpret_cast<const float *>(ws + b.off_sshp); sa.ssh_count = ssh_count;
         sa.scale = scale; sa.norms = reinterpret_cast<float *>(ws + b.off_norms);
         hipLaunchKernelGGL(scale_kernel, dim3(b.count), dim3(64), 0, s, sa);
       }
@@ -819,7 +929,8 @@ int shampoo_plan(const shampoo_config *cfg, int64_t *table, int64_t cap, int64_t
     const Block &b = p.blocks[i];
     int64_t *row = table + 8 * i;
     row[0] = b.param; row[1] = b.row0; row[2] = b.col0; row[3] = b.m; row[4] = b.n;
-    row[5] = b.bucket; row[6] = b.slot; row[7] = 0;
+    row[5] = b.bucket; row[6] = b.slot;
+    row[7] = (p.buckets[b.bucket].diagL ? 1 : 0) | (p.buckets[b.bucket].diagR ? 2 : 0);
   }
   return SHAMPOO_OK;
 }
@@ -892,15 +1003,18 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
   for (size_t i = 0; i < p.buckets.size(); ++i) {
     Bucket &b = p.buckets[i];
     const int64_t B = b.count;
-    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_L), 0.f, B * b.m * b.m, s))) return fail(rc);
-    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_R), 0.f, B * b.n * b.n, s))) return fail(rc);
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_L), 0.f, B * (int64_t)b.l_elems(), s))) return fail(rc);
+    if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_R), 0.f, B * (int64_t)b.r_elems(), s))) return fail(rc);
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_P), 0.f, B * b.m * b.n, s))) return fail(rc);
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_norms), 0.f, B * 2, s))) return fail(rc);
+    // roots start as the identity (a diagonalised side: the vector of ones)
     const int64_t tl = B * b.m * b.m, tr = B * b.n * b.n;
-    hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tl + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<float *>(o->ws + b.off_Linv), b.m, tl);
-    hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tr + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<float *>(o->ws + b.off_Rinv), b.n, tr);
+    if (b.diagL) { if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_Linv), 1.f, B * b.m, s))) return fail(rc); }
+    else hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tl + 255) / 256)), dim3(256), 0, s,
+                            reinterpret_cast<float *>(o->ws + b.off_Linv), b.m, tl);
+    if (b.diagR) { if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_Rinv), 1.f, B * b.n, s))) return fail(rc); }
+    else hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tr + 255) / 256)), dim3(256), 0, s,
+                            reinterpret_cast<float *>(o->ws + b.off_Rinv), b.n, tr);
     if (hipGetLastError() != hipSuccess) return fail(SHAMPOO_ERR_HIP);
     if (hipMemcpyAsync(o->ws + b.off_desc, descs[i].data(), descs[i].size() * sizeof(BlockDesc),
                        hipMemcpyHostToDevice, s) != hipSuccess)
@@ -911,7 +1025,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
     std::vector<SmallBlock> small;
     for (size_t i = 0; i < p.buckets.size(); ++i) {
       const Bucket &b = p.buckets[i];
-      if (b.m > SB || b.n > SB) continue;
+      if (b.m > SB || b.n > SB || b.whole()) continue;
       for (int64_t k = 0; k < b.count; ++k) {
         SmallBlock sb;
         sb.d = descs[i][k]; sb.m = b.m; sb.n = b.n;
@@ -978,11 +1092,11 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
   HIP_TRY(hipSetDevice(o->cfg.device));
   Plan &p = o->plan;
   unsigned char *ws = o->ws;
-  if (o->ndim[param] == 1) {
+  if (p.param_blocks[param].empty()) {   // 1-D, or a matrix on the diagonal-method path
     if (block != 0 || (which != SHAMPOO_GET_A && which != SHAMPOO_GET_M && which != SHAMPOO_GET_GF)) return SHAMPOO_ERR_SHAPE;
     if (which == SHAMPOO_GET_M && !(o->cfg.momentum > 0.f)) return SHAMPOO_ERR_SHAPE;
     if (which == SHAMPOO_GET_GF && !o->use_b1) return SHAMPOO_ERR_SHAPE;
-    const size_t len = (size_t)o->shape[2 * param];
+    const size_t len = (size_t)o->shape[2 * param] * (o->ndim[param] == 2 ? (size_t)o->shape[2 * param + 1] : 1);
     if (bytes != len * 4) return SHAMPOO_ERR_SHAPE;
     const size_t off_state = which == SHAMPOO_GET_A ? o->off_A : (which == SHAMPOO_GET_M ? o->off_M : o->off_Gf);
     const float *src = reinterpret_cast<const float *>(ws + off_state) + p.param_state_offset[param];
@@ -996,10 +1110,10 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
   const unsigned char *src = nullptr;
   size_t need = 0;
   switch (which) {
-    case SHAMPOO_GET_L: src = ws + bk.off_L + (size_t)b.slot * m * m * 4; need = m * m * 4; break;
-    case SHAMPOO_GET_R: src = ws + bk.off_R + (size_t)b.slot * n * n * 4; need = n * n * 4; break;
-    case SHAMPOO_GET_LINV: src = ws + bk.off_Linv + (size_t)b.slot * m * m * 4; need = m * m * 4; break;
-    case SHAMPOO_GET_RINV: src = ws + bk.off_Rinv + (size_t)b.slot * n * n * 4; need = n * n * 4; break;
+    case SHAMPOO_GET_L: need = bk.l_elems() * 4; src = ws + bk.off_L + (size_t)b.slot * need; break;
+    case SHAMPOO_GET_R: need = bk.r_elems() * 4; src = ws + bk.off_R + (size_t)b.slot * need; break;
+    case SHAMPOO_GET_LINV: need = bk.l_elems() * 4; src = ws + bk.off_Linv + (size_t)b.slot * need; break;
+    case SHAMPOO_GET_RINV: need = bk.r_elems() * 4; src = ws + bk.off_Rinv + (size_t)b.slot * need; break;
     case SHAMPOO_GET_PSH: src = ws + bk.off_P + (size_t)b.slot * m * n * 4; need = m * n * 4; break;
     case SHAMPOO_GET_NORMS: src = ws + bk.off_norms + (size_t)b.slot * 8; need = 8; break;
     case SHAMPOO_GET_A:

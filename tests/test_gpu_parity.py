@@ -77,7 +77,7 @@ class Pair:
 
     def __init__(self, shapes, b, beta2, f, start=0, mu=0.9, eps=1e-12, eps_g=1e-10, bf16=False, seed=0,
                  beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad",
-                 bias_correction=False, newton=None, grafting_beta2=0.999):
+                 bias_correction=False, newton=None, grafting_beta2=0.999, large_dim_method="blocking"):
         self.shapes = shapes
         self.bf16 = bf16
         self.f, self.start, self.eps = f, start, f32(eps)
@@ -85,12 +85,14 @@ class Pair:
                              B.GRAD_BF16 if bf16 else B.GRAD_F32, 0, beta1, weight_decay, decoupled, nesterov,
                              {"adagrad": B.GRAFT_ADAGRAD, "sgd": B.GRAFT_SGD, "rmsprop": B.GRAFT_RMSPROP,
                               "adam": B.GRAFT_ADAM}[grafting], bias_correction,
-                             B.ROOT_NEWTON if newton else B.ROOT_EIGH, *(newton or (1e-6, 100)), grafting_beta2)
+                             B.ROOT_NEWTON if newton else B.ROOT_EIGH, *(newton or (1e-6, 100)), grafting_beta2,
+                             {"blocking": B.LARGE_DIM_BLOCKING, "adagrad": B.LARGE_DIM_ADAGRAD,
+                              "diagonal": B.LARGE_DIM_DIAGONAL}[large_dim_method])
         self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, start, f32(eps_g), f32(mu),
                                     f32(beta1), f32(weight_decay), decoupled, nesterov, grafting,
                                     bias_correction, "newton" if newton else "eigh",
                                     *((f32(newton[0]), newton[1]) if newton else (1e-6, 100)),
-                                    f32(grafting_beta2))
+                                    f32(grafting_beta2), large_dim_method)
         self.newton = newton
         w0 = wl.init_params(shapes, seed)
         self.w0 = [w.astype(np.float64) for w in w0]
@@ -113,7 +115,7 @@ class Pair:
                 for k in range(len(self.ora.blocks[i])):
                     a = 0.0
                     for F in (self.ora.L[i][k], self.ora.R[i][k]):
-                        lam_min = max(np.linalg.eigvalsh(F)[0], 0.0)
+                        lam_min = max(np.linalg.eigvalsh(F)[0] if F.ndim == 2 else F.min(), 0.0)
                         a += 0.25 * self.THETA * np.linalg.norm(F) / (lam_min + self.eps)
                     self.allow[(i, k)] = a
                     self.allow_hist[(i, k)] = max(a, self.allow_hist.get((i, k), 0.0))
@@ -150,7 +152,7 @@ class Pair:
         for i, s in enumerate(self.shapes):
             wg = self.w_gpu[i].cpu().numpy().astype(np.float64)
             dw_g, dw_o = wg - self.w0[i], self.w_ora[i] - self.w0[i]
-            if len(s) == 1:
+            if len(s) == 1 or self.ora.whole[i] == "adagrad":
                 worst["A"] = max(worst["A"], rel(self.gpu.get(i, 0, B.GET_A).cpu().numpy(), self.ora.A[i]))
                 e2e("dW", dw_g, dw_o, (i, -1))
                 if self.ora.mu > 0:
@@ -177,8 +179,9 @@ class Pair:
                         if self.newton:
                             root = lambda F: so.root_inverse_newton(c2 * F.astype(np.float64), self.eps, 4,
                                                                     f32(self.newton[0]), self.newton[1])[0]
-                        else:
-                            root = lambda F: so.root_inverse(c2 * F.astype(np.float64), self.eps, 0.25)[0]
+                        else:   # a diagonalised factor (vector): the same box on its entries
+                            root = lambda F: (so.root_inverse(c2 * F.astype(np.float64), self.eps, 0.25)[0] if F.ndim == 2
+                                              else (c2 * F.astype(np.float64) + self.eps) ** -0.25)
                         worst["root"] = max(worst["root"], rel(Li, root(L)), rel(Ri, root(R)))
                     P = self.gpu.get(i, k, B.GET_PSH).cpu().numpy()
                     c1 = 1.0
@@ -187,8 +190,8 @@ class Pair:
                     g_dir = c1 * self.ora.Gf[i][sl] if self.ora.beta1 > 0 else (
                         self.g_last[i][sl] + (self.ora.wd * self.w_prev[i][sl]
                                               if self.ora.wd > 0 and not self.ora.decoupled else 0.0))
-                    worst["gemm"] = max(worst["gemm"], rel(P, so.shampoo_direction(
-                        Li.astype(np.float64), g_dir, Ri.astype(np.float64))))
+                    full = lambda X: np.diag(X.astype(np.float64)) if X.ndim == 1 else X.astype(np.float64)
+                    worst["gemm"] = max(worst["gemm"], rel(P, so.shampoo_direction(full(Li), g_dir, full(Ri))))
                     e2e("Psh", P, self.ora.P_sh[i][k], (i, k))
                     norms = self.gpu.get(i, k, B.GET_NORMS).cpu().numpy()
                     assert abs(norms[0] - self.ora.s_g[i][k]) <= 2e-4 * self.ora.s_g[i][k] + 1e-30
@@ -537,3 +540,34 @@ def test_rmsprop_and_adam_grafting(grafting, bc):
     for t in range(5):
         p.step(wl.gaussian_grads(shapes, 80, t, 1e-2), 0.01, t)
         p.check(t)
+
+
+# ---------------------------------------------------------------------------
+# Large-dimension methods other than blocking (Sec. 4.2.2, 4.2.3)
+# ---------------------------------------------------------------------------
+def test_adagrad_large_dim_method():
+    say("case large dim adagrad")
+    shapes = [(200, 48), (64, 64), (9,)]      # the first exceeds the block size: diagonal method
+    p = Pair(shapes, 128, 0.999, 2, large_dim_method="adagrad")
+    table, _ = p.gpu.plan()
+    assert [int(r[0]) for r in table] == [1]
+    for t in range(4):
+        p.step(wl.gaussian_grads(shapes, 91, t, 1e-2), 0.01, t)
+        p.check(t)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_diagonal_shampoo(bf16):
+    """Whole parameters with the factor of each dimension above the block size diagonalised:
+    (diag, full), (full, diag), (diag, diag) next to an ordinary small block; tall enough for
+    several row segments of the column reduction."""
+    say(f"case diagonal shampoo bf16={bf16}")
+    shapes = [(600, 48), (40, 264), (300, 200), (64, 64), (9,)]
+    p = Pair(shapes, 128, 0.99, 2, eps=1e-6, large_dim_method="diagonal", bf16=bf16)
+    table, _ = p.gpu.plan()
+    assert [(int(r[0]), int(r[3]), int(r[4]), int(r[7])) for r in table] == [
+        (0, 600, 48, 1), (1, 40, 264, 2), (2, 300, 200, 3), (3, 64, 64, 0)]
+    for t in range(5):
+        p.step(wl.gaussian_grads(shapes, 92, t, 1e-2), 0.01, t)
+        p.check(t)
+    assert p.gpu.status()["failed_roots"] == 0

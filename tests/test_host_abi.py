@@ -93,7 +93,7 @@ def test_workspace_holds_the_state_of_the_memory_rule():
     (dict(momentum=1.0), -3), (dict(momentum=-0.1), -3), (dict(grad_dtype=7), -3),
     (dict(beta1=1.0), -3), (dict(beta1=-0.5), -3), (dict(weight_decay=-1.0), -3), (dict(grafting_type=5), -3),
     (dict(grafting_type=B.GRAFT_ADAM, grafting_beta2=0.0), -3), (dict(grafting_type=B.GRAFT_RMSPROP, grafting_beta2=1.5), -3),
-    (dict(root_method=3), -3), (dict(root_method=B.ROOT_NEWTON, newton_tolerance=-1.0), -3),
+    (dict(large_dim_method=3), -3), (dict(root_method=3), -3), (dict(root_method=B.ROOT_NEWTON, newton_tolerance=-1.0), -3),
     (dict(root_method=B.ROOT_NEWTON, newton_max_iterations=5000), -3),
     (dict(root_method=B.ROOT_NEWTON, root_exponent=1.0 / 3.0), -7),
 ])
@@ -130,3 +130,20 @@ def test_bad_shapes_are_rejected():
     # create checks the workspace before touching any device
     assert L.shampoo_create(ctypes.byref(cfg_for([(8, 8)], 4)), None, 0, None, ctypes.byref(out)) == -4
     assert L.shampoo_create(ctypes.byref(cfg_for([(8, 8)], 4)), None, 0, None, None) == -1
+
+
+def test_planner_large_dimension_methods():
+    """Sec. 4.2.2 / 4.2.3: under "adagrad" a matrix above the block size leaves the block table,
+    under "diagonal" it stays whole with flags for its diagonalised sides."""
+    shapes = [(600, 48), (40, 264), (300, 200), (64, 64), (9,)]
+    t, nb = B.shampoo_plan(cfg_for(shapes, 128, large_dim_method=B.LARGE_DIM_ADAGRAD))
+    assert [tuple(int(x) for x in r[:5]) for r in t] == [(3, 0, 0, 64, 64)] and nb == 1
+    t, nb = B.shampoo_plan(cfg_for(shapes, 128, large_dim_method=B.LARGE_DIM_DIAGONAL))
+    assert [(int(r[0]), int(r[3]), int(r[4]), int(r[7])) for r in t] == [
+        (0, 600, 48, 1), (1, 40, 264, 2), (2, 300, 200, 3), (3, 64, 64, 0)]
+    assert nb == 4
+    # diagonal Shampoo stores d1 + d2 numbers per factor pair instead of d1^2 + d2^2 (Sec. 4.2.3)
+    big = [(100000, 64)]
+    blocked = B.shampoo_workspace_bytes(cfg_for(big, 1024, momentum=0.9))
+    diag = B.shampoo_workspace_bytes(cfg_for(big, 1024, momentum=0.9, large_dim_method=B.LARGE_DIM_DIAGONAL))
+    assert diag < blocked - 2 * 97 * 1024 * 1024 * 4
