@@ -185,3 +185,27 @@ def test_block_size_2048():
         p.step(wl.gaussian_grads(shapes, 90, t, 1e-3), 0.01, t)
         p.check(t)
     assert p.gpu.status() == {"refreshes": 2, "failed_roots": 0}
+
+
+@pytest.mark.gpu
+def test_root_inverse_4096():
+    """The largest block sizes the paper recommends are 4096 and 8192 (Sec. 4.2.1): one
+    well-conditioned 4096 x 4096 factor through the blocked eigensolver (64 pivot pairs per
+    round, 127 rounds per sweep) against the oracle."""
+    import torch
+    from test_gpu_parity import say, rel
+    say("case root inverse n=4096")
+    n = 4096
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4096)
+    G = torch.randn((n, 2 * n), generator=g, device="cuda", dtype=torch.float32) * 1e-2
+    a = (G @ G.T) / (2 * n)
+    a = 0.5 * (a + a.T)
+    x, lam, failed = B.shampoo_root_inverse(a[None], 1e-12, 0.25, True, True)
+    assert int(failed[0]) == 0
+    X, lam_o = so.root_inverse(a.cpu().numpy(), float(np.float32(1e-12)), 0.25)
+    e_x = rel(x[0].cpu().numpy(), X)
+    e_l = np.abs(np.sort(lam[0].cpu().numpy().astype(np.float64)) - lam_o).max() / lam_o.max()
+    say(f"    X rel err {e_x:.1e}, eigenvalue err {e_l:.1e} lambda_max")
+    assert e_x <= 1e-4 and e_l <= 2e-6
+    assert torch.equal(x[0], x[0].T)
