@@ -17,9 +17,15 @@ the root-inverse refresh; it runs in the warm-up and its time is reported separa
 
 One JSON line is printed:
   metric/value        milliseconds per (non-refresh) step, whole job, one GPU
-  roofline            the dominant kernel: for blocks above 128 the float32-MFMA GEMM of the
-                      two-sided preconditioning (algorithmic flops per launch / average launch
-                      duration); for workloads whose blocks are at most 128 x 128 the
+  roofline            the dominant kernel: for blocks above 128 the GEMM of the two-sided
+                      preconditioning.  With bf16 gradients it runs on the bf16 matrix cores from
+                      float32 operands split exactly into three bf16 planes (six exact products per
+                      float32 product for P = T Rbar, three for T = Lbar G): `achieved` is the
+                      executed bf16 MFMA rate (algorithmic flops x products / launch time) against
+                      the 2.5 PFLOP/s bf16 peak, and `algorithmic_tflops` the float32-equivalent
+                      rate; with --fp32-matrix-cores or float32 gradients it is the float32-MFMA
+                      kernel against 157.3 TFLOP/s.  For workloads whose blocks are at most
+                      128 x 128 it is the
                       single-workgroup block-step kernel, which is bound by HBM (algorithmic
                       bytes per launch / average launch duration).  Durations come from HIP
                       events recorded by the library on the step's stream
@@ -38,6 +44,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel (P = T Rbar) on the transformer workload, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (x2.0 / x1.0):
 # profiles/transformer_b1024_hbm_traffic_pmc.md
@@ -45,6 +52,9 @@ TRAFFIC_BYTES = {"transformer": 14.43e9 + 4.83e9}
 # the same for the single-workgroup block-step kernel on the ResNet-50 shapes:
 # profiles/resnet50_b128_hbm_traffic_pmc.md
 FUSED_TRAFFIC_BYTES = {"resnet50": 0.849e9 + 0.631e9}
+# and for the two bf16 three-plane GEMMs of the transformer workload (average of the two launches):
+# profiles/transformer_b1024_hbm_traffic_pmc.md
+X3_TRAFFIC_BYTES = {"transformer": 21.66e9 + 4.83e9}
 PEAK_HBM_GBS = 8000.0
 TILE = 128
 
@@ -153,6 +163,9 @@ def main():
                     help="run this many untimed grafting-only steps first (start_preconditioning_step), so that "
                          "the timed refresh sees factors accumulated over that many gradients; must be a "
                          "multiple of the workload's precondition_frequency")
+    ap.add_argument("--fp32-matrix-cores", action="store_true",
+                    help="keep the preconditioning products on the float32 matrix cores (default: bf16 matrix "
+                         "cores with the exact three-plane split when the gradients are bf16)")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the reference for scaling HBM counters")
     args = ap.parse_args()
@@ -184,7 +197,8 @@ def main():
              for s in shapes] for _ in range(2)]
     opt = B.Shampoo(shapes, wk["block"], 0.999, 1e-12, 0.25, f, t_first, 1e-10, 0.9,
                     B.GRAD_BF16 if wk["bf16"] else B.GRAD_F32,
-                    root_method=B.ROOT_NEWTON if args.root_method == "newton" else B.ROOT_EIGH)
+                    root_method=B.ROOT_NEWTON if args.root_method == "newton" else B.ROOT_EIGH,
+                    precond_matrix_cores=B.MATRIX_CORES_FP32 if args.fp32_matrix_cores else B.MATRIX_CORES_AUTO)
     table, n_buckets = opt.plan()
     n_elems = sum(int(np.prod(s)) for s in shapes)
 
@@ -220,20 +234,38 @@ def main():
 
     alg_f, alg_p, exe_f, exe_p = flop_counts(table)
     st_ms = {k: v[0] / args.steps for k, v in stages.items()}
-    # two launches of the same GEMM kernel per bucket in the preconditioning stage
-    n_launch = stages["precond"][1] * 2
-    launch_ms = stages["precond"][0] / max(n_launch, 1)
-    gemm_flops_per_launch = alg_p * args.steps / max(n_launch, 1)
+    # the dominant kernel is the second product of the preconditioning stage, P = T Rbar
+    # (2 m n^2 flops per block; one launch per bucket and step)
+    alg_p2 = sum(2.0 * float(r[3]) * float(r[4]) ** 2 for r in table)
+    n_launch = stages["precond2"][1]
+    launch_ms = stages["precond2"][0] / max(n_launch, 1)
+    gemm_flops_per_launch = alg_p2 * args.steps / max(n_launch, 1)
     achieved = gemm_flops_per_launch / (launch_ms * 1e-3) / 1e12 if launch_ms > 0 else 0.0
+    st_ms["precond"] += st_ms.pop("precond2")
+    first_ms = stages["precond"][0] / max(stages["precond"][1], 1)
     gsz = 2 if wk["bf16"] else 4
     ew_bytes = {"graft": (gsz + 8.0) * n_elems, "update": 20.0 * n_elems}
-    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                "traffic": TRAFFIC_BYTES.get(args.workload),
-                "kernel": "gemm_mfma_kernel (two-sided preconditioning, fp32 MFMA)",
-                "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch}
+    x3 = wk["bf16"] and not args.fp32_matrix_cores and wk["block"] % 8 == 0
+    if x3:
+        # P = T Rbar executes 6 bf16 products per float32 product (T = Lbar G: 3, the gradient is bf16)
+        executed = achieved * 6.0
+        roofline = {"bound": "mfma", "achieved": executed, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": executed / PEAK_BF16_MFMA_TFLOPS, "traffic": X3_TRAFFIC_BYTES.get(args.workload),
+                    "kernel": "gemm_bf16x3_kernel<3,3> (P = T Rbar, bf16 MFMA on three-plane float32 operands)",
+                    "matrix_core_dtype": "bf16", "products_per_float32_product": 6,
+                    "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch * 6.0,
+                    "first_product_launch_ms": first_ms,
+                    "algorithmic_flops_per_launch": gemm_flops_per_launch, "algorithmic_tflops": achieved,
+                    "algorithmic_frac_of_fp32_mfma_peak": achieved / PEAK_FP32_MFMA_TFLOPS}
+    else:
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                    "traffic": TRAFFIC_BYTES.get(args.workload),
+                    "kernel": "gemm_mfma_kernel (P = T Rbar, fp32 MFMA)",
+                    "matrix_core_dtype": "f32", "first_product_launch_ms": first_ms,
+                    "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch}
     fused_ms, fused_launches = stages["fused"]
-    if fused_launches > 0 and fused_ms >= stages["precond"][0]:
+    if fused_launches > 0 and fused_ms >= stages["precond"][0] + stages["precond2"][0]:
         bytes_per_launch = fused_bytes(table, gsz) * args.steps / fused_launches
         f_launch_ms = fused_ms / fused_launches
         gbs = bytes_per_launch / (f_launch_ms * 1e-3) / 1e9
@@ -257,6 +289,7 @@ def main():
         "config": {"workload": wk["label"], "params": n_elems, "blocks": int(len(table)),
                    "buckets": int(n_buckets), "block_size": wk["block"], "precondition_frequency": f,
                    "grad_dtype": "bf16" if wk["bf16"] else "f32", "root_method": args.root_method,
+                   "precond_matrix_cores": "f32" if (args.fp32_matrix_cores or not wk["bf16"]) else "bf16x3",
                    "first_refresh_at_step": t_first},
         "refresh_ms": refresh_ms,
         "first_step_ms": first_step_ms,

@@ -49,6 +49,7 @@ enum {
 enum { SHAMPOO_GRAD_F32 = 0, SHAMPOO_GRAD_BF16 = 1 };
 enum { SHAMPOO_GRAFT_ADAGRAD = 0, SHAMPOO_GRAFT_SGD = 1, SHAMPOO_GRAFT_RMSPROP = 2, SHAMPOO_GRAFT_ADAM = 3 };
 enum { SHAMPOO_ROOT_EIGH = 0, SHAMPOO_ROOT_NEWTON = 1 };
+enum { SHAMPOO_MATRIX_CORES_AUTO = 0, SHAMPOO_MATRIX_CORES_FP32 = 1 };
 enum { SHAMPOO_LARGE_DIM_BLOCKING = 0, SHAMPOO_LARGE_DIM_ADAGRAD = 1, SHAMPOO_LARGE_DIM_DIAGONAL = 2 };
 
 /*
@@ -94,6 +95,11 @@ typedef struct {
                              condition number float32 can resolve                            */
   float newton_tolerance; /* stop when ||M_k - I||_inf < this; 0 selects 1e-6 (Sec. 3.2.1)     */
   int32_t newton_max_iterations; /* iteration cap, <= 1000; 0 selects 100                     */
+  int32_t precond_matrix_cores; /* SHAMPOO_MATRIX_CORES_AUTO (default): with bf16 gradients and blocks
+                             whose shape and alignment allow it, Lbar G Rbar runs on the bf16 matrix
+                             cores from float32 operands split exactly into three bf16 planes (six
+                             exact products accumulated in float32: float32 accuracy at 3/8 of the
+                             float32-MFMA time); SHAMPOO_MATRIX_CORES_FP32: always the float32 MFMA   */
   int32_t grad_dtype;     /* SHAMPOO_GRAD_F32 or SHAMPOO_GRAD_BF16; parameters are float32   */
   int32_t device;         /* HIP device ordinal                                              */
 } shampoo_config;
@@ -187,12 +193,13 @@ enum {
   SHAMPOO_STAGE_FACTOR = 0,   /* both symmetric rank-k factor updates       */
   SHAMPOO_STAGE_GRAFT = 1,    /* grafting state + graft norm                */
   SHAMPOO_STAGE_ROOT = 2,     /* root-inverse refresh                       */
-  SHAMPOO_STAGE_PRECOND = 3,  /* both GEMMs of Lbar G Rbar                  */
+  SHAMPOO_STAGE_PRECOND = 3,  /* T = Lbar G (diagonal Shampoo: the whole Lbar G Rbar) */
   SHAMPOO_STAGE_UPDATE = 4,   /* rescale + momentum + parameter update      */
   SHAMPOO_STAGE_DIAG = 5,     /* 1-D parameters                             */
   SHAMPOO_STAGE_FUSED = 6,    /* blocks <= 128 x 128 on steps without refresh: factor update,
                                  grafting, preconditioning and update in one kernel */
-  SHAMPOO_STAGE_COUNT = 7
+  SHAMPOO_STAGE_PRECOND2 = 7, /* P = T Rbar, with the sums of squares of P  */
+  SHAMPOO_STAGE_COUNT = 8
 };
 /* enable != 0: later steps record events around each stage (small overhead). */
 int shampoo_set_timing(shampoo_opt *opt, int32_t enable);

@@ -18,8 +18,9 @@ GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF = ran
 GRAFT_ADAGRAD, GRAFT_SGD, GRAFT_RMSPROP, GRAFT_ADAM = 0, 1, 2, 3
 ROOT_EIGH, ROOT_NEWTON = 0, 1
 LARGE_DIM_BLOCKING, LARGE_DIM_ADAGRAD, LARGE_DIM_DIAGONAL = 0, 1, 2
-STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG, STAGE_FUSED = range(7)
-STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag", "fused")
+MATRIX_CORES_AUTO, MATRIX_CORES_FP32 = 0, 1
+STAGE_FACTOR, STAGE_GRAFT, STAGE_ROOT, STAGE_PRECOND, STAGE_UPDATE, STAGE_DIAG, STAGE_FUSED, STAGE_PRECOND2 = range(8)
+STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag", "fused", "precond2")
 
 EXPORTS = (
     "shampoo_plan", "shampoo_workspace_bytes", "shampoo_create", "shampoo_step", "shampoo_get",
@@ -53,6 +54,7 @@ class ShampooConfig(ctypes.Structure):
         ("root_method", ctypes.c_int32),
         ("newton_tolerance", ctypes.c_float),
         ("newton_max_iterations", ctypes.c_int32),
+        ("precond_matrix_cores", ctypes.c_int32),
         ("grad_dtype", ctypes.c_int32),
         ("device", ctypes.c_int32),
     ]
@@ -120,7 +122,7 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
                 newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999,
-                large_dim_method=LARGE_DIM_BLOCKING):
+                large_dim_method=LARGE_DIM_BLOCKING, precond_matrix_cores=MATRIX_CORES_AUTO):
     """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
     n = len(shapes)
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
@@ -132,7 +134,8 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                         precondition_frequency, start_preconditioning_step, graft_epsilon,
                         momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
                         1 if use_nesterov else 0, grafting_type, grafting_beta2, 1 if use_bias_correction else 0,
-                        large_dim_method, root_method, newton_tolerance, newton_max_iterations, grad_dtype, device)
+                        large_dim_method, root_method, newton_tolerance, newton_max_iterations,
+                        precond_matrix_cores, grad_dtype, device)
     cfg._keep = (ndim, shape)
     return cfg
 
@@ -167,7 +170,7 @@ class Shampoo:
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
                 newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999,
-                large_dim_method=LARGE_DIM_BLOCKING):
+                large_dim_method=LARGE_DIM_BLOCKING, precond_matrix_cores=MATRIX_CORES_AUTO):
         import torch
         self.shapes = [tuple(s) for s in shapes]
         self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
@@ -175,7 +178,7 @@ class Shampoo:
                                momentum, grad_dtype, device, beta1, weight_decay,
                                use_decoupled_weight_decay, use_nesterov, grafting_type,
                                use_bias_correction, root_method, newton_tolerance, newton_max_iterations,
-                               grafting_beta2, large_dim_method)
+                               grafting_beta2, large_dim_method, precond_matrix_cores)
         self.device = torch.device("cuda", device)
         nbytes = shampoo_workspace_bytes(self.cfg)
         if nbytes == 0:

@@ -18,6 +18,7 @@
 #include "diag_shampoo.h"
 #include "eigh_jacobi.h"
 #include "elementwise.h"
+#include "gemm_bf16x3.h"
 #include "gemm_mfma.h"
 #include "newton_root.h"
 #include "syrk_bf16.h"
@@ -51,6 +52,10 @@ struct Bucket {
   int32_t m, n, count;
   // byte offsets into the workspace
   size_t off_L, off_R, off_Linv, off_Rinv, off_P, off_desc, off_sgp, off_sshp, off_scale, off_norms;
+  size_t off_Linv3 = 0, off_Rinv3 = 0;   // the roots as three bf16 planes (bf16 gradients, bf16_mfma buckets)
+  size_t off_Gt = 0;     // bf16 transpose of the bucket's gradient blocks, made by the factor update and
+                         // read again by the first preconditioning product of the same step
+  bool planes = false;
   EwGeom geom;
   int32_t tiles_m, tiles_n;
   bool bf16_mfma;   // shapes, offsets and leading dimensions allow the bf16 matrix-core factor update
@@ -112,6 +117,8 @@ int check_config(const shampoo_config *c) {
       if (c->ndim[i] == 2 && (c->shape[2 * i] > INT32_MAX / 2 || c->shape[2 * i + 1] > INT32_MAX / 2))
         return SHAMPOO_ERR_UNSUPPORTED;
   if (c->root_method != SHAMPOO_ROOT_EIGH && c->root_method != SHAMPOO_ROOT_NEWTON) return SHAMPOO_ERR_HYPER;
+  if (c->precond_matrix_cores != SHAMPOO_MATRIX_CORES_AUTO && c->precond_matrix_cores != SHAMPOO_MATRIX_CORES_FP32)
+    return SHAMPOO_ERR_HYPER;
   if (c->root_method == SHAMPOO_ROOT_NEWTON) {
     if (c->newton_tolerance < 0.f || !std::isfinite(c->newton_tolerance)) return SHAMPOO_ERR_HYPER;
     if (c->newton_max_iterations < 0 || c->newton_max_iterations > 1000) return SHAMPOO_ERR_HYPER;
@@ -520,7 +527,7 @@ struct shampoo_opt {
   unsigned char *ws = nullptr;
   size_t ws_bytes = 0;
   // workspace offsets
-  size_t off_Gt = 0, off_G1 = 0, off_Gf = 0, off_g1tab = 0, off_gftab = 0, off_prep = 0, off_small = 0;
+  size_t off_G1 = 0, off_Gf = 0, off_g1tab = 0, off_gftab = 0, off_prep = 0, off_small = 0;
   int64_t n_small = 0;     // blocks of at most 128 x 128 (single-workgroup step kernel)
   bool use_l2 = false, use_b1 = false;
   size_t off_A = 0, off_M = 0, off_T = 0, off_wtab = 0, off_gtab = 0, off_diag = 0, off_count = 0, off_eig = 0;
@@ -548,7 +555,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offG1tab = take((size_t)c->n_params * sizeof(void *));
   const size_t offGftab = take((size_t)c->n_params * sizeof(void *));
   const size_t offPrep = (use_l2 || use_b1) ? take(std::max<size_t>(1, p.prep_chunks.size()) * sizeof(DiagChunk)) : 0;
-  size_t t_elems = 0, gt_elems = 0, eig_bytes = 0;
+  size_t t_elems = 0, eig_bytes = 0;
   std::vector<EigLayout> eL, eR;
   for (auto &b : p.buckets) {
     const size_t B = b.count, m = b.m, n = b.n;
@@ -557,13 +564,21 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     b.off_Linv = take(B * b.l_elems() * 4);
     b.off_Rinv = take(B * b.r_elems() * 4);
     b.off_P = take(B * m * n * 4);
+    // bf16 gradients: the preconditioning products run on the bf16 matrix cores from
+    // operands kept split in three bf16 planes
+    b.planes = c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2 && !use_b1 &&
+               c->precond_matrix_cores != SHAMPOO_MATRIX_CORES_FP32;
+    if (b.planes) {
+      b.off_Linv3 = take(B * m * m * 6);
+      b.off_Rinv3 = take(B * n * n * 6);
+    }
     b.off_desc = take(B * sizeof(BlockDesc));
     b.off_sgp = take(B * b.geom.chunks * 4);
     b.off_sshp = take(B * std::max<size_t>((size_t)b.tiles_m * b.tiles_n, (size_t)b.geom.chunks) * 4);
     b.off_scale = take(B * 4);
     b.off_norms = take(B * 8);
-    t_elems = std::max(t_elems, B * m * n);
-    if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) gt_elems = std::max(gt_elems, B * m * n);
+    t_elems = std::max(t_elems, B * m * n * (b.planes ? 3 : 2) / 2);   // T as three bf16 planes: 6 bytes per element
+    if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) b.off_Gt = take(B * m * n * 2);
     // a diagonalised side needs no eigensolver workspace (stand-in layout of a 1 x 1 problem)
     const int em = b.diagL ? 1 : b.m, en = b.diagR ? 1 : b.n;
     eL.push_back(eig_layout(em, b.count));
@@ -574,7 +589,6 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
       eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
   }
   const size_t offT = take(t_elems * 4);
-  const size_t offGt = take(gt_elems * 2);
   const size_t offW = take((size_t)c->n_params * sizeof(void *));
   const size_t offG = take((size_t)c->n_params * sizeof(void *));
   const size_t offD = take(std::max<size_t>(1, p.diag_chunks.size()) * sizeof(DiagChunk));
@@ -584,7 +598,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offC = take(64);
   const size_t offE = take(eig_bytes);
   if (o) {
-    o->off_A = offA; o->off_M = offM; o->off_T = offT; o->off_Gt = offGt;
+    o->off_A = offA; o->off_M = offM; o->off_T = offT;
     o->off_G1 = offG1; o->off_Gf = offGf; o->off_g1tab = offG1tab; o->off_gftab = offGftab; o->off_prep = offPrep;
     o->use_l2 = use_l2; o->use_b1 = use_b1; o->off_wtab = offW; o->off_gtab = offG;
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
@@ -607,6 +621,21 @@ struct StageTimer {
     o->intervals[stage].push_back({a, b});
   }
 };
+
+// Re-splits the roots of every bucket that keeps them as bf16 planes (after create and after
+// every refresh).
+int split_roots(shampoo_opt *o, hipStream_t s) {
+  for (auto &b : o->plan.buckets) {
+    if (!b.planes) continue;
+    const int64_t nl = (int64_t)b.count * b.m * b.m, nr = (int64_t)b.count * b.n * b.n;
+    hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const float *>(o->ws + b.off_Linv), reinterpret_cast<uint16_t *>(o->ws + b.off_Linv3), nl);
+    hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const float *>(o->ws + b.off_Rinv), reinterpret_cast<uint16_t *>(o->ws + b.off_Rinv3), nr);
+    HIP_TRY(hipGetLastError());
+  }
+  return SHAMPOO_OK;
+}
 
 // GT: element type of the caller's gradients.  GS: of the gradients that feed the factors and
 // the grafting state (GT, or float when l2 weight decay materialises G + wd W).  GD: of the
@@ -681,7 +710,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
     if (sizeof(GS) == 2 && b.bf16_mfma && o->ptrs_aligned16) {
       StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
-      uint16_t *Gt = reinterpret_cast<uint16_t *>(ws + o->off_Gt);
+      uint16_t *Gt = reinterpret_cast<uint16_t *>(ws + b.off_Gt);
       TransposeArgs ta;
       ta.desc = desc; ta.g_table = gs_tab; ta.out = Gt; ta.m = b.m; ta.n = b.n;
       hipLaunchKernelGGL(transpose_bf16_kernel, dim3((b.n + 63) / 64, (b.m + 63) / 64, b.count), dim3(256), 0, s, ta);
@@ -804,6 +833,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       if (rc) return rc;
     }
     o->n_refresh++;
+    if ((rc = split_roots(o, s))) return rc;
   }
   for (auto &b : p.buckets) {
     const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
@@ -853,7 +883,38 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         HIP_TRY(hipGetLastError());
         ssh_count = b.geom.chunks;
       }
+    } else if (use_shampoo && sizeof(GD) == 2 && sizeof(GS) == 2 && b.planes && o->ptrs_aligned16) {
+      // bf16 gradients: both products on the bf16 matrix cores, float32-accurate through the
+      // three-plane split of the float32 operands (the gradient itself is one exact plane);
+      // B operands are read along k: G^T is the bf16 transpose made for the factor update
+      const int64_t per = ((int64_t)b.tiles_m * b.tiles_n * b.count + NUM_XCD - 1) / NUM_XCD;
+      uint16_t *T3 = reinterpret_cast<uint16_t *>(T);
+      const int64_t t_plane = (int64_t)b.count * b.m * b.n;
+      {
+      StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
+      GemmX3Args g{};
+      g.a = reinterpret_cast<const uint16_t *>(ws + b.off_Linv3);
+      g.a_plane_stride = (int64_t)b.count * b.m * b.m; g.a_batch_stride = (int64_t)b.m * b.m; g.lda = b.m;
+      g.b = reinterpret_cast<const uint16_t *>(ws + b.off_Gt); g.b_plane_stride = 0;
+      g.b_batch_stride = (int64_t)b.m * b.n; g.ldb = b.m;
+      g.c3 = T3; g.c3_plane_stride = t_plane; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
+      g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1;
+      g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.batch = b.count;
+      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 1, X3_STORE_SPLIT>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, g);
+      }
+      StageTimer t2(o, SHAMPOO_STAGE_PRECOND2, s);
+      GemmX3Args h{};
+      h.a = T3; h.a_plane_stride = t_plane; h.a_batch_stride = (int64_t)b.m * b.n; h.lda = b.n;
+      h.b = reinterpret_cast<const uint16_t *>(ws + b.off_Rinv3);
+      h.b_plane_stride = (int64_t)b.count * b.n * b.n; h.b_batch_stride = (int64_t)b.n * b.n; h.ldb = b.n;
+      h.c = P; h.c_batch_stride = (int64_t)b.m * b.n; h.ldc = b.n;
+      h.M = b.m; h.N = b.n; h.K = b.n; h.alpha = 1.f;
+      h.norm_partial = reinterpret_cast<float *>(ws + b.off_sshp);
+      h.tiles_m = b.tiles_m; h.tiles_n = b.tiles_n; h.batch = b.count;
+      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 3, X3_STORE_NORM>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, h);
+      HIP_TRY(hipGetLastError());
     } else if (use_shampoo) {
+      {
       StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
       GemmArgs g{};
       // T = Lbar G   (Lbar symmetric: A(i,k) read as Lbar[k][i], contiguous in i)
@@ -864,7 +925,9 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.tiles = b.tiles_m * b.tiles_n; g.batch = b.count;
       rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE, false>(g, s);
       if (rc) return rc;
+      }
       // P = T Rbar, with per-tile sums of squares
+      StageTimer t2(o, SHAMPOO_STAGE_PRECOND2, s);
       GemmArgs h{};
       h.a.base = T; h.a.batch_stride = (int64_t)b.m * b.n; h.a.ld = b.n;
       h.b.base = ws + b.off_Rinv; h.b.batch_stride = (int64_t)b.n * b.n; h.b.ld = b.n;
@@ -1020,6 +1083,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
                        hipMemcpyHostToDevice, s) != hipSuccess)
       return fail(SHAMPOO_ERR_HIP);
   }
+  if ((rc = split_roots(o, s))) return fail(rc);
   if (o->n_small > 0) {
     // largest blocks first, so that the tail of the launch is made of the cheapest workgroups
     std::vector<SmallBlock> small;

@@ -77,7 +77,8 @@ class Pair:
 
     def __init__(self, shapes, b, beta2, f, start=0, mu=0.9, eps=1e-12, eps_g=1e-10, bf16=False, seed=0,
                  beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad",
-                 bias_correction=False, newton=None, grafting_beta2=0.999, large_dim_method="blocking"):
+                 bias_correction=False, newton=None, grafting_beta2=0.999, large_dim_method="blocking",
+                 fp32_matrix_cores=False):
         self.shapes = shapes
         self.bf16 = bf16
         self.f, self.start, self.eps = f, start, f32(eps)
@@ -87,7 +88,8 @@ class Pair:
                               "adam": B.GRAFT_ADAM}[grafting], bias_correction,
                              B.ROOT_NEWTON if newton else B.ROOT_EIGH, *(newton or (1e-6, 100)), grafting_beta2,
                              {"blocking": B.LARGE_DIM_BLOCKING, "adagrad": B.LARGE_DIM_ADAGRAD,
-                              "diagonal": B.LARGE_DIM_DIAGONAL}[large_dim_method])
+                              "diagonal": B.LARGE_DIM_DIAGONAL}[large_dim_method],
+                             B.MATRIX_CORES_FP32 if fp32_matrix_cores else B.MATRIX_CORES_AUTO)
         self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, start, f32(eps_g), f32(mu),
                                     f32(beta1), f32(weight_decay), decoupled, nesterov, grafting,
                                     bias_correction, "newton" if newton else "eigh",
@@ -251,12 +253,14 @@ def test_ragged_shapes(b):
         p.check(t)
 
 
-def test_bf16_gradients_and_larger_blocks():
+@pytest.mark.parametrize("fp32_mc", [False, True])
+def test_bf16_gradients_and_larger_blocks(fp32_mc):
     """bf16 gradients (widened exactly), block 256 so that the blocked eigensolver
-    and multi-tile GEMMs run."""
-    say("case bf16")
+    and multi-tile GEMMs run; the preconditioning products on the bf16 matrix cores
+    (three-plane split, the default) and on the float32 ones."""
+    say(f"case bf16 fp32_matrix_cores={fp32_mc}")
     shapes = [(512, 256), (256,), (300, 520)]
-    p = Pair(shapes, 256, 0.999, 4, bf16=True)
+    p = Pair(shapes, 256, 0.999, 4, bf16=True, fp32_matrix_cores=fp32_mc)
     for t in range(6):
         p.step(wl.gaussian_grads(shapes, 4, t, 1e-3), 0.01, t)
         if t in (0, 3, 4, 5):

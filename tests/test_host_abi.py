@@ -93,7 +93,7 @@ def test_workspace_holds_the_state_of_the_memory_rule():
     (dict(momentum=1.0), -3), (dict(momentum=-0.1), -3), (dict(grad_dtype=7), -3),
     (dict(beta1=1.0), -3), (dict(beta1=-0.5), -3), (dict(weight_decay=-1.0), -3), (dict(grafting_type=5), -3),
     (dict(grafting_type=B.GRAFT_ADAM, grafting_beta2=0.0), -3), (dict(grafting_type=B.GRAFT_RMSPROP, grafting_beta2=1.5), -3),
-    (dict(large_dim_method=3), -3), (dict(root_method=3), -3), (dict(root_method=B.ROOT_NEWTON, newton_tolerance=-1.0), -3),
+    (dict(large_dim_method=3), -3), (dict(precond_matrix_cores=2), -3), (dict(root_method=3), -3), (dict(root_method=B.ROOT_NEWTON, newton_tolerance=-1.0), -3),
     (dict(root_method=B.ROOT_NEWTON, newton_max_iterations=5000), -3),
     (dict(root_method=B.ROOT_NEWTON, root_exponent=1.0 / 3.0), -7),
 ])
