@@ -331,6 +331,18 @@ __global__ __launch_bounds__(GEMM_THREADS, SHAMPOO_GEMM_MINBLOCKS) void gemm_mfm
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       const int j = col0 + wn * 64 + ni * 32 + (lane & 31);
+      // EPI_SYRK with a nonzero beta: the 16 old values of an MFMA tile are requested before
+      // its first store.  The mirrored stores may alias later loads, so interleaved they
+      // would cost one memory round trip per element instead of one per tile.
+      float old[EPI == EPI_SYRK ? 16 : 1];
+      if (EPI == EPI_SYRK) {
+        const bool need = ACC64 ? (g.beta_d != 0.0) : (g.beta != 0.f);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          old[EPI == EPI_SYRK ? v : 0] = (need && i < g.M && j <= i) ? c[(int64_t)i * ldc + j] : 0.f;
+        }
+      }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int ibase = row0 + wm * 64 + mi * 32 + 8 * q + 4 * (lane >> 5);
@@ -343,11 +355,9 @@ __global__ __launch_bounds__(GEMM_THREADS, SHAMPOO_GEMM_MINBLOCKS) void gemm_mfm
               // only the lower triangle is computed; its mirror image is written with the
               // same bits so the factor stays exactly symmetric
               if (j <= i) {
-                if (ACC64) {
-                  double vd = g.alpha_d * acc64[ACC64 ? mi : 0][ACC64 ? ni : 0][ACC64 ? 4 * q + e : 0];
-                  if (g.beta_d != 0.0) vd += g.beta_d * (double)c[(int64_t)i * ldc + j];
-                  v = (float)vd;
-                } else if (g.beta != 0.f) v += g.beta * c[(int64_t)i * ldc + j];
+                const float o = old[EPI == EPI_SYRK ? 4 * q + e : 0];
+                if (ACC64) v = (float)(g.alpha_d * acc64[ACC64 ? mi : 0][ACC64 ? ni : 0][ACC64 ? 4 * q + e : 0] + g.beta_d * (double)o);
+                else v += g.beta * o;
                 c[(int64_t)i * ldc + j] = v;
                 if (j < i) c[(int64_t)j * ldc + i] = v;
               }

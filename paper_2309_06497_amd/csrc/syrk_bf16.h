@@ -38,8 +38,15 @@ struct SyrkBf16Args {
 
 // Requires: operand base 16-byte aligned, ld % 8 == 0 (checked by the host).
 __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf16Args g) {
-  __shared__ __align__(16) uint16_t As[2][BM][SLD];
-  __shared__ __align__(16) uint16_t Bs[2][BN][SLD];
+  // one LDS region: the operand slabs during the k loop, then the tile on its way to the
+  // mirrored (transposed) position
+  constexpr int SYRK_TLD = BM + 1;
+  constexpr int SLAB_BYTES = 2 * BM * SLD * 2;
+  constexpr int LDS_BYTES = BN * SYRK_TLD * 4 > 2 * SLAB_BYTES ? BN * SYRK_TLD * 4 : 2 * SLAB_BYTES;
+  __shared__ __align__(16) unsigned char smem[LDS_BYTES];
+  uint16_t (*As)[BM][SLD] = reinterpret_cast<uint16_t (*)[BM][SLD]>(smem);
+  uint16_t (*Bs)[BN][SLD] = reinterpret_cast<uint16_t (*)[BN][SLD]>(smem + SLAB_BYTES);
+  float *Ts = reinterpret_cast<float *>(smem);
   const int total = g.tiles * g.batch;
   const int logical = xcd_remap(blockIdx.x, total);
   if (logical >= total) return;
@@ -119,27 +126,55 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
     __syncthreads();
   }
 
+  // Epilogue.  The lower-triangular tile is stored from the accumulators (rows of 32
+  // consecutive floats per half wavefront).  Its mirror image would be a scatter of single
+  // floats, so the tile goes through LDS transposed and is stored along rows as well; a
+  // diagonal tile is completed to the full symmetric tile in LDS and stored once.  Both
+  // copies carry the same bits, so the factor stays exactly symmetric.
   float *c = g.c + (int64_t)b * g.c_batch_stride;
   const int ldc = g.ldc;
+  const bool diag = ti == tj;
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
-      const int j = col0 + wn * 64 + ni * 32 + (lane & 31);
+      const int jl = wn * 64 + ni * 32 + (lane & 31), j = col0 + jl;
+      float old[16];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int v = 0; v < 16; ++v) {
+        const int i = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        old[v] = (g.beta != 0.0 && i < g.M && j <= i) ? c[(int64_t)i * ldc + j] : 0.f;
+      }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = row0 + wm * 64 + mi * 32 + 8 * q + 4 * (lane >> 5) + e;
-          if (i < g.M && j <= i) {
-            double vd = g.alpha * acc64[mi][ni][4 * q + e];
-            if (g.beta != 0.0) vd += g.beta * (double)c[(int64_t)i * ldc + j];
-            const float v = (float)vd;
-            c[(int64_t)i * ldc + j] = v;
-            if (j < i) c[(int64_t)j * ldc + i] = v;
-          }
+      for (int v = 0; v < 16; ++v) {
+        const int il = wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), i = row0 + il;
+        const float x = (float)(g.alpha * acc64[mi][ni][v] + g.beta * (double)old[v]);
+        if (diag) {
+          if (jl <= il) { Ts[il * SYRK_TLD + jl] = x; Ts[jl * SYRK_TLD + il] = x; }
+        } else {
+          Ts[jl * SYRK_TLD + il] = x;
+          if (i < g.M && j < g.M) c[(int64_t)i * ldc + j] = x;
         }
+      }
     }
+  __syncthreads();
+  {
+    // rows of the LDS tile -> rows of C at (col0, row0) (or (row0, row0) for a diagonal tile)
+    const int rbase = diag ? row0 : col0, cbase = row0;
+    const int cx = (tid & 31) * 4;
+    const bool vec = (ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(c) & 15) == 0;
+    for (int rr = tid >> 5; rr < BM; rr += GEMM_THREADS / 32) {
+      const int gi = rbase + rr, gj = cbase + cx;
+      if (gi >= g.M || gj >= g.M) continue;
+      const float *src = Ts + rr * SYRK_TLD + cx;
+      if (vec && gj + 3 < g.M) {
+        *reinterpret_cast<float4 *>(c + (int64_t)gi * ldc + gj) = make_float4(src[0], src[1], src[2], src[3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (gj + e < g.M) c[(int64_t)gi * ldc + gj + e] = src[e];
+      }
+    }
+  }
 }
 
 struct TransposeArgs {
