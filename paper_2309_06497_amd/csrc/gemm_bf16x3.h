@@ -19,9 +19,9 @@
 //   T = Lbar G       A = Lbar (three planes)   B = G^T (the bf16 transpose of the block, one plane)
 //   P = T Rbar       A = T (three planes)      B = Rbar (symmetric, three planes)
 // Tile 128 x 128 per workgroup of 4 wavefronts (64 x 64 each, 2 x 2 MFMA tiles); operand
-// slabs of 32 values of k are staged in LDS as [plane][row][k] (rows padded to 80 bytes,
-// 60 KB for 3 + 3 planes, two workgroups per CU); the global loads of the next slab are in
-// flight while the current one is multiplied.  An MFMA operand is 8 consecutive k of one row per lane:
+// slabs of 32 values of k (64 for the first product) are staged in LDS as [plane][row][k]
+// (rows padded by 16 bytes; 60 KB for 3 + 3 planes, two workgroups per CU); the global loads
+// of the next slab are in flight while the current one is multiplied.  An MFMA operand is 8 consecutive k of one row per lane:
 // lane = row % 32 + 32 * (k / 8).
 // Requires K % 8 == 0, leading dimensions % 8 == 0 and 16-byte aligned operands (the host
 // checks, and otherwise uses the float32-MFMA kernel).
@@ -33,17 +33,14 @@
 
 namespace shampoo {
 
-#ifndef SHAMPOO_X3_BK
-#define SHAMPOO_X3_BK 32
+#ifndef SHAMPOO_X3_BK1
+#define SHAMPOO_X3_BK1 64
 #endif
-#ifndef SHAMPOO_X3_MINBLOCKS
-#define SHAMPOO_X3_MINBLOCKS 2
+#ifndef SHAMPOO_X3_BK2
+#define SHAMPOO_X3_BK2 32
 #endif
-constexpr int XBK = SHAMPOO_X3_BK;      // k per slab (16 or 32)
-constexpr int XLD = XBK + 8;            // LDS row stride, bf16 elements (an odd number of 16-byte units)
-constexpr int XCPR = XBK / 8;           // 16-byte chunks per row of a slab
-constexpr int XRPP = GEMM_THREADS / XCPR;   // rows per pass of the loader
-constexpr int XPASS = BM / XRPP;
+constexpr int X3_BK_FIRST = SHAMPOO_X3_BK1;    // k per slab of T = Lbar G (3 + 1 planes)
+constexpr int X3_BK_SECOND = SHAMPOO_X3_BK2;   // k per slab of P = T Rbar (3 + 3 planes)
 
 enum { X3_STORE_NORM = 0, X3_STORE_SPLIT = 1 };
 
@@ -84,8 +81,13 @@ __global__ __launch_bounds__(256) void split3_kernel(const float *in, uint16_t *
   out[i] = (uint16_t)h; out[count + i] = (uint16_t)m; out[2 * count + i] = (uint16_t)l;
 }
 
-template <int NA, int NB, int EPI>
-__global__ __launch_bounds__(GEMM_THREADS, SHAMPOO_X3_MINBLOCKS) void gemm_bf16x3_kernel(const GemmX3Args g) {
+// XBK: k per slab (16, 32 or 64)
+template <int NA, int NB, int EPI, int XBK>
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16x3_kernel(const GemmX3Args g) {
+  constexpr int XLD = XBK + 8;                // LDS row stride, bf16 elements (an odd number of 16-byte units)
+  constexpr int XCPR = XBK / 8;               // 16-byte chunks per row of a slab
+  constexpr int XRPP = GEMM_THREADS / XCPR;   // rows per pass of the loader
+  constexpr int XPASS = BM / XRPP;
   __shared__ __align__(16) uint16_t As[NA][BM][XLD];
   __shared__ __align__(16) uint16_t Bs[NB][BN][XLD];
   __shared__ float red[4];
@@ -105,9 +107,12 @@ __global__ __launch_bounds__(GEMM_THREADS, SHAMPOO_X3_MINBLOCKS) void gemm_bf16x
   const uint16_t *pb = g.b + (int64_t)b * g.b_batch_stride + (int64_t)(col0 + r) * g.ldb + kc;
   // The slab after the one being multiplied is already on its way into registers; it is
   // written to LDS once every wavefront has finished reading the current one.  (Measured on
-  // the 1024-blocks: slabs of 32 in one LDS buffer 20.3 ms for both products; slabs of 16
-  // double-buffered 25.4; slabs of 32 double-buffered, one workgroup per CU, 28.9; loads two
-  // slabs ahead 21.9.)
+  // the 1024-blocks, both products together: slabs of 32 in one LDS buffer 20.3 ms; slabs of
+  // 16 double-buffered 25.4; slabs of 32 double-buffered, one workgroup per CU, 28.9; loads
+  // two slabs ahead 21.9; 8 wavefronts of which 4 only move operands and 4 only multiply,
+  // double-buffered, 25.5; the same with the LDS reads of the next 16 k issued ahead of the
+  // MFMAs, 26.9.  With real roots instead of identities every variant is ~25 % slower: the
+  // same instruction stream on denser data, i.e. the clocks give way.)
   uint4 ra[XPASS][NA], rb[XPASS][NB];
   auto fetch = [&](int k0) {
     const bool kin = k0 + kc < g.K;     // K % 8 == 0: a chunk is entirely in or out

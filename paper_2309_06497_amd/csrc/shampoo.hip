@@ -900,7 +900,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       g.c3 = T3; g.c3_plane_stride = t_plane; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
       g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1;
       g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.batch = b.count;
-      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 1, X3_STORE_SPLIT>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, g);
+      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 1, X3_STORE_SPLIT, X3_BK_FIRST>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, g);
       }
       StageTimer t2(o, SHAMPOO_STAGE_PRECOND2, s);
       GemmX3Args h{};
@@ -911,7 +911,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       h.M = b.m; h.N = b.n; h.K = b.n; h.alpha = 1.f;
       h.norm_partial = reinterpret_cast<float *>(ws + b.off_sshp);
       h.tiles_m = b.tiles_m; h.tiles_n = b.tiles_n; h.batch = b.count;
-      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 3, X3_STORE_NORM>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, h);
+      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 3, X3_STORE_NORM, X3_BK_SECOND>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, h);
       HIP_TRY(hipGetLastError());
     } else if (use_shampoo) {
       {
