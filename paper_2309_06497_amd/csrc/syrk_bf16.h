@@ -22,7 +22,11 @@ namespace shampoo {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int SBK = 32;          // k per slab
+#ifndef SHAMPOO_SYRK_CHAIN
+#define SHAMPOO_SYRK_CHAIN 2
+#endif
+constexpr int SCH = SHAMPOO_SYRK_CHAIN;   // MFMAs (16 k each) chained in float32 before the float64 flush
+constexpr int SBK = 16 * SCH;             // k per slab
 constexpr int SLD = SBK + 8;     // LDS row stride, bf16 elements
 
 struct SyrkBf16Args {
@@ -66,13 +70,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   const uint16_t *xb = x + (int64_t)col0 * ld;
   const int rows_a = g.M - row0, rows_b = g.M - col0;
 
-  // thread (r, kc): rows r and r + 64, 8 consecutive k starting at kc
-  const int r = tid >> 2, kc = (tid & 3) * 8;
-  uint4 ra[2], rb[2];
+  // thread (r, kc): rows r + SRPP * h, 8 consecutive k starting at kc
+  constexpr int SCPR = SBK / 8, SRPP = GEMM_THREADS / SCPR, SPASS = BM / SRPP;
+  const int r = tid / SCPR, kc = (tid % SCPR) * 8;
+  uint4 ra[SPASS], rb[SPASS];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int rr = r + 64 * h;
+    for (int h = 0; h < SPASS; ++h) {
+      const int rr = r + SRPP * h;
       const bool kin = k0 + kc < g.K;     // K % 8 == 0: a chunk is entirely in or out
       ra[h] = (rr < rows_a && kin) ? *reinterpret_cast<const uint4 *>(xa + (int64_t)rr * ld + k0 + kc) : make_uint4(0, 0, 0, 0);
       rb[h] = (rr < rows_b && kin) ? *reinterpret_cast<const uint4 *>(xb + (int64_t)rr * ld + k0 + kc) : make_uint4(0, 0, 0, 0);
@@ -80,9 +85,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      *reinterpret_cast<uint4 *>(&As[buf][r + 64 * h][kc]) = ra[h];
-      *reinterpret_cast<uint4 *>(&Bs[buf][r + 64 * h][kc]) = rb[h];
+    for (int h = 0; h < SPASS; ++h) {
+      *reinterpret_cast<uint4 *>(&As[buf][r + SRPP * h][kc]) = ra[h];
+      *reinterpret_cast<uint4 *>(&Bs[buf][r + SRPP * h][kc]) = rb[h];
     }
   };
 
@@ -105,20 +110,17 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) fetch((kt + 1) * SBK);
-    bf16x8 a[2][2], bb[2][2];   // [k-step][tile]
-#pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        a[s][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[cur][wm * 64 + t * 32 + fi][s * 16 + fk]));
-        bb[s][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[cur][wn * 64 + t * 32 + fi][s * 16 + fk]));
-      }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        floatx16 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], bb[0][j], zero, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], bb[1][j], acc, 0, 0, 0);
+        floatx16 acc = zero;
+#pragma unroll
+        for (int s = 0; s < SCH; ++s) {
+          const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[cur][wm * 64 + i * 32 + fi][s * 16 + fk]));
+          const bf16x8 bb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[cur][wn * 64 + j * 32 + fi][s * 16 + fk]));
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc, 0, 0, 0);
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc64[i][j][v] += (double)acc[v];
       }
