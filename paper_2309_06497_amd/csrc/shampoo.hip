@@ -887,7 +887,9 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       // bf16 gradients: both products on the bf16 matrix cores, float32-accurate through the
       // three-plane split of the float32 operands (the gradient itself is one exact plane);
       // B operands are read along k: G^T is the bf16 transpose made for the factor update
-      const int64_t per = ((int64_t)b.tiles_m * b.tiles_n * b.count + NUM_XCD - 1) / NUM_XCD;
+      const int x3_tm = (b.m + X3_TM - 1) / X3_TM, x3_tn = (b.n + X3_TN - 1) / X3_TN;
+      const int64_t per = ((int64_t)x3_tm * x3_tn * b.count + NUM_XCD - 1) / NUM_XCD;
+      ssh_count = x3_tm * x3_tn;
       uint16_t *T3 = reinterpret_cast<uint16_t *>(T);
       const int64_t t_plane = (int64_t)b.count * b.m * b.n;
       {
@@ -899,8 +901,8 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       g.b_batch_stride = (int64_t)b.m * b.n; g.ldb = b.m;
       g.c3 = T3; g.c3_plane_stride = t_plane; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
       g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1;
-      g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.batch = b.count;
-      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 1, X3_STORE_SPLIT, X3_BK_FIRST>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, g);
+      g.tiles_m = x3_tm; g.tiles_n = x3_tn; g.batch = b.count;
+      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 1, X3_STORE_SPLIT>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, g);
       }
       StageTimer t2(o, SHAMPOO_STAGE_PRECOND2, s);
       GemmX3Args h{};
@@ -910,8 +912,8 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       h.c = P; h.c_batch_stride = (int64_t)b.m * b.n; h.ldc = b.n;
       h.M = b.m; h.N = b.n; h.K = b.n; h.alpha = 1.f;
       h.norm_partial = reinterpret_cast<float *>(ws + b.off_sshp);
-      h.tiles_m = b.tiles_m; h.tiles_n = b.tiles_n; h.batch = b.count;
-      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 3, X3_STORE_NORM, X3_BK_SECOND>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, h);
+      h.tiles_m = x3_tm; h.tiles_n = x3_tn; h.batch = b.count;
+      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 3, X3_STORE_NORM>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, h);
       HIP_TRY(hipGetLastError());
     } else if (use_shampoo) {
       {

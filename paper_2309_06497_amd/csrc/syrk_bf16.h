@@ -8,11 +8,23 @@
 // to float32.  R = G^T G runs through the same kernel on a bf16 transpose of the
 // block (transpose_bf16_kernel), so both operands are always read along k.
 //
-// Tile 128 x 128 per workgroup of 4 wavefronts (64 x 64 each, 2 x 2 MFMA tiles);
-// operand tiles are staged in LDS as [row][k] with 32 values of k per slab (rows
-// padded to 80 bytes), double-buffered.  An MFMA operand is 8 consecutive k of one
-// row per lane: lane = row % 32 + 32 * (k / 8).  Only lower-triangular tiles are
-// computed; the mirror image is written with the same bits.
+// Tile 128 x 128 per workgroup of 4 wavefronts (64 x 64 each, 2 x 2 MFMA tiles).
+// The operand slabs (128 rows x 32 k of each operand) never pass through registers:
+// global_load_lds_dwordx4 moves 16 bytes per lane straight into LDS, three slabs deep,
+// so that two slabs are in flight while one is multiplied.  Such a load writes the 64
+// lanes' chunks to consecutive LDS addresses, which leaves no room for row padding;
+// bank conflicts are avoided by a swizzle instead: the 16-byte chunk c of row r sits at
+// chunk position c ^ ((r >> 1) & 3) of its 64-byte LDS row (the lane picks its global
+// address accordingly).  An MFMA operand is 8 consecutive k of one row per lane:
+// lane = row % 32 + 32 * (k / 8).
+//
+// The compiler's own wait-count placement would wait for every outstanding load before
+// the first LDS read of a slab (it cannot tell the stages apart), so the LDS reads of the
+// main loop and the waits that belong to them are written as inline assembly, and the
+// workgroup barrier of the loop is the bare s_barrier: the loads of later slabs stay in
+// flight across it.
+//
+// Only lower-triangular tiles are computed; the mirror image is written with the same bits.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -21,13 +33,14 @@
 namespace shampoo {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void glb_void;
 
-#ifndef SHAMPOO_SYRK_CHAIN
-#define SHAMPOO_SYRK_CHAIN 2
-#endif
-constexpr int SCH = SHAMPOO_SYRK_CHAIN;   // MFMAs (16 k each) chained in float32 before the float64 flush
-constexpr int SBK = 16 * SCH;             // k per slab
-constexpr int SLD = SBK + 8;     // LDS row stride, bf16 elements
+constexpr int SBK = 32;                        // k per slab: two MFMAs chained in float32, then the float64 flush
+constexpr int SYRK_SLAB = BM * SBK * 2;        // bytes of one operand slab
+constexpr int SYRK_STAGE = 2 * SYRK_SLAB;      // A slab, then B slab
+constexpr int SYRK_STAGES = 3;
 
 struct SyrkBf16Args {
   Operand a;                 // bf16 matrix X (rows x K, k contiguous); C = beta C + alpha X X^T
@@ -40,16 +53,39 @@ struct SyrkBf16Args {
   int32_t batch;
 };
 
-// Requires: operand base 16-byte aligned, ld % 8 == 0 (checked by the host).
+// a wave-uniform pointer, held in scalar registers
+__device__ __forceinline__ const char *uniform_ptr(const void *p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ void syrk_flush(double (&dst)[16], const floatx16 &src) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) dst[v] += (double)src[v];
+}
+
+__device__ __forceinline__ floatx16 syrk_chain(const u32x4 &a0, const u32x4 &b0, const u32x4 &a1, const u32x4 &b1) {
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
+  return acc;
+}
+
+#define SYRK_DS_READ(dst, addr, imm) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm) : "memory")
+// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters at their maxima)
+#define SYRK_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+#define SYRK_SB() __builtin_amdgcn_sched_barrier(0)
+
+// Requires: operand base 16-byte aligned, ld % 8 == 0, K % 8 == 0 (checked by the host).
 __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf16Args g) {
   // one LDS region: the operand slabs during the k loop, then the tile on its way to the
   // mirrored (transposed) position
   constexpr int SYRK_TLD = BM + 1;
-  constexpr int SLAB_BYTES = 2 * BM * SLD * 2;
-  constexpr int LDS_BYTES = BN * SYRK_TLD * 4 > 2 * SLAB_BYTES ? BN * SYRK_TLD * 4 : 2 * SLAB_BYTES;
-  __shared__ __align__(16) unsigned char smem[LDS_BYTES];
-  uint16_t (*As)[BM][SLD] = reinterpret_cast<uint16_t (*)[BM][SLD]>(smem);
-  uint16_t (*Bs)[BN][SLD] = reinterpret_cast<uint16_t (*)[BN][SLD]>(smem + SLAB_BYTES);
+  constexpr int LDS_BYTES = BN * SYRK_TLD * 4 > SYRK_STAGES * SYRK_STAGE ? BN * SYRK_TLD * 4 : SYRK_STAGES * SYRK_STAGE;
+  __shared__ __align__(128) unsigned char smem[LDS_BYTES];   // the k-step addresses below differ by an XOR
   float *Ts = reinterpret_cast<float *>(smem);
   const int total = g.tiles * g.batch;
   const int logical = xcd_remap(blockIdx.x, total);
@@ -70,26 +106,39 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   const uint16_t *xb = x + (int64_t)col0 * ld;
   const int rows_a = g.M - row0, rows_b = g.M - col0;
 
-  // thread (r, kc): rows r + SRPP * h, 8 consecutive k starting at kc
-  constexpr int SCPR = SBK / 8, SRPP = GEMM_THREADS / SCPR, SPASS = BM / SRPP;
-  const int r = tid / SCPR, kc = (tid % SCPR) * 8;
-  uint4 ra[SPASS], rb[SPASS];
-  auto fetch = [&](int k0) {
+  // Chunk position p = 64 q + lane of a slab (q = 2 wave + t): LDS row p / 4, position p % 4
+  // within it.  Rows past the end of the matrix read its last row instead: they only reach
+  // elements of the tile that are never stored.
+  constexpr int PER_WAVE = BM * (SBK / 8) / 64 / 4;
+  constexpr int PW = 2 * PER_WAVE;               // loads per wavefront per slab
+  const int uw = __builtin_amdgcn_readfirstlane(wave);
+  uint32_t offa[PER_WAVE], offb[PER_WAVE];
+  int chunk_k[PER_WAVE];
 #pragma unroll
-    for (int h = 0; h < SPASS; ++h) {
-      const int rr = r + SRPP * h;
-      const bool kin = k0 + kc < g.K;     // K % 8 == 0: a chunk is entirely in or out
-      ra[h] = (rr < rows_a && kin) ? *reinterpret_cast<const uint4 *>(xa + (int64_t)rr * ld + k0 + kc) : make_uint4(0, 0, 0, 0);
-      rb[h] = (rr < rows_b && kin) ? *reinterpret_cast<const uint4 *>(xb + (int64_t)rr * ld + k0 + kc) : make_uint4(0, 0, 0, 0);
+  for (int t = 0; t < PER_WAVE; ++t) {
+    const int p = (wave * PER_WAVE + t) * 64 + lane;
+    const int row = p >> 2, ch = (p & 3) ^ ((row >> 1) & 3);
+    chunk_k[t] = ch * 8;
+    offa[t] = (uint32_t)(min(row, rows_a - 1) * ld + ch * 8) * 2u;
+    offb[t] = (uint32_t)(min(row, rows_b - 1) * ld + ch * 8) * 2u;
+  }
+  auto issue = [&](int stage, int k0) {
+    const char *ga = uniform_ptr(xa + k0);
+    const char *gb = uniform_ptr(xb + k0);
+    unsigned char *sa = smem + stage * SYRK_STAGE, *sb = sa + SYRK_SLAB;
+#pragma unroll
+    for (int t = 0; t < PER_WAVE; ++t) {
+      const int q = uw * PER_WAVE + t;
+      __builtin_amdgcn_global_load_lds((glb_void *)(ga + offa[t]), (lds_void *)(sa + q * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(gb + offb[t]), (lds_void *)(sb + q * 1024), 16, 0, 0);
     }
   };
-  auto stash = [&](int buf) {
-#pragma unroll
-    for (int h = 0; h < SPASS; ++h) {
-      *reinterpret_cast<uint4 *>(&As[buf][r + SRPP * h][kc]) = ra[h];
-      *reinterpret_cast<uint4 *>(&Bs[buf][r + SRPP * h][kc]) = rb[h];
-    }
-  };
+
+  // LDS byte addresses of this lane's operand rows: k step s of a slab is chunk 2 s + lane / 32
+  const int fi = lane & 31, fq = lane >> 5;
+  const uint32_t lbase = (uint32_t)(uintptr_t)(lds_void *)smem;
+  const uint32_t la0 = lbase + ((wm * 64 + fi) * SBK + ((fq ^ ((fi >> 1) & 3)) * 8)) * 2, la1 = la0 ^ 32;
+  const uint32_t lb0 = lbase + ((wn * 64 + fi) * SBK + ((fq ^ ((fi >> 1) & 3)) * 8)) * 2, lb1 = lb0 ^ 32;
 
   double acc64[2][2][16];
 #pragma unroll
@@ -98,35 +147,74 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc64[i][j][v] = 0.0;
-  floatx16 zero;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 
-  const int nk = (g.K + SBK - 1) / SBK;
-  fetch(0);
-  stash(0);
-  __syncthreads();
-  const int fi = lane & 31, fk = (lane >> 5) * 8;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) fetch((kt + 1) * SBK);
+  const int nk = g.K / SBK;                      // full slabs; K % SBK values of k remain
+  if (nk > 0) issue(0, 0);
+  if (nk > 1) issue(1, SBK);
+  u32x4 oa[2][2], ob[2][2];                      // [i or j][k step]
+  floatx16 X, Y;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        floatx16 acc = zero;
-#pragma unroll
-        for (int s = 0; s < SCH; ++s) {
-          const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&As[cur][wm * 64 + i * 32 + fi][s * 16 + fk]));
-          const bf16x8 bb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(&Bs[cur][wn * 64 + j * 32 + fi][s * 16 + fk]));
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bb, acc, 0, 0, 0);
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc64[i][j][v] += (double)acc[v];
-      }
-    if (kt + 1 < nk) stash(cur ^ 1);
-    __syncthreads();
+  for (int v = 0; v < 16; ++v) Y[v] = 0.f;
+  // The eight operand reads of the slab in stage S, then, for the four 32 x 32 tiles of the
+  // wavefront, the MFMA pair of one tile issued before the float64 flush of the tile before
+  // it, so that the flush (VALU) runs beside the MFMAs.  The accumulator of the last tile (Y)
+  // is flushed during the next slab.
+#define SYRK_SLAB_PRODUCT(S)                                                              \
+  {                                                                                       \
+    SYRK_DS_READ(oa[0][0], la0, (S) * SYRK_STAGE);                                        \
+    SYRK_DS_READ(ob[0][0], lb0, (S) * SYRK_STAGE + SYRK_SLAB);                            \
+    SYRK_DS_READ(oa[0][1], la1, (S) * SYRK_STAGE);                                        \
+    SYRK_DS_READ(ob[0][1], lb1, (S) * SYRK_STAGE + SYRK_SLAB);                            \
+    SYRK_DS_READ(oa[1][0], la0, (S) * SYRK_STAGE + 32 * SBK * 2);                         \
+    SYRK_DS_READ(ob[1][0], lb0, (S) * SYRK_STAGE + SYRK_SLAB + 32 * SBK * 2);             \
+    SYRK_DS_READ(oa[1][1], la1, (S) * SYRK_STAGE + 32 * SBK * 2);                         \
+    SYRK_DS_READ(ob[1][1], lb1, (S) * SYRK_STAGE + SYRK_SLAB + 32 * SBK * 2);             \
+    asm volatile("s_waitcnt lgkmcnt(0)"                                                   \
+                 : "+v"(oa[0][0]), "+v"(oa[0][1]), "+v"(oa[1][0]), "+v"(oa[1][1]),        \
+                   "+v"(ob[0][0]), "+v"(ob[0][1]), "+v"(ob[1][0]), "+v"(ob[1][1]) :: "memory"); \
+    SYRK_SB();                                                                            \
+    X = syrk_chain(oa[0][0], ob[0][0], oa[0][1], ob[0][1]); SYRK_SB();                    \
+    syrk_flush(acc64[1][1], Y); SYRK_SB();                                                \
+    Y = syrk_chain(oa[0][0], ob[1][0], oa[0][1], ob[1][1]); SYRK_SB();                    \
+    syrk_flush(acc64[0][0], X); SYRK_SB();                                                \
+    X = syrk_chain(oa[1][0], ob[0][0], oa[1][1], ob[0][1]); SYRK_SB();                    \
+    syrk_flush(acc64[0][1], Y); SYRK_SB();                                                \
+    Y = syrk_chain(oa[1][0], ob[1][0], oa[1][1], ob[1][1]); SYRK_SB();                    \
+    syrk_flush(acc64[1][0], X); SYRK_SB();                                                \
   }
+
+  if (g.K % SBK) {
+    // The ragged end of k goes first, through registers with zero fill, into the third
+    // stage, while the first two full slabs are on their way.
+    const int k0 = nk * SBK;
+#pragma unroll
+    for (int t = 0; t < PER_WAVE; ++t) {
+      const int q = wave * PER_WAVE + t;
+      const bool kin = k0 + chunk_k[t] < g.K;      // K % 8 == 0: a chunk is entirely in or out
+      const uint4 va = kin ? *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(xa + k0) + offa[t]) : make_uint4(0, 0, 0, 0);
+      const uint4 vb = kin ? *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(xb + k0) + offb[t]) : make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<uint4 *>(smem + 2 * SYRK_STAGE + q * 1024 + lane * 16) = va;
+      *reinterpret_cast<uint4 *>(smem + 2 * SYRK_STAGE + SYRK_SLAB + q * 1024 + lane * 16) = vb;
+    }
+    __syncthreads();
+    SYRK_SLAB_PRODUCT(2);
+  }
+  // Slab kt is multiplied while slabs kt + 1 and kt + 2 are on their way.
+#define SYRK_STEP(S, NEXT, KT)                                                            \
+  {                                                                                       \
+    if ((KT) + 1 < nk) { SYRK_WAIT_VM(PW); } else { SYRK_WAIT_VM(0); }                    \
+    __builtin_amdgcn_s_barrier();                                                         \
+    if ((KT) + 2 < nk) issue(NEXT, ((KT) + 2) * SBK);                                     \
+    if ((KT) < nk) SYRK_SLAB_PRODUCT(S);                                                  \
+  }
+  for (int kt = 0; kt < nk; kt += 3) {
+    SYRK_STEP(0, 2, kt);
+    SYRK_STEP(1, 0, kt + 1);
+    SYRK_STEP(2, 1, kt + 2);
+  }
+  syrk_flush(acc64[1][1], Y);
+  SYRK_WAIT_VM(0);
+  __syncthreads();                               // the slabs are dead: the region becomes Ts
 
   // Epilogue.  The lower-triangular tile is stored from the accumulators (rows of 32
   // consecutive floats per half wavefront).  Its mirror image would be a scatter of single
@@ -136,21 +224,35 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   float *c = g.c + (int64_t)b * g.c_batch_stride;
   const int ldc = g.ldc;
   const bool diag = ti == tj;
+  // The old values of half a quadrant (32 x 64) are requested before any of them is used,
+  // from clamped (always valid) addresses so that the loads are unconditional: one memory
+  // round trip per half instead of one per element.
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < 2; ++mi) {
+    float old[2][16];
+    if (g.beta != 0.0) {
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) {
+        const int j = min(col0 + wn * 64 + ni * 32 + (lane & 31), g.M - 1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = min(row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), g.M - 1);
+          old[ni][v] = c[(int64_t)i * ldc + j];
+        }
+      }
+    } else {
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) old[ni][v] = 0.f;
+    }
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       const int jl = wn * 64 + ni * 32 + (lane & 31), j = col0 + jl;
-      float old[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        old[v] = (g.beta != 0.0 && i < g.M && j <= i) ? c[(int64_t)i * ldc + j] : 0.f;
-      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int il = wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), i = row0 + il;
-        const float x = (float)(g.alpha * acc64[mi][ni][v] + g.beta * (double)old[v]);
+        const float x = (float)(g.alpha * acc64[mi][ni][v] + g.beta * (double)old[ni][v]);
         if (diag) {
           if (jl <= il) { Ts[il * SYRK_TLD + jl] = x; Ts[jl * SYRK_TLD + il] = x; }
         } else {
@@ -159,6 +261,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
         }
       }
     }
+  }
   __syncthreads();
   {
     // rows of the LDS tile -> rows of C at (col0, row0) (or (row0, row0) for a diagonal tile)
@@ -178,6 +281,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
     }
   }
 }
+#undef SYRK_STEP
+#undef SYRK_SLAB_PRODUCT
 
 struct TransposeArgs {
   const BlockDesc *desc;

@@ -267,6 +267,18 @@ def test_bf16_gradients_and_larger_blocks(fp32_mc):
             p.check(t)
 
 
+def test_bf16_ragged_blocks_on_matrix_cores():
+    """bf16 gradients with block sides that are multiples of 8 but not of the 32-deep k slab
+    of the bf16 factor kernel (200, 72, 8): the ragged end of k and the clamped rows of
+    partial tiles."""
+    say("case bf16 ragged k")
+    shapes = [(328, 456), (264, 40)]
+    p = Pair(shapes, 256, 0.999, 1, eps=1e-6, bf16=True)
+    for t in range(4):
+        p.step(wl.gaussian_grads(shapes, 21, t, 1e-3), 0.01, t)
+        p.check(t)
+
+
 def test_grafting_warmup_then_shampoo():
     say("case warmup")
     shapes = [(96, 80), (33,)]
