@@ -52,9 +52,9 @@ TRAFFIC_BYTES = {"transformer": 14.43e9 + 4.83e9}
 # the same for the single-workgroup block-step kernel on the ResNet-50 shapes:
 # profiles/resnet50_b128_hbm_traffic_pmc.md
 FUSED_TRAFFIC_BYTES = {"resnet50": 0.849e9 + 0.631e9}
-# and for the two bf16 three-plane GEMMs of the transformer workload (average of the two launches):
+# and for P = T Rbar on the bf16 matrix cores (three-plane operands) of the transformer workload:
 # profiles/transformer_b1024_hbm_traffic_pmc.md
-X3_TRAFFIC_BYTES = {"transformer": 21.66e9 + 4.83e9}
+X3_TRAFFIC_BYTES = {"transformer": 14.50e9 + 4.83e9}
 PEAK_HBM_GBS = 8000.0
 TILE = 128
 
