@@ -44,6 +44,18 @@ weight decay, no momentum):
                 replaced by its diagonal: l_i <- beta2 l_i + (1-beta2) sum_j G_ij^2 (likewise
                 r_j), root inverse elementwise by the same framed box (Sec. 4.2.3).
 
+  A parameter of order 3 or more first has its small dimensions merged (Sec. 4.2.1): going
+  from the left, a dimension is multiplied into the current group while the product stays
+  within the block size.  If two dimensions remain it is the matrix case above on the merged
+  shape.  Otherwise (three or more remain, or one: everything merged) it is Shampoo for a
+  tensor of order w (Sec. 2.3 / 3, "root 2w"): every dimension is cut into pieces of at most
+  the block size; each sub-tensor block keeps one factor per dimension k,
+      L_k <- beta2 L_k + (1-beta2) G_(k) G_(k)^T      (G_(k): the mode-k unfolding),
+  its root inverse is taken with exponent 2 * root_exponent / w (1/(2w) for root_exponent =
+  1/4; w = 1 is full-matrix AdaGrad with exponent 1/2), and
+      P_shampoo = G x_1 Lbar_1 x_2 Lbar_2 ... x_w Lbar_w     (mode products);
+  grafting, decay, momentum and the update are those of the matrix case.
+
 Readings of the paper taken here (each also listed in the design notes):
   * Factors start at zero and epsilon enters only inside the root-inverse
     routine (the complete pseudocode + framed box), not as L_{-1} = eps*I.
@@ -65,6 +77,11 @@ Readings of the paper taken here (each also listed in the design notes):
     step (W <- W + lr P), and the text equations give W_{t+1} = (1 - lr wd) W_t - ....
   * 1-D parameters run the diagonal method that the blocks graft from (AdaGrad, RMSprop or
     Adam; Sec. 4.2.2 offers exactly these in place of Shampoo), and AdaGrad under SGD grafting.
+  * root_exponent is the matrix value (1/4); a tensor of order w uses 2 * root_exponent / w,
+    i.e. the paper's exponent multiplier applied to the default 1/(2w).  Merging applies to
+    parameters given with three or more dimensions; a matrix is taken as the caller shaped it
+    (the workloads reshape convolution weights to matrices themselves).  The large-dimension
+    methods other than blocking apply to matrices only.
   * RMSprop and Adam grafting differ only in the bias correction of the second moment,
     which Adam applies when bias correction is on; gradient filtering (beta1) is the
     optimizer-wide heuristic of Sec. 3.1.1 for every grafting type.
@@ -75,7 +92,9 @@ momentum and Nesterov sums, trace identities, independent Jacobi eigensolver,
 geometric weight decay, l2 as a shifted gradient, constant-gradient filtering,
 SGD-graft step length, bias correction under a constant gradient, coupled Newton against
 the spectral definition and scalar closed forms, RMSprop / Adam grafting against textbook
-RMSprop and Adam on 1-D parameters).
+RMSprop and Adam on 1-D parameters, merging against the paper's worked example, the
+order-3 direction against the explicit Kronecker product and against closed forms on rank-one
+tensors and fully merged vectors).
 """
 import numpy as np
 
@@ -97,6 +116,66 @@ def block_partition(rows, cols, b):
             c0 = j * b
             blocks.append((r0, c0, min(b, rows - r0), min(b, cols - c0)))
     return blocks
+
+
+def merge_dims(shape, b):
+    """Merging small dimensions (Sec. 4.2.1): consecutive dimensions are merged, from the
+    left, while the product stays within b.  (10, 2, 2, 4) with b = 8 gives (10, 4, 4)."""
+    shape = [int(d) for d in shape]
+    if not shape or any(d <= 0 for d in shape) or b <= 0:
+        raise ValueError("bad shape or block size")
+    merged, cur = [], shape[0]
+    for d in shape[1:]:
+        if cur * d <= b:
+            cur *= d
+        else:
+            merged.append(cur)
+            cur = d
+    merged.append(cur)
+    return tuple(merged)
+
+
+def tensor_block_partition(shape, b):
+    """Blocks of an order-w tensor: every dimension cut into pieces of at most b (full pieces
+    except the last).  Returns a list of (starts, dims), block indices in row-major order."""
+    pieces = []
+    for d in shape:
+        k = -(-d // b)
+        pieces.append([(i * b, min(b, d - i * b)) for i in range(k)])
+    blocks = [((), ())]
+    for dim_pieces in pieces:
+        blocks = [(st + (s0,), dm + (dd,)) for (st, dm) in blocks for (s0, dd) in dim_pieces]
+    return blocks
+
+
+def unfold(G, k):
+    """Mode-k unfolding G_(k): dimension k becomes the rows, all others the columns."""
+    G = np.asarray(G, dtype=np.float64)
+    return np.moveaxis(G, k, 0).reshape(G.shape[k], -1)
+
+
+def tensor_factor_update(Ls, G, beta2):
+    """L_k <- beta2 L_k + (1 - beta2) G_(k) G_(k)^T for every dimension k (plain sums when
+    beta2 == 1): the tensor form of the Kronecker factors (Sec. 2.3, Sec. 3.1.1)."""
+    out = []
+    for k, L in enumerate(Ls):
+        Gk = unfold(G, k)
+        S = Gk @ Gk.T
+        out.append(beta2 * L + (1.0 - beta2) * S if beta2 < 1.0 else L + S)
+    return out
+
+
+def mode_product(G, X, k):
+    """G x_k X: every mode-k fibre of G is multiplied by the matrix X."""
+    return np.moveaxis(np.tensordot(X, G, axes=(1, k)), 0, k)
+
+
+def tensor_shampoo_direction(Xs, G):
+    """P_shampoo = G x_1 X_1 x_2 X_2 ... x_w X_w (Sec. 2.3, tensor case)."""
+    P = np.asarray(G, dtype=np.float64)
+    for k, X in enumerate(Xs):
+        P = mode_product(P, X, k)
+    return P
 
 
 # ----------------------------------------------------------------------------
@@ -236,54 +315,78 @@ class ShampooOracle:
         self.A, self.M, self.Gf = [], [], []
         self.P_sh = []        # last Shampoo direction per block (for inspection)
         self.s_g, self.s_sh = [], []   # last squared norms per block
-        for s in self.shapes:
-            self.A.append(np.zeros(s))
-            self.M.append(np.zeros(s))
-            self.Gf.append(np.zeros(s))
-            big = len(s) == 2 and (s[0] > self.b or s[1] > self.b)
-            if len(s) == 2 and big and large_dim_method == "adagrad":
-                self.whole.append("adagrad")
-                self.blocks.append([])
-                for lst in (self.L, self.R, self.Lbar, self.Rbar, self.P_sh, self.s_g, self.s_sh):
-                    lst.append([])
-            elif len(s) == 2 and big and large_dim_method == "diagonal":
-                dl, dr = s[0] > self.b, s[1] > self.b
-                self.whole.append((dl, dr))
-                self.blocks.append([(0, 0, s[0], s[1])])
-                # a diagonalised factor is stored as the vector of its diagonal
-                self.L.append([np.zeros(s[0]) if dl else np.zeros((s[0], s[0]))])
-                self.R.append([np.zeros(s[1]) if dr else np.zeros((s[1], s[1]))])
-                self.Lbar.append([np.ones(s[0]) if dl else np.eye(s[0])])
-                self.Rbar.append([np.ones(s[1]) if dr else np.eye(s[1])])
-                self.P_sh.append([None])
-                self.s_g.append([0.0])
-                self.s_sh.append([0.0])
-            elif len(s) == 2:
+        # the shape each parameter is worked on (after merging); state arrays have this shape
+        self.view_shapes = [merge_dims(s, self.b) if len(s) >= 3 else s for s in self.shapes]
+        # tensor parameters (order 1 after merging, or >= 3): per block the list of factors / roots
+        self.tblocks, self.TL, self.TLbar = {}, {}, {}
+        for i, s in enumerate(self.view_shapes):
+            if len(self.shapes[i]) >= 3 and len(s) != 2:
+                blks = tensor_block_partition(s, self.b)
+                self.tblocks[i] = blks
+                self.TL[i] = [[np.zeros((d, d)) for d in dims] for (_, dims) in blks]
+                self.TLbar[i] = [[np.eye(d) for d in dims] for (_, dims) in blks]
+                self.A.append(np.zeros(s)); self.M.append(np.zeros(s)); self.Gf.append(np.zeros(s))
                 self.whole.append(None)
-                blks = block_partition(s[0], s[1], self.b)
-                self.blocks.append(blks)
-                self.L.append([np.zeros((m, m)) for (_, _, m, n) in blks])
-                self.R.append([np.zeros((n, n)) for (_, _, m, n) in blks])
-                # before the first refresh the previous root is the identity
-                self.Lbar.append([np.eye(m) for (_, _, m, n) in blks])
-                self.Rbar.append([np.eye(n) for (_, _, m, n) in blks])
+                self.blocks.append([])
+                for lst in (self.L, self.R, self.Lbar, self.Rbar):
+                    lst.append([])
                 self.P_sh.append([None] * len(blks))
                 self.s_g.append([0.0] * len(blks))
                 self.s_sh.append([0.0] * len(blks))
-            elif len(s) == 1:
-                self.whole.append(None)
-                self.blocks.append([])
-                for lst in (self.L, self.R, self.Lbar, self.Rbar, self.P_sh,
-                            self.s_g, self.s_sh):
-                    lst.append([])
-            else:
-                raise ValueError("only 1-D and 2-D parameters")
+                continue
+            self._init_matrix_or_vector(s)
 
-    def _root(self, F):
+    def _init_matrix_or_vector(self, s):
+        """State of a vector or matrix parameter of (merged) shape s."""
+        large_dim_method = self.large_dim_method
+        self.A.append(np.zeros(s))
+        self.M.append(np.zeros(s))
+        self.Gf.append(np.zeros(s))
+        big = len(s) == 2 and (s[0] > self.b or s[1] > self.b)
+        if len(s) == 2 and big and large_dim_method == "adagrad":
+            self.whole.append("adagrad")
+            self.blocks.append([])
+            for lst in (self.L, self.R, self.Lbar, self.Rbar, self.P_sh, self.s_g, self.s_sh):
+                lst.append([])
+        elif len(s) == 2 and big and large_dim_method == "diagonal":
+            dl, dr = s[0] > self.b, s[1] > self.b
+            self.whole.append((dl, dr))
+            self.blocks.append([(0, 0, s[0], s[1])])
+            # a diagonalised factor is stored as the vector of its diagonal
+            self.L.append([np.zeros(s[0]) if dl else np.zeros((s[0], s[0]))])
+            self.R.append([np.zeros(s[1]) if dr else np.zeros((s[1], s[1]))])
+            self.Lbar.append([np.ones(s[0]) if dl else np.eye(s[0])])
+            self.Rbar.append([np.ones(s[1]) if dr else np.eye(s[1])])
+            self.P_sh.append([None])
+            self.s_g.append([0.0])
+            self.s_sh.append([0.0])
+        elif len(s) == 2:
+            self.whole.append(None)
+            blks = block_partition(s[0], s[1], self.b)
+            self.blocks.append(blks)
+            self.L.append([np.zeros((m, m)) for (_, _, m, n) in blks])
+            self.R.append([np.zeros((n, n)) for (_, _, m, n) in blks])
+            # before the first refresh the previous root is the identity
+            self.Lbar.append([np.eye(m) for (_, _, m, n) in blks])
+            self.Rbar.append([np.eye(n) for (_, _, m, n) in blks])
+            self.P_sh.append([None] * len(blks))
+            self.s_g.append([0.0] * len(blks))
+            self.s_sh.append([0.0] * len(blks))
+        elif len(s) == 1:
+            self.whole.append(None)
+            self.blocks.append([])
+            for lst in (self.L, self.R, self.Lbar, self.Rbar, self.P_sh,
+                        self.s_g, self.s_sh):
+                lst.append([])
+        else:
+            raise ValueError("bad parameter shape")
+
+    def _root(self, F, r=None):
+        r = self.r if r is None else r
         if self.root_method == "newton":
-            return root_inverse_newton(F, self.epsilon, int(round(1.0 / self.r)), self.newton_tol,
+            return root_inverse_newton(F, self.epsilon, int(round(1.0 / r)), self.newton_tol,
                                        self.newton_max_iter)[0]
-        return root_inverse(F, self.epsilon, self.r)[0]
+        return root_inverse(F, self.epsilon, r)[0]
 
     def _graft_state(self, A, G):
         if self.grafting in ("rmsprop", "adam"):
@@ -320,9 +423,11 @@ class ShampooOracle:
             c1 = 1.0 / (1.0 - self.beta1 ** (t + 1))
         if self.bias_correction and self.beta2 < 1.0:
             c2 = 1.0 / (1.0 - self.beta2 ** (t + 1))
-        for i, s in enumerate(self.shapes):
-            G = np.asarray(grads[i], dtype=np.float64)
-            W = params[i]
+        for i, s in enumerate(self.view_shapes):
+            G = np.asarray(grads[i], dtype=np.float64).reshape(s)
+            W = params[i].reshape(s)      # a view: merging moves no data (Sec. 4.2.1)
+            if W.base is None and W is not params[i]:
+                raise ValueError("parameters must be C-contiguous")
             if self.wd > 0.0 and not self.decoupled:
                 G = G + self.wd * W
             if self.beta1 > 0.0:
@@ -330,6 +435,9 @@ class ShampooOracle:
                 Gf = c1 * self.Gf[i]
             else:
                 Gf = G
+            if i in self.tblocks:
+                self._tensor_blocks(i, G, Gf, W, lr, t, refresh, c2)
+                continue
             if len(s) == 1 or self.whole[i] == "adagrad":
                 self.A[i] = self._graft_state(self.A[i], G)
                 P = -graft_direction(Gf, self._second_moment(self.A[i], t), self.eps_g)
@@ -362,6 +470,33 @@ class ShampooOracle:
                 else:
                     P = -Pg
                 self._finish(i, sl, P, W, lr)
+
+    def _tensor_blocks(self, i, G, Gf, W, lr, t, refresh, c2):
+        """Shampoo for a tensor of order w (Sec. 2.3 / 3): one factor per dimension, roots with
+        exponent 2 r / w, mode products; everything else as for a matrix block."""
+        w = len(self.view_shapes[i])
+        rw = 2.0 * self.r / w
+        for k, (starts, dims) in enumerate(self.tblocks[i]):
+            sl = tuple(slice(s0, s0 + d) for s0, d in zip(starts, dims))
+            Gb, Gfb = G[sl], Gf[sl]
+            self.TL[i][k] = tensor_factor_update(self.TL[i][k], Gb, self.beta2)
+            if self.grafting != "sgd":
+                self.A[i][sl] = self._graft_state(self.A[i][sl], Gb)
+            if refresh:
+                self.TLbar[i][k] = [self._root(c2 * L, rw) for L in self.TL[i][k]]
+            if self.grafting != "sgd":
+                Pg = graft_direction(Gfb, self._second_moment(self.A[i][sl], t), self.eps_g)
+            else:
+                Pg = Gfb.copy()
+            self.s_g[i][k] = float(np.sum(Pg * Pg))
+            if t >= self.start:
+                Psh = tensor_shampoo_direction(self.TLbar[i][k], Gfb)
+                self.P_sh[i][k] = Psh
+                self.s_sh[i][k] = float(np.sum(Psh * Psh))
+                P = grafted_direction(Psh, Pg)
+            else:
+                P = -Pg
+            self._finish(i, sl, P, W, lr)
 
     def _diagonal_shampoo(self, i, G, Gf, t, refresh, c2):
         """Sec. 4.2.3 on a whole parameter: factors of the large dimensions are diagonal."""

@@ -754,3 +754,147 @@ def test_diagonal_method_leaves_small_matrices_alone():
         g = [rng(99 + t).standard_normal((4, 3))]
         a.step(Wa, g, 0.1, t); b.step(Wb, g, 0.1, t)
     assert np.array_equal(Wa[0], Wb[0])
+
+
+# ---------------------------------------------------------------------------
+# merging and tensors of order w (Sec. 2.3, Sec. 4.2.1)
+# ---------------------------------------------------------------------------
+def test_merging_worked_example_of_the_paper():
+    """Sec. 4.2.1: with maximum dimension 8 a 10 x 2 x 2 x 4 tensor becomes 10 x 4 x 4
+    (tests/golden/merge_dims.txt holds the example and a few consequences of the rule)."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "merge_dims.txt")
+    rows = [ln.split("#")[0].split() for ln in open(path) if ln.split("#")[0].strip()]
+    assert len(rows) >= 5
+    for b, shape, merged in rows:
+        shape = tuple(int(x) for x in shape.split("x"))
+        merged = tuple(int(x) for x in merged.split("x"))
+        assert so.merge_dims(shape, int(b)) == merged, (b, shape)
+        assert int(np.prod(merged)) == int(np.prod(shape))      # a view: no element added or lost
+
+
+def test_tensor_blocks_tile_the_tensor_exactly_once():
+    shape, b = (5, 3, 7), 3
+    seen = np.zeros(shape, dtype=int)
+    blks = so.tensor_block_partition(shape, b)
+    assert len(blks) == 2 * 1 * 3
+    for starts, dims in blks:
+        assert all(1 <= d <= b for d in dims)
+        seen[tuple(slice(s0, s0 + d) for s0, d in zip(starts, dims))] += 1
+    assert (seen == 1).all()
+    # row-major order of the block indices: the last dimension moves fastest
+    assert [st for st, _ in blks[:3]] == [(0, 0, 0), (0, 0, 3), (0, 0, 6)]
+
+
+def test_order3_factors_and_direction_against_explicit_loops_and_kronecker():
+    """L_k = G_(k) G_(k)^T written as explicit sums, and the mode products against the
+    Kronecker form: vec(G x_1 X1 x_2 X2 x_3 X3) = (X1 kron X2 kron X3) vec(G), row-major vec."""
+    r = rng(70)
+    d = (3, 4, 2)
+    G = r.standard_normal(d)
+    Ls = so.tensor_factor_update([np.zeros((n, n)) for n in d], G, 1.0)
+    L1 = np.zeros((3, 3)); L2 = np.zeros((4, 4)); L3 = np.zeros((2, 2))
+    for i in range(3):
+        for j in range(4):
+            for k in range(2):
+                for a in range(3):
+                    L1[i, a] += G[i, j, k] * G[a, j, k]
+                for a in range(4):
+                    L2[j, a] += G[i, j, k] * G[i, a, k]
+                for a in range(2):
+                    L3[k, a] += G[i, j, k] * G[i, j, a]
+    for got, want in zip(Ls, (L1, L2, L3)):
+        assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
+    # EMA form
+    Ls2 = so.tensor_factor_update(Ls, G, 0.9)
+    assert np.allclose(Ls2[1], 0.9 * L2 + 0.1 * L2, rtol=1e-13)
+    Xs = [r.standard_normal((n, n)) for n in d]
+    Xs = [x + x.T for x in Xs]
+    P = so.tensor_shampoo_direction(Xs, G)
+    K = np.kron(np.kron(Xs[0], Xs[1]), Xs[2])
+    assert np.allclose(P.reshape(-1), K @ G.reshape(-1), rtol=1e-12, atol=1e-12)
+    # and the inverse-root form of the preconditioner: (L1 kron L2 kron L3)^(-1/6) vec(G)
+    eps = 1e-3
+    roots = [so.root_inverse(L, eps, 1.0 / 6.0)[0] for L in Ls]
+    big = np.kron(np.kron(Ls[0] + eps * np.eye(3), Ls[1] + eps * np.eye(4)), Ls[2] + eps * np.eye(2))
+    lam, Q = np.linalg.eigh(big)
+    want = (Q * lam ** (-1.0 / 6.0)) @ Q.T @ G.reshape(-1)
+    assert np.allclose(so.tensor_shampoo_direction(roots, G).reshape(-1), want, rtol=1e-9, atol=1e-12)
+
+
+def test_order3_step_on_a_rank_one_tensor_has_a_closed_form():
+    """G = a o b o c: every factor is ||G||^2 times a projector, so with exponent 1/(2w) = 1/6
+    per dimension the Shampoo direction is G / sqrt(||G||^2 + eps): any other exponent shows."""
+    r = rng(71)
+    a, b_, c = r.standard_normal(5), r.standard_normal(4), r.standard_normal(6)
+    G = np.einsum("i,j,k->ijk", a, b_, c)
+    eps = 1e-4
+    o = so.ShampooOracle([(5, 4, 6)], 8, 1.0, eps, 0.25, 1, momentum=0.0, grafting="sgd")
+    assert 0 in o.tblocks and o.view_shapes[0] == (5, 4, 6)
+    W = [np.zeros((5, 4, 6))]
+    o.step(W, [G], 1.0, 0)
+    g2 = float(np.sum(G * G))
+    assert np.allclose(o.P_sh[0][0], G / np.sqrt(g2 + eps), rtol=1e-9, atol=1e-12)
+    # SGD grafting: the step has the length of the gradient, the direction of P_shampoo (= that of G)
+    assert np.allclose(W[0], -G, rtol=1e-9, atol=1e-12)
+    # the three roots individually: (L_k + eps I)^(-1/6) a_k = (||G||^2 + eps)^(-1/6) a_k
+    for k, v in enumerate((a, b_, c)):
+        assert np.allclose(o.TLbar[0][0][k] @ v, (g2 + eps) ** (-1.0 / 6.0) * v, rtol=1e-9)
+
+
+def test_fully_merged_tensor_is_full_matrix_adagrad():
+    """Everything merged: Shampoo on a vector, one factor sum g g^T with exponent 1/2
+    (Sec. 4.2.1).  After one gradient (L + eps I)^(-1/2) g = g / sqrt(||g||^2 + eps); after two,
+    the direction is checked against the explicit matrix inverse square root."""
+    r = rng(72)
+    shape = (2, 3, 2)                    # 12 <= b = 16: merges to a vector of 12
+    eps = 1e-6
+    o = so.ShampooOracle([shape], 16, 1.0, eps, 0.25, 1, momentum=0.0, grafting="sgd")
+    assert o.view_shapes[0] == (12,) and 0 in o.tblocks
+    W = [np.zeros(shape)]
+    g0 = r.standard_normal(shape)
+    o.step(W, [g0], 1.0, 0)
+    assert np.allclose(o.P_sh[0][0].reshape(-1), g0.reshape(-1) / np.sqrt(np.sum(g0 * g0) + eps), rtol=1e-9)
+    g1 = r.standard_normal(shape)
+    o.step(W, [g1], 1.0, 1)
+    L = np.outer(g0.reshape(-1), g0.reshape(-1)) + np.outer(g1.reshape(-1), g1.reshape(-1)) + eps * np.eye(12)
+    lam, Q = np.linalg.eigh(L)
+    want = (Q / np.sqrt(lam)) @ Q.T @ g1.reshape(-1)
+    assert np.allclose(o.P_sh[0][0].reshape(-1), want, rtol=1e-8, atol=1e-12)
+
+
+def test_tensor_that_merges_to_a_matrix_runs_the_matrix_case():
+    """(6, 5, 2) with b = 10 merges to (6, 10) and must follow exactly the trajectory of the
+    6 x 10 matrix (merging is only a view); (6, 2, 2, 5) merges to (6, 4, 5) and stays a tensor."""
+    assert so.merge_dims((6, 2, 2, 5), 10) == (6, 4, 5)
+    r = rng(73)
+    kw = dict(momentum=0.9, beta1=0.9, weight_decay=0.01, use_nesterov=True)
+    o3 = so.ShampooOracle([(6, 5, 2)], 10, 0.99, 1e-8, 0.25, 2, **kw)
+    o2 = so.ShampooOracle([(6, 10)], 10, 0.99, 1e-8, 0.25, 2, **kw)
+    assert o3.view_shapes[0] == (6, 10) and 0 not in o3.tblocks
+    w0 = r.standard_normal((6, 5, 2))
+    W3, W2 = [w0.copy()], [w0.reshape(6, 10).copy()]
+    for t in range(4):
+        g = r.standard_normal((6, 5, 2))
+        o3.step(W3, [g], 0.05, t)
+        o2.step(W2, [g.reshape(6, 10)], 0.05, t)
+    assert np.array_equal(W3[0].reshape(6, 10), W2[0])
+
+
+def test_order3_blocks_are_independent_and_heuristics_apply_per_block():
+    """A 4 x 6 x 4 tensor cut with b = 4 into two blocks along the middle dimension behaves as
+    the separate 4 x 4 x 4 and 4 x 2 x 4 tensors (same hyper-parameters)."""
+    r = rng(74)
+    kw = dict(momentum=0.5, weight_decay=0.02, grafting="adagrad")
+    whole = so.ShampooOracle([(4, 6, 4)], 4, 0.9, 1e-6, 0.25, 1, **kw)
+    parts = so.ShampooOracle([(4, 4, 4), (4, 2, 4)], 4, 0.9, 1e-6, 0.25, 1, **kw)
+    assert [d for _, d in whole.tblocks[0]] == [(4, 4, 4), (4, 2, 4)]
+    w0 = r.standard_normal((4, 6, 4))
+    Ww = [w0.copy()]
+    Wp = [np.ascontiguousarray(w0[:, :4, :]), np.ascontiguousarray(w0[:, 4:, :])]
+    for t in range(3):
+        g = r.standard_normal((4, 6, 4))
+        whole.step(Ww, [g], 0.1, t)
+        parts.step(Wp, [np.ascontiguousarray(g[:, :4, :]), np.ascontiguousarray(g[:, 4:, :])], 0.1, t)
+    assert np.allclose(Ww[0][:, :4, :], Wp[0], rtol=1e-12, atol=1e-14)
+    assert np.allclose(Ww[0][:, 4:, :], Wp[1], rtol=1e-12, atol=1e-14)
