@@ -5,8 +5,9 @@
  * step of Shi et al., "A Distributed Data-Parallel PyTorch Implementation of
  * the Distributed Shampoo Optimizer for Training Neural Networks At-Scale"
  * (arXiv 2309.06497), restricted to one GPU: blocked Kronecker-factor
- * accumulation, periodic inverse-root refresh by batched symmetric
- * eigendecomposition, two-sided preconditioning, AdaGrad or SGD grafting,
+ * accumulation (matrices, and tensors of order three after merging of small
+ * dimensions), periodic inverse-root refresh by batched symmetric
+ * eigendecomposition, preconditioning by the roots, AdaGrad or SGD grafting,
  * gradient filtering, weight decay, (Nesterov) momentum and the parameter
  * update.  The multi-GPU distribution of the paper (Sec. 4.1)
  * is not part of this library.
@@ -51,6 +52,7 @@ enum { SHAMPOO_GRAFT_ADAGRAD = 0, SHAMPOO_GRAFT_SGD = 1, SHAMPOO_GRAFT_RMSPROP =
 enum { SHAMPOO_ROOT_EIGH = 0, SHAMPOO_ROOT_NEWTON = 1 };
 enum { SHAMPOO_MATRIX_CORES_AUTO = 0, SHAMPOO_MATRIX_CORES_FP32 = 1 };
 enum { SHAMPOO_LARGE_DIM_BLOCKING = 0, SHAMPOO_LARGE_DIM_ADAGRAD = 1, SHAMPOO_LARGE_DIM_DIAGONAL = 2 };
+#define SHAMPOO_MAX_NDIM 4
 
 /*
  * Optimizer configuration (copied at create; the arrays need not outlive the call).
@@ -59,8 +61,18 @@ enum { SHAMPOO_LARGE_DIM_BLOCKING = 0, SHAMPOO_LARGE_DIM_ADAGRAD = 1, SHAMPOO_LA
  */
 typedef struct {
   int32_t n_params;       /* number of parameters (tensors), >= 1                          */
-  const int32_t *ndim;    /* host [n_params]: 1 (diagonal AdaGrad path, Sec. 4.2.2) or 2    */
-  const int64_t *shape;   /* host [2*n_params]: rows, cols (cols ignored when ndim == 1)    */
+  const int32_t *ndim;    /* host [n_params]: 1 (diagonal AdaGrad path, Sec. 4.2.2), 2, 3 or 4.
+                             A parameter of 3 or 4 dimensions first has its small dimensions
+                             merged (Sec. 4.2.1: from the left, a dimension joins the current
+                             group while the product stays <= block_size; only a view, no data
+                             moves).  Two dimensions left: the matrix case on the merged shape.
+                             Three left, or one (all merged): Shampoo for a tensor of that order
+                             w (Sec. 2.3), one factor per dimension, root exponent
+                             2 * root_exponent / w, blocks of at most block_size per dimension.
+                             Four left: SHAMPOO_ERR_UNSUPPORTED                              */
+  const int64_t *shape;   /* host [SHAMPOO_MAX_NDIM * n_params]: the ndim[i] dimensions of
+                             parameter i, slowest first, at shape[SHAMPOO_MAX_NDIM * i ...];
+                             the remaining entries are ignored                               */
   int32_t block_size;     /* b: max_preconditioner_dim of Sec. 4.2.1, >= 1                  */
   float beta2;            /* in (0,1]; 1 = plain sum of G G^T, < 1 = EMA (Sec. 3.1.1)       */
   float epsilon;          /* > 0: added to the eigenvalues in the root inverse (Sec. 3.2.1) */
@@ -87,12 +99,14 @@ typedef struct {
                              SHAMPOO_LARGE_DIM_ADAGRAD: the diagonal method on its entries, as for a
                              1-D parameter (Sec. 4.2.2);
                              SHAMPOO_LARGE_DIM_DIAGONAL: kept whole, the factor of each such
-                             dimension replaced by its diagonal (Sec. 4.2.3)                  */
+                             dimension replaced by its diagonal (Sec. 4.2.3).
+                             Tensors of order 1 or 3 (after merging) are always blocked      */
   int32_t root_method;    /* SHAMPOO_ROOT_EIGH: eigendecomposition (framed box of Sec. 3.2.1, default);
                              SHAMPOO_ROOT_NEWTON: coupled inverse Newton iteration of the same
                              section on L + epsilon I, in float32; needs 1/root_exponent in
-                             {1, 2, 4, 8} (else SHAMPOO_ERR_UNSUPPORTED) and factors whose
-                             condition number float32 can resolve                            */
+                             {1, 2, 4, 8} (else SHAMPOO_ERR_UNSUPPORTED; for a tensor parameter
+                             the exponent in question is 2 * root_exponent / w) and factors
+                             whose condition number float32 can resolve                      */
   float newton_tolerance; /* stop when ||M_k - I||_inf < this; 0 selects 1e-6 (Sec. 3.2.1)     */
   int32_t newton_max_iterations; /* iteration cap, <= 1000; 0 selects 100                     */
   int32_t precond_matrix_cores; /* SHAMPOO_MATRIX_CORES_AUTO (default): with bf16 gradients and blocks
@@ -109,9 +123,12 @@ typedef struct {
  * parameter is cut into ceil(rows/b) x ceil(cols/b) blocks, all b x b except
  * in the last block row / column.  Blocks of equal (m, n) form a bucket and
  * are numbered (slot) in parameter order, row-major inside a parameter.
- * Writes up to `cap` rows of 8 int64 {param, row0, col0, m, n, bucket, slot, flags}
+ * Writes up to `cap` rows of 10 int64 {param, row0, col0, m, n, bucket, slot, flags, s3, d3}
  * into `table` (host, may be NULL when cap == 0) and the total number of
  * blocks / buckets into *n_blocks / *n_buckets (host, may be NULL).
+ * A block of a tensor parameter (flags bit 2) starts at (row0, col0, s3) of the merged
+ * shape and measures m x n x d3 (n = d3 = 1 for a fully merged one); matrix blocks have
+ * s3 = 0, d3 = 1.  Tensor blocks are numbered in row-major order of their block indices.
  * Under SHAMPOO_LARGE_DIM_DIAGONAL a parameter with a dimension above b is one row
  * (m, n = its shape) with flags bit 0 / bit 1 set where the left / right factor is
  * diagonal; under SHAMPOO_LARGE_DIM_ADAGRAD such a parameter has no row (it is handled
@@ -148,6 +165,10 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
  *       (P = -P_graft while step < start; 1-D parameters: -Gf/(sqrt(A)+eps_g))
  *   P <- P - wd W   (decoupled weight decay only)        (Sec. 3.1.2)
  *   M <- mu M + P ; W <- W + lr M  (Nesterov: lr (mu M + P))          (Sec. 3.1.3)
+ * A block of a tensor parameter has one factor per dimension k,
+ *   L_k <- beta2 L_k + (1-beta2) G_(k) G_(k)^T  (G_(k): mode-k unfolding),
+ * and P_shampoo = G x_1 Lbar_1 x_2 Lbar_2 x_3 Lbar_3 (mode products, Sec. 2.3); the
+ * other lines apply unchanged.
  * params: host array [n_params] of device pointers, float32, contiguous
  *         row-major with the shapes given at create; updated in place.
  * grads:  host array [n_params] of device pointers, float32 or bfloat16 per
@@ -169,8 +190,13 @@ enum {
   SHAMPOO_GET_M = 5,      /* same shape as A; error if momentum == 0         */
   SHAMPOO_GET_PSH = 6,    /* m x n: last Lbar G Rbar                         */
   SHAMPOO_GET_NORMS = 7,  /* 2 floats: ||P_graft||_F^2, ||P_shampoo||_F^2 of the last step */
-  SHAMPOO_GET_GF = 8      /* same shape as A: filtered gradient; error if beta1 == 0       */
+  SHAMPOO_GET_GF = 8,     /* same shape as A: filtered gradient; error if beta1 == 0       */
+  SHAMPOO_GET_L2 = 9,     /* tensor blocks only: the factor of the middle dimension, n x n   */
+  SHAMPOO_GET_L2INV = 10  /* and its root                                                    */
 };
+/* For a block m x n x d3 of a tensor parameter: L / LINV belong to the first dimension
+ * (m x m), L2 / L2INV to the second (n x n), R / RINV to the last (d3 x d3); A, M, PSH, GF
+ * are the dense m x n x d3 block. */
 
 /*
  * Copy one piece of state of block `block` (row-major index inside parameter

@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshampoo.so")
 
 GRAD_F32, GRAD_BF16 = 0, 1
-GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF = range(9)
+GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF, GET_L2, GET_L2INV = range(11)
+MAX_NDIM = 4
 GRAFT_ADAGRAD, GRAFT_SGD, GRAFT_RMSPROP, GRAFT_ADAM = 0, 1, 2, 3
 ROOT_EIGH, ROOT_NEWTON = 0, 1
 LARGE_DIM_BLOCKING, LARGE_DIM_ADAGRAD, LARGE_DIM_DIAGONAL = 0, 1, 2
@@ -128,8 +129,9 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
     flat = []
     for s in shapes:
-        flat += [int(s[0]), int(s[1]) if len(s) > 1 else 1]
-    shape = (ctypes.c_int64 * max(2 * n, 1))(*flat)
+        dims = [int(d) for d in s][:MAX_NDIM]
+        flat += dims + [1] * (MAX_NDIM - len(dims))
+    shape = (ctypes.c_int64 * max(MAX_NDIM * n, 1))(*flat)
     cfg = ShampooConfig(n, ndim, shape, block_size, beta2, epsilon, root_exponent,
                         precondition_frequency, start_preconditioning_step, graft_epsilon,
                         momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
@@ -141,11 +143,11 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
 
 
 def shampoo_plan(cfg):
-    """Returns (table int64 [n_blocks, 8], n_buckets); rows are
-    {param, row0, col0, m, n, bucket, slot, 0}.  Host only."""
+    """Returns (table int64 [n_blocks, 10], n_buckets); rows are
+    {param, row0, col0, m, n, bucket, slot, flags, s3, d3}.  Host only."""
     nb, nk = ctypes.c_int64(0), ctypes.c_int64(0)
     _check(lib().shampoo_plan(ctypes.byref(cfg), None, 0, ctypes.byref(nb), ctypes.byref(nk)))
-    table = np.zeros((max(nb.value, 1), 8), dtype=np.int64)
+    table = np.zeros((max(nb.value, 1), 10), dtype=np.int64)
     _check(lib().shampoo_plan(ctypes.byref(cfg), table.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                               nb.value, ctypes.byref(nb), ctypes.byref(nk)))
     return table[:nb.value], nk.value
@@ -209,11 +211,17 @@ class Shampoo:
         else:
             if not 0 <= block < len(rows):
                 raise ShampooError(-2)
-            m, n, flags = int(rows[block, 3]), int(rows[block, 4]), int(rows[block, 7])
-            lshape = (m,) if flags & 1 else (m, m)
-            rshape = (n,) if flags & 2 else (n, n)
-            shape = {GET_L: lshape, GET_LINV: lshape, GET_R: rshape, GET_RINV: rshape,
-                     GET_A: (m, n), GET_M: (m, n), GET_PSH: (m, n), GET_NORMS: (2,), GET_GF: (m, n)}[which]
+            m, n, flags, d3 = int(rows[block, 3]), int(rows[block, 4]), int(rows[block, 7]), int(rows[block, 9])
+            if flags & 4:        # a block of a tensor parameter: m x n x d3, one factor per dimension
+                blk = (m, n, d3)
+                shape = {GET_L: (m, m), GET_LINV: (m, m), GET_L2: (n, n), GET_L2INV: (n, n),
+                         GET_R: (d3, d3), GET_RINV: (d3, d3), GET_A: blk, GET_M: blk, GET_PSH: blk,
+                         GET_NORMS: (2,), GET_GF: blk}[which]
+            else:
+                lshape = (m,) if flags & 1 else (m, m)
+                rshape = (n,) if flags & 2 else (n, n)
+                shape = {GET_L: lshape, GET_LINV: lshape, GET_R: rshape, GET_RINV: rshape,
+                         GET_A: (m, n), GET_M: (m, n), GET_PSH: (m, n), GET_NORMS: (2,), GET_GF: (m, n)}[which]
         out = torch.empty(shape, dtype=torch.float32, device=self.device)
         _check(lib().shampoo_get(self.handle, param, block, which, ctypes.c_void_p(out.data_ptr()),
                                  out.numel() * 4, _stream_ptr()))

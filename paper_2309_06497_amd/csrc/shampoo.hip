@@ -22,6 +22,7 @@
 #include "gemm_mfma.h"
 #include "newton_root.h"
 #include "syrk_bf16.h"
+#include "tensor_blocks.h"
 
 using namespace shampoo;
 
@@ -47,6 +48,21 @@ struct Block {
   int64_t row0, col0;
   int32_t m, n;
   int32_t bucket, slot;
+  // tensor blocks (Sec. 2.3): start and size along the third dimension, and where the block
+  // sits in the block-contiguous copy of the parameter that the kernels work on
+  int64_t s3 = 0;
+  int32_t d3 = 1;
+  int64_t voff = 0;
+  bool tensor = false;
+};
+// How a parameter is worked on after merging of small dimensions (Sec. 4.2.1).
+enum { P_VECTOR = 0, P_MATRIX = 1, P_TENSOR = 2 };
+struct PShape {
+  int kind = P_VECTOR;
+  int64_t rows = 1, cols = 1;   // P_MATRIX: the (merged) shape; P_VECTOR: rows = length
+  int64_t d[3] = {1, 1, 1};     // P_TENSOR: the merged dimensions
+  int modes = 0;                // P_TENSOR: 3, or 1 when everything merged into one dimension
+  int64_t elems() const { return kind == P_TENSOR ? d[0] * d[1] * d[2] : rows * cols; }
 };
 struct Bucket {
   int32_t m, n, count;
@@ -63,9 +79,16 @@ struct Bucket {
   // bucket holds whole parameters, one per slot
   bool diagL = false, diagR = false;
   int32_t col_segs = 1, rows_per_seg = 0;   // row segments of the column-sum reduction
+  // tensor blocks d1 x d2 x d3: the elementwise kernels see them as m x n = d1 x (d2 d3)
+  // matrices inside a block-contiguous copy of the parameter; L belongs to the first
+  // dimension, L2 to the second, R to the third
+  bool t3 = false;
+  int32_t d2 = 1, d3 = 1, modes = 0;
+  size_t off_L2 = 0, off_L2inv = 0, off_desc3 = 0;
   bool whole() const { return diagL || diagR; }
+  int32_t rdim() const { return t3 ? d3 : n; }
   size_t l_elems() const { return diagL ? (size_t)m : (size_t)m * m; }
-  size_t r_elems() const { return diagR ? (size_t)n : (size_t)n * n; }
+  size_t r_elems() const { return diagR ? (size_t)n : (size_t)rdim() * rdim(); }
 };
 struct Plan {
   std::vector<Block> blocks;
@@ -74,8 +97,39 @@ struct Plan {
   std::vector<int64_t> param_state_offset;         // element offset of each parameter in A / M
   std::vector<DiagChunk> diag_chunks;   // 1-D parameters
   std::vector<DiagChunk> prep_chunks;   // 2-D parameters, flat (used by the l2 / filtering pre-pass)
+  std::vector<PShape> pshape;           // per parameter
   int64_t total_elems = 0;
 };
+
+// Merging of small dimensions (Sec. 4.2.1) and the resulting kind of parameter.  Returns
+// SHAMPOO_OK, or the error for a shape that is out of range or merges to order 4.
+int param_shape(const shampoo_config *c, int i, PShape &ps) {
+  const int nd = c->ndim[i];
+  if (nd < 1 || nd > SHAMPOO_MAX_NDIM) return SHAMPOO_ERR_SHAPE;
+  const int64_t *sh = c->shape + (size_t)SHAMPOO_MAX_NDIM * i;
+  for (int k = 0; k < nd; ++k) {
+    if (sh[k] < 1) return SHAMPOO_ERR_SHAPE;
+    if (sh[k] > (int64_t)1 << 30) return SHAMPOO_ERR_UNSUPPORTED;
+  }
+  ps = PShape();
+  if (nd == 1) { ps.kind = P_VECTOR; ps.rows = sh[0]; return SHAMPOO_OK; }
+  if (nd == 2) { ps.kind = P_MATRIX; ps.rows = sh[0]; ps.cols = sh[1]; return SHAMPOO_OK; }
+  int64_t merged[SHAMPOO_MAX_NDIM];
+  int cnt = 0;
+  int64_t cur = sh[0];
+  for (int k = 1; k < nd; ++k) {
+    if (cur * sh[k] <= c->block_size) cur *= sh[k];
+    else { merged[cnt++] = cur; cur = sh[k]; }
+  }
+  merged[cnt++] = cur;
+  if (cnt == 2) { ps.kind = P_MATRIX; ps.rows = merged[0]; ps.cols = merged[1]; return SHAMPOO_OK; }
+  if (cnt > 3) return SHAMPOO_ERR_UNSUPPORTED;
+  ps.kind = P_TENSOR;
+  ps.modes = cnt;
+  for (int k = 0; k < cnt; ++k) ps.d[k] = merged[k];
+  if (ps.d[0] * ps.d[1] * ps.d[2] > (int64_t)1 << 40) return SHAMPOO_ERR_UNSUPPORTED;
+  return SHAMPOO_OK;
+}
 
 // p = 1 / r when that is 1, 2, 4 or 8 (the powers the coupled Newton iteration forms by
 // repeated squaring), else 0
@@ -91,11 +145,9 @@ int check_config(const shampoo_config *c) {
   if (c->block_size < 1) return SHAMPOO_ERR_SHAPE;
   if (c->block_size > MAX_BLOCK_SIZE) return SHAMPOO_ERR_UNSUPPORTED;
   for (int i = 0; i < c->n_params; ++i) {
-    if (c->ndim[i] != 1 && c->ndim[i] != 2) return SHAMPOO_ERR_SHAPE;
-    if (c->shape[2 * i] < 1) return SHAMPOO_ERR_SHAPE;
-    if (c->ndim[i] == 2 && c->shape[2 * i + 1] < 1) return SHAMPOO_ERR_SHAPE;
-    if (c->shape[2 * i] > (int64_t)1 << 30) return SHAMPOO_ERR_UNSUPPORTED;
-    if (c->ndim[i] == 2 && c->shape[2 * i + 1] > (int64_t)1 << 30) return SHAMPOO_ERR_UNSUPPORTED;
+    PShape ps;
+    const int rc = param_shape(c, i, ps);
+    if (rc) return rc;
   }
   if (!(c->beta2 > 0.f && c->beta2 <= 1.f)) return SHAMPOO_ERR_HYPER;
   if (!(c->epsilon > 0.f) || !std::isfinite(c->epsilon)) return SHAMPOO_ERR_HYPER;
@@ -113,9 +165,11 @@ int check_config(const shampoo_config *c) {
   if (c->large_dim_method < SHAMPOO_LARGE_DIM_BLOCKING || c->large_dim_method > SHAMPOO_LARGE_DIM_DIAGONAL)
     return SHAMPOO_ERR_HYPER;
   if (c->large_dim_method == SHAMPOO_LARGE_DIM_DIAGONAL)
-    for (int i = 0; i < c->n_params; ++i)
-      if (c->ndim[i] == 2 && (c->shape[2 * i] > INT32_MAX / 2 || c->shape[2 * i + 1] > INT32_MAX / 2))
-        return SHAMPOO_ERR_UNSUPPORTED;
+    for (int i = 0; i < c->n_params; ++i) {
+      PShape ps;
+      param_shape(c, i, ps);
+      if (ps.kind == P_MATRIX && (ps.rows > INT32_MAX / 2 || ps.cols > INT32_MAX / 2)) return SHAMPOO_ERR_UNSUPPORTED;
+    }
   if (c->root_method != SHAMPOO_ROOT_EIGH && c->root_method != SHAMPOO_ROOT_NEWTON) return SHAMPOO_ERR_HYPER;
   if (c->precond_matrix_cores != SHAMPOO_MATRIX_CORES_AUTO && c->precond_matrix_cores != SHAMPOO_MATRIX_CORES_FP32)
     return SHAMPOO_ERR_HYPER;
@@ -123,6 +177,11 @@ int check_config(const shampoo_config *c) {
     if (c->newton_tolerance < 0.f || !std::isfinite(c->newton_tolerance)) return SHAMPOO_ERR_HYPER;
     if (c->newton_max_iterations < 0 || c->newton_max_iterations > 1000) return SHAMPOO_ERR_HYPER;
     if (newton_p_of(c->root_exponent) == 0) return SHAMPOO_ERR_UNSUPPORTED;
+    for (int i = 0; i < c->n_params; ++i) {
+      PShape ps;
+      param_shape(c, i, ps);
+      if (ps.kind == P_TENSOR && newton_p_of(2.f * c->root_exponent / (float)ps.modes) == 0) return SHAMPOO_ERR_UNSUPPORTED;
+    }
   }
   return SHAMPOO_OK;
 }
@@ -146,18 +205,36 @@ EwGeom make_geom(int m, int n) {
 
 void make_plan(const shampoo_config *c, Plan &p) {
   const int64_t b = c->block_size;
-  std::map<std::tuple<int, int, int>, int> bucket_of;   // (m, n, diagonal sides) -> bucket
+  // (m, n, diagonal sides | tensor, d2, d3) -> bucket
+  std::map<std::tuple<int, int, int, int, int>, int> bucket_of;
   p.param_blocks.assign(c->n_params, {});
   p.param_state_offset.assign(c->n_params, 0);
+  p.pshape.assign(c->n_params, PShape());
   int64_t off = 0;
+  auto bucket_for = [&](int m, int n, int flags, int d2, int d3, int modes) {
+    auto key = std::make_tuple(m, n, flags, d2, d3);
+    auto it = bucket_of.find(key);
+    if (it == bucket_of.end()) {
+      Bucket bk{};
+      bk.m = m; bk.n = n; bk.count = 0;
+      bk.diagL = (flags & 1) != 0; bk.diagR = (flags & 2) != 0;
+      bk.t3 = (flags & 4) != 0; bk.d2 = d2; bk.d3 = d3; bk.modes = modes;
+      bucket_of[key] = (int)p.buckets.size();
+      p.buckets.push_back(bk);
+      it = bucket_of.find(key);
+    }
+    return it->second;
+  };
   for (int i = 0; i < c->n_params; ++i) {
     p.param_state_offset[i] = off;
-    const int64_t rows = c->shape[2 * i];
-    const bool large = c->ndim[i] == 2 && (rows > b || c->shape[2 * i + 1] > b);
+    PShape &ps = p.pshape[i];
+    param_shape(c, i, ps);
+    const int64_t rows = ps.rows, cols = ps.cols;
+    const bool large = ps.kind == P_MATRIX && (rows > b || cols > b);
     // 1-D parameters, and under the "adagrad" large-dimension method (Sec. 4.2.2) every
     // matrix with a dimension above the block size, take the diagonal path on their entries
-    if (c->ndim[i] == 1 || (large && c->large_dim_method == SHAMPOO_LARGE_DIM_ADAGRAD)) {
-      const int64_t len = c->ndim[i] == 1 ? rows : rows * c->shape[2 * i + 1];
+    if (ps.kind == P_VECTOR || (large && c->large_dim_method == SHAMPOO_LARGE_DIM_ADAGRAD)) {
+      const int64_t len = rows * cols;
       for (int64_t s = 0; s < len; s += DIAG_CHUNK) {
         DiagChunk dc;
         dc.param = i;
@@ -169,14 +246,38 @@ void make_plan(const shampoo_config *c, Plan &p) {
       off += (len + 3) / 4 * 4;
       continue;
     }
-    const int64_t cols = c->shape[2 * i + 1];
-    for (int64_t st = 0; st < rows * cols; st += DIAG_CHUNK) {
+    const int64_t elems = ps.elems();
+    for (int64_t st = 0; st < elems; st += DIAG_CHUNK) {
       DiagChunk dc;
       dc.param = i;
-      dc.len = (int32_t)std::min<int64_t>(DIAG_CHUNK, rows * cols - st);
+      dc.len = (int32_t)std::min<int64_t>(DIAG_CHUNK, elems - st);
       dc.start = st;
       dc.state_offset = off + st;
       p.prep_chunks.push_back(dc);
+    }
+    if (ps.kind == P_TENSOR) {
+      // every dimension cut into pieces of at most b; blocks in row-major order of their
+      // indices.  All pieces before the last one of a dimension are full, which gives the
+      // offset of a block inside the block-contiguous copy in closed form.
+      const int64_t D1 = ps.d[0], D2 = ps.d[1], D3 = ps.d[2];
+      const int64_t k1n = (D1 + b - 1) / b, k2n = (D2 + b - 1) / b, k3n = (D3 + b - 1) / b;
+      for (int64_t k1 = 0; k1 < k1n; ++k1)
+        for (int64_t k2 = 0; k2 < k2n; ++k2)
+          for (int64_t k3 = 0; k3 < k3n; ++k3) {
+            Block blk;
+            blk.param = i; blk.tensor = true;
+            blk.row0 = k1 * b; blk.col0 = k2 * b; blk.s3 = k3 * b;
+            blk.m = (int32_t)std::min<int64_t>(b, D1 - blk.row0);
+            blk.n = (int32_t)std::min<int64_t>(b, D2 - blk.col0);
+            blk.d3 = (int32_t)std::min<int64_t>(b, D3 - blk.s3);
+            blk.voff = blk.row0 * D2 * D3 + (int64_t)blk.m * (blk.col0 * D3) + (int64_t)blk.m * blk.n * blk.s3;
+            blk.bucket = bucket_for(blk.m, blk.n * blk.d3, 4, blk.n, blk.d3, ps.modes);
+            blk.slot = p.buckets[blk.bucket].count++;
+            p.param_blocks[i].push_back((int32_t)p.blocks.size());
+            p.blocks.push_back(blk);
+          }
+      off += (elems + 3) / 4 * 4;
+      continue;
     }
     // diagonal Shampoo (Sec. 4.2.3): the parameter stays whole, one "block"
     const bool whole = large && c->large_dim_method == SHAMPOO_LARGE_DIM_DIAGONAL;
@@ -191,27 +292,19 @@ void make_plan(const shampoo_config *c, Plan &p) {
         blk.col0 = bj * bb;
         blk.m = (int32_t)std::min<int64_t>(bb, rows - blk.row0);
         blk.n = (int32_t)std::min<int64_t>(bb, cols - blk.col0);
-        auto key = std::make_tuple(blk.m, blk.n, flags);
-        auto it = bucket_of.find(key);
-        if (it == bucket_of.end()) {
-          Bucket bk{};
-          bk.m = blk.m; bk.n = blk.n; bk.count = 0;
-          bk.diagL = (flags & 1) != 0; bk.diagR = (flags & 2) != 0;
-          bucket_of[key] = (int)p.buckets.size();
-          p.buckets.push_back(bk);
-          it = bucket_of.find(key);
-        }
-        blk.bucket = it->second;
-        blk.slot = p.buckets[it->second].count++;
+        blk.bucket = bucket_for(blk.m, blk.n, flags, 1, 1, 0);
+        blk.slot = p.buckets[blk.bucket].count++;
         p.param_blocks[i].push_back((int32_t)p.blocks.size());
         p.blocks.push_back(blk);
       }
     off += (rows * cols + 3) / 4 * 4;
   }
   p.total_elems = off;
-  for (auto &bk : p.buckets) bk.bf16_mfma = (bk.m % 8 == 0) && (bk.n % 8 == 0) && bk.count <= 65535 && !bk.whole();
+  for (auto &bk : p.buckets)
+    bk.bf16_mfma = (bk.m % 8 == 0) && (bk.n % 8 == 0) && bk.count <= 65535 && !bk.whole() && !bk.t3;
   for (const Block &blk : p.blocks) {
-    const int64_t ld = c->shape[2 * blk.param + 1];
+    if (blk.tensor) continue;
+    const int64_t ld = p.pshape[blk.param].cols;
     if (ld % 8 != 0 || (blk.row0 * ld + blk.col0) % 8 != 0) p.buckets[blk.bucket].bf16_mfma = false;
   }
   for (auto &bk : p.buckets) {
@@ -522,7 +615,7 @@ int newton_root_batched(const float *a, int n, int batch, float eps, int p, floa
 struct shampoo_opt {
   shampoo_config cfg;
   std::vector<int32_t> ndim;
-  std::vector<int64_t> shape;
+  std::vector<int64_t> shape;   // [SHAMPOO_MAX_NDIM * n_params], as given
   Plan plan;
   unsigned char *ws = nullptr;
   size_t ws_bytes = 0;
@@ -531,7 +624,12 @@ struct shampoo_opt {
   int64_t n_small = 0;     // blocks of at most 128 x 128 (single-workgroup step kernel)
   bool use_l2 = false, use_b1 = false;
   size_t off_A = 0, off_M = 0, off_T = 0, off_wtab = 0, off_gtab = 0, off_diag = 0, off_count = 0, off_eig = 0;
-  std::vector<EigLayout> eig_L, eig_R;   // per bucket
+  std::vector<EigLayout> eig_L, eig_R, eig_2;   // per bucket (eig_2: middle dimension of tensor blocks)
+  // tensor parameters: block-contiguous copies of the gradient and the parameter (byte offsets
+  // into the workspace, 0 for other parameters), and a second scratch array the size of T
+  std::vector<size_t> off_Gb, off_Wb;
+  size_t off_T2 = 0;
+  bool has_tensor = false;
   std::vector<void *> last_w, last_g;    // pointer tables currently on the device
   bool ptrs_aligned16 = false;           // every gradient pointer is 16-byte aligned
   int64_t last_step = -1;
@@ -555,14 +653,20 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offG1tab = take((size_t)c->n_params * sizeof(void *));
   const size_t offGftab = take((size_t)c->n_params * sizeof(void *));
   const size_t offPrep = (use_l2 || use_b1) ? take(std::max<size_t>(1, p.prep_chunks.size()) * sizeof(DiagChunk)) : 0;
-  size_t t_elems = 0, eig_bytes = 0;
-  std::vector<EigLayout> eL, eR;
+  size_t t_elems = 0, t2_elems = 0, eig_bytes = 0;
+  std::vector<EigLayout> eL, eR, e2;
   for (auto &b : p.buckets) {
     const size_t B = b.count, m = b.m, n = b.n;
     b.off_L = take(B * b.l_elems() * 4);
     b.off_R = take(B * b.r_elems() * 4);
     b.off_Linv = take(B * b.l_elems() * 4);
     b.off_Rinv = take(B * b.r_elems() * 4);
+    if (b.t3) {
+      b.off_L2 = take(B * (size_t)b.d2 * b.d2 * 4);
+      b.off_L2inv = take(B * (size_t)b.d2 * b.d2 * 4);
+      b.off_desc3 = take(B * sizeof(BlockDesc));
+      t2_elems = std::max(t2_elems, B * m * n);
+    }
     b.off_P = take(B * m * n * 4);
     // bf16 gradients: the preconditioning products run on the bf16 matrix cores from
     // operands kept split in three bf16 planes
@@ -574,26 +678,42 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     }
     b.off_desc = take(B * sizeof(BlockDesc));
     b.off_sgp = take(B * b.geom.chunks * 4);
-    b.off_sshp = take(B * std::max<size_t>((size_t)b.tiles_m * b.tiles_n, (size_t)b.geom.chunks) * 4);
+    // partial sums of ||P_shampoo||^2: one per tile of the last product (tensor blocks: the
+    // (d2 d1) x d3 product of the third dimension) or per chunk of an elementwise pass
+    size_t ssh_parts = std::max<size_t>((size_t)b.tiles_m * b.tiles_n, (size_t)b.geom.chunks);
+    if (b.t3) ssh_parts = std::max(ssh_parts, (size_t)((b.m * b.d2 + BM - 1) / BM) * ((b.d3 + BN - 1) / BN));
+    b.off_sshp = take(B * ssh_parts * 4);
     b.off_scale = take(B * 4);
     b.off_norms = take(B * 8);
     t_elems = std::max(t_elems, B * m * n * (b.planes ? 3 : 2) / 2);   // T as three bf16 planes: 6 bytes per element
     if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) b.off_Gt = take(B * m * n * 2);
     // a diagonalised side needs no eigensolver workspace (stand-in layout of a 1 x 1 problem)
-    const int em = b.diagL ? 1 : b.m, en = b.diagR ? 1 : b.n;
+    const int em = b.diagL ? 1 : b.m, en = b.diagR ? 1 : b.rdim();
     eL.push_back(eig_layout(em, b.count));
     eR.push_back(eig_layout(en, b.count));
+    e2.push_back(eig_layout(b.d2, b.count));
     if (c->root_method == SHAMPOO_ROOT_NEWTON)
-      eig_bytes = std::max(eig_bytes, std::max(newton_layout(em, b.count).bytes, newton_layout(en, b.count).bytes));
+      eig_bytes = std::max(eig_bytes, std::max(newton_layout(em, b.count).bytes,
+                                               std::max(newton_layout(en, b.count).bytes, newton_layout(b.d2, b.count).bytes)));
     else
-      eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, eR.back().bytes));
+      eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, std::max(eR.back().bytes, e2.back().bytes)));
   }
   const size_t offT = take(t_elems * 4);
+  const size_t offT2 = t2_elems ? take(t2_elems * 4) : 0;
+  std::vector<size_t> offGb(c->n_params, 0), offWb(c->n_params, 0);
+  bool has_tensor = false;
+  for (int i = 0; i < c->n_params; ++i) {
+    if (p.pshape[i].kind != P_TENSOR) continue;
+    has_tensor = true;
+    const size_t el = (size_t)p.pshape[i].elems();
+    offGb[i] = take(el * (c->grad_dtype == SHAMPOO_GRAD_BF16 ? 2 : 4));
+    offWb[i] = take(el * 4);
+  }
   const size_t offW = take((size_t)c->n_params * sizeof(void *));
   const size_t offG = take((size_t)c->n_params * sizeof(void *));
   const size_t offD = take(std::max<size_t>(1, p.diag_chunks.size()) * sizeof(DiagChunk));
   int64_t n_small = 0;
-  for (auto &b : p.buckets) if (b.m <= SB && b.n <= SB && !b.whole()) n_small += b.count;
+  for (auto &b : p.buckets) if (b.m <= SB && b.n <= SB && !b.whole() && !b.t3) n_small += b.count;
   const size_t offSmall = take(std::max<size_t>(1, (size_t)n_small) * sizeof(SmallBlock));
   const size_t offC = take(64);
   const size_t offE = take(eig_bytes);
@@ -603,7 +723,8 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     o->use_l2 = use_l2; o->use_b1 = use_b1; o->off_wtab = offW; o->off_gtab = offG;
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
     o->off_small = offSmall; o->n_small = n_small;
-    o->eig_L = eL; o->eig_R = eR;
+    o->eig_L = eL; o->eig_R = eR; o->eig_2 = e2;
+    o->off_T2 = offT2; o->off_Gb = offGb; o->off_Wb = offWb; o->has_tensor = has_tensor;
   }
   return off;
 }
@@ -680,6 +801,34 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
                          ? (float)(1.0 / (1.0 - std::pow((double)c.grafting_beta2, (double)(step + 1)))) : 1.f;
   int rc;
 
+  // Tensor parameters (Sec. 2.3): the step works on block-contiguous copies of their gradient
+  // and of the parameter itself; the pointer tables on the device name those copies.
+  auto tensor_copy_args = [&](int i) {
+    const PShape &ps = p.pshape[i];
+    TensorCopyArgs ta{};
+    ta.D1 = ps.d[0]; ta.D2 = ps.d[1]; ta.D3 = ps.d[2]; ta.b = c.block_size;
+    ta.k2n = (int32_t)((ps.d[1] + c.block_size - 1) / c.block_size);
+    ta.k3n = (int32_t)((ps.d[2] + c.block_size - 1) / c.block_size);
+    return ta;
+  };
+  auto tensor_copy_grid = [&](int i) {
+    const int64_t per = std::min<int64_t>(c.block_size, p.pshape[i].d[0]) * std::min<int64_t>(c.block_size, p.pshape[i].d[1]) *
+                        std::min<int64_t>(c.block_size, p.pshape[i].d[2]);
+    return dim3((unsigned)p.param_blocks[i].size(), (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, (per + 2047) / 2048)));
+  };
+  if (o->has_tensor) {
+    StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
+    for (int i = 0; i < c.n_params; ++i) {
+      if (p.pshape[i].kind != P_TENSOR) continue;
+      TensorCopyArgs ta = tensor_copy_args(i);
+      ta.tensor_in = o->last_g[i]; ta.copy_out = ws + o->off_Gb[i];
+      hipLaunchKernelGGL((tensor_block_copy_kernel<GT, false>), tensor_copy_grid(i), dim3(256), 0, s, ta);
+      ta.tensor_in = o->last_w[i]; ta.copy_out = ws + o->off_Wb[i];
+      hipLaunchKernelGGL((tensor_block_copy_kernel<float, false>), tensor_copy_grid(i), dim3(256), 0, s, ta);
+    }
+    HIP_TRY(hipGetLastError());
+  }
+
   if ((o->use_l2 || o->use_b1) && !p.prep_chunks.empty()) {
     StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
     PrepArgs pa;
@@ -692,7 +841,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   // resident in LDS) whenever no refresh separates the factor update from the
   // preconditioning and the default heuristics are in force.
   const bool small_ok = use_shampoo && !refresh && !o->use_l2 && !o->use_b1 && !sgd;
-  auto fused = [&](const Bucket &b) { return small_ok && b.m <= SB && b.n <= SB && !b.whole(); };
+  auto fused = [&](const Bucket &b) { return small_ok && b.m <= SB && b.n <= SB && !b.whole() && !b.t3; };
   if (small_ok && o->n_small > 0) {
     StageTimer t(o, SHAMPOO_STAGE_FUSED, s);
     SmallStepArgs f;
@@ -756,7 +905,35 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         rc = launch_gemm<K_CONTIG, K_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
         if (rc) return rc;
       }
-      if (b.diagR) {
+      if (b.t3) {
+        // Above: L_1 <- beta L_1 + alpha G_(1) G_(1)^T, the block being d1 x (d2 d3).  The other
+        // dimensions exist only for a tensor of order three.
+        if (b.modes == 3) {
+          // L_3 <- beta L_3 + alpha G_(3) G_(3)^T: the block as (d1 d2) x d3, read "rows along k"
+          g.desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc3);
+          g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.d3 * b.d3; g.ldc = b.d3;
+          g.M = b.d3; g.N = b.d3; g.K = b.m * b.d2;
+          g.tiles_m = g.tiles_n = (b.d3 + BM - 1) / BM; g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
+          rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
+          if (rc) return rc;
+          // L_2 <- beta L_2 + alpha G_(2) G_(2)^T: the block with its first two indices swapped, d2 x (d1 d3)
+          float *T2 = reinterpret_cast<float *>(ws + o->off_T2);
+          PermuteArgs pm{};
+          pm.desc = desc; pm.table = gs_tab; pm.dst = T2; pm.d1 = b.m; pm.d2 = b.d2; pm.d3 = b.d3;
+          const unsigned pchunks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, ((int64_t)b.m * b.n + 2047) / 2048));
+          hipLaunchKernelGGL(permute_12_kernel<GS>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
+          HIP_TRY(hipGetLastError());
+          GemmArgs h{};
+          h.a.base = T2; h.a.batch_stride = (int64_t)b.m * b.n; h.a.ld = b.m * b.d3;
+          h.b = h.a;
+          h.alpha = (float)alpha; h.beta = (float)beta; h.alpha_d = alpha; h.beta_d = beta; h.batch = b.count;
+          h.c = reinterpret_cast<float *>(ws + b.off_L2); h.c_batch_stride = (int64_t)b.d2 * b.d2; h.ldc = b.d2;
+          h.M = b.d2; h.N = b.d2; h.K = b.m * b.d3;
+          h.tiles_m = h.tiles_n = (b.d2 + BM - 1) / BM; h.tiles = h.tiles_m * (h.tiles_m + 1) / 2;
+          rc = launch_gemm<K_CONTIG, K_CONTIG, float, float, EPI_SYRK, false, FLUSH>(h, s);
+          if (rc) return rc;
+        }
+      } else if (b.diagR) {
         // r_j <- beta r_j + alpha sum_i G_ij^2, rows cut into segments whose partial sums go through T
         df.vec = reinterpret_cast<float *>(ws + b.off_R);
         df.partial = T; df.segs = b.col_segs; df.rows_per_seg = b.rows_per_seg;
@@ -809,6 +986,28 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         }
         continue;
       }
+      if (b.t3) {
+        // one root per dimension, exponent 2 r / w (Sec. 2.3: "root 2w")
+        const float rw = 2.f * c.root_exponent / (float)b.modes;
+        const int dims[3] = {b.m, b.d2, b.d3};
+        const size_t fac[3] = {b.off_L, b.off_L2, b.off_R}, inv[3] = {b.off_Linv, b.off_L2inv, b.off_Rinv};
+        const EigLayout *lay[3] = {&o->eig_L[i], &o->eig_2[i], &o->eig_R[i]};
+        for (int k = 0; k < b.modes; ++k) {
+          if (c.root_method == SHAMPOO_ROOT_NEWTON) {
+            const float tol = c.newton_tolerance > 0.f ? c.newton_tolerance : 1e-6f;
+            const int cap = c.newton_max_iterations > 0 ? c.newton_max_iterations : 100;
+            rc = newton_root_batched(reinterpret_cast<float *>(ws + fac[k]), dims[k], b.count, c.epsilon, newton_p_of(rw), c2,
+                                     tol, cap, reinterpret_cast<float *>(ws + inv[k]), nullptr, nullptr, fail_count,
+                                     ws + o->off_eig, newton_layout(dims[k], b.count), s);
+          } else {
+            rc = root_inverse_batched(reinterpret_cast<float *>(ws + fac[k]), dims[k], b.count, c.epsilon, rw, c2,
+                                      reinterpret_cast<float *>(ws + inv[k]), nullptr, nullptr, fail_count,
+                                      ws + o->off_eig, *lay[k], s);
+          }
+          if (rc) return rc;
+        }
+        continue;
+      }
       if (c.root_method == SHAMPOO_ROOT_NEWTON) {
         const int pw = newton_p_of(c.root_exponent);
         const float tol = c.newton_tolerance > 0.f ? c.newton_tolerance : 1e-6f;
@@ -841,7 +1040,56 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     float *scale = reinterpret_cast<float *>(ws + b.off_scale);
     if (fused(b)) continue;
     int ssh_count = b.tiles_m * b.tiles_n;
-    if (use_shampoo && b.whole()) {
+    if (use_shampoo && b.t3) {
+      // P = G x_1 Lbar_1 x_2 Lbar_2 x_3 Lbar_3 (Sec. 2.3).  Mode 1 on the block as d1 x (d2 d3);
+      // then the first two indices are swapped so that mode 2 is a plain product on
+      // d2 x (d1 d3) and mode 3 one on (d2 d1) x d3; the result is swapped back.
+      StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
+      float *T2 = reinterpret_cast<float *>(ws + o->off_T2);
+      float *ssh = reinterpret_cast<float *>(ws + b.off_sshp);
+      const int64_t mn = (int64_t)b.m * b.n;
+      GemmArgs g{};
+      g.a.base = ws + b.off_Linv; g.a.batch_stride = (int64_t)b.m * b.m; g.a.ld = b.m;
+      g.b.from_table = 1; g.desc = desc; g.ptr_table = gd_tab;
+      g.c_batch_stride = mn; g.ldc = b.n;
+      g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1; g.beta = 0.f;
+      g.tiles_m = b.tiles_m; g.tiles_n = b.tiles_n; g.tiles = b.tiles_m * b.tiles_n; g.batch = b.count;
+      if (b.modes == 1) {
+        g.c = P; g.norm_partial = ssh;
+        rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE_NORM, false>(g, s);
+        if (rc) return rc;
+      } else {
+        g.c = T;
+        rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE, false>(g, s);
+        if (rc) return rc;
+        const unsigned pchunks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, (mn + 2047) / 2048));
+        PermuteArgs pm{};
+        pm.src = T; pm.dst = T2; pm.d1 = b.m; pm.d2 = b.d2; pm.d3 = b.d3;
+        hipLaunchKernelGGL(permute_12_kernel<float>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
+        HIP_TRY(hipGetLastError());
+        GemmArgs h{};
+        h.a.base = ws + b.off_L2inv; h.a.batch_stride = (int64_t)b.d2 * b.d2; h.a.ld = b.d2;
+        h.b.base = T2; h.b.batch_stride = mn; h.b.ld = b.m * b.d3;
+        h.c = T; h.c_batch_stride = mn; h.ldc = b.m * b.d3;
+        h.M = b.d2; h.N = b.m * b.d3; h.K = b.d2; h.alpha = 1.f; h.beta = 0.f;
+        h.tiles_m = (h.M + BM - 1) / BM; h.tiles_n = (h.N + BN - 1) / BN; h.tiles = h.tiles_m * h.tiles_n; h.batch = b.count;
+        rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_STORE, false>(h, s);
+        if (rc) return rc;
+        GemmArgs q{};
+        q.a.base = T; q.a.batch_stride = mn; q.a.ld = b.d3;
+        q.b.base = ws + b.off_Rinv; q.b.batch_stride = (int64_t)b.d3 * b.d3; q.b.ld = b.d3;
+        q.c = T2; q.c_batch_stride = mn; q.ldc = b.d3;
+        q.M = b.d2 * b.m; q.N = b.d3; q.K = b.d3; q.alpha = 1.f; q.beta = 0.f;
+        q.tiles_m = (q.M + BM - 1) / BM; q.tiles_n = (q.N + BN - 1) / BN; q.tiles = q.tiles_m * q.tiles_n; q.batch = b.count;
+        q.norm_partial = ssh;
+        rc = launch_gemm<K_CONTIG, ROW_CONTIG, float, float, EPI_STORE_NORM, false>(q, s);
+        if (rc) return rc;
+        ssh_count = q.tiles;
+        pm.src = T2; pm.dst = P; pm.d1 = b.d2; pm.d2 = b.m; pm.d3 = b.d3;
+        hipLaunchKernelGGL(permute_12_kernel<float>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
+        HIP_TRY(hipGetLastError());
+      }
+    } else if (use_shampoo && b.whole()) {
       // diagonal Shampoo: a diagonalised side scales rows / columns instead of multiplying
       StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
       DiagScaleArgs ds{};
@@ -960,6 +1208,17 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       HIP_TRY(hipGetLastError());
     }
   }
+  if (o->has_tensor) {
+    // the updated block-contiguous copies go back into the caller's tensors
+    StageTimer t(o, SHAMPOO_STAGE_UPDATE, s);
+    for (int i = 0; i < c.n_params; ++i) {
+      if (p.pshape[i].kind != P_TENSOR) continue;
+      TensorCopyArgs ta = tensor_copy_args(i);
+      ta.copy_in = ws + o->off_Wb[i]; ta.tensor_out = o->last_w[i];
+      hipLaunchKernelGGL((tensor_block_copy_kernel<float, true>), tensor_copy_grid(i), dim3(256), 0, s, ta);
+    }
+    HIP_TRY(hipGetLastError());
+  }
   if (!p.diag_chunks.empty()) {
     StageTimer t(o, SHAMPOO_STAGE_DIAG, s);
     DiagArgs d;
@@ -992,10 +1251,11 @@ int shampoo_plan(const shampoo_config *cfg, int64_t *table, int64_t cap, int64_t
   const int64_t cnt = std::min<int64_t>(cap, (int64_t)p.blocks.size());
   for (int64_t i = 0; i < cnt; ++i) {
     const Block &b = p.blocks[i];
-    int64_t *row = table + 8 * i;
+    int64_t *row = table + 10 * i;
     row[0] = b.param; row[1] = b.row0; row[2] = b.col0; row[3] = b.m; row[4] = b.n;
     row[5] = b.bucket; row[6] = b.slot;
-    row[7] = (p.buckets[b.bucket].diagL ? 1 : 0) | (p.buckets[b.bucket].diagR ? 2 : 0);
+    row[7] = (p.buckets[b.bucket].diagL ? 1 : 0) | (p.buckets[b.bucket].diagR ? 2 : 0) | (b.tensor ? 4 : 0);
+    row[8] = b.s3; row[9] = b.d3;
   }
   return SHAMPOO_OK;
 }
@@ -1017,7 +1277,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
   if (!o) return SHAMPOO_ERR_HIP;
   o->cfg = *cfg;
   o->ndim.assign(cfg->ndim, cfg->ndim + cfg->n_params);
-  o->shape.assign(cfg->shape, cfg->shape + 2 * (size_t)cfg->n_params);
+  o->shape.assign(cfg->shape, cfg->shape + (size_t)SHAMPOO_MAX_NDIM * cfg->n_params);
   o->cfg.ndim = o->ndim.data();
   o->cfg.shape = o->shape.data();
   make_plan(&o->cfg, o->plan);
@@ -1055,14 +1315,28 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
         return fail(SHAMPOO_ERR_HIP);
     if (hipStreamSynchronize(s) != hipSuccess) return fail(SHAMPOO_ERR_HIP);   // t1, t2 go out of scope
   }
-  std::vector<std::vector<BlockDesc>> descs(p.buckets.size());
-  for (size_t i = 0; i < p.buckets.size(); ++i) descs[i].resize(p.buckets[i].count);
+  std::vector<std::vector<BlockDesc>> descs(p.buckets.size()), descs3(p.buckets.size());
+  for (size_t i = 0; i < p.buckets.size(); ++i) {
+    descs[i].resize(p.buckets[i].count);
+    if (p.buckets[i].t3) descs3[i].resize(p.buckets[i].count);
+  }
   for (const Block &b : p.blocks) {
     BlockDesc d;
     d.param = b.param;
-    d.ld = (int32_t)o->shape[2 * b.param + 1];
-    d.offset = b.row0 * d.ld + b.col0;
-    d.state_offset = p.param_state_offset[b.param] + d.offset;
+    if (b.tensor) {
+      // a block of the block-contiguous copy, as a d1 x (d2 d3) matrix; the second descriptor
+      // shows the same memory as the (d1 d2) x d3 matrix of the third dimension
+      d.ld = b.n * b.d3;
+      d.offset = b.voff;
+      d.state_offset = p.param_state_offset[b.param] + d.offset;
+      BlockDesc d3 = d;
+      d3.ld = b.d3;
+      descs3[b.bucket][b.slot] = d3;
+    } else {
+      d.ld = (int32_t)p.pshape[b.param].cols;
+      d.offset = b.row0 * d.ld + b.col0;
+      d.state_offset = p.param_state_offset[b.param] + d.offset;
+    }
     descs[b.bucket][b.slot] = d;
   }
   for (size_t i = 0; i < p.buckets.size(); ++i) {
@@ -1072,14 +1346,23 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_R), 0.f, B * (int64_t)b.r_elems(), s))) return fail(rc);
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_P), 0.f, B * b.m * b.n, s))) return fail(rc);
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_norms), 0.f, B * 2, s))) return fail(rc);
+    if (b.t3) {
+      const int64_t t2 = B * b.d2 * b.d2;
+      if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_L2), 0.f, t2, s))) return fail(rc);
+      hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((t2 + 255) / 256)), dim3(256), 0, s,
+                         reinterpret_cast<float *>(o->ws + b.off_L2inv), b.d2, t2);
+      if (hipMemcpyAsync(o->ws + b.off_desc3, descs3[i].data(), descs3[i].size() * sizeof(BlockDesc),
+                         hipMemcpyHostToDevice, s) != hipSuccess)
+        return fail(SHAMPOO_ERR_HIP);
+    }
     // roots start as the identity (a diagonalised side: the vector of ones)
-    const int64_t tl = B * b.m * b.m, tr = B * b.n * b.n;
+    const int64_t tl = B * b.m * b.m, tr = B * (int64_t)b.rdim() * b.rdim();
     if (b.diagL) { if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_Linv), 1.f, B * b.m, s))) return fail(rc); }
     else hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tl + 255) / 256)), dim3(256), 0, s,
                             reinterpret_cast<float *>(o->ws + b.off_Linv), b.m, tl);
     if (b.diagR) { if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_Rinv), 1.f, B * b.n, s))) return fail(rc); }
     else hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((tr + 255) / 256)), dim3(256), 0, s,
-                            reinterpret_cast<float *>(o->ws + b.off_Rinv), b.n, tr);
+                            reinterpret_cast<float *>(o->ws + b.off_Rinv), b.rdim(), tr);
     if (hipGetLastError() != hipSuccess) return fail(SHAMPOO_ERR_HIP);
     if (hipMemcpyAsync(o->ws + b.off_desc, descs[i].data(), descs[i].size() * sizeof(BlockDesc),
                        hipMemcpyHostToDevice, s) != hipSuccess)
@@ -1091,7 +1374,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
     std::vector<SmallBlock> small;
     for (size_t i = 0; i < p.buckets.size(); ++i) {
       const Bucket &b = p.buckets[i];
-      if (b.m > SB || b.n > SB || b.whole()) continue;
+      if (b.m > SB || b.n > SB || b.whole() || b.t3) continue;
       for (int64_t k = 0; k < b.count; ++k) {
         SmallBlock sb;
         sb.d = descs[i][k]; sb.m = b.m; sb.n = b.n;
@@ -1138,8 +1421,13 @@ int shampoo_step(shampoo_opt *o, void *const *params, const void *const *grads, 
       if (reinterpret_cast<uintptr_t>(grads[i]) % 16 != 0) o->ptrs_aligned16 = false;
     o->last_g.resize(np);
     for (int i = 0; i < np; ++i) o->last_g[i] = const_cast<void *>(grads[i]);
-    HIP_TRY(hipMemcpyAsync(o->ws + o->off_wtab, o->last_w.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(o->ws + o->off_gtab, o->last_g.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
+    // tensor parameters are worked on in block-contiguous copies inside the workspace
+    std::vector<void *> tw(o->last_w), tg(o->last_g);
+    for (int i = 0; i < np; ++i)
+      if (o->plan.pshape[i].kind == P_TENSOR) { tw[i] = o->ws + o->off_Wb[i]; tg[i] = o->ws + o->off_Gb[i]; }
+    HIP_TRY(hipMemcpyAsync(o->ws + o->off_wtab, tw.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(o->ws + o->off_gtab, tg.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
+    if (o->has_tensor) HIP_TRY(hipStreamSynchronize(s));   // tw, tg go out of scope
   }
   o->last_step = step;
   if (o->cfg.grad_dtype == SHAMPOO_GRAD_BF16) {
@@ -1162,7 +1450,7 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
     if (block != 0 || (which != SHAMPOO_GET_A && which != SHAMPOO_GET_M && which != SHAMPOO_GET_GF)) return SHAMPOO_ERR_SHAPE;
     if (which == SHAMPOO_GET_M && !(o->cfg.momentum > 0.f)) return SHAMPOO_ERR_SHAPE;
     if (which == SHAMPOO_GET_GF && !o->use_b1) return SHAMPOO_ERR_SHAPE;
-    const size_t len = (size_t)o->shape[2 * param] * (o->ndim[param] == 2 ? (size_t)o->shape[2 * param + 1] : 1);
+    const size_t len = (size_t)p.pshape[param].elems();
     if (bytes != len * 4) return SHAMPOO_ERR_SHAPE;
     const size_t off_state = which == SHAMPOO_GET_A ? o->off_A : (which == SHAMPOO_GET_M ? o->off_M : o->off_Gf);
     const float *src = reinterpret_cast<const float *>(ws + off_state) + p.param_state_offset[param];
@@ -1180,16 +1468,29 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
     case SHAMPOO_GET_R: need = bk.r_elems() * 4; src = ws + bk.off_R + (size_t)b.slot * need; break;
     case SHAMPOO_GET_LINV: need = bk.l_elems() * 4; src = ws + bk.off_Linv + (size_t)b.slot * need; break;
     case SHAMPOO_GET_RINV: need = bk.r_elems() * 4; src = ws + bk.off_Rinv + (size_t)b.slot * need; break;
-    case SHAMPOO_GET_PSH: src = ws + bk.off_P + (size_t)b.slot * m * n * 4; need = m * n * 4; break;
+    case SHAMPOO_GET_L2:
+    case SHAMPOO_GET_L2INV:
+      if (!bk.t3) return SHAMPOO_ERR_SHAPE;
+      need = (size_t)bk.d2 * bk.d2 * 4;
+      src = ws + (which == SHAMPOO_GET_L2 ? bk.off_L2 : bk.off_L2inv) + (size_t)b.slot * need;
+      break;
+    case SHAMPOO_GET_PSH: need = m * n * (size_t)b.d3 * 4; src = ws + bk.off_P + (size_t)b.slot * need; break;
     case SHAMPOO_GET_NORMS: src = ws + bk.off_norms + (size_t)b.slot * 8; need = 8; break;
     case SHAMPOO_GET_A:
     case SHAMPOO_GET_M:
     case SHAMPOO_GET_GF: {
       if (which == SHAMPOO_GET_M && !(o->cfg.momentum > 0.f)) return SHAMPOO_ERR_SHAPE;
       if (which == SHAMPOO_GET_GF && !o->use_b1) return SHAMPOO_ERR_SHAPE;
-      if (bytes != m * n * 4) return SHAMPOO_ERR_SHAPE;
-      const int64_t ld = o->shape[2 * param + 1];
       const size_t off_state = which == SHAMPOO_GET_A ? o->off_A : (which == SHAMPOO_GET_M ? o->off_M : o->off_Gf);
+      if (b.tensor) {   // state of a tensor parameter is kept block-contiguous
+        const size_t need_t = m * n * (size_t)b.d3 * 4;
+        if (bytes != need_t) return SHAMPOO_ERR_SHAPE;
+        const float *base_t = reinterpret_cast<const float *>(ws + off_state) + p.param_state_offset[param] + b.voff;
+        HIP_TRY(hipMemcpyAsync(dst, base_t, need_t, hipMemcpyDeviceToDevice, s));
+        return SHAMPOO_OK;
+      }
+      if (bytes != m * n * 4) return SHAMPOO_ERR_SHAPE;
+      const int64_t ld = p.pshape[param].cols;
       const float *base = reinterpret_cast<const float *>(ws + off_state) +
                           p.param_state_offset[param] + b.row0 * ld + b.col0;
       HIP_TRY(hipMemcpy2DAsync(dst, n * 4, base, (size_t)ld * 4, n * 4, m, hipMemcpyDeviceToDevice, s));

@@ -587,3 +587,161 @@ def test_diagonal_shampoo(bf16):
         p.step(wl.gaussian_grads(shapes, 92, t, 1e-2), 0.01, t)
         p.check(t)
     assert p.gpu.status()["failed_roots"] == 0
+
+
+# ---------------------------------------------------------------------------
+# tensor parameters: merging of small dimensions and Shampoo of order w (Sec. 2.3, 4.2.1)
+# ---------------------------------------------------------------------------
+class TensorPair:
+    """Library and oracle side by side on parameters of 3 or 4 dimensions (plus matrices and
+    vectors).  Per tensor block: factors of every dimension <= 1e-5 against the oracle; roots
+    against the oracle's root inverse of the GPU's own factor bits, the mode products against
+    their float64 value from the GPU's roots, P_shampoo, M and the whole parameter update
+    against the oracle's trajectory <= 2e-3."""
+
+    def __init__(self, shapes, b, beta2, f, eps=1e-6, mu=0.9, bf16=False, seed=0, **kw):
+        self.shapes, self.b, self.f, self.eps, self.bf16 = shapes, b, f, f32(eps), bf16
+        graft = kw.get("grafting", "adagrad")
+        self.gpu = B.Shampoo(shapes, b, beta2, eps, 0.25, f, 0, 1e-10, mu,
+                             B.GRAD_BF16 if bf16 else B.GRAD_F32, 0, kw.get("beta1", 0.0), kw.get("weight_decay", 0.0),
+                             kw.get("decoupled", True), kw.get("nesterov", False),
+                             {"adagrad": B.GRAFT_ADAGRAD, "sgd": B.GRAFT_SGD, "rmsprop": B.GRAFT_RMSPROP,
+                              "adam": B.GRAFT_ADAM}[graft], kw.get("bias_correction", False),
+                             B.ROOT_NEWTON if kw.get("newton") else B.ROOT_EIGH, 1e-6, 100, 0.99)
+        self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, 0, f32(1e-10), f32(mu),
+                                    f32(kw.get("beta1", 0.0)), f32(kw.get("weight_decay", 0.0)), kw.get("decoupled", True),
+                                    kw.get("nesterov", False), graft, kw.get("bias_correction", False),
+                                    "newton" if kw.get("newton") else "eigh", f32(1e-6), 100, f32(0.99))
+        w0 = wl.init_params(shapes, seed)
+        self.w0 = [w.astype(np.float64) for w in w0]
+        self.w_ora = [w.astype(np.float64) for w in w0]
+        self.w_gpu = to_dev(w0)
+
+    def step(self, grads_np, lr, t):
+        import torch
+        g_dev = to_dev(grads_np, self.bf16)
+        self.gpu.step(self.w_gpu, g_dev, lr, t)
+        torch.cuda.synchronize()
+        self.g_last = grads_for_oracle(g_dev)
+        self.w_prev = [w.copy() for w in self.w_ora]
+        self.ora.step(self.w_ora, self.g_last, f32(lr), t)
+
+    def resync(self):
+        """Hand the oracle the GPU's weights (see Pair.resync): used with l2 decay, where the
+        weights feed back into the state."""
+        self.w_ora = [w.cpu().numpy().astype(np.float64) for w in self.w_gpu]
+        self.w0 = [w.copy() for w in self.w_ora]
+
+    def check(self, t, plain=True):
+        """plain: no filtering / l2 shift, so the direction's input is the gradient itself."""
+        refresh = t % self.f == 0
+        worst = {"factor": 0.0, "A": 0.0, "root": 0.0, "modes": 0.0, "Psh": 0.0, "M": 0.0, "dW": 0.0}
+        for i, s in enumerate(self.shapes):
+            wg = self.w_gpu[i].cpu().numpy().astype(np.float64)
+            worst["dW"] = max(worst["dW"], rel(wg - self.w0[i], self.w_ora[i] - self.w0[i]))
+            if i not in self.ora.tblocks:
+                continue
+            vs = self.ora.view_shapes[i]
+            w = len(vs)
+            gv = self.g_last[i].reshape(vs).astype(np.float64)
+            for k, (starts, dims) in enumerate(self.ora.tblocks[i]):
+                sl = tuple(slice(s0, s0 + d) for s0, d in zip(starts, dims))
+                sel = [(B.GET_L, B.GET_LINV), (B.GET_L2, B.GET_L2INV), (B.GET_R, B.GET_RINV)][:w] if w == 3 else [(B.GET_L, B.GET_LINV)]
+                roots = []
+                for mode, (gf, gi) in enumerate(sel):
+                    F = self.gpu.get(i, k, gf).cpu().numpy()
+                    X = self.gpu.get(i, k, gi).cpu().numpy()
+                    assert F.shape == (dims[mode], dims[mode])
+                    assert np.array_equal(F, F.T) and np.array_equal(X, X.T)
+                    worst["factor"] = max(worst["factor"], rel(F, self.ora.TL[i][k][mode]))
+                    if refresh:
+                        c2 = 1.0
+                        if self.ora.bias_correction and self.ora.beta2 < 1.0:
+                            c2 = 1.0 / (1.0 - self.ora.beta2 ** (t + 1))
+                        want = so.root_inverse(c2 * F.astype(np.float64), self.eps, 0.5 / w)[0]
+                        worst["root"] = max(worst["root"], rel(X, want))
+                    roots.append(X.astype(np.float64))
+                blk3 = tuple(dims) + (1,) * (3 - w)
+                A = self.gpu.get(i, k, B.GET_A).cpu().numpy()
+                assert A.shape == blk3
+                if self.ora.grafting != "sgd":
+                    worst["A"] = max(worst["A"], rel(A.reshape(dims), self.ora.A[i][sl]))
+                P = self.gpu.get(i, k, B.GET_PSH).cpu().numpy().reshape(dims)
+                if plain:
+                    worst["modes"] = max(worst["modes"], rel(P, so.tensor_shampoo_direction(roots, gv[sl])))
+                worst["Psh"] = max(worst["Psh"], rel(P, self.ora.P_sh[i][k]))
+                norms = self.gpu.get(i, k, B.GET_NORMS).cpu().numpy()
+                assert abs(norms[0] - self.ora.s_g[i][k]) <= 2e-4 * self.ora.s_g[i][k] + 1e-30
+                assert abs(norms[1] - np.sum(P.astype(np.float64) ** 2)) <= 1e-4 * norms[1] + 1e-30
+                if self.ora.mu > 0:
+                    M = self.gpu.get(i, k, B.GET_M).cpu().numpy().reshape(dims)
+                    worst["M"] = max(worst["M"], rel(M, self.ora.M[i][sl]))
+        say(f"    t={t} worst: " + " ".join(f"{k}={v:.1e}" for k, v in worst.items()))
+        assert worst["factor"] <= TOL_FACTOR and worst["A"] <= 1e-6
+        for key in ("root", "modes", "Psh", "M", "dW"):
+            assert worst[key] <= TOL_DIR, (key, worst[key])
+
+
+TENSOR_SHAPES = [(12, 10, 3, 3),   # merges to 12 x 10 x 9 with b = 16: one block
+                 (40, 20, 6),      # blocks 16/16/8 x 16/4 x 6: ragged pieces in two dimensions
+                 (2, 3, 2),        # merges to a vector of 12: one factor, exponent 1/2
+                 (6, 5, 2),        # merges to the matrix 6 x 10
+                 (24, 16), (9,)]
+
+
+def test_tensor_parameters_every_step():
+    say("case tensors")
+    shapes = TENSOR_SHAPES
+    p = TensorPair(shapes, 16, 0.99, 1, weight_decay=0.01)
+    table, nb = p.gpu.plan()
+    assert sum(1 for r in table if int(r[7]) & 4) == 1 + 3 * 2 * 1 + 1
+    for t in range(4):
+        p.step(wl.gaussian_grads(shapes, 31, t, 1e-2), 0.01, t)
+        p.check(t)
+    assert p.gpu.status() == {"refreshes": 4, "failed_roots": 0}
+
+
+def test_tensor_parameters_with_stale_roots_and_heuristics():
+    """Roots refreshed every third step; filtering, decoupled decay, Nesterov, bias correction
+    and RMSprop grafting on tensor blocks (the elementwise kernels see them through their
+    copies); then l2 decay, where the weights enter the factors (fresh roots, weights handed
+    over after every check as in the matrix case)."""
+    say("case tensors + heuristics")
+    shapes = TENSOR_SHAPES
+    p = TensorPair(shapes, 16, 0.99, 3, beta1=0.9, weight_decay=0.05, nesterov=True,
+                   bias_correction=True, grafting="rmsprop")
+    for t in range(5):
+        p.step(wl.gaussian_grads(shapes, 32, t, 1e-2), 0.01, t)
+        p.check(t, plain=False)
+    say("case tensors + l2")
+    p = TensorPair(shapes, 16, 0.99, 1, weight_decay=0.5, decoupled=False, grafting="sgd")
+    for t in range(3):
+        p.step(wl.gaussian_grads(shapes, 35, t, 1e-2), 0.01, t)
+        p.check(t, plain=False)
+        p.resync()
+
+
+def test_tensor_parameters_bf16_gradients_and_larger_blocks():
+    """bf16 gradients; blocks above 128 in one dimension so that the blocked eigensolver and
+    multi-tile products run on tensor blocks too."""
+    say("case tensors bf16")
+    shapes = [(160, 24, 3, 3), (72, 40, 12), (300,)]   # 160 x 24 x 9 with b = 160
+    p = TensorPair(shapes, 160, 0.999, 2, bf16=True)
+    for t in range(4):
+        p.step(wl.gaussian_grads(shapes, 33, t, 1e-3), 0.01, t)
+        p.check(t)
+
+
+def test_fully_merged_tensor_with_newton_roots():
+    """w = 1 needs the inverse square root: p = 2 is one of the powers the coupled Newton
+    iteration supports, an order-3 tensor (p = 6) is refused at create."""
+    say("case merged tensor + newton")
+    shapes = [(2, 3, 2), (4, 2, 2)]
+    p = TensorPair(shapes, 16, 0.9, 1, eps=1e-4, newton=True)
+    for t in range(3):
+        p.step(wl.gaussian_grads(shapes, 34, t, 1e-2), 0.01, t)
+        wg = [w.cpu().numpy().astype(np.float64) for w in p.w_gpu]
+        for i in range(len(shapes)):
+            assert rel(wg[i] - p.w0[i], p.w_ora[i] - p.w0[i]) <= TOL_DIR
+    with pytest.raises(B.ShampooError):
+        B.Shampoo([(8, 8, 8)], 4, 0.99, 1e-6, 0.25, 1, root_method=B.ROOT_NEWTON)

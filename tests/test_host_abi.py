@@ -113,8 +113,14 @@ def test_bad_shapes_are_rejected():
     cfg = cfg_for([(8, 8)], 4)
     cfg.n_params = 0
     assert L.shampoo_plan(ctypes.byref(cfg), None, 0, None, None) == -2
-    cfg = cfg_for([(8, 8, 8)], 4)   # ndim 3
+    cfg = cfg_for([(8, 8)], 4)
+    cfg._keep[0][0] = 5             # ndim 5
     assert L.shampoo_plan(ctypes.byref(cfg), None, 0, None, None) == -2
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8, 0)], 4)), None, 0, None, None) == -2
+    # four dimensions that do not merge: order 4 is not supported
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8, 8, 8)], 4)), None, 0, None, None) == -7
+    # coupled Newton needs 1 / exponent in {1, 2, 4, 8}: an order-3 tensor would need 6
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8, 8)], 4, root_method=B.ROOT_NEWTON)), None, 0, None, None) == -7
     # a table pointer is required when cap > 0
     assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8)], 4)), None, 3, None, None) == -1
     # null handles
@@ -147,3 +153,33 @@ def test_planner_large_dimension_methods():
     blocked = B.shampoo_workspace_bytes(cfg_for(big, 1024, momentum=0.9))
     diag = B.shampoo_workspace_bytes(cfg_for(big, 1024, momentum=0.9, large_dim_method=B.LARGE_DIM_DIAGONAL))
     assert diag < blocked - 2 * 97 * 1024 * 1024 * 4
+
+
+def test_planner_merges_small_dimensions_and_blocks_tensors():
+    """Sec. 4.2.1: merging (the same cases as tests/golden/merge_dims.txt, seen through the
+    planner) and blocking of what stays a tensor; block order and the oracle's partition agree."""
+    from oracle import shampoo_oracle as so
+    # merges to a matrix: blocked like the matrix
+    t, nb = B.shampoo_plan(cfg_for([(256, 64, 1, 1)], 128))
+    assert [tuple(int(x) for x in r[:5]) for r in t] == [(0, 0, 0, 128, 64), (0, 128, 0, 128, 64)]
+    assert all(int(r[7]) == 0 and int(r[9]) == 1 for r in t)
+    # stays of order 3: (64, 64, 3, 3) -> (64, 64, 9), one block
+    t, nb = B.shampoo_plan(cfg_for([(64, 64, 3, 3)], 128))
+    assert [tuple(int(x) for x in r) for r in t] == [(0, 0, 0, 64, 64, 0, 0, 4, 0, 9)]
+    # everything merges: one factor (full-matrix AdaGrad), block len x 1 x 1
+    t, nb = B.shampoo_plan(cfg_for([(2, 3, 2)], 16))
+    assert [tuple(int(x) for x in r) for r in t] == [(0, 0, 0, 12, 1, 0, 0, 4, 0, 1)]
+    # blocking of a tensor, against the oracle's partition (row-major order of block indices)
+    shape, b = (10, 7, 5), 4
+    t, nb = B.shampoo_plan(cfg_for([shape], b))
+    want = so.tensor_block_partition(so.merge_dims(shape, b), b)
+    got = [((int(r[1]), int(r[2]), int(r[8])), (int(r[3]), int(r[4]), int(r[9]))) for r in t]
+    assert got == want and all(int(r[7]) == 4 for r in t)
+    # buckets: equal (d1, d2, d3) share one; slots count up inside it
+    keys = {}
+    for r in t:
+        k = (int(r[3]), int(r[4]), int(r[9]))
+        assert keys.setdefault(k, int(r[5])) == int(r[5])
+    assert nb == len(keys)
+    # a tensor block needs three factors and roots: workspace grows accordingly
+    assert B.shampoo_workspace_bytes(cfg_for([(64, 64, 9)], 128)) > 2 * 4 * (64 * 64 * 2 + 81)
