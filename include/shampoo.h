@@ -64,8 +64,8 @@ typedef struct {
   const int32_t *ndim;    /* host [n_params]: 1 (diagonal AdaGrad path, Sec. 4.2.2), 2, 3 or 4.
                              A parameter of 3 or 4 dimensions first has its small dimensions
                              merged (Sec. 4.2.1: from the left, a dimension joins the current
-                             group while the product stays <= block_size; only a view, no data
-                             moves).  Two dimensions left: the matrix case on the merged shape.
+                             group while the product stays <= block_size, a dimension of size 1
+                             always; only a view, no data moves).  Two dimensions left: the matrix case on the merged shape.
                              Three left, or one (all merged): Shampoo for a tensor of that order
                              w (Sec. 2.3), one factor per dimension, root exponent
                              2 * root_exponent / w, blocks of at most block_size per dimension.

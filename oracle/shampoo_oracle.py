@@ -46,7 +46,7 @@ weight decay, no momentum):
 
   A parameter of order 3 or more first has its small dimensions merged (Sec. 4.2.1): going
   from the left, a dimension is multiplied into the current group while the product stays
-  within the block size.  If two dimensions remain it is the matrix case above on the merged
+  within the block size (a dimension of size 1 always is).  If two dimensions remain it is the matrix case above on the merged
   shape.  Otherwise (three or more remain, or one: everything merged) it is Shampoo for a
   tensor of order w (Sec. 2.3 / 3, "root 2w"): every dimension is cut into pieces of at most
   the block size; each sub-tensor block keeps one factor per dimension k,
@@ -120,13 +120,15 @@ def block_partition(rows, cols, b):
 
 def merge_dims(shape, b):
     """Merging small dimensions (Sec. 4.2.1): consecutive dimensions are merged, from the
-    left, while the product stays within b.  (10, 2, 2, 4) with b = 8 gives (10, 4, 4)."""
+    left, while the product stays within b.  (10, 2, 2, 4) with b = 8 gives (10, 4, 4).
+    A dimension of size 1 always merges (it changes no product; the paper names the removal
+    of unit dimensions as a purpose of merging): (512, 256, 1, 1) with b = 128 is (512, 256)."""
     shape = [int(d) for d in shape]
     if not shape or any(d <= 0 for d in shape) or b <= 0:
         raise ValueError("bad shape or block size")
     merged, cur = [], shape[0]
     for d in shape[1:]:
-        if cur * d <= b:
+        if cur * d <= b or d == 1 or cur == 1:
             cur *= d
         else:
             merged.append(cur)

@@ -85,6 +85,7 @@ struct Bucket {
   bool t3 = false;
   int32_t d2 = 1, d3 = 1, modes = 0;
   size_t off_L2 = 0, off_L2inv = 0, off_desc3 = 0;
+  int32_t split3 = 1;   // row ranges of the (d1 d2) x d3 unfolding whose Gram matrices are formed separately
   bool whole() const { return diagL || diagR; }
   int32_t rdim() const { return t3 ? d3 : n; }
   size_t l_elems() const { return diagL ? (size_t)m : (size_t)m * m; }
@@ -118,7 +119,8 @@ int param_shape(const shampoo_config *c, int i, PShape &ps) {
   int cnt = 0;
   int64_t cur = sh[0];
   for (int k = 1; k < nd; ++k) {
-    if (cur * sh[k] <= c->block_size) cur *= sh[k];
+    // a dimension of size 1 changes no product and always merges
+    if (cur * sh[k] <= c->block_size || sh[k] == 1 || cur == 1) cur *= sh[k];
     else { merged[cnt++] = cur; cur = sh[k]; }
   }
   merged[cnt++] = cur;
@@ -308,6 +310,14 @@ void make_plan(const shampoo_config *c, Plan &p) {
     if (ld % 8 != 0 || (blk.row0 * ld + blk.col0) % 8 != 0) p.buckets[blk.bucket].bf16_mfma = false;
   }
   for (auto &bk : p.buckets) {
+    if (bk.t3 && bk.modes == 3) {
+      // the factor of the last dimension sums over d1 d2 rows into one small tile per block:
+      // split the rows (whole slices of the first index) so that the launch fills the GPU
+      for (int sdiv = 1; sdiv <= std::min(bk.m, 64); ++sdiv)
+        if (bk.m % sdiv == 0 && (int64_t)(bk.m / sdiv) * bk.d2 >= 64 && (int64_t)sdiv * bk.d3 <= (int64_t)bk.m * bk.d2 &&
+            (int64_t)bk.count * sdiv <= 1 << 20)
+          bk.split3 = sdiv;
+    }
     bk.geom = make_geom(bk.m, bk.n);
     bk.tiles_m = (bk.m + BM - 1) / BM;
     bk.tiles_n = (bk.n + BN - 1) / BN;
@@ -664,7 +674,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     if (b.t3) {
       b.off_L2 = take(B * (size_t)b.d2 * b.d2 * 4);
       b.off_L2inv = take(B * (size_t)b.d2 * b.d2 * 4);
-      b.off_desc3 = take(B * sizeof(BlockDesc));
+      b.off_desc3 = take(B * (size_t)b.split3 * sizeof(BlockDesc));
       t2_elems = std::max(t2_elems, B * m * n);
     }
     b.off_P = take(B * m * n * 4);
@@ -909,15 +919,23 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         // Above: L_1 <- beta L_1 + alpha G_(1) G_(1)^T, the block being d1 x (d2 d3).  The other
         // dimensions exist only for a tensor of order three.
         if (b.modes == 3) {
-          // L_3 <- beta L_3 + alpha G_(3) G_(3)^T: the block as (d1 d2) x d3, read "rows along k"
+          // L_3 <- beta L_3 + alpha G_(3) G_(3)^T: the block as (d1 d2) x d3, read "rows along k".
+          // Its rows are cut into split3 ranges, each a batch entry that leaves its Gram matrix
+          // in scratch; gram_reduce_kernel adds them up in float64 and applies the moving average.
+          float *T2 = reinterpret_cast<float *>(ws + o->off_T2);
           g.desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc3);
-          g.c = reinterpret_cast<float *>(ws + b.off_R); g.c_batch_stride = (int64_t)b.d3 * b.d3; g.ldc = b.d3;
-          g.M = b.d3; g.N = b.d3; g.K = b.m * b.d2;
+          g.c = T2; g.c_batch_stride = (int64_t)b.d3 * b.d3; g.ldc = b.d3;
+          g.M = b.d3; g.N = b.d3; g.K = (b.m / b.split3) * b.d2;
+          g.alpha = 1.f; g.beta = 0.f; g.alpha_d = 1.0; g.beta_d = 0.0; g.batch = b.count * b.split3;
           g.tiles_m = g.tiles_n = (b.d3 + BM - 1) / BM; g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
           rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
           if (rc) return rc;
+          GramReduceArgs gr;
+          gr.partial = T2; gr.factor = reinterpret_cast<float *>(ws + b.off_R); gr.d = b.d3; gr.splits = b.split3;
+          gr.alpha = alpha; gr.beta = beta;
+          hipLaunchKernelGGL(gram_reduce_kernel, dim3((b.d3 * b.d3 + 255) / 256, b.count), dim3(256), 0, s, gr);
+          HIP_TRY(hipGetLastError());
           // L_2 <- beta L_2 + alpha G_(2) G_(2)^T: the block with its first two indices swapped, d2 x (d1 d3)
-          float *T2 = reinterpret_cast<float *>(ws + o->off_T2);
           PermuteArgs pm{};
           pm.desc = desc; pm.table = gs_tab; pm.dst = T2; pm.d1 = b.m; pm.d2 = b.d2; pm.d3 = b.d3;
           const unsigned pchunks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, ((int64_t)b.m * b.n + 2047) / 2048));
@@ -1318,7 +1336,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
   std::vector<std::vector<BlockDesc>> descs(p.buckets.size()), descs3(p.buckets.size());
   for (size_t i = 0; i < p.buckets.size(); ++i) {
     descs[i].resize(p.buckets[i].count);
-    if (p.buckets[i].t3) descs3[i].resize(p.buckets[i].count);
+    if (p.buckets[i].t3) descs3[i].resize((size_t)p.buckets[i].count * p.buckets[i].split3);
   }
   for (const Block &b : p.blocks) {
     BlockDesc d;
@@ -1329,9 +1347,14 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
       d.ld = b.n * b.d3;
       d.offset = b.voff;
       d.state_offset = p.param_state_offset[b.param] + d.offset;
-      BlockDesc d3 = d;
-      d3.ld = b.d3;
-      descs3[b.bucket][b.slot] = d3;
+      // (one entry per row range of the split Gram product, see split3)
+      const int sp = p.buckets[b.bucket].split3;
+      for (int k = 0; k < sp; ++k) {
+        BlockDesc d3 = d;
+        d3.ld = b.d3;
+        d3.offset = b.voff + (int64_t)k * (b.m / sp) * b.n * b.d3;
+        descs3[b.bucket][(size_t)b.slot * sp + k] = d3;
+      }
     } else {
       d.ld = (int32_t)p.pshape[b.param].cols;
       d.offset = b.row0 * d.ld + b.col0;

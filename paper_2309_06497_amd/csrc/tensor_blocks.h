@@ -78,4 +78,27 @@ __global__ __launch_bounds__(256) void permute_12_kernel(const PermuteArgs g) {
   }
 }
 
+struct GramReduceArgs {
+  const float *partial;   // [slot][splits][d][d]
+  float *factor;          // [slot][d][d]
+  int32_t d, splits;
+  double alpha, beta;
+};
+
+// factor <- beta factor + alpha sum_s partial_s, in float64, fixed order.  The factor of the
+// last dimension of a tensor block is a d3 x d3 Gram matrix over d1 d2 rows (d3 = 9 for a
+// 3 x 3 convolution, 16384 rows at block size 128): its rows are split into `splits` ranges
+// whose Gram matrices are separate batch entries of the SYRK launch.  grid (ceil(d d / 256), slots).
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const GramReduceArgs g) {
+  const int slot = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  const int dd = g.d * g.d;
+  if (e >= dd) return;
+  const float *p = g.partial + (int64_t)slot * g.splits * dd + e;
+  double acc = 0.0;
+  for (int s = 0; s < g.splits; ++s) acc += (double)p[(int64_t)s * dd];
+  float *f = g.factor + (int64_t)slot * dd + e;
+  *f = (float)(g.beta * (double)*f + g.alpha * acc);
+}
+
 }  // namespace shampoo

@@ -71,6 +71,36 @@ def resnet50_shapes():
     return shapes
 
 
+def resnet50_conv4d_shapes():
+    """The same network with its convolution weights left as (out, in, kh, kw) tensors, the
+    form the paper's merging of small dimensions (Sec. 4.2.1) starts from: with block size
+    128 a 1 x 1 convolution merges to the matrix (out, in), a 3 x 3 one to the order-3 tensor
+    (out, in, 9) and the 7 x 7 stem to (64, 21, 7)."""
+    shapes = []
+    for s in resnet50_shapes():
+        shapes.append(s)
+    out, i = [], 0
+    # walk the 2-D list again, restoring (cin, k) from the construction order
+    def conv_bn(cout, cin, k):
+        out.append((cout, cin, k, k))
+        out.append((cout,))
+        out.append((cout,))
+    conv_bn(64, 3, 7)
+    cin = 64
+    for width, depth in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for blk in range(depth):
+            conv_bn(width, cin, 1)
+            conv_bn(width, width, 3)
+            conv_bn(width * 4, width, 1)
+            if blk == 0:
+                conv_bn(width * 4, cin, 1)
+            cin = width * 4
+    out.append((2048, 1000))
+    out.append((1000,))
+    assert [numel(a) for a in out] == [numel(b) for b in shapes]
+    return out
+
+
 def transformer_shapes(layers=24, d=2048):
     """Per layer: LayerNorm (w, b), QKV d x 3d, attention out d x d, LayerNorm
     (w, b), MLP up d x 4d, MLP down 4d x d; one final LayerNorm pair."""

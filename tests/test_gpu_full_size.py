@@ -174,6 +174,28 @@ def test_resnet50_shapes_every_block():
 
 
 @pytest.mark.gpu
+@pytest.mark.timeout(900)
+def test_resnet50_with_convolution_weights_as_tensors():
+    """ResNet-50 with its convolution weights given as (out, in, kh, kw): merging (Sec. 4.2.1)
+    turns the 1 x 1 ones into matrices and leaves the 3 x 3 ones and the stem as order-3
+    tensors (out, in, 9) / (64, 21, 7), blocked at 128; every tensor block's factors, roots,
+    direction and momentum and every parameter's update against the oracle."""
+    from test_gpu_parity import TensorPair, say
+    say("case resnet50, 4-D convolution weights")
+    shapes = wl.resnet50_conv4d_shapes()
+    sig = wl.per_tensor_sigmas(shapes, 22)
+    p = TensorPair(shapes, 128, 0.999, 2, eps=1e-6)
+    table, _ = p.gpu.plan()
+    n_tensor = sum(1 for r in table if int(r[7]) & 4)
+    say(f"    {len(table)} blocks, {n_tensor} of them tensor blocks")
+    assert n_tensor == 1 + 3 * 1 + 4 * 1 + 6 * 4 + 3 * 16      # stem; 3 x 3 convolutions of widths 64, 128, 256, 512
+    for t in range(3):
+        p.step(wl.gaussian_grads(shapes, 22, t, sig), 0.01, t)
+        p.check(t)
+    assert p.gpu.status() == {"refreshes": 2, "failed_roots": 0}
+
+
+@pytest.mark.gpu
 def test_block_size_2048():
     """Sec. 4.2.1 / Table 5 use preconditioner blocks up to 8192; one 2048 x 2048 block exercises
     16 x 16 tiles per GEMM and the blocked eigensolver at n = 2048 inside the optimizer."""
