@@ -105,8 +105,11 @@ typedef struct {
                              SHAMPOO_ROOT_NEWTON: coupled inverse Newton iteration of the same
                              section on L + epsilon I, in float32; needs 1/root_exponent in
                              {1, 2, 4, 8} (else SHAMPOO_ERR_UNSUPPORTED; for a tensor parameter
-                             the exponent in question is 2 * root_exponent / w) and factors
-                             whose condition number float32 can resolve                      */
+                             the exponent in question is 2 * root_exponent / w).  A factor whose
+                             iterates do not stay finite (condition number beyond float32) is
+                             handed to the eigendecomposition instead (the guard of Sec. 3.2.3);
+                             to learn whether any did, a refresh step under this method waits
+                             for `stream` once per batch of factors                          */
   float newton_tolerance; /* stop when ||M_k - I||_inf < this; 0 selects 1e-6 (Sec. 3.2.1)     */
   int32_t newton_max_iterations; /* iteration cap, <= 1000; 0 selects 100                     */
   int32_t precond_matrix_cores; /* SHAMPOO_MATRIX_CORES_AUTO (default): with bf16 gradients and blocks
@@ -173,9 +176,9 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
  *         row-major with the shapes given at create; updated in place.
  * grads:  host array [n_params] of device pointers, float32 or bfloat16 per
  *         grad_dtype, same shapes; read only.
- * Asynchronous on `stream`.  A factor whose eigendecomposition is not finite
- * keeps its previous root (Sec. 3.2.3); such events are counted, see
- * shampoo_status.
+ * Asynchronous on `stream` (except refresh steps under SHAMPOO_ROOT_NEWTON, see
+ * root_method).  A factor whose eigendecomposition is not finite keeps its
+ * previous root (Sec. 3.2.3); such events are counted, see shampoo_status.
  */
 int shampoo_step(shampoo_opt *opt, void *const *params, const void *const *grads,
                  float lr, int64_t step, void *stream);

@@ -386,8 +386,13 @@ class ShampooOracle:
     def _root(self, F, r=None):
         r = self.r if r is None else r
         if self.root_method == "newton":
-            return root_inverse_newton(F, self.epsilon, int(round(1.0 / r)), self.newton_tol,
-                                       self.newton_max_iter)[0]
+            with np.errstate(over="ignore", invalid="ignore"):
+                X, _, err = root_inverse_newton(F, self.epsilon, int(round(1.0 / r)), self.newton_tol,
+                                                self.newton_max_iter)
+            # guard of Sec. 3.2.3: a failed root computation is retried by the other, more
+            # accurate routine (here: the eigendecomposition) before the previous root is kept
+            if np.isfinite(err) and np.all(np.isfinite(X)):
+                return X
         return root_inverse(F, self.epsilon, r)[0]
 
     def _graft_state(self, A, G):

@@ -225,12 +225,14 @@ struct SmallRootArgs {
   int32_t n;
   float epsilon, r;
   float scale;           // the root is taken of scale * A (bias correction, Sec. 3.1.1); 1 = off
+  const int32_t *only;   // optional [batch]: matrices whose entry is 0 are left alone (x untouched)
 };
 
 // NT threads per workgroup: 256 while several matrices fit the LDS of a CU (n <= 64); 1024
 // above, where only one or two do and more wavefronts are the only way to hide LDS latency.
 template <int NT>
 __global__ __launch_bounds__(NT) void rootinv_small_kernel(const SmallRootArgs g) {
+  if (g.only && g.only[blockIdx.x] == 0) return;   // the whole workgroup, before any barrier
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int NW = NT / 64;
   __shared__ float redf[NW];
@@ -372,6 +374,8 @@ struct BlockInitArgs {
   const float *a; int64_t a_stride; int32_t n;
   double *w; float *qt; int32_t np;
   float *dmax; int32_t *failed; int32_t *rot;
+  const int32_t *only;   // optional [batch]: a matrix whose entry is 0 is marked 2 in `failed`, which
+                         // every later kernel takes as "leave alone" without counting it as a failure
 };
 
 // W = pad(sym(A)), Qt = I, dmax, failed, rot = 0.  grid (np, batch), 256 threads.
@@ -380,6 +384,10 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
   double *w = g.w + (int64_t)b * np * np + (int64_t)i * np;
   float *qt = g.qt + (int64_t)b * np * np + (int64_t)i * np;
   const float *a = g.a + (int64_t)b * g.a_stride;
+  if (g.only && g.only[b] == 0) {
+    if (i == 0 && threadIdx.x == 0) g.failed[b] = 2;
+    return;
+  }
   int bad = 0;
   for (int j = threadIdx.x; j < np; j += 256) {
     double v = 0.0;
@@ -808,7 +816,7 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
   if (lane == 0) redi[wave] = badf;
   __syncthreads();
   badf = redi[0] | redi[1] | redi[2] | redi[3];
-  if (tid == 0) {
+  if (tid == 0 && bad != 2) {   // 2: not this call's matrix (see BlockInitArgs::only)
     g.failed[b] = badf;
     if (g.failed_out) g.failed_out[b] = badf;
     if (badf && g.fail_count) atomicAdd(g.fail_count, 1ull);

@@ -408,7 +408,7 @@ AuxStreams *aux_streams() {
 // Block-Jacobi root inverse of `cnt` matrices, using workspace slots [slot0, slot0 + cnt).
 int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float scale, float *x, float *lambda,
                        int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
-                       const EigLayout &e, int slot0, hipStream_t s) {
+                       const EigLayout &e, int slot0, hipStream_t s, const int32_t *only) {
   const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
   double *w = reinterpret_cast<double *>(ws + e.off_w) + (int64_t)slot0 * np * np;
   float *qt = reinterpret_cast<float *>(ws + e.off_qt) + (int64_t)slot0 * np * np;
@@ -424,7 +424,7 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   if (rc) return rc;
   BlockInitArgs ia;
   ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
-  ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot;
+  ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot; ia.only = only;
   hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cnt), dim3(256), 0, s, ia);
   HIP_TRY(hipGetLastError());
   BlockJacArgs ja;
@@ -461,16 +461,17 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
 }
 
 // X_i = rootinv(scale * A_i) for a batch of dense n x n matrices.  ws: eig_layout(n, >= chunk) region.
+// only: optional device array [batch]; matrices whose entry is 0 are skipped (x left as it is).
 int root_inverse_batched(const float *a, int n, int batch, float eps, float r, float scale, float *x, float *lambda,
                          int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
-                         const EigLayout &e, hipStream_t s) {
+                         const EigLayout &e, hipStream_t s, const int32_t *only = nullptr) {
   if (batch <= 0) return SHAMPOO_OK;
   if (n <= JAC_SMALL_MAX) {
     SmallRootArgs g;
     g.a = a; g.a_stride = (int64_t)n * n;
     g.x = x; g.x_stride = (int64_t)n * n;
     g.lambda = lambda; g.failed = failed_user; g.fail_count = fail_count;
-    g.n = n; g.epsilon = eps; g.r = r; g.scale = scale;
+    g.n = n; g.epsilon = eps; g.r = r; g.scale = scale; g.only = only;
     const size_t lds = rootinv_small_lds_bytes(n);
     if (n <= 64) {
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(rootinv_small_kernel<256>),
@@ -504,7 +505,8 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
       const int rc = block_jacobi_solve(a + (int64_t)(b0 + first) * n * n, n, cnt, eps, r, scale,
                                         x + (int64_t)(b0 + first) * n * n,
                                         lambda ? lambda + (int64_t)(b0 + first) * n : nullptr,
-                                        failed_user ? failed_user + b0 + first : nullptr, fail_count, ws, e, first, sk);
+                                        failed_user ? failed_user + b0 + first : nullptr, fail_count, ws, e, first, sk,
+                                        only ? only + b0 + first : nullptr);
       if (rc) return rc;
       first += cnt;
     }
@@ -640,6 +642,7 @@ struct shampoo_opt {
   std::vector<size_t> off_Gb, off_Wb;
   size_t off_T2 = 0;
   bool has_tensor = false;
+  size_t off_nfail = 0;   // coupled Newton: per-matrix failure flags of one batch (int32)
   std::vector<void *> last_w, last_g;    // pointer tables currently on the device
   bool ptrs_aligned16 = false;           // every gradient pointer is 16-byte aligned
   int64_t last_step = -1;
@@ -663,7 +666,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offG1tab = take((size_t)c->n_params * sizeof(void *));
   const size_t offGftab = take((size_t)c->n_params * sizeof(void *));
   const size_t offPrep = (use_l2 || use_b1) ? take(std::max<size_t>(1, p.prep_chunks.size()) * sizeof(DiagChunk)) : 0;
-  size_t t_elems = 0, t2_elems = 0, eig_bytes = 0;
+  size_t t_elems = 0, t2_elems = 0, eig_bytes = 0, max_count = 1;
   std::vector<EigLayout> eL, eR, e2;
   for (auto &b : p.buckets) {
     const size_t B = b.count, m = b.m, n = b.n;
@@ -702,11 +705,12 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     eL.push_back(eig_layout(em, b.count));
     eR.push_back(eig_layout(en, b.count));
     e2.push_back(eig_layout(b.d2, b.count));
+    // under coupled Newton the eigensolver is the fallback of the guard (Sec. 3.2.3): room for both
     if (c->root_method == SHAMPOO_ROOT_NEWTON)
       eig_bytes = std::max(eig_bytes, std::max(newton_layout(em, b.count).bytes,
                                                std::max(newton_layout(en, b.count).bytes, newton_layout(b.d2, b.count).bytes)));
-    else
-      eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, std::max(eR.back().bytes, e2.back().bytes)));
+    eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, std::max(eR.back().bytes, e2.back().bytes)));
+    max_count = std::max(max_count, (size_t)b.count);
   }
   const size_t offT = take(t_elems * 4);
   const size_t offT2 = t2_elems ? take(t2_elems * 4) : 0;
@@ -726,6 +730,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   for (auto &b : p.buckets) if (b.m <= SB && b.n <= SB && !b.whole() && !b.t3) n_small += b.count;
   const size_t offSmall = take(std::max<size_t>(1, (size_t)n_small) * sizeof(SmallBlock));
   const size_t offC = take(64);
+  const size_t offNf = take(max_count * 4);
   const size_t offE = take(eig_bytes);
   if (o) {
     o->off_A = offA; o->off_M = offM; o->off_T = offT;
@@ -734,6 +739,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
     o->off_small = offSmall; o->n_small = n_small;
     o->eig_L = eL; o->eig_R = eR; o->eig_2 = e2;
+    o->off_nfail = offNf;
     o->off_T2 = offT2; o->off_Gb = offGb; o->off_Wb = offWb; o->has_tensor = has_tensor;
   }
   return off;
@@ -766,6 +772,34 @@ int split_roots(shampoo_opt *o, hipStream_t s) {
     HIP_TRY(hipGetLastError());
   }
   return SHAMPOO_OK;
+}
+
+// Coupled Newton with the guard of Sec. 3.2.3.  The paper retries a failed root computation in
+// higher precision and keeps the previous root only if that fails too; here the float32
+// iteration is the first attempt, and a matrix whose iterates do not stay finite (a condition
+// number beyond float32) is handed to the eigendecomposition, which works on a float64 copy.
+// Whether any matrix failed is read back, so a refresh under root_method = NEWTON waits for
+// the stream once per factor batch; failures of the fallback are what gets counted.
+int newton_root_guarded(shampoo_opt *o, const float *F, int dim, int count, float r_exp, float c2, float *Fi,
+                        const EigLayout &lay, hipStream_t s) {
+  const shampoo_config &c = o->cfg;
+  unsigned char *ws = o->ws;
+  unsigned long long *counters = reinterpret_cast<unsigned long long *>(ws + o->off_count);
+  unsigned long long *newton_failed = counters + 1;
+  int32_t *flags = reinterpret_cast<int32_t *>(ws + o->off_nfail);
+  const float tol = c.newton_tolerance > 0.f ? c.newton_tolerance : 1e-6f;
+  const int cap = c.newton_max_iterations > 0 ? c.newton_max_iterations : 100;
+  int rc = launch_fill(reinterpret_cast<float *>(newton_failed), 0.f, 2, s);
+  if (rc) return rc;
+  rc = newton_root_batched(F, dim, count, c.epsilon, newton_p_of(r_exp), c2, tol, cap, Fi, nullptr, flags, newton_failed,
+                           ws + o->off_eig, newton_layout(dim, count), s);
+  if (rc) return rc;
+  unsigned long long n_failed = 0;
+  HIP_TRY(hipMemcpyAsync(&n_failed, newton_failed, sizeof(n_failed), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (n_failed == 0) return SHAMPOO_OK;
+  return root_inverse_batched(F, dim, count, c.epsilon, r_exp, c2, Fi, nullptr, nullptr, counters, ws + o->off_eig, lay, s,
+                              flags);
 }
 
 // GT: element type of the caller's gradients.  GS: of the gradients that feed the factors and
@@ -1012,11 +1046,8 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         const EigLayout *lay[3] = {&o->eig_L[i], &o->eig_2[i], &o->eig_R[i]};
         for (int k = 0; k < b.modes; ++k) {
           if (c.root_method == SHAMPOO_ROOT_NEWTON) {
-            const float tol = c.newton_tolerance > 0.f ? c.newton_tolerance : 1e-6f;
-            const int cap = c.newton_max_iterations > 0 ? c.newton_max_iterations : 100;
-            rc = newton_root_batched(reinterpret_cast<float *>(ws + fac[k]), dims[k], b.count, c.epsilon, newton_p_of(rw), c2,
-                                     tol, cap, reinterpret_cast<float *>(ws + inv[k]), nullptr, nullptr, fail_count,
-                                     ws + o->off_eig, newton_layout(dims[k], b.count), s);
+            rc = newton_root_guarded(o, reinterpret_cast<float *>(ws + fac[k]), dims[k], b.count, rw, c2,
+                                     reinterpret_cast<float *>(ws + inv[k]), *lay[k], s);
           } else {
             rc = root_inverse_batched(reinterpret_cast<float *>(ws + fac[k]), dims[k], b.count, c.epsilon, rw, c2,
                                       reinterpret_cast<float *>(ws + inv[k]), nullptr, nullptr, fail_count,
@@ -1027,16 +1058,11 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         continue;
       }
       if (c.root_method == SHAMPOO_ROOT_NEWTON) {
-        const int pw = newton_p_of(c.root_exponent);
-        const float tol = c.newton_tolerance > 0.f ? c.newton_tolerance : 1e-6f;
-        const int cap = c.newton_max_iterations > 0 ? c.newton_max_iterations : 100;
-        rc = newton_root_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, pw, c2, tol, cap,
-                                 reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
-                                 ws + o->off_eig, newton_layout(b.m, b.count), s);
+        rc = newton_root_guarded(o, reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.root_exponent, c2,
+                                 reinterpret_cast<float *>(ws + b.off_Linv), o->eig_L[i], s);
         if (rc) return rc;
-        rc = newton_root_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, pw, c2, tol, cap,
-                                 reinterpret_cast<float *>(ws + b.off_Rinv), nullptr, nullptr, fail_count,
-                                 ws + o->off_eig, newton_layout(b.n, b.count), s);
+        rc = newton_root_guarded(o, reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.root_exponent, c2,
+                                 reinterpret_cast<float *>(ws + b.off_Rinv), o->eig_R[i], s);
         if (rc) return rc;
         continue;
       }
