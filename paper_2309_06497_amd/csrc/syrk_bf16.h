@@ -292,21 +292,37 @@ struct TransposeArgs {
 };
 
 // out[slot][j][i] = G_block[i][j] (bf16 bits).  grid (ceil(n/64), ceil(m/64), blocks), 256 threads.
+// Both sides move 16 bytes per lane (8 bf16 along the contiguous direction); the transposition
+// itself happens in LDS.  Requires m % 8 == 0, n % 8 == 0, 16-byte aligned rows on both sides
+// (the conditions of the bf16 matrix-core path, checked by the host).
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeArgs g) {
   __shared__ uint16_t tile[64][66];
   const BlockDesc d = g.desc[blockIdx.z];
   const uint16_t *src = reinterpret_cast<const uint16_t *>(g.g_table[d.param]) + d.offset;
   uint16_t *dst = g.out + (int64_t)blockIdx.z * g.m * g.n;
   const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int ii = ty; ii < 64; ii += 4) {
-    const int i = i0 + ii, j = j0 + tx;
-    tile[ii][tx] = (i < g.m && j < g.n) ? src[(int64_t)i * d.ld + j] : (uint16_t)0;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int idx = threadIdx.x + 256 * h, r = idx >> 3, c = (idx & 7) * 8;
+    const int i = i0 + r, j = j0 + c;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (i < g.m && j < g.n) v = *reinterpret_cast<const uint4 *>(src + (int64_t)i * d.ld + j);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {      // rows of 66 elements are only 4-byte aligned
+      *reinterpret_cast<uint32_t *>(&tile[r][c + 2 * e]) = w[e];
+    }
   }
   __syncthreads();
-  for (int jj = ty; jj < 64; jj += 4) {
-    const int j = j0 + jj, i = i0 + tx;
-    if (j < g.n && i < g.m) dst[(int64_t)j * g.m + i] = tile[tx][jj];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int idx = threadIdx.x + 256 * h, jr = idx >> 3, c = (idx & 7) * 8;   // output row jr, columns c .. c + 7
+    const int j = j0 + jr, i = i0 + c;
+    if (j >= g.n || i >= g.m) continue;
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[c + 2 * e][jr] | ((uint32_t)tile[c + 2 * e + 1][jr] << 16);
+    *reinterpret_cast<uint4 *>(dst + (int64_t)j * g.m + i) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 
