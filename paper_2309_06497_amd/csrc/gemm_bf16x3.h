@@ -41,7 +41,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "gemm_mfma.h"
-#include "syrk_bf16.h"
+#include "lds_dma.h"
 
 namespace shampoo {
 
@@ -89,8 +89,8 @@ __global__ __launch_bounds__(256) void split3_kernel(const float *in, uint16_t *
   out[i] = (uint16_t)h; out[count + i] = (uint16_t)m; out[2 * count + i] = (uint16_t)l;
 }
 
-#define X3_DS_READ(dst, addr, imm) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm) : "memory")
-#define X3_SB() __builtin_amdgcn_sched_barrier(0)
+#define X3_DS_READ(dst, addr, imm) LDS_DS_READ_B128(dst, addr, imm)
+#define X3_SB() LDS_SCHED_BARRIER()
 // the two 32-row tiles of plane S of the A slab / the four of plane U of the B slab, at the k step of (LA, LB)
 #define X3_RD_A(S, LA) { X3_DS_READ(a[S][0], LA, (S) * X3_A_SLAB); X3_DS_READ(a[S][1], LA, (S) * X3_A_SLAB + 2048); }
 #define X3_RD_B(DST, U, LB) { X3_DS_READ(DST[0], LB, (U) * X3_B_SLAB); X3_DS_READ(DST[1], LB, (U) * X3_B_SLAB + 2048); \
@@ -275,14 +275,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void gemm_bf16x3_kernel(const Gemm
   int stage = 0, stage_in = NST - 1;
   for (int kt = 0; kt < nk; ++kt) {
     // outstanding: slab kt, and slab kt + 1 if there are three stages and it exists
-    if (NST == 3 && kt + 1 < nk) { SYRK_WAIT_VM(PW); } else { SYRK_WAIT_VM(0); }
+    if (NST == 3 && kt + 1 < nk) { LDS_DMA_WAIT_VM(PW); } else { LDS_DMA_WAIT_VM(0); }
     __builtin_amdgcn_s_barrier();
     const int kin = kt + NST - 1;
     slab_product((uint32_t)(stage * STAGE), kin < nk, smem + stage_in * STAGE, min(kin, nk - 1) * X3_BK);
     stage = stage + 1 == NST ? 0 : stage + 1;
     stage_in = stage_in + 1 == NST ? 0 : stage_in + 1;
   }
-  SYRK_WAIT_VM(0);
+  LDS_DMA_WAIT_VM(0);
 
   // epilogue: accumulator element v of MFMA tile (mi, ni) is
   // row = wm*64 + mi*32 + 8*(v/4) + 4*(lane/32) + v%4, col = wn*128 + ni*32 + lane%32

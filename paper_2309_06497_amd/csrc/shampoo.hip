@@ -30,7 +30,10 @@ namespace {
 
 constexpr int64_t MAX_BLOCK_SIZE = 8192;
 constexpr size_t ALIGN = 256;
-constexpr size_t EIG_CHUNK_BYTES = (size_t)3 << 30;   // W + Qt of one chunk of the block solver
+#ifndef SHAMPOO_EIG_CHUNK_GIB
+#define SHAMPOO_EIG_CHUNK_GIB 3
+#endif
+constexpr size_t EIG_CHUNK_BYTES = (size_t)SHAMPOO_EIG_CHUNK_GIB << 30;   // W + Qt of one chunk of the block solver
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 

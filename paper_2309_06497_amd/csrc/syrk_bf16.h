@@ -29,13 +29,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "gemm_mfma.h"
+#include "lds_dma.h"
 
 namespace shampoo {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void lds_void;
-typedef const __attribute__((address_space(1))) void glb_void;
 
 constexpr int SBK = 32;                        // k per slab: two MFMAs chained in float32, then the float64 flush
 constexpr int SYRK_SLAB = BM * SBK * 2;        // bytes of one operand slab
@@ -53,13 +49,6 @@ struct SyrkBf16Args {
   int32_t batch;
 };
 
-// a wave-uniform pointer, held in scalar registers
-__device__ __forceinline__ const char *uniform_ptr(const void *p) {
-  const uint64_t v = reinterpret_cast<uint64_t>(p);
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-  return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
-}
-
 __device__ __forceinline__ void syrk_flush(double (&dst)[16], const floatx16 &src) {
 #pragma unroll
   for (int v = 0; v < 16; ++v) dst[v] += (double)src[v];
@@ -74,10 +63,6 @@ __device__ __forceinline__ floatx16 syrk_chain(const u32x4 &a0, const u32x4 &b0,
   return acc;
 }
 
-#define SYRK_DS_READ(dst, addr, imm) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(imm) : "memory")
-// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters at their maxima)
-#define SYRK_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
-#define SYRK_SB() __builtin_amdgcn_sched_barrier(0)
 
 // Requires: operand base 16-byte aligned, ld % 8 == 0, K % 8 == 0 (checked by the host).
 __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf16Args g) {
@@ -161,26 +146,26 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   // is flushed during the next slab.
 #define SYRK_SLAB_PRODUCT(S)                                                              \
   {                                                                                       \
-    SYRK_DS_READ(oa[0][0], la0, (S) * SYRK_STAGE);                                        \
-    SYRK_DS_READ(ob[0][0], lb0, (S) * SYRK_STAGE + SYRK_SLAB);                            \
-    SYRK_DS_READ(oa[0][1], la1, (S) * SYRK_STAGE);                                        \
-    SYRK_DS_READ(ob[0][1], lb1, (S) * SYRK_STAGE + SYRK_SLAB);                            \
-    SYRK_DS_READ(oa[1][0], la0, (S) * SYRK_STAGE + 32 * SBK * 2);                         \
-    SYRK_DS_READ(ob[1][0], lb0, (S) * SYRK_STAGE + SYRK_SLAB + 32 * SBK * 2);             \
-    SYRK_DS_READ(oa[1][1], la1, (S) * SYRK_STAGE + 32 * SBK * 2);                         \
-    SYRK_DS_READ(ob[1][1], lb1, (S) * SYRK_STAGE + SYRK_SLAB + 32 * SBK * 2);             \
+    LDS_DS_READ_B128(oa[0][0], la0, (S) * SYRK_STAGE);                                        \
+    LDS_DS_READ_B128(ob[0][0], lb0, (S) * SYRK_STAGE + SYRK_SLAB);                            \
+    LDS_DS_READ_B128(oa[0][1], la1, (S) * SYRK_STAGE);                                        \
+    LDS_DS_READ_B128(ob[0][1], lb1, (S) * SYRK_STAGE + SYRK_SLAB);                            \
+    LDS_DS_READ_B128(oa[1][0], la0, (S) * SYRK_STAGE + 32 * SBK * 2);                         \
+    LDS_DS_READ_B128(ob[1][0], lb0, (S) * SYRK_STAGE + SYRK_SLAB + 32 * SBK * 2);             \
+    LDS_DS_READ_B128(oa[1][1], la1, (S) * SYRK_STAGE + 32 * SBK * 2);                         \
+    LDS_DS_READ_B128(ob[1][1], lb1, (S) * SYRK_STAGE + SYRK_SLAB + 32 * SBK * 2);             \
     asm volatile("s_waitcnt lgkmcnt(0)"                                                   \
                  : "+v"(oa[0][0]), "+v"(oa[0][1]), "+v"(oa[1][0]), "+v"(oa[1][1]),        \
                    "+v"(ob[0][0]), "+v"(ob[0][1]), "+v"(ob[1][0]), "+v"(ob[1][1]) :: "memory"); \
-    SYRK_SB();                                                                            \
-    X = syrk_chain(oa[0][0], ob[0][0], oa[0][1], ob[0][1]); SYRK_SB();                    \
-    syrk_flush(acc64[1][1], Y); SYRK_SB();                                                \
-    Y = syrk_chain(oa[0][0], ob[1][0], oa[0][1], ob[1][1]); SYRK_SB();                    \
-    syrk_flush(acc64[0][0], X); SYRK_SB();                                                \
-    X = syrk_chain(oa[1][0], ob[0][0], oa[1][1], ob[0][1]); SYRK_SB();                    \
-    syrk_flush(acc64[0][1], Y); SYRK_SB();                                                \
-    Y = syrk_chain(oa[1][0], ob[1][0], oa[1][1], ob[1][1]); SYRK_SB();                    \
-    syrk_flush(acc64[1][0], X); SYRK_SB();                                                \
+    LDS_SCHED_BARRIER();                                                                            \
+    X = syrk_chain(oa[0][0], ob[0][0], oa[0][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
+    syrk_flush(acc64[1][1], Y); LDS_SCHED_BARRIER();                                                \
+    Y = syrk_chain(oa[0][0], ob[1][0], oa[0][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
+    syrk_flush(acc64[0][0], X); LDS_SCHED_BARRIER();                                                \
+    X = syrk_chain(oa[1][0], ob[0][0], oa[1][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
+    syrk_flush(acc64[0][1], Y); LDS_SCHED_BARRIER();                                                \
+    Y = syrk_chain(oa[1][0], ob[1][0], oa[1][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
+    syrk_flush(acc64[1][0], X); LDS_SCHED_BARRIER();                                                \
   }
 
   if (g.K % SBK) {
@@ -202,7 +187,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   // Slab kt is multiplied while slabs kt + 1 and kt + 2 are on their way.
 #define SYRK_STEP(S, NEXT, KT)                                                            \
   {                                                                                       \
-    if ((KT) + 1 < nk) { SYRK_WAIT_VM(PW); } else { SYRK_WAIT_VM(0); }                    \
+    if ((KT) + 1 < nk) { LDS_DMA_WAIT_VM(PW); } else { LDS_DMA_WAIT_VM(0); }                    \
     __builtin_amdgcn_s_barrier();                                                         \
     if ((KT) + 2 < nk) issue(NEXT, ((KT) + 2) * SBK);                                     \
     if ((KT) < nk) SYRK_SLAB_PRODUCT(S);                                                  \
@@ -213,7 +198,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
     SYRK_STEP(2, 1, kt + 2);
   }
   syrk_flush(acc64[1][1], Y);
-  SYRK_WAIT_VM(0);
+  LDS_DMA_WAIT_VM(0);
   __syncthreads();                               // the slabs are dead: the region becomes Ts
 
   // Epilogue.  The lower-triangular tile is stored from the accumulators (rows of 32
