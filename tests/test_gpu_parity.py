@@ -743,6 +743,27 @@ def test_tensor_parameters_bf16_gradients_and_larger_blocks():
         p.check(t)
 
 
+def test_tensor_edge_cases():
+    """Middle and last dimensions above 128 (blocked eigensolver and multi-tile products on those
+    factors, rows of 17952 elements for the elementwise kernels), dimensions of 1 and 2, a zero
+    gradient on one tensor block (its step must be exactly zero, not NaN), momentum off."""
+    import torch
+    say("case tensor edge cases")
+    shapes = [(4, 136, 132), (3, 2, 5), (7, 1, 9, 1), (6, 6, 6), (2, 140, 3)]
+    p = TensorPair(shapes, 136, 1.0, 1, mu=0.0)
+    # an order-3 tensor, two fully merged ones, a matrix, and an order-3 tensor cut along its middle
+    assert p.ora.view_shapes == [(4, 136, 132), (30,), (63,), (36, 6), (2, 140, 3)]
+    assert sorted(p.ora.tblocks) == [0, 1, 2, 4] and len(p.ora.tblocks[4]) == 2
+    for t in range(2):
+        g = wl.gaussian_grads(shapes, 36, t, 1e-2)
+        g[1][:] = 0.0
+        p.step(g, 0.1, t)
+        p.check(t)
+    assert torch.equal(p.w_gpu[1].cpu(), torch.from_numpy(wl.init_params(shapes, 0)[1]))
+    for w in p.w_gpu:
+        assert torch.isfinite(w).all()
+
+
 def test_newton_failures_fall_back_to_the_eigendecomposition():
     """Guard of Sec. 3.2.3: thin blocks give rank-deficient factors whose condition number
     (lambda_max / 1e-12) float32 cannot iterate on; the optimizer hands exactly those to the
