@@ -126,12 +126,15 @@ typedef struct {
  * parameter is cut into ceil(rows/b) x ceil(cols/b) blocks, all b x b except
  * in the last block row / column.  Blocks of equal (m, n) form a bucket and
  * are numbered (slot) in parameter order, row-major inside a parameter.
- * Writes up to `cap` rows of 10 int64 {param, row0, col0, m, n, bucket, slot, flags, s3, d3}
+ * Writes up to `cap` rows of 12 int64
+ * {param, row0, col0, m, n, bucket, slot, flags, s3, d3, s4, d4}
  * into `table` (host, may be NULL when cap == 0) and the total number of
  * blocks / buckets into *n_blocks / *n_buckets (host, may be NULL).
- * A block of a tensor parameter (flags bit 2) starts at (row0, col0, s3) of the merged
- * shape and measures m x n x d3 (n = d3 = 1 for a fully merged one); matrix blocks have
- * s3 = 0, d3 = 1.  Tensor blocks are numbered in row-major order of their block indices.
+ * A block of a tensor parameter (flags bit 2, and the order 1, 3 or 4 of the merged tensor
+ * in flags bits 4..6) starts at (row0, col0, s3, s4) of the merged
+ * shape and measures m x n x d3 x d4 (sizes 1 for the dimensions it does not have); matrix
+ * blocks have s3 = s4 = 0, d3 = d4 = 1.  Tensor blocks are numbered in row-major order of
+ * their block indices.
  * Under SHAMPOO_LARGE_DIM_DIAGONAL a parameter with a dimension above b is one row
  * (m, n = its shape) with flags bit 0 / bit 1 set where the left / right factor is
  * diagonal; under SHAMPOO_LARGE_DIM_ADAGRAD such a parameter has no row (it is handled
@@ -170,7 +173,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
  *   M <- mu M + P ; W <- W + lr M  (Nesterov: lr (mu M + P))          (Sec. 3.1.3)
  * A block of a tensor parameter has one factor per dimension k,
  *   L_k <- beta2 L_k + (1-beta2) G_(k) G_(k)^T  (G_(k): mode-k unfolding),
- * and P_shampoo = G x_1 Lbar_1 x_2 Lbar_2 x_3 Lbar_3 (mode products, Sec. 2.3); the
+ * and P_shampoo = G x_1 Lbar_1 x_2 Lbar_2 ... x_w Lbar_w (mode products, Sec. 2.3); the
  * other lines apply unchanged.
  * params: host array [n_params] of device pointers, float32, contiguous
  *         row-major with the shapes given at create; updated in place.
@@ -194,12 +197,14 @@ enum {
   SHAMPOO_GET_PSH = 6,    /* m x n: last Lbar G Rbar                         */
   SHAMPOO_GET_NORMS = 7,  /* 2 floats: ||P_graft||_F^2, ||P_shampoo||_F^2 of the last step */
   SHAMPOO_GET_GF = 8,     /* same shape as A: filtered gradient; error if beta1 == 0       */
-  SHAMPOO_GET_L2 = 9,     /* tensor blocks only: the factor of the middle dimension, n x n   */
-  SHAMPOO_GET_L2INV = 10  /* and its root                                                    */
+  SHAMPOO_GET_L2 = 9,     /* tensor blocks of order 3 or 4: the factor of the second dimension, n x n */
+  SHAMPOO_GET_L2INV = 10, /* and its root                                                    */
+  SHAMPOO_GET_L3 = 11,    /* tensor blocks of order 4: the factor of the third dimension, d3 x d3 */
+  SHAMPOO_GET_L3INV = 12  /* and its root                                                    */
 };
-/* For a block m x n x d3 of a tensor parameter: L / LINV belong to the first dimension
- * (m x m), L2 / L2INV to the second (n x n), R / RINV to the last (d3 x d3); A, M, PSH, GF
- * are the dense m x n x d3 block. */
+/* For a block m x n x d3 (x d4) of a tensor parameter: L / LINV belong to the first dimension
+ * (m x m), R / RINV to the last one, L2 / L2INV and L3 / L3INV to those between; A, M, PSH,
+ * GF are the dense block. */
 
 /*
  * Copy one piece of state of block `block` (row-major index inside parameter

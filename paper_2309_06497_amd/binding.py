@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libshampoo.so")
 
 GRAD_F32, GRAD_BF16 = 0, 1
-GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF, GET_L2, GET_L2INV = range(11)
+GET_L, GET_R, GET_LINV, GET_RINV, GET_A, GET_M, GET_PSH, GET_NORMS, GET_GF, GET_L2, GET_L2INV, GET_L3, GET_L3INV = range(13)
 MAX_NDIM = 4
 GRAFT_ADAGRAD, GRAFT_SGD, GRAFT_RMSPROP, GRAFT_ADAM = 0, 1, 2, 3
 ROOT_EIGH, ROOT_NEWTON = 0, 1
@@ -143,11 +143,11 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
 
 
 def shampoo_plan(cfg):
-    """Returns (table int64 [n_blocks, 10], n_buckets); rows are
-    {param, row0, col0, m, n, bucket, slot, flags, s3, d3}.  Host only."""
+    """Returns (table int64 [n_blocks, 12], n_buckets); rows are
+    {param, row0, col0, m, n, bucket, slot, flags, s3, d3, s4, d4}.  Host only."""
     nb, nk = ctypes.c_int64(0), ctypes.c_int64(0)
     _check(lib().shampoo_plan(ctypes.byref(cfg), None, 0, ctypes.byref(nb), ctypes.byref(nk)))
-    table = np.zeros((max(nb.value, 1), 10), dtype=np.int64)
+    table = np.zeros((max(nb.value, 1), 12), dtype=np.int64)
     _check(lib().shampoo_plan(ctypes.byref(cfg), table.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
                               nb.value, ctypes.byref(nb), ctypes.byref(nk)))
     return table[:nb.value], nk.value
@@ -211,11 +211,13 @@ class Shampoo:
         else:
             if not 0 <= block < len(rows):
                 raise ShampooError(-2)
-            m, n, flags, d3 = int(rows[block, 3]), int(rows[block, 4]), int(rows[block, 7]), int(rows[block, 9])
-            if flags & 4:        # a block of a tensor parameter: m x n x d3, one factor per dimension
-                blk = (m, n, d3)
+            m, n, flags, d3, d4 = (int(rows[block, k]) for k in (3, 4, 7, 9, 11))
+            if flags & 4:        # a block of a tensor parameter: m x n x d3 (x d4), one factor per dimension
+                blk = (m, n, d3, d4) if (flags >> 4) == 4 else (m, n, d3)
+                dl = blk[-1]     # R / RINV belong to the last dimension
                 shape = {GET_L: (m, m), GET_LINV: (m, m), GET_L2: (n, n), GET_L2INV: (n, n),
-                         GET_R: (d3, d3), GET_RINV: (d3, d3), GET_A: blk, GET_M: blk, GET_PSH: blk,
+                         GET_L3: (d3, d3), GET_L3INV: (d3, d3),
+                         GET_R: (dl, dl), GET_RINV: (dl, dl), GET_A: blk, GET_M: blk, GET_PSH: blk,
                          GET_NORMS: (2,), GET_GF: blk}[which]
             else:
                 lshape = (m,) if flags & 1 else (m, m)

@@ -51,10 +51,10 @@ struct Block {
   int64_t row0, col0;
   int32_t m, n;
   int32_t bucket, slot;
-  // tensor blocks (Sec. 2.3): start and size along the third dimension, and where the block
-  // sits in the block-contiguous copy of the parameter that the kernels work on
-  int64_t s3 = 0;
-  int32_t d3 = 1;
+  // tensor blocks (Sec. 2.3): start and size along the third and fourth dimension, and where
+  // the block sits in the block-contiguous copy of the parameter that the kernels work on
+  int64_t s3 = 0, s4 = 0;
+  int32_t d3 = 1, d4 = 1;
   int64_t voff = 0;
   bool tensor = false;
 };
@@ -63,9 +63,9 @@ enum { P_VECTOR = 0, P_MATRIX = 1, P_TENSOR = 2 };
 struct PShape {
   int kind = P_VECTOR;
   int64_t rows = 1, cols = 1;   // P_MATRIX: the (merged) shape; P_VECTOR: rows = length
-  int64_t d[3] = {1, 1, 1};     // P_TENSOR: the merged dimensions
-  int modes = 0;                // P_TENSOR: 3, or 1 when everything merged into one dimension
-  int64_t elems() const { return kind == P_TENSOR ? d[0] * d[1] * d[2] : rows * cols; }
+  int64_t d[4] = {1, 1, 1, 1};  // P_TENSOR: the merged dimensions
+  int modes = 0;                // P_TENSOR: 3 or 4, or 1 when everything merged into one dimension
+  int64_t elems() const { return kind == P_TENSOR ? d[0] * d[1] * d[2] * d[3] : rows * cols; }
 };
 struct Bucket {
   int32_t m, n, count;
@@ -82,15 +82,16 @@ struct Bucket {
   // bucket holds whole parameters, one per slot
   bool diagL = false, diagR = false;
   int32_t col_segs = 1, rows_per_seg = 0;   // row segments of the column-sum reduction
-  // tensor blocks d1 x d2 x d3: the elementwise kernels see them as m x n = d1 x (d2 d3)
+  // tensor blocks d1 x d2 x d3 (x d4): the elementwise kernels see them as m x n = d1 x (d2 d3 d4)
   // matrices inside a block-contiguous copy of the parameter; L belongs to the first
-  // dimension, L2 to the second, R to the third
+  // dimension, R to the last, mid[0] (and mid[1] for order 4) to the ones between
   bool t3 = false;
-  int32_t d2 = 1, d3 = 1, modes = 0;
-  size_t off_L2 = 0, off_L2inv = 0, off_desc3 = 0;
-  int32_t split3 = 1;   // row ranges of the (d1 d2) x d3 unfolding whose Gram matrices are formed separately
+  int32_t td[4] = {1, 1, 1, 1}, modes = 0;
+  size_t off_mid[2] = {0, 0}, off_midinv[2] = {0, 0}, off_desc3 = 0;
+  int32_t split3 = 1;   // row ranges of the (N / d_last) x d_last unfolding whose Gram matrices are formed separately
   bool whole() const { return diagL || diagR; }
-  int32_t rdim() const { return t3 ? d3 : n; }
+  int32_t dlast() const { return modes > 1 ? td[modes - 1] : 1; }
+  int32_t rdim() const { return t3 ? dlast() : n; }
   size_t l_elems() const { return diagL ? (size_t)m : (size_t)m * m; }
   size_t r_elems() const { return diagR ? (size_t)n : (size_t)rdim() * rdim(); }
 };
@@ -106,7 +107,7 @@ struct Plan {
 };
 
 // Merging of small dimensions (Sec. 4.2.1) and the resulting kind of parameter.  Returns
-// SHAMPOO_OK, or the error for a shape that is out of range or merges to order 4.
+// SHAMPOO_OK, or the error for a shape that is out of range.
 int param_shape(const shampoo_config *c, int i, PShape &ps) {
   const int nd = c->ndim[i];
   if (nd < 1 || nd > SHAMPOO_MAX_NDIM) return SHAMPOO_ERR_SHAPE;
@@ -128,11 +129,14 @@ int param_shape(const shampoo_config *c, int i, PShape &ps) {
   }
   merged[cnt++] = cur;
   if (cnt == 2) { ps.kind = P_MATRIX; ps.rows = merged[0]; ps.cols = merged[1]; return SHAMPOO_OK; }
-  if (cnt > 3) return SHAMPOO_ERR_UNSUPPORTED;
   ps.kind = P_TENSOR;
   ps.modes = cnt;
   for (int k = 0; k < cnt; ++k) ps.d[k] = merged[k];
-  if (ps.d[0] * ps.d[1] * ps.d[2] > (int64_t)1 << 40) return SHAMPOO_ERR_UNSUPPORTED;
+  if ((double)ps.d[0] * (double)ps.d[1] * (double)ps.d[2] * (double)ps.d[3] > (double)((int64_t)1 << 40)) return SHAMPOO_ERR_UNSUPPORTED;
+  // one block is indexed with 32-bit products of its sizes
+  double block_elems = 1.0;
+  for (int k = 0; k < cnt; ++k) block_elems *= (double)std::min<int64_t>(ps.d[k], c->block_size);
+  if (block_elems > (double)(1 << 30)) return SHAMPOO_ERR_UNSUPPORTED;
   return SHAMPOO_OK;
 }
 
@@ -210,20 +214,20 @@ EwGeom make_geom(int m, int n) {
 
 void make_plan(const shampoo_config *c, Plan &p) {
   const int64_t b = c->block_size;
-  // (m, n, diagonal sides | tensor, d2, d3) -> bucket
-  std::map<std::tuple<int, int, int, int, int>, int> bucket_of;
+  // (m, n, diagonal sides | tensor, d2, d3, d4) -> bucket
+  std::map<std::tuple<int, int, int, int, int, int>, int> bucket_of;
   p.param_blocks.assign(c->n_params, {});
   p.param_state_offset.assign(c->n_params, 0);
   p.pshape.assign(c->n_params, PShape());
   int64_t off = 0;
-  auto bucket_for = [&](int m, int n, int flags, int d2, int d3, int modes) {
-    auto key = std::make_tuple(m, n, flags, d2, d3);
+  auto bucket_for = [&](int m, int n, int flags, int d2, int d3, int d4, int modes) {
+    auto key = std::make_tuple(m, n, flags, d2, d3, d4);
     auto it = bucket_of.find(key);
     if (it == bucket_of.end()) {
       Bucket bk{};
       bk.m = m; bk.n = n; bk.count = 0;
       bk.diagL = (flags & 1) != 0; bk.diagR = (flags & 2) != 0;
-      bk.t3 = (flags & 4) != 0; bk.d2 = d2; bk.d3 = d3; bk.modes = modes;
+      bk.t3 = (flags & 4) != 0; bk.td[0] = m; bk.td[1] = d2; bk.td[2] = d3; bk.td[3] = d4; bk.modes = modes;
       bucket_of[key] = (int)p.buckets.size();
       p.buckets.push_back(bk);
       it = bucket_of.find(key);
@@ -264,23 +268,26 @@ void make_plan(const shampoo_config *c, Plan &p) {
       // every dimension cut into pieces of at most b; blocks in row-major order of their
       // indices.  All pieces before the last one of a dimension are full, which gives the
       // offset of a block inside the block-contiguous copy in closed form.
-      const int64_t D1 = ps.d[0], D2 = ps.d[1], D3 = ps.d[2];
-      const int64_t k1n = (D1 + b - 1) / b, k2n = (D2 + b - 1) / b, k3n = (D3 + b - 1) / b;
+      const int64_t D1 = ps.d[0], D2 = ps.d[1], D3 = ps.d[2], D4 = ps.d[3];
+      const int64_t k1n = (D1 + b - 1) / b, k2n = (D2 + b - 1) / b, k3n = (D3 + b - 1) / b, k4n = (D4 + b - 1) / b;
       for (int64_t k1 = 0; k1 < k1n; ++k1)
         for (int64_t k2 = 0; k2 < k2n; ++k2)
-          for (int64_t k3 = 0; k3 < k3n; ++k3) {
-            Block blk;
-            blk.param = i; blk.tensor = true;
-            blk.row0 = k1 * b; blk.col0 = k2 * b; blk.s3 = k3 * b;
-            blk.m = (int32_t)std::min<int64_t>(b, D1 - blk.row0);
-            blk.n = (int32_t)std::min<int64_t>(b, D2 - blk.col0);
-            blk.d3 = (int32_t)std::min<int64_t>(b, D3 - blk.s3);
-            blk.voff = blk.row0 * D2 * D3 + (int64_t)blk.m * (blk.col0 * D3) + (int64_t)blk.m * blk.n * blk.s3;
-            blk.bucket = bucket_for(blk.m, blk.n * blk.d3, 4, blk.n, blk.d3, ps.modes);
-            blk.slot = p.buckets[blk.bucket].count++;
-            p.param_blocks[i].push_back((int32_t)p.blocks.size());
-            p.blocks.push_back(blk);
-          }
+          for (int64_t k3 = 0; k3 < k3n; ++k3)
+            for (int64_t k4 = 0; k4 < k4n; ++k4) {
+              Block blk;
+              blk.param = i; blk.tensor = true;
+              blk.row0 = k1 * b; blk.col0 = k2 * b; blk.s3 = k3 * b; blk.s4 = k4 * b;
+              blk.m = (int32_t)std::min<int64_t>(b, D1 - blk.row0);
+              blk.n = (int32_t)std::min<int64_t>(b, D2 - blk.col0);
+              blk.d3 = (int32_t)std::min<int64_t>(b, D3 - blk.s3);
+              blk.d4 = (int32_t)std::min<int64_t>(b, D4 - blk.s4);
+              blk.voff = blk.row0 * D2 * D3 * D4 + (int64_t)blk.m * (blk.col0 * D3 * D4) +
+                         (int64_t)blk.m * blk.n * (blk.s3 * D4) + (int64_t)blk.m * blk.n * blk.d3 * blk.s4;
+              blk.bucket = bucket_for(blk.m, blk.n * blk.d3 * blk.d4, 4, blk.n, blk.d3, blk.d4, ps.modes);
+              blk.slot = p.buckets[blk.bucket].count++;
+              p.param_blocks[i].push_back((int32_t)p.blocks.size());
+              p.blocks.push_back(blk);
+            }
       off += (elems + 3) / 4 * 4;
       continue;
     }
@@ -297,7 +304,7 @@ void make_plan(const shampoo_config *c, Plan &p) {
         blk.col0 = bj * bb;
         blk.m = (int32_t)std::min<int64_t>(bb, rows - blk.row0);
         blk.n = (int32_t)std::min<int64_t>(bb, cols - blk.col0);
-        blk.bucket = bucket_for(blk.m, blk.n, flags, 1, 1, 0);
+        blk.bucket = bucket_for(blk.m, blk.n, flags, 1, 1, 1, 0);
         blk.slot = p.buckets[blk.bucket].count++;
         p.param_blocks[i].push_back((int32_t)p.blocks.size());
         p.blocks.push_back(blk);
@@ -313,11 +320,12 @@ void make_plan(const shampoo_config *c, Plan &p) {
     if (ld % 8 != 0 || (blk.row0 * ld + blk.col0) % 8 != 0) p.buckets[blk.bucket].bf16_mfma = false;
   }
   for (auto &bk : p.buckets) {
-    if (bk.t3 && bk.modes == 3) {
-      // the factor of the last dimension sums over d1 d2 rows into one small tile per block:
-      // split the rows (whole slices of the first index) so that the launch fills the GPU
+    if (bk.t3 && bk.modes >= 3) {
+      // the factor of the last dimension sums over N / d_last rows into one small tile per
+      // block: split the rows (whole slices of the first index) so that the launch fills the GPU
+      const int64_t inner = (int64_t)bk.n / bk.dlast();   // rows of the unfolding per slice of the first index
       for (int sdiv = 1; sdiv <= std::min(bk.m, 64); ++sdiv)
-        if (bk.m % sdiv == 0 && (int64_t)(bk.m / sdiv) * bk.d2 >= 64 && (int64_t)sdiv * bk.d3 <= (int64_t)bk.m * bk.d2 &&
+        if (bk.m % sdiv == 0 && (int64_t)(bk.m / sdiv) * inner >= 64 && (int64_t)sdiv * bk.dlast() <= (int64_t)bk.m * inner &&
             (int64_t)bk.count * sdiv <= 1 << 20)
           bk.split3 = sdiv;
     }
@@ -639,7 +647,7 @@ struct shampoo_opt {
   int64_t n_small = 0;     // blocks of at most 128 x 128 (single-workgroup step kernel)
   bool use_l2 = false, use_b1 = false;
   size_t off_A = 0, off_M = 0, off_T = 0, off_wtab = 0, off_gtab = 0, off_diag = 0, off_count = 0, off_eig = 0;
-  std::vector<EigLayout> eig_L, eig_R, eig_2;   // per bucket (eig_2: middle dimension of tensor blocks)
+  std::vector<EigLayout> eig_L, eig_R, eig_mid[2];   // per bucket (eig_mid: the middle dimensions of tensor blocks)
   // tensor parameters: block-contiguous copies of the gradient and the parameter (byte offsets
   // into the workspace, 0 for other parameters), and a second scratch array the size of T
   std::vector<size_t> off_Gb, off_Wb;
@@ -670,7 +678,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
   const size_t offGftab = take((size_t)c->n_params * sizeof(void *));
   const size_t offPrep = (use_l2 || use_b1) ? take(std::max<size_t>(1, p.prep_chunks.size()) * sizeof(DiagChunk)) : 0;
   size_t t_elems = 0, t2_elems = 0, eig_bytes = 0, max_count = 1;
-  std::vector<EigLayout> eL, eR, e2;
+  std::vector<EigLayout> eL, eR, eM[2];
   for (auto &b : p.buckets) {
     const size_t B = b.count, m = b.m, n = b.n;
     b.off_L = take(B * b.l_elems() * 4);
@@ -678,8 +686,10 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     b.off_Linv = take(B * b.l_elems() * 4);
     b.off_Rinv = take(B * b.r_elems() * 4);
     if (b.t3) {
-      b.off_L2 = take(B * (size_t)b.d2 * b.d2 * 4);
-      b.off_L2inv = take(B * (size_t)b.d2 * b.d2 * 4);
+      for (int k = 0; k + 2 < b.modes; ++k) {
+        b.off_mid[k] = take(B * (size_t)b.td[k + 1] * b.td[k + 1] * 4);
+        b.off_midinv[k] = take(B * (size_t)b.td[k + 1] * b.td[k + 1] * 4);
+      }
       b.off_desc3 = take(B * (size_t)b.split3 * sizeof(BlockDesc));
       t2_elems = std::max(t2_elems, B * m * n);
     }
@@ -697,7 +707,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     // partial sums of ||P_shampoo||^2: one per tile of the last product (tensor blocks: the
     // (d2 d1) x d3 product of the third dimension) or per chunk of an elementwise pass
     size_t ssh_parts = std::max<size_t>((size_t)b.tiles_m * b.tiles_n, (size_t)b.geom.chunks);
-    if (b.t3) ssh_parts = std::max(ssh_parts, (size_t)((b.m * b.d2 + BM - 1) / BM) * ((b.d3 + BN - 1) / BN));
+    if (b.t3) ssh_parts = std::max(ssh_parts, (size_t)((m * n / b.dlast() + BM - 1) / BM) * ((b.dlast() + BN - 1) / BN));
     b.off_sshp = take(B * ssh_parts * 4);
     b.off_scale = take(B * 4);
     b.off_norms = take(B * 8);
@@ -707,12 +717,13 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     const int em = b.diagL ? 1 : b.m, en = b.diagR ? 1 : b.rdim();
     eL.push_back(eig_layout(em, b.count));
     eR.push_back(eig_layout(en, b.count));
-    e2.push_back(eig_layout(b.d2, b.count));
+    for (int k = 0; k < 2; ++k) eM[k].push_back(eig_layout(b.td[k + 1], b.count));
     // under coupled Newton the eigensolver is the fallback of the guard (Sec. 3.2.3): room for both
     if (c->root_method == SHAMPOO_ROOT_NEWTON)
-      eig_bytes = std::max(eig_bytes, std::max(newton_layout(em, b.count).bytes,
-                                               std::max(newton_layout(en, b.count).bytes, newton_layout(b.d2, b.count).bytes)));
-    eig_bytes = std::max(eig_bytes, std::max(eL.back().bytes, std::max(eR.back().bytes, e2.back().bytes)));
+      eig_bytes = std::max(eig_bytes, std::max(std::max(newton_layout(em, b.count).bytes, newton_layout(en, b.count).bytes),
+                                               std::max(newton_layout(b.td[1], b.count).bytes, newton_layout(b.td[2], b.count).bytes)));
+    eig_bytes = std::max(eig_bytes, std::max(std::max(eL.back().bytes, eR.back().bytes),
+                                             std::max(eM[0].back().bytes, eM[1].back().bytes)));
     max_count = std::max(max_count, (size_t)b.count);
   }
   const size_t offT = take(t_elems * 4);
@@ -741,7 +752,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     o->use_l2 = use_l2; o->use_b1 = use_b1; o->off_wtab = offW; o->off_gtab = offG;
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
     o->off_small = offSmall; o->n_small = n_small;
-    o->eig_L = eL; o->eig_R = eR; o->eig_2 = e2;
+    o->eig_L = eL; o->eig_R = eR; o->eig_mid[0] = eM[0]; o->eig_mid[1] = eM[1];
     o->off_nfail = offNf;
     o->off_T2 = offT2; o->off_Gb = offGb; o->off_Wb = offWb; o->has_tensor = has_tensor;
   }
@@ -853,14 +864,15 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   auto tensor_copy_args = [&](int i) {
     const PShape &ps = p.pshape[i];
     TensorCopyArgs ta{};
-    ta.D1 = ps.d[0]; ta.D2 = ps.d[1]; ta.D3 = ps.d[2]; ta.b = c.block_size;
+    ta.D1 = ps.d[0]; ta.D2 = ps.d[1]; ta.D3 = ps.d[2]; ta.D4 = ps.d[3]; ta.b = c.block_size;
     ta.k2n = (int32_t)((ps.d[1] + c.block_size - 1) / c.block_size);
     ta.k3n = (int32_t)((ps.d[2] + c.block_size - 1) / c.block_size);
+    ta.k4n = (int32_t)((ps.d[3] + c.block_size - 1) / c.block_size);
     return ta;
   };
   auto tensor_copy_grid = [&](int i) {
     const int64_t per = std::min<int64_t>(c.block_size, p.pshape[i].d[0]) * std::min<int64_t>(c.block_size, p.pshape[i].d[1]) *
-                        std::min<int64_t>(c.block_size, p.pshape[i].d[2]);
+                        std::min<int64_t>(c.block_size, p.pshape[i].d[2]) * std::min<int64_t>(c.block_size, p.pshape[i].d[3]);
     return dim3((unsigned)p.param_blocks[i].size(), (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, (per + 2047) / 2048)));
   };
   if (o->has_tensor) {
@@ -953,40 +965,47 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         if (rc) return rc;
       }
       if (b.t3) {
-        // Above: L_1 <- beta L_1 + alpha G_(1) G_(1)^T, the block being d1 x (d2 d3).  The other
-        // dimensions exist only for a tensor of order three.
-        if (b.modes == 3) {
-          // L_3 <- beta L_3 + alpha G_(3) G_(3)^T: the block as (d1 d2) x d3, read "rows along k".
-          // Its rows are cut into split3 ranges, each a batch entry that leaves its Gram matrix
-          // in scratch; gram_reduce_kernel adds them up in float64 and applies the moving average.
+        // Above: L_1 <- beta L_1 + alpha G_(1) G_(1)^T, the block being d1 x (d2 d3 d4).  The other
+        // dimensions exist only for a tensor of order three or four.
+        if (b.modes >= 3) {
+          // Last dimension: the block as (N / d_last) x d_last, read "rows along k".  Its rows
+          // are cut into split3 ranges, each a batch entry that leaves its Gram matrix in
+          // scratch; gram_reduce_kernel adds them up in float64 and applies the moving average.
           float *T2 = reinterpret_cast<float *>(ws + o->off_T2);
+          const int dl = b.dlast(), inner = b.n / dl;
           g.desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc3);
-          g.c = T2; g.c_batch_stride = (int64_t)b.d3 * b.d3; g.ldc = b.d3;
-          g.M = b.d3; g.N = b.d3; g.K = (b.m / b.split3) * b.d2;
+          g.c = T2; g.c_batch_stride = (int64_t)dl * dl; g.ldc = dl;
+          g.M = dl; g.N = dl; g.K = (b.m / b.split3) * inner;
           g.alpha = 1.f; g.beta = 0.f; g.alpha_d = 1.0; g.beta_d = 0.0; g.batch = b.count * b.split3;
-          g.tiles_m = g.tiles_n = (b.d3 + BM - 1) / BM; g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
+          g.tiles_m = g.tiles_n = (dl + BM - 1) / BM; g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
           rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
           if (rc) return rc;
           GramReduceArgs gr;
-          gr.partial = T2; gr.factor = reinterpret_cast<float *>(ws + b.off_R); gr.d = b.d3; gr.splits = b.split3;
+          gr.partial = T2; gr.factor = reinterpret_cast<float *>(ws + b.off_R); gr.d = dl; gr.splits = b.split3;
           gr.alpha = alpha; gr.beta = beta;
-          hipLaunchKernelGGL(gram_reduce_kernel, dim3((b.d3 * b.d3 + 255) / 256, b.count), dim3(256), 0, s, gr);
+          hipLaunchKernelGGL(gram_reduce_kernel, dim3((dl * dl + 255) / 256, b.count), dim3(256), 0, s, gr);
           HIP_TRY(hipGetLastError());
-          // L_2 <- beta L_2 + alpha G_(2) G_(2)^T: the block with its first two indices swapped, d2 x (d1 d3)
-          PermuteArgs pm{};
-          pm.desc = desc; pm.table = gs_tab; pm.dst = T2; pm.d1 = b.m; pm.d2 = b.d2; pm.d3 = b.d3;
-          const unsigned pchunks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, ((int64_t)b.m * b.n + 2047) / 2048));
-          hipLaunchKernelGGL(permute_12_kernel<GS>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
-          HIP_TRY(hipGetLastError());
-          GemmArgs h{};
-          h.a.base = T2; h.a.batch_stride = (int64_t)b.m * b.n; h.a.ld = b.m * b.d3;
-          h.b = h.a;
-          h.alpha = (float)alpha; h.beta = (float)beta; h.alpha_d = alpha; h.beta_d = beta; h.batch = b.count;
-          h.c = reinterpret_cast<float *>(ws + b.off_L2); h.c_batch_stride = (int64_t)b.d2 * b.d2; h.ldc = b.d2;
-          h.M = b.d2; h.N = b.d2; h.K = b.m * b.d3;
-          h.tiles_m = h.tiles_n = (b.d2 + BM - 1) / BM; h.tiles = h.tiles_m * (h.tiles_m + 1) / 2;
-          rc = launch_gemm<K_CONTIG, K_CONTIG, float, float, EPI_SYRK, false, FLUSH>(h, s);
-          if (rc) return rc;
+          // Middle dimensions k: the block as pre x d_k x post with its first two indices swapped,
+          // d_k x (pre post)
+          int pre = b.m;
+          for (int k = 1; k + 1 < b.modes; ++k) {
+            const int dk = b.td[k], post = b.n / (pre / b.m * dk);
+            PermuteArgs pm{};
+            pm.desc = desc; pm.table = gs_tab; pm.dst = T2; pm.d1 = pre; pm.d2 = dk; pm.d3 = post;
+            const unsigned pchunks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, ((int64_t)b.m * b.n + 2047) / 2048));
+            hipLaunchKernelGGL(permute_12_kernel<GS>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
+            HIP_TRY(hipGetLastError());
+            GemmArgs h{};
+            h.a.base = T2; h.a.batch_stride = (int64_t)b.m * b.n; h.a.ld = pre * post;
+            h.b = h.a;
+            h.alpha = (float)alpha; h.beta = (float)beta; h.alpha_d = alpha; h.beta_d = beta; h.batch = b.count;
+            h.c = reinterpret_cast<float *>(ws + b.off_mid[k - 1]); h.c_batch_stride = (int64_t)dk * dk; h.ldc = dk;
+            h.M = dk; h.N = dk; h.K = pre * post;
+            h.tiles_m = h.tiles_n = (dk + BM - 1) / BM; h.tiles = h.tiles_m * (h.tiles_m + 1) / 2;
+            rc = launch_gemm<K_CONTIG, K_CONTIG, float, float, EPI_SYRK, false, FLUSH>(h, s);
+            if (rc) return rc;
+            pre *= dk;
+          }
         }
       } else if (b.diagR) {
         // r_j <- beta r_j + alpha sum_i G_ij^2, rows cut into segments whose partial sums go through T
@@ -1044,9 +1063,13 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       if (b.t3) {
         // one root per dimension, exponent 2 r / w (Sec. 2.3: "root 2w")
         const float rw = 2.f * c.root_exponent / (float)b.modes;
-        const int dims[3] = {b.m, b.d2, b.d3};
-        const size_t fac[3] = {b.off_L, b.off_L2, b.off_R}, inv[3] = {b.off_Linv, b.off_L2inv, b.off_Rinv};
-        const EigLayout *lay[3] = {&o->eig_L[i], &o->eig_2[i], &o->eig_R[i]};
+        int dims[4]; size_t fac[4], inv[4]; const EigLayout *lay[4];
+        for (int k = 0; k < b.modes; ++k) {
+          dims[k] = b.td[k];
+          if (k == 0) { fac[k] = b.off_L; inv[k] = b.off_Linv; lay[k] = &o->eig_L[i]; }
+          else if (k == b.modes - 1) { fac[k] = b.off_R; inv[k] = b.off_Rinv; lay[k] = &o->eig_R[i]; }
+          else { fac[k] = b.off_mid[k - 1]; inv[k] = b.off_midinv[k - 1]; lay[k] = &o->eig_mid[k - 1][i]; }
+        }
         for (int k = 0; k < b.modes; ++k) {
           if (c.root_method == SHAMPOO_ROOT_NEWTON) {
             rc = newton_root_guarded(o, reinterpret_cast<float *>(ws + fac[k]), dims[k], b.count, rw, c2,
@@ -1088,9 +1111,10 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     if (fused(b)) continue;
     int ssh_count = b.tiles_m * b.tiles_n;
     if (use_shampoo && b.t3) {
-      // P = G x_1 Lbar_1 x_2 Lbar_2 x_3 Lbar_3 (Sec. 2.3).  Mode 1 on the block as d1 x (d2 d3);
-      // then the first two indices are swapped so that mode 2 is a plain product on
-      // d2 x (d1 d3) and mode 3 one on (d2 d1) x d3; the result is swapped back.
+      // P = G x_1 Lbar_1 x_2 Lbar_2 ... x_w Lbar_w (Sec. 2.3).  Mode 1 on the block as
+      // d1 x (d2 ... dw); a middle mode k on the block as pre x d_k x post: its first two
+      // indices are swapped, the product is the plain one on d_k x (pre post), and they are
+      // swapped back; the last mode on the block as (N / d_w) x d_w, with the norm epilogue.
       StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
       float *T2 = reinterpret_cast<float *>(ws + o->off_T2);
       float *ssh = reinterpret_cast<float *>(ws + b.off_sshp);
@@ -1106,35 +1130,43 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE_NORM, false>(g, s);
         if (rc) return rc;
       } else {
-        g.c = T;
+        float *cur = T, *other = T2;
+        g.c = cur;
         rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, GD, EPI_STORE, false>(g, s);
         if (rc) return rc;
         const unsigned pchunks = (unsigned)std::max<int64_t>(1, std::min<int64_t>(64, (mn + 2047) / 2048));
-        PermuteArgs pm{};
-        pm.src = T; pm.dst = T2; pm.d1 = b.m; pm.d2 = b.d2; pm.d3 = b.d3;
-        hipLaunchKernelGGL(permute_12_kernel<float>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
-        HIP_TRY(hipGetLastError());
-        GemmArgs h{};
-        h.a.base = ws + b.off_L2inv; h.a.batch_stride = (int64_t)b.d2 * b.d2; h.a.ld = b.d2;
-        h.b.base = T2; h.b.batch_stride = mn; h.b.ld = b.m * b.d3;
-        h.c = T; h.c_batch_stride = mn; h.ldc = b.m * b.d3;
-        h.M = b.d2; h.N = b.m * b.d3; h.K = b.d2; h.alpha = 1.f; h.beta = 0.f;
-        h.tiles_m = (h.M + BM - 1) / BM; h.tiles_n = (h.N + BN - 1) / BN; h.tiles = h.tiles_m * h.tiles_n; h.batch = b.count;
-        rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_STORE, false>(h, s);
-        if (rc) return rc;
+        int pre = b.m;
+        for (int k = 1; k + 1 < b.modes; ++k) {
+          const int dk = b.td[k], post = (int)(mn / ((int64_t)pre * dk));
+          PermuteArgs pm{};
+          pm.src = cur; pm.dst = other; pm.d1 = pre; pm.d2 = dk; pm.d3 = post;
+          hipLaunchKernelGGL(permute_12_kernel<float>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
+          HIP_TRY(hipGetLastError());
+          GemmArgs h{};
+          h.a.base = ws + b.off_midinv[k - 1]; h.a.batch_stride = (int64_t)dk * dk; h.a.ld = dk;
+          h.b.base = other; h.b.batch_stride = mn; h.b.ld = pre * post;
+          h.c = cur; h.c_batch_stride = mn; h.ldc = pre * post;
+          h.M = dk; h.N = pre * post; h.K = dk; h.alpha = 1.f; h.beta = 0.f;
+          h.tiles_m = (h.M + BM - 1) / BM; h.tiles_n = (h.N + BN - 1) / BN; h.tiles = h.tiles_m * h.tiles_n; h.batch = b.count;
+          rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_STORE, false>(h, s);
+          if (rc) return rc;
+          pm.src = cur; pm.dst = other; pm.d1 = dk; pm.d2 = pre; pm.d3 = post;
+          hipLaunchKernelGGL(permute_12_kernel<float>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
+          HIP_TRY(hipGetLastError());
+          std::swap(cur, other);
+          pre *= dk;
+        }
+        const int dl = b.dlast();
         GemmArgs q{};
-        q.a.base = T; q.a.batch_stride = mn; q.a.ld = b.d3;
-        q.b.base = ws + b.off_Rinv; q.b.batch_stride = (int64_t)b.d3 * b.d3; q.b.ld = b.d3;
-        q.c = T2; q.c_batch_stride = mn; q.ldc = b.d3;
-        q.M = b.d2 * b.m; q.N = b.d3; q.K = b.d3; q.alpha = 1.f; q.beta = 0.f;
+        q.a.base = cur; q.a.batch_stride = mn; q.a.ld = dl;
+        q.b.base = ws + b.off_Rinv; q.b.batch_stride = (int64_t)dl * dl; q.b.ld = dl;
+        q.c = P; q.c_batch_stride = mn; q.ldc = dl;
+        q.M = (int)(mn / dl); q.N = dl; q.K = dl; q.alpha = 1.f; q.beta = 0.f;
         q.tiles_m = (q.M + BM - 1) / BM; q.tiles_n = (q.N + BN - 1) / BN; q.tiles = q.tiles_m * q.tiles_n; q.batch = b.count;
         q.norm_partial = ssh;
         rc = launch_gemm<K_CONTIG, ROW_CONTIG, float, float, EPI_STORE_NORM, false>(q, s);
         if (rc) return rc;
         ssh_count = q.tiles;
-        pm.src = T2; pm.dst = P; pm.d1 = b.d2; pm.d2 = b.m; pm.d3 = b.d3;
-        hipLaunchKernelGGL(permute_12_kernel<float>, dim3(pchunks, b.count), dim3(256), 0, s, pm);
-        HIP_TRY(hipGetLastError());
       }
     } else if (use_shampoo && b.whole()) {
       // diagonal Shampoo: a diagonalised side scales rows / columns instead of multiplying
@@ -1298,11 +1330,11 @@ int shampoo_plan(const shampoo_config *cfg, int64_t *table, int64_t cap, int64_t
   const int64_t cnt = std::min<int64_t>(cap, (int64_t)p.blocks.size());
   for (int64_t i = 0; i < cnt; ++i) {
     const Block &b = p.blocks[i];
-    int64_t *row = table + 10 * i;
+    int64_t *row = table + 12 * i;
     row[0] = b.param; row[1] = b.row0; row[2] = b.col0; row[3] = b.m; row[4] = b.n;
     row[5] = b.bucket; row[6] = b.slot;
-    row[7] = (p.buckets[b.bucket].diagL ? 1 : 0) | (p.buckets[b.bucket].diagR ? 2 : 0) | (b.tensor ? 4 : 0);
-    row[8] = b.s3; row[9] = b.d3;
+    row[7] = (p.buckets[b.bucket].diagL ? 1 : 0) | (p.buckets[b.bucket].diagR ? 2 : 0) | (b.tensor ? 4 | (p.buckets[b.bucket].modes << 4) : 0);
+    row[8] = b.s3; row[9] = b.d3; row[10] = b.s4; row[11] = b.d4;
   }
   return SHAMPOO_OK;
 }
@@ -1373,15 +1405,15 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
     if (b.tensor) {
       // a block of the block-contiguous copy, as a d1 x (d2 d3) matrix; the second descriptor
       // shows the same memory as the (d1 d2) x d3 matrix of the third dimension
-      d.ld = b.n * b.d3;
+      d.ld = b.n * b.d3 * b.d4;
       d.offset = b.voff;
       d.state_offset = p.param_state_offset[b.param] + d.offset;
       // (one entry per row range of the split Gram product, see split3)
       const int sp = p.buckets[b.bucket].split3;
       for (int k = 0; k < sp; ++k) {
         BlockDesc d3 = d;
-        d3.ld = b.d3;
-        d3.offset = b.voff + (int64_t)k * (b.m / sp) * b.n * b.d3;
+        d3.ld = p.buckets[b.bucket].dlast();
+        d3.offset = b.voff + (int64_t)k * (b.m / sp) * d.ld;
         descs3[b.bucket][(size_t)b.slot * sp + k] = d3;
       }
     } else {
@@ -1399,10 +1431,12 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_P), 0.f, B * b.m * b.n, s))) return fail(rc);
     if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_norms), 0.f, B * 2, s))) return fail(rc);
     if (b.t3) {
-      const int64_t t2 = B * b.d2 * b.d2;
-      if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_L2), 0.f, t2, s))) return fail(rc);
-      hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((t2 + 255) / 256)), dim3(256), 0, s,
-                         reinterpret_cast<float *>(o->ws + b.off_L2inv), b.d2, t2);
+      for (int k = 0; k + 2 < b.modes; ++k) {
+        const int64_t t2 = B * b.td[k + 1] * b.td[k + 1];
+        if ((rc = launch_fill(reinterpret_cast<float *>(o->ws + b.off_mid[k]), 0.f, t2, s))) return fail(rc);
+        hipLaunchKernelGGL(eye_kernel, dim3((unsigned)((t2 + 255) / 256)), dim3(256), 0, s,
+                           reinterpret_cast<float *>(o->ws + b.off_midinv[k]), b.td[k + 1], t2);
+      }
       if (hipMemcpyAsync(o->ws + b.off_desc3, descs3[i].data(), descs3[i].size() * sizeof(BlockDesc),
                          hipMemcpyHostToDevice, s) != hipSuccess)
         return fail(SHAMPOO_ERR_HIP);
@@ -1522,11 +1556,15 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
     case SHAMPOO_GET_RINV: need = bk.r_elems() * 4; src = ws + bk.off_Rinv + (size_t)b.slot * need; break;
     case SHAMPOO_GET_L2:
     case SHAMPOO_GET_L2INV:
-      if (!bk.t3) return SHAMPOO_ERR_SHAPE;
-      need = (size_t)bk.d2 * bk.d2 * 4;
-      src = ws + (which == SHAMPOO_GET_L2 ? bk.off_L2 : bk.off_L2inv) + (size_t)b.slot * need;
+    case SHAMPOO_GET_L3:
+    case SHAMPOO_GET_L3INV: {
+      const int k = (which == SHAMPOO_GET_L2 || which == SHAMPOO_GET_L2INV) ? 0 : 1;
+      if (!bk.t3 || k + 2 >= bk.modes) return SHAMPOO_ERR_SHAPE;
+      need = (size_t)bk.td[k + 1] * bk.td[k + 1] * 4;
+      src = ws + ((which == SHAMPOO_GET_L2 || which == SHAMPOO_GET_L3) ? bk.off_mid[k] : bk.off_midinv[k]) + (size_t)b.slot * need;
       break;
-    case SHAMPOO_GET_PSH: need = m * n * (size_t)b.d3 * 4; src = ws + bk.off_P + (size_t)b.slot * need; break;
+    }
+    case SHAMPOO_GET_PSH: need = m * n * (size_t)b.d3 * b.d4 * 4; src = ws + bk.off_P + (size_t)b.slot * need; break;
     case SHAMPOO_GET_NORMS: src = ws + bk.off_norms + (size_t)b.slot * 8; need = 8; break;
     case SHAMPOO_GET_A:
     case SHAMPOO_GET_M:
@@ -1535,7 +1573,7 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
       if (which == SHAMPOO_GET_GF && !o->use_b1) return SHAMPOO_ERR_SHAPE;
       const size_t off_state = which == SHAMPOO_GET_A ? o->off_A : (which == SHAMPOO_GET_M ? o->off_M : o->off_Gf);
       if (b.tensor) {   // state of a tensor parameter is kept block-contiguous
-        const size_t need_t = m * n * (size_t)b.d3 * 4;
+        const size_t need_t = m * n * (size_t)b.d3 * b.d4 * 4;
         if (bytes != need_t) return SHAMPOO_ERR_SHAPE;
         const float *base_t = reinterpret_cast<const float *>(ws + off_state) + p.param_state_offset[param] + b.voff;
         HIP_TRY(hipMemcpyAsync(dst, base_t, need_t, hipMemcpyDeviceToDevice, s));

@@ -613,13 +613,14 @@ class TensorPair:
     def __init__(self, shapes, b, beta2, f, eps=1e-6, mu=0.9, bf16=False, seed=0, **kw):
         self.shapes, self.b, self.f, self.eps, self.bf16 = shapes, b, f, f32(eps), bf16
         graft = kw.get("grafting", "adagrad")
-        self.gpu = B.Shampoo(shapes, b, beta2, eps, 0.25, f, 0, 1e-10, mu,
+        self.r = r = kw.get("root_exponent", 0.25)
+        self.gpu = B.Shampoo(shapes, b, beta2, eps, r, f, 0, 1e-10, mu,
                              B.GRAD_BF16 if bf16 else B.GRAD_F32, 0, kw.get("beta1", 0.0), kw.get("weight_decay", 0.0),
                              kw.get("decoupled", True), kw.get("nesterov", False),
                              {"adagrad": B.GRAFT_ADAGRAD, "sgd": B.GRAFT_SGD, "rmsprop": B.GRAFT_RMSPROP,
                               "adam": B.GRAFT_ADAM}[graft], kw.get("bias_correction", False),
                              B.ROOT_NEWTON if kw.get("newton") else B.ROOT_EIGH, 1e-6, 100, 0.99)
-        self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, 0, f32(1e-10), f32(mu),
+        self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), f32(r) if r != 0.25 else 0.25, f, 0, f32(1e-10), f32(mu),
                                     f32(kw.get("beta1", 0.0)), f32(kw.get("weight_decay", 0.0)), kw.get("decoupled", True),
                                     kw.get("nesterov", False), graft, kw.get("bias_correction", False),
                                     "newton" if kw.get("newton") else "eigh", f32(1e-6), 100, f32(0.99))
@@ -657,7 +658,10 @@ class TensorPair:
             gv = self.g_last[i].reshape(vs).astype(np.float64)
             for k, (starts, dims) in enumerate(self.ora.tblocks[i]):
                 sl = tuple(slice(s0, s0 + d) for s0, d in zip(starts, dims))
-                sel = [(B.GET_L, B.GET_LINV), (B.GET_L2, B.GET_L2INV), (B.GET_R, B.GET_RINV)][:w] if w == 3 else [(B.GET_L, B.GET_LINV)]
+                sel = {1: [(B.GET_L, B.GET_LINV)],
+                       3: [(B.GET_L, B.GET_LINV), (B.GET_L2, B.GET_L2INV), (B.GET_R, B.GET_RINV)],
+                       4: [(B.GET_L, B.GET_LINV), (B.GET_L2, B.GET_L2INV), (B.GET_L3, B.GET_L3INV),
+                           (B.GET_R, B.GET_RINV)]}[w]
                 roots = []
                 for mode, (gf, gi) in enumerate(sel):
                     F = self.gpu.get(i, k, gf).cpu().numpy()
@@ -669,10 +673,10 @@ class TensorPair:
                         c2 = 1.0
                         if self.ora.bias_correction and self.ora.beta2 < 1.0:
                             c2 = 1.0 / (1.0 - self.ora.beta2 ** (t + 1))
-                        want = so.root_inverse(c2 * F.astype(np.float64), self.eps, 0.5 / w)[0]
+                        want = so.root_inverse(c2 * F.astype(np.float64), self.eps, 2.0 * self.r / w)[0]
                         worst["root"] = max(worst["root"], rel(X, want))
                     roots.append(X.astype(np.float64))
-                blk3 = tuple(dims) + (1,) * (3 - w)
+                blk3 = tuple(dims) + (1,) * max(0, 3 - w)
                 A = self.gpu.get(i, k, B.GET_A).cpu().numpy()
                 assert A.shape == blk3
                 if self.ora.grafting != "sgd":
@@ -762,6 +766,56 @@ def test_tensor_edge_cases():
     assert torch.equal(p.w_gpu[1].cpu(), torch.from_numpy(wl.init_params(shapes, 0)[1]))
     for w in p.w_gpu:
         assert torch.isfinite(w).all()
+
+
+ORDER4_SHAPES = [(9, 6, 5, 7),     # b = 4: cut in every dimension, ragged last pieces 1, 2, 1, 3
+                 (5, 6, 7, 8),     # b = 6: first dimension whole, the others 6 / 6+1 / 6+2
+                 (3, 3, 3, 3),     # 3 * 3 > 6: nothing merges, one block
+                 (10, 3, 2, 4),    # b = 6: 10 | 3*2 = 6 | 4: merges to order 3
+                 (7, 5), (11,)]
+
+
+def test_order_four_tensors_every_step():
+    """Sec. 2.3 with w = 4: four factors per block, root exponent 1/8, the preconditioned block is
+    G x_1 X_1 x_2 X_2 x_3 X_3 x_4 X_4.  Blocks cut and ragged in every dimension, fresh roots."""
+    say("case order-4 tensors, b = 4")
+    shapes = ORDER4_SHAPES
+    p = TensorPair(shapes, 4, 0.99, 1)
+    assert p.ora.view_shapes[:4] == [(9, 6, 5, 7), (5, 6, 7, 8), (3, 3, 3, 3), (10, 3, 2, 4)]
+    table, nb = p.gpu.plan()
+    assert sum(1 for r in table if int(r[0]) == 0) == 3 * 2 * 2 * 2
+    for t in range(3):
+        p.step(wl.gaussian_grads(shapes, 51, t, 1e-2), 0.01, t)
+        p.check(t)
+    assert p.gpu.status() == {"refreshes": 3, "failed_roots": 0}
+    say("case order-4 tensors, b = 6, stale roots, heuristics, bf16 gradients")
+    p = TensorPair(shapes, 6, 0.99, 2, bf16=True, beta1=0.9, weight_decay=0.05, nesterov=True,
+                   bias_correction=True, grafting="adam")
+    assert p.ora.view_shapes[3] == (10, 6, 4)
+    for t in range(4):
+        p.step(wl.gaussian_grads(shapes, 52, t, 1e-2), 0.01, t)
+        p.check(t, plain=False)
+
+
+def test_order_four_tensors_larger_factors_and_newton():
+    """Factors above 128 in the two middle dimensions (blocked eigensolver and several tiles per
+    product on each of them, rows of the last unfolding split over ranges), then the coupled
+    Newton roots: root exponent 1/8 per factor is a power the iteration forms by squaring."""
+    say("case order-4, large middle dimensions")
+    shapes = [(3, 132, 130, 5), (20, 12, 13, 40)]
+    p = TensorPair(shapes, 136, 1.0, 1, mu=0.0)
+    assert p.ora.view_shapes == [(3, 132, 130, 5), (20, 12, 13, 40)]
+    for t in range(2):
+        p.step(wl.gaussian_grads(shapes, 53, t, 1e-2), 0.1, t)
+        p.check(t)
+    say("case order-4, coupled Newton")
+    shapes = [(20, 12, 9, 40), (3, 3, 3, 3)]
+    p = TensorPair(shapes, 16, 0.99, 1, newton=True)
+    assert len(p.ora.tblocks[0]) == 2 * 1 * 1 * 3
+    for t in range(2):
+        p.step(wl.gaussian_grads(shapes, 54, t, 1e-2), 0.01, t)
+        p.check(t)
+    assert p.gpu.status()["failed_roots"] == 0
 
 
 def test_newton_failures_fall_back_to_the_eigendecomposition():

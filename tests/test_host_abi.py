@@ -117,8 +117,10 @@ def test_bad_shapes_are_rejected():
     cfg._keep[0][0] = 5             # ndim 5
     assert L.shampoo_plan(ctypes.byref(cfg), None, 0, None, None) == -2
     assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8, 0)], 4)), None, 0, None, None) == -2
-    # four dimensions that do not merge: order 4 is not supported
-    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8, 8, 8)], 4)), None, 0, None, None) == -7
+    # four dimensions that do not merge are planned as a tensor of order 4 ...
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8, 8, 8)], 4)), None, 0, None, None) == 0
+    # ... unless one block would pass 2^30 elements
+    assert L.shampoo_plan(ctypes.byref(cfg_for([(256, 256, 256, 256)], 200)), None, 0, None, None) == -7
     # coupled Newton needs 1 / exponent in {1, 2, 4, 8}: an order-3 tensor would need 6
     assert L.shampoo_plan(ctypes.byref(cfg_for([(8, 8, 8)], 4, root_method=B.ROOT_NEWTON)), None, 0, None, None) == -7
     # a table pointer is required when cap > 0
@@ -165,17 +167,27 @@ def test_planner_merges_small_dimensions_and_blocks_tensors():
     assert all(int(r[7]) == 0 and int(r[9]) == 1 for r in t)
     # stays of order 3: (64, 64, 3, 3) -> (64, 64, 9), one block
     t, nb = B.shampoo_plan(cfg_for([(64, 64, 3, 3)], 128))
-    assert [tuple(int(x) for x in r) for r in t] == [(0, 0, 0, 64, 64, 0, 0, 4, 0, 9)]
+    assert [tuple(int(x) for x in r) for r in t] == [(0, 0, 0, 64, 64, 0, 0, 4 | 3 << 4, 0, 9, 0, 1)]
     # everything merges: one factor (full-matrix AdaGrad), block len x 1 x 1
     t, nb = B.shampoo_plan(cfg_for([(2, 3, 2)], 16))
-    assert [tuple(int(x) for x in r) for r in t] == [(0, 0, 0, 12, 1, 0, 0, 4, 0, 1)]
+    assert [tuple(int(x) for x in r) for r in t] == [(0, 0, 0, 12, 1, 0, 0, 4 | 1 << 4, 0, 1, 0, 1)]
     # blocking of a tensor, against the oracle's partition (row-major order of block indices)
     shape, b = (10, 7, 5), 4
     t, nb = B.shampoo_plan(cfg_for([shape], b))
     want = so.tensor_block_partition(so.merge_dims(shape, b), b)
     got = [((int(r[1]), int(r[2]), int(r[8])), (int(r[3]), int(r[4]), int(r[9]))) for r in t]
-    assert got == want and all(int(r[7]) == 4 for r in t)
+    assert got == want and all(int(r[7]) == 4 | 3 << 4 for r in t)
+    # order 4: four dimensions that do not merge, cut in every dimension
+    shape, b = (9, 6, 5, 7), 4
+    t, nb = B.shampoo_plan(cfg_for([shape], b))
+    assert so.merge_dims(shape, b) == shape
+    want = so.tensor_block_partition(shape, b)
+    got = [((int(r[1]), int(r[2]), int(r[8]), int(r[10])), (int(r[3]), int(r[4]), int(r[9]), int(r[11]))) for r in t]
+    assert got == want and all(int(r[7]) == 4 | 4 << 4 for r in t)
+    assert nb == len({sz for _, sz in want})
     # buckets: equal (d1, d2, d3) share one; slots count up inside it
+    shape, b = (10, 7, 5), 4
+    t, nb = B.shampoo_plan(cfg_for([shape], b))
     keys = {}
     for r in t:
         k = (int(r[3]), int(r[4]), int(r[9]))
