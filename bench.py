@@ -18,11 +18,11 @@ the root-inverse refresh; it runs in the warm-up and its time is reported separa
 One JSON line is printed:
   metric/value        milliseconds per (non-refresh) step, whole job, one GPU
   roofline            the dominant kernel: for blocks above 128 the GEMM of the two-sided
-                      preconditioning.  With bf16 gradients it runs on the bf16 matrix cores from
-                      float32 operands split exactly into three bf16 planes (six exact products per
-                      float32 product for P = T Rbar, three for T = Lbar G): `achieved` is the
-                      executed bf16 MFMA rate (algorithmic flops x products / launch time) against
-                      the 2.5 PFLOP/s bf16 peak, and `algorithmic_tflops` the float32-equivalent
+                      preconditioning.  With bf16 gradients it runs on the fp16 matrix cores from
+                      float32 operands split into two scaled fp16 planes (three exact products per
+                      float32 product for P = T Rbar, two for T = Lbar G): `achieved` is the
+                      executed fp16 MFMA rate (algorithmic flops x products / launch time) against
+                      the 2.5 PFLOP/s fp16 peak, and `algorithmic_tflops` the float32-equivalent
                       rate; with --fp32-matrix-cores or float32 gradients it is the float32-MFMA
                       kernel against 157.3 TFLOP/s.  For workloads whose blocks are at most
                       128 x 128 it is the
@@ -44,7 +44,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
-PEAK_BF16_MFMA_TFLOPS = 2500.0
+PEAK_F16_MFMA_TFLOPS = 2500.0
 # HBM bytes per launch of the dominant kernel (P = T Rbar) on the transformer workload, from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB copy (x2.0 / x1.0):
 # profiles/transformer_b1024_hbm_traffic_pmc.md
@@ -52,9 +52,9 @@ TRAFFIC_BYTES = {"transformer": 14.43e9 + 4.83e9}
 # the same for the single-workgroup block-step kernel on the ResNet-50 shapes:
 # profiles/resnet50_b128_hbm_traffic_pmc.md
 FUSED_TRAFFIC_BYTES = {"resnet50": 0.849e9 + 0.631e9}
-# and for P = T Rbar on the bf16 matrix cores (three-plane operands) of the transformer workload:
+# and for P = T Rbar on the fp16 matrix cores (two-plane operands) of the transformer workload:
 # profiles/transformer_b1024_hbm_traffic_pmc.md
-X3_TRAFFIC_BYTES = {"transformer": 14.50e9 + 4.83e9}
+X2_TRAFFIC_BYTES = {"transformer": 9.66e9 + 4.83e9}
 PEAK_HBM_GBS = 8000.0
 TILE = 128
 
@@ -165,7 +165,7 @@ def main():
                          "multiple of the workload's precondition_frequency")
     ap.add_argument("--fp32-matrix-cores", action="store_true",
                     help="keep the preconditioning products on the float32 matrix cores (default: bf16 matrix "
-                         "cores with the exact three-plane split when the gradients are bf16)")
+                         "cores with the two-plane split when the gradients are bf16)")
     ap.add_argument("--copy-ref", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the reference for scaling HBM counters")
     args = ap.parse_args()
@@ -245,15 +245,15 @@ def main():
     first_ms = stages["precond"][0] / max(stages["precond"][1], 1)
     gsz = 2 if wk["bf16"] else 4
     ew_bytes = {"graft": (gsz + 8.0) * n_elems, "update": 20.0 * n_elems}
-    x3 = wk["bf16"] and not args.fp32_matrix_cores and wk["block"] % 8 == 0
-    if x3:
-        # P = T Rbar executes 6 bf16 products per float32 product (T = Lbar G: 3, the gradient is bf16)
-        executed = achieved * 6.0
-        roofline = {"bound": "mfma", "achieved": executed, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                    "frac": executed / PEAK_BF16_MFMA_TFLOPS, "traffic": X3_TRAFFIC_BYTES.get(args.workload),
-                    "kernel": "gemm_bf16x3_kernel<3,3> (P = T Rbar, bf16 MFMA on three-plane float32 operands)",
-                    "matrix_core_dtype": "bf16", "products_per_float32_product": 6,
-                    "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch * 6.0,
+    x2 = wk["bf16"] and not args.fp32_matrix_cores and wk["block"] % 8 == 0
+    if x2:
+        # P = T Rbar executes 3 fp16 products per float32 product (T = Lbar G: 2, the gradient is one plane)
+        executed = achieved * 3.0
+        roofline = {"bound": "mfma", "achieved": executed, "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": executed / PEAK_F16_MFMA_TFLOPS, "traffic": X2_TRAFFIC_BYTES.get(args.workload),
+                    "kernel": "gemm_f16x2_kernel<256, 2> (P = T Rbar, fp16 MFMA on two-plane float32 operands)",
+                    "matrix_core_dtype": "f16", "products_per_float32_product": 3,
+                    "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch * 3.0,
                     "first_product_launch_ms": first_ms,
                     "algorithmic_flops_per_launch": gemm_flops_per_launch, "algorithmic_tflops": achieved,
                     "algorithmic_frac_of_fp32_mfma_peak": achieved / PEAK_FP32_MFMA_TFLOPS}
@@ -289,7 +289,7 @@ def main():
         "config": {"workload": wk["label"], "params": n_elems, "blocks": int(len(table)),
                    "buckets": int(n_buckets), "block_size": wk["block"], "precondition_frequency": f,
                    "grad_dtype": "bf16" if wk["bf16"] else "f32", "root_method": args.root_method,
-                   "precond_matrix_cores": "f32" if (args.fp32_matrix_cores or not wk["bf16"]) else "bf16x3",
+                   "precond_matrix_cores": "f32" if (args.fp32_matrix_cores or not wk["bf16"]) else "f16x2",
                    "first_refresh_at_step": t_first},
         "refresh_ms": refresh_ms,
         "first_step_ms": first_step_ms,

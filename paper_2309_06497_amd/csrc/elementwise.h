@@ -31,6 +31,7 @@ struct EwArgs {
   float *m_state;                // momentum state, same layout (nullptr when mu == 0)
   const float *p;                // [slot][m][n] Shampoo directions
   float *sg_partial;             // [slot][chunks]
+  float *gmax_partial;           // graft_kernel: [slot][chunks] max |G| of the chunk (nullptr: not wanted)
   const float *scale;            // [slot]
   int32_t m, n;
   EwGeom geom;
@@ -81,12 +82,13 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
   const int tx = tid & ((1 << lx) - 1), ty = tid >> lx, ny = EW_THREADS >> lx;
   const int r0 = chunk * g.geom.rows_per_wg;
   const int r1 = min(r0 + g.geom.rows_per_wg, g.m);
-  float ss = 0.f;
+  float ss = 0.f, gmax = 0.f;
   for (int i = r0 + ty; i < r1; i += ny)
     for (int j = tx * 4; j < n; j += 4 << lx) {
       const int valid = min(4, n - j);
       float gv[4], dv[4], av[4];
       load_g4<GD>(dp + (int64_t)i * ld + j, vec, valid, dv);
+      gmax = fmaxf(fmaxf(gmax, fmaxf(fabsf(dv[0]), fabsf(dv[1]))), fmaxf(fabsf(dv[2]), fabsf(dv[3])));
       if (g.same_src) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) gv[e] = dv[e];
@@ -113,6 +115,14 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
   if ((tid & 63) == 0) red[tid >> 6] = ss;
   __syncthreads();
   if (tid == 0) g.sg_partial[(int64_t)slot * g.geom.chunks + chunk] = (red[0] + red[1]) + (red[2] + red[3]);
+  if (g.gmax_partial) {       // uniform
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) gmax = fmaxf(gmax, __shfl_xor(gmax, off, 64));
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = gmax;
+    __syncthreads();
+    if (tid == 0) g.gmax_partial[(int64_t)slot * g.geom.chunks + chunk] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  }
 }
 
 struct ScaleArgs {

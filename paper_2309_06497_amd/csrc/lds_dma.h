@@ -1,5 +1,5 @@
 // Pieces shared by the kernels that feed the bf16 matrix cores through direct global-to-LDS
-// loads (syrk_bf16.h, gemm_bf16x3.h).
+// loads (syrk_bf16.h, gemm_f16x2.h).
 //
 // global_load_lds_dwordx4 writes the 16 bytes of lane i at LDS address M0 + 16 i: a wavefront
 // fills 1 KiB of consecutive LDS, each lane choosing its own global address.  The compiler

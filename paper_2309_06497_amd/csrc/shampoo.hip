@@ -18,7 +18,7 @@
 #include "diag_shampoo.h"
 #include "eigh_jacobi.h"
 #include "elementwise.h"
-#include "gemm_bf16x3.h"
+#include "gemm_f16x2.h"
 #include "gemm_mfma.h"
 #include "newton_root.h"
 #include "syrk_bf16.h"
@@ -71,8 +71,11 @@ struct Bucket {
   int32_t m, n, count;
   // byte offsets into the workspace
   size_t off_L, off_R, off_Linv, off_Rinv, off_P, off_desc, off_sgp, off_sshp, off_scale, off_norms;
-  size_t off_Linv3 = 0, off_Rinv3 = 0;   // the roots as three bf16 planes (bf16 gradients, bf16_mfma buckets)
-  size_t off_Gt = 0;     // bf16 transpose of the bucket's gradient blocks, made by the factor update and
+  // bf16 gradients, bf16_mfma buckets: both roots as two scaled fp16 planes, what the scales
+  // are made from (matrix_stats_kernel of both roots, max |G| per piece of a block) and the
+  // scales themselves
+  size_t off_Linv2h = 0, off_Rinv2h = 0, off_stat_l = 0, off_stat_r = 0, off_gmaxp = 0, off_s_g = 0, off_inv_g2 = 0, off_t_scale = 0, off_inv_ts = 0;
+  size_t off_Gt = 0;     // 16-bit transpose of the bucket's gradient blocks (bf16, or scaled fp16 where the fp16 products follow), made by the factor update and
                          // read again by the first preconditioning product of the same step
   bool planes = false;
   EwGeom geom;
@@ -694,13 +697,20 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
       t2_elems = std::max(t2_elems, B * m * n);
     }
     b.off_P = take(B * m * n * 4);
-    // bf16 gradients: the preconditioning products run on the bf16 matrix cores from
-    // operands kept split in three bf16 planes
+    // bf16 gradients: the preconditioning products run on the fp16 matrix cores from
+    // operands kept split in two scaled fp16 planes
     b.planes = c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2 && !use_b1 &&
                c->precond_matrix_cores != SHAMPOO_MATRIX_CORES_FP32;
     if (b.planes) {
-      b.off_Linv3 = take(B * m * m * 6);
-      b.off_Rinv3 = take(B * n * n * 6);
+      b.off_Linv2h = take(B * m * m * 4);
+      b.off_Rinv2h = take(B * n * n * 4);
+      b.off_stat_l = take(B * 8);
+      b.off_stat_r = take(B * 8);
+      b.off_gmaxp = take(B * b.geom.chunks * 4);
+      b.off_s_g = take(B * 4);
+      b.off_inv_g2 = take(B * 4);
+      b.off_t_scale = take(B * 4);
+      b.off_inv_ts = take(B * 4);
     }
     b.off_desc = take(B * sizeof(BlockDesc));
     b.off_sgp = take(B * b.geom.chunks * 4);
@@ -711,7 +721,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     b.off_sshp = take(B * ssh_parts * 4);
     b.off_scale = take(B * 4);
     b.off_norms = take(B * 8);
-    t_elems = std::max(t_elems, B * m * n * (b.planes ? 3 : 2) / 2);   // T as three bf16 planes: 6 bytes per element
+    t_elems = std::max(t_elems, B * m * n);   // float32, or two fp16 planes
     if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) b.off_Gt = take(B * m * n * 2);
     // a diagonalised side needs no eigensolver workspace (stand-in layout of a 1 x 1 problem)
     const int em = b.diagL ? 1 : b.m, en = b.diagR ? 1 : b.rdim();
@@ -773,16 +783,20 @@ struct StageTimer {
   }
 };
 
-// Re-splits the roots of every bucket that keeps them as bf16 planes (after create and after
+// Re-splits the roots of every bucket that keeps them as planes (after create and after
 // every refresh).
 int split_roots(shampoo_opt *o, hipStream_t s) {
   for (auto &b : o->plan.buckets) {
     if (!b.planes) continue;
     const int64_t nl = (int64_t)b.count * b.m * b.m, nr = (int64_t)b.count * b.n * b.n;
-    hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<const float *>(o->ws + b.off_Linv), reinterpret_cast<uint16_t *>(o->ws + b.off_Linv3), nl);
-    hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<const float *>(o->ws + b.off_Rinv), reinterpret_cast<uint16_t *>(o->ws + b.off_Rinv3), nr);
+    const float *Li = reinterpret_cast<const float *>(o->ws + b.off_Linv), *Ri = reinterpret_cast<const float *>(o->ws + b.off_Rinv);
+    float *stat_l = reinterpret_cast<float *>(o->ws + b.off_stat_l), *stat_r = reinterpret_cast<float *>(o->ws + b.off_stat_r);
+    hipLaunchKernelGGL(matrix_stats_kernel, dim3(b.count), dim3(256), 0, s, Li, stat_l, b.m);
+    hipLaunchKernelGGL(matrix_stats_kernel, dim3(b.count), dim3(256), 0, s, Ri, stat_r, b.n);
+    hipLaunchKernelGGL(split2h_kernel, dim3((unsigned)((nl + 255) / 256)), dim3(256), 0, s,
+                       Li, stat_l, reinterpret_cast<uint16_t *>(o->ws + b.off_Linv2h), (int64_t)b.m * b.m, nl);
+    hipLaunchKernelGGL(split2h_kernel, dim3((unsigned)((nr + 255) / 256)), dim3(256), 0, s,
+                       Ri, stat_r, reinterpret_cast<uint16_t *>(o->ws + b.off_Rinv2h), (int64_t)b.n * b.n, nr);
     HIP_TRY(hipGetLastError());
   }
   return SHAMPOO_OK;
@@ -913,14 +927,42 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     hipLaunchKernelGGL(block_step_small_kernel<GT>, dim3((unsigned)o->n_small), dim3(SB_THREADS), 0, s, f);
     HIP_TRY(hipGetLastError());
   }
+  // scales of the fp16 operands of a bucket's preconditioning products (and of R's update)
+  auto launch_x2_scales = [&](const Bucket &b) {
+    X2ScaleArgs xs;
+    xs.gmax_partial = reinterpret_cast<const float *>(ws + b.off_gmaxp); xs.parts = b.geom.chunks;
+    xs.stat_l = reinterpret_cast<const float *>(ws + b.off_stat_l); xs.stat_r = reinterpret_cast<const float *>(ws + b.off_stat_r);
+    xs.c1 = c1;
+    xs.s_g = reinterpret_cast<float *>(ws + b.off_s_g); xs.inv_g2 = reinterpret_cast<float *>(ws + b.off_inv_g2);
+    xs.t_scale = reinterpret_cast<float *>(ws + b.off_t_scale); xs.inv_ts = reinterpret_cast<float *>(ws + b.off_inv_ts);
+    hipLaunchKernelGGL(x2_scales_kernel, dim3(b.count), dim3(64), 0, s, xs);
+  };
   for (auto &b : p.buckets) {
     if (fused(b)) continue;
     const BlockDesc *desc = reinterpret_cast<const BlockDesc *>(ws + b.off_desc);
+    // grafting state and norm first: the same pass finds max |G| of every block, which scales
+    // the fp16 planes of this step's first product
+    {
+      StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
+      EwArgs e{};
+      e.desc = desc; e.w_table = wtab; e.g_table = gs_tab; e.gd_table = gd_tab; e.a_state = A; e.m_state = M;
+      e.sg_partial = reinterpret_cast<float *>(ws + b.off_sgp);
+      e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
+      e.sgd_graft = sgd; e.same_src = (gs_tab == gd_tab) ? 1 : 0; e.gd_scale = c1;
+      e.a_decay = a_decay; e.a_gain = a_gain; e.a_bc = a_bc;
+      if (b.planes) e.gmax_partial = reinterpret_cast<float *>(ws + b.off_gmaxp);
+      hipLaunchKernelGGL((graft_kernel<GS, GD>), dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
+      HIP_TRY(hipGetLastError());
+    }
     if (sizeof(GS) == 2 && b.bf16_mfma && o->ptrs_aligned16) {
       StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
+      // fp16 operands of this step's preconditioning products (and of R's update): their scales first
+      const bool x2 = sizeof(GD) == 2 && b.planes;
+      if (x2) launch_x2_scales(b);
       uint16_t *Gt = reinterpret_cast<uint16_t *>(ws + b.off_Gt);
       TransposeArgs ta;
       ta.desc = desc; ta.g_table = gs_tab; ta.out = Gt; ta.m = b.m; ta.n = b.n;
+      ta.scale = x2 ? reinterpret_cast<const float *>(ws + b.off_s_g) : nullptr;
       hipLaunchKernelGGL(transpose_bf16_kernel, dim3((b.n + 63) / 64, (b.m + 63) / 64, b.count), dim3(256), 0, s, ta);
       SyrkBf16Args sa{};
       sa.desc = desc; sa.ptr_table = gs_tab; sa.alpha = alpha; sa.beta = beta; sa.batch = b.count;
@@ -931,7 +973,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       {
         const int64_t total = (int64_t)sa.tiles * sa.batch;
         const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
-        hipLaunchKernelGGL(syrk_bf16_kernel, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+        hipLaunchKernelGGL(syrk_bf16_kernel<false>, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
       }
       // R <- beta R + alpha (G^T)(G^T)^T
       sa.a.from_table = 0; sa.a.base = Gt; sa.a.batch_stride = (int64_t)b.m * b.n; sa.a.ld = b.m;
@@ -940,7 +982,12 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       {
         const int64_t total = (int64_t)sa.tiles * sa.batch;
         const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
-        hipLaunchKernelGGL(syrk_bf16_kernel, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+        if (x2) {
+          sa.x_scale2 = reinterpret_cast<const float *>(ws + b.off_inv_g2);
+          hipLaunchKernelGGL(syrk_bf16_kernel<true>, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+        } else {
+          hipLaunchKernelGGL(syrk_bf16_kernel<false>, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+        }
       }
       HIP_TRY(hipGetLastError());
     } else {
@@ -1022,17 +1069,6 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         rc = launch_gemm<ROW_CONTIG, ROW_CONTIG, GS, GS, EPI_SYRK, false, FLUSH>(g, s);
         if (rc) return rc;
       }
-    }
-    {
-      StageTimer t(o, SHAMPOO_STAGE_GRAFT, s);
-      EwArgs e{};
-      e.desc = desc; e.w_table = wtab; e.g_table = gs_tab; e.gd_table = gd_tab; e.a_state = A; e.m_state = M;
-      e.sg_partial = reinterpret_cast<float *>(ws + b.off_sgp);
-      e.m = b.m; e.n = b.n; e.geom = b.geom; e.graft_eps = c.graft_epsilon; e.mu = c.momentum; e.lr = lr;
-      e.sgd_graft = sgd; e.same_src = (gs_tab == gd_tab) ? 1 : 0; e.gd_scale = c1;
-      e.a_decay = a_decay; e.a_gain = a_gain; e.a_bc = a_bc;
-      hipLaunchKernelGGL((graft_kernel<GS, GD>), dim3((unsigned)b.geom.chunks * b.count), dim3(EW_THREADS), 0, s, e);
-      HIP_TRY(hipGetLastError());
     }
   }
   if (refresh) {
@@ -1211,36 +1247,49 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
         ssh_count = b.geom.chunks;
       }
     } else if (use_shampoo && sizeof(GD) == 2 && sizeof(GS) == 2 && b.planes && o->ptrs_aligned16) {
-      // bf16 gradients: both products on the bf16 matrix cores, float32-accurate through the
-      // three-plane split of the float32 operands (the gradient itself is one exact plane);
-      // B operands are read along k: G^T is the bf16 transpose made for the factor update
-      const int x3_tm = (b.m + X3_TM - 1) / X3_TM, x3_tn = (b.n + X3_TN - 1) / X3_TN;
-      const int64_t per = ((int64_t)x3_tm * x3_tn * b.count + NUM_XCD - 1) / NUM_XCD;
-      ssh_count = x3_tm * x3_tn;
-      uint16_t *T3 = reinterpret_cast<uint16_t *>(T);
+      // bf16 gradients: both products on the fp16 matrix cores, float32-accurate through
+      // two-plane splits of the float32 operands (Lbar, T, Rbar), each scaled by a power of two
+      // into the fp16 range; the gradient is one fp16 plane (exact: 8 significant bits).
+      // B operands are read along k: G^T is the scaled fp16 transpose made for the factor update.
+      const int tm128 = (b.m + 127) / 128, x2_tn = (b.n + X2_TN - 1) / X2_TN;
+      // tiles of 256 rows (half the operand traffic per multiply) unless padding the rows to
+      // 256 would add more than an eighth to the work
+      const int tm256 = (b.m + 255) / 256;
+      const bool tall = tm256 * 256 * 8 <= tm128 * 128 * 9;
+      const int h_tm = tall ? tm256 : tm128;
+      const int64_t per_h = ((int64_t)h_tm * x2_tn * b.count + NUM_XCD - 1) / NUM_XCD;
+      ssh_count = h_tm * x2_tn;
+      uint16_t *T2h = reinterpret_cast<uint16_t *>(T);
       const int64_t t_plane = (int64_t)b.count * b.m * b.n;
       {
       StageTimer t(o, SHAMPOO_STAGE_PRECOND, s);
-      GemmX3Args g{};
-      g.a = reinterpret_cast<const uint16_t *>(ws + b.off_Linv3);
+      if (refresh) launch_x2_scales(b);   // the roots, and with them their scales, have just changed
+      GemmX2Args g{};
+      g.a = reinterpret_cast<const uint16_t *>(ws + b.off_Linv2h);
       g.a_plane_stride = (int64_t)b.count * b.m * b.m; g.a_batch_stride = (int64_t)b.m * b.m; g.lda = b.m;
       g.b = reinterpret_cast<const uint16_t *>(ws + b.off_Gt); g.b_plane_stride = 0;
       g.b_batch_stride = (int64_t)b.m * b.n; g.ldb = b.m;
-      g.c3 = T3; g.c3_plane_stride = t_plane; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
-      g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1;
-      g.tiles_m = x3_tm; g.tiles_n = x3_tn; g.batch = b.count;
-      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 1, X3_STORE_SPLIT>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, g);
+      g.c2 = T2h; g.c2_plane_stride = t_plane; g.c_batch_stride = (int64_t)b.m * b.n; g.ldc = b.n;
+      g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1; g.out_scale = reinterpret_cast<const float *>(ws + b.off_t_scale);
+      g.tiles_m = h_tm; g.tiles_n = x2_tn; g.batch = b.count;
+      if (tall)
+        hipLaunchKernelGGL((gemm_f16x2_kernel<256, 1, X2_STORE_SPLIT>), dim3((unsigned)(per_h * NUM_XCD)), dim3(512), 0, s, g);
+      else
+        hipLaunchKernelGGL((gemm_f16x2_kernel<128, 1, X2_STORE_SPLIT>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, g);
       }
       StageTimer t2(o, SHAMPOO_STAGE_PRECOND2, s);
-      GemmX3Args h{};
-      h.a = T3; h.a_plane_stride = t_plane; h.a_batch_stride = (int64_t)b.m * b.n; h.lda = b.n;
-      h.b = reinterpret_cast<const uint16_t *>(ws + b.off_Rinv3);
+      GemmX2Args h{};
+      h.a = T2h; h.a_plane_stride = t_plane; h.a_batch_stride = (int64_t)b.m * b.n; h.lda = b.n;
+      h.b = reinterpret_cast<const uint16_t *>(ws + b.off_Rinv2h);
       h.b_plane_stride = (int64_t)b.count * b.n * b.n; h.b_batch_stride = (int64_t)b.n * b.n; h.ldb = b.n;
       h.c = P; h.c_batch_stride = (int64_t)b.m * b.n; h.ldc = b.n;
-      h.M = b.m; h.N = b.n; h.K = b.n; h.alpha = 1.f;
+      h.M = b.m; h.N = b.n; h.K = b.n; h.alpha = 1.f; h.out_scale = reinterpret_cast<const float *>(ws + b.off_inv_ts);
       h.norm_partial = reinterpret_cast<float *>(ws + b.off_sshp);
-      h.tiles_m = x3_tm; h.tiles_n = x3_tn; h.batch = b.count;
-      hipLaunchKernelGGL((gemm_bf16x3_kernel<3, 3, X3_STORE_NORM>), dim3((unsigned)(per * NUM_XCD)), dim3(GEMM_THREADS), 0, s, h);
+      h.tiles_m = h_tm; h.tiles_n = x2_tn; h.batch = b.count;
+      if (tall)
+        hipLaunchKernelGGL((gemm_f16x2_kernel<256, 2, X2_STORE_NORM>), dim3((unsigned)(per_h * NUM_XCD)), dim3(512), 0, s, h);
+      else
+        hipLaunchKernelGGL((gemm_f16x2_kernel<128, 2, X2_STORE_NORM>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, h);
       HIP_TRY(hipGetLastError());
     } else if (use_shampoo) {
       {

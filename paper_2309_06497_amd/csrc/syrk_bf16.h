@@ -14,8 +14,10 @@
 // so that two slabs are in flight while one is multiplied.  Such a load writes the 64
 // lanes' chunks to consecutive LDS addresses, which leaves no room for row padding;
 // bank conflicts are avoided by a swizzle instead: the 16-byte chunk c of row r sits at
-// chunk position c ^ ((r >> 1) & 3) of its 64-byte LDS row (the lane picks its global
-// address accordingly).  An MFMA operand is 8 consecutive k of one row per lane:
+// chunk position c ^ ((r >> 2) & 3) of its 64-byte LDS row (the lane picks its global
+// address accordingly).  A 16-byte read is served 16 lanes at a time from 64 banks of 4 bytes:
+// the 16 rows of such a group start at banks 16 (r % 4), and rows with equal r % 4 take
+// different chunk positions, so the group covers every bank once (SQ_LDS_BANK_CONFLICT = 0).  An MFMA operand is 8 consecutive k of one row per lane:
 // lane = row % 32 + 32 * (k / 8).
 //
 // The compiler's own wait-count placement would wait for every outstanding load before
@@ -36,7 +38,7 @@ namespace shampoo {
 constexpr int SBK = 32;                        // k per slab: two MFMAs chained in float32, then the float64 flush
 constexpr int SYRK_SLAB = BM * SBK * 2;        // bytes of one operand slab
 constexpr int SYRK_STAGE = 2 * SYRK_SLAB;      // A slab, then B slab
-constexpr int SYRK_STAGES = 3;
+constexpr int SYRK_STAGES = 3;                 // a fourth stage fits the LDS footprint and measured no faster
 
 struct SyrkBf16Args {
   Operand a;                 // bf16 matrix X (rows x K, k contiguous); C = beta C + alpha X X^T
@@ -45,6 +47,7 @@ struct SyrkBf16Args {
   float *c; int64_t c_batch_stride; int32_t ldc;
   int32_t M, K;              // C is M x M
   double alpha, beta;
+  const float *x_scale2;     // [batch] X holds fp16 values s x: 1 / s^2, applied with alpha (nullptr: X is bf16)
   int32_t tiles;             // lower-triangular tile count per batch entry
   int32_t batch;
 };
@@ -54,17 +57,28 @@ __device__ __forceinline__ void syrk_flush(double (&dst)[16], const floatx16 &sr
   for (int v = 0; v < 16; ++v) dst[v] += (double)src[v];
 }
 
+typedef _Float16 syrk_f16x8 __attribute__((ext_vector_type(8)));
+
+template <bool F16>
 __device__ __forceinline__ floatx16 syrk_chain(const u32x4 &a0, const u32x4 &b0, const u32x4 &a1, const u32x4 &b1) {
   floatx16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
+  if constexpr (F16) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(syrk_f16x8, a0), __builtin_bit_cast(syrk_f16x8, b0), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(syrk_f16x8, a1), __builtin_bit_cast(syrk_f16x8, b1), acc, 0, 0, 0);
+  } else {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
+  }
   return acc;
 }
 
 
 // Requires: operand base 16-byte aligned, ld % 8 == 0, K % 8 == 0 (checked by the host).
+// F16: the operand holds fp16 values (the scaled transpose of a bf16 block: products of two
+// such values are exact in float32 as well) and the fp16 matrix-core instruction is used.
+template <bool F16>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf16Args g) {
   // one LDS region: the operand slabs during the k loop, then the tile on its way to the
   // mirrored (transposed) position
@@ -102,11 +116,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
 #pragma unroll
   for (int t = 0; t < PER_WAVE; ++t) {
     const int p = (wave * PER_WAVE + t) * 64 + lane;
-    const int row = p >> 2, ch = (p & 3) ^ ((row >> 1) & 3);
+    const int row = p >> 2, ch = (p & 3) ^ ((row >> 2) & 3);
     chunk_k[t] = ch * 8;
     offa[t] = (uint32_t)(min(row, rows_a - 1) * ld + ch * 8) * 2u;
     offb[t] = (uint32_t)(min(row, rows_b - 1) * ld + ch * 8) * 2u;
   }
+  // A tile on the diagonal multiplies a row panel by itself: only the B slab is loaded, and
+  // the A operand is read from it as well.
+  const bool diag = ti == tj;
   auto issue = [&](int stage, int k0) {
     const char *ga = uniform_ptr(xa + k0);
     const char *gb = uniform_ptr(xb + k0);
@@ -114,7 +131,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
 #pragma unroll
     for (int t = 0; t < PER_WAVE; ++t) {
       const int q = uw * PER_WAVE + t;
-      __builtin_amdgcn_global_load_lds((glb_void *)(ga + offa[t]), (lds_void *)(sa + q * 1024), 16, 0, 0);
+      if (!diag) __builtin_amdgcn_global_load_lds((glb_void *)(ga + offa[t]), (lds_void *)(sa + q * 1024), 16, 0, 0);
       __builtin_amdgcn_global_load_lds((glb_void *)(gb + offb[t]), (lds_void *)(sb + q * 1024), 16, 0, 0);
     }
   };
@@ -122,8 +139,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   // LDS byte addresses of this lane's operand rows: k step s of a slab is chunk 2 s + lane / 32
   const int fi = lane & 31, fq = lane >> 5;
   const uint32_t lbase = (uint32_t)(uintptr_t)(lds_void *)smem;
-  const uint32_t la0 = lbase + ((wm * 64 + fi) * SBK + ((fq ^ ((fi >> 1) & 3)) * 8)) * 2, la1 = la0 ^ 32;
-  const uint32_t lb0 = lbase + ((wn * 64 + fi) * SBK + ((fq ^ ((fi >> 1) & 3)) * 8)) * 2, lb1 = lb0 ^ 32;
+  const uint32_t la0 = lbase + (diag ? SYRK_SLAB : 0) + ((wm * 64 + fi) * SBK + ((fq ^ ((fi >> 2) & 3)) * 8)) * 2, la1 = la0 ^ 32;
+  const uint32_t lb0 = lbase + ((wn * 64 + fi) * SBK + ((fq ^ ((fi >> 2) & 3)) * 8)) * 2, lb1 = lb0 ^ 32;
 
   double acc64[2][2][16];
 #pragma unroll
@@ -158,19 +175,19 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
                  : "+v"(oa[0][0]), "+v"(oa[0][1]), "+v"(oa[1][0]), "+v"(oa[1][1]),        \
                    "+v"(ob[0][0]), "+v"(ob[0][1]), "+v"(ob[1][0]), "+v"(ob[1][1]) :: "memory"); \
     LDS_SCHED_BARRIER();                                                                            \
-    X = syrk_chain(oa[0][0], ob[0][0], oa[0][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
+    X = syrk_chain<F16>(oa[0][0], ob[0][0], oa[0][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
     syrk_flush(acc64[1][1], Y); LDS_SCHED_BARRIER();                                                \
-    Y = syrk_chain(oa[0][0], ob[1][0], oa[0][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
+    Y = syrk_chain<F16>(oa[0][0], ob[1][0], oa[0][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
     syrk_flush(acc64[0][0], X); LDS_SCHED_BARRIER();                                                \
-    X = syrk_chain(oa[1][0], ob[0][0], oa[1][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
+    X = syrk_chain<F16>(oa[1][0], ob[0][0], oa[1][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
     syrk_flush(acc64[0][1], Y); LDS_SCHED_BARRIER();                                                \
-    Y = syrk_chain(oa[1][0], ob[1][0], oa[1][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
+    Y = syrk_chain<F16>(oa[1][0], ob[1][0], oa[1][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
     syrk_flush(acc64[1][0], X); LDS_SCHED_BARRIER();                                                \
   }
 
   if (g.K % SBK) {
-    // The ragged end of k goes first, through registers with zero fill, into the third
-    // stage, while the first two full slabs are on their way.
+    // The ragged end of k goes first, through registers with zero fill, into the last
+    // stage, while the first full slabs are on their way.
     const int k0 = nk * SBK;
 #pragma unroll
     for (int t = 0; t < PER_WAVE; ++t) {
@@ -178,16 +195,17 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
       const bool kin = k0 + chunk_k[t] < g.K;      // K % 8 == 0: a chunk is entirely in or out
       const uint4 va = kin ? *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(xa + k0) + offa[t]) : make_uint4(0, 0, 0, 0);
       const uint4 vb = kin ? *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(xb + k0) + offb[t]) : make_uint4(0, 0, 0, 0);
-      *reinterpret_cast<uint4 *>(smem + 2 * SYRK_STAGE + q * 1024 + lane * 16) = va;
-      *reinterpret_cast<uint4 *>(smem + 2 * SYRK_STAGE + SYRK_SLAB + q * 1024 + lane * 16) = vb;
+      *reinterpret_cast<uint4 *>(smem + (SYRK_STAGES - 1) * SYRK_STAGE + q * 1024 + lane * 16) = va;
+      *reinterpret_cast<uint4 *>(smem + (SYRK_STAGES - 1) * SYRK_STAGE + SYRK_SLAB + q * 1024 + lane * 16) = vb;
     }
     __syncthreads();
-    SYRK_SLAB_PRODUCT(2);
+    SYRK_SLAB_PRODUCT(SYRK_STAGES - 1);
   }
   // Slab kt is multiplied while slabs kt + 1 and kt + 2 are on their way.
+#define SYRK_WAIT(N) { if (diag) { LDS_DMA_WAIT_VM((N) * PER_WAVE); } else { LDS_DMA_WAIT_VM((N) * PW); } }
 #define SYRK_STEP(S, NEXT, KT)                                                            \
   {                                                                                       \
-    if ((KT) + 1 < nk) { LDS_DMA_WAIT_VM(PW); } else { LDS_DMA_WAIT_VM(0); }                    \
+    if ((KT) + 1 < nk) SYRK_WAIT(1) else SYRK_WAIT(0)                                     \
     __builtin_amdgcn_s_barrier();                                                         \
     if ((KT) + 2 < nk) issue(NEXT, ((KT) + 2) * SBK);                                     \
     if ((KT) < nk) SYRK_SLAB_PRODUCT(S);                                                  \
@@ -208,7 +226,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   // copies carry the same bits, so the factor stays exactly symmetric.
   float *c = g.c + (int64_t)b * g.c_batch_stride;
   const int ldc = g.ldc;
-  const bool diag = ti == tj;
+  const double alpha = g.x_scale2 ? g.alpha * (double)g.x_scale2[b] : g.alpha;
   // The old values of half a quadrant (32 x 64) are requested before any of them is used,
   // from clamped (always valid) addresses so that the loads are unconditional: one memory
   // round trip per half instead of one per element.
@@ -237,7 +255,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int il = wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), i = row0 + il;
-        const float x = (float)(g.alpha * acc64[mi][ni][v] + g.beta * (double)old[ni][v]);
+        const float x = (float)(alpha * acc64[mi][ni][v] + g.beta * (double)old[ni][v]);
         if (diag) {
           if (jl <= il) { Ts[il * SYRK_TLD + jl] = x; Ts[jl * SYRK_TLD + il] = x; }
         } else {
@@ -267,16 +285,18 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   }
 }
 #undef SYRK_STEP
+#undef SYRK_WAIT
 #undef SYRK_SLAB_PRODUCT
 
 struct TransposeArgs {
   const BlockDesc *desc;
   const void *const *g_table;
   uint16_t *out;             // [slot][n][m]
+  const float *scale;        // [slot] nullptr: out is bf16 like the block; else out = fp16(scale * block)
   int32_t m, n;
 };
 
-// out[slot][j][i] = G_block[i][j] (bf16 bits).  grid (ceil(n/64), ceil(m/64), blocks), 256 threads.
+// out[slot][j][i] = G_block[i][j] (bf16 bits, or fp16 bits of the scaled value).  grid (ceil(n/64), ceil(m/64), blocks), 256 threads.
 // Both sides move 16 bytes per lane (8 bf16 along the contiguous direction); the transposition
 // itself happens in LDS.  Requires m % 8 == 0, n % 8 == 0, 16-byte aligned rows on both sides
 // (the conditions of the bf16 matrix-core path, checked by the host).
@@ -292,7 +312,15 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeArgs
     const int i = i0 + r, j = j0 + c;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (i < g.m && j < g.n) v = *reinterpret_cast<const uint4 *>(src + (int64_t)i * d.ld + j);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    if (g.scale) {      // uniform: bf16 -> scaled fp16 (exact unless it underflows: 8 significant bits go into 11)
+      const float sc = g.scale[blockIdx.z];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const _Float16 lo = (_Float16)(__uint_as_float(w[e] << 16) * sc), hi = (_Float16)(__uint_as_float(w[e] & 0xffff0000u) * sc);
+        w[e] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+      }
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {      // rows of 66 elements are only 4-byte aligned
       *reinterpret_cast<uint32_t *>(&tile[r][c + 2 * e]) = w[e];
