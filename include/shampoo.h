@@ -113,10 +113,12 @@ typedef struct {
   float newton_tolerance; /* stop when ||M_k - I||_inf < this; 0 selects 1e-6 (Sec. 3.2.1)     */
   int32_t newton_max_iterations; /* iteration cap, <= 1000; 0 selects 100                     */
   int32_t precond_matrix_cores; /* SHAMPOO_MATRIX_CORES_AUTO (default): with bf16 gradients and blocks
-                             whose shape and alignment allow it, Lbar G Rbar runs on the bf16 matrix
-                             cores from float32 operands split exactly into three bf16 planes (six
-                             exact products accumulated in float32: float32 accuracy at 3/8 of the
-                             float32-MFMA time); SHAMPOO_MATRIX_CORES_FP32: always the float32 MFMA   */
+                             whose shape and alignment allow it, Lbar G Rbar runs on the fp16 matrix
+                             cores from float32 operands split into two fp16 planes each, scaled
+                             per block by a power of two (three exact products accumulated in
+                             float32: float32 accuracy at 3/16 of the float32-MFMA time; elements
+                             below 2^-16 of a block's largest keep absolute, not relative,
+                             accuracy); SHAMPOO_MATRIX_CORES_FP32: always the float32 MFMA          */
   int32_t grad_dtype;     /* SHAMPOO_GRAD_F32 or SHAMPOO_GRAD_BF16; parameters are float32   */
   int32_t device;         /* HIP device ordinal                                              */
 } shampoo_config;

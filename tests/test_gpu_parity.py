@@ -290,6 +290,31 @@ def test_bf16_ragged_blocks_on_matrix_cores():
         p.check(t)
 
 
+def test_bf16_products_at_extreme_gradient_scales():
+    """The preconditioning products of bf16 gradients run on fp16 planes scaled by powers of two
+    (from max |G| of the block and from the roots' largest elements).  Gradients of size 1e-15
+    and 1e+10, rows that span six decades inside one block, and a block that is zero must leave
+    the products float32-accurate: Lbar G Rbar against the float64 product of the GPU's own
+    roots <= 2e-5, everything else to the usual bars.  Fresh roots every step, so the scales of
+    the roots change under the products as well."""
+    import torch
+    shapes = [(256, 384), (384, 256)]
+    for name, sigma, eps, span in (("tiny", 1e-15, 1e-30, False), ("huge", 1e10, 1e20, False), ("rows", 1e-3, 1e-9, True)):
+        say(f"case bf16 scaling: {name}")
+        p = Pair(shapes, 256, 0.999, 1, eps=eps, eps_g=sigma * 1e-7, bf16=True)
+        for t in range(3):
+            g = wl.gaussian_grads(shapes, 61, t, sigma)
+            if span:
+                for x in g:
+                    x *= (10.0 ** (-6.0 * np.arange(x.shape[0]) / x.shape[0]))[:, None].astype(np.float32)
+                g[1][:, :128] = 0.0     # the left block of the second parameter: a zero gradient
+            p.step(g, 0.01, t)
+            worst, _ = p.check(t)
+            assert worst["gemm"] <= 2e-5, worst
+        for w in p.w_gpu:
+            assert torch.isfinite(w).all()
+
+
 def test_grafting_warmup_then_shampoo():
     say("case warmup")
     shapes = [(96, 80), (33,)]
