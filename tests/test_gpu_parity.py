@@ -290,6 +290,19 @@ def test_bf16_ragged_blocks_on_matrix_cores():
         p.check(t)
 
 
+def test_bf16_ragged_blocks_on_tall_tiles():
+    """One 1000 x 520 block: the 256-row tiles of the fp16 products with a partial last tile in
+    both directions (rows 768 ... 999 of 1024, columns 512 ... 519 of 768), k = 1000 and 520 with
+    ragged ends of 8, and the factor kernel's partial tiles at 1000 and 520."""
+    say("case bf16 ragged, 256-row tiles")
+    shapes = [(1000, 520)]
+    p = Pair(shapes, 1024, 0.999, 1, eps=1e-6, bf16=True)
+    for t in range(2):
+        p.step(wl.gaussian_grads(shapes, 22, t, 1e-3), 0.01, t)
+        worst, _ = p.check(t)
+        assert worst["gemm"] <= 2e-5, worst
+
+
 def test_bf16_products_at_extreme_gradient_scales():
     """The preconditioning products of bf16 gradients run on fp16 planes scaled by powers of two
     (from max |G| of the block and from the roots' largest elements).  Gradients of size 1e-15
