@@ -53,6 +53,7 @@ struct JacScratch {      // small per-workgroup LDS arrays
   int p[JAC_SMALL_MAX / 2];
   int q[JAC_SMALL_MAX / 2];
   int flag;
+  unsigned rounds[4];     // bit r: round r of the current sweep has a pair above the threshold
 };
 
 // Pair k of round r of a round-robin tournament over `cnt` (even) players.
@@ -106,8 +107,30 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
   int any = 0;
   for (int sw = 0; sw < max_sweeps; ++sw) {
     if (tid == 0) sc->flag = 0;
+    if (tid < 4) sc->rounds[tid] = 0u;
+    __syncthreads();
+    // Which rounds of this sweep have anything to do: every pair is held against the
+    // threshold once, up front, and a round without a pair above it is skipped whole (two
+    // barriers and an LDS round trip each: in the late sweeps of a solve that is most rounds,
+    // and in the block solver most pivots).  A pair that other rotations of this sweep push
+    // over the threshold waits for the next sweep, which only ends the iteration when no
+    // pair is above the threshold at its start.  Pair (p, q), p < q, meets in round
+    // r = p if q = s - 1, else r with 2 r = p + q (mod s - 1), i.e. r = (p + q) (s / 2) mod (s - 1).
+    {
+      const int JW = s > 64 ? 128 : 64;                 // columns per row pass
+      const int j = tid & (JW - 1);
+      for (int i = tid / JW; i < s; i += NT / JW) {
+        if (j >= i) continue;                           // j < i < s
+        const double aij = fabs(At[at(i, j)]);
+        if (aij > tol_abs && aij * aij > tol_rel * tol_rel * fabs(At[at(i, i)] * At[at(j, j)])) {
+          const int r = (i == s - 1) ? j : ((i + j) * half) % (s - 1);
+          atomicOr(&sc->rounds[r >> 5], 1u << (r & 31));
+        }
+      }
+    }
     __syncthreads();
     for (int r = 0; r < s - 1; ++r) {
+      if (!((sc->rounds[r >> 5] >> (r & 31)) & 1u)) continue;      // uniform
       if (tid < half) {
         int p, q;
         rr_pair(s, r, tid, p, q);   // p < q
