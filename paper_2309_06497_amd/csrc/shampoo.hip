@@ -1254,8 +1254,9 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       const int tm128 = (b.m + 127) / 128, x2_tn = (b.n + X2_TN - 1) / X2_TN;
       // tiles of 256 rows (half the operand traffic per multiply) unless padding the rows to
       // 256 would add more than an eighth to the work
+      // and unless there are too few of them to give every CU one
       const int tm256 = (b.m + 255) / 256;
-      const bool tall = tm256 * 256 * 8 <= tm128 * 128 * 9;
+      const bool tall = tm256 * 256 * 8 <= tm128 * 128 * 9 && (int64_t)tm256 * x2_tn * b.count >= 256;
       const int h_tm = tall ? tm256 : tm128;
       const int64_t per_h = ((int64_t)h_tm * x2_tn * b.count + NUM_XCD - 1) / NUM_XCD;
       ssh_count = h_tm * x2_tn;

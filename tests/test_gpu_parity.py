@@ -291,16 +291,18 @@ def test_bf16_ragged_blocks_on_matrix_cores():
 
 
 def test_bf16_ragged_blocks_on_tall_tiles():
-    """One 1000 x 520 block: the 256-row tiles of the fp16 products with a partial last tile in
-    both directions (rows 768 ... 999 of 1024, columns 512 ... 519 of 768), k = 1000 and 520 with
-    ragged ends of 8, and the factor kernel's partial tiles at 1000 and 520."""
+    """16 blocks of 1000 x 1000 (and 8 of 1000 x 80): enough tiles for the 256-row variant of the
+    fp16 products, with a partial last tile in both directions (rows 768 ... 999 of 1024, columns
+    768 ... 999 of 1024), k = 1000 with a ragged end of 8, and the factor kernel's partial tiles;
+    the thin bucket takes the 128-row variant."""
     say("case bf16 ragged, 256-row tiles")
-    shapes = [(1000, 520)]
-    p = Pair(shapes, 1024, 0.999, 1, eps=1e-6, bf16=True)
-    for t in range(2):
-        p.step(wl.gaussian_grads(shapes, 22, t, 1e-3), 0.01, t)
-        worst, _ = p.check(t)
-        assert worst["gemm"] <= 2e-5, worst
+    shapes = [(8000, 2080)]
+    p = Pair(shapes, 1000, 0.999, 1, eps=1e-6, bf16=True)
+    table, nb = p.gpu.plan()
+    assert nb == 2 and sum(1 for r in table if int(r[4]) == 1000) == 16
+    p.step(wl.gaussian_grads(shapes, 22, 0, 1e-3), 0.01, 0)
+    worst, _ = p.check(0)
+    assert worst["gemm"] <= 2e-5, worst
 
 
 def test_bf16_products_at_extreme_gradient_scales():
