@@ -29,15 +29,17 @@
 //   T = Lbar G       A = Lbar (two planes)   B = G^T (the scaled fp16 transpose of the block, one plane)
 //   P = T Rbar       A = T (two planes)      B = Rbar (symmetric, two planes)
 //
-// Tile TM x 256 per workgroup, TM = 256 (8 wavefronts, two per SIMD) or 128 (4 wavefronts),
-// 64 x 128 per wavefront (2 x 4 MFMA tiles), one workgroup per CU.  Operand slabs of 32 values
-// of k (64-byte rows) never pass through registers: global_load_lds_dwordx4 writes 16 bytes per
-// lane straight into LDS, the next slab (the next two where three stages fit) in flight while
-// the current one is multiplied.  LDS rows are unpadded (the 64 lanes of such a load fill
-// consecutive addresses); the 16-byte chunk c of row r sits at chunk position
-// c ^ ((r >> 2) & 3): a 16-byte read is served 16 lanes at a time from 64 banks of 4 bytes, the
-// 16 rows of such a group start at banks 16 (r % 4), and rows with equal r % 4 take different
-// chunk positions, so the group covers every bank once (SQ_LDS_BANK_CONFLICT reads 0).
+// Tile TM x 256 per workgroup of 4 wavefronts, one workgroup per CU: TM = 256 with 128 x 128 per
+// wavefront (4 x 4 MFMA tiles, 256 accumulator registers), or TM = 128 with 64 x 128 per
+// wavefront; 8 wavefronts of 64 x 128 on the 256-row tile (two per SIMD) measured the same.
+// Operand slabs of 32 values of k (64-byte rows) never pass through registers:
+// global_load_lds_dwordx4 writes 16 bytes per lane straight into LDS, the next slab (the next
+// two where three stages fit) in flight while the current one is multiplied.  LDS rows are
+// unpadded (the 64 lanes of such a load fill consecutive addresses); the 16-byte chunk c of row
+// r sits at chunk position c ^ ((r >> 2) & 3): a 16-byte read is served 16 lanes at a time from
+// 64 banks of 4 bytes, the 16 rows of such a group start at banks 16 (r % 4), and rows with
+// equal r % 4 take different chunk positions, so the group covers every bank once
+// (SQ_LDS_BANK_CONFLICT reads 0).
 // An MFMA operand is 8 consecutive k of one row per lane: lane = row % 32 + 32 * (k / 8).
 //
 // The LDS reads are scheduled by hand (inline assembly, with the s_waitcnt that belongs to
@@ -167,38 +169,46 @@ __global__ __launch_bounds__(64) void x2_scales_kernel(const X2ScaleArgs g) {
 
 #define X2_DS_READ(dst, addr, imm) LDS_DS_READ_B128(dst, addr, imm)
 #define X2_SB() LDS_SCHED_BARRIER()
-// the two 32-row tiles of plane S of the A slab into ARR[I] / the four of plane U of the B slab
+// the MI 32-row tiles of plane S of the A slab into ARR[I] / the four of plane U of the B slab
 // into DST, at the k step of (LA, LB)
-#define X2_RD_A(ARR, I, S, LA) { X2_DS_READ(ARR[I][0], LA, (S) * A_SLAB); X2_DS_READ(ARR[I][1], LA, (S) * A_SLAB + 2048); }
+#define X2_RD_A(ARR, I, S, LA) { X2_DS_READ(ARR[I][0], LA, (S) * A_SLAB); X2_DS_READ(ARR[I][1], LA, (S) * A_SLAB + 2048); \
+                                 if constexpr (MI == 4) { X2_DS_READ(ARR[I][MI - 2], LA, (S) * A_SLAB + 4096); X2_DS_READ(ARR[I][MI - 1], LA, (S) * A_SLAB + 6144); } }
 #define X2_RD_B(DST, U, LB) { X2_DS_READ(DST[0], LB, (U) * X2_B_SLAB); X2_DS_READ(DST[1], LB, (U) * X2_B_SLAB + 2048); \
                               X2_DS_READ(DST[2], LB, (U) * X2_B_SLAB + 4096); X2_DS_READ(DST[3], LB, (U) * X2_B_SLAB + 6144); }
-// wait until at most N LDS reads are outstanding; the named registers are valid afterwards
-#define X2_WAIT_A(N, ARR, I) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(ARR[I][0]), "+v"(ARR[I][1]) :: "memory")
-#define X2_WAIT_B(N, B_) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(B_[0]), "+v"(B_[1]), "+v"(B_[2]), "+v"(B_[3]) :: "memory")
-#define X2_WAIT_AB(N, ARR, I, B_) asm volatile("s_waitcnt lgkmcnt(" #N ")" : "+v"(ARR[I][0]), "+v"(ARR[I][1]), "+v"(B_[0]), "+v"(B_[1]), "+v"(B_[2]), "+v"(B_[3]) :: "memory")
-// eight MFMAs: the two tiles ARR[I] of a plane of A against the four tiles B_ of a plane of B
+// wait until at most N2 (MI = 2) or N4 (MI = 4) LDS reads are outstanding; the named registers
+// are valid afterwards
+#define X2_WAIT_A(N2, N4, ARR, I) { if constexpr (MI == 2) asm volatile("s_waitcnt lgkmcnt(" #N2 ")" : "+v"(ARR[I][0]), "+v"(ARR[I][1]) :: "memory"); \
+    else asm volatile("s_waitcnt lgkmcnt(" #N4 ")" : "+v"(ARR[I][0]), "+v"(ARR[I][1]), "+v"(ARR[I][MI - 2]), "+v"(ARR[I][MI - 1]) :: "memory"); }
+#define X2_WAIT_B(N2, N4, B_) { if constexpr (MI == 2) asm volatile("s_waitcnt lgkmcnt(" #N2 ")" : "+v"(B_[0]), "+v"(B_[1]), "+v"(B_[2]), "+v"(B_[3]) :: "memory"); \
+    else asm volatile("s_waitcnt lgkmcnt(" #N4 ")" : "+v"(B_[0]), "+v"(B_[1]), "+v"(B_[2]), "+v"(B_[3]) :: "memory"); }
+#define X2_WAIT_AB(N2, N4, ARR, I, B_) { if constexpr (MI == 2) asm volatile("s_waitcnt lgkmcnt(" #N2 ")" : "+v"(ARR[I][0]), "+v"(ARR[I][1]), "+v"(B_[0]), "+v"(B_[1]), "+v"(B_[2]), "+v"(B_[3]) :: "memory"); \
+    else asm volatile("s_waitcnt lgkmcnt(" #N4 ")" : "+v"(ARR[I][0]), "+v"(ARR[I][1]), "+v"(ARR[I][MI - 2]), "+v"(ARR[I][MI - 1]), "+v"(B_[0]), "+v"(B_[1]), "+v"(B_[2]), "+v"(B_[3]) :: "memory"); }
+// 4 MI MFMAs: the MI tiles ARR[I] of a plane of A against the four tiles B_ of a plane of B
 #define X2_GROUP(ARR, I, B_)                                                                              \
   {                                                                                                       \
-    _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                                      \
+    _Pragma("unroll") for (int i_ = 0; i_ < MI; ++i_)                                                     \
       _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_)                                                    \
         acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, ARR[I][i_]),       \
                                                              __builtin_bit_cast(f16x8, B_[j_]), acc[i_][j_], 0, 0, 0); \
   }
 
-// NB: planes of B (2, or 1 for the scaled gradient); A always has two.
-template <int TM, int NB, int EPI>
-__global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args g) {
-  static_assert(TM == 128 || TM == 256, "4 or 8 wavefronts of 64 x 128 each");
+// TM x 256 workgroup tile of wavefront tiles WM x 128.  NB: planes of B (2, or 1 for the scaled
+// gradient); A always has two.
+template <int TM, int WM, int NB, int EPI>
+__global__ __launch_bounds__(TM / WM * 128, 1) void gemm_f16x2_kernel(const GemmX2Args g) {
+  static_assert((TM == 128 && WM == 64) || (TM == 256 && (WM == 64 || WM == 128)), "wavefront tiles of 64 or 128 rows");
   static_assert(NB == 1 || NB == 2, "planes of B");
   constexpr int NA = 2;
-  constexpr int NW = TM / 32;                  // wavefronts, as NW / 2 x 2
-  constexpr int BL = 16 / NW;                  // 1 KiB pieces of a B plane slab that one wavefront loads
+  constexpr int MI = WM / 32;                  // 32-row MFMA tiles per wavefront
+  constexpr int NW = TM / WM * 2;              // wavefronts, as TM / WM x 2
+  constexpr int AL = TM / (16 * NW);           // 1 KiB pieces of an A plane slab that one wavefront loads
+  constexpr int BL = 16 / NW;                  // and of a B plane slab
   constexpr int A_SLAB = TM * X2_BK * 2;       // bytes of one plane of the A slab
   // TM = 128: 48 KB (2 + 2 planes), 32 KB (2 + 1); TM = 256: 64 KB (2 + 2), 48 KB (2 + 1)
   constexpr int STAGE = NA * A_SLAB + NB * X2_B_SLAB;
   constexpr int NST = STAGE > 49152 ? 2 : 3;
   static_assert(NST * STAGE <= 147456, "LDS");
-  constexpr int PW = 2 * NA + BL * NB;         // loads per wavefront per slab
+  constexpr int PW = AL * NA + BL * NB;        // loads per wavefront per slab
   __shared__ __align__(128) unsigned char smem[NST * STAGE];   // the k-step addresses below differ by an XOR
   __shared__ float red[NW];
   const int tiles = g.tiles_m * g.tiles_n;
@@ -219,11 +229,11 @@ __global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args 
   // Rows past the end of the matrix read its last row instead: they only reach elements of
   // the tile that are never stored.
   const int uw = __builtin_amdgcn_readfirstlane(wave);
-  uint32_t offa[2], offb[BL];
-  int chunk_a[2], chunk_b[BL];
+  uint32_t offa[AL], offb[BL];
+  int chunk_a[AL], chunk_b[BL];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int p = (wave * 2 + t) * 64 + lane, row = p >> 2, ch = (p & 3) ^ ((row >> 2) & 3);
+  for (int t = 0; t < AL; ++t) {
+    const int p = (wave * AL + t) * 64 + lane, row = p >> 2, ch = (p & 3) ^ ((row >> 2) & 3);
     chunk_a[t] = ch * 8;
     offa[t] = (uint32_t)(min(row, rows_a - 1) * g.lda + ch * 8) * 2u;
   }
@@ -239,8 +249,8 @@ __global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args 
     for (int s = 0; s < NA; ++s) {
       const char *ga = uniform_ptr(pa + s * g.a_plane_stride + k0);
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
-        __builtin_amdgcn_global_load_lds((glb_void *)(ga + offa[t]), (lds_void *)(st + s * A_SLAB + (uw * 2 + t) * 1024), 16, 0, 0);
+      for (int t = 0; t < AL; ++t)
+        __builtin_amdgcn_global_load_lds((glb_void *)(ga + offa[t]), (lds_void *)(st + s * A_SLAB + (uw * AL + t) * 1024), 16, 0, 0);
     }
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
@@ -254,12 +264,12 @@ __global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args 
   // LDS byte addresses of this lane's operand rows in stage 0, k step 0 (k step 1: ^ 32)
   const int fi = lane & 31, fq = lane >> 5;
   const uint32_t lbase = (uint32_t)(uintptr_t)(lds_void *)smem;
-  const uint32_t la0 = lbase + (wm * 64 + fi) * 64 + ((fq ^ ((fi >> 2) & 3)) * 16);
+  const uint32_t la0 = lbase + (wm * WM + fi) * 64 + ((fq ^ ((fi >> 2) & 3)) * 16);
   const uint32_t lb0 = lbase + NA * A_SLAB + (wn * 128 + fi) * 64 + ((fq ^ ((fi >> 2) & 3)) * 16);
 
-  floatx16 acc[2][4];
+  floatx16 acc[MI][4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -267,13 +277,13 @@ __global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args 
   // operand registers: a[0] / a[1] the planes h / l of A and b0 / b1 those of B at the first k
   // step; ay / by0 the h planes at the second k step, whose l planes go into the registers that
   // b1 and a[0] have left by then
-  u32x4 a[2][2], b0[4], b1[4], ay[1][2], by0[4];
+  u32x4 a[2][MI], b0[4], b1[4], ay[1][MI], by0[4];
 
-  // One 1 KiB piece of the next slab: the loads are spread between the MFMA groups, two after
-  // each, so that a wavefront never queues more than the texture path takes at once (a
-  // wavefront stalled on issuing loads issues no MFMAs either).  With eight wavefronts each
-  // loads two pieces of a B plane, not four: pieces 2 and 3 do not exist then.
-#define X2_DMA_A(S, T) __builtin_amdgcn_global_load_lds((glb_void *)(ga[S] + offa[T]), (lds_void *)(st_in + (S) * A_SLAB + (uw * 2 + (T)) * 1024), 16, 0, 0)
+  // One 1 KiB piece of the next slab: the loads are spread between the MFMA groups, so that a
+  // wavefront never queues more than the texture path takes at once (a wavefront stalled on
+  // issuing loads issues no MFMAs either).  With eight wavefronts each loads two pieces of a
+  // plane, not four: pieces 2 and 3 do not exist then.
+#define X2_DMA_A(S, T) { if constexpr ((T) < AL) __builtin_amdgcn_global_load_lds((glb_void *)(ga[S] + offa[(T) < AL ? (T) : 0]), (lds_void *)(st_in + (S) * A_SLAB + (uw * AL + (T)) * 1024), 16, 0, 0); }
 #define X2_DMA_B(U, T) { if constexpr ((T) < BL) __builtin_amdgcn_global_load_lds((glb_void *)(gb[U] + offb[(T) < BL ? (T) : 0]), (lds_void *)(st_in + NA * A_SLAB + (U) * X2_B_SLAB + (uw * BL + (T)) * 1024), 16, 0, 0); }
   // The products of one slab (two k steps of 16) in the stage at byte offset `so`, and, if
   // `feed`, the loads of the slab at k0 into the stage at `st_in`.
@@ -285,32 +295,38 @@ __global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args 
 #pragma unroll
     for (int u = 0; u < NB; ++u) gb[u] = uniform_ptr(pb + u * g.b_plane_stride + k0);
     if constexpr (NB == 1) {
-      // planes (h, l) of A against the single plane of B
+      // planes (h, l) of A against the single plane of B; the wait counts are the reads issued
+      // after the ones waited for (MI per A plane, 4 per B plane)
       X2_RD_A(a, 0, 0, la); X2_RD_B(b0, 0, lb); X2_RD_A(a, 1, 1, la);
       X2_SB();
-      X2_WAIT_AB(2, a, 0, b0); X2_SB();                 // outstanding after ah, b: al = 2
-      X2_GROUP(a, 0, b0); X2_RD_A(ay, 0, 0, la1); X2_RD_B(by0, 0, lb1); if (feed) { X2_DMA_A(0, 0); X2_DMA_A(0, 1); } X2_SB();
-      X2_WAIT_A(6, a, 1); X2_SB();                      // ah' b' = 6
-      X2_GROUP(a, 1, b0); X2_RD_A(a, 0, 1, la1); if (feed) { X2_DMA_A(1, 0); X2_DMA_A(1, 1); } X2_SB();   // al' into a[0]
-      X2_WAIT_AB(2, ay, 0, by0); X2_SB();               // al' = 2
+      X2_WAIT_AB(2, 4, a, 0, b0); X2_SB();              // outstanding after ah, b: al
+      X2_GROUP(a, 0, b0); X2_RD_A(ay, 0, 0, la1); X2_RD_B(by0, 0, lb1);
+      if (feed) { X2_DMA_A(0, 0); X2_DMA_A(0, 1); X2_DMA_A(0, 2); X2_DMA_A(0, 3); } X2_SB();
+      X2_WAIT_A(6, 8, a, 1); X2_SB();                   // ah' b'
+      X2_GROUP(a, 1, b0); X2_RD_A(a, 0, 1, la1);        // al' into a[0]
+      if (feed) { X2_DMA_A(1, 0); X2_DMA_A(1, 1); X2_DMA_A(1, 2); X2_DMA_A(1, 3); } X2_SB();
+      X2_WAIT_AB(2, 4, ay, 0, by0); X2_SB();            // al'
       X2_GROUP(ay, 0, by0); if (feed) { X2_DMA_B(0, 0); X2_DMA_B(0, 1); } X2_SB();
-      X2_WAIT_A(0, a, 0); X2_SB();
+      X2_WAIT_A(0, 0, a, 0); X2_SB();
       X2_GROUP(a, 0, by0); if (feed) { X2_DMA_B(0, 2); X2_DMA_B(0, 3); } X2_SB();
     } else {
       // planes (h, l) of both operands: the pairs (h,h) (h,l) (l,h)
       X2_RD_A(a, 0, 0, la); X2_RD_B(b0, 0, lb); X2_RD_B(b1, 1, lb); X2_RD_A(a, 1, 1, la);
       X2_SB();
-      X2_WAIT_AB(6, a, 0, b0); X2_SB();                 // outstanding after ah, bh: bl al = 6
-      X2_GROUP(a, 0, b0); X2_RD_A(ay, 0, 0, la1); X2_RD_B(by0, 0, lb1); if (feed) { X2_DMA_A(0, 0); X2_DMA_A(0, 1); } X2_SB();
-      X2_WAIT_B(8, b1); X2_SB();                        // al ah' bh' = 8
-      X2_GROUP(a, 0, b1); X2_RD_B(b1, 1, lb1); if (feed) { X2_DMA_A(1, 0); X2_DMA_A(1, 1); } X2_SB();     // bl' into b1
-      X2_WAIT_A(10, a, 1); X2_SB();                     // ah' bh' bl' = 10
-      X2_GROUP(a, 1, b0); X2_RD_A(a, 0, 1, la1); if (feed) { X2_DMA_B(0, 0); X2_DMA_B(0, 1); } X2_SB();   // al' into a[0]
-      X2_WAIT_AB(6, ay, 0, by0); X2_SB();               // bl' al' = 6
+      X2_WAIT_AB(6, 8, a, 0, b0); X2_SB();              // outstanding after ah, bh: bl al
+      X2_GROUP(a, 0, b0); X2_RD_A(ay, 0, 0, la1); X2_RD_B(by0, 0, lb1);
+      if (feed) { X2_DMA_A(0, 0); X2_DMA_A(0, 1); X2_DMA_A(0, 2); X2_DMA_A(0, 3); } X2_SB();
+      X2_WAIT_B(8, 12, b1); X2_SB();                    // al ah' bh'
+      X2_GROUP(a, 0, b1); X2_RD_B(b1, 1, lb1);          // bl' into b1
+      if (feed) { X2_DMA_A(1, 0); X2_DMA_A(1, 1); X2_DMA_A(1, 2); X2_DMA_A(1, 3); } X2_SB();
+      X2_WAIT_A(10, 12, a, 1); X2_SB();                 // ah' bh' bl'
+      X2_GROUP(a, 1, b0); X2_RD_A(a, 0, 1, la1);        // al' into a[0]
+      if (feed) { X2_DMA_B(0, 0); X2_DMA_B(0, 1); } X2_SB();
+      X2_WAIT_AB(6, 8, ay, 0, by0); X2_SB();            // bl' al'
       X2_GROUP(ay, 0, by0); if (feed) { X2_DMA_B(0, 2); X2_DMA_B(0, 3); } X2_SB();
-      X2_WAIT_B(2, b1); X2_SB();                        // al' = 2
+      X2_WAIT_B(2, 4, b1); X2_SB();                     // al'
       X2_GROUP(ay, 0, b1); if (feed) { X2_DMA_B(1, 0); X2_DMA_B(1, 1); } X2_SB();
-      X2_WAIT_A(0, a, 0); X2_SB();
+      X2_WAIT_A(0, 0, a, 0); X2_SB();
       X2_GROUP(a, 0, by0); if (feed) { X2_DMA_B(1, 2); X2_DMA_B(1, 3); } X2_SB();
     }
   };
@@ -327,11 +343,11 @@ __global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args 
 #pragma unroll
     for (int s = 0; s < NA; ++s)
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+      for (int t = 0; t < AL; ++t) {
         const bool kin = k0 + chunk_a[t] < g.K;    // K % 8 == 0: a chunk is entirely in or out
         const uint4 v = kin ? *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(pa + s * g.a_plane_stride + k0) + offa[t])
                             : make_uint4(0, 0, 0, 0);
-        *reinterpret_cast<uint4 *>(st + s * A_SLAB + (wave * 2 + t) * 1024 + lane * 16) = v;
+        *reinterpret_cast<uint4 *>(st + s * A_SLAB + (wave * AL + t) * 1024 + lane * 16) = v;
       }
 #pragma unroll
     for (int u = 0; u < NB; ++u)
@@ -359,17 +375,20 @@ __global__ __launch_bounds__(TM * 2, 1) void gemm_f16x2_kernel(const GemmX2Args 
   LDS_DMA_WAIT_VM(0);
 
   // epilogue: accumulator element v of MFMA tile (mi, ni) is
-  // row = wm*64 + mi*32 + 8*(v/4) + 4*(lane/32) + v%4, col = wn*128 + ni*32 + lane%32
+  // row = wm*WM + mi*32 + 8*(v/4) + 4*(lane/32) + v%4, col = wn*128 + ni*32 + lane%32
+  // (one store instruction covers two rows of 32 consecutive columns: whole 128-byte lines
+  // for the float32 result; storing runs of four columns per lane from transposed result
+  // tiles takes a quarter of the instructions and measured slower, 5.0 -> 5.8 ms for T)
   float ss = 0.f;
   const float alpha = g.out_scale ? g.alpha * g.out_scale[b] : g.alpha;
 #pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
+  for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
       const int j = col0 + wn * 128 + ni * 32 + (lane & 31);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int i = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int i = row0 + wm * WM + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
         if (i < g.M && j < g.N) {
           const float x = alpha * acc[mi][ni][v];
           const int64_t at = (int64_t)b * g.c_batch_stride + (int64_t)i * g.ldc + j;

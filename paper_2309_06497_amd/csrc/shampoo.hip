@@ -1274,9 +1274,9 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       g.M = b.m; g.N = b.n; g.K = b.m; g.alpha = c1; g.out_scale = reinterpret_cast<const float *>(ws + b.off_t_scale);
       g.tiles_m = h_tm; g.tiles_n = x2_tn; g.batch = b.count;
       if (tall)
-        hipLaunchKernelGGL((gemm_f16x2_kernel<256, 1, X2_STORE_SPLIT>), dim3((unsigned)(per_h * NUM_XCD)), dim3(512), 0, s, g);
+        hipLaunchKernelGGL((gemm_f16x2_kernel<256, 128, 1, X2_STORE_SPLIT>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, g);
       else
-        hipLaunchKernelGGL((gemm_f16x2_kernel<128, 1, X2_STORE_SPLIT>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, g);
+        hipLaunchKernelGGL((gemm_f16x2_kernel<128, 64, 1, X2_STORE_SPLIT>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, g);
       }
       StageTimer t2(o, SHAMPOO_STAGE_PRECOND2, s);
       GemmX2Args h{};
@@ -1288,9 +1288,9 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       h.norm_partial = reinterpret_cast<float *>(ws + b.off_sshp);
       h.tiles_m = h_tm; h.tiles_n = x2_tn; h.batch = b.count;
       if (tall)
-        hipLaunchKernelGGL((gemm_f16x2_kernel<256, 2, X2_STORE_NORM>), dim3((unsigned)(per_h * NUM_XCD)), dim3(512), 0, s, h);
+        hipLaunchKernelGGL((gemm_f16x2_kernel<256, 128, 2, X2_STORE_NORM>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, h);
       else
-        hipLaunchKernelGGL((gemm_f16x2_kernel<128, 2, X2_STORE_NORM>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, h);
+        hipLaunchKernelGGL((gemm_f16x2_kernel<128, 64, 2, X2_STORE_NORM>), dim3((unsigned)(per_h * NUM_XCD)), dim3(256), 0, s, h);
       HIP_TRY(hipGetLastError());
     } else if (use_shampoo) {
       {
