@@ -5,8 +5,11 @@
 // accumulation is as careful as on the float32 path: here two chained MFMAs (32
 // values of k) are accumulated in float32 and then added into float64 registers,
 // and beta2 L + (1 - beta2) S is evaluated in float64 before the single rounding
-// to float32.  R = G^T G runs through the same kernel on a bf16 transpose of the
-// block (transpose_bf16_kernel), so both operands are always read along k.
+// to float32.  R = G^T G runs through the same kernel on a 16-bit transpose of the
+// block (transpose_bf16_kernel), so both operands are always read along k; where the
+// fp16 preconditioning products follow, that transpose holds fp16(s G) with a power of
+// two s per block (8 significant bits go into 11, so nothing is lost unless it
+// underflows), the fp16 instruction is used and 1 / s^2 is applied with alpha.
 //
 // Tile 128 x 128 per workgroup of 4 wavefronts (64 x 64 each, 2 x 2 MFMA tiles).
 // The operand slabs (128 rows x 32 k of each operand) never pass through registers:
@@ -17,8 +20,8 @@
 // chunk position c ^ ((r >> 2) & 3) of its 64-byte LDS row (the lane picks its global
 // address accordingly).  A 16-byte read is served 16 lanes at a time from 64 banks of 4 bytes:
 // the 16 rows of such a group start at banks 16 (r % 4), and rows with equal r % 4 take
-// different chunk positions, so the group covers every bank once (SQ_LDS_BANK_CONFLICT = 0).  An MFMA operand is 8 consecutive k of one row per lane:
-// lane = row % 32 + 32 * (k / 8).
+// different chunk positions, so the group covers every bank once.  An MFMA operand is 8
+// consecutive k of one row per lane: lane = row % 32 + 32 * (k / 8).
 //
 // The compiler's own wait-count placement would wait for every outstanding load before
 // the first LDS read of a slab (it cannot tell the stages apart), so the LDS reads of the
