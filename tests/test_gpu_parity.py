@@ -305,6 +305,21 @@ def test_bf16_ragged_blocks_on_tall_tiles():
     assert worst["gemm"] <= 2e-5, worst
 
 
+def test_bf16_thin_blocks_on_tall_tiles():
+    """128 blocks of 512 x 40: the 256-row tiles with a B operand of 40 rows inside a 256-column
+    tile (rows past the end read the last valid one), k = 512 and k = 40 (one full slab and a
+    ragged end of 8)."""
+    say("case bf16 thin blocks, 256-row tiles")
+    shapes = [(65536, 40)]
+    p = Pair(shapes, 512, 0.999, 1, eps=1e-6, bf16=True)
+    table, nb = p.gpu.plan()
+    assert nb == 1 and len(table) == 128
+    for t in range(2):
+        p.step(wl.gaussian_grads(shapes, 23, t, 1e-3), 0.01, t)
+        worst, _ = p.check(t)
+        assert worst["gemm"] <= 2e-5, worst
+
+
 def test_bf16_products_at_extreme_gradient_scales():
     """The preconditioning products of bf16 gradients run on fp16 planes scaled by powers of two
     (from max |G| of the block and from the roots' largest elements).  Gradients of size 1e-15
