@@ -47,6 +47,13 @@ constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver (n <= 128), float64 
 constexpr double JAC_BLOCK_TOL_REL = 1e-7;
 constexpr double JAC_SMALL_TOL_ABS = 1e-15;
 
+// blocks of the two-sided update per thread: s / 2 (s / 2 + 1) / 2 blocks must fit on the
+// workgroup, which holds for the two uses (s <= 64 on 256 threads, s <= 128 on 1024)
+constexpr int JAC_BLOCKS_PER_THREAD = 3;
+static_assert((JAC_PIV / 2) * (JAC_PIV / 2 + 1) / 2 <= JAC_BLOCKS_PER_THREAD * JAC_PIV_THREADS, "pivot blocks per thread");
+static_assert(32 * 33 / 2 <= JAC_BLOCKS_PER_THREAD * 256 && (JAC_SMALL_MAX / 2) * (JAC_SMALL_MAX / 2 + 1) / 2 <= JAC_BLOCKS_PER_THREAD * 1024,
+              "LDS solver blocks per thread");
+
 struct JacScratch {      // small per-workgroup LDS arrays
   double s[JAC_SMALL_MAX / 2];
   double t[JAC_SMALL_MAX / 2];
@@ -105,6 +112,22 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
   const int half = s >> 1;
   auto at = [LDA](int i, int j) { return SQUARE ? i * LDA + j : tri(i, j); };
   int any = 0;
+  // this thread's blocks (k, l), l <= k, of the two-sided update: numbers tid, tid + NT, ...
+  // of the half (half + 1) / 2 blocks (at most UB each: 528 on 256 threads at s = 64, 2080 on
+  // 1024 at s = 128)
+  constexpr int UB = JAC_BLOCKS_PER_THREAD;
+  int bk[UB], bl[UB];
+#pragma unroll
+  for (int u = 0; u < UB; ++u) {
+    const int bnum = tid + u * NT;
+    bk[u] = -1; bl[u] = 0;
+    if (bnum < half * (half + 1) / 2) {
+      int k = (int)((sqrtf(8.f * (float)bnum + 1.f) - 1.f) * 0.5f);
+      while ((k + 1) * (k + 2) / 2 <= bnum) ++k;
+      while (k * (k + 1) / 2 > bnum) --k;
+      bk[u] = k; bl[u] = bnum - k * (k + 1) / 2;
+    }
+  }
   for (int sw = 0; sw < max_sweeps; ++sw) {
     if (tid == 0) sc->flag = 0;
     if (tid < 4) sc->rounds[tid] = 0u;
@@ -156,47 +179,46 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
         sc->s[tid] = sn; sc->t[tid] = tp; sc->p[tid] = p; sc->q[tid] = q;
       }
       __syncthreads();
-      // A <- R^T A R on the blocks with l <= k.  Blocks are independent, so a thread first
-      // loads all of its blocks of a pass, then rotates, then stores (the loads overlap).
-      constexpr int U = NT >= 1024 ? 2 : 4;
-      for (int l = tid & 31; l < half; l += 32) {
-        const int pl = sc->p[l], ql = sc->q[l];
-        const double sl = sc->s[l], tl = sc->t[l];
-        for (int k0 = tid >> 5; k0 < half; k0 += (NT / 32) * U) {
-          double a[U], b[U], c[U], d[U], sk[U], tk[U];
-          int ia[U], ib[U], ic[U], id[U], pk[U], qk[U];
-          bool act[U];
+      // A <- R^T A R on the blocks (k, l) with l <= k, dealt evenly over the threads (block
+      // k (k + 1) / 2 + l to thread (that number) mod NT: a (k, l) grid with the half above the
+      // diagonal switched off would cost every wavefront all of its slots).  Blocks are
+      // independent, so a thread first loads all of its blocks, then rotates, then stores (the
+      // loads overlap).
+      {
+        double a[UB], b[UB], c[UB], d[UB], sk[UB], tk[UB], sl[UB], tl[UB];
+        int ia[UB], ib[UB], ic[UB], id[UB], pk[UB], qk[UB], pl[UB], ql[UB];
+        bool act[UB];
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const int k = k0 + (NT / 32) * u;
-            act[u] = k < half && l <= k;
+        for (int u = 0; u < UB; ++u) {
+          act[u] = bk[u] >= 0;
+          if (act[u]) {
+            const int k = bk[u], l = bl[u];
+            sk[u] = sc->s[k]; sl[u] = sc->s[l];
+            act[u] = !(sk[u] == 0.0 && sl[u] == 0.0);
             if (act[u]) {
-              pk[u] = sc->p[k]; qk[u] = sc->q[k]; sk[u] = sc->s[k]; tk[u] = sc->t[k];
-              act[u] = !(sk[u] == 0.0 && sl == 0.0);
-            }
-            if (act[u]) {
-              ia[u] = at(pk[u], pl); ib[u] = at(pk[u], ql); ic[u] = at(qk[u], pl); id[u] = at(qk[u], ql);
+              pk[u] = sc->p[k]; qk[u] = sc->q[k]; tk[u] = sc->t[k];
+              pl[u] = sc->p[l]; ql[u] = sc->q[l]; tl[u] = sc->t[l];
+              ia[u] = at(pk[u], pl[u]); ib[u] = at(pk[u], ql[u]); ic[u] = at(qk[u], pl[u]); id[u] = at(qk[u], ql[u]);
               a[u] = At[ia[u]]; b[u] = At[ib[u]]; c[u] = At[ic[u]]; d[u] = At[id[u]];
             }
           }
+        }
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            if (!act[u]) continue;
-            const int k = k0 + (NT / 32) * u;
-            // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
-            const double a1 = a[u] - sk[u] * (c[u] + tk[u] * a[u]), c1 = c[u] + sk[u] * (a[u] - tk[u] * c[u]);
-            const double b1 = b[u] - sk[u] * (d[u] + tk[u] * b[u]), d1 = d[u] + sk[u] * (b[u] - tk[u] * d[u]);
-            // columns: (a1, b1) and (c1, d1) are (x, y) pairs of rotation l
-            const double a2 = a1 - sl * (b1 + tl * a1), b2 = b1 + sl * (a1 - tl * b1);
-            const double c2 = c1 - sl * (d1 + tl * c1), d2 = d1 + sl * (c1 - tl * d1);
-            if (k == l) {   // pivot block: (p, q) and (q, p) are the annihilated element
-              At[ia[u]] = a2; At[ib[u]] = 0.0; At[id[u]] = d2;
-              if (SQUARE) At[ic[u]] = 0.0;
-            } else {
-              At[ia[u]] = a2; At[ib[u]] = b2; At[ic[u]] = c2; At[id[u]] = d2;
-              if (SQUARE) {
-                At[at(pl, pk[u])] = a2; At[at(ql, pk[u])] = b2; At[at(pl, qk[u])] = c2; At[at(ql, qk[u])] = d2;
-              }
+        for (int u = 0; u < UB; ++u) {
+          if (!act[u]) continue;
+          // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
+          const double a1 = a[u] - sk[u] * (c[u] + tk[u] * a[u]), c1 = c[u] + sk[u] * (a[u] - tk[u] * c[u]);
+          const double b1 = b[u] - sk[u] * (d[u] + tk[u] * b[u]), d1 = d[u] + sk[u] * (b[u] - tk[u] * d[u]);
+          // columns: (a1, b1) and (c1, d1) are (x, y) pairs of rotation l
+          const double a2 = a1 - sl[u] * (b1 + tl[u] * a1), b2 = b1 + sl[u] * (a1 - tl[u] * b1);
+          const double c2 = c1 - sl[u] * (d1 + tl[u] * c1), d2 = d1 + sl[u] * (c1 - tl[u] * d1);
+          if (bk[u] == bl[u]) {   // pivot block: (p, q) and (q, p) are the annihilated element
+            At[ia[u]] = a2; At[ib[u]] = 0.0; At[id[u]] = d2;
+            if (SQUARE) At[ic[u]] = 0.0;
+          } else {
+            At[ia[u]] = a2; At[ib[u]] = b2; At[ic[u]] = c2; At[id[u]] = d2;
+            if (SQUARE) {
+              At[at(pl[u], pk[u])] = a2; At[at(ql[u], pk[u])] = b2; At[at(pl[u], qk[u])] = c2; At[at(ql[u], qk[u])] = d2;
             }
           }
         }
