@@ -74,6 +74,29 @@ __device__ __host__ __forceinline__ void rr_pair(int cnt, int r, int k, int &p, 
   if (p > q) { const int t = p; p = q; q = t; }
 }
 
+// The pivots of the block solver are made of two index halves whose diagonal blocks were
+// diagonalised by the pivots before (up to what one sweep leaves behind), so their sweeps
+// take the pairs in a different order: rounds 0 .. s / 2 - 1 hold the pairs across the halves
+// (index k of the first with index (k + r) mod s / 2 of the second), rounds s / 2 .. s - 2 the
+// pairs within the halves (both halves play the same tournament at once).  From the second
+// visit on the rounds within the halves find nothing above the threshold and are skipped whole.
+// s / 2 must be a power of two.
+__device__ __forceinline__ void halves_pair(int s, int r, int k, int &p, int &q) {
+  const int h = s >> 1;
+  if (r < h) { p = k; q = h + ((k + r) & (h - 1)); }
+  else {
+    rr_pair(h, r - h, k & ((h >> 1) - 1), p, q);
+    if (k >= (h >> 1)) { p += h; q += h; }
+  }
+}
+// the round in which halves_pair brings i and j together (j < i)
+__device__ __forceinline__ int halves_round(int s, int i, int j) {
+  const int h = s >> 1;
+  if (j < h && i >= h) return (i - h - j) & (h - 1);
+  const int il = i & (h - 1), jl = j & (h - 1);
+  return h + ((il == h - 1) ? jl : ((il + jl) * (h >> 1)) % (h - 1));
+}
+
 // 1 / sqrt(x) and 1 / x for finite x > 0 (x != 0 for the reciprocal) to float64 accuracy:
 // hardware estimate + three Newton steps (each squares the relative error)
 __device__ __forceinline__ double rsqrt_newton(double x) {
@@ -105,7 +128,8 @@ __device__ __forceinline__ int tri(int i, int j) {
 // LDS access of a round is then bank-conflict free, at twice the footprint; the
 // mirror image of each updated block is written as well.
 // Returns nonzero if any rotation was applied.  All NT threads of the workgroup must call it.
-template <bool SQUARE, int NT>
+// HALVES: the pair order of halves_pair instead of the plain tournament.
+template <bool SQUARE, int NT, bool HALVES = false>
 __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const int LDA, int max_sweeps,
                              double tol_rel, double tol_abs, JacScratch *sc) {
   const int tid = threadIdx.x;
@@ -146,7 +170,7 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
         if (j >= i) continue;                           // j < i < s
         const double aij = fabs(At[at(i, j)]);
         if (aij > tol_abs && aij * aij > tol_rel * tol_rel * fabs(At[at(i, i)] * At[at(j, j)])) {
-          const int r = (i == s - 1) ? j : ((i + j) * half) % (s - 1);
+          const int r = HALVES ? halves_round(s, i, j) : (i == s - 1) ? j : ((i + j) * half) % (s - 1);
           atomicOr(&sc->rounds[r >> 5], 1u << (r & 31));
         }
       }
@@ -156,7 +180,7 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
       if (!((sc->rounds[r >> 5] >> (r & 31)) & 1u)) continue;      // uniform
       if (tid < half) {
         int p, q;
-        rr_pair(s, r, tid, p, q);   // p < q
+        if (HALVES) halves_pair(s, r, tid, p, q); else rr_pair(s, r, tid, p, q);   // p < q
         const double app = At[at(p, p)], aqq = At[at(q, q)], apq = At[at(q, p)];
         double sn = 0.0, tp = 0.0;
         const double aa = fabs(apq);
@@ -483,7 +507,7 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
   }
   __syncthreads();
   const double dm = (double)g.dmax[b];
-  const int any = jacobi_sweeps<true, JAC_PIV_THREADS>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, g.tol_rel,
+  const int any = jacobi_sweeps<true, JAC_PIV_THREADS, true>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, g.tol_rel,
                                       JAC_SMALL_TOL_ABS * dm, &sc);
   __syncthreads();
   if (tid == 0) {
