@@ -37,7 +37,7 @@ constexpr int JAC_PIV = 2 * JAC_NB;   // pivot size
 constexpr int JAC_SMALL_MAX = 128;    // largest n solved entirely in LDS
 constexpr int JAC_SMALL_SWEEPS = 20;
 constexpr int JAC_OUTER_SWEEPS = 16;
-constexpr int JAC_INNER_SWEEPS = 1;
+constexpr int JAC_INNER_SWEEPS = 1;    // 2: 256 roots of n = 1024 in 1.00 s instead of 0.80 s
 // rotation thresholds |a_pq| > rel * sqrt(|a_pp a_qq|) and > abs * max|diag(input)|
 constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver (n <= 128), float64 copy of the factor
 // Block solver: an off-diagonal element left at tau sqrt(a_ii a_jj) tilts the two
@@ -552,22 +552,6 @@ __device__ __forceinline__ void copy_subblock(double *w, int np, double *X, int 
   }
 }
 
-// The MFMA operand registers of a rotation block for one wavefront quadrant: element
-// [2 * (kk / 4) + h] = J[kk + lane / 16][off + 16 h + lane % 16], read straight from global
-// memory (the 16 KB block is shared by every pair-block of its row and column, so it
-// stays in L2); the identity if that pivot did not rotate.
-__device__ __forceinline__ void load_rotation_regs(float (&jr)[32], const float *jb, int idx, bool ident, int off,
-                                                   int lane) {
-  const int li = lane & 15, lk = lane >> 4;
-#pragma unroll
-  for (int q = 0; q < 16; ++q)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int row = 4 * q + lk, col = off + 16 * h + li;
-      jr[2 * q + h] = ident ? (row == col ? 1.f : 0.f) : jb[((int64_t)idx * JAC_PIV + row) * JAC_PIV + col];
-    }
-}
-
 // One 32 x 32 sub-block of W on its way to / from the LDS tile X (64 x 64, stride APP_LD),
 // split into a global -> register half and a register -> LDS half so that the global loads
 // of the next pair-block can be in flight while the current one is multiplied.
@@ -604,22 +588,39 @@ inline int appw_segments(int hp) {
   return s;
 }
 
+constexpr int APP_JLD = JAC_PIV + 4;   // LDS row stride of J_l: rows 4 apart start 16 banks apart
+
 // W_kl <- J_k^T W_kl J_l for the pair-blocks l <= k of one matrix, in float64 on the
 // matrix cores.  grid (appw_segments(hp), batch): a workgroup walks up to APPW_SEG
-// consecutive pair-blocks of block row k.  J_k stays in registers for the whole walk, and
-// while one pair-block is multiplied the W tile of the next one is already being fetched
-// into registers (its J_l follows as soon as the current one has been consumed), so the HBM latency is paid once per workgroup rather than
-// once per pair-block.  Wavefront (wi, wj) owns the 32 x 32 quadrant as 2 x 2 tiles of
-// 16 x 16; a 16x16x4 MFMA takes A(i, k) from lane (i = lane % 16, k = lane / 16), B(k, j)
-// likewise, and leaves D(4 (lane / 16) + v, lane % 16) in element v of the lane's result.
+// consecutive pair-blocks of block row k; while one pair-block is multiplied the W tile and
+// the J_l of the next one are already on their way into registers, so the HBM latency is
+// paid once per workgroup rather than once per pair-block.
+//
+// A 16x16x4 float64 MFMA takes A(i, k) from lane (i = lane % 16, k = lane / 16), B(k, j)
+// likewise (j = lane % 16), and leaves D(lane / 16 + 4 v, lane % 16) in element v of the
+// lane's result.  Wavefront w owns rows 16 w .. 16 w + 15 of the result and needs no exchange
+// with the others between the two products:
+//   first   T^T = X^T J_k, as four 16 x 16 tiles t over the columns kk of X, restricted to the
+//           wavefront's 16 columns i of J_k (16 registers, loaded once per walk):
+//           element v of tile t is T[16 w + lane % 16][16 t + g + 4 v], g = lane / 16;
+//   second  C = T J_l: that element is, as it stands, the A operand of a k step that covers
+//           the four values kk = 16 t + g + 4 v, g = 0 .. 3 (a sum may take its terms in any
+//           order as long as both operands agree); B is J_l[16 t + g + 4 v][16 u + lane % 16],
+//           read from LDS, where row 16 t + g + 4 v is kept at row 16 t + 4 g + v so that the
+//           four rows of a read start 16 banks apart.
+// The result leaves the registers straight for W: element v of tile u is
+// C[16 w + g + 4 v][16 u + lane % 16], i.e. half a row of a stored sub-block per 16 lanes (where
+// the sub-block is stored transposed: 32 consecutive bytes per 4 lanes).  Only the pair-block on
+// the diagonal (k = l) goes back through LDS, where it is completed from its lower half so
+// that the diagonal sub-blocks stay exactly symmetric.
 __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const BlockJacArgs g) {
-  __shared__ __align__(32) double X[JAC_PIV * APP_LD];   // W_kl, then (J_k^T W_kl)^T, then the result
+  __shared__ __align__(32) double X[JAC_PIV * APP_LD];   // W_kl (and the result of a diagonal pair-block)
+  __shared__ __align__(16) float Jl[JAC_PIV * APP_JLD];
   const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wi = wave >> 1, wj = wave & 1;
   const int32_t *ident = g.ident + b * hp;
   const float *jb = g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV;
   // segment -> (k, first l)
@@ -643,105 +644,98 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
   int pk, qk;
   rr_pair(nblk, g.round, k, pk, qk);
 
-  float jk[32], jl[32];
+  const int li = lane & 15, lg = lane >> 4;
+  float jk[16];                   // J_k[4 q + lg][16 wave + li]; the identity if that pivot did not rotate
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int row = 4 * q + lg, col = 16 * wave + li;
+    jk[q] = idk ? (row == col ? 1.f : 0.f) : jb[((int64_t)k * JAC_PIV + row) * JAC_PIV + col];
+  }
   double wt[4][4];
-  const int li = lane & 15, lk = lane >> 4;
-  load_rotation_regs(jk, jb, k, idk, wi * 32, lane);
-  {
+  float4 jn[4];
+  const int jr = tid >> 4, jc4 = (tid & 15) * 4;
+  auto fetch = [&](int lx) {
     int pl, ql;
-    rr_pair(nblk, g.round, l, pl, ql);
+    rr_pair(nblk, g.round, lx, pl, ql);
     sub_fetch(w, np, pk, pl, tid, wt[0]);
     sub_fetch(w, np, pk, ql, tid, wt[1]);
     sub_fetch(w, np, qk, pl, tid, wt[2]);
     sub_fetch(w, np, qk, ql, tid, wt[3]);
-    load_rotation_regs(jl, jb, l, ident[l] != 0, wj * 32, lane);
-  }
+    const bool idl = ident[lx] != 0;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int i = jr + 16 * h;
+      if (idl) jn[h] = make_float4(i == jc4 ? 1.f : 0.f, i == jc4 + 1 ? 1.f : 0.f, i == jc4 + 2 ? 1.f : 0.f, i == jc4 + 3 ? 1.f : 0.f);
+      else jn[h] = *reinterpret_cast<const float4 *>(jb + ((int64_t)lx * JAC_PIV + i) * JAC_PIV + jc4);
+    }
+  };
+  fetch(l);
   for (bool first = true; l < l_end; first = false) {
     const int ln = next_active(l + 1);   // l_end if this is the last one
     int pl, ql;
     rr_pair(nblk, g.round, l, pl, ql);
-    if (!first) __syncthreads();   // the previous result has left X
+    if (!first) __syncthreads();   // every wavefront is done with X and J_l of the pair-block before
     sub_stash(X, pk, pl, 0, 0, tid, wt[0]);
     sub_stash(X, pk, ql, 0, JAC_NB, tid, wt[1]);
     sub_stash(X, qk, pl, JAC_NB, 0, tid, wt[2]);
     sub_stash(X, qk, ql, JAC_NB, JAC_NB, tid, wt[3]);
+#pragma unroll
+    for (int h = 0; h < 4; ++h) *reinterpret_cast<float4 *>(&Jl[(16 * h + 4 * (jr & 3) + (jr >> 2)) * APP_JLD + jc4]) = jn[h];
     __syncthreads();
-    if (ln < l_end) {               // next W tile: in flight during the products below
-      int pn, qn;
-      rr_pair(nblk, g.round, ln, pn, qn);
-      sub_fetch(w, np, pk, pn, tid, wt[0]);
-      sub_fetch(w, np, pk, qn, tid, wt[1]);
-      sub_fetch(w, np, qk, pn, tid, wt[2]);
-      sub_fetch(w, np, qk, qn, tid, wt[3]);
-    }
-    doublex4 acc[2][2];
-    // T = J_k^T X :  A(i, kk) = Jk[kk][i], B(kk, j) = X[kk][j]
+    if (ln < l_end) fetch(ln);     // in flight during the products below
+
+    doublex4 t1[4], c2[4];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < 4; ++t) { t1[t] = (doublex4){0.0, 0.0, 0.0, 0.0}; c2[t] = (doublex4){0.0, 0.0, 0.0, 0.0}; }
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      const int row = (4 * q + lk) * APP_LD;
-      // widened at the point of use: kept as float64 across the walk, J_k alone would hold 64 registers
-      float f0 = jk[2 * q], f1 = jk[2 * q + 1];
-      asm volatile("" : "+v"(f0), "+v"(f1));
-      const double a0 = (double)f0, a1 = (double)f1;
-      const double b0 = X[row + wj * 32 + li], b1 = X[row + wj * 32 + 16 + li];
-      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+      float f = jk[q];
+      asm volatile("" : "+v"(f));          // widened at the point of use, not held as float64 across the walk
+      const double bq = (double)f;
+      const double *xr = &X[(4 * q + lg) * APP_LD + li];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) t1[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(xr[16 * t], bq, t1[t], 0, 0, 0);
     }
-    __syncthreads();   // all reads of X done
-    // X <- T^T : lane holds T(i0 .. i0+3, j)
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const int i0 = wi * 32 + a * 16 + 4 * lk, j = wj * 32 + e * 16 + li;
-        *reinterpret_cast<doublex4 *>(&X[j * APP_LD + i0]) = acc[a][e];
+      for (int v = 0; v < 4; ++v) {
+        const float *jrow = &Jl[(16 * t + 4 * lg + v) * APP_JLD + li];   // row 16 t + lg + 4 v of J_l (stored permuted)
+        const double av = t1[t][v];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) c2[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, (double)jrow[16 * u], c2[u], 0, 0, 0);
       }
-    __syncthreads();
-    // C = T J_l :  A(i, kk) = X[kk][i] (= T[i][kk]), B(kk, j) = Jl[kk][j]
+    if (k != l) {
+      const int ra = wave < 2 ? pk : qk;
+      const int ii0 = (16 * wave & 31) + lg;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+      for (int u = 0; u < 4; ++u) {
+        const int cb = u < 2 ? pl : ql;
+        const int jj = (16 * u & 31) + li;
+        if (ra > cb) {
 #pragma unroll
-      for (int e = 0; e < 2; ++e) acc[a][e] = (doublex4){0.0, 0.0, 0.0, 0.0};
+          for (int v = 0; v < 4; ++v) w[(int64_t)(ra * JAC_NB + ii0 + 4 * v) * np + cb * JAC_NB + jj] = c2[u][v];
+        } else {        // stored transposed
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int row = (4 * q + lk) * APP_LD;
-      const double a0 = X[row + wi * 32 + li], a1 = X[row + wi * 32 + 16 + li];
-      float f0 = jl[2 * q], f1 = jl[2 * q + 1];
-      asm volatile("" : "+v"(f0), "+v"(f1));
-      const double b0 = (double)f0, b1 = (double)f1;
-      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
-    }
-    // the next J_l: in flight during the write-back and the first product of the next pair-block
-    if (ln < l_end) load_rotation_regs(jl, jb, ln, ident[ln] != 0, wj * 32, lane);
-    __syncthreads();   // all reads of X (= T^T) done
-    // X <- C.  On the diagonal pair-block (k == l) only the lower half of C is kept and
-    // mirrored, so that the diagonal sub-blocks stay exactly symmetric.
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const int j = wj * 32 + e * 16 + li;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int i = wi * 32 + a * 16 + 4 * lk + v;
-          if (k != l) X[i * APP_LD + j] = acc[a][e][v];
-          else if (j <= i) { X[i * APP_LD + j] = acc[a][e][v]; X[j * APP_LD + i] = acc[a][e][v]; }
+          for (int v = 0; v < 4; ++v) w[(int64_t)(cb * JAC_NB + jj) * np + ra * JAC_NB + ii0 + 4 * v] = c2[u][v];
         }
       }
-    __syncthreads();
-    copy_subblock<false>(w, np, X, pk, pl, 0, 0, tid);
-    copy_subblock<false>(w, np, X, qk, pl, JAC_NB, 0, tid);
-    copy_subblock<false>(w, np, X, qk, ql, JAC_NB, JAC_NB, tid);
-    if (k != l) copy_subblock<false>(w, np, X, pk, ql, 0, JAC_NB, tid);   // (pk, qk) is the mirror of (qk, pk)
+    } else {
+      __syncthreads();   // all reads of X done
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = 16 * u + li;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int i = 16 * wave + lg + 4 * v;
+          if (j <= i) { X[i * APP_LD + j] = c2[u][v]; X[j * APP_LD + i] = c2[u][v]; }
+        }
+      }
+      __syncthreads();
+      copy_subblock<false>(w, np, X, pk, pl, 0, 0, tid);
+      copy_subblock<false>(w, np, X, qk, pl, JAC_NB, 0, tid);   // (pk, qk) is its mirror image
+      copy_subblock<false>(w, np, X, qk, ql, JAC_NB, JAC_NB, tid);
+    }
     l = ln;
   }
 }
