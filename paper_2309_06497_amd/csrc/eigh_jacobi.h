@@ -514,7 +514,8 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
     g.ident[b * (nblk / 2) + pair] = any ? 0 : 1;
     if (any) atomicAdd(&g.rot[b * JAC_OUTER_SWEEPS + g.sweep], 1);
   }
-  if (!any) return;
+  // written even when nothing rotated (the identity): the W update then loads rotation blocks
+  // unconditionally
   float *jout = g.jbuf + ((int64_t)b * (nblk / 2) + pair) * JAC_PIV * JAC_PIV;
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) jout[i * JAC_PIV + (tid & 63)] = Js[i * PIV_LD + (tid & 63)];
 }
@@ -645,14 +646,14 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
   rr_pair(nblk, g.round, k, pk, qk);
 
   const int li = lane & 15, lg = lane >> 4;
-  float jk[16];                   // J_k[4 q + lg][16 wave + li]; the identity if that pivot did not rotate
+  float jk[16];                   // J_k[4 q + lg][16 wave + li]
 #pragma unroll
   for (int q = 0; q < 16; ++q) {
     const int row = 4 * q + lg, col = 16 * wave + li;
-    jk[q] = idk ? (row == col ? 1.f : 0.f) : jb[((int64_t)k * JAC_PIV + row) * JAC_PIV + col];
+    jk[q] = jb[((int64_t)k * JAC_PIV + row) * JAC_PIV + col];
   }
   double wt[4][4];
-  float4 jn[4];
+  float4 jn0, jn1, jn2, jn3;
   const int jr = tid >> 4, jc4 = (tid & 15) * 4;
   auto fetch = [&](int lx) {
     int pl, ql;
@@ -661,13 +662,11 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
     sub_fetch(w, np, pk, ql, tid, wt[1]);
     sub_fetch(w, np, qk, pl, tid, wt[2]);
     sub_fetch(w, np, qk, ql, tid, wt[3]);
-    const bool idl = ident[lx] != 0;
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const int i = jr + 16 * h;
-      if (idl) jn[h] = make_float4(i == jc4 ? 1.f : 0.f, i == jc4 + 1 ? 1.f : 0.f, i == jc4 + 2 ? 1.f : 0.f, i == jc4 + 3 ? 1.f : 0.f);
-      else jn[h] = *reinterpret_cast<const float4 *>(jb + ((int64_t)lx * JAC_PIV + i) * JAC_PIV + jc4);
-    }
+    const float *js = jb + ((int64_t)lx * JAC_PIV + jr) * JAC_PIV + jc4;
+    jn0 = *reinterpret_cast<const float4 *>(js);
+    jn1 = *reinterpret_cast<const float4 *>(js + 16 * JAC_PIV);
+    jn2 = *reinterpret_cast<const float4 *>(js + 32 * JAC_PIV);
+    jn3 = *reinterpret_cast<const float4 *>(js + 48 * JAC_PIV);
   };
   fetch(l);
   for (bool first = true; l < l_end; first = false) {
@@ -679,32 +678,54 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
     sub_stash(X, pk, ql, 0, JAC_NB, tid, wt[1]);
     sub_stash(X, qk, pl, JAC_NB, 0, tid, wt[2]);
     sub_stash(X, qk, ql, JAC_NB, JAC_NB, tid, wt[3]);
-#pragma unroll
-    for (int h = 0; h < 4; ++h) *reinterpret_cast<float4 *>(&Jl[(16 * h + 4 * (jr & 3) + (jr >> 2)) * APP_JLD + jc4]) = jn[h];
+    {
+      float *jd = &Jl[(4 * (jr & 3) + (jr >> 2)) * APP_JLD + jc4];   // row i of J_l is kept at row (i & ~15) + 4 (i & 3) + ((i & 15) >> 2)
+      *reinterpret_cast<float4 *>(jd) = jn0;
+      *reinterpret_cast<float4 *>(jd + 16 * APP_JLD) = jn1;
+      *reinterpret_cast<float4 *>(jd + 32 * APP_JLD) = jn2;
+      *reinterpret_cast<float4 *>(jd + 48 * APP_JLD) = jn3;
+    }
     __syncthreads();
     if (ln < l_end) fetch(ln);     // in flight during the products below
 
     doublex4 t1[4], c2[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) { t1[t] = (doublex4){0.0, 0.0, 0.0, 0.0}; c2[t] = (doublex4){0.0, 0.0, 0.0, 0.0}; }
+    // Operands of step q + 1 are read from LDS before the four MFMAs of step q (64 cycles
+    // each) are issued; the scheduling barriers keep the compiler from hoisting every read of
+    // the loop to its top, which costs a workgroup per CU in registers.
+    double xq[2][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) xq[0][t] = X[lg * APP_LD + li + 16 * t];
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
+      if (q + 1 < 16) {
+        const double *xr = &X[(4 * (q + 1) + lg) * APP_LD + li];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) xq[(q + 1) & 1][t] = xr[16 * t];
+      }
       float f = jk[q];
       asm volatile("" : "+v"(f));          // widened at the point of use, not held as float64 across the walk
       const double bq = (double)f;
-      const double *xr = &X[(4 * q + lg) * APP_LD + li];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) t1[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(xr[16 * t], bq, t1[t], 0, 0, 0);
+      for (int t = 0; t < 4; ++t) t1[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(xq[q & 1][t], bq, t1[t], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    float jq[2][4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int u = 0; u < 4; ++u) jq[0][u] = Jl[(4 * lg) * APP_JLD + li + 16 * u];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const float *jrow = &Jl[(16 * t + 4 * lg + v) * APP_JLD + li];   // row 16 t + lg + 4 v of J_l (stored permuted)
-        const double av = t1[t][v];
+    for (int s = 0; s < 16; ++s) {       // step s = 4 t + v: row 16 t + lg + 4 v of J_l, kept at row 16 t + 4 lg + v
+      if (s + 1 < 16) {
+        const float *jrow = &Jl[(16 * ((s + 1) >> 2) + 4 * lg + ((s + 1) & 3)) * APP_JLD + li];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) c2[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, (double)jrow[16 * u], c2[u], 0, 0, 0);
+        for (int u = 0; u < 4; ++u) jq[(s + 1) & 1][u] = jrow[16 * u];
       }
+      const double av = t1[s >> 2][s & 3];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) c2[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, (double)jq[s & 1][u], c2[u], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (k != l) {
       const int ra = wave < 2 ? pk : qk;
       const int ii0 = (16 * wave & 31) + lg;
