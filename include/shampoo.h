@@ -291,6 +291,16 @@ int shampoo_root_inverse_newton(const float *a, int32_t n, int32_t batch, float 
                                 int32_t *iterations, int32_t *failed,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* The order in which the Jacobi eigensolver of the refresh (Sec. 3.2.1: the root inverse by
+ * symmetric eigendecomposition) visits index pairs: pair `k` (0 <= k < s / 2) of round `round`
+ * (0 <= round < s - 1) of a sweep over s indices, written to *p < *q.  Every round is a
+ * perfect matching and the s - 1 rounds cover every pair once.  halves = 0: the plain
+ * tournament (any even s >= 2, the solver for n <= 128).  halves = 1: the order of the
+ * 64 x 64 pivots of the blocked solver (s / 2 a power of two, s >= 4): rounds 0 .. s / 2 - 1
+ * pair the first half of the indices with the second, the remaining rounds pair within the
+ * halves.  Host only, no device work; SHAMPOO_ERR_NULL / SHAMPOO_ERR_SHAPE on bad arguments. */
+int shampoo_jacobi_pair(int32_t s, int32_t halves, int32_t round, int32_t k, int32_t *p, int32_t *q);
+
 /* Static, NUL-terminated description of a return code. */
 const char *shampoo_strerror(int code);
 

@@ -27,7 +27,8 @@ EXPORTS = (
     "shampoo_plan", "shampoo_workspace_bytes", "shampoo_create", "shampoo_step", "shampoo_get",
     "shampoo_status", "shampoo_set_timing", "shampoo_get_timing", "shampoo_destroy",
     "shampoo_root_inverse_workspace_bytes", "shampoo_root_inverse",
-    "shampoo_root_inverse_newton_workspace_bytes", "shampoo_root_inverse_newton", "shampoo_strerror",
+    "shampoo_root_inverse_newton_workspace_bytes", "shampoo_root_inverse_newton", "shampoo_jacobi_pair",
+    "shampoo_strerror",
 )
 
 
@@ -100,6 +101,8 @@ def lib():
     L.shampoo_root_inverse_newton_workspace_bytes.restype = sz
     L.shampoo_root_inverse_newton.argtypes = [vp, i32, i32, f32, i32, f32, i32, vp, vp, vp, vp, sz, vp]
     L.shampoo_root_inverse_newton.restype = ctypes.c_int
+    L.shampoo_jacobi_pair.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(ctypes.c_int32)] * 2
+    L.shampoo_jacobi_pair.restype = ctypes.c_int
     L.shampoo_strerror.argtypes = [ctypes.c_int]
     L.shampoo_strerror.restype = ctypes.c_char_p
     _lib = L
@@ -288,6 +291,13 @@ def shampoo_root_inverse(a, epsilon, r, want_lambda=False, want_failed=False):
     if want_failed:
         res.append(failed)
     return res[0] if len(res) == 1 else tuple(res)
+
+
+def shampoo_jacobi_pair(s, halves, rnd, k):
+    """(p, q), p < q: pair k of round rnd of the eigensolver's sweep over s indices (host only)."""
+    p, q = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().shampoo_jacobi_pair(s, int(bool(halves)), rnd, k, ctypes.byref(p), ctypes.byref(q)))
+    return p.value, q.value
 
 
 def shampoo_root_inverse_newton(a, epsilon, p, tolerance=1e-6, max_iterations=100, want_iterations=False,

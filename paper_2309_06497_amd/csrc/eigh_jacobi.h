@@ -81,7 +81,7 @@ __device__ __host__ __forceinline__ void rr_pair(int cnt, int r, int k, int &p, 
 // pairs within the halves (both halves play the same tournament at once).  From the second
 // visit on the rounds within the halves find nothing above the threshold and are skipped whole.
 // s / 2 must be a power of two.
-__device__ __forceinline__ void halves_pair(int s, int r, int k, int &p, int &q) {
+__device__ __host__ __forceinline__ void halves_pair(int s, int r, int k, int &p, int &q) {
   const int h = s >> 1;
   if (r < h) { p = k; q = h + ((k + r) & (h - 1)); }
   else {

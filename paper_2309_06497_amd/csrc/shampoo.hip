@@ -1733,6 +1733,16 @@ int shampoo_root_inverse_newton(const float *a, int32_t n, int32_t batch, float 
                              static_cast<unsigned char *>(workspace), e, static_cast<hipStream_t>(stream));
 }
 
+int shampoo_jacobi_pair(int32_t s, int32_t halves, int32_t round, int32_t k, int32_t *p, int32_t *q) {
+  if (!p || !q) return SHAMPOO_ERR_NULL;
+  if (s < 2 || (s & 1) || round < 0 || round >= s - 1 || k < 0 || k >= s / 2) return SHAMPOO_ERR_SHAPE;
+  if (halves && (s < 4 || ((s / 2) & (s / 2 - 1)) != 0)) return SHAMPOO_ERR_SHAPE;
+  int pp, qq;
+  if (halves) halves_pair(s, round, k, pp, qq); else rr_pair(s, round, k, pp, qq);
+  *p = pp; *q = qq;
+  return SHAMPOO_OK;
+}
+
 const char *shampoo_strerror(int code) {
   switch (code) {
     case SHAMPOO_OK: return "success";

@@ -195,3 +195,29 @@ def test_planner_merges_small_dimensions_and_blocks_tensors():
     assert nb == len(keys)
     # a tensor block needs three factors and roots: workspace grows accordingly
     assert B.shampoo_workspace_bytes(cfg_for([(64, 64, 9)], 128)) > 2 * 4 * (64 * 64 * 2 + 81)
+
+
+@pytest.mark.parametrize("s,halves", [(2, 0), (6, 0), (64, 0), (128, 0), (4, 1), (16, 1), (64, 1)])
+def test_jacobi_pair_schedule_is_a_tournament(s, halves):
+    """Every round of the eigensolver's sweep is a perfect matching and the s - 1 rounds meet
+    every pair once; in the pivot order the first s / 2 rounds pair across the two halves."""
+    seen = set()
+    for r in range(s - 1):
+        used = set()
+        for k in range(s // 2):
+            p, q = B.shampoo_jacobi_pair(s, halves, r, k)
+            assert 0 <= p < q < s
+            assert p not in used and q not in used
+            used.update((p, q))
+            assert (p, q) not in seen
+            seen.add((p, q))
+            if halves:
+                assert (p < s // 2 <= q) == (r < s // 2)
+        assert len(used) == s
+    assert len(seen) == s * (s - 1) // 2
+
+
+def test_jacobi_pair_rejects_bad_arguments():
+    for args in [(3, 0, 0, 0), (64, 0, 63, 0), (64, 0, 0, 32), (12, 1, 0, 0), (2, 1, 0, 0), (64, 0, -1, 0)]:
+        with pytest.raises(B.ShampooError):
+            B.shampoo_jacobi_pair(*args)
