@@ -659,6 +659,7 @@ struct shampoo_opt {
   size_t off_nfail = 0;   // coupled Newton: per-matrix failure flags of one batch (int32)
   std::vector<void *> last_w, last_g;    // pointer tables currently on the device
   bool ptrs_aligned16 = false;           // every gradient pointer is 16-byte aligned
+  std::vector<char> upper_stale;         // per bucket: the factors' tiles above the diagonal of tiles are out of date
   int64_t last_step = -1;
   int64_t n_refresh = 0;
   bool timing = false;
@@ -763,6 +764,7 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     o->off_diag = offD; o->off_count = offC; o->off_eig = offE;
     o->off_small = offSmall; o->n_small = n_small;
     o->eig_L = eL; o->eig_R = eR; o->eig_mid[0] = eM[0]; o->eig_mid[1] = eM[1];
+    o->upper_stale.assign(o->plan.buckets.size(), 0);
     o->off_nfail = offNf;
     o->off_T2 = offT2; o->off_Gb = offGb; o->off_Wb = offWb; o->has_tensor = has_tensor;
   }
@@ -833,6 +835,24 @@ int newton_root_guarded(shampoo_opt *o, const float *F, int dim, int count, floa
 // GT: element type of the caller's gradients.  GS: of the gradients that feed the factors and
 // the grafting state (GT, or float when l2 weight decay materialises G + wd W).  GD: of the
 // gradients that feed the directions (float when filtered or shifted, else GT).
+// The bf16 factor update writes only the tiles on and below the diagonal of tiles; whoever
+// needs the whole symmetric factor (the refresh, the state query) completes it first.
+int complete_factors(shampoo_opt *o, size_t bucket, hipStream_t s) {
+  if (!o->upper_stale[bucket]) return SHAMPOO_OK;
+  const Bucket &b = o->plan.buckets[bucket];
+  const int dims[2] = {(int)b.m, (int)b.n};
+  const size_t offs[2] = {b.off_L, b.off_R};
+  for (int side = 0; side < 2; ++side) {
+    const int n = dims[side], pieces = (n + 31) / 32;
+    if (n <= BM) continue;   // a single tile: nothing above the diagonal
+    hipLaunchKernelGGL(mirror_upper_tiles_kernel, dim3(pieces, pieces, b.count), dim3(256), 0, s,
+                       reinterpret_cast<float *>(o->ws + offs[side]), (int64_t)n * n, n);
+  }
+  HIP_TRY(hipGetLastError());
+  o->upper_stale[bucket] = 0;
+  return SHAMPOO_OK;
+}
+
 template <typename GT, typename GS, typename GD>
 int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   const shampoo_config &c = o->cfg;
@@ -966,6 +986,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       hipLaunchKernelGGL(transpose_bf16_kernel, dim3((b.n + 63) / 64, (b.m + 63) / 64, b.count), dim3(256), 0, s, ta);
       SyrkBf16Args sa{};
       sa.desc = desc; sa.ptr_table = gs_tab; sa.alpha = alpha; sa.beta = beta; sa.batch = b.count;
+      sa.lower_only = 1; o->upper_stale[&b - p.buckets.data()] = 1;
       // L <- beta L + alpha G G^T
       sa.a.from_table = 1;
       sa.c = reinterpret_cast<float *>(ws + b.off_L); sa.c_batch_stride = (int64_t)b.m * b.m; sa.ldc = b.m;
@@ -992,6 +1013,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       HIP_TRY(hipGetLastError());
     } else {
       StageTimer t(o, SHAMPOO_STAGE_FACTOR, s);
+      o->upper_stale[&b - p.buckets.data()] = 0;   // these kernels read the lower triangle and write both
       GemmArgs g{};
       g.a.from_table = 1; g.b.from_table = 1;
       g.desc = desc; g.ptr_table = gs_tab;
@@ -1075,6 +1097,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     StageTimer t(o, SHAMPOO_STAGE_ROOT, s);
     for (size_t i = 0; i < p.buckets.size(); ++i) {
       auto &b = p.buckets[i];
+      if ((rc = complete_factors(o, i, s))) return rc;
       if (b.whole()) {
         // diagonal sides: elementwise root; full sides: the eigensolver
         for (int side = 0; side < 2; ++side) {
@@ -1600,8 +1623,14 @@ int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, voi
   const unsigned char *src = nullptr;
   size_t need = 0;
   switch (which) {
-    case SHAMPOO_GET_L: need = bk.l_elems() * 4; src = ws + bk.off_L + (size_t)b.slot * need; break;
-    case SHAMPOO_GET_R: need = bk.r_elems() * 4; src = ws + bk.off_R + (size_t)b.slot * need; break;
+    case SHAMPOO_GET_L:
+    case SHAMPOO_GET_R: {
+      const int rcf = complete_factors(o, (size_t)b.bucket, s);
+      if (rcf) return rcf;
+      need = (which == SHAMPOO_GET_L ? bk.l_elems() : bk.r_elems()) * 4;
+      src = ws + (which == SHAMPOO_GET_L ? bk.off_L : bk.off_R) + (size_t)b.slot * need;
+      break;
+    }
     case SHAMPOO_GET_LINV: need = bk.l_elems() * 4; src = ws + bk.off_Linv + (size_t)b.slot * need; break;
     case SHAMPOO_GET_RINV: need = bk.r_elems() * 4; src = ws + bk.off_Rinv + (size_t)b.slot * need; break;
     case SHAMPOO_GET_L2:

@@ -29,7 +29,9 @@
 // workgroup barrier of the loop is the bare s_barrier: the loads of later slabs stay in
 // flight across it.
 //
-// Only lower-triangular tiles are computed; the mirror image is written with the same bits.
+// Only lower-triangular tiles are computed; the mirror image is written with the same bits,
+// or, with lower_only, left to mirror_upper_tiles_kernel: nothing in a step reads the tiles above
+// the diagonal, only the refresh and the state query do.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -53,6 +55,7 @@ struct SyrkBf16Args {
   const float *x_scale2;     // [batch] X holds fp16 values s x: 1 / s^2, applied with alpha (nullptr: X is bf16)
   int32_t tiles;             // lower-triangular tile count per batch entry
   int32_t batch;
+  int32_t lower_only;        // nonzero: tiles above the diagonal of tiles are not written (mirror_upper_tiles_kernel completes them on demand)
 };
 
 __device__ __forceinline__ void syrk_flush(double (&dst)[16], const floatx16 &src) {
@@ -262,12 +265,13 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
         if (diag) {
           if (jl <= il) { Ts[il * SYRK_TLD + jl] = x; Ts[jl * SYRK_TLD + il] = x; }
         } else {
-          Ts[jl * SYRK_TLD + il] = x;
+          if (!g.lower_only) Ts[jl * SYRK_TLD + il] = x;
           if (i < g.M && j < g.M) c[(int64_t)i * ldc + j] = x;
         }
       }
     }
   }
+  if (!diag && g.lower_only) return;   // uniform across the workgroup
   __syncthreads();
   {
     // rows of the LDS tile -> rows of C at (col0, row0) (or (row0, row0) for a diagonal tile)
@@ -290,6 +294,28 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
 #undef SYRK_STEP
 #undef SYRK_WAIT
 #undef SYRK_SLAB_PRODUCT
+
+// C[i][j] = C[j][i] for every element whose tile (of BM x BM) lies above the diagonal of tiles:
+// completes a factor that syrk_bf16_kernel updated with lower_only.  grid (ceil(n / 32),
+// ceil(n / 32), batch), 256 threads; a 32 x 32 piece never straddles two tiles.
+__global__ __launch_bounds__(256) void mirror_upper_tiles_kernel(float *c, int64_t batch_stride, int n) {
+  __shared__ float t[32][33];
+  const int i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;     // destination piece (i0, j0)
+  if (i0 / BM >= j0 / BM) return;
+  float *m = c + (int64_t)blockIdx.z * batch_stride;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int r = ty; r < 32; r += 8) {
+    const int si = j0 + r, sj = i0 + tx;                       // source piece (j0, i0)
+    if (si < n && sj < n) t[r][tx] = m[(int64_t)si * n + sj];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = ty; r < 32; r += 8) {
+    const int di = i0 + r, dj = j0 + tx;
+    if (di < n && dj < n) m[(int64_t)di * n + dj] = t[tx][r];
+  }
+}
 
 struct TransposeArgs {
   const BlockDesc *desc;
