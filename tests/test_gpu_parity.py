@@ -104,9 +104,18 @@ class Pair:
         self.allow_hist = {}  # largest allowance so far (for M and W)
         self.g_last = None
 
-    def step(self, grads_np, lr, t):
+    def step(self, grads_np, lr, t, misalign=False):
         import torch
         g_dev = to_dev(grads_np, self.bf16)
+        if misalign:      # the same values at addresses that are not multiples of 16 bytes
+            moved = []
+            for g in g_dev:
+                buf = torch.empty(g.numel() + 8, dtype=g.dtype, device=g.device)
+                v = buf[1:1 + g.numel()].view(g.shape)
+                v.copy_(g)
+                assert v.data_ptr() % 16 != 0 and v.is_contiguous()
+                moved.append(v)
+            g_dev = moved
         self.w_prev = [w.copy() for w in self.w_ora]
         self.gpu.step(self.w_gpu, g_dev, lr, t)
         torch.cuda.synchronize()
@@ -287,6 +296,20 @@ def test_bf16_ragged_blocks_on_matrix_cores():
     p = Pair(shapes, 256, 0.999, 1, eps=1e-6, bf16=True)
     for t in range(4):
         p.step(wl.gaussian_grads(shapes, 21, t, 1e-3), 0.01, t)
+        p.check(t)
+
+
+def test_bf16_factor_tiles_when_the_kernel_choice_alternates():
+    """The bf16 factor kernel leaves the tiles above the diagonal of tiles to a mirror pass that
+    runs before a refresh and before a factor is read back; gradients at addresses that are not
+    multiples of 16 bytes take the float32 kernels instead, which write both halves.  Steps that
+    alternate between the two, with refreshes in between, must give the same factors, roots and
+    weights as the oracle at every step."""
+    say("case bf16 factor kernels alternating")
+    shapes = [(512, 384)]
+    p = Pair(shapes, 256, 0.999, 2, eps=1e-6, bf16=True)
+    for t in range(5):
+        p.step(wl.gaussian_grads(shapes, 27, t, 1e-3), 0.01, t, misalign=(t % 2 == 1))
         p.check(t)
 
 
@@ -684,9 +707,18 @@ class TensorPair:
         self.w_ora = [w.astype(np.float64) for w in w0]
         self.w_gpu = to_dev(w0)
 
-    def step(self, grads_np, lr, t):
+    def step(self, grads_np, lr, t, misalign=False):
         import torch
         g_dev = to_dev(grads_np, self.bf16)
+        if misalign:      # the same values at addresses that are not multiples of 16 bytes
+            moved = []
+            for g in g_dev:
+                buf = torch.empty(g.numel() + 8, dtype=g.dtype, device=g.device)
+                v = buf[1:1 + g.numel()].view(g.shape)
+                v.copy_(g)
+                assert v.data_ptr() % 16 != 0 and v.is_contiguous()
+                moved.append(v)
+            g_dev = moved
         self.gpu.step(self.w_gpu, g_dev, lr, t)
         torch.cuda.synchronize()
         self.g_last = grads_for_oracle(g_dev)
