@@ -688,9 +688,9 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
     __syncthreads();
     if (ln < l_end) fetch(ln);     // in flight during the products below
 
-    doublex4 t1[4], c2[4];
+    doublex4 t1[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) { t1[t] = (doublex4){0.0, 0.0, 0.0, 0.0}; c2[t] = (doublex4){0.0, 0.0, 0.0, 0.0}; }
+    for (int t = 0; t < 4; ++t) t1[t] = (doublex4){0.0, 0.0, 0.0, 0.0};
     // Operands of step q + 1 are read from LDS before the four MFMAs of step q (64 cycles
     // each) are issued; the scheduling barriers keep the compiler from hoisting every read of
     // the loop to its top, which costs a workgroup per CU in registers.
@@ -711,47 +711,60 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
       for (int t = 0; t < 4; ++t) t1[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(xq[q & 1][t], bq, t1[t], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    float jq[2][4];
+    if (k == l) __syncthreads();   // all reads of X done: the result of a diagonal pair-block is completed there
+    // The second product, two of its four 16-column tiles at a time; each tile leaves as soon
+    // as it is done.  (All four at once: 1 % slower.  Without the prefetch the kernel fits three
+    // workgroups per CU and is 6 % slower.)
+    constexpr int UW = 2;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) jq[0][u] = Jl[(4 * lg) * APP_JLD + li + 16 * u];
+    for (int u0 = 0; u0 < 4; u0 += UW) {
+      doublex4 c2[UW];
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {       // step s = 4 t + v: row 16 t + lg + 4 v of J_l, kept at row 16 t + 4 lg + v
-      if (s + 1 < 16) {
-        const float *jrow = &Jl[(16 * ((s + 1) >> 2) + 4 * lg + ((s + 1) & 3)) * APP_JLD + li];
+      for (int u = 0; u < UW; ++u) c2[u] = (doublex4){0.0, 0.0, 0.0, 0.0};
+      float jq[2][UW];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) jq[(s + 1) & 1][u] = jrow[16 * u];
+      for (int u = 0; u < UW; ++u) jq[0][u] = Jl[(4 * lg) * APP_JLD + li + 16 * (u0 + u)];
+#pragma unroll
+      for (int s = 0; s < 16; ++s) {       // step s = 4 t + v: row 16 t + lg + 4 v of J_l, kept at row 16 t + 4 lg + v
+        if (s + 1 < 16) {
+          const float *jrow = &Jl[(16 * ((s + 1) >> 2) + 4 * lg + ((s + 1) & 3)) * APP_JLD + li];
+#pragma unroll
+          for (int u = 0; u < UW; ++u) jq[(s + 1) & 1][u] = jrow[16 * (u0 + u)];
+        }
+        const double av = t1[s >> 2][s & 3];
+#pragma unroll
+        for (int u = 0; u < UW; ++u) c2[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, (double)jq[s & 1][u], c2[u], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      const double av = t1[s >> 2][s & 3];
+      if (k != l) {
+        const int ra = wave < 2 ? pk : qk;
+        const int ii0 = (16 * wave & 31) + lg;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) c2[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, (double)jq[s & 1][u], c2[u], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int uu = 0; uu < UW; ++uu) {
+          const int u = u0 + uu;
+          const int cb = u < 2 ? pl : ql;
+          const int jj = (16 * u & 31) + li;
+          if (ra > cb) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) w[(int64_t)(ra * JAC_NB + ii0 + 4 * v) * np + cb * JAC_NB + jj] = c2[uu][v];
+          } else {        // stored transposed
+#pragma unroll
+            for (int v = 0; v < 4; ++v) w[(int64_t)(cb * JAC_NB + jj) * np + ra * JAC_NB + ii0 + 4 * v] = c2[uu][v];
+          }
+        }
+      } else {
+#pragma unroll
+        for (int uu = 0; uu < UW; ++uu) {
+          const int j = 16 * (u0 + uu) + li;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int i = 16 * wave + lg + 4 * v;
+            if (j <= i) { X[i * APP_LD + j] = c2[uu][v]; X[j * APP_LD + i] = c2[uu][v]; }
+          }
+        }
+      }
     }
-    if (k != l) {
-      const int ra = wave < 2 ? pk : qk;
-      const int ii0 = (16 * wave & 31) + lg;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int cb = u < 2 ? pl : ql;
-        const int jj = (16 * u & 31) + li;
-        if (ra > cb) {
-#pragma unroll
-          for (int v = 0; v < 4; ++v) w[(int64_t)(ra * JAC_NB + ii0 + 4 * v) * np + cb * JAC_NB + jj] = c2[u][v];
-        } else {        // stored transposed
-#pragma unroll
-          for (int v = 0; v < 4; ++v) w[(int64_t)(cb * JAC_NB + jj) * np + ra * JAC_NB + ii0 + 4 * v] = c2[u][v];
-        }
-      }
-    } else {
-      __syncthreads();   // all reads of X done
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int j = 16 * u + li;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int i = 16 * wave + lg + 4 * v;
-          if (j <= i) { X[i * APP_LD + j] = c2[u][v]; X[j * APP_LD + i] = c2[u][v]; }
-        }
-      }
+    if (k == l) {
       __syncthreads();
       copy_subblock<false>(w, np, X, pk, pl, 0, 0, tid);
       copy_subblock<false>(w, np, X, qk, pl, JAC_NB, 0, tid);   // (pk, qk) is its mirror image
