@@ -55,10 +55,10 @@ static_assert(32 * 33 / 2 <= JAC_BLOCKS_PER_THREAD * 256 && (JAC_SMALL_MAX / 2) 
               "LDS solver blocks per thread");
 
 struct JacScratch {      // small per-workgroup LDS arrays
-  double s[JAC_SMALL_MAX / 2];
-  double t[JAC_SMALL_MAX / 2];
-  int p[JAC_SMALL_MAX / 2];
-  int q[JAC_SMALL_MAX / 2];
+  // per rotation of the current round: (sin, sin / (1 + cos)) and (p, q, offset of row p, offset
+  // of row q in the LDS matrix), each read with one 16-byte LDS access
+  double2 st[JAC_SMALL_MAX / 2];
+  int4 pq[JAC_SMALL_MAX / 2];
   int flag;
   unsigned rounds[4];     // bit r: round r of the current sweep has a pair above the threshold
 };
@@ -135,6 +135,9 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
   const int tid = threadIdx.x;
   const int half = s >> 1;
   auto at = [LDA](int i, int j) { return SQUARE ? i * LDA + j : tri(i, j); };
+  // the same from row offsets (i LDA, or i (i + 1) / 2 for the packed triangle) computed once per rotation
+  auto rowoff = [LDA](int i) { return SQUARE ? i * LDA : i * (i + 1) / 2; };
+  auto atr = [](int i, int ri, int j, int rj) { return SQUARE ? ri + j : (i >= j ? ri + j : rj + i); };
   int any = 0;
   // this thread's blocks (k, l), l <= k, of the two-sided update: numbers tid, tid + NT, ...
   // of the half (half + 1) / 2 blocks (at most UB each: 528 on 256 threads at s = 64, 2080 on
@@ -200,7 +203,7 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
           if (!(fabs(sn) <= 1.0)) { sn = 0.0; tp = 0.0; }   // non-finite: leave the pair alone
           if (sn != 0.0) sc->flag = 1;
         }
-        sc->s[tid] = sn; sc->t[tid] = tp; sc->p[tid] = p; sc->q[tid] = q;
+        sc->st[tid] = make_double2(sn, tp); sc->pq[tid] = make_int4(p, q, rowoff(p), rowoff(q));
       }
       __syncthreads();
       // A <- R^T A R on the blocks (k, l) with l <= k, dealt evenly over the threads (block
@@ -210,19 +213,20 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
       // loads overlap).
       {
         double a[UB], b[UB], c[UB], d[UB], sk[UB], tk[UB], sl[UB], tl[UB];
-        int ia[UB], ib[UB], ic[UB], id[UB], pk[UB], qk[UB], pl[UB], ql[UB];
+        int ia[UB], ib[UB], ic[UB], id[UB];
+        int4 k4[UB], l4[UB];
         bool act[UB];
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
           act[u] = bk[u] >= 0;
           if (act[u]) {
-            const int k = bk[u], l = bl[u];
-            sk[u] = sc->s[k]; sl[u] = sc->s[l];
+            const double2 stk = sc->st[bk[u]], stl = sc->st[bl[u]];
+            sk[u] = stk.x; tk[u] = stk.y; sl[u] = stl.x; tl[u] = stl.y;
             act[u] = !(sk[u] == 0.0 && sl[u] == 0.0);
             if (act[u]) {
-              pk[u] = sc->p[k]; qk[u] = sc->q[k]; tk[u] = sc->t[k];
-              pl[u] = sc->p[l]; ql[u] = sc->q[l]; tl[u] = sc->t[l];
-              ia[u] = at(pk[u], pl[u]); ib[u] = at(pk[u], ql[u]); ic[u] = at(qk[u], pl[u]); id[u] = at(qk[u], ql[u]);
+              k4[u] = sc->pq[bk[u]]; l4[u] = sc->pq[bl[u]];
+              ia[u] = atr(k4[u].x, k4[u].z, l4[u].x, l4[u].z); ib[u] = atr(k4[u].x, k4[u].z, l4[u].y, l4[u].w);
+              ic[u] = atr(k4[u].y, k4[u].w, l4[u].x, l4[u].z); id[u] = atr(k4[u].y, k4[u].w, l4[u].y, l4[u].w);
               a[u] = At[ia[u]]; b[u] = At[ib[u]]; c[u] = At[ic[u]]; d[u] = At[id[u]];
             }
           }
@@ -242,7 +246,7 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
           } else {
             At[ia[u]] = a2; At[ib[u]] = b2; At[ic[u]] = c2; At[id[u]] = d2;
             if (SQUARE) {
-              At[at(pl[u], pk[u])] = a2; At[at(ql[u], pk[u])] = b2; At[at(pl[u], qk[u])] = c2; At[at(ql[u], qk[u])] = d2;
+              At[l4[u].z + k4[u].x] = a2; At[l4[u].w + k4[u].x] = b2; At[l4[u].z + k4[u].y] = c2; At[l4[u].w + k4[u].y] = d2;
             }
           }
         }
@@ -250,10 +254,12 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
       // J <- J R (columns), same load / rotate / store batching over rows
       constexpr int V = NT >= 1024 ? 4 : 8;
       for (int l = tid & 31; l < half; l += 32) {
-        const float sl = (float)sc->s[l];
+        const double2 stl = sc->st[l];
+        const float sl = (float)stl.x;
         if (sl == 0.f) continue;
-        const float tl = (float)sc->t[l];
-        const int pl = sc->p[l], ql = sc->q[l];
+        const float tl = (float)stl.y;
+        const int4 l4 = sc->pq[l];
+        const int pl = l4.x, ql = l4.y;
         for (int i0 = tid >> 5; i0 < s; i0 += (NT / 32) * V) {
           float x[V], y[V];
 #pragma unroll
@@ -363,11 +369,12 @@ __global__ __launch_bounds__(NT) void rootinv_small_kernel(const SmallRootArgs g
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   __syncthreads();
-  if (lane == 0) reinterpret_cast<double *>(sc->s)[wave] = lmin;   // rotation scratch is free now
+  double *red = reinterpret_cast<double *>(sc->st);   // rotation scratch is free now
+  if (lane == 0) red[wave] = lmin;
   __syncthreads();
-  lmin = sc->s[0];
+  lmin = red[0];
 #pragma unroll
-  for (int w = 1; w < NW; ++w) lmin = fmin(lmin, sc->s[w]);
+  for (int w = 1; w < NW; ++w) lmin = fmin(lmin, red[w]);
   const double shift = fmin(lmin, 0.0);
   int badf = 0;
   for (int i = tid; i < s; i += NT) {
