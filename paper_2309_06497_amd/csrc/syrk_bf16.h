@@ -1,10 +1,11 @@
 // Factor update for bf16 gradients on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16).
 //
 // The product of two bf16 values is exact in float32, so G G^T of a bf16 gradient
-// loses nothing on the bf16 MFMA path (16x the float32 MFMA rate) provided the
-// accumulation is as careful as on the float32 path: here two chained MFMAs (32
-// values of k) are accumulated in float32 and then added into float64 registers,
-// and beta2 L + (1 - beta2) S is evaluated in float64 before the single rounding
+// loses nothing on the bf16 MFMA path (16x the float32 MFMA rate) but the roundings of the
+// float32 accumulator, one per MFMA of 16 values of k: measured 1.3e-7 ... 1.9e-7 of the
+// factor's norm at k = 1024, against a bar of 1e-5 (float64 accumulators, flushed every 32
+// values of k, gave 4e-8 and cost a quarter of the kernel's speed: they took 128 registers
+// per lane).  beta2 L + (1 - beta2) S is evaluated in float64 before the single rounding
 // to float32.  R = G^T G runs through the same kernel on a 16-bit transpose of the
 // block (transpose_bf16_kernel), so both operands are always read along k; where the
 // fp16 preconditioning products follow, that transpose holds fp16(s G) with a power of
@@ -40,7 +41,7 @@
 
 namespace shampoo {
 
-constexpr int SBK = 32;                        // k per slab: two MFMAs chained in float32, then the float64 flush
+constexpr int SBK = 32;                        // k per slab: two MFMAs per 32 x 32 tile
 constexpr int SYRK_SLAB = BM * SBK * 2;        // bytes of one operand slab
 constexpr int SYRK_STAGE = 2 * SYRK_SLAB;      // A slab, then B slab
 constexpr int SYRK_STAGES = 3;                 // a fourth stage fits the LDS footprint and measured no faster
@@ -58,28 +59,16 @@ struct SyrkBf16Args {
   int32_t lower_only;        // nonzero: tiles above the diagonal of tiles are not written (mirror_upper_tiles_kernel completes them on demand)
 };
 
-__device__ __forceinline__ void syrk_flush(double (&dst)[16], const floatx16 &src) {
-#pragma unroll
-  for (int v = 0; v < 16; ++v) dst[v] += (double)src[v];
-}
-
 typedef _Float16 syrk_f16x8 __attribute__((ext_vector_type(8)));
 
 template <bool F16>
-__device__ __forceinline__ floatx16 syrk_chain(const u32x4 &a0, const u32x4 &b0, const u32x4 &a1, const u32x4 &b1) {
-  floatx16 acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+__device__ __forceinline__ floatx16 syrk_mfma(floatx16 acc, const u32x4 &a0, const u32x4 &b0) {
   if constexpr (F16) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(syrk_f16x8, a0), __builtin_bit_cast(syrk_f16x8, b0), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(syrk_f16x8, a1), __builtin_bit_cast(syrk_f16x8, b1), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(syrk_f16x8, a0), __builtin_bit_cast(syrk_f16x8, b0), acc, 0, 0, 0);
   } else {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), __builtin_bit_cast(bf16x8, b1), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, b0), acc, 0, 0, 0);
   }
-  return acc;
 }
-
 
 // Requires: operand base 16-byte aligned, ld % 8 == 0, K % 8 == 0 (checked by the host).
 // F16: the operand holds fp16 values (the scaled transpose of a bf16 block: products of two
@@ -148,25 +137,20 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
   const uint32_t la0 = lbase + (diag ? SYRK_SLAB : 0) + ((wm * 64 + fi) * SBK + ((fq ^ ((fi >> 2) & 3)) * 8)) * 2, la1 = la0 ^ 32;
   const uint32_t lb0 = lbase + ((wn * 64 + fi) * SBK + ((fq ^ ((fi >> 2) & 3)) * 8)) * 2, lb1 = lb0 ^ 32;
 
-  double acc64[2][2][16];
+  floatx16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc64[i][j][v] = 0.0;
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int nk = g.K / SBK;                      // full slabs; K % SBK values of k remain
   if (nk > 0) issue(0, 0);
   if (nk > 1) issue(1, SBK);
   u32x4 oa[2][2], ob[2][2];                      // [i or j][k step]
-  floatx16 X, Y;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) Y[v] = 0.f;
-  // The eight operand reads of the slab in stage S, then, for the four 32 x 32 tiles of the
-  // wavefront, the MFMA pair of one tile issued before the float64 flush of the tile before
-  // it, so that the flush (VALU) runs beside the MFMAs.  The accumulator of the last tile (Y)
-  // is flushed during the next slab.
+  // The eight operand reads of the slab in stage S, then the eight MFMAs of the wavefront's four
+  // 32 x 32 tiles (the two of one tile four instructions apart).
 #define SYRK_SLAB_PRODUCT(S)                                                              \
   {                                                                                       \
     LDS_DS_READ_B128(oa[0][0], la0, (S) * SYRK_STAGE);                                        \
@@ -181,14 +165,15 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
                  : "+v"(oa[0][0]), "+v"(oa[0][1]), "+v"(oa[1][0]), "+v"(oa[1][1]),        \
                    "+v"(ob[0][0]), "+v"(ob[0][1]), "+v"(ob[1][0]), "+v"(ob[1][1]) :: "memory"); \
     LDS_SCHED_BARRIER();                                                                            \
-    X = syrk_chain<F16>(oa[0][0], ob[0][0], oa[0][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
-    syrk_flush(acc64[1][1], Y); LDS_SCHED_BARRIER();                                                \
-    Y = syrk_chain<F16>(oa[0][0], ob[1][0], oa[0][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
-    syrk_flush(acc64[0][0], X); LDS_SCHED_BARRIER();                                                \
-    X = syrk_chain<F16>(oa[1][0], ob[0][0], oa[1][1], ob[0][1]); LDS_SCHED_BARRIER();                    \
-    syrk_flush(acc64[0][1], Y); LDS_SCHED_BARRIER();                                                \
-    Y = syrk_chain<F16>(oa[1][0], ob[1][0], oa[1][1], ob[1][1]); LDS_SCHED_BARRIER();                    \
-    syrk_flush(acc64[1][0], X); LDS_SCHED_BARRIER();                                                \
+    acc[0][0] = syrk_mfma<F16>(acc[0][0], oa[0][0], ob[0][0]);                            \
+    acc[0][1] = syrk_mfma<F16>(acc[0][1], oa[0][0], ob[1][0]);                            \
+    acc[1][0] = syrk_mfma<F16>(acc[1][0], oa[1][0], ob[0][0]);                            \
+    acc[1][1] = syrk_mfma<F16>(acc[1][1], oa[1][0], ob[1][0]);                            \
+    acc[0][0] = syrk_mfma<F16>(acc[0][0], oa[0][1], ob[0][1]);                            \
+    acc[0][1] = syrk_mfma<F16>(acc[0][1], oa[0][1], ob[1][1]);                            \
+    acc[1][0] = syrk_mfma<F16>(acc[1][0], oa[1][1], ob[0][1]);                            \
+    acc[1][1] = syrk_mfma<F16>(acc[1][1], oa[1][1], ob[1][1]);                            \
+    LDS_SCHED_BARRIER();                                                                  \
   }
 
   if (g.K % SBK) {
@@ -221,7 +206,6 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
     SYRK_STEP(1, 0, kt + 1);
     SYRK_STEP(2, 1, kt + 2);
   }
-  syrk_flush(acc64[1][1], Y);
   LDS_DMA_WAIT_VM(0);
   __syncthreads();                               // the slabs are dead: the region becomes Ts
 
@@ -261,7 +245,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int il = wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), i = row0 + il;
-        const float x = (float)(alpha * acc64[mi][ni][v] + g.beta * (double)old[ni][v]);
+        const float x = (float)(alpha * (double)acc[mi][ni][v] + g.beta * (double)old[ni][v]);
         if (diag) {
           if (jl <= il) { Ts[il * SYRK_TLD + jl] = x; Ts[jl * SYRK_TLD + il] = x; }
         } else {

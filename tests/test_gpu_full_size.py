@@ -37,7 +37,7 @@ def test_transformer_full_size_sampled_blocks():
     vectors against the oracle.  Bars: factors 1e-5; root inverse against the oracle's on the
     same float32 factor bits 2e-3; directions, momentum and parameter updates 2e-3, plus --
     while the t = 0 roots are in use -- the allowance for what float32 storage of an
-    ill-conditioned factor can cost: theta ||L||_F / (4 (lambda_min + eps)), theta = 1e-7,
+    ill-conditioned factor can cost: theta ||L||_F / (4 (lambda_min + eps)), theta = 2e-7,
     summed over both factors (the stored factor is within theta ||L||_F of the exact one, an
     eigenvalue moves by at most that, and (lambda + eps)^(-1/4) by a quarter of the relative
     change).  From t = 3 on the allowance is negligible and the bar is the plain 2e-3 for the
@@ -90,7 +90,7 @@ def test_transformer_full_size_sampled_blocks():
                 Li = opt.get(i, k, B.GET_LINV).cpu().numpy()
                 e_root = rel(Li, so.root_inverse(L, f32(1e-12), 0.25)[0])
                 assert e_root <= 2e-3
-                allow[key] = sum(0.25 * 1e-7 * np.linalg.norm(Fm) / (max(np.linalg.eigvalsh(Fm)[0], 0.0) + f32(1e-12))
+                allow[key] = sum(0.25 * 2e-7 * np.linalg.norm(Fm) / (max(np.linalg.eigvalsh(Fm)[0], 0.0) + f32(1e-12))
                                  for Fm in (ora[key].L[0][0], ora[key].R[0][0]))
                 allow_hist[key] = max(allow_hist[key], allow[key])
             say(f"    block {key}: L={e_l:.1e} R={e_r:.1e} root={e_root:.1e} Psh={e_p:.1e} M={e_m:.1e} dW={e_w:.1e}"
