@@ -986,7 +986,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       hipLaunchKernelGGL(transpose_bf16_kernel, dim3((b.n + 63) / 64, (b.m + 63) / 64, b.count), dim3(256), 0, s, ta);
       SyrkBf16Args sa{};
       sa.desc = desc; sa.ptr_table = gs_tab; sa.alpha = alpha; sa.beta = beta; sa.batch = b.count;
-      sa.lower_only = 1; o->upper_stale[&b - p.buckets.data()] = 1;
+      o->upper_stale[&b - p.buckets.data()] = 1;   // the kernel writes the tiles on and below the diagonal only
       // L <- beta L + alpha G G^T
       sa.a.from_table = 1;
       sa.c = reinterpret_cast<float *>(ws + b.off_L); sa.c_batch_stride = (int64_t)b.m * b.m; sa.ldc = b.m;

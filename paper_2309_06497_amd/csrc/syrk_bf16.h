@@ -30,9 +30,9 @@
 // workgroup barrier of the loop is the bare s_barrier: the loads of later slabs stay in
 // flight across it.
 //
-// Only lower-triangular tiles are computed; the mirror image is written with the same bits,
-// or, with lower_only, left to mirror_upper_tiles_kernel: nothing in a step reads the tiles above
-// the diagonal, only the refresh and the state query do.
+// Only the tiles on and below the diagonal of tiles are computed and written; the mirror image
+// is left to mirror_upper_tiles_kernel: nothing in a step reads the tiles above the diagonal,
+// only the refresh and the state query do.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -56,7 +56,6 @@ struct SyrkBf16Args {
   const float *x_scale2;     // [batch] X holds fp16 values s x: 1 / s^2, applied with alpha (nullptr: X is bf16)
   int32_t tiles;             // lower-triangular tile count per batch entry
   int32_t batch;
-  int32_t lower_only;        // nonzero: tiles above the diagonal of tiles are not written (mirror_upper_tiles_kernel completes them on demand)
 };
 
 typedef _Float16 syrk_f16x8 __attribute__((ext_vector_type(8)));
@@ -74,13 +73,8 @@ __device__ __forceinline__ floatx16 syrk_mfma(floatx16 acc, const u32x4 &a0, con
 // F16: the operand holds fp16 values (the scaled transpose of a bf16 block: products of two
 // such values are exact in float32 as well) and the fp16 matrix-core instruction is used.
 template <bool F16>
-__global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf16Args g) {
-  // one LDS region: the operand slabs during the k loop, then the tile on its way to the
-  // mirrored (transposed) position
-  constexpr int SYRK_TLD = BM + 1;
-  constexpr int LDS_BYTES = BN * SYRK_TLD * 4 > SYRK_STAGES * SYRK_STAGE ? BN * SYRK_TLD * 4 : SYRK_STAGES * SYRK_STAGE;
-  __shared__ __align__(128) unsigned char smem[LDS_BYTES];   // the k-step addresses below differ by an XOR
-  float *Ts = reinterpret_cast<float *>(smem);
+__global__ __launch_bounds__(GEMM_THREADS, 3) void syrk_bf16_kernel(const SyrkBf16Args g) {
+  __shared__ __align__(128) unsigned char smem[SYRK_STAGES * SYRK_STAGE];   // the k-step addresses below differ by an XOR
   const int total = g.tiles * g.batch;
   const int logical = xcd_remap(blockIdx.x, total);
   if (logical >= total) return;
@@ -207,13 +201,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
     SYRK_STEP(2, 1, kt + 2);
   }
   LDS_DMA_WAIT_VM(0);
-  __syncthreads();                               // the slabs are dead: the region becomes Ts
 
-  // Epilogue.  The lower-triangular tile is stored from the accumulators (rows of 32
-  // consecutive floats per half wavefront).  Its mirror image would be a scatter of single
-  // floats, so the tile goes through LDS transposed and is stored along rows as well; a
-  // diagonal tile is completed to the full symmetric tile in LDS and stored once.  Both
-  // copies carry the same bits, so the factor stays exactly symmetric.
+  // Epilogue.  Every computed tile (on or below the diagonal of tiles) is stored from the
+  // accumulators, rows of 32 consecutive floats per half wavefront.  A tile on the diagonal is
+  // stored whole: its elements (i, j) and (j, i) are the same products summed in the same order
+  // by the matrix cores, from the same old values, so they carry the same bits and the factor
+  // stays exactly symmetric.  The tiles above the diagonal are mirror_upper_tiles_kernel's.
   float *c = g.c + (int64_t)b * g.c_batch_stride;
   const int ldc = g.ldc;
   const double alpha = g.x_scale2 ? g.alpha * (double)g.x_scale2[b] : g.alpha;
@@ -241,36 +234,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
     }
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
-      const int jl = wn * 64 + ni * 32 + (lane & 31), j = col0 + jl;
+      const int j = col0 + wn * 64 + ni * 32 + (lane & 31);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int il = wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), i = row0 + il;
+        const int i = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
         const float x = (float)(alpha * (double)acc[mi][ni][v] + g.beta * (double)old[ni][v]);
-        if (diag) {
-          if (jl <= il) { Ts[il * SYRK_TLD + jl] = x; Ts[jl * SYRK_TLD + il] = x; }
-        } else {
-          if (!g.lower_only) Ts[jl * SYRK_TLD + il] = x;
-          if (i < g.M && j < g.M) c[(int64_t)i * ldc + j] = x;
-        }
-      }
-    }
-  }
-  if (!diag && g.lower_only) return;   // uniform across the workgroup
-  __syncthreads();
-  {
-    // rows of the LDS tile -> rows of C at (col0, row0) (or (row0, row0) for a diagonal tile)
-    const int rbase = diag ? row0 : col0, cbase = row0;
-    const int cx = (tid & 31) * 4;
-    const bool vec = (ldc & 3) == 0 && (reinterpret_cast<uintptr_t>(c) & 15) == 0;
-    for (int rr = tid >> 5; rr < BM; rr += GEMM_THREADS / 32) {
-      const int gi = rbase + rr, gj = cbase + cx;
-      if (gi >= g.M || gj >= g.M) continue;
-      const float *src = Ts + rr * SYRK_TLD + cx;
-      if (vec && gj + 3 < g.M) {
-        *reinterpret_cast<float4 *>(c + (int64_t)gi * ldc + gj) = make_float4(src[0], src[1], src[2], src[3]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) if (gj + e < g.M) c[(int64_t)gi * ldc + gj + e] = src[e];
+        if (i < g.M && j < g.M) c[(int64_t)i * ldc + j] = x;
       }
     }
   }
@@ -280,7 +249,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void syrk_bf16_kernel(const SyrkBf
 #undef SYRK_SLAB_PRODUCT
 
 // C[i][j] = C[j][i] for every element whose tile (of BM x BM) lies above the diagonal of tiles:
-// completes a factor that syrk_bf16_kernel updated with lower_only.  grid (ceil(n / 32),
+// completes a factor that syrk_bf16_kernel has updated.  grid (ceil(n / 32),
 // ceil(n / 32), batch), 256 threads; a 32 x 32 piece never straddles two tiles.
 __global__ __launch_bounds__(256) void mirror_upper_tiles_kernel(float *c, int64_t batch_stride, int n) {
   __shared__ float t[32][33];
