@@ -853,6 +853,14 @@ int complete_factors(shampoo_opt *o, size_t bucket, hipStream_t s) {
   return SHAMPOO_OK;
 }
 
+// A factor of dimension `dim` that has so far summed (step + 1) gradients of `cols` columns
+// each is a near-singular Gram matrix until it holds a few times more columns than it has
+// rows (a Gaussian dim x N matrix has the condition number ((sqrt N + sqrt dim) / (sqrt N -
+// sqrt dim))^2 squared into its Gram matrix: 1e7 and more at N = dim, 34 at N = 2 dim, 9 at
+// N = 4 dim).  While it is, a root taken from it weights its smallest eigenvalues most, and
+// the bf16 factor update sums in float64 (syrk_bf16.h).
+inline bool young_factor(int64_t step, int cols, int dim) { return (step + 1) * (int64_t)cols < 4 * (int64_t)dim; }
+
 template <typename GT, typename GS, typename GD>
 int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   const shampoo_config &c = o->cfg;
@@ -994,7 +1002,10 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       {
         const int64_t total = (int64_t)sa.tiles * sa.batch;
         const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
-        hipLaunchKernelGGL(syrk_bf16_kernel<false>, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+        if (young_factor(step, b.n, b.m))
+          hipLaunchKernelGGL((syrk_bf16_kernel<false, true>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+        else
+          hipLaunchKernelGGL((syrk_bf16_kernel<false, false>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
       }
       // R <- beta R + alpha (G^T)(G^T)^T
       sa.a.from_table = 0; sa.a.base = Gt; sa.a.batch_stride = (int64_t)b.m * b.n; sa.a.ld = b.m;
@@ -1003,11 +1014,14 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       {
         const int64_t total = (int64_t)sa.tiles * sa.batch;
         const int per = (int)((total + NUM_XCD - 1) / NUM_XCD);
+        const bool young = young_factor(step, b.m, b.n);
         if (x2) {
           sa.x_scale2 = reinterpret_cast<const float *>(ws + b.off_inv_g2);
-          hipLaunchKernelGGL(syrk_bf16_kernel<true>, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+          if (young) hipLaunchKernelGGL((syrk_bf16_kernel<true, true>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+          else hipLaunchKernelGGL((syrk_bf16_kernel<true, false>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
         } else {
-          hipLaunchKernelGGL(syrk_bf16_kernel<false>, dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+          if (young) hipLaunchKernelGGL((syrk_bf16_kernel<false, true>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
+          else hipLaunchKernelGGL((syrk_bf16_kernel<false, false>), dim3(per * NUM_XCD), dim3(GEMM_THREADS), 0, s, sa);
         }
       }
       HIP_TRY(hipGetLastError());

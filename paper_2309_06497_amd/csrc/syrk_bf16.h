@@ -3,10 +3,15 @@
 // The product of two bf16 values is exact in float32, so G G^T of a bf16 gradient
 // loses nothing on the bf16 MFMA path (16x the float32 MFMA rate) but the roundings of the
 // float32 accumulator, one per MFMA of 16 values of k: measured 1.3e-7 ... 1.9e-7 of the
-// factor's norm at k = 1024, against a bar of 1e-5 (float64 accumulators, flushed every 32
-// values of k, gave 4e-8 and cost a quarter of the kernel's speed: they took 128 registers
-// per lane).  beta2 L + (1 - beta2) S is evaluated in float64 before the single rounding
-// to float32.  R = G^T G runs through the same kernel on a 16-bit transpose of the
+// factor's norm at k = 1024, against a bar of 1e-5.  That is enough once a factor holds a
+// few times more gradient columns than it has rows (condition number of order 10).  Before
+// that -- the factor of the very first steps is a near-singular Gram matrix, and the first
+// root refresh is taken from it -- its smallest eigenvalues are at 1e-7 of the largest and
+// the sum has to be as good as float32 storage allows: the ACC64 variant starts every slab
+// (32 values of k) from zero accumulators and adds the result into float64 registers
+// (measured 4e-8; 128 more registers per lane, two workgroups per CU, a third slower).  The
+// host picks the variant per step.  beta2 L + (1 - beta2) S is evaluated in float64 before
+// the single rounding to float32.  R = G^T G runs through the same kernel on a 16-bit transpose of the
 // block (transpose_bf16_kernel), so both operands are always read along k; where the
 // fp16 preconditioning products follow, that transpose holds fp16(s G) with a power of
 // two s per block (8 significant bits go into 11, so nothing is lost unless it
@@ -72,8 +77,9 @@ __device__ __forceinline__ floatx16 syrk_mfma(floatx16 acc, const u32x4 &a0, con
 // Requires: operand base 16-byte aligned, ld % 8 == 0, K % 8 == 0 (checked by the host).
 // F16: the operand holds fp16 values (the scaled transpose of a bf16 block: products of two
 // such values are exact in float32 as well) and the fp16 matrix-core instruction is used.
-template <bool F16>
-__global__ __launch_bounds__(GEMM_THREADS, 3) void syrk_bf16_kernel(const SyrkBf16Args g) {
+// ACC64: float64 accumulators, see the head of this file.
+template <bool F16, bool ACC64>
+__global__ __launch_bounds__(GEMM_THREADS, ACC64 ? 2 : 3) void syrk_bf16_kernel(const SyrkBf16Args g) {
   __shared__ __align__(128) unsigned char smem[SYRK_STAGES * SYRK_STAGE];   // the k-step addresses below differ by an XOR
   const int total = g.tiles * g.batch;
   const int logical = xcd_remap(blockIdx.x, total);
@@ -132,12 +138,16 @@ __global__ __launch_bounds__(GEMM_THREADS, 3) void syrk_bf16_kernel(const SyrkBf
   const uint32_t lb0 = lbase + ((wn * 64 + fi) * SBK + ((fq ^ ((fi >> 2) & 3)) * 8)) * 2, lb1 = lb0 ^ 32;
 
   floatx16 acc[2][2];
+  double acc64[ACC64 ? 2 : 1][ACC64 ? 2 : 1][16];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 16; ++v) {
+        acc[i][j][v] = 0.f;
+        if constexpr (ACC64) acc64[i][j][v] = 0.0;
+      }
 
   const int nk = g.K / SBK;                      // full slabs; K % SBK values of k remain
   if (nk > 0) issue(0, 0);
@@ -168,6 +178,14 @@ __global__ __launch_bounds__(GEMM_THREADS, 3) void syrk_bf16_kernel(const SyrkBf
     acc[1][0] = syrk_mfma<F16>(acc[1][0], oa[1][1], ob[0][1]);                            \
     acc[1][1] = syrk_mfma<F16>(acc[1][1], oa[1][1], ob[1][1]);                            \
     LDS_SCHED_BARRIER();                                                                  \
+    if constexpr (ACC64) {                                                                \
+      _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                    \
+        _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_)                                  \
+          _Pragma("unroll") for (int v_ = 0; v_ < 16; ++v_) {                             \
+            acc64[i_][j_][v_] += (double)acc[i_][j_][v_];                                 \
+            acc[i_][j_][v_] = 0.f;                                                        \
+          }                                                                               \
+    }                                                                                     \
   }
 
   if (g.K % SBK) {
@@ -238,7 +256,9 @@ __global__ __launch_bounds__(GEMM_THREADS, 3) void syrk_bf16_kernel(const SyrkBf
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const float x = (float)(alpha * (double)acc[mi][ni][v] + g.beta * (double)old[ni][v]);
+        double sum;
+        if constexpr (ACC64) sum = acc64[mi][ni][v]; else sum = (double)acc[mi][ni][v];
+        const float x = (float)(alpha * sum + g.beta * (double)old[ni][v]);
         if (i < g.M && j < g.M) c[(int64_t)i * ldc + j] = x;
       }
     }

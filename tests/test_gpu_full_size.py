@@ -34,14 +34,11 @@ def f32(x):
 def test_transformer_full_size_sampled_blocks():
     """Five steps of the 1.2e9-parameter set with the roots refreshed at t = 0 (from a single
     gradient: ill-conditioned) and t = 3 (well conditioned); sampled blocks and two LayerNorm
-    vectors against the oracle.  Bars: factors 1e-5; root inverse against the oracle's on the
-    same float32 factor bits 2e-3; directions, momentum and parameter updates 2e-3, plus --
-    while the t = 0 roots are in use -- the allowance for what float32 storage of an
-    ill-conditioned factor can cost: theta ||L||_F / (4 (lambda_min + eps)), theta = 2e-7,
-    summed over both factors (the stored factor is within theta ||L||_F of the exact one, an
-    eigenvalue moves by at most that, and (lambda + eps)^(-1/4) by a quarter of the relative
-    change).  From t = 3 on the allowance is negligible and the bar is the plain 2e-3 for the
-    direction; M and W still carry the earlier steps."""
+    vectors against the oracle.  Bars, all plain: factors 1e-5; root inverse against the
+    oracle's on the same float32 factor bits 2e-4; directions, momentum and parameter updates
+    2e-3 at every step, also while the roots of the single-gradient factors are in use (the
+    factor update of those first steps sums in float64; what remains is the float32 storage of
+    the factor, measured 3e-4 ... 6e-4 in the direction)."""
     import torch
     shapes = wl.transformer_shapes()
     dev = torch.device("cuda", 0)
@@ -67,8 +64,7 @@ def test_transformer_full_size_sampled_blocks():
     w0 = {key: w_ora[key][0].copy() for key in sample}
     ora_v = {i: so.ShampooOracle([shapes[i]], 1024, f32(0.999), f32(1e-12), 0.25, F, 0, f32(1e-10), f32(0.9)) for i in vecs}
     wv_ora = {i: [params[i].cpu().numpy().astype(np.float64)] for i in vecs}
-    allow = {key: 0.0 for key in sample}
-    allow_hist = {key: 0.0 for key in sample}
+    cond = {key: 0.0 for key in sample}
     for t in range(5):
         say(f"  step {t}")
         grads = [(torch.randn(s, generator=gen, device=dev) * 1e-3).to(torch.bfloat16) for s in shapes]
@@ -89,17 +85,16 @@ def test_transformer_full_size_sampled_blocks():
             if t % F == 0:
                 Li = opt.get(i, k, B.GET_LINV).cpu().numpy()
                 e_root = rel(Li, so.root_inverse(L, f32(1e-12), 0.25)[0])
-                assert e_root <= 2e-3
-                allow[key] = sum(0.25 * 2e-7 * np.linalg.norm(Fm) / (max(np.linalg.eigvalsh(Fm)[0], 0.0) + f32(1e-12))
-                                 for Fm in (ora[key].L[0][0], ora[key].R[0][0]))
-                allow_hist[key] = max(allow_hist[key], allow[key])
+                assert e_root <= 2e-4
+                # smallest eigenvalue of the factors against the largest: what makes t = 0 hard
+                cond[key] = max(np.linalg.eigvalsh(Fm)[-1] / max(np.linalg.eigvalsh(Fm)[0], 1e-300)
+                                for Fm in (ora[key].L[0][0], ora[key].R[0][0]))
             say(f"    block {key}: L={e_l:.1e} R={e_r:.1e} root={e_root:.1e} Psh={e_p:.1e} M={e_m:.1e} dW={e_w:.1e}"
-                f" (allowance {allow[key]:.1e})")
+                f" (condition number of the factors in use {cond[key]:.1e})")
             assert e_l <= 1e-5 and e_r <= 1e-5
-            assert e_p <= 2e-3 + allow[key]
-            assert e_m <= 2e-3 + allow_hist[key] and e_w <= 2e-3 + allow_hist[key]
+            assert e_p <= 2e-3 and e_m <= 2e-3 and e_w <= 2e-3
             if t >= F:
-                assert allow[key] <= 1e-4 and e_p <= 2e-3
+                assert e_p <= 2e-5
         for i in vecs:
             ora_v[i].step(wv_ora[i], [grads[i].to(torch.float32).cpu().numpy()], f32(0.01), t)
             assert rel(params[i].cpu().numpy(), wv_ora[i][0]) <= 1e-6
@@ -153,7 +148,7 @@ def test_root_inverse_stress_2048():
         assert e_top <= 1e-5
         assert e_range <= 2e-3
         assert e_x4 <= 2e-3
-        assert e_full <= 0.5
+        assert e_full <= 3e-3
 
 
 @pytest.mark.timeout(900)

@@ -16,6 +16,8 @@ pytestmark = pytest.mark.gpu
 
 TOL_FACTOR = 1e-5
 TOL_DIR = 2e-3
+TOL_ROOT = 2e-4     # GPU root vs the oracle's root of the same float32 factor bits (measured <= 2e-5)
+TOL_GEMM = 2e-5     # GPU Lbar G Rbar vs the float64 product of the GPU's roots (measured <= 4e-6)
 
 
 def say(msg):
@@ -50,30 +52,91 @@ def grads_for_oracle(dev_grads):
     return [g.to(torch.float32).cpu().numpy() for g in dev_grads]
 
 
+class StorageEffect:
+    """First-order effect of float32 storage of a factor F on its root X = f(F),
+    f(lambda) = (lambda - min(lambda_min, 0) + eps)^(-1/4): for F = Q diag(lambda) Q^T and a
+    symmetric perturbation E, dX = Q (D o (Q^T E Q)) Q^T with the divided differences
+    D_ij = (f_i - f_j) / (lambda_i - lambda_j), D_ii = f'(lambda_i) (the derivative of a matrix
+    function; the dependence of the shift on lambda_min is left out: it is zero for the positive
+    semi-definite factors in exact arithmetic).  E models one rounding to float32 of every
+    entry: E_ij = F_ij u_ij, u_ij = u_ji uniform in [-2^-24, 2^-24], independent.  Uses only
+    numpy and the oracle's factor; a diagonalised factor (a vector) is treated entry by entry."""
+
+    DRAWS = 4
+
+    def __init__(self, F, eps, seed):
+        F = np.asarray(F, dtype=np.float64)
+        self.rng = np.random.default_rng(seed)
+        if F.ndim == 1:
+            lp = F - min(F.min(), 0.0) + eps
+            self.F, self.Q, self.D = F.astype(np.float32), None, (-0.25 * lp ** -1.25).astype(np.float32)
+            return
+        lam, Q = np.linalg.eigh(F)
+        lp = lam - min(lam[0], 0.0) + eps
+        f = lp ** -0.25
+        d = lp[:, None] - lp[None, :]
+        mid = 0.5 * (lp[:, None] + lp[None, :])
+        close = np.abs(d) <= 1e-7 * mid
+        with np.errstate(divide="ignore", invalid="ignore"):
+            D = (f[:, None] - f[None, :]) / d
+        D[close] = (-0.25 * mid ** -1.25)[close]
+        self.F, self.Q, self.D = F.astype(np.float32), Q.astype(np.float32), D.astype(np.float32)
+
+    def draw(self):
+        """One dX (dense float64 matrix)."""
+        u = 2.0 ** -24
+        F = self.F.astype(np.float64)
+        if self.Q is None:
+            return np.diag(self.D.astype(np.float64) * F * self.rng.uniform(-u, u, F.shape))
+        U = np.triu(self.rng.uniform(-u, u, F.shape))
+        E = F * (U + np.triu(U, 1).T)
+        Q = self.Q.astype(np.float64)
+        return Q @ (self.D.astype(np.float64) * (Q.T @ E @ Q)) @ Q.T
+
+
 class Pair:
     """Runs the library and the oracle side by side on the same inputs.
 
     Checks after a step:
       factors     GPU L, R vs the oracle's float64 factors                 <= 1e-5
       roots       (refresh steps) GPU root vs the oracle's root inverse of the
-                  GPU's own float32 factor bits (isolates the eigensolver)    <= 2e-3
-      direction   GPU Lbar G Rbar vs the float64 product of the GPU's roots   <= 2e-3
+                  GPU's own float32 factor bits (isolates the eigensolver)    <= tol_root
+      direction   GPU Lbar G Rbar vs the float64 product of the GPU's roots   <= tol_gemm
       end to end  GPU P_shampoo, M, W vs the oracle's own trajectory:
-                  per block                                  <= 2e-3 + conditioning allowance
-                  over all blocks with allowance <= 2e-3 together            <= 2e-3
-    The allowance is what float32 storage of a factor can cost: the stored factor
-    differs from the exact one by |E| <= theta ||L||_F (theta = 2e-7, the measured
-    factor error: up to 1.9e-7 on the bf16 matrix-core path, 4e-8 on the float32 one), an eigenvalue moves by at most that, and (lambda + eps)^(-1/4)
-    then changes by at most the relative amount theta ||L||_F / (4 (lambda_min + eps)).
-    It only matters (a) for the first refresh, taken from a single gradient (L = G G^T
-    has the squared condition number of G); later factors are well conditioned and the
-    allowance vanishes; (b) for rank-deficient factors of thin edge blocks used with a
-    stale root, where the null space is weighted by (noise + eps)^(-1/4) and float32
-    noise is not small against eps = 1e-12.  M and W carry earlier steps with them, so
-    they are held to the largest allowance seen so far.
+                  over all resolved blocks together (the plain bar; Lbar G Rbar of a
+                  block weighted by the norm grafting rescales it to)        <= 2e-3
+                  per resolved block                   <= 2e-3 + min(allowance, 10 x 2e-3)
+    The stage-wise bars are about ten times what the kernels measure (the design doc lists the
+    measurements): roots 2e-4 (1e-6 at n <= 128 ... 2e-5 at n = 1024 measured), products 2e-5
+    (<= 4e-6 measured).
+
+    Float32 storage of a factor is part of the workload, and it limits what any kernel can
+    deliver end to end: a root weights the smallest eigenvalues of its factor most, the first
+    refresh is taken from a single gradient (a Gram matrix with the squared condition number
+    of G, 1e7 and up for square blocks), and thin edge blocks have rank-deficient factors for
+    many steps, whose null space a stale root weights by (rounding noise + eps)^(-1/4) with
+    eps = 1e-12.  What that storage costs is computed from the oracle alone (`StorageEffect`),
+    per block and step: s = the root-mean-square relative change of the oracle's direction
+    Lbar G Rbar when every entry of its factors is moved by an independent relative rounding
+    error of float32 (uniform in +-2^-24), to first order in the error.
+      * 2 s <= 2e-3 ("resolved"): the block counts in the all-blocks aggregate, which is held
+        to the plain 2e-3, and on its own it is held to 2e-3 + min(8 s, 10 x 2e-3).  The 8 is
+        2 x 4: the device's factor carries about two such roundings (the sum G G^T, which the
+        kernels deliver at storage accuracy: measured 4e-8 ... 9e-8 of the factor's norm
+        against 3.4e-8 for one rounding; and the moving average), and among the few thousand
+        block-steps of a test a four-sigma draw occurs.
+      * 2 s > 2e-3: float32 does not resolve what the root weights most; the block is not graded
+        end to end (stage by stage it is held to the same bars as every other block: the root
+        against the oracle's on the *same* float32 bits is well posed), it is counted, and
+        the test fails if more than `max_unresolved` of the blocks (5 %, rounded up,
+        unless the test says why it needs more) are in that state.
+    M and W carry earlier steps with them: they use the largest s a block has had at a checked
+    step, and a block that was unresolved stays out.
     """
 
-    THETA = 2e-7
+    ALLOW_FACTOR = 8.0             # per-block allowance = ALLOW_FACTOR * s ...
+    ALLOW_CAP_BARS = 10.0          # ... but at most this many times the bar
+    RESOLVED_FACTOR = 2.0          # resolved: RESOLVED_FACTOR * s <= bar
 
     def __init__(self, shapes, b, beta2, f, start=0, mu=0.9, eps=1e-12, eps_g=1e-10, bf16=False, seed=0,
                  beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad",
@@ -100,8 +163,9 @@ class Pair:
         self.w0 = [w.astype(np.float64) for w in w0]
         self.w_ora = [w.astype(np.float64) for w in w0]
         self.w_gpu = to_dev(w0)
-        self.allow = {}      # (param, block) -> conditioning allowance of the roots in use
-        self.allow_hist = {}  # largest allowance so far (for M and W)
+        self.effect = {}     # (param, block) -> StorageEffect of the two factors whose roots are in use
+        self.s_now = {}      # (param, block) -> s of the last checked step
+        self.s_hist = {}     # largest s so far (for M and W)
         self.g_last = None
 
     def step(self, grads_np, lr, t, misalign=False):
@@ -124,12 +188,29 @@ class Pair:
         if t >= self.start and t % self.f == 0:
             for i, s in enumerate(self.shapes):
                 for k in range(len(self.ora.blocks[i])):
-                    a = 0.0
-                    for F in (self.ora.L[i][k], self.ora.R[i][k]):
-                        lam_min = max(np.linalg.eigvalsh(F)[0] if F.ndim == 2 else F.min(), 0.0)
-                        a += 0.25 * self.THETA * np.linalg.norm(F) / (lam_min + self.eps)
-                    self.allow[(i, k)] = a
-                    self.allow_hist[(i, k)] = max(a, self.allow_hist.get((i, k), 0.0))
+                    c2 = 1.0
+                    if self.ora.bias_correction and self.ora.beta2 < 1.0:
+                        c2 = 1.0 / (1.0 - self.ora.beta2 ** (t + 1))
+                    self.effect[(i, k)] = tuple(StorageEffect(c2 * F, self.eps, 1000 * i + k)
+                                                for F in (self.ora.L[i][k], self.ora.R[i][k]))
+
+    def _oracle_root(self, F, t):
+        """The oracle's root of a factor given as an array (float32 bits or float64), by the
+        refresh rule in force at step t."""
+        c2 = 1.0
+        if self.ora.bias_correction and self.ora.beta2 < 1.0:
+            c2 = 1.0 / (1.0 - self.ora.beta2 ** (t + 1))
+        F = c2 * F.astype(np.float64)
+        if F.ndim == 1:     # a diagonalised factor (vector): the same box on its entries
+            return (F + self.eps) ** -0.25
+        if self.newton:
+            # the oracle's rule: an iteration that does not stay finite gives way to the
+            # spectral definition
+            with np.errstate(all="ignore"):
+                X = so.root_inverse_newton(F, self.eps, 4, f32(self.newton[0]), self.newton[1])[0]
+            if np.all(np.isfinite(X)):
+                return X
+        return so.root_inverse(F, self.eps, 0.25)[0]
 
     def resync(self):
         """Hand the oracle the GPU's weights, so that the next step's dW is compared on equal
@@ -138,7 +219,8 @@ class Pair:
         self.w_ora = [w.cpu().numpy().astype(np.float64) for w in self.w_gpu]
         self.w0 = [w.copy() for w in self.w_ora]
 
-    def check(self, t, use_shampoo=True, tol_dir=TOL_DIR, history=True, roots=True):
+    def check(self, t, use_shampoo=True, tol_dir=TOL_DIR, history=True, roots=True, tol_root=TOL_ROOT, tol_gemm=TOL_GEMM,
+              max_unresolved=0.05):
         """history=False skips M and W, which also carry the errors of earlier steps.
         roots=False skips the comparison of the root matrices themselves (their action on the
         gradient is still compared): for factors that float32 cannot resolve, e.g. the ones
@@ -150,17 +232,23 @@ class Pair:
         den = {"Psh": 0.0, "M": 0.0, "dW": 0.0}
         over = []
         excluded = set()
+        lost_worst = {"Psh": 0.0, "M": 0.0, "dW": 0.0}
+        n_blocks = sum(max(1, len(bl)) for bl in self.ora.blocks)
 
-        def e2e(key, got, want, blk):
+        def e2e(key, got, want, blk, weight=None):
             d = np.linalg.norm(np.asarray(got, np.float64) - want) ** 2
             w = np.linalg.norm(want) ** 2
-            allow = (self.allow if key == "Psh" else self.allow_hist).get(blk, 0.0)
-            if allow <= tol_dir:
-                num[key] += d; den[key] += w
-            else:
-                excluded.add(blk)
             r = np.sqrt(d / w) if w > 0 else np.sqrt(d)
+            if weight is not None and w > 0:      # the block enters the aggregate with this squared norm
+                d, w = d / w * weight, weight
+            s_blk = (self.s_now if key == "Psh" else self.s_hist).get(blk, 0.0)
+            if self.RESOLVED_FACTOR * s_blk > tol_dir:
+                excluded.add(blk)
+                lost_worst[key] = max(lost_worst[key], r)
+                return
+            num[key] += d; den[key] += w
             worst[key] = max(worst[key], r)
+            allow = min(self.ALLOW_FACTOR * s_blk, self.ALLOW_CAP_BARS * tol_dir)
             if r > tol_dir + allow:
                 over.append((key, blk, r, allow))
 
@@ -188,23 +276,7 @@ class Pair:
                     Ri = self.gpu.get(i, k, B.GET_RINV).cpu().numpy()
                     assert np.array_equal(Li, Li.T) and np.array_equal(Ri, Ri.T)
                     if refresh and roots:
-                        c2 = 1.0
-                        if self.ora.bias_correction and self.ora.beta2 < 1.0:
-                            c2 = 1.0 / (1.0 - self.ora.beta2 ** (t + 1))
-                        if self.newton:
-                            def root(F):
-                                # the oracle's rule: an iteration that does not stay finite gives way
-                                # to the spectral definition
-                                with np.errstate(all="ignore"):
-                                    X = so.root_inverse_newton(c2 * F.astype(np.float64), self.eps, 4,
-                                                               f32(self.newton[0]), self.newton[1])[0]
-                                if np.all(np.isfinite(X)):
-                                    return X
-                                return so.root_inverse(c2 * F.astype(np.float64), self.eps, 0.25)[0]
-                        else:   # a diagonalised factor (vector): the same box on its entries
-                            root = lambda F: (so.root_inverse(c2 * F.astype(np.float64), self.eps, 0.25)[0] if F.ndim == 2
-                                              else (c2 * F.astype(np.float64) + self.eps) ** -0.25)
-                        worst["root"] = max(worst["root"], rel(Li, root(L)), rel(Ri, root(R)))
+                        worst["root"] = max(worst["root"], rel(Li, self._oracle_root(L, t)), rel(Ri, self._oracle_root(R, t)))
                     P = self.gpu.get(i, k, B.GET_PSH).cpu().numpy()
                     c1 = 1.0
                     if self.ora.bias_correction and self.ora.beta1 > 0:
@@ -214,7 +286,18 @@ class Pair:
                                               if self.ora.wd > 0 and not self.ora.decoupled else 0.0))
                     full = lambda X: np.diag(X.astype(np.float64)) if X.ndim == 1 else X.astype(np.float64)
                     worst["gemm"] = max(worst["gemm"], rel(P, so.shampoo_direction(full(Li), g_dir, full(Ri))))
-                    e2e("Psh", P, self.ora.P_sh[i][k], (i, k))
+                    if (i, k) in self.effect:
+                        el, er = self.effect[(i, k)]
+                        lo, ro = full(self.ora.Lbar[i][k]), full(self.ora.Rbar[i][k])
+                        d2 = np.mean([np.linalg.norm(el.draw() @ g_dir @ ro + lo @ g_dir @ er.draw()) ** 2
+                                      for _ in range(StorageEffect.DRAWS)])
+                        s_blk = np.sqrt(d2) / max(np.linalg.norm(self.ora.P_sh[i][k]), 1e-300)
+                        self.s_now[(i, k)] = s_blk
+                        self.s_hist[(i, k)] = max(s_blk, self.s_hist.get((i, k), 0.0))
+                    # Grafting rescales every block's Lbar G Rbar to the norm of its grafted
+                    # direction, so that is the weight with which a block's relative error enters
+                    # the error of the search direction as a whole
+                    e2e("Psh", P, self.ora.P_sh[i][k], (i, k), weight=self.ora.s_g[i][k])
                     norms = self.gpu.get(i, k, B.GET_NORMS).cpu().numpy()
                     assert abs(norms[0] - self.ora.s_g[i][k]) <= 2e-4 * self.ora.s_g[i][k] + 1e-30
                     assert abs(norms[1] - np.sum(P.astype(np.float64) ** 2)) <= 1e-4 * norms[1] + 1e-30
@@ -224,12 +307,16 @@ class Pair:
                     e2e("dW", dw_g[sl], dw_o[sl], (i, k))
         total = {k: (np.sqrt(num[k] / den[k]) if den[k] > 0 else 0.0) for k in num}
         say(f"    t={t} worst block: " + " ".join(f"{k}={v:.1e}" for k, v in worst.items())
-            + f" | all but {len(excluded)} blocks: " + " ".join(f"{k}={v:.1e}" for k, v in total.items()))
+            + f" | all {n_blocks - len(excluded)} resolved blocks: " + " ".join(f"{k}={v:.1e}" for k, v in total.items())
+            + f" (largest s {max([v for v in self.s_now.values() if self.RESOLVED_FACTOR * v <= tol_dir], default=0.0):.1e})"
+            + (f" | {len(excluded)} unresolved in float32 (not graded end to end): "
+               + " ".join(f"{k}={v:.1e}" for k, v in lost_worst.items()) if excluded else ""))
         assert worst["L"] <= TOL_FACTOR and worst["R"] <= TOL_FACTOR
         assert worst["A"] <= 1e-6
-        assert worst["root"] <= tol_dir and worst["gemm"] <= tol_dir
+        assert worst["root"] <= tol_root and worst["gemm"] <= tol_gemm, (worst["root"], worst["gemm"])
         assert all(v <= tol_dir for v in total.values()), total
         assert not over, over[:5]
+        assert len(excluded) <= np.ceil(max_unresolved * n_blocks), (len(excluded), n_blocks)
         return worst, total
 
 
@@ -241,7 +328,10 @@ def test_tiny_config_every_step():
     p = Pair(shapes, 64, 1.0, 10)
     for t in range(20):
         p.step(wl.gaussian_grads(shapes, 1, t, 0.01), 0.01, t)
-        p.check(t)
+        # Until the second refresh the roots are those of single-gradient 64 x 64 Gram matrices
+        # (condition number 1e5 ... 1e7): s = 5e-4 ... 2e-3 per block, right at the bar, and at
+        # some steps two of the eight blocks are on the far side of it.
+        p.check(t, max_unresolved=0.25)
     st = p.gpu.status()
     assert st["refreshes"] == 2 and st["failed_roots"] == 0
 
@@ -284,7 +374,10 @@ def test_bf16_gradients_and_larger_blocks(fp32_mc):
     for t in range(6):
         p.step(wl.gaussian_grads(shapes, 4, t, 1e-3), 0.01, t)
         if t in (0, 3, 4, 5):
-            p.check(t)
+            # four of the nine blocks are thin edge blocks (256 x 8, 44 x 256 twice, 44 x 8) whose
+            # larger factor is still rank-deficient after five gradients: with eps = 1e-12 their
+            # stale roots are not resolved by float32
+            p.check(t, max_unresolved=4 / 9)
 
 
 def test_bf16_ragged_blocks_on_matrix_cores():
@@ -476,7 +569,9 @@ def test_step_argument_errors():
 def test_decoupled_weight_decay_with_nesterov():
     say("case decoupled wd + nesterov")
     shapes = [(96, 80), (33,), (64, 64)]
-    p = Pair(shapes, 64, 0.999, 2, weight_decay=0.1, decoupled=True, nesterov=True)
+    # eps = 1e-6 keeps the stale roots of the rank-deficient edge blocks (64 x 16, 32 x 64, 32 x 16)
+    # well posed: this case is about the decay and the look-ahead, not about conditioning
+    p = Pair(shapes, 64, 0.999, 2, weight_decay=0.1, decoupled=True, nesterov=True, eps=1e-6)
     for t in range(5):
         p.step(wl.gaussian_grads(shapes, 31, t, 1e-2), 0.01, t)
         p.check(t)
@@ -516,7 +611,8 @@ def test_l2_weight_decay_with_bf16_gradients():
 def test_sgd_grafting_and_warmup():
     say("case sgd grafting")
     shapes = [(96, 80), (33,)]
-    p = Pair(shapes, 64, 0.999, 2, start=2, grafting="sgd")
+    # eps = 1e-6: see test_decoupled_weight_decay_with_nesterov
+    p = Pair(shapes, 64, 0.999, 2, start=2, grafting="sgd", eps=1e-6)
     for t in range(5):
         p.step(wl.gaussian_grads(shapes, 35, t, 1e-2), 0.01, t)
         p.check(t, use_shampoo=(t >= 2))
