@@ -5,12 +5,12 @@
  * step of Shi et al., "A Distributed Data-Parallel PyTorch Implementation of
  * the Distributed Shampoo Optimizer for Training Neural Networks At-Scale"
  * (arXiv 2309.06497), restricted to one GPU: blocked Kronecker-factor
- * accumulation (matrices, and tensors of order three after merging of small
- * dimensions), periodic inverse-root refresh by batched symmetric
- * eigendecomposition, preconditioning by the roots, AdaGrad or SGD grafting,
- * gradient filtering, weight decay, (Nesterov) momentum and the parameter
- * update.  The multi-GPU distribution of the paper (Sec. 4.1)
- * is not part of this library.
+ * accumulation (matrices, and tensors of order one, three and four after merging
+ * of small dimensions), periodic inverse-root refresh by batched symmetric
+ * eigendecomposition (or the coupled inverse Newton iteration), preconditioning
+ * by the roots, AdaGrad / SGD / RMSprop / Adam grafting, gradient filtering,
+ * bias correction, weight decay, (Nesterov) momentum and the parameter update.
+ * The multi-GPU distribution of the paper (Sec. 4.1) is not part of this library.
  *
  * Conventions for every entry point
  *   - "device pointer": memory of the GPU the optimizer was created on,
@@ -57,7 +57,7 @@ enum { SHAMPOO_LARGE_DIM_BLOCKING = 0, SHAMPOO_LARGE_DIM_ADAGRAD = 1, SHAMPOO_LA
 /*
  * Optimizer configuration (copied at create; the arrays need not outlive the call).
  * Hyper-parameters are those of the paper's complete pseudocode (Sec. 3,
- * "Complete Distributed Shampoo Pseudocode"), without bias correction.
+ * "Complete Distributed Shampoo Pseudocode").
  */
 typedef struct {
   int32_t n_params;       /* number of parameters (tensors), >= 1                          */
@@ -66,10 +66,10 @@ typedef struct {
                              merged (Sec. 4.2.1: from the left, a dimension joins the current
                              group while the product stays <= block_size, a dimension of size 1
                              always; only a view, no data moves).  Two dimensions left: the matrix case on the merged shape.
-                             Three left, or one (all merged): Shampoo for a tensor of that order
-                             w (Sec. 2.3), one factor per dimension, root exponent
-                             2 * root_exponent / w, blocks of at most block_size per dimension.
-                             Four left: SHAMPOO_ERR_UNSUPPORTED                              */
+                             Three or four left, or one (all merged): Shampoo for a tensor of that
+                             order w (Sec. 2.3), one factor per dimension, root exponent
+                             2 * root_exponent / w, blocks of at most block_size per dimension
+                             (a block of more than 2^30 elements: SHAMPOO_ERR_UNSUPPORTED)   */
   const int64_t *shape;   /* host [SHAMPOO_MAX_NDIM * n_params]: the ndim[i] dimensions of
                              parameter i, slowest first, at shape[SHAMPOO_MAX_NDIM * i ...];
                              the remaining entries are ignored                               */
@@ -100,7 +100,9 @@ typedef struct {
                              1-D parameter (Sec. 4.2.2);
                              SHAMPOO_LARGE_DIM_DIAGONAL: kept whole, the factor of each such
                              dimension replaced by its diagonal (Sec. 4.2.3).
-                             Tensors of order 1 or 3 (after merging) are always blocked      */
+                             Tensors of order 1, 3 or 4 (after merging) are always blocked;
+                             more than 65535 whole parameters or tensor blocks of one shape:
+                             SHAMPOO_ERR_UNSUPPORTED                                          */
   int32_t root_method;    /* SHAMPOO_ROOT_EIGH: eigendecomposition (framed box of Sec. 3.2.1, default);
                              SHAMPOO_ROOT_NEWTON: coupled inverse Newton iteration of the same
                              section on L + epsilon I, in float32; needs 1/root_exponent in
@@ -182,7 +184,13 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
  * grads:  host array [n_params] of device pointers, float32 or bfloat16 per
  *         grad_dtype, same shapes; read only.
  * Asynchronous on `stream` (except refresh steps under SHAMPOO_ROOT_NEWTON, see
- * root_method).  A factor whose eigendecomposition is not finite keeps its
+ * root_method, and a call that follows a change of the params / grads pointers, which first
+ * waits for `stream`: the tables it sends replace those an earlier call may still be copying).
+ * With bf16 gradients the factor update of the first steps, while a factor has summed fewer than
+ * four times as many gradient columns as it has rows, adds up in float64 (the later ones in the
+ * float32 accumulators of the matrix cores): a root taken from such a young factor weights its
+ * smallest eigenvalues most.  If a launch fails (SHAMPOO_ERR_HIP) the state is partly updated
+ * and `step` does not count as taken.  A factor whose eigendecomposition is not finite keeps its
  * previous root (Sec. 3.2.3); such events are counted, see shampoo_status.
  */
 int shampoo_step(shampoo_opt *opt, void *const *params, const void *const *grads,

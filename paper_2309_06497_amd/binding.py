@@ -185,6 +185,7 @@ class Shampoo:
                                use_bias_correction, root_method, newton_tolerance, newton_max_iterations,
                                grafting_beta2, large_dim_method, precond_matrix_cores)
         self.device = torch.device("cuda", device)
+        self.grad_dtype = grad_dtype
         nbytes = shampoo_workspace_bytes(self.cfg)
         if nbytes == 0:
             raise ShampooError(lib().shampoo_plan(ctypes.byref(self.cfg), None, 0, None, None) or -2)
@@ -199,9 +200,22 @@ class Shampoo:
 
     def step(self, params, grads, lr, step):
         """params / grads: lists of contiguous CUDA tensors (float32 / float32-or-bfloat16)."""
+        import torch
+        gdt = torch.bfloat16 if self.grad_dtype == GRAD_BF16 else torch.float32
+        if len(params) != self._n or len(grads) != self._n:
+            raise ValueError("one parameter and one gradient tensor per declared parameter")
         for i in range(self._n):
-            self._pw[i] = params[i].data_ptr()
-            self._pg[i] = grads[i].data_ptr()
+            w, g = params[i], grads[i]
+            if not (w.is_cuda and g.is_cuda and w.device == self.device and g.device == self.device):
+                raise ValueError(f"parameter {i}: tensors must live on {self.device}")
+            if w.dtype != torch.float32 or g.dtype != gdt:
+                raise ValueError(f"parameter {i}: parameters are float32, gradients {gdt}")
+            if not (w.is_contiguous() and g.is_contiguous()):
+                raise ValueError(f"parameter {i}: tensors must be contiguous")
+            if tuple(w.shape) != tuple(self.shapes[i]) or tuple(g.shape) != tuple(self.shapes[i]):
+                raise ValueError(f"parameter {i}: shape differs from the one given at creation")
+            self._pw[i] = w.data_ptr()
+            self._pg[i] = g.data_ptr()
         _check(lib().shampoo_step(self.handle, self._pw, self._pg, lr, step, _stream_ptr()))
 
     def get(self, param, block, which):

@@ -19,8 +19,7 @@ FLAGS = [
 
 def build(verbose=True):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    extra = os.environ.get("SHAMPOO_EXTRA_FLAGS", "").split()   # e.g. -DSHAMPOO_GEMM_BK=32
-    cmd = [hipcc] + FLAGS + extra + SOURCES + ["-o", LIB]
+    cmd = [hipcc] + FLAGS + SOURCES + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -172,12 +172,6 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
   float *mp = g.m_state ? g.m_state + d.state_offset : nullptr;
   const int ld = d.ld;
 
-#ifdef SB_PROFILE   // compile-time diagnostic: cycle stamps of the phases, printed for two workgroups
-  long long tp[8]; tp[0] = clock64();
-#define SB_STAMP(k) tp[k] = clock64();
-#else
-#define SB_STAMP(k)
-#endif
   // ---- G -> LDS, grafting state and graft norm on the way (each element once)
   {
     const bool vec = ((ld & 3) == 0) && ((n & 3) == 0) && ((d.offset & 3) == 0) && ((d.state_offset & 3) == 0) &&
@@ -221,7 +215,6 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
     if (tid == 0) norms[0] = ss;
     // (ss = s_g stays in a register of every thread until the update)
     // ---- factor updates (Gs is read-only here, no barriers needed)
-    SB_STAMP(1)
     {
       float *Lp = reinterpret_cast<float *>(g.ws + sbk.off_L), *Rp = reinterpret_cast<float *>(g.ws + sbk.off_R);
       const int r0 = wm * 64, c0 = wn * 64;
@@ -237,14 +230,12 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
       if (l1) sb_half_products<0>(Gs, n, r0 + 32, c0, l32, khalf, acc64);
       if (q0) sb_half_prefetch(Rp, n, g.beta_d, r0, c0, l32, khalf, oldA);
       if (l1) sb_half_store(Lp, m, g.alpha_d, g.beta_d, r0 + 32, c0, l32, khalf, acc64, oldB);
-      SB_STAMP(2)
       if (q0) sb_half_products<1>(Gs, m, r0, c0, l32, khalf, acc64);
       if (q1) sb_half_prefetch(Rp, n, g.beta_d, r0 + 32, c0, l32, khalf, oldB);
       if (q0) sb_half_store(Rp, n, g.alpha_d, g.beta_d, r0, c0, l32, khalf, acc64, oldA);
       if (q1) sb_half_products<1>(Gs, m, r0 + 32, c0, l32, khalf, acc64);
       if (q1) sb_half_store(Rp, n, g.alpha_d, g.beta_d, r0 + 32, c0, l32, khalf, acc64, oldB);
     }
-    SB_STAMP(3)
 
     floatx16 acc[2][2];
     const bool active = wm * 64 < m && wn * 64 < n;    // wave-uniform: this quadrant holds part of the block
@@ -284,8 +275,6 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
             for (int e = 0; e < 4; ++e)
               Gs[(wm * 64 + mi * 32 + 8 * q + 4 * khalf + e) * SB_LD + wn * 64 + ni * 32 + l32] = acc[mi][ni][4 * q + e];
     }
-
-    SB_STAMP(4)
     // ---- P_sh = T Rbar: A(i,k) = T[i][k] from LDS, B(k,j) = Rbar[k][j] through Xs
     {
       const float *Ri = reinterpret_cast<const float *>(g.ws + sbk.off_Rinv);
@@ -320,8 +309,6 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
         __syncthreads();
       }
     }
-
-    SB_STAMP(5)
     // ---- norms, scale, momentum and parameter update straight from the accumulators
     float sp = 0.f;
 #pragma unroll
@@ -343,7 +330,6 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
     // zero (or non-finite) norms give a zero step for the block instead of NaN
     const bool ok = (ss > 0.f) && (sp > 0.f) && (ss <= 3.0e38f) && (sp <= 3.0e38f);
     const float sc = ok ? (float)(-sqrt((double)ss / (double)sp)) : 0.f;
-    SB_STAMP(6)
     float *Pp = reinterpret_cast<float *>(g.ws + sbk.off_P);
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
@@ -368,16 +354,9 @@ __global__ __launch_bounds__(SB_THREADS, 2) void block_step_small_kernel(const S
           }
         }
       }
-#ifdef SB_PROFILE
-    tp[7] = clock64();
-    if (tid == 0 && (slot == 0 || slot == 300))
-      printf("slot %d cycles: load %lld  L %lld  R %lld  T %lld  P %lld  norm %lld  upd %lld  total %lld\n", slot,
-             tp[1] - tp[0], tp[2] - tp[1], tp[3] - tp[2], tp[4] - tp[3], tp[5] - tp[4], tp[6] - tp[5], tp[7] - tp[6], tp[7] - tp[0]);
-#endif
   }
 }
 
-#undef SB_STAMP
 #undef SB_ZERO_ACC
 #undef SB_MFMA4
 

@@ -28,10 +28,7 @@
 namespace shampoo {
 
 constexpr int JAC_THREADS = 256;
-#ifndef SHAMPOO_PIV_THREADS
-#define SHAMPOO_PIV_THREADS 256
-#endif
-constexpr int JAC_PIV_THREADS = SHAMPOO_PIV_THREADS;   // workgroup of the 64 x 64 pivot solver
+constexpr int JAC_PIV_THREADS = 256;   // workgroup of the 64 x 64 pivot solver
 constexpr int JAC_NB = 32;            // block-column width of the block solver
 constexpr int JAC_PIV = 2 * JAC_NB;   // pivot size
 constexpr int JAC_SMALL_MAX = 128;    // largest n solved entirely in LDS
@@ -584,10 +581,7 @@ __device__ __forceinline__ void sub_stash(double *X, int ra, int cb, int xi, int
   }
 }
 
-#ifndef SHAMPOO_APPW_SEG
-#define SHAMPOO_APPW_SEG 4
-#endif
-constexpr int APPW_SEG = SHAMPOO_APPW_SEG;   // pair-blocks of one block row handled by one workgroup
+constexpr int APPW_SEG = 4;   // pair-blocks of one block row handled by one workgroup
 
 // number of workgroups per matrix: row k of the lower triangle has k + 1 pair-blocks
 inline int appw_segments(int hp) {

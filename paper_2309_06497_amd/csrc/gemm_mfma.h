@@ -24,17 +24,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 128;
 constexpr int BN = 128;
-#ifndef SHAMPOO_GEMM_BK
-#define SHAMPOO_GEMM_BK 16
-#endif
-#ifndef SHAMPOO_GEMM_PAD
-#define SHAMPOO_GEMM_PAD 4
-#endif
-#ifndef SHAMPOO_GEMM_MINBLOCKS
-#define SHAMPOO_GEMM_MINBLOCKS 2
-#endif
-constexpr int BK = SHAMPOO_GEMM_BK;          // k-slab depth (multiple of 8)
-constexpr int LDS_PAD = SHAMPOO_GEMM_PAD;
+constexpr int BK = 16;          // k-slab depth (multiple of 8)
+constexpr int LDS_PAD = 4;
 constexpr int LOAD_PASSES = BK / 8;          // 128 x BK floats = 256 threads x LOAD_PASSES float4
 constexpr int GEMM_THREADS = 256;
 constexpr int NUM_XCD = 8;
@@ -218,7 +209,7 @@ __device__ __forceinline__ const T *operand_ptr(const Operand &o, const BlockDes
 // whose condition number is the square of G's, and a plain float32 running sum
 // over k would perturb its small eigenvalues by more than the parity budget.
 template <int AO, int BO, typename TA, typename TB, int EPI, bool KSCALE, int ACC64 = 0>
-__global__ __launch_bounds__(GEMM_THREADS, SHAMPOO_GEMM_MINBLOCKS) void gemm_mfma_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_mfma_kernel(const GemmArgs g) {
   __shared__ __align__(16) float As[2][BK][BM + LDS_PAD];
   __shared__ __align__(16) float Bs[2][BK][BN + LDS_PAD];
   __shared__ float red[4];

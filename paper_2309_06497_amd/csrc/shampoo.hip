@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <tuple>
 #include <new>
 #include <utility>
@@ -30,10 +31,7 @@ namespace {
 
 constexpr int64_t MAX_BLOCK_SIZE = 8192;
 constexpr size_t ALIGN = 256;
-#ifndef SHAMPOO_EIG_CHUNK_GIB
-#define SHAMPOO_EIG_CHUNK_GIB 3
-#endif
-constexpr size_t EIG_CHUNK_BYTES = (size_t)SHAMPOO_EIG_CHUNK_GIB << 30;   // W + Qt of one chunk of the block solver
+constexpr size_t EIG_CHUNK_BYTES = (size_t)3 << 30;   // W + Qt of one chunk of the block solver
 
 inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -340,6 +338,13 @@ void make_plan(const shampoo_config *c, Plan &p) {
   }
 }
 
+// Whole-parameter and tensor buckets are launched with the block index as grid.y / grid.z.
+int check_plan(const Plan &p) {
+  for (const auto &b : p.buckets)
+    if ((b.whole() || b.t3) && b.count > 65535) return SHAMPOO_ERR_UNSUPPORTED;
+  return SHAMPOO_OK;
+}
+
 // ---------------------------------------------------------------------------
 // Root-inverse workspace (shared by the optimizer and the stand-alone call)
 // ---------------------------------------------------------------------------
@@ -349,18 +354,9 @@ struct EigLayout {
   size_t bytes = 0;
 };
 
-EigLayout eig_layout(int n, int batch) {
-  EigLayout e;
-  if (n <= JAC_SMALL_MAX) {     // LDS solver: only the per-matrix failure flags
-    e.chunk = batch;
-    e.off_failed = 0;
-    e.bytes = align_up((size_t)std::max(batch, 1) * sizeof(int32_t));
-    return e;
-  }
-  e.np = (n + JAC_PIV - 1) / JAC_PIV * JAC_PIV;
+// Offsets for chunks of `chunk` matrices of the block solver (np already set).
+void eig_offsets(EigLayout &e) {
   const size_t mat = (size_t)e.np * e.np * sizeof(float);
-  // W is float64, Qt float32: 3 float-sized matrices per solve
-  e.chunk = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)batch, 32768), EIG_CHUNK_BYTES / (3 * mat)));
   size_t off = 0;
   e.off_w = off; off += align_up(2 * mat * e.chunk);
   e.off_qt = off; off += align_up(mat * e.chunk);
@@ -372,6 +368,28 @@ EigLayout eig_layout(int n, int batch) {
   e.off_failed = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
   e.off_f = off; off += align_up((size_t)e.chunk * e.np * sizeof(float));
   e.bytes = off;
+}
+
+// budget: bytes that the W and Qt arrays of one chunk may take (the other arrays are small);
+// hard_cap != 0: the whole layout must fit into that many bytes (bytes = 0 in the result if
+// not even one matrix does).
+EigLayout eig_layout(int n, int batch, size_t budget = EIG_CHUNK_BYTES, size_t hard_cap = 0) {
+  EigLayout e;
+  if (n <= JAC_SMALL_MAX) {     // LDS solver: no scratch in device memory
+    e.chunk = batch;
+    e.off_failed = 0;
+    e.bytes = align_up((size_t)std::max(batch, 1) * sizeof(int32_t));
+    return e;
+  }
+  e.np = (n + JAC_PIV - 1) / JAC_PIV * JAC_PIV;
+  const size_t mat = (size_t)e.np * e.np * sizeof(float);
+  // W is float64, Qt float32: 3 float-sized matrices per solve
+  e.chunk = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)batch, 32768), budget / (3 * mat)));
+  eig_offsets(e);
+  if (hard_cap) {
+    while (e.bytes > hard_cap && e.chunk > 1) { --e.chunk; eig_offsets(e); }
+    if (e.bytes > hard_cap) e.bytes = 0;
+  }
   return e;
 }
 
@@ -393,31 +411,42 @@ int launch_fill(float *p, float v, int64_t n, hipStream_t s) {
   return SHAMPOO_OK;
 }
 
-#ifndef SHAMPOO_JAC_STREAMS
-#define SHAMPOO_JAC_STREAMS 4
-#endif
-constexpr int JAC_STREAMS = SHAMPOO_JAC_STREAMS;   // sub-chunks of the block solver that run concurrently
+constexpr int JAC_STREAMS = 4;   // sub-chunks of the block solver that run concurrently
 
+// Helper streams (default priority) and fork / join events of the block solver.
 struct AuxStreams {
-  hipStream_t stream[JAC_STREAMS - 1];
-  hipEvent_t fork, join[JAC_STREAMS - 1];
+  hipStream_t stream[JAC_STREAMS - 1] = {};
+  hipEvent_t fork = nullptr, join[JAC_STREAMS - 1] = {};
+  int state = 0;   // 0 = not tried, 1 = ready, -1 = unavailable (everything then runs on the caller's stream)
+  bool ready() {
+    if (state == 0) {
+      state = 1;
+      if (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess) { fork = nullptr; state = -1; }
+      for (int i = 0; i < JAC_STREAMS - 1 && state == 1; ++i) {
+        if (hipStreamCreateWithFlags(&stream[i], hipStreamNonBlocking) != hipSuccess) { stream[i] = nullptr; state = -1; }
+        else if (hipEventCreateWithFlags(&join[i], hipEventDisableTiming) != hipSuccess) { join[i] = nullptr; state = -1; }
+      }
+      if (state == -1) release();
+    }
+    return state == 1;
+  }
+  // Waits for the helper streams' work, then frees streams and events.
+  void release() {
+    for (int i = 0; i < JAC_STREAMS - 1; ++i) {
+      if (stream[i]) { (void)hipStreamSynchronize(stream[i]); (void)hipStreamDestroy(stream[i]); stream[i] = nullptr; }
+      if (join[i]) { (void)hipEventDestroy(join[i]); join[i] = nullptr; }
+    }
+    if (fork) { (void)hipEventDestroy(fork); fork = nullptr; }
+  }
 };
 
-// Lazily created helper streams (default priority) and fork / join events; nullptr if
-// the runtime refuses, in which case everything runs on the caller's stream.
-AuxStreams *aux_streams() {
-  static AuxStreams a;
-  static int state = 0;   // 0 = not tried, 1 = ready, -1 = unavailable
-  if (state == 0) {
-    state = 1;
-    if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess) state = -1;
-    for (int i = 0; i < JAC_STREAMS - 1 && state == 1; ++i) {
-      if (hipStreamCreateWithFlags(&a.stream[i], hipStreamNonBlocking) != hipSuccess) state = -1;
-      else if (hipEventCreateWithFlags(&a.join[i], hipEventDisableTiming) != hipSuccess) state = -1;
-    }
-  }
-  return state == 1 ? &a : nullptr;
-}
+// What the stand-alone entry points keep per GPU until the process ends.
+constexpr int MAX_DEVICES = 64;
+struct PerDevice {
+  std::mutex mutex;
+  AuxStreams aux;                      // helper streams of shampoo_root_inverse
+};
+PerDevice per_device[MAX_DEVICES];
 
 // Block-Jacobi root inverse of `cnt` matrices, using workspace slots [slot0, slot0 + cnt).
 int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float scale, float *x, float *lambda,
@@ -475,10 +504,12 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
 }
 
 // X_i = rootinv(scale * A_i) for a batch of dense n x n matrices.  ws: eig_layout(n, >= chunk) region.
+// aux: helper streams for the sub-chunks of the block solver (the caller owns them and
+// serialises their use), or nullptr.
 // only: optional device array [batch]; matrices whose entry is 0 are skipped (x left as it is).
 int root_inverse_batched(const float *a, int n, int batch, float eps, float r, float scale, float *x, float *lambda,
                          int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
-                         const EigLayout &e, hipStream_t s, const int32_t *only = nullptr) {
+                         const EigLayout &e, hipStream_t s, AuxStreams *aux, const int32_t *only = nullptr) {
   if (batch <= 0) return SHAMPOO_OK;
   if (n <= JAC_SMALL_MAX) {
     SmallRootArgs g;
@@ -503,7 +534,8 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
   // that run on separate streams: the pivot kernel is bound by LDS, the W update by
   // the float64 matrix cores and the Q update by HBM, so sub-chunks that are in
   // different phases overlap on the same CUs.
-  AuxStreams *aux = aux_streams();
+  // aux == nullptr: everything on the caller's stream.
+  if (aux && !aux->ready()) aux = nullptr;
   const int n_sub = aux ? JAC_STREAMS : 1;
   for (int b0 = 0; b0 < batch; b0 += e.chunk) {
     const int cb = std::min(e.chunk, batch - b0);
@@ -547,7 +579,8 @@ constexpr int NEWTON_MATS = 7;   // M, M', X, X', T and two buffers for the powe
 NewtonLayout newton_layout(int n, int batch) {
   NewtonLayout e;
   e.mat = align_up((size_t)n * n * sizeof(float));
-  e.chunk = (int)std::max<size_t>(1, std::min<size_t>((size_t)std::max(batch, 1), EIG_CHUNK_BYTES / (NEWTON_MATS * e.mat)));
+  // the kernels take the matrix index as grid.y
+  e.chunk = (int)std::max<size_t>(1, std::min<size_t>(std::min<size_t>((size_t)std::max(batch, 1), 32768), EIG_CHUNK_BYTES / (NEWTON_MATS * e.mat)));
   size_t off = 0;
   e.off_mats = off; off += (size_t)NEWTON_MATS * e.chunk * e.mat;
   e.off_rowpart = off; off += align_up((size_t)e.chunk * n * sizeof(double));
@@ -657,7 +690,9 @@ struct shampoo_opt {
   size_t off_T2 = 0;
   bool has_tensor = false;
   size_t off_nfail = 0;   // coupled Newton: per-matrix failure flags of one batch (int32)
-  std::vector<void *> last_w, last_g;    // pointer tables currently on the device
+  std::vector<void *> last_w, last_g;    // the caller's pointers of the last step
+  std::vector<void *> tab_w, tab_g;      // the pointer tables as sent to the device (source of the asynchronous copies)
+  AuxStreams aux;                        // helper streams of the block solver, created at the first large refresh
   bool ptrs_aligned16 = false;           // every gradient pointer is 16-byte aligned
   std::vector<char> upper_stale;         // per bucket: the factors' tiles above the diagonal of tiles are out of date
   int64_t last_step = -1;
@@ -829,7 +864,7 @@ int newton_root_guarded(shampoo_opt *o, const float *F, int dim, int count, floa
   HIP_TRY(hipStreamSynchronize(s));
   if (n_failed == 0) return SHAMPOO_OK;
   return root_inverse_batched(F, dim, count, c.epsilon, r_exp, c2, Fi, nullptr, nullptr, counters, ws + o->off_eig, lay, s,
-                              flags);
+                              &o->aux, flags);
 }
 
 // GT: element type of the caller's gradients.  GS: of the gradients that feed the factors and
@@ -1127,7 +1162,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
             HIP_TRY(hipGetLastError());
           } else {
             rc = root_inverse_batched(F, dim, b.count, c.epsilon, c.root_exponent, c2, Fi, nullptr, nullptr, fail_count,
-                                      ws + o->off_eig, side == 0 ? o->eig_L[i] : o->eig_R[i], s);
+                                      ws + o->off_eig, side == 0 ? o->eig_L[i] : o->eig_R[i], s, &o->aux);
             if (rc) return rc;
           }
         }
@@ -1150,7 +1185,7 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
           } else {
             rc = root_inverse_batched(reinterpret_cast<float *>(ws + fac[k]), dims[k], b.count, c.epsilon, rw, c2,
                                       reinterpret_cast<float *>(ws + inv[k]), nullptr, nullptr, fail_count,
-                                      ws + o->off_eig, *lay[k], s);
+                                      ws + o->off_eig, *lay[k], s, &o->aux);
           }
           if (rc) return rc;
         }
@@ -1167,11 +1202,11 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       }
       rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
-                                ws + o->off_eig, o->eig_L[i], s);
+                                ws + o->off_eig, o->eig_L[i], s, &o->aux);
       if (rc) return rc;
       rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Rinv), nullptr, nullptr, fail_count,
-                                ws + o->off_eig, o->eig_R[i], s);
+                                ws + o->off_eig, o->eig_R[i], s, &o->aux);
       if (rc) return rc;
     }
     o->n_refresh++;
@@ -1412,6 +1447,7 @@ int shampoo_plan(const shampoo_config *cfg, int64_t *table, int64_t cap, int64_t
   if (cap < 0 || (cap > 0 && !table)) return SHAMPOO_ERR_NULL;
   Plan p;
   make_plan(cfg, p);
+  if (const int rp = check_plan(p)) return rp;
   if (n_blocks) *n_blocks = (int64_t)p.blocks.size();
   if (n_buckets) *n_buckets = (int64_t)p.buckets.size();
   const int64_t cnt = std::min<int64_t>(cap, (int64_t)p.blocks.size());
@@ -1430,6 +1466,7 @@ size_t shampoo_workspace_bytes(const shampoo_config *cfg) {
   if (check_config(cfg)) return 0;
   Plan p;
   make_plan(cfg, p);
+  if (check_plan(p)) return 0;
   return layout(cfg, p, nullptr);
 }
 
@@ -1447,6 +1484,7 @@ int shampoo_create(const shampoo_config *cfg, void *workspace, size_t workspace_
   o->cfg.ndim = o->ndim.data();
   o->cfg.shape = o->shape.data();
   make_plan(&o->cfg, o->plan);
+  if ((rc = check_plan(o->plan))) { delete o; return rc; }
   const size_t need = layout(&o->cfg, o->plan, o);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % ALIGN) != 0 || workspace_bytes < need) {
     delete o;
@@ -1583,8 +1621,7 @@ int shampoo_step(shampoo_opt *o, void *const *params, const void *const *grads, 
   if (!std::isfinite(lr)) return SHAMPOO_ERR_HYPER;
   hipStream_t s = static_cast<hipStream_t>(stream);
   HIP_TRY(hipSetDevice(o->cfg.device));
-  // pointer tables: re-sent only when they change; the copy from pageable
-  // memory is staged before hipMemcpyAsync returns, so the vectors may be reused
+  // pointer tables: re-sent only when they change
   bool same = (int)o->last_w.size() == np;
   for (int i = 0; same && i < np; ++i) same = o->last_w[i] == params[i] && o->last_g[i] == grads[i];
   if (!same) {
@@ -1594,21 +1631,29 @@ int shampoo_step(shampoo_opt *o, void *const *params, const void *const *grads, 
       if (reinterpret_cast<uintptr_t>(grads[i]) % 16 != 0) o->ptrs_aligned16 = false;
     o->last_g.resize(np);
     for (int i = 0; i < np; ++i) o->last_g[i] = const_cast<void *>(grads[i]);
+    // The tables are copied from vectors that the handle owns.  An earlier copy may still be
+    // reading them (the runtime is free to defer a copy from pageable memory), so the stream
+    // is drained before they are overwritten: once per change of the caller's pointers.
+    if (!o->tab_w.empty()) HIP_TRY(hipStreamSynchronize(s));
+    o->tab_w = o->last_w; o->tab_g = o->last_g;
     // tensor parameters are worked on in block-contiguous copies inside the workspace
-    std::vector<void *> tw(o->last_w), tg(o->last_g);
     for (int i = 0; i < np; ++i)
-      if (o->plan.pshape[i].kind == P_TENSOR) { tw[i] = o->ws + o->off_Wb[i]; tg[i] = o->ws + o->off_Gb[i]; }
-    HIP_TRY(hipMemcpyAsync(o->ws + o->off_wtab, tw.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(o->ws + o->off_gtab, tg.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
-    if (o->has_tensor) HIP_TRY(hipStreamSynchronize(s));   // tw, tg go out of scope
+      if (o->plan.pshape[i].kind == P_TENSOR) { o->tab_w[i] = o->ws + o->off_Wb[i]; o->tab_g[i] = o->ws + o->off_Gb[i]; }
+    HIP_TRY(hipMemcpyAsync(o->ws + o->off_wtab, o->tab_w.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(o->ws + o->off_gtab, o->tab_g.data(), np * sizeof(void *), hipMemcpyHostToDevice, s));
   }
-  o->last_step = step;
+  int rc;
   if (o->cfg.grad_dtype == SHAMPOO_GRAD_BF16) {
-    if (o->use_l2) return step_impl<uint16_t, float, float>(o, lr, step, s);
-    if (o->use_b1) return step_impl<uint16_t, uint16_t, float>(o, lr, step, s);
-    return step_impl<uint16_t, uint16_t, uint16_t>(o, lr, step, s);
+    if (o->use_l2) rc = step_impl<uint16_t, float, float>(o, lr, step, s);
+    else if (o->use_b1) rc = step_impl<uint16_t, uint16_t, float>(o, lr, step, s);
+    else rc = step_impl<uint16_t, uint16_t, uint16_t>(o, lr, step, s);
+  } else {
+    rc = step_impl<float, float, float>(o, lr, step, s);
   }
-  return step_impl<float, float, float>(o, lr, step, s);
+  // A step whose launches failed (SHAMPOO_ERR_HIP) leaves the state partly updated; the step
+  // counter then stays where it was, so the error is not masked by SHAMPOO_ERR_STEP on a retry.
+  if (rc == SHAMPOO_OK) o->last_step = step;
+  return rc;
 }
 
 int shampoo_get(shampoo_opt *o, int32_t param, int32_t block, int32_t which, void *dst, size_t bytes,
@@ -1728,6 +1773,7 @@ int shampoo_destroy(shampoo_opt *o) {
   if (!o) return SHAMPOO_ERR_NULL;
   for (auto &v : o->intervals)
     for (auto &iv : v) { (void)hipEventDestroy(iv.a); (void)hipEventDestroy(iv.b); }
+  if (o->aux.state == 1) { (void)hipSetDevice(o->cfg.device); o->aux.release(); }
   delete o;
   return SHAMPOO_OK;
 }
@@ -1751,8 +1797,16 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
     const int rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, batch, s);
     if (rc) return rc;
   }
+  // The helper streams of the stand-alone call are shared by every caller of a device: the
+  // lock keeps one call's fork / join events together while its work is enqueued.
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES || n <= JAC_SMALL_MAX)
+    return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
+                                static_cast<unsigned char *>(workspace), e, s, nullptr);
+  std::lock_guard<std::mutex> lock(per_device[dev].mutex);
   return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
-                              static_cast<unsigned char *>(workspace), e, s);
+                              static_cast<unsigned char *>(workspace), e, s, &per_device[dev].aux);
 }
 
 size_t shampoo_root_inverse_newton_workspace_bytes(int32_t n, int32_t batch) {
