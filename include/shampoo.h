@@ -277,6 +277,24 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * shampoo_root_inverse for callers that cannot allocate device memory or must not see an
+ * allocation happen: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments and results as shampoo_root_inverse without the
+ * workspace: the solver's working arrays live in a fixed array of
+ * SHAMPOO_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU, held
+ * until the process ends), and matrices are processed as many at a time as fit there
+ * (n = 2048: one, n = 1024: five; n <= 128 needs no scratch at all).  The call allocates
+ * nothing, creates no streams and enqueues kernels only (no memset nodes), all on `stream`.
+ * n > SHAMPOO_STATIC_MAX_N: SHAMPOO_ERR_UNSUPPORTED, nothing enqueued.
+ * Every call on a GPU uses that GPU's one array: calls whose work overlaps on one GPU (two
+ * streams, two threads) race; the caller orders them.
+ */
+#define SHAMPOO_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+#define SHAMPOO_STATIC_MAX_N 2048
+int shampoo_root_inverse_static(const float *a, int32_t n, int32_t batch, float epsilon, float r,
+                                float *x, float *lambda, int32_t *failed, void *stream);
+
+/*
  * Stand-alone batched coupled inverse Newton iteration (Sec. 3.2.1, item 2):
  *   A_i = a_i + epsilon I,  c = (2 ||A_i||_F / (p + 1))^(1/p),  X_0 = I / c,  M_0 = A_i / c^p,
  *   X_{k+1} = X_k T_k,  M_{k+1} = T_k^p M_k,  T_k = ((p + 1) I - M_k) / p,

@@ -26,7 +26,7 @@ STAGE_NAMES = ("factor", "graft", "root", "precond", "update", "diag", "fused", 
 EXPORTS = (
     "shampoo_plan", "shampoo_workspace_bytes", "shampoo_create", "shampoo_step", "shampoo_get",
     "shampoo_status", "shampoo_set_timing", "shampoo_get_timing", "shampoo_destroy",
-    "shampoo_root_inverse_workspace_bytes", "shampoo_root_inverse",
+    "shampoo_root_inverse_workspace_bytes", "shampoo_root_inverse", "shampoo_root_inverse_static",
     "shampoo_root_inverse_newton_workspace_bytes", "shampoo_root_inverse_newton", "shampoo_jacobi_pair",
     "shampoo_strerror",
 )
@@ -97,6 +97,8 @@ def lib():
     L.shampoo_root_inverse_workspace_bytes.restype = sz
     L.shampoo_root_inverse.argtypes = [vp, i32, i32, f32, f32, vp, vp, vp, vp, sz, vp]
     L.shampoo_root_inverse.restype = ctypes.c_int
+    L.shampoo_root_inverse_static.argtypes = [vp, i32, i32, f32, f32, vp, vp, vp, vp]
+    L.shampoo_root_inverse_static.restype = ctypes.c_int
     L.shampoo_root_inverse_newton_workspace_bytes.argtypes = [i32, i32]
     L.shampoo_root_inverse_newton_workspace_bytes.restype = sz
     L.shampoo_root_inverse_newton.argtypes = [vp, i32, i32, f32, i32, f32, i32, vp, vp, vp, vp, sz, vp]
@@ -305,6 +307,24 @@ def shampoo_root_inverse(a, epsilon, r, want_lambda=False, want_failed=False):
     if want_failed:
         res.append(failed)
     return res[0] if len(res) == 1 else tuple(res)
+
+
+def shampoo_root_inverse_static(a, epsilon, r, x, lam=None, failed=None):
+    """shampoo_root_inverse without a workspace (the library's fixed scratch array is used):
+    a, x: CUDA float32 tensors [batch, n, n]; lam [batch, n] float32 and failed [batch] int32
+    optional.  Outputs are written into the tensors given: nothing is allocated here either.
+    Asynchronous on the current stream."""
+    import torch
+    assert a.is_cuda and a.dtype == torch.float32 and a.dim() == 3 and a.shape[1] == a.shape[2] and a.is_contiguous()
+    assert x.is_cuda and x.dtype == torch.float32 and x.shape == a.shape and x.is_contiguous()
+    batch, n = a.shape[0], a.shape[1]
+    assert lam is None or (lam.dtype == torch.float32 and lam.shape == (batch, n) and lam.is_contiguous())
+    assert failed is None or (failed.dtype == torch.int32 and failed.shape == (batch,) and failed.is_contiguous())
+    with torch.cuda.device(a.device):
+        _check(lib().shampoo_root_inverse_static(
+            ctypes.c_void_p(a.data_ptr()), n, batch, epsilon, r, ctypes.c_void_p(x.data_ptr()),
+            ctypes.c_void_p(lam.data_ptr()) if lam is not None else None,
+            ctypes.c_void_p(failed.data_ptr()) if failed is not None else None, _stream_ptr()))
 
 
 def shampoo_jacobi_pair(s, halves, rnd, k):

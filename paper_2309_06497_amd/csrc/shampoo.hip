@@ -27,6 +27,12 @@
 
 using namespace shampoo;
 
+// Scratch of shampoo_root_inverse_static: the block solver's working arrays (float64 copy of
+// the matrices, accumulated rotations, pivot blocks, flags) for as many matrices at a time as
+// fit.  One copy per GPU the library runs on, held until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress: kernels are given the address obtained there.
+static __device__ __align__(256) unsigned char scratch[SHAMPOO_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int64_t MAX_BLOCK_SIZE = 8192;
@@ -445,6 +451,7 @@ constexpr int MAX_DEVICES = 64;
 struct PerDevice {
   std::mutex mutex;
   AuxStreams aux;                      // helper streams of shampoo_root_inverse
+  unsigned char *scratch = nullptr;    // device address of `scratch` on this GPU
 };
 PerDevice per_device[MAX_DEVICES];
 
@@ -1807,6 +1814,38 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
   std::lock_guard<std::mutex> lock(per_device[dev].mutex);
   return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
                               static_cast<unsigned char *>(workspace), e, s, &per_device[dev].aux);
+}
+
+int shampoo_root_inverse_static(const float *a, int32_t n, int32_t batch, float epsilon, float r, float *x,
+                                float *lambda, int32_t *failed, void *stream) {
+  if (!a || !x) return SHAMPOO_ERR_NULL;
+  if (n < 1 || batch < 1) return SHAMPOO_ERR_SHAPE;
+  if (n > SHAMPOO_STATIC_MAX_N) return SHAMPOO_ERR_UNSUPPORTED;
+  if (!(epsilon > 0.f) || !std::isfinite(epsilon) || !(r > 0.f) || !std::isfinite(r)) return SHAMPOO_ERR_HYPER;
+  const EigLayout e = eig_layout(n, batch, SHAMPOO_STATIC_SCRATCH_BYTES, SHAMPOO_STATIC_SCRATCH_BYTES);
+  if (e.bytes == 0 || e.bytes > SHAMPOO_STATIC_SCRATCH_BYTES) return SHAMPOO_ERR_UNSUPPORTED;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return SHAMPOO_ERR_UNSUPPORTED;
+  unsigned char *ws = nullptr;
+  {
+    // every GPU holds its own copy of the array at its own address: looked up once per device
+    std::lock_guard<std::mutex> lock(per_device[dev].mutex);
+    if (!per_device[dev].scratch) {
+      void *ptr = nullptr;
+      HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+      if (!ptr) return SHAMPOO_ERR_HIP;
+      per_device[dev].scratch = static_cast<unsigned char *>(ptr);
+    }
+    ws = per_device[dev].scratch;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (failed) {
+    const int rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, batch, s);   // a fill kernel, not a memset node
+    if (rc) return rc;
+  }
+  // everything on the caller's stream: no helper streams are created on this path
+  return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr, ws, e, s, nullptr);
 }
 
 size_t shampoo_root_inverse_newton_workspace_bytes(int32_t n, int32_t batch) {
