@@ -842,6 +842,53 @@ def test_order3_step_on_a_rank_one_tensor_has_a_closed_form():
         assert np.allclose(o.TLbar[0][0][k] @ v, (g2 + eps) ** (-1.0 / 6.0) * v, rtol=1e-9)
 
 
+def test_order4_step_on_a_rank_one_tensor_has_a_closed_form():
+    """G = a o b o c o d (order w = 4): every factor is ||G||^2 times a projector, so with the
+    exponent 2 r / w = 1 / (2 w) = 1/8 per dimension (Sec. 2.3: "root 2w") the four roots together
+    give G / sqrt(||G||^2 + eps), and each root alone scales its own vector by
+    (||G||^2 + eps)^(-1/8).  An exponent of 1/6 or 1/4 per dimension shows in both."""
+    r = rng(75)
+    vs = [r.standard_normal(n) for n in (3, 4, 2, 5)]
+    G = np.einsum("i,j,k,l->ijkl", *vs)
+    eps = 1e-4
+    o = so.ShampooOracle([(3, 4, 2, 5)], 5, 1.0, eps, 0.25, 1, momentum=0.0, grafting="sgd")
+    assert 0 in o.tblocks and o.view_shapes[0] == (3, 4, 2, 5)     # nothing merges at block size 5
+    W = [np.zeros((3, 4, 2, 5))]
+    o.step(W, [G], 1.0, 0)
+    g2 = float(np.sum(G * G))
+    assert np.allclose(o.P_sh[0][0], G / np.sqrt(g2 + eps), rtol=1e-9, atol=1e-12)
+    assert not np.allclose(o.P_sh[0][0], G * (g2 + eps) ** (-4.0 / 6.0), rtol=1e-3)
+    for k, v in enumerate(vs):
+        assert np.allclose(o.TLbar[0][0][k] @ v, (g2 + eps) ** (-1.0 / 8.0) * v, rtol=1e-9)
+    assert np.allclose(W[0], -G, rtol=1e-9, atol=1e-12)
+
+
+def test_order4_factors_and_direction_against_explicit_loops_and_kronecker():
+    """Order 4: L_k = G_(k) G_(k)^T as explicit sums for every mode, and the direction of a full
+    step against ((L1 + eps I) kron ... kron (L4 + eps I))^(-1/8) vec(G), row-major vec."""
+    r = rng(76)
+    d = (2, 3, 2, 3)
+    G = r.standard_normal(d)
+    Ls = so.tensor_factor_update([np.zeros((n, n)) for n in d], G, 1.0)
+    want = [np.zeros((n, n)) for n in d]
+    for idx in np.ndindex(*d):
+        for mode in range(4):
+            for a in range(d[mode]):
+                jdx = list(idx); jdx[mode] = a
+                want[mode][idx[mode], a] += G[idx] * G[tuple(jdx)]
+    for got, w_ in zip(Ls, want):
+        assert np.allclose(got, w_, rtol=1e-13, atol=1e-13)
+    eps = 1e-3
+    o = so.ShampooOracle([d], 3, 1.0, eps, 0.25, 1, momentum=0.0, grafting="sgd")
+    o.step([np.zeros(d)], [G], 1.0, 0)
+    big = np.eye(1)
+    for L in want:
+        big = np.kron(big, L + eps * np.eye(L.shape[0]))
+    lam, Q = np.linalg.eigh(big)
+    direction = (Q * lam ** (-1.0 / 8.0)) @ Q.T @ G.reshape(-1)
+    assert np.allclose(o.P_sh[0][0].reshape(-1), direction, rtol=1e-9, atol=1e-12)
+
+
 def test_fully_merged_tensor_is_full_matrix_adagrad():
     """Everything merged: Shampoo on a vector, one factor sum g g^T with exponent 1/2
     (Sec. 4.2.1).  After one gradient (L + eps I)^(-1/2) g = g / sqrt(||g||^2 + eps); after two,
