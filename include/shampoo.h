@@ -121,6 +121,14 @@ typedef struct {
                              float32: float32 accuracy at 3/16 of the float32-MFMA time; elements
                              below 2^-16 of a block's largest keep absolute, not relative,
                              accuracy); SHAMPOO_MATRIX_CORES_FP32: always the float32 MFMA          */
+  int32_t warm_start_roots; /* != 0: the eigendecomposition of a refresh starts from the eigenvectors of
+                             the previous one (Sec. 3.2.1, 4.3: between refreshes a factor changes
+                             little) instead of from the identity: W = Q^T L Q is formed in float64
+                             and the Jacobi sweeps begin there.  Factors of dimension <= 128 (solved
+                             inside one workgroup) and the coupled Newton iteration ignore it.  Costs
+                             one more float32 matrix per factor in the workspace.  Every 16th refresh
+                             starts cold, which bounds the drift of the accumulated float32
+                             eigenvectors away from orthogonality.  0 (default): every refresh cold */
   int32_t grad_dtype;     /* SHAMPOO_GRAD_F32 or SHAMPOO_GRAD_BF16; parameters are float32   */
   int32_t device;         /* HIP device ordinal                                              */
 } shampoo_config;
@@ -275,6 +283,23 @@ size_t shampoo_root_inverse_workspace_bytes(int32_t n, int32_t batch);
 int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon, float r,
                          float *x, float *lambda, int32_t *failed,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * shampoo_root_inverse with a warm start (n > 128 only, else SHAMPOO_ERR_UNSUPPORTED): the
+ * eigenvectors are kept in the caller's array qt between calls.
+ * qt:     device, batch x np x np float32, np = n rounded up to a multiple of 64; rows are
+ *         eigenvectors.  start == 0: a cold solve (qt is overwritten).  start != 0: qt holds the
+ *         result of an earlier call on matrices close to a (the same factors some steps
+ *         earlier): the solve starts from W = qt a qt^T, formed in float64, and qt is updated.
+ *         A matrix that fails (see `failed`) leaves its part of qt as it was.
+ * sweeps: device int32[batch] or NULL: the number of Jacobi sweeps in which anything rotated
+ *         (the last one of a solve never does: it finds every pair below the threshold).
+ * Everything else as shampoo_root_inverse; the workspace is larger by the float64 panel.
+ */
+size_t shampoo_root_inverse_warm_workspace_bytes(int32_t n, int32_t batch);
+int shampoo_root_inverse_warm(const float *a, int32_t n, int32_t batch, float epsilon, float r,
+                              float *x, float *lambda, int32_t *failed, float *qt, int32_t start,
+                              int32_t *sweeps, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * shampoo_root_inverse for callers that cannot allocate device memory or must not see an

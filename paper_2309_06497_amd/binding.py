@@ -27,6 +27,7 @@ EXPORTS = (
     "shampoo_plan", "shampoo_workspace_bytes", "shampoo_create", "shampoo_step", "shampoo_get",
     "shampoo_status", "shampoo_set_timing", "shampoo_get_timing", "shampoo_destroy",
     "shampoo_root_inverse_workspace_bytes", "shampoo_root_inverse", "shampoo_root_inverse_static",
+    "shampoo_root_inverse_warm_workspace_bytes", "shampoo_root_inverse_warm",
     "shampoo_root_inverse_newton_workspace_bytes", "shampoo_root_inverse_newton", "shampoo_jacobi_pair",
     "shampoo_strerror",
 )
@@ -57,6 +58,7 @@ class ShampooConfig(ctypes.Structure):
         ("newton_tolerance", ctypes.c_float),
         ("newton_max_iterations", ctypes.c_int32),
         ("precond_matrix_cores", ctypes.c_int32),
+        ("warm_start_roots", ctypes.c_int32),
         ("grad_dtype", ctypes.c_int32),
         ("device", ctypes.c_int32),
     ]
@@ -97,6 +99,10 @@ def lib():
     L.shampoo_root_inverse_workspace_bytes.restype = sz
     L.shampoo_root_inverse.argtypes = [vp, i32, i32, f32, f32, vp, vp, vp, vp, sz, vp]
     L.shampoo_root_inverse.restype = ctypes.c_int
+    L.shampoo_root_inverse_warm_workspace_bytes.argtypes = [i32, i32]
+    L.shampoo_root_inverse_warm_workspace_bytes.restype = sz
+    L.shampoo_root_inverse_warm.argtypes = [vp, i32, i32, f32, f32, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    L.shampoo_root_inverse_warm.restype = ctypes.c_int
     L.shampoo_root_inverse_static.argtypes = [vp, i32, i32, f32, f32, vp, vp, vp, vp]
     L.shampoo_root_inverse_static.restype = ctypes.c_int
     L.shampoo_root_inverse_newton_workspace_bytes.argtypes = [i32, i32]
@@ -128,7 +134,8 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                 use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
                 newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999,
-                large_dim_method=LARGE_DIM_BLOCKING, precond_matrix_cores=MATRIX_CORES_AUTO):
+                large_dim_method=LARGE_DIM_BLOCKING, precond_matrix_cores=MATRIX_CORES_AUTO,
+                warm_start_roots=False):
     """Builds a ShampooConfig; keeps the shape arrays alive on the returned object."""
     n = len(shapes)
     ndim = (ctypes.c_int32 * max(n, 1))(*[len(s) for s in shapes])
@@ -142,7 +149,7 @@ def make_config(shapes, block_size, beta2, epsilon, root_exponent, precondition_
                         momentum, beta1, weight_decay, 1 if use_decoupled_weight_decay else 0,
                         1 if use_nesterov else 0, grafting_type, grafting_beta2, 1 if use_bias_correction else 0,
                         large_dim_method, root_method, newton_tolerance, newton_max_iterations,
-                        precond_matrix_cores, grad_dtype, device)
+                        precond_matrix_cores, 1 if warm_start_roots else 0, grad_dtype, device)
     cfg._keep = (ndim, shape)
     return cfg
 
@@ -177,7 +184,8 @@ class Shampoo:
                  use_decoupled_weight_decay=True, use_nesterov=False, grafting_type=GRAFT_ADAGRAD,
                 use_bias_correction=False, root_method=ROOT_EIGH,
                 newton_tolerance=1e-6, newton_max_iterations=100, grafting_beta2=0.999,
-                large_dim_method=LARGE_DIM_BLOCKING, precond_matrix_cores=MATRIX_CORES_AUTO):
+                large_dim_method=LARGE_DIM_BLOCKING, precond_matrix_cores=MATRIX_CORES_AUTO,
+                warm_start_roots=False):
         import torch
         self.shapes = [tuple(s) for s in shapes]
         self.cfg = make_config(self.shapes, block_size, beta2, epsilon, root_exponent,
@@ -185,7 +193,7 @@ class Shampoo:
                                momentum, grad_dtype, device, beta1, weight_decay,
                                use_decoupled_weight_decay, use_nesterov, grafting_type,
                                use_bias_correction, root_method, newton_tolerance, newton_max_iterations,
-                               grafting_beta2, large_dim_method, precond_matrix_cores)
+                               grafting_beta2, large_dim_method, precond_matrix_cores, warm_start_roots)
         self.device = torch.device("cuda", device)
         self.grad_dtype = grad_dtype
         nbytes = shampoo_workspace_bytes(self.cfg)
@@ -307,6 +315,34 @@ def shampoo_root_inverse(a, epsilon, r, want_lambda=False, want_failed=False):
     if want_failed:
         res.append(failed)
     return res[0] if len(res) == 1 else tuple(res)
+
+
+def shampoo_root_inverse_warm(a, epsilon, r, qt, start):
+    """shampoo_root_inverse with the eigenvectors kept in qt ([batch, np, np] float32 CUDA tensor,
+    np = n rounded up to 64) between calls; start: begin from them.  Returns
+    (X, eigenvalues, failed, sweeps)."""
+    import torch
+    assert a.is_cuda and a.dtype == torch.float32 and a.dim() == 3 and a.shape[1] == a.shape[2]
+    a = a.contiguous()
+    batch, n = a.shape[0], a.shape[1]
+    npad = (n + 63) // 64 * 64
+    assert qt.is_cuda and qt.dtype == torch.float32 and tuple(qt.shape) == (batch, npad, npad) and qt.is_contiguous()
+    x = torch.empty_like(a)
+    lam = torch.empty((batch, n), dtype=torch.float32, device=a.device)
+    failed = torch.zeros((batch,), dtype=torch.int32, device=a.device)
+    sweeps = torch.zeros((batch,), dtype=torch.int32, device=a.device)
+    nbytes = lib().shampoo_root_inverse_warm_workspace_bytes(n, batch)
+    if nbytes == 0:
+        raise ShampooError(-7)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=a.device)
+    with torch.cuda.device(a.device):
+        _check(lib().shampoo_root_inverse_warm(
+            ctypes.c_void_p(a.data_ptr()), n, batch, epsilon, r, ctypes.c_void_p(x.data_ptr()),
+            ctypes.c_void_p(lam.data_ptr()), ctypes.c_void_p(failed.data_ptr()), ctypes.c_void_p(qt.data_ptr()),
+            1 if start else 0, ctypes.c_void_p(sweeps.data_ptr()), ctypes.c_void_p(ws.data_ptr()), ws.numel(),
+            _stream_ptr()))
+        torch.cuda.current_stream().synchronize()   # ws is released on return
+    return x, lam, failed, sweeps
 
 
 def shampoo_root_inverse_static(a, epsilon, r, x, lam=None, failed=None):

@@ -449,9 +449,11 @@ struct BlockInitArgs {
   float *dmax; int32_t *failed; int32_t *rot;
   const int32_t *only;   // optional [batch]: a matrix whose entry is 0 is marked 2 in `failed`, which
                          // every later kernel takes as "leave alone" without counting it as a failure
+  int32_t warm;          // nonzero: Qt holds the eigenvectors of an earlier solve and stays; W is made
+                         // from it afterwards (congruence_f64.h); only the flags and dmax are set here
 };
 
-// W = pad(sym(A)), Qt = I, dmax, failed, rot = 0.  grid (np, batch), 256 threads.
+// W = pad(sym(A)), Qt = I (unless warm), dmax, failed, rot = 0.  grid (np, batch), 256 threads.
 __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs g) {
   const int b = blockIdx.y, i = blockIdx.x, np = g.np, n = g.n;
   double *w = g.w + (int64_t)b * np * np + (int64_t)i * np;
@@ -469,8 +471,10 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
       if (!(fabsf(lo) <= 3.0e38f) || !(fabsf(up) <= 3.0e38f)) bad = 1;
       v = 0.5 * ((double)lo + (double)up);
     }
-    w[j] = v;
-    qt[j] = (i == j) ? 1.f : 0.f;
+    if (!g.warm) {
+      w[j] = v;
+      qt[j] = (i == j) ? 1.f : 0.f;
+    }
   }
   if (bad) g.failed[b] = 1;
   if (i < n && threadIdx.x == 0) {
@@ -858,6 +862,8 @@ struct BlockFinalArgs {
   int32_t *failed;       // [batch] in/out
   int32_t *failed_out;   // optional user-visible copy
   unsigned long long *fail_count;
+  const int32_t *rot;    // [batch][JAC_OUTER_SWEEPS] pivots that rotated per sweep
+  int32_t *sweeps_out;   // optional [batch]: number of sweeps in which anything rotated
 };
 
 // One workgroup per matrix: eigenvalues, shift, f(lambda).
@@ -914,6 +920,11 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
   if (lane == 0) redi[wave] = badf;
   __syncthreads();
   badf = redi[0] | redi[1] | redi[2] | redi[3];
+  if (tid == 0 && g.sweeps_out && bad != 2) {
+    int cnt = 0;
+    for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw) cnt += g.rot[b * JAC_OUTER_SWEEPS + sw] != 0;
+    g.sweeps_out[b] = cnt;
+  }
   if (tid == 0 && bad != 2) {   // 2: not this call's matrix (see BlockInitArgs::only)
     g.failed[b] = badf;
     if (g.failed_out) g.failed_out[b] = badf;

@@ -16,6 +16,7 @@
 
 #include "../../include/shampoo.h"
 #include "block_step_small.h"
+#include "congruence_f64.h"
 #include "diag_shampoo.h"
 #include "eigh_jacobi.h"
 #include "elementwise.h"
@@ -79,6 +80,7 @@ struct Bucket {
   // are made from (matrix_stats_kernel of both roots, max |G| per piece of a block) and the
   // scales themselves
   size_t off_Linv2h = 0, off_Rinv2h = 0, off_stat_l = 0, off_stat_r = 0, off_gmaxp = 0, off_s_g = 0, off_inv_g2 = 0, off_t_scale = 0, off_inv_ts = 0;
+  size_t off_QtL = 0, off_QtR = 0;   // warm start: eigenvectors of the previous refresh, [count][np][np] float32
   size_t off_Gt = 0;     // 16-bit transpose of the bucket's gradient blocks (bf16, or scaled fp16 where the fp16 products follow), made by the factor update and
                          // read again by the first preconditioning product of the same step
   bool planes = false;
@@ -354,9 +356,12 @@ int check_plan(const Plan &p) {
 // ---------------------------------------------------------------------------
 // Root-inverse workspace (shared by the optimizer and the stand-alone call)
 // ---------------------------------------------------------------------------
+constexpr int CONGRUENCE_PANEL = 256;   // columns of T = A Qt^T formed at a time (warm start)
+
 struct EigLayout {
   int32_t np = 0, chunk = 0;
-  size_t off_w = 0, off_qt = 0, off_j = 0, off_ident = 0, off_rot = 0, off_dmax = 0, off_failed = 0, off_f = 0;
+  bool warm = false;       // room for the float64 panel of the warm start's congruence
+  size_t off_w = 0, off_qt = 0, off_j = 0, off_ident = 0, off_rot = 0, off_dmax = 0, off_failed = 0, off_f = 0, off_t = 0;
   size_t bytes = 0;
 };
 
@@ -373,14 +378,16 @@ void eig_offsets(EigLayout &e) {
   e.off_dmax = off; off += align_up((size_t)e.chunk * sizeof(float));
   e.off_failed = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
   e.off_f = off; off += align_up((size_t)e.chunk * e.np * sizeof(float));
+  if (e.warm) { e.off_t = off; off += align_up((size_t)e.chunk * e.np * std::min(e.np, CONGRUENCE_PANEL) * sizeof(double)); }
   e.bytes = off;
 }
 
 // budget: bytes that the W and Qt arrays of one chunk may take (the other arrays are small);
 // hard_cap != 0: the whole layout must fit into that many bytes (bytes = 0 in the result if
 // not even one matrix does).
-EigLayout eig_layout(int n, int batch, size_t budget = EIG_CHUNK_BYTES, size_t hard_cap = 0) {
+EigLayout eig_layout(int n, int batch, size_t budget = EIG_CHUNK_BYTES, size_t hard_cap = 0, bool warm = false) {
   EigLayout e;
+  e.warm = warm && n > JAC_SMALL_MAX;
   if (n <= JAC_SMALL_MAX) {     // LDS solver: no scratch in device memory
     e.chunk = batch;
     e.off_failed = 0;
@@ -456,12 +463,21 @@ struct PerDevice {
 PerDevice per_device[MAX_DEVICES];
 
 // Block-Jacobi root inverse of `cnt` matrices, using workspace slots [slot0, slot0 + cnt).
+// Warm start (WarmStart::qt != nullptr): the rows of Qt are kept between solves in the caller's
+// array; with `start` set the solve begins at W = Qt A Qt^T instead of W = A, Qt = I.
+struct WarmStart {
+  float *qt = nullptr;          // [batch][np][np]: eigenvectors, read (start) and written
+  bool start = false;
+  int32_t *sweeps = nullptr;    // optional [batch]: sweeps in which anything rotated
+};
+
 int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float scale, float *x, float *lambda,
                        int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
-                       const EigLayout &e, int slot0, hipStream_t s, const int32_t *only) {
+                       const EigLayout &e, int slot0, hipStream_t s, const int32_t *only, const WarmStart &ws_in) {
   const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
   double *w = reinterpret_cast<double *>(ws + e.off_w) + (int64_t)slot0 * np * np;
-  float *qt = reinterpret_cast<float *>(ws + e.off_qt) + (int64_t)slot0 * np * np;
+  float *qt = ws_in.qt ? ws_in.qt : reinterpret_cast<float *>(ws + e.off_qt) + (int64_t)slot0 * np * np;
+  const bool warm = ws_in.qt && ws_in.start && e.warm;
   float *jbuf = reinterpret_cast<float *>(ws + e.off_j) + (int64_t)slot0 * hp * JAC_PIV * JAC_PIV;
   int32_t *ident = reinterpret_cast<int32_t *>(ws + e.off_ident) + (int64_t)slot0 * hp;
   int32_t *rot = reinterpret_cast<int32_t *>(ws + e.off_rot) + (int64_t)slot0 * JAC_OUTER_SWEEPS;
@@ -475,8 +491,32 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   BlockInitArgs ia;
   ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
   ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot; ia.only = only;
+  ia.warm = warm ? 1 : 0;
   hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cnt), dim3(256), 0, s, ia);
   HIP_TRY(hipGetLastError());
+  if (warm) {
+    // W = Qt A Qt^T, a panel of columns at a time: T = A Qt^T[:, panel], W[:, panel] = Qt T
+    const int pw_max = std::min(np, CONGRUENCE_PANEL);
+    double *tp = reinterpret_cast<double *>(ws + e.off_t) + (int64_t)slot0 * np * pw_max;
+    for (int col0 = 0; col0 < np; col0 += pw_max) {
+      const int pw = std::min(pw_max, np - col0);
+      CongruenceArgs c1{};
+      c1.a = a; c1.a_batch = (int64_t)n * n; c1.lda = n;
+      c1.b = qt + (int64_t)col0 * np; c1.b_batch = (int64_t)np * np; c1.ldb = np;
+      c1.c = tp; c1.c_batch = (int64_t)np * pw_max; c1.ldc = pw_max;
+      c1.M = n; c1.N = pw; c1.K = n; c1.col0 = 0; c1.skip = failed;
+      hipLaunchKernelGGL((congruence_gemm_kernel<false, false>), dim3((pw + CG_TILE - 1) / CG_TILE, (n + CG_TILE - 1) / CG_TILE, cnt),
+                         dim3(CG_THREADS), 0, s, c1);
+      CongruenceArgs c2{};
+      c2.a = qt; c2.a_batch = (int64_t)np * np; c2.lda = np;
+      c2.b = tp; c2.b_batch = (int64_t)np * pw_max; c2.ldb = pw_max;
+      c2.c = w; c2.c_batch = (int64_t)np * np; c2.ldc = np;
+      c2.M = np; c2.N = pw; c2.K = n; c2.col0 = col0; c2.skip = failed;
+      hipLaunchKernelGGL((congruence_gemm_kernel<true, true>), dim3((pw + CG_TILE - 1) / CG_TILE, (np + CG_TILE - 1) / CG_TILE, cnt),
+                         dim3(CG_THREADS), 0, s, c2);
+    }
+    HIP_TRY(hipGetLastError());
+  }
   BlockJacArgs ja;
   ja.w = w; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
   ja.np = np;
@@ -496,6 +536,7 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   fa.w = w; fa.qt = qt; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.scale = scale; fa.fvals = fv;
   fa.lambda = lambda;
   fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
+  fa.rot = rot; fa.sweeps_out = ws_in.sweeps;
   hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);
   HIP_TRY(hipGetLastError());
   GemmArgs g{};
@@ -516,7 +557,8 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
 // only: optional device array [batch]; matrices whose entry is 0 are skipped (x left as it is).
 int root_inverse_batched(const float *a, int n, int batch, float eps, float r, float scale, float *x, float *lambda,
                          int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
-                         const EigLayout &e, hipStream_t s, AuxStreams *aux, const int32_t *only = nullptr) {
+                         const EigLayout &e, hipStream_t s, AuxStreams *aux, const int32_t *only = nullptr,
+                         const WarmStart &warm = WarmStart()) {
   if (batch <= 0) return SHAMPOO_OK;
   if (n <= JAC_SMALL_MAX) {
     SmallRootArgs g;
@@ -555,11 +597,14 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
     for (int k = 0; k < subs; ++k) {
       const int cnt = cb / subs + (k < cb % subs ? 1 : 0);
       hipStream_t sk = k == 0 ? s : aux->stream[k - 1];
+      WarmStart wk = warm;
+      if (wk.qt) wk.qt += (int64_t)(b0 + first) * e.np * e.np;
+      if (wk.sweeps) wk.sweeps += b0 + first;
       const int rc = block_jacobi_solve(a + (int64_t)(b0 + first) * n * n, n, cnt, eps, r, scale,
                                         x + (int64_t)(b0 + first) * n * n,
                                         lambda ? lambda + (int64_t)(b0 + first) * n : nullptr,
                                         failed_user ? failed_user + b0 + first : nullptr, fail_count, ws, e, first, sk,
-                                        only ? only + b0 + first : nullptr);
+                                        only ? only + b0 + first : nullptr, wk);
       if (rc) return rc;
       first += cnt;
     }
@@ -768,8 +813,11 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     if (c->grad_dtype == SHAMPOO_GRAD_BF16 && b.bf16_mfma && !use_l2) b.off_Gt = take(B * m * n * 2);
     // a diagonalised side needs no eigensolver workspace (stand-in layout of a 1 x 1 problem)
     const int em = b.diagL ? 1 : b.m, en = b.diagR ? 1 : b.rdim();
-    eL.push_back(eig_layout(em, b.count));
-    eR.push_back(eig_layout(en, b.count));
+    const bool warm = c->warm_start_roots != 0 && c->root_method == SHAMPOO_ROOT_EIGH;
+    eL.push_back(eig_layout(em, b.count, EIG_CHUNK_BYTES, 0, warm));
+    eR.push_back(eig_layout(en, b.count, EIG_CHUNK_BYTES, 0, warm));
+    if (eL.back().warm) b.off_QtL = take(B * (size_t)eL.back().np * eL.back().np * 4);
+    if (eR.back().warm) b.off_QtR = take(B * (size_t)eR.back().np * eR.back().np * 4);
     for (int k = 0; k < 2; ++k) eM[k].push_back(eig_layout(b.td[k + 1], b.count));
     // under coupled Newton the eigensolver is the fallback of the guard (Sec. 3.2.3): room for both
     if (c->root_method == SHAMPOO_ROOT_NEWTON)
@@ -901,6 +949,8 @@ int complete_factors(shampoo_opt *o, size_t bucket, hipStream_t s) {
 // sqrt dim))^2 squared into its Gram matrix: 1e7 and more at N = dim, 34 at N = 2 dim, 9 at
 // N = 4 dim).  While it is, a root taken from it weights its smallest eigenvalues most, and
 // the bf16 factor update sums in float64 (syrk_bf16.h).
+constexpr int64_t WARM_RESTART_PERIOD = 16;
+
 inline bool young_factor(int64_t step, int cols, int dim) { return (step + 1) * (int64_t)cols < 4 * (int64_t)dim; }
 
 template <typename GT, typename GS, typename GD>
@@ -1151,6 +1201,15 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
   }
   if (refresh) {
     StageTimer t(o, SHAMPOO_STAGE_ROOT, s);
+    // Warm start: from the eigenvectors of the previous refresh, except at the first refresh and
+    // at every WARM_RESTART_PERIOD-th one (the accumulated float32 eigenvectors drift away from
+    // orthogonality by about 1e-6 per solve; a cold solve resets that).
+    const bool warm_now = o->n_refresh > 0 && o->n_refresh % WARM_RESTART_PERIOD != 0;
+    auto warm_of = [&](const EigLayout &lay, size_t off_qt) {
+      WarmStart w;
+      if (lay.warm && off_qt) { w.qt = reinterpret_cast<float *>(ws + off_qt); w.start = warm_now; }
+      return w;
+    };
     for (size_t i = 0; i < p.buckets.size(); ++i) {
       auto &b = p.buckets[i];
       if ((rc = complete_factors(o, i, s))) return rc;
@@ -1169,7 +1228,8 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
             HIP_TRY(hipGetLastError());
           } else {
             rc = root_inverse_batched(F, dim, b.count, c.epsilon, c.root_exponent, c2, Fi, nullptr, nullptr, fail_count,
-                                      ws + o->off_eig, side == 0 ? o->eig_L[i] : o->eig_R[i], s, &o->aux);
+                                      ws + o->off_eig, side == 0 ? o->eig_L[i] : o->eig_R[i], s, &o->aux, nullptr,
+                                      warm_of(side == 0 ? o->eig_L[i] : o->eig_R[i], side == 0 ? b.off_QtL : b.off_QtR));
             if (rc) return rc;
           }
         }
@@ -1209,11 +1269,11 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       }
       rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
-                                ws + o->off_eig, o->eig_L[i], s, &o->aux);
+                                ws + o->off_eig, o->eig_L[i], s, &o->aux, nullptr, warm_of(o->eig_L[i], b.off_QtL));
       if (rc) return rc;
       rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Rinv), nullptr, nullptr, fail_count,
-                                ws + o->off_eig, o->eig_R[i], s, &o->aux);
+                                ws + o->off_eig, o->eig_R[i], s, &o->aux, nullptr, warm_of(o->eig_R[i], b.off_QtR));
       if (rc) return rc;
     }
     o->n_refresh++;
@@ -1814,6 +1874,38 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
   std::lock_guard<std::mutex> lock(per_device[dev].mutex);
   return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
                               static_cast<unsigned char *>(workspace), e, s, &per_device[dev].aux);
+}
+
+size_t shampoo_root_inverse_warm_workspace_bytes(int32_t n, int32_t batch) {
+  if (n <= JAC_SMALL_MAX || batch < 1 || n > MAX_BLOCK_SIZE) return 0;
+  return eig_layout(n, batch, EIG_CHUNK_BYTES, 0, true).bytes;
+}
+
+int shampoo_root_inverse_warm(const float *a, int32_t n, int32_t batch, float epsilon, float r, float *x,
+                              float *lambda, int32_t *failed, float *qt, int32_t start, int32_t *sweeps,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+  if (!a || !x || !qt) return SHAMPOO_ERR_NULL;
+  if (n < 1 || batch < 1) return SHAMPOO_ERR_SHAPE;
+  if (n > MAX_BLOCK_SIZE || n <= JAC_SMALL_MAX) return SHAMPOO_ERR_UNSUPPORTED;
+  if (!(epsilon > 0.f) || !std::isfinite(epsilon) || !(r > 0.f) || !std::isfinite(r)) return SHAMPOO_ERR_HYPER;
+  const EigLayout e = eig_layout(n, batch, EIG_CHUNK_BYTES, 0, true);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % ALIGN) != 0 || workspace_bytes < e.bytes)
+    return SHAMPOO_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (failed) {
+    const int rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, batch, s);
+    if (rc) return rc;
+  }
+  WarmStart w;
+  w.qt = qt; w.start = start != 0; w.sweeps = sweeps;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES)
+    return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
+                                static_cast<unsigned char *>(workspace), e, s, nullptr, nullptr, w);
+  std::lock_guard<std::mutex> lock(per_device[dev].mutex);
+  return root_inverse_batched(a, n, batch, epsilon, r, 1.f, x, lambda, failed, nullptr,
+                              static_cast<unsigned char *>(workspace), e, s, &per_device[dev].aux, nullptr, w);
 }
 
 int shampoo_root_inverse_static(const float *a, int32_t n, int32_t batch, float epsilon, float r, float *x,

@@ -151,3 +151,28 @@ def psd_stress_matrix(n, rank, seed, index, ridge=1e-6):
     g = _rng(seed, 0x53, index).standard_normal((n, rank))
     A = g @ g.T + ridge * np.eye(n)
     return A.astype(np.float32), g
+
+
+def persistent_subspace_grads(shapes, seed, step, sigma, noise=0.05, decay=1.0):
+    """Gradients whose singular vectors persist over the steps, as those of a network in
+    training do (the eigenvectors of its Kronecker factors move slowly, which is what a warm
+    start of the root-inverse refresh can use): for a matrix parameter
+        G_t = sigma (U diag(s_k c_tk) V^T sqrt(min(m, n)) + noise Z_t),
+    U, V fixed orthonormal bases drawn once per (seed, parameter), s_k = (k + 1)^(-decay) a fixed
+    spectrum, c_tk = 1 + 0.3 N(0, 1) a fresh jitter of every singular value, Z_t fresh N(0, 1)
+    noise.  Vectors get plain Gaussian gradients.  float32, one stream per (seed, step, index)."""
+    out = []
+    for i, s in enumerate(shapes):
+        r = _rng(seed, 0x50, step, i)
+        if len(s) != 2:
+            out.append((r.standard_normal(s) * sigma).astype(np.float32))
+            continue
+        m, n = s
+        k = min(m, n)
+        rb = _rng(seed, 0x42, i)                     # the bases do not depend on the step
+        U = np.linalg.qr(rb.standard_normal((m, k)))[0]
+        V = np.linalg.qr(rb.standard_normal((n, k)))[0]
+        sv = (np.arange(k) + 1.0) ** (-decay) * (1.0 + 0.3 * r.standard_normal(k))
+        G = (U * sv) @ V.T * np.sqrt(k) + noise * r.standard_normal((m, n))
+        out.append((G * sigma).astype(np.float32))
+    return out

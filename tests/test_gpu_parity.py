@@ -141,7 +141,7 @@ class Pair:
     def __init__(self, shapes, b, beta2, f, start=0, mu=0.9, eps=1e-12, eps_g=1e-10, bf16=False, seed=0,
                  beta1=0.0, weight_decay=0.0, decoupled=True, nesterov=False, grafting="adagrad",
                  bias_correction=False, newton=None, grafting_beta2=0.999, large_dim_method="blocking",
-                 fp32_matrix_cores=False):
+                 fp32_matrix_cores=False, warm_start=False):
         self.shapes = shapes
         self.bf16 = bf16
         self.f, self.start, self.eps = f, start, f32(eps)
@@ -152,7 +152,8 @@ class Pair:
                              B.ROOT_NEWTON if newton else B.ROOT_EIGH, *(newton or (1e-6, 100)), grafting_beta2,
                              {"blocking": B.LARGE_DIM_BLOCKING, "adagrad": B.LARGE_DIM_ADAGRAD,
                               "diagonal": B.LARGE_DIM_DIAGONAL}[large_dim_method],
-                             B.MATRIX_CORES_FP32 if fp32_matrix_cores else B.MATRIX_CORES_AUTO)
+                             B.MATRIX_CORES_FP32 if fp32_matrix_cores else B.MATRIX_CORES_AUTO,
+                             warm_start_roots=warm_start)
         self.ora = so.ShampooOracle(shapes, b, f32(beta2), f32(eps), 0.25, f, start, f32(eps_g), f32(mu),
                                     f32(beta1), f32(weight_decay), decoupled, nesterov, grafting,
                                     bias_correction, "newton" if newton else "eigh",
@@ -1044,3 +1045,69 @@ def test_fully_merged_tensor_with_newton_roots():
             assert rel(wg[i] - p.w0[i], p.w_ora[i] - p.w0[i]) <= TOL_DIR
     with pytest.raises(B.ShampooError):
         B.Shampoo([(8, 8, 8)], 4, 0.99, 1e-6, 0.25, 1, root_method=B.ROOT_NEWTON)
+
+
+# ---------------------------------------------------------------------------
+# warm start of the refresh from the previous eigenvectors (Sec. 3.2.1, 4.3)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [200, 512])
+def test_warm_started_root_inverse_standalone(n):
+    """Factors of gradients whose singular vectors persist (workloads.persistent_subspace_grads),
+    taken every ten steps of the moving average: the first root inverse starts cold, the later
+    ones from the eigenvectors the call before left behind.  Every result against the oracle's
+    root of the same float32 bits (the warm start changes the path, not the answer), and the
+    warm solves must need fewer sweeps than the cold one.  A start from eigenvectors that have
+    nothing to do with the matrix must still give the right root."""
+    import torch
+    say(f"case warm-started root inverse n={n}")
+    batch, eps = 3, f32(1e-12)
+    shapes = [(n, n + 40)] * batch
+    L = [np.zeros((n, n)) for _ in range(batch)]
+    npad = (n + 63) // 64 * 64
+    qt = torch.zeros((batch, npad, npad), dtype=torch.float32, device="cuda")
+    sweeps_seen = []
+    for k in range(3):
+        for t in range(10 * k, 10 * k + 10):
+            g = wl.persistent_subspace_grads(shapes, 77, t, 1e-3)
+            for i in range(batch):
+                L[i] = so.factor_update(L[i], np.zeros((n + 40, n + 40)), g[i], f32(0.99))[0]
+        a = np.stack([x.astype(np.float32) for x in L])
+        a = ((a + a.transpose(0, 2, 1)) * 0.5).astype(np.float32)
+        x, lam, failed, sweeps = B.shampoo_root_inverse_warm(torch.from_numpy(a).cuda(), 1e-12, 0.25, qt, k > 0)
+        assert int(failed.sum()) == 0
+        worst = 0.0
+        for i in range(batch):
+            xo, lo = so.root_inverse(a[i], eps, 0.25)
+            xi = x[i].cpu().numpy()
+            assert np.array_equal(xi, xi.T)
+            worst = max(worst, rel(xi, xo))
+            assert np.abs(np.sort(lam[i].cpu().numpy()) - lo).max() / lo.max() <= 2e-6
+        sweeps_seen.append(sweeps.cpu().numpy().copy())
+        say(f"    refresh {k} ({'warm' if k else 'cold'}): X err {worst:.1e}, sweeps that rotated {sweeps_seen[-1].tolist()}")
+        assert worst <= TOL_ROOT
+    assert (sweeps_seen[1] < sweeps_seen[0]).all() and (sweeps_seen[2] < sweeps_seen[0]).all()
+    # unrelated starting vectors: the eigenvectors left by these factors, used on Wishart matrices
+    a2 = wishart_batch(n, batch, 500 + n)
+    x, lam, failed, sweeps = B.shampoo_root_inverse_warm(torch.from_numpy(a2).cuda(), 1e-12, 0.25, qt, True)
+    assert int(failed.sum()) == 0
+    for i in range(batch):
+        assert rel(x[i].cpu().numpy(), so.root_inverse(a2[i], eps, 0.25)[0]) <= TOL_ROOT
+    say(f"    unrelated start: sweeps {sweeps.cpu().numpy().tolist()}")
+    with pytest.raises(B.ShampooError):
+        B.shampoo_root_inverse_warm(torch.zeros((1, 64, 64), device="cuda"), 1e-12, 0.25,
+                                    torch.zeros((1, 64, 64), device="cuda"), False)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_warm_start_inside_the_optimizer(bf16):
+    """warm_start_roots on: blocks of 256 (the blocked eigensolver) and of 128 and below (which
+    ignore the option), persistent-subspace gradients, roots refreshed every third step for
+    eleven steps: every refresh after the first starts from the previous eigenvectors.  All
+    the usual bars at every step."""
+    say(f"case warm start in the optimizer, bf16={bf16}")
+    shapes = [(512, 256), (256,), (128, 320)]
+    p = Pair(shapes, 256, 0.99, 3, eps=1e-8, bf16=bf16, warm_start=True)
+    for t in range(11):
+        p.step(wl.persistent_subspace_grads(shapes, 78, t, 1e-3), 0.01, t)
+        p.check(t)
+    assert p.gpu.status() == {"refreshes": 4, "failed_roots": 0}
