@@ -33,7 +33,7 @@ constexpr int JAC_NB = 32;            // block-column width of the block solver
 constexpr int JAC_PIV = 2 * JAC_NB;   // pivot size
 constexpr int JAC_SMALL_MAX = 128;    // largest n solved entirely in LDS
 constexpr int JAC_SMALL_SWEEPS = 20;
-constexpr int JAC_OUTER_SWEEPS = 16;
+constexpr int JAC_OUTER_SWEEPS = 24;   // float32 and float64 sweeps of the block solver together (a cap: converged matrices skip)
 constexpr int JAC_INNER_SWEEPS = 1;    // 2: 256 roots of n = 1024 in 1.00 s instead of 0.80 s
 // rotation thresholds |a_pq| > rel * sqrt(|a_pp a_qq|) and > abs * max|diag(input)|
 constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver (n <= 128), float64 copy of the factor
@@ -43,6 +43,12 @@ constexpr double JAC_SMALL_TOL_REL = 1e-11;   // LDS solver (n <= 128), float64 
 // accuracy of the accumulated Q, and one sweep cheaper than 1e-11.
 constexpr double JAC_BLOCK_TOL_REL = 1e-7;
 constexpr double JAC_SMALL_TOL_ABS = 1e-15;
+// The float32 sweeps of a cold block solve: as many as it takes float32 to run out of
+// resolution (pairs below 1e-6 of their diagonal entries, or below 2e-7 of the largest
+// diagonal entry, are left to the float64 sweeps that follow).
+constexpr int JAC_F32_SWEEPS = 8;
+constexpr double JAC_F32_TOL_REL = 1e-6;
+constexpr double JAC_F32_TOL_ABS = 2e-7;
 
 // blocks of the two-sided update per thread: s / 2 (s / 2 + 1) / 2 blocks must fit on the
 // workgroup, which holds for the two uses (s <= 64 on 256 threads, s <= 128 on 1024)
@@ -109,6 +115,21 @@ __device__ __forceinline__ double rcp_newton(double x) {
   return y;
 }
 
+// float32 versions (the float32 sweeps of the mixed-precision block solver): the hardware
+// estimates are good to about one unit in the last place; one Newton step each
+__device__ __forceinline__ float rsqrt_newton(float x) {
+  float y = __builtin_amdgcn_rsqf(x);
+  return y * (1.5f - 0.5f * x * y * y);
+}
+__device__ __forceinline__ float rcp_newton(float x) {
+  float y = __builtin_amdgcn_rcpf(x);
+  return y * (2.0f - x * y);
+}
+__device__ __forceinline__ double jac_abs(double x) { return fabs(x); }
+__device__ __forceinline__ float jac_abs(float x) { return fabsf(x); }
+__device__ __forceinline__ double jac_copysign(double x, double y) { return copysign(x, y); }
+__device__ __forceinline__ float jac_copysign(float x, float y) { return copysignf(x, y); }
+
 // index of element (i, j) of a symmetric matrix stored as its packed lower triangle
 __device__ __forceinline__ int tri(int i, int j) {
   return i >= j ? i * (i + 1) / 2 + j : j * (j + 1) / 2 + i;
@@ -126,9 +147,10 @@ __device__ __forceinline__ int tri(int i, int j) {
 // mirror image of each updated block is written as well.
 // Returns nonzero if any rotation was applied.  All NT threads of the workgroup must call it.
 // HALVES: the pair order of halves_pair instead of the plain tournament.
-template <bool SQUARE, int NT, bool HALVES = false>
-__device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const int LDA, int max_sweeps,
-                             double tol_rel, double tol_abs, JacScratch *sc) {
+// T: float64, or float32 for the first sweeps of the mixed-precision block solver.
+template <bool SQUARE, int NT, bool HALVES = false, typename T = double>
+__device__ int jacobi_sweeps(T *At, float *Js, int s, const int LD, const int LDA, int max_sweeps,
+                             T tol_rel, T tol_abs, JacScratch *sc) {
   const int tid = threadIdx.x;
   const int half = s >> 1;
   auto at = [LDA](int i, int j) { return SQUARE ? i * LDA + j : tri(i, j); };
@@ -168,8 +190,8 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
       const int j = tid & (JW - 1);
       for (int i = tid / JW; i < s; i += NT / JW) {
         if (j >= i) continue;                           // j < i < s
-        const double aij = fabs(At[at(i, j)]);
-        if (aij > tol_abs && aij * aij > tol_rel * tol_rel * fabs(At[at(i, i)] * At[at(j, j)])) {
+        const T aij = jac_abs(At[at(i, j)]);
+        if (aij > tol_abs && aij * aij > tol_rel * tol_rel * jac_abs(At[at(i, i)] * At[at(j, j)])) {
           const int r = HALVES ? halves_round(s, i, j) : (i == s - 1) ? j : ((i + j) * half) % (s - 1);
           atomicOr(&sc->rounds[r >> 5], 1u << (r & 31));
         }
@@ -181,26 +203,26 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
       if (tid < half) {
         int p, q;
         if (HALVES) halves_pair(s, r, tid, p, q); else rr_pair(s, r, tid, p, q);   // p < q
-        const double app = At[at(p, p)], aqq = At[at(q, q)], apq = At[at(q, p)];
-        double sn = 0.0, tp = 0.0;
-        const double aa = fabs(apq);
-        if (aa > tol_abs && aa * aa > tol_rel * tol_rel * fabs(app * aqq)) {
+        const T app = At[at(p, p)], aqq = At[at(q, q)], apq = At[at(q, p)];
+        T sn = 0, tp = 0;
+        const T aa = jac_abs(apq);
+        if (aa > tol_abs && aa * aa > tol_rel * tol_rel * jac_abs(app * aqq)) {
           // t = tan of the rotation angle, the smaller root of t^2 + 2 zeta t - 1 = 0 with
           // zeta = (a_qq - a_pp) / (2 a_pq):  t = h / (d + sign(d) sqrt(d^2 + h^2)).
           // This chain is the serial part of every round (32 lanes work, 224 wait), so the
           // square root and the reciprocals start from the hardware estimates and are
           // polished by Newton steps instead of going through the full library routines.
-          const double d = aqq - app, h = 2.0 * apq;
-          const double x = d * d + h * h;
-          const double hyp = x * rsqrt_newton(x);
-          const double t = h * rcp_newton(d + copysign(hyp, d));
-          const double c = rsqrt_newton(1.0 + t * t);   // cos
+          const T d = aqq - app, h = (T)2 * apq;
+          const T x = d * d + h * h;
+          const T hyp = x * rsqrt_newton(x);
+          const T t = h * rcp_newton(d + jac_copysign(hyp, d));
+          const T c = rsqrt_newton((T)1 + t * t);   // cos
           sn = t * c;
-          tp = sn * rcp_newton(1.0 + c);                 // sin / (1 + cos)
-          if (!(fabs(sn) <= 1.0)) { sn = 0.0; tp = 0.0; }   // non-finite: leave the pair alone
-          if (sn != 0.0) sc->flag = 1;
+          tp = sn * rcp_newton((T)1 + c);                 // sin / (1 + cos)
+          if (!(jac_abs(sn) <= (T)1)) { sn = 0; tp = 0; }   // non-finite: leave the pair alone
+          if (sn != (T)0) sc->flag = 1;
         }
-        sc->st[tid] = make_double2(sn, tp); sc->pq[tid] = make_int4(p, q, rowoff(p), rowoff(q));
+        sc->st[tid] = make_double2((double)sn, (double)tp); sc->pq[tid] = make_int4(p, q, rowoff(p), rowoff(q));
       }
       __syncthreads();
       // A <- R^T A R on the blocks (k, l) with l <= k, dealt evenly over the threads (block
@@ -209,7 +231,7 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
       // independent, so a thread first loads all of its blocks, then rotates, then stores (the
       // loads overlap).
       {
-        double a[UB], b[UB], c[UB], d[UB], sk[UB], tk[UB], sl[UB], tl[UB];
+        T a[UB], b[UB], c[UB], d[UB], sk[UB], tk[UB], sl[UB], tl[UB];
         int ia[UB], ib[UB], ic[UB], id[UB];
         int4 k4[UB], l4[UB];
         bool act[UB];
@@ -218,8 +240,8 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
           act[u] = bk[u] >= 0;
           if (act[u]) {
             const double2 stk = sc->st[bk[u]], stl = sc->st[bl[u]];
-            sk[u] = stk.x; tk[u] = stk.y; sl[u] = stl.x; tl[u] = stl.y;
-            act[u] = !(sk[u] == 0.0 && sl[u] == 0.0);
+            sk[u] = (T)stk.x; tk[u] = (T)stk.y; sl[u] = (T)stl.x; tl[u] = (T)stl.y;
+            act[u] = !(sk[u] == (T)0 && sl[u] == (T)0);
             if (act[u]) {
               k4[u] = sc->pq[bk[u]]; l4[u] = sc->pq[bl[u]];
               ia[u] = atr(k4[u].x, k4[u].z, l4[u].x, l4[u].z); ib[u] = atr(k4[u].x, k4[u].z, l4[u].y, l4[u].w);
@@ -232,14 +254,14 @@ __device__ int jacobi_sweeps(double *At, float *Js, int s, const int LD, const i
         for (int u = 0; u < UB; ++u) {
           if (!act[u]) continue;
           // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
-          const double a1 = a[u] - sk[u] * (c[u] + tk[u] * a[u]), c1 = c[u] + sk[u] * (a[u] - tk[u] * c[u]);
-          const double b1 = b[u] - sk[u] * (d[u] + tk[u] * b[u]), d1 = d[u] + sk[u] * (b[u] - tk[u] * d[u]);
+          const T a1 = a[u] - sk[u] * (c[u] + tk[u] * a[u]), c1 = c[u] + sk[u] * (a[u] - tk[u] * c[u]);
+          const T b1 = b[u] - sk[u] * (d[u] + tk[u] * b[u]), d1 = d[u] + sk[u] * (b[u] - tk[u] * d[u]);
           // columns: (a1, b1) and (c1, d1) are (x, y) pairs of rotation l
-          const double a2 = a1 - sl[u] * (b1 + tl[u] * a1), b2 = b1 + sl[u] * (a1 - tl[u] * b1);
-          const double c2 = c1 - sl[u] * (d1 + tl[u] * c1), d2 = d1 + sl[u] * (c1 - tl[u] * d1);
+          const T a2 = a1 - sl[u] * (b1 + tl[u] * a1), b2 = b1 + sl[u] * (a1 - tl[u] * b1);
+          const T c2 = c1 - sl[u] * (d1 + tl[u] * c1), d2 = d1 + sl[u] * (c1 - tl[u] * d1);
           if (bk[u] == bl[u]) {   // pivot block: (p, q) and (q, p) are the annihilated element
-            At[ia[u]] = a2; At[ib[u]] = 0.0; At[id[u]] = d2;
-            if (SQUARE) At[ic[u]] = 0.0;
+            At[ia[u]] = a2; At[ib[u]] = (T)0; At[id[u]] = d2;
+            if (SQUARE) At[ic[u]] = (T)0;
           } else {
             At[ia[u]] = a2; At[ib[u]] = b2; At[ic[u]] = c2; At[id[u]] = d2;
             if (SQUARE) {
@@ -431,6 +453,7 @@ typedef double doublex4 __attribute__((ext_vector_type(4)));
 
 struct BlockJacArgs {
   double *w;
+  float *w32;            // the float32 copy of W that the first sweeps of a cold solve work on (same layout)
   float *qt;
   float *jbuf;
   int32_t *ident;        // [batch][np/64]: pivot of the current round needed no rotation
@@ -439,13 +462,20 @@ struct BlockJacArgs {
   const int32_t *failed; // [batch]
   int32_t np;            // padded size
   int32_t round, sweep;
+  int32_t phase_start;   // index of the first sweep of the current phase (float32 or float64 sweeps): a sweep is
+                         // skipped when the one before it, in the same phase, rotated nothing
   int32_t inner_sweeps;  // Jacobi sweeps per pivot
   double tol_rel;        // rotation threshold relative to sqrt(|a_pp a_qq|)
+  double tol_abs_rel;    // ... and absolute threshold as a fraction of max |diag(input)|
+  __device__ __forceinline__ bool converged(int b) const {
+    return sweep > phase_start && rot[b * JAC_OUTER_SWEEPS + sweep - 1] == 0;
+  }
 };
 
 struct BlockInitArgs {
   const float *a; int64_t a_stride; int32_t n;
-  double *w; float *qt; int32_t np;
+  void *w;               // float64, or float32 for a mixed-precision cold solve
+  float *qt; int32_t np;
   float *dmax; int32_t *failed; int32_t *rot;
   const int32_t *only;   // optional [batch]: a matrix whose entry is 0 is marked 2 in `failed`, which
                          // every later kernel takes as "leave alone" without counting it as a failure
@@ -454,9 +484,10 @@ struct BlockInitArgs {
 };
 
 // W = pad(sym(A)), Qt = I (unless warm), dmax, failed, rot = 0.  grid (np, batch), 256 threads.
+template <typename T>
 __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs g) {
   const int b = blockIdx.y, i = blockIdx.x, np = g.np, n = g.n;
-  double *w = g.w + (int64_t)b * np * np + (int64_t)i * np;
+  T *w = reinterpret_cast<T *>(g.w) + (int64_t)b * np * np + (int64_t)i * np;
   float *qt = g.qt + (int64_t)b * np * np + (int64_t)i * np;
   const float *a = g.a + (int64_t)b * g.a_stride;
   if (g.only && g.only[b] == 0) {
@@ -472,7 +503,7 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
       v = 0.5 * ((double)lo + (double)up);
     }
     if (!g.warm) {
-      w[j] = v;
+      w[j] = (T)v;
       qt[j] = (i == j) ? 1.f : 0.f;
     }
   }
@@ -492,31 +523,32 @@ constexpr int PIV_LD = JAC_PIV + 1;
 // its rows.  A sub-block needed "the other way round" is read transposed.
 
 // One workgroup per (pair, matrix): diagonalise the 64 x 64 pivot.
+template <typename T>
 __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const BlockJacArgs g) {
-  __shared__ double At[JAC_PIV * PIV_LD];
+  __shared__ T At[JAC_PIV * PIV_LD];
   __shared__ float Js[JAC_PIV * PIV_LD];
   __shared__ JacScratch sc;
   const int b = blockIdx.y, pair = blockIdx.x;
   if (g.failed[b]) return;
-  if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;   // converged
+  if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB;
   int pb, qb;
   rr_pair(nblk, g.round, pair, pb, qb);   // pb < qb
-  const double *w = g.w + (int64_t)b * np * np;
+  const T *w = (sizeof(T) == 8 ? reinterpret_cast<const T *>(g.w) : reinterpret_cast<const T *>(g.w32)) + (int64_t)b * np * np;
   const int tid = threadIdx.x;
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) {
     const int j = tid & 63;
     const int gi = (i < JAC_NB ? pb * JAC_NB + i : qb * JAC_NB + i - JAC_NB);
     const int gj = (j < JAC_NB ? pb * JAC_NB + j : qb * JAC_NB + j - JAC_NB);
     // lower triangle of W (gi >= gj when j <= i, because pb < qb), mirrored into LDS
-    const double v = (j <= i) ? w[(int64_t)gi * np + gj] : w[(int64_t)gj * np + gi];
+    const T v = (j <= i) ? w[(int64_t)gi * np + gj] : w[(int64_t)gj * np + gi];
     At[i * PIV_LD + j] = v;
     Js[i * PIV_LD + j] = (i == j) ? 1.f : 0.f;
   }
   __syncthreads();
   const double dm = (double)g.dmax[b];
-  const int any = jacobi_sweeps<true, JAC_PIV_THREADS, true>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, g.tol_rel,
-                                      JAC_SMALL_TOL_ABS * dm, &sc);
+  const int any = jacobi_sweeps<true, JAC_PIV_THREADS, true, T>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, (T)g.tol_rel,
+                                         (T)(g.tol_abs_rel * dm), &sc);
   __syncthreads();
   if (tid == 0) {
     g.ident[b * (nblk / 2) + pair] = any ? 0 : 1;
@@ -619,18 +651,21 @@ constexpr int APP_JLD = JAC_PIV + 4;   // LDS row stride of J_l: rows 4 apart st
 // the sub-block is stored transposed: 32 consecutive bytes per 4 lanes).  Only the pair-block on
 // the diagonal (k = l) goes back through LDS, where it is completed from its lower half so
 // that the diagonal sub-blocks stay exactly symmetric.
-__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const BlockJacArgs g) {
-  __shared__ __align__(32) double X[JAC_PIV * APP_LD];   // W_kl (and the result of a diagonal pair-block)
-  __shared__ __align__(16) float Jl[JAC_PIV * APP_JLD];
+constexpr int APPLY_LDS_BYTES = JAC_PIV * APP_LD * 12;    // what each of the three update bodies below needs
+
+// bx: index of the workgroup among the appw_segments(hp) of the W update
+__device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int bx, unsigned char *smem) {
+  double *X = reinterpret_cast<double *>(smem);                               // [JAC_PIV * APP_LD] W_kl (and the result of a diagonal pair-block)
+  float *Jl = reinterpret_cast<float *>(smem + JAC_PIV * APP_LD * 8);         // [JAC_PIV * APP_JLD]
   const int b = blockIdx.y;
   if (g.failed[b]) return;
-  if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;
+  if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t *ident = g.ident + b * hp;
   const float *jb = g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV;
   // segment -> (k, first l)
-  int seg = blockIdx.x, k = 0;
+  int seg = bx, k = 0;
   for (;;) {
     const int ns = (k + 1 + APPW_SEG - 1) / APPW_SEG;
     if (seg < ns) break;
@@ -779,6 +814,112 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
   }
 }
 
+__device__ __forceinline__ floatx16 mfma_64(const float *At, const float *B, int wi, int wj, int lane);
+
+// The same update on the float32 copy of W (the first sweeps of a mixed-precision cold solve):
+// W_kl <- J_k^T W_kl J_l on the float32 matrix cores, both products through LDS.
+// First Y^T = X^T J_k (the result's rows are the k index of the second product, so it goes back
+// to LDS as it comes out of the accumulators, over X), then C = Y J_l.  Wavefront (wi, wj) owns
+// the 32 x 32 quadrant (wi, wj) of each result, which is one stored sub-block of W.  Same grid and
+// walk as blockjac_apply_w_kernel.
+__device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, int bx, unsigned char *smem) {
+  float *X = reinterpret_cast<float *>(smem);            // [JAC_PIV * APP_LD] W_kl, then Y^T, then (diagonal pair-block) the result
+  float *Jk = X + JAC_PIV * APP_LD;
+  float *Jl = Jk + JAC_PIV * APP_LD;
+  const int b = blockIdx.y;
+  if (g.failed[b]) return;
+  if (g.converged(b)) return;
+  const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wi = wave >> 1, wj = wave & 1;
+  const int32_t *ident = g.ident + b * hp;
+  const float *jb = g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV;
+  int seg = bx, k = 0;
+  for (;;) {
+    const int ns = (k + 1 + APPW_SEG - 1) / APPW_SEG;
+    if (seg < ns) break;
+    seg -= ns; ++k;
+  }
+  const int l_first = seg * APPW_SEG, l_end = min(l_first + APPW_SEG, k + 1);
+  const bool idk = ident[k] != 0;
+  float *w = g.w32 + (int64_t)b * np * np;
+  int pk, qk;
+  rr_pair(nblk, g.round, k, pk, qk);
+  bool have_jk = false;
+  // one 32 x 32 sub-block between W and the 64 x 64 LDS tile (see copy_subblock)
+  auto sub_load = [&](int ra, int cb, int xi, int xj) {
+    const bool tr = ra < cb;
+    const int gr0 = (tr ? cb : ra) * JAC_NB, gc0 = (tr ? ra : cb) * JAC_NB;
+    const int ii = tid >> 3, j4 = (tid & 7) * 4;       // 32 rows x 8 float4
+    const float4 v = *reinterpret_cast<const float4 *>(w + (int64_t)(gr0 + ii) * np + gc0 + j4);
+    if (tr) {
+      X[(xi + j4) * APP_LD + xj + ii] = v.x; X[(xi + j4 + 1) * APP_LD + xj + ii] = v.y;
+      X[(xi + j4 + 2) * APP_LD + xj + ii] = v.z; X[(xi + j4 + 3) * APP_LD + xj + ii] = v.w;
+    } else {
+      *reinterpret_cast<float4 *>(&X[(xi + ii) * APP_LD + xj + j4]) = v;
+    }
+  };
+  auto sub_store = [&](int ra, int cb, int xi, int xj) {   // ra >= cb: stored as it is
+    const int ii = tid >> 3, j4 = (tid & 7) * 4;
+    *reinterpret_cast<float4 *>(w + (int64_t)(ra * JAC_NB + ii) * np + cb * JAC_NB + j4) =
+        *reinterpret_cast<const float4 *>(&X[(xi + ii) * APP_LD + xj + j4]);
+  };
+  for (int l = l_first; l < l_end; ++l) {
+    if (idk && ident[l] != 0) continue;                  // uniform: neither side rotates
+    int pl, ql;
+    rr_pair(nblk, g.round, l, pl, ql);
+    __syncthreads();                                     // the tile of the pair-block before is done with
+    if (!have_jk) { load_rotation(Jk, jb, k, idk, tid); have_jk = true; }
+    load_rotation(Jl, jb, l, ident[l] != 0, tid);
+    sub_load(pk, pl, 0, 0);
+    sub_load(pk, ql, 0, JAC_NB);
+    sub_load(qk, pl, JAC_NB, 0);
+    sub_load(qk, ql, JAC_NB, JAC_NB);
+    __syncthreads();
+    // Y^T(kk, i) = sum_m X(m, kk) J_k(m, i)
+    const floatx16 yt = mfma_64(X, Jk, wi, wj, lane);
+    __syncthreads();                                     // every wavefront has read X
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        X[(wi * 32 + 8 * q + 4 * (lane >> 5) + e) * APP_LD + wj * 32 + (lane & 31)] = yt[4 * q + e];
+    __syncthreads();
+    // C(i, j) = sum_kk Y^T(kk, i) J_l(kk, j)
+    const floatx16 c = mfma_64(X, Jl, wi, wj, lane);
+    const int ra = wi ? qk : pk, cb = wj ? ql : pl;
+    if (k != l) {
+      const int j = lane & 31;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i0 = 8 * q + 4 * (lane >> 5);
+        if (ra > cb) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[(int64_t)(ra * JAC_NB + i0 + e) * np + cb * JAC_NB + j] = c[4 * q + e];
+        } else {          // stored transposed: four consecutive floats per lane
+          *reinterpret_cast<float4 *>(w + (int64_t)(cb * JAC_NB + j) * np + ra * JAC_NB + i0) =
+              make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
+        }
+      }
+    } else {
+      // the diagonal pair-block is completed from its lower half, so that the sub-blocks on the
+      // diagonal of W stay exactly symmetric
+      __syncthreads();                                   // every wavefront has read Y^T
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = wi * 32 + 8 * q + 4 * (lane >> 5) + e, j = wj * 32 + (lane & 31);
+          if (j <= i) { X[i * APP_LD + j] = c[4 * q + e]; X[j * APP_LD + i] = c[4 * q + e]; }
+        }
+      __syncthreads();
+      sub_store(pk, pl, 0, 0);
+      sub_store(qk, pl, JAC_NB, 0);                      // (pk, qk) is its mirror image and is not kept
+      sub_store(qk, ql, JAC_NB, JAC_NB);
+    }
+  }
+}
+
 // 64 x 64 x 64 float32 product on one workgroup: wavefront (wi, wj) computes the 32 x 32
 // tile  C[i][j] = sum_k At[k][i] * B[k][j]  from LDS (both operands k-major).
 __device__ __forceinline__ floatx16 mfma_64(const float *At, const float *B, int wi, int wj, int lane) {
@@ -796,17 +937,18 @@ constexpr int APPQ_TILES = 4;   // 64-column tiles of Qt handled by one workgrou
 
 // Qt rows of pair k <- J_k^T (those rows), APPQ_TILES 64-column tiles per workgroup,
 // float32 MFMA.  grid (hp * ceil(np / 256), batch).
-__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const BlockJacArgs g) {
-  __shared__ __align__(16) float Jk[JAC_PIV * APP_LD];
-  __shared__ __align__(16) float X[2][JAC_PIV * APP_LD];
+// bx: index of the workgroup among the hp * ceil(np / 256) of the Q update
+__device__ __forceinline__ void blockjac_apply_q_body(const BlockJacArgs &g, int bx, unsigned char *smem) {
+  float *Jk = reinterpret_cast<float *>(smem);           // [JAC_PIV * APP_LD]
+  float (*X)[JAC_PIV * APP_LD] = reinterpret_cast<float (*)[JAC_PIV * APP_LD]>(Jk + JAC_PIV * APP_LD);   // [2][...]
   const int b = blockIdx.y;
   if (g.failed[b]) return;
-  if (g.sweep > 0 && g.rot[b * JAC_OUTER_SWEEPS + g.sweep - 1] == 0) return;
+  if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2, ctiles = np / JAC_PIV;
   const int groups = (ctiles + APPQ_TILES - 1) / APPQ_TILES;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wi = wave >> 1, wj = wave & 1;
-  const int k = blockIdx.x / groups, grp = blockIdx.x - k * groups;
+  const int k = bx / groups, grp = bx - k * groups;
   if (g.ident[b * hp + k]) return;
   float *qt = g.qt + (int64_t)b * np * np;
   int pk, qk;
@@ -851,6 +993,21 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const 
   }
 #undef APPQ_FETCH
 #undef APPQ_STASH
+}
+
+// The three updates as kernels of their own (one launch for W and Q^T together measured 3 %
+// slower: the two bodies then share one register allocation and one occupancy limit).
+__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const BlockJacArgs g) {
+  __shared__ __align__(32) unsigned char smem[APPLY_LDS_BYTES];
+  blockjac_apply_w_body(g, blockIdx.x, smem);
+}
+__global__ __launch_bounds__(JAC_THREADS, 3) void blockjac_apply_w32_kernel(const BlockJacArgs g) {
+  __shared__ __align__(32) unsigned char smem[APPLY_LDS_BYTES];
+  blockjac_apply_w32_body(g, blockIdx.x, smem);
+}
+__global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const BlockJacArgs g) {
+  __shared__ __align__(32) unsigned char smem[APPLY_LDS_BYTES];
+  blockjac_apply_q_body(g, blockIdx.x, smem);
 }
 
 struct BlockFinalArgs {

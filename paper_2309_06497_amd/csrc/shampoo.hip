@@ -360,7 +360,7 @@ constexpr int CONGRUENCE_PANEL = 256;   // columns of T = A Qt^T formed at a tim
 
 struct EigLayout {
   int32_t np = 0, chunk = 0;
-  bool warm = false;       // room for the float64 panel of the warm start's congruence
+  bool warm = false;       // block solver: room for the float64 panel of the congruence W = Qt A Qt^T
   size_t off_w = 0, off_qt = 0, off_j = 0, off_ident = 0, off_rot = 0, off_dmax = 0, off_failed = 0, off_f = 0, off_t = 0;
   size_t bytes = 0;
 };
@@ -387,7 +387,8 @@ void eig_offsets(EigLayout &e) {
 // not even one matrix does).
 EigLayout eig_layout(int n, int batch, size_t budget = EIG_CHUNK_BYTES, size_t hard_cap = 0, bool warm = false) {
   EigLayout e;
-  e.warm = warm && n > JAC_SMALL_MAX;
+  (void)warm;
+  e.warm = n > JAC_SMALL_MAX;   // the float64 panel serves the warm start and the mixed-precision cold solve alike
   if (n <= JAC_SMALL_MAX) {     // LDS solver: no scratch in device memory
     e.chunk = batch;
     e.off_failed = 0;
@@ -491,10 +492,21 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
   BlockInitArgs ia;
   ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
   ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot; ia.only = only;
+  // A cold solve runs its first sweeps on a float32 copy of W (twice the matrix-core and vector
+  // rates, half the bytes), then continues exactly like a warm start: W = Qt A Qt^T is formed in
+  // float64 from the rotations accumulated so far, and float64 sweeps finish the job.  What the
+  // float32 sweeps cannot resolve (eigenvalues below 1e-7 of the largest) is left to them.
+  const bool mixed = !warm;
+  float *w32 = reinterpret_cast<float *>(w);      // shares the memory of W: it is dead when W is formed
   ia.warm = warm ? 1 : 0;
-  hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cnt), dim3(256), 0, s, ia);
+  if (mixed) {
+    ia.w = w32;
+    hipLaunchKernelGGL(blockjac_init_kernel<float>, dim3(np, cnt), dim3(256), 0, s, ia);
+  } else {
+    hipLaunchKernelGGL(blockjac_init_kernel<double>, dim3(np, cnt), dim3(256), 0, s, ia);
+  }
   HIP_TRY(hipGetLastError());
-  if (warm) {
+  auto congruence = [&]() {
     // W = Qt A Qt^T, a panel of columns at a time: T = A Qt^T[:, panel], W[:, panel] = Qt T
     const int pw_max = std::min(np, CONGRUENCE_PANEL);
     double *tp = reinterpret_cast<double *>(ws + e.off_t) + (int64_t)slot0 * np * pw_max;
@@ -515,21 +527,36 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
       hipLaunchKernelGGL((congruence_gemm_kernel<true, true>), dim3((pw + CG_TILE - 1) / CG_TILE, (np + CG_TILE - 1) / CG_TILE, cnt),
                          dim3(CG_THREADS), 0, s, c2);
     }
-    HIP_TRY(hipGetLastError());
-  }
+  };
   BlockJacArgs ja;
-  ja.w = w; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
+  ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
   ja.np = np;
   ja.inner_sweeps = JAC_INNER_SWEEPS;
-  ja.tol_rel = JAC_BLOCK_TOL_REL;
   const int appw_seg = appw_segments(hp);
-  for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
+  const int q_blocks = hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES);
+  int sw = 0;
+  if (mixed) {
+    ja.phase_start = 0; ja.tol_rel = JAC_F32_TOL_REL; ja.tol_abs_rel = JAC_F32_TOL_ABS;
+    for (; sw < JAC_F32_SWEEPS; ++sw)
+      for (int rd = 0; rd < nblk - 1; ++rd) {
+        ja.round = rd; ja.sweep = sw;
+        hipLaunchKernelGGL(blockjac_pivot_kernel<float>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_w32_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(q_blocks, cnt), dim3(JAC_THREADS), 0, s, ja);
+      }
+    HIP_TRY(hipGetLastError());
+  }
+  if (mixed || warm) {
+    congruence();
+    HIP_TRY(hipGetLastError());
+  }
+  ja.phase_start = sw; ja.tol_rel = JAC_BLOCK_TOL_REL; ja.tol_abs_rel = JAC_SMALL_TOL_ABS;
+  for (; sw < JAC_OUTER_SWEEPS; ++sw)
     for (int rd = 0; rd < nblk - 1; ++rd) {
       ja.round = rd; ja.sweep = sw;
-      hipLaunchKernelGGL(blockjac_pivot_kernel, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+      hipLaunchKernelGGL(blockjac_pivot_kernel<double>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
       hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
-      hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES), cnt),
-                         dim3(JAC_THREADS), 0, s, ja);
+      hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(q_blocks, cnt), dim3(JAC_THREADS), 0, s, ja);
     }
   HIP_TRY(hipGetLastError());
   BlockFinalArgs fa;
@@ -816,8 +843,8 @@ size_t layout(const shampoo_config *c, Plan &p, shampoo_opt *o) {
     const bool warm = c->warm_start_roots != 0 && c->root_method == SHAMPOO_ROOT_EIGH;
     eL.push_back(eig_layout(em, b.count, EIG_CHUNK_BYTES, 0, warm));
     eR.push_back(eig_layout(en, b.count, EIG_CHUNK_BYTES, 0, warm));
-    if (eL.back().warm) b.off_QtL = take(B * (size_t)eL.back().np * eL.back().np * 4);
-    if (eR.back().warm) b.off_QtR = take(B * (size_t)eR.back().np * eR.back().np * 4);
+    if (warm && eL.back().np > 0) b.off_QtL = take(B * (size_t)eL.back().np * eL.back().np * 4);
+    if (warm && eR.back().np > 0) b.off_QtR = take(B * (size_t)eR.back().np * eR.back().np * 4);
     for (int k = 0; k < 2; ++k) eM[k].push_back(eig_layout(b.td[k + 1], b.count));
     // under coupled Newton the eigensolver is the fallback of the guard (Sec. 3.2.3): room for both
     if (c->root_method == SHAMPOO_ROOT_NEWTON)
