@@ -472,44 +472,91 @@ struct WarmStart {
   int32_t *sweeps = nullptr;    // optional [batch]: sweeps in which anything rotated
 };
 
-int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float scale, float *x, float *lambda,
-                       int32_t *failed_user, unsigned long long *fail_count, unsigned char *ws,
-                       const EigLayout &e, int slot0, hipStream_t s, const int32_t *only, const WarmStart &ws_in) {
-  const int np = e.np, nblk = np / JAC_NB, hp = nblk / 2;
-  double *w = reinterpret_cast<double *>(ws + e.off_w) + (int64_t)slot0 * np * np;
-  float *qt = ws_in.qt ? ws_in.qt : reinterpret_cast<float *>(ws + e.off_qt) + (int64_t)slot0 * np * np;
-  const bool warm = ws_in.qt && ws_in.start && e.warm;
-  float *jbuf = reinterpret_cast<float *>(ws + e.off_j) + (int64_t)slot0 * hp * JAC_PIV * JAC_PIV;
-  int32_t *ident = reinterpret_cast<int32_t *>(ws + e.off_ident) + (int64_t)slot0 * hp;
-  int32_t *rot = reinterpret_cast<int32_t *>(ws + e.off_rot) + (int64_t)slot0 * JAC_OUTER_SWEEPS;
-  float *dmax = reinterpret_cast<float *>(ws + e.off_dmax) + slot0;
-  int32_t *failed = reinterpret_cast<int32_t *>(ws + e.off_failed) + slot0;
-  float *fv = reinterpret_cast<float *>(ws + e.off_f) + (int64_t)slot0 * np;
-  int rc = launch_fill(dmax, 0.f, cnt, s);
-  if (rc) return rc;
-  rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, cnt, s);
-  if (rc) return rc;
-  BlockInitArgs ia;
-  ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
-  ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot; ia.only = only;
-  // A cold solve runs its first sweeps on a float32 copy of W (twice the matrix-core and vector
-  // rates, half the bytes), then continues exactly like a warm start: W = Qt A Qt^T is formed in
-  // float64 from the rotations accumulated so far, and float64 sweeps finish the job.  What the
-  // float32 sweeps cannot resolve (eigenvalues below 1e-7 of the largest) is left to them.
-  const bool mixed = !warm;
-  float *w32 = reinterpret_cast<float *>(w);      // shares the memory of W: it is dead when W is formed
-  ia.warm = warm ? 1 : 0;
-  if (mixed) {
-    ia.w = w32;
-    hipLaunchKernelGGL(blockjac_init_kernel<float>, dim3(np, cnt), dim3(256), 0, s, ia);
-  } else {
-    hipLaunchKernelGGL(blockjac_init_kernel<double>, dim3(np, cnt), dim3(256), 0, s, ia);
+// One sub-chunk of a block-Jacobi solve: `cnt` matrices in workspace slots [slot0, slot0 + cnt),
+// all of its work on one stream.  The solve is enqueued phase by phase (begin, then sweep after
+// sweep, then finish) so that the caller can interleave the sub-chunks of a chunk: the host
+// needs a few microseconds per launch and a solve is thousands of launches, so a sub-chunk
+// that were enqueued whole before the next one would run alone for most of its time.
+struct BlockSolve {
+  const float *a; int n, cnt; float eps, r, scale; float *x, *lambda; int32_t *failed_user;
+  unsigned long long *fail_count; unsigned char *ws; const EigLayout *e; int slot0; hipStream_t s;
+  const int32_t *only; WarmStart warm_in;
+  // derived
+  int np = 0, nblk = 0, hp = 0, sw = 0;
+  bool warm = false, mixed = false;
+  double *w = nullptr; float *w32 = nullptr, *qt = nullptr, *fv = nullptr;
+  int32_t *rot = nullptr, *failed = nullptr;
+  BlockJacArgs ja{};
+
+  int begin() {
+    np = e->np; nblk = np / JAC_NB; hp = nblk / 2;
+    w = reinterpret_cast<double *>(ws + e->off_w) + (int64_t)slot0 * np * np;
+    qt = warm_in.qt ? warm_in.qt : reinterpret_cast<float *>(ws + e->off_qt) + (int64_t)slot0 * np * np;
+    warm = warm_in.qt && warm_in.start && e->warm;
+    float *jbuf = reinterpret_cast<float *>(ws + e->off_j) + (int64_t)slot0 * hp * JAC_PIV * JAC_PIV;
+    int32_t *ident = reinterpret_cast<int32_t *>(ws + e->off_ident) + (int64_t)slot0 * hp;
+    rot = reinterpret_cast<int32_t *>(ws + e->off_rot) + (int64_t)slot0 * JAC_OUTER_SWEEPS;
+    float *dmax = reinterpret_cast<float *>(ws + e->off_dmax) + slot0;
+    failed = reinterpret_cast<int32_t *>(ws + e->off_failed) + slot0;
+    fv = reinterpret_cast<float *>(ws + e->off_f) + (int64_t)slot0 * np;
+    int rc = launch_fill(dmax, 0.f, cnt, s);
+    if (rc) return rc;
+    rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, cnt, s);
+    if (rc) return rc;
+    BlockInitArgs ia;
+    ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
+    ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot; ia.only = only;
+    // A cold solve runs its first sweeps on a float32 copy of W (twice the matrix-core and vector
+    // rates, half the bytes), then continues exactly like a warm start: W = Qt A Qt^T is formed in
+    // float64 from the rotations accumulated so far, and float64 sweeps finish the job.  What the
+    // float32 sweeps cannot resolve (eigenvalues below 1e-7 of the largest) is left to them.
+    mixed = !warm;
+    w32 = reinterpret_cast<float *>(w);      // shares the memory of W: it is dead when W is formed
+    ia.warm = warm ? 1 : 0;
+    if (mixed) {
+      ia.w = w32;
+      hipLaunchKernelGGL(blockjac_init_kernel<float>, dim3(np, cnt), dim3(256), 0, s, ia);
+    } else {
+      hipLaunchKernelGGL(blockjac_init_kernel<double>, dim3(np, cnt), dim3(256), 0, s, ia);
+    }
+    HIP_TRY(hipGetLastError());
+    ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
+    ja.np = np;
+    ja.inner_sweeps = JAC_INNER_SWEEPS;
+    sw = 0;
+    return SHAMPOO_OK;
   }
-  HIP_TRY(hipGetLastError());
-  auto congruence = [&]() {
+  int f32_sweeps() const { return mixed ? JAC_F32_SWEEPS : 0; }
+  // The next sweep: float32 while sw < f32_sweeps(), then (once) the congruence, then float64.
+  int sweep() {
+    const int appw_seg = appw_segments(hp);
+    const int q_blocks = hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES);
+    const bool f32 = sw < f32_sweeps();
+    if (f32) {
+      ja.phase_start = 0; ja.tol_rel = JAC_F32_TOL_REL; ja.tol_abs_rel = JAC_F32_TOL_ABS;
+    } else {
+      if (sw == f32_sweeps() && (mixed || warm)) congruence();
+      ja.phase_start = f32_sweeps(); ja.tol_rel = JAC_BLOCK_TOL_REL; ja.tol_abs_rel = JAC_SMALL_TOL_ABS;
+    }
+    for (int rd = 0; rd < nblk - 1; ++rd) {
+      ja.round = rd; ja.sweep = sw;
+      if (f32) {
+        hipLaunchKernelGGL(blockjac_pivot_kernel<float>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_w32_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
+      } else {
+        hipLaunchKernelGGL(blockjac_pivot_kernel<double>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
+      }
+      hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(q_blocks, cnt), dim3(JAC_THREADS), 0, s, ja);
+    }
+    HIP_TRY(hipGetLastError());
+    ++sw;
+    return SHAMPOO_OK;
+  }
+  void congruence() {
     // W = Qt A Qt^T, a panel of columns at a time: T = A Qt^T[:, panel], W[:, panel] = Qt T
     const int pw_max = std::min(np, CONGRUENCE_PANEL);
-    double *tp = reinterpret_cast<double *>(ws + e.off_t) + (int64_t)slot0 * np * pw_max;
+    double *tp = reinterpret_cast<double *>(ws + e->off_t) + (int64_t)slot0 * np * pw_max;
     for (int col0 = 0; col0 < np; col0 += pw_max) {
       const int pw = std::min(pw_max, np - col0);
       CongruenceArgs c1{};
@@ -527,56 +574,27 @@ int block_jacobi_solve(const float *a, int n, int cnt, float eps, float r, float
       hipLaunchKernelGGL((congruence_gemm_kernel<true, true>), dim3((pw + CG_TILE - 1) / CG_TILE, (np + CG_TILE - 1) / CG_TILE, cnt),
                          dim3(CG_THREADS), 0, s, c2);
     }
-  };
-  BlockJacArgs ja;
-  ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
-  ja.np = np;
-  ja.inner_sweeps = JAC_INNER_SWEEPS;
-  const int appw_seg = appw_segments(hp);
-  const int q_blocks = hp * ((np / JAC_PIV + APPQ_TILES - 1) / APPQ_TILES);
-  int sw = 0;
-  if (mixed) {
-    ja.phase_start = 0; ja.tol_rel = JAC_F32_TOL_REL; ja.tol_abs_rel = JAC_F32_TOL_ABS;
-    for (; sw < JAC_F32_SWEEPS; ++sw)
-      for (int rd = 0; rd < nblk - 1; ++rd) {
-        ja.round = rd; ja.sweep = sw;
-        hipLaunchKernelGGL(blockjac_pivot_kernel<float>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
-        hipLaunchKernelGGL(blockjac_apply_w32_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
-        hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(q_blocks, cnt), dim3(JAC_THREADS), 0, s, ja);
-      }
-    HIP_TRY(hipGetLastError());
   }
-  if (mixed || warm) {
-    congruence();
+  int finish() {
+    BlockFinalArgs fa;
+    fa.w = w; fa.qt = qt; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.scale = scale; fa.fvals = fv;
+    fa.lambda = lambda;
+    fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
+    fa.rot = rot; fa.sweeps_out = warm_in.sweeps;
+    hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);
     HIP_TRY(hipGetLastError());
+    GemmArgs g{};
+    g.a.base = qt; g.a.batch_stride = (int64_t)np * np; g.a.ld = np; g.a.from_table = 0;
+    g.b = g.a;
+    g.c = x; g.c_batch_stride = (int64_t)n * n; g.ldc = n;
+    g.M = n; g.N = n; g.K = np; g.alpha = 1.f; g.beta = 0.f;
+    g.kscale = fv; g.kscale_stride = np; g.skip = failed;
+    g.tiles_m = g.tiles_n = (n + BM - 1) / BM;
+    g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
+    g.batch = cnt;
+    return launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_SYRK, true>(g, s);
   }
-  ja.phase_start = sw; ja.tol_rel = JAC_BLOCK_TOL_REL; ja.tol_abs_rel = JAC_SMALL_TOL_ABS;
-  for (; sw < JAC_OUTER_SWEEPS; ++sw)
-    for (int rd = 0; rd < nblk - 1; ++rd) {
-      ja.round = rd; ja.sweep = sw;
-      hipLaunchKernelGGL(blockjac_pivot_kernel<double>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
-      hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
-      hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(q_blocks, cnt), dim3(JAC_THREADS), 0, s, ja);
-    }
-  HIP_TRY(hipGetLastError());
-  BlockFinalArgs fa;
-  fa.w = w; fa.qt = qt; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.scale = scale; fa.fvals = fv;
-  fa.lambda = lambda;
-  fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
-  fa.rot = rot; fa.sweeps_out = ws_in.sweeps;
-  hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);
-  HIP_TRY(hipGetLastError());
-  GemmArgs g{};
-  g.a.base = qt; g.a.batch_stride = (int64_t)np * np; g.a.ld = np; g.a.from_table = 0;
-  g.b = g.a;
-  g.c = x; g.c_batch_stride = (int64_t)n * n; g.ldc = n;
-  g.M = n; g.N = n; g.K = np; g.alpha = 1.f; g.beta = 0.f;
-  g.kscale = fv; g.kscale_stride = np; g.skip = failed;
-  g.tiles_m = g.tiles_n = (n + BM - 1) / BM;
-  g.tiles = g.tiles_m * (g.tiles_m + 1) / 2;
-  g.batch = cnt;
-  return launch_gemm<ROW_CONTIG, ROW_CONTIG, float, float, EPI_SYRK, true>(g, s);
-}
+};
 
 // X_i = rootinv(scale * A_i) for a batch of dense n x n matrices.  ws: eig_layout(n, >= chunk) region.
 // aux: helper streams for the sub-chunks of the block solver (the caller owns them and
@@ -620,21 +638,28 @@ int root_inverse_batched(const float *a, int n, int batch, float eps, float r, f
       HIP_TRY(hipEventRecord(aux->fork, s));
       for (int k = 1; k < subs; ++k) HIP_TRY(hipStreamWaitEvent(aux->stream[k - 1], aux->fork, 0));
     }
+    BlockSolve solve[JAC_STREAMS];
     int first = 0;
     for (int k = 0; k < subs; ++k) {
       const int cnt = cb / subs + (k < cb % subs ? 1 : 0);
-      hipStream_t sk = k == 0 ? s : aux->stream[k - 1];
       WarmStart wk = warm;
       if (wk.qt) wk.qt += (int64_t)(b0 + first) * e.np * e.np;
       if (wk.sweeps) wk.sweeps += b0 + first;
-      const int rc = block_jacobi_solve(a + (int64_t)(b0 + first) * n * n, n, cnt, eps, r, scale,
-                                        x + (int64_t)(b0 + first) * n * n,
-                                        lambda ? lambda + (int64_t)(b0 + first) * n : nullptr,
-                                        failed_user ? failed_user + b0 + first : nullptr, fail_count, ws, e, first, sk,
-                                        only ? only + b0 + first : nullptr, wk);
-      if (rc) return rc;
+      solve[k] = BlockSolve{a + (int64_t)(b0 + first) * n * n, n, cnt, eps, r, scale,
+                            x + (int64_t)(b0 + first) * n * n,
+                            lambda ? lambda + (int64_t)(b0 + first) * n : nullptr,
+                            failed_user ? failed_user + b0 + first : nullptr, fail_count, ws, &e, first,
+                            k == 0 ? s : aux->stream[k - 1], only ? only + b0 + first : nullptr, wk};
       first += cnt;
     }
+    // sweep by sweep across the sub-chunks, so that all of them are under way from the start
+    for (int k = 0; k < subs; ++k)
+      if (const int rc = solve[k].begin()) return rc;
+    for (int sw = 0; sw < JAC_OUTER_SWEEPS; ++sw)
+      for (int k = 0; k < subs; ++k)
+        if (const int rc = solve[k].sweep()) return rc;
+    for (int k = 0; k < subs; ++k)
+      if (const int rc = solve[k].finish()) return rc;
     if (subs > 1)
       for (int k = 1; k < subs; ++k) {
         HIP_TRY(hipEventRecord(aux->join[k - 1], aux->stream[k - 1]));
