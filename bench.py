@@ -1,6 +1,7 @@
 """Benchmark of the per-block Shampoo step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload transformer|resnet50|uniform]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload transformer|resnet50|uniform|rootstress]
+                    [--block-size 2048|4096|8192]
 
 Workload (default): the transformer-shaped parameter set -- 24 layers at d = 2048
 (QKV 2048x6144, attention out 2048x2048, MLP up 2048x8192, MLP down 8192x2048,
@@ -16,20 +17,30 @@ the root-inverse refresh; it runs in the warm-up and its time is reported separa
 (`refresh_ms`).  The K timed steps are non-refresh steps.
 
 One JSON line is printed:
-  metric/value        milliseconds per (non-refresh) step, whole job, one GPU
-  roofline            the dominant kernel: for blocks above 128 the GEMM of the two-sided
-                      preconditioning.  With bf16 gradients it runs on the fp16 matrix cores from
-                      float32 operands split into two scaled fp16 planes (three exact products per
-                      float32 product for P = T Rbar, two for T = Lbar G): `achieved` is the
-                      executed fp16 MFMA rate (algorithmic flops x products / launch time) against
-                      the 2.5 PFLOP/s fp16 peak, and `algorithmic_tflops` the float32-equivalent
-                      rate; with --fp32-matrix-cores or float32 gradients it is the float32-MFMA
-                      kernel against 157.3 TFLOP/s.  For workloads whose blocks are at most
-                      128 x 128 it is the
+  metric/value        milliseconds per (non-refresh) step, whole job, one GPU; next to it
+                      `refresh_ms` (one root-inverse refresh of every factor, taken at the first
+                      timed refresh) and `amortized_ms_per_step` = value + refresh_ms / f
+  roofline            the dominant kernel: for blocks above 128 the second GEMM of the two-sided
+                      preconditioning, P = T Rbar.  `achieved` is its ALGORITHMIC rate: 2 m n^2 flops
+                      per block x blocks per launch / average launch duration, against the dense
+                      peak of the matrix-core type it runs on.  With bf16 gradients that is the fp16
+                      matrix cores (2.5 PFLOP/s): the float32 operands are split into two scaled
+                      fp16 planes and three exact fp16 products make one float32 product, so the
+                      matrix cores execute three times the algorithmic flops: `executed_tflops` /
+                      `executed_frac` give that utilisation separately.  With --fp32-matrix-cores
+                      or float32 gradients it is the float32-MFMA kernel against 157.3 TFLOP/s
+                      (the default run carries that variant's step and roofline in
+                      `fp32_matrix_cores`, from a short second run without refresh).  For workloads
+                      whose blocks are at most 128 x 128 the dominant kernel is the
                       single-workgroup block-step kernel, which is bound by HBM (algorithmic
                       bytes per launch / average launch duration).  Durations come from HIP
                       events recorded by the library on the step's stream
-  cpu_baseline        the fp64 numpy oracle timed on the host on a sample of blocks
+  cpu_baseline        the fp64 numpy oracle timed on the host, stage by stage, on a sample of
+                      blocks (48 of the largest bucket for a non-refresh step, 16 factors for
+                      the refresh), scaled linearly to the whole block set
+
+--workload rootstress times the root-inverse stress case instead (256 matrices of 2048 x 2048,
+rank 64 + 1e-6 I): one JSON line with metric root_inverse_ms.
 """
 import argparse
 import json
@@ -59,12 +70,13 @@ PEAK_HBM_GBS = 8000.0
 TILE = 128
 
 
-def workload(name):
+def workload(name, block_size=None):
     from paper_2309_06497_amd import workloads as wl
     from paper_2309_06497_amd import binding as B
     if name == "transformer":
-        return dict(shapes=wl.transformer_shapes(), block=1024, sigma=1e-3, f=100, bf16=True,
-                    label="transformer 24 x d2048, block 1024, 1152 blocks, bf16 gradients")
+        b = block_size or 1024
+        return dict(shapes=wl.transformer_shapes(), block=b, sigma=1e-3, f=100, bf16=True,
+                    label=f"transformer 24 x d2048, block {b}, bf16 gradients")
     if name == "resnet50":
         return dict(shapes=wl.resnet50_shapes(), block=128, sigma=1e-3, f=50, bf16=False,
                     label="ResNet-50 shapes, block 128, 1576 blocks, fp32 gradients")
@@ -100,9 +112,9 @@ def fused_bytes(table, gsz):
 
 
 def cpu_baseline(wk, table, rng_seed=0):
-    """The oracle, untuned, on the host cores: a bounded sample of blocks of the largest
-    bucket for one non-refresh step, and a few factors for the refresh; scaled linearly to
-    the whole block set (blocks are independent)."""
+    """The oracle, untuned, on the host cores, stage by stage: a bounded sample of blocks of
+    the largest bucket for one non-refresh step, and a few factors for the refresh; scaled
+    linearly to the whole block set (blocks are independent)."""
     from oracle import shampoo_oracle as so
     rng = np.random.default_rng(rng_seed)
     sizes = {}
@@ -110,40 +122,97 @@ def cpu_baseline(wk, table, rng_seed=0):
         sizes[(int(row[3]), int(row[4]))] = sizes.get((int(row[3]), int(row[4])), 0) + 1
     (m, n), _ = max(sizes.items(), key=lambda kv: kv[1] * kv[0][0] * kv[0][1])
     elems_total = sum(float(r[3]) * float(r[4]) for r in table)
-    n_step = 8 if m * n >= 512 * 512 else 64
-    n_root = 4 if m >= 512 else 32
+    n_step = 48 if m * n >= 512 * 512 else 256
+    if m * n >= 4096 * 2048:
+        n_step = 4
+    n_root = 8 if m >= 512 else 64
+    if m >= 4096:
+        n_root = 1
     f32 = lambda v: float(np.float32(v))
     state = []
     for _ in range(n_step):
         G = (rng.standard_normal((m, n)) * wk["sigma"]).astype(np.float32)
         L, R = so.factor_update(np.zeros((m, m)), np.zeros((n, n)), G, f32(0.999))
         state.append([L, R, np.eye(m), np.eye(n), np.zeros((m, n)), np.zeros((m, n)), np.zeros((m, n))])
-    t0 = time.perf_counter()
+    stage = {"factor": 0.0, "graft": 0.0, "precond": 0.0, "update": 0.0}
+    clk = time.perf_counter
     for st in state:
         G = (rng.standard_normal((m, n)) * wk["sigma"]).astype(np.float32)
+        t0 = clk()
         st[0], st[1] = so.factor_update(st[0], st[1], G, f32(0.999))
+        t1 = clk()
         st[4] = so.graft_state_update(st[4], G)
         Pg = so.graft_direction(G, st[4], f32(1e-10))
-        P = so.grafted_direction(so.shampoo_direction(st[2], G, st[3]), Pg)
+        t2 = clk()
+        Psh = so.shampoo_direction(st[2], G, st[3])
+        t3 = clk()
+        P = so.grafted_direction(Psh, Pg)
         st[5] = f32(0.9) * st[5] + P
         st[6] += f32(0.01) * st[5]
-    t_step = (time.perf_counter() - t0) / (n_step * m * n) * elems_total
-    t0 = time.perf_counter()
+        t4 = clk()
+        stage["factor"] += t1 - t0; stage["graft"] += t2 - t1; stage["precond"] += t3 - t2; stage["update"] += t4 - t3
+    scale = elems_total / (n_step * m * n)
+    stage_ms = {k: v * scale * 1e3 for k, v in stage.items()}
+    t0 = clk()
     for st in state[:n_root]:
         so.root_inverse(st[0], f32(1e-12), 0.25)
         so.root_inverse(st[1], f32(1e-12), 0.25)
-    t_root = (time.perf_counter() - t0) / (n_root * (m * m + n * n)) * sum(
+    t_root = (clk() - t0) / (n_root * (m * m + n * n)) * sum(
         float(r[3]) ** 2 + float(r[4]) ** 2 for r in table)
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count()
-    return {"value": t_step * 1e3, "unit": "ms/step", "cores": cores, "kind": "oracle",
-            "refresh_ms": t_root * 1e3,
-            "sample": f"{n_step} of {len(table)} blocks ({m}x{n}) for one non-refresh step and "
-                      f"{2 * n_root} factors for the refresh, numpy float64 (LAPACK eigh), "
+    return {"value": sum(stage_ms.values()), "unit": "ms/step", "cores": cores, "kind": "oracle",
+            "stage_ms_per_step": stage_ms, "refresh_ms": t_root * 1e3,
+            "sample": f"{n_step} of {len(table)} blocks ({m}x{n}) for one non-refresh step, timed stage by "
+                      f"stage, and {2 * n_root} factors for the refresh, numpy float64 (LAPACK eigh), "
                       f"scaled linearly to the whole block set (extrapolated)"}
+
+
+def rootstress(args):
+    """The root-inverse stress case: 256 matrices of 2048 x 2048, rank 64 + 1e-6 I."""
+    import torch
+    from paper_2309_06497_amd import binding as B
+    from oracle import shampoo_oracle as so
+    n, rank, batch = 2048, 64, 256
+    dev = torch.device("cuda", 0)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    a = torch.empty((batch, n, n), dtype=torch.float32, device=dev)
+    for i in range(0, batch, 16):     # formed in float64, rounded once to float32
+        g = torch.randn((16, n, rank), generator=gen, device=dev, dtype=torch.float64)
+        a[i:i + 16] = (g @ g.transpose(1, 2) + 1e-6 * torch.eye(n, dtype=torch.float64, device=dev)).to(torch.float32)
+    times = []
+    for rep in range(max(args.warmup, 1) + max(args.steps // 5, 1)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        x, failed = B.shampoo_root_inverse(a, 1e-12, 0.25, False, True)
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3)
+    timed = times[max(args.warmup, 1):]
+    ms = sum(timed) / len(timed)
+    out = {"metric": "root_inverse_ms", "value": ms, "unit": "ms", "n_gpus": 1, "steps": len(timed),
+           "warmup": max(args.warmup, 1), "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32 in / out, f32 + f64 sweeps", "data": "synthetic",
+           "config": {"workload": "root-inverse stress: 256 matrices of 2048 x 2048, rank 64 + 1e-6 I, eps 1e-12, exponent 1/4"},
+           "ms_per_matrix": ms / batch, "failed_roots": int(failed.sum())}
+    if not args.no_cpu_baseline:
+        a_host = a[:2].cpu().numpy()
+        t0 = time.perf_counter()
+        for k in range(2):
+            so.root_inverse(a_host[k], float(np.float32(1e-12)), 0.25)
+        t_cpu = (time.perf_counter() - t0) / 2 * batch
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        out["cpu_baseline"] = {"value": t_cpu * 1e3, "unit": "ms", "cores": cores, "kind": "oracle",
+                               "sample": "2 of the 256 matrices, numpy float64 (LAPACK eigh), scaled linearly (extrapolated)"}
+    print(json.dumps(out))
+    return 0
 
 
 def main():
@@ -152,6 +221,11 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="transformer")
+    ap.add_argument("--block-size", type=int, default=None,
+                    help="block size of the transformer workload (default 1024; 2048, 4096 and 8192 are the "
+                         "larger preconditioner sizes of Sec. 4.2.1 / Table 5)")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the short second run of the default workload on the float32 matrix cores")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-refresh", action="store_true",
                     help="number the steps from 1 so that no root refresh runs (roots stay the identity); "
@@ -173,10 +247,12 @@ def main():
         print("bench.py: this build runs on one GPU only (the multi-GPU distribution of the "
               "paper is out of scope); rerun with --gpus 1", file=sys.stderr)
         return 2
+    if args.workload == "rootstress":
+        return rootstress(args)
     import torch
     from paper_2309_06497_amd import binding as B
 
-    wk = workload(args.workload)
+    wk = workload(args.workload, args.block_size)
     shapes = wk["shapes"]
     f = wk["f"]
     warm = max(args.warmup, 1)
@@ -246,22 +322,25 @@ def main():
     gsz = 2 if wk["bf16"] else 4
     ew_bytes = {"graft": (gsz + 8.0) * n_elems, "update": 20.0 * n_elems}
     x2 = wk["bf16"] and not args.fp32_matrix_cores and wk["block"] % 8 == 0
+    default_shape = args.workload == "transformer" and wk["block"] == 1024
     if x2:
         # P = T Rbar executes 3 fp16 products per float32 product (T = Lbar G: 2, the gradient is one plane)
         executed = achieved * 3.0
-        roofline = {"bound": "mfma", "achieved": executed, "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                    "frac": executed / PEAK_F16_MFMA_TFLOPS, "traffic": X2_TRAFFIC_BYTES.get(args.workload),
-                    "kernel": "gemm_f16x2_kernel<256, 2> (P = T Rbar, fp16 MFMA on two-plane float32 operands)",
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_F16_MFMA_TFLOPS,
+                    "traffic": X2_TRAFFIC_BYTES.get(args.workload) if default_shape else None,
+                    "kernel": "gemm_f16x2_kernel<256, 128, 2, 0> (P = T Rbar, fp16 MFMA on two-plane float32 operands)",
                     "matrix_core_dtype": "f16", "products_per_float32_product": 3,
-                    "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch * 3.0,
+                    "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch,
+                    "executed_flops_per_launch": gemm_flops_per_launch * 3.0,
+                    "executed_tflops": executed, "executed_frac": executed / PEAK_F16_MFMA_TFLOPS,
                     "first_product_launch_ms": first_ms,
-                    "algorithmic_flops_per_launch": gemm_flops_per_launch, "algorithmic_tflops": achieved,
-                    "algorithmic_frac_of_fp32_mfma_peak": achieved / PEAK_FP32_MFMA_TFLOPS}
+                    "frac_of_fp32_mfma_peak": achieved / PEAK_FP32_MFMA_TFLOPS}
     else:
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                    "traffic": TRAFFIC_BYTES.get(args.workload),
-                    "kernel": "gemm_mfma_kernel (P = T Rbar, fp32 MFMA)",
+                    "traffic": TRAFFIC_BYTES.get(args.workload) if default_shape else None,
+                    "kernel": "gemm_mfma_kernel<0, 1, float, float, 1, false, 0> (P = T Rbar, fp32 MFMA)",
                     "matrix_core_dtype": "f32", "first_product_launch_ms": first_ms,
                     "launch_ms": launch_ms, "flops_per_launch": gemm_flops_per_launch}
     fused_ms, fused_launches = stages["fused"]
@@ -284,7 +363,7 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32 state and accumulation, operands of the preconditioning products as two fp16 planes" if x2 else "f32",
         "data": "synthetic",
         "config": {"workload": wk["label"], "params": n_elems, "blocks": int(len(table)),
                    "buckets": int(n_buckets), "block_size": wk["block"], "precondition_frequency": f,
@@ -310,10 +389,41 @@ def main():
         },
         "status": status,
     }
+    if x2 and default_shape and not args.no_secondary and not args.skip_refresh:
+        out["fp32_matrix_cores"] = secondary_fp32(B, torch, wk, shapes, params, pool, alg_p2, args.steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wk, table)
     print(json.dumps(out))
     return 0
+
+
+def secondary_fp32(B, torch, wk, shapes, params, pool, alg_p2, steps):
+    """The same workload with the preconditioning products kept on the float32 matrix cores
+    (bench.py --fp32-matrix-cores runs it in full): a short second run without refresh (the
+    roots stay the identity, which changes no kernel's work), for the step time and the
+    roofline of the float32 MFMA kernel."""
+    opt = B.Shampoo(shapes, wk["block"], 0.999, 1e-12, 0.25, wk["f"], 0, 1e-10, 0.9, B.GRAD_BF16,
+                    precond_matrix_cores=B.MATRIX_CORES_FP32)
+    opt.set_timing(True)
+    w = [p.clone() for p in params]
+    for t in range(1, 3):
+        opt.step(w, pool[t % 2], 0.01, t)
+    torch.cuda.synchronize()
+    opt.get_timing()
+    n = max(3, steps // 2)
+    t0 = time.perf_counter()
+    for t in range(3, 3 + n):
+        opt.step(w, pool[t % 2], 0.01, t)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / n
+    st = opt.get_timing()
+    launch_ms = st["precond2"][0] / max(st["precond2"][1], 1)
+    tf = alg_p2 * n / max(st["precond2"][1], 1) / (launch_ms * 1e-3) / 1e12
+    return {"ms_per_step": ms, "steps": n, "roots": "identity (no refresh in this second run)",
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf / PEAK_FP32_MFMA_TFLOPS, "launch_ms": launch_ms,
+                         "kernel": "gemm_mfma_kernel<0, 1, float, float, 1, false, 0> (P = T Rbar, fp32 MFMA)"},
+            "command": "python bench.py --fp32-matrix-cores"}
 
 
 if __name__ == "__main__":
