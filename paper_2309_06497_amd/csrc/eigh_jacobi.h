@@ -846,13 +846,17 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
   int pk, qk;
   rr_pair(nblk, g.round, k, pk, qk);
   bool have_jk = false;
-  // one 32 x 32 sub-block between W and the 64 x 64 LDS tile (see copy_subblock)
-  auto sub_load = [&](int ra, int cb, int xi, int xj) {
+  // One 32 x 32 sub-block on its way from W to the 64 x 64 LDS tile, in two halves (global ->
+  // register, register -> LDS) so that the loads of the next pair-block are in flight while
+  // the current one is multiplied.  Thread -> row tid / 8 of the stored sub-block, 4 columns.
+  const int ii = tid >> 3, j4 = (tid & 7) * 4;
+  auto sub_fetch32 = [&](int ra, int cb) {
     const bool tr = ra < cb;
     const int gr0 = (tr ? cb : ra) * JAC_NB, gc0 = (tr ? ra : cb) * JAC_NB;
-    const int ii = tid >> 3, j4 = (tid & 7) * 4;       // 32 rows x 8 float4
-    const float4 v = *reinterpret_cast<const float4 *>(w + (int64_t)(gr0 + ii) * np + gc0 + j4);
-    if (tr) {
+    return *reinterpret_cast<const float4 *>(w + (int64_t)(gr0 + ii) * np + gc0 + j4);
+  };
+  auto sub_stash32 = [&](const float4 &v, int ra, int cb, int xi, int xj) {
+    if (ra < cb) {     // kept transposed in W
       X[(xi + j4) * APP_LD + xj + ii] = v.x; X[(xi + j4 + 1) * APP_LD + xj + ii] = v.y;
       X[(xi + j4 + 2) * APP_LD + xj + ii] = v.z; X[(xi + j4 + 3) * APP_LD + xj + ii] = v.w;
     } else {
@@ -860,22 +864,46 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
     }
   };
   auto sub_store = [&](int ra, int cb, int xi, int xj) {   // ra >= cb: stored as it is
-    const int ii = tid >> 3, j4 = (tid & 7) * 4;
     *reinterpret_cast<float4 *>(w + (int64_t)(ra * JAC_NB + ii) * np + cb * JAC_NB + j4) =
         *reinterpret_cast<const float4 *>(&X[(xi + ii) * APP_LD + xj + j4]);
   };
-  for (int l = l_first; l < l_end; ++l) {
-    if (idk && ident[l] != 0) continue;                  // uniform: neither side rotates
+  // the pair-blocks of this walk that rotate at all, in order (uniform across the workgroup)
+  auto next_active = [&](int from) {
+    int l = from;
+    while (l < l_end && idk && ident[l] != 0) ++l;
+    return l;
+  };
+  float4 wx[4], jn[4];      // the next pair-block: its four sub-blocks and its J_l
+  const int jr = tid >> 4, jc4 = (tid & 15) * 4;
+  auto fetch = [&](int lx) {
+    int pl, ql;
+    rr_pair(nblk, g.round, lx, pl, ql);
+    wx[0] = sub_fetch32(pk, pl); wx[1] = sub_fetch32(pk, ql); wx[2] = sub_fetch32(qk, pl); wx[3] = sub_fetch32(qk, ql);
+    const bool idl = ident[lx] != 0;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const int i = jr + 16 * h;
+      if (idl) jn[h] = make_float4(i == jc4 ? 1.f : 0.f, i == jc4 + 1 ? 1.f : 0.f, i == jc4 + 2 ? 1.f : 0.f, i == jc4 + 3 ? 1.f : 0.f);
+      else jn[h] = *reinterpret_cast<const float4 *>(jb + ((int64_t)lx * JAC_PIV + i) * JAC_PIV + jc4);
+    }
+  };
+  int l = next_active(l_first);
+  if (l >= l_end) return;
+  fetch(l);
+  while (l < l_end) {
+    const int ln = next_active(l + 1);                   // l_end if this is the last one
     int pl, ql;
     rr_pair(nblk, g.round, l, pl, ql);
     __syncthreads();                                     // the tile of the pair-block before is done with
     if (!have_jk) { load_rotation(Jk, jb, k, idk, tid); have_jk = true; }
-    load_rotation(Jl, jb, l, ident[l] != 0, tid);
-    sub_load(pk, pl, 0, 0);
-    sub_load(pk, ql, 0, JAC_NB);
-    sub_load(qk, pl, JAC_NB, 0);
-    sub_load(qk, ql, JAC_NB, JAC_NB);
+#pragma unroll
+    for (int h = 0; h < 4; ++h) *reinterpret_cast<float4 *>(&Jl[(jr + 16 * h) * APP_LD + jc4]) = jn[h];
+    sub_stash32(wx[0], pk, pl, 0, 0);
+    sub_stash32(wx[1], pk, ql, 0, JAC_NB);
+    sub_stash32(wx[2], qk, pl, JAC_NB, 0);
+    sub_stash32(wx[3], qk, ql, JAC_NB, JAC_NB);
     __syncthreads();
+    if (ln < l_end) fetch(ln);                           // in flight during the products below
     // Y^T(kk, i) = sum_m X(m, kk) J_k(m, i)
     const floatx16 yt = mfma_64(X, Jk, wi, wj, lane);
     __syncthreads();                                     // every wavefront has read X
@@ -917,6 +945,7 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
       sub_store(qk, pl, JAC_NB, 0);                      // (pk, qk) is its mirror image and is not kept
       sub_store(qk, ql, JAC_NB, JAC_NB);
     }
+    l = ln;
   }
 }
 
