@@ -83,6 +83,40 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
   const int r0 = chunk * g.geom.rows_per_wg;
   const int r1 = min(r0 + g.geom.rows_per_wg, g.m);
   float ss = 0.f, gmax = 0.f;
+  if (vec && g.same_src && !g.sgd_graft) {
+    // The common case, four column passes at a time, every load requested before the first store.
+    constexpr int U = 4;
+    const int step = 4 << lx;
+    for (int i = r0 + ty; i < r1; i += ny)
+      for (int j0 = tx * 4; j0 < n; j0 += U * step) {
+        float gq[U][4];
+        float4 av[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = j0 + u * step;
+          if (j < n) {
+            Elem<GD>::load4(dp + (int64_t)i * ld + j, gq[u]);
+            av[u] = *reinterpret_cast<const float4 *>(ap + (int64_t)i * ld + j);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = j0 + u * step;
+          if (j < n) {
+            float a4[4] = {av[u].x, av[u].y, av[u].z, av[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float gv = gq[u][e];
+              gmax = fmaxf(gmax, fabsf(gv));
+              a4[e] = g.a_decay * a4[e] + g.a_gain * (gv * gv);
+              const float pg = (gv * g.gd_scale) / (sqrtf(g.a_bc * a4[e]) + g.graft_eps);
+              ss += pg * pg;
+            }
+            *reinterpret_cast<float4 *>(ap + (int64_t)i * ld + j) = make_float4(a4[0], a4[1], a4[2], a4[3]);
+          }
+        }
+      }
+  } else
   for (int i = r0 + ty; i < r1; i += ny)
     for (int j = tx * 4; j < n; j += 4 << lx) {
       const int valid = min(4, n - j);
@@ -171,6 +205,44 @@ __global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
   const int r0 = chunk * g.geom.rows_per_wg;
   const int r1 = min(r0 + g.geom.rows_per_wg, g.m);
   const float sc = g.graft_only ? 0.f : g.scale[slot];
+  if (vec && !g.graft_only && mp) {
+    // The common case, four column passes at a time: all twelve 16-byte loads of a thread are
+    // requested before the first store (a store between two loads would make the second one
+    // wait: the compiler cannot tell that M, W and P do not overlap).
+    constexpr int U = 4;
+    const int step = 4 << lx;
+    for (int i = r0 + ty; i < r1; i += ny)
+      for (int j0 = tx * 4; j0 < n; j0 += U * step) {
+        float4 pv[U], wv[U], mv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = j0 + u * step;
+          if (j < n) {
+            pv[u] = *reinterpret_cast<const float4 *>(pp + (int64_t)i * n + j);
+            wv[u] = *reinterpret_cast<const float4 *>(wp + (int64_t)i * ld + j);
+            mv[u] = *reinterpret_cast<const float4 *>(mp + (int64_t)i * ld + j);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = j0 + u * step;
+          if (j < n) {
+            float p4[4] = {pv[u].x * sc, pv[u].y * sc, pv[u].z * sc, pv[u].w * sc};
+            float w4[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+            float m4[4] = {mv[u].x, mv[u].y, mv[u].z, mv[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (g.wd_decoupled != 0.f) p4[e] -= g.wd_decoupled * w4[e];
+              m4[e] = g.mu * m4[e] + p4[e];
+              w4[e] += g.lr * (g.nesterov ? g.mu * m4[e] + p4[e] : m4[e]);
+            }
+            *reinterpret_cast<float4 *>(mp + (int64_t)i * ld + j) = make_float4(m4[0], m4[1], m4[2], m4[3]);
+            *reinterpret_cast<float4 *>(wp + (int64_t)i * ld + j) = make_float4(w4[0], w4[1], w4[2], w4[3]);
+          }
+        }
+      }
+    return;
+  }
   for (int i = r0 + ty; i < r1; i += ny)
     for (int j = tx * 4; j < n; j += 4 << lx) {
       const int valid = min(4, n - j);
