@@ -308,7 +308,7 @@ int shampoo_root_inverse_warm(const float *a, int32_t n, int32_t batch, float ep
  * workspace: the solver's working arrays live in a fixed array of
  * SHAMPOO_STATIC_SCRATCH_BYTES inside the library's device image (one copy per GPU, held
  * until the process ends), and matrices are processed as many at a time as fit there
- * (n = 2048: one, n = 1024: five; n <= 128 needs no scratch at all).  The call allocates
+ * (n = 2048: one, n = 1024: four; n <= 128 needs no scratch at all).  The call allocates
  * nothing, creates no streams and enqueues kernels only (no memset nodes), all on `stream`.
  * n > SHAMPOO_STATIC_MAX_N: SHAMPOO_ERR_UNSUPPORTED, nothing enqueued.
  * Every call on a GPU uses that GPU's one array: calls whose work overlaps on one GPU (two

@@ -106,9 +106,8 @@ class Pair:
                   over all resolved blocks together (the plain bar; Lbar G Rbar of a
                   block weighted by the norm grafting rescales it to)        <= 2e-3
                   per resolved block                   <= 2e-3 + min(allowance, 10 x 2e-3)
-    The stage-wise bars are about ten times what the kernels measure (the design doc lists the
-    measurements): roots 2e-4 (1e-6 at n <= 128 ... 2e-5 at n = 1024 measured), products 2e-5
-    (<= 4e-6 measured).
+    The stage-wise bars are about ten times what the kernels measure: roots 2e-4 (1e-6 at
+    n <= 128 ... 2e-5 at n = 1024 measured), products 2e-5 (<= 4e-6 measured).
 
     Float32 storage of a factor is part of the workload, and it limits what any kernel can
     deliver end to end: a root weights the smallest eigenvalues of its factor most, the first
