@@ -349,7 +349,12 @@ int shampoo_root_inverse_newton(const float *a, int32_t n, int32_t batch, float 
  * tournament (any even s >= 2, the solver for n <= 128).  halves = 1: the order of the
  * 64 x 64 pivots of the blocked solver (s / 2 a power of two, s >= 4): rounds 0 .. s / 2 - 1
  * pair the first half of the indices with the second, the remaining rounds pair within the
- * halves.  Host only, no device work; SHAMPOO_ERR_NULL / SHAMPOO_ERR_SHAPE on bad arguments. */
+ * halves.  halves = 2: the order of the block columns of the blocked solver when their number
+ * s is a multiple of 4: indices 2 S and 2 S + 1 form a super-column, round 0 pairs the members
+ * of every super-column, and rounds 1 + 2 R, 2 + 2 R are the two rounds of the meetings (S, T)
+ * of round R of the super-columns' own tournament: (2 S, 2 T), (2 S + 1, 2 T + 1), then
+ * (2 S, 2 T + 1), (2 S + 1, 2 T); pairs 2 K and 2 K + 1 of both rounds belong to meeting K.
+ * Host only, no device work; SHAMPOO_ERR_NULL / SHAMPOO_ERR_SHAPE on bad arguments. */
 int shampoo_jacobi_pair(int32_t s, int32_t halves, int32_t round, int32_t k, int32_t *p, int32_t *q);
 
 /* Static, NUL-terminated description of a return code. */

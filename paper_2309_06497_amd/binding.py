@@ -366,7 +366,7 @@ def shampoo_root_inverse_static(a, epsilon, r, x, lam=None, failed=None):
 def shampoo_jacobi_pair(s, halves, rnd, k):
     """(p, q), p < q: pair k of round rnd of the eigensolver's sweep over s indices (host only)."""
     p, q = ctypes.c_int32(), ctypes.c_int32()
-    _check(lib().shampoo_jacobi_pair(s, int(bool(halves)), rnd, k, ctypes.byref(p), ctypes.byref(q)))
+    _check(lib().shampoo_jacobi_pair(s, int(halves), rnd, k, ctypes.byref(p), ctypes.byref(q)))
     return p.value, q.value
 
 

@@ -13,9 +13,14 @@
 //  * n > 128: two-sided block Jacobi.  The matrix (padded to a multiple of 64)
 //    is cut into 32-wide block columns; a round pairs them up, each 64 x 64
 //    pivot is diagonalised by the LDS solver above, and the 64 x 64 rotation
-//    blocks are applied to A (both sides, A_kl <- J_k^T A_kl J_l, float64 MFMA)
-//    and to Q^T (rows, float32 MFMA).  The reconstruction Q f(Lambda) Q^T reuses
-//    the batched SYRK kernel.
+//    blocks are applied to A (both sides, A_kl <- J_k^T A_kl J_l; float32 MFMA in
+//    the first sweeps of a cold solve, float64 MFMA afterwards) and to the rows of
+//    Q^T.  When the number of block columns is a multiple of 4 the rounds are
+//    ordered so that two consecutive ones stay inside four block columns
+//    (grouped_pair); Q^T then takes both in one pass over memory, on the fp16
+//    matrix cores with operands split into two fp16 terms, and the pivots of all
+//    rounds but the first of a sweep rotate only the pairs across their two block
+//    columns.  The reconstruction Q f(Lambda) Q^T reuses the batched SYRK kernel.
 //
 // Rotations are applied in the form x' = x - s (y + tau x), y' = y + s (x - tau y)
 // with tau = s / (1 + c): for small angles the cosine rounds to 1 and the plain
@@ -100,6 +105,23 @@ __device__ __forceinline__ int halves_round(int s, int i, int j) {
   return h + ((il == h - 1) ? jl : ((il + jl) * (h >> 1)) % (h - 1));
 }
 
+// The rounds of the block solver over `cnt` block columns.  group == 1: the plain tournament.
+// group == 2 (cnt a multiple of 4): block columns 2 S and 2 S + 1 form a super-column; round 0
+// pairs the two members of every super-column, and the super-columns then play a tournament of
+// their own in which every meeting (S, T) takes two consecutive rounds, 1 + 2 R and 2 + 2 R:
+// first (2 S, 2 T) and (2 S + 1, 2 T + 1), then (2 S, 2 T + 1) and (2 S + 1, 2 T).  Every pair of
+// block columns still meets exactly once per sweep, and the two rounds of a meeting stay inside
+// four block columns, so the rows of Q^T they rotate can take both rotations in one pass over
+// memory.  Pivot k of a round belongs to meeting k / 2.
+__device__ __host__ __forceinline__ void grouped_pair(int cnt, int group, int r, int k, int &p, int &q) {
+  if (group == 1) { rr_pair(cnt, r, k, p, q); return; }
+  if (r == 0) { p = 2 * k; q = 2 * k + 1; return; }
+  const int R = (r - 1) >> 1, sub = (r - 1) & 1, i = k & 1;
+  int S, T;
+  rr_pair(cnt >> 1, R, k >> 1, S, T);
+  p = 2 * S + i; q = 2 * T + (i ^ sub);
+}
+
 // 1 / sqrt(x) and 1 / x for finite x > 0 (x != 0 for the reciprocal) to float64 accuracy:
 // hardware estimate + three Newton steps (each squares the relative error)
 __device__ __forceinline__ double rsqrt_newton(double x) {
@@ -150,7 +172,8 @@ __device__ __forceinline__ int tri(int i, int j) {
 // T: float64, or float32 for the first sweeps of the mixed-precision block solver.
 template <bool SQUARE, int NT, bool HALVES = false, typename T = double>
 __device__ int jacobi_sweeps(T *At, float *Js, int s, const int LD, const int LDA, int max_sweeps,
-                             T tol_rel, T tol_abs, JacScratch *sc) {
+                             T tol_rel, T tol_abs, JacScratch *sc, int n_rounds = -1) {
+  if (n_rounds < 0) n_rounds = s - 1;
   const int tid = threadIdx.x;
   const int half = s >> 1;
   auto at = [LDA](int i, int j) { return SQUARE ? i * LDA + j : tri(i, j); };
@@ -193,12 +216,12 @@ __device__ int jacobi_sweeps(T *At, float *Js, int s, const int LD, const int LD
         const T aij = jac_abs(At[at(i, j)]);
         if (aij > tol_abs && aij * aij > tol_rel * tol_rel * jac_abs(At[at(i, i)] * At[at(j, j)])) {
           const int r = HALVES ? halves_round(s, i, j) : (i == s - 1) ? j : ((i + j) * half) % (s - 1);
-          atomicOr(&sc->rounds[r >> 5], 1u << (r & 31));
+          if (r < n_rounds) atomicOr(&sc->rounds[r >> 5], 1u << (r & 31));
         }
       }
     }
     __syncthreads();
-    for (int r = 0; r < s - 1; ++r) {
+    for (int r = 0; r < n_rounds; ++r) {
       if (!((sc->rounds[r >> 5] >> (r & 31)) & 1u)) continue;      // uniform
       if (tid < half) {
         int p, q;
@@ -442,7 +465,10 @@ inline size_t rootinv_small_lds_bytes(int n) {
 //   W  [np][np] float64  the matrix being diagonalised (padding: zero, decoupled);
 //                        kept exactly symmetric (mirrored writes)
 //   Qt [np][np] float32  accumulated rotations, transposed (rows are eigenvectors)
-//   J  [np/64][64][64] float32 rotation blocks of the current round
+//   J  [np/64][64][64] float32 rotation blocks of the current round, and the same
+//      blocks transposed as two fp16 terms (for the update of Q^T on the fp16 matrix
+//      cores); two rounds' worth, because the two rounds of a meeting of
+//      super-columns are applied to Q^T together
 // W is float64 for the same reason as in the LDS solver: the update
 // A_kl <- J_k^T A_kl J_l runs on the float64 matrix cores (v_mfma_f64_16x16x4_f64),
 // so eigenvalues far below 2^-24 lambda_max survive the ~400 updates of a solve.
@@ -455,8 +481,14 @@ struct BlockJacArgs {
   double *w;
   float *w32;            // the float32 copy of W that the first sweeps of a cold solve work on (same layout)
   float *qt;
-  float *jbuf;
+  float *jbuf;           // [batch][np/64][64][64]: rotation blocks of the current round
   int32_t *ident;        // [batch][np/64]: pivot of the current round needed no rotation
+  int32_t *ident2;       // the flags of the second round of a meeting of two super-columns (group == 2; read by
+                         // the two-round Q^T update only, which finds the first round's in ident)
+  uint16_t *jt16;        // [batch][np/64][2][64][64] fp16: J^T of the current round as two fp16 terms of 2^13 J^T
+  uint16_t *jt16_2;      // ... and of the second round of a meeting
+  int32_t group;         // 1 or 2: see grouped_pair
+  int32_t cross_only;    // the pivots rotate only pairs across their two block columns
   int32_t *rot;          // [batch][JAC_OUTER_SWEEPS]: pivots that rotated, per outer sweep
   const float *dmax;     // [batch]
   const int32_t *failed; // [batch]
@@ -470,6 +502,8 @@ struct BlockJacArgs {
   __device__ __forceinline__ bool converged(int b) const {
     return sweep > phase_start && rot[b * JAC_OUTER_SWEEPS + sweep - 1] == 0;
   }
+  // block columns (p < q) of pivot k of the current round
+  __device__ __forceinline__ void pair(int k, int &p, int &q) const { grouped_pair(np / JAC_NB, group, round, k, p, q); }
 };
 
 struct BlockInitArgs {
@@ -515,6 +549,19 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
   if (i == 0 && threadIdx.x < JAC_OUTER_SWEEPS) g.rot[b * JAC_OUTER_SWEEPS + threadIdx.x] = 0;
 }
 
+typedef _Float16 jac_f16x8 __attribute__((ext_vector_type(8)));
+constexpr float JAC_F16_SCALE = 8192.f;                  // 2^13
+
+__device__ __forceinline__ uint32_t pack_f16x2(_Float16 a, _Float16 b) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+}
+// the two fp16 terms of JAC_F16_SCALE * x
+__device__ __forceinline__ void split_scaled(float x, _Float16 &h, _Float16 &l) {
+  const float sx = x * JAC_F16_SCALE;
+  h = (_Float16)sx;
+  l = (_Float16)(sx - (float)h);
+}
+
 constexpr int PIV_LD = JAC_PIV + 1;
 
 // Only the lower triangle of W is kept up to date, as 32 x 32 sub-blocks (a, b)
@@ -533,7 +580,7 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
   if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB;
   int pb, qb;
-  rr_pair(nblk, g.round, pair, pb, qb);   // pb < qb
+  g.pair(pair, pb, qb);   // pb < qb
   const T *w = (sizeof(T) == 8 ? reinterpret_cast<const T *>(g.w) : reinterpret_cast<const T *>(g.w32)) + (int64_t)b * np * np;
   const int tid = threadIdx.x;
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) {
@@ -548,7 +595,7 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
   __syncthreads();
   const double dm = (double)g.dmax[b];
   const int any = jacobi_sweeps<true, JAC_PIV_THREADS, true, T>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, (T)g.tol_rel,
-                                         (T)(g.tol_abs_rel * dm), &sc);
+                                         (T)(g.tol_abs_rel * dm), &sc, g.cross_only ? JAC_PIV / 2 : -1);
   __syncthreads();
   if (tid == 0) {
     g.ident[b * (nblk / 2) + pair] = any ? 0 : 1;
@@ -558,6 +605,25 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
   // unconditionally
   float *jout = g.jbuf + ((int64_t)b * (nblk / 2) + pair) * JAC_PIV * JAC_PIV;
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) jout[i * JAC_PIV + (tid & 63)] = Js[i * PIV_LD + (tid & 63)];
+  // ... and transposed, as the two fp16 terms of 2^13 J^T, for the update of Q^T on the fp16
+  // matrix cores: thread -> row tid / 4 of J^T, 16 consecutive k
+  static_assert(JAC_PIV_THREADS == 4 * JAC_PIV, "one row of J^T per four threads");
+  {
+    const int i = tid >> 2, k0 = (tid & 3) * 16;
+    uint32_t hw[8], lw[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      _Float16 h0, l0, h1, l1;
+      split_scaled(Js[(k0 + 2 * e) * PIV_LD + i], h0, l0);
+      split_scaled(Js[(k0 + 2 * e + 1) * PIV_LD + i], h1, l1);
+      hw[e] = pack_f16x2(h0, h1); lw[e] = pack_f16x2(l0, l1);
+    }
+    uint16_t *jt = g.jt16 + (((int64_t)b * (nblk / 2) + pair) * 2 * JAC_PIV + i) * JAC_PIV + k0;
+    *reinterpret_cast<uint4 *>(jt) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+    *reinterpret_cast<uint4 *>(jt + 8) = make_uint4(hw[4], hw[5], hw[6], hw[7]);
+    *reinterpret_cast<uint4 *>(jt + JAC_PIV * JAC_PIV) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+    *reinterpret_cast<uint4 *>(jt + JAC_PIV * JAC_PIV + 8) = make_uint4(lw[4], lw[5], lw[6], lw[7]);
+  }
 }
 
 constexpr int APP_LD = JAC_PIV + 4;
@@ -683,7 +749,7 @@ __device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int
   if (l >= l_end) return;
   double *w = g.w + (int64_t)b * np * np;
   int pk, qk;
-  rr_pair(nblk, g.round, k, pk, qk);
+  g.pair(k, pk, qk);
 
   const int li = lane & 15, lg = lane >> 4;
   float jk[16];                   // J_k[4 q + lg][16 wave + li]
@@ -697,7 +763,7 @@ __device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int
   const int jr = tid >> 4, jc4 = (tid & 15) * 4;
   auto fetch = [&](int lx) {
     int pl, ql;
-    rr_pair(nblk, g.round, lx, pl, ql);
+    g.pair(lx, pl, ql);
     sub_fetch(w, np, pk, pl, tid, wt[0]);
     sub_fetch(w, np, pk, ql, tid, wt[1]);
     sub_fetch(w, np, qk, pl, tid, wt[2]);
@@ -712,7 +778,7 @@ __device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int
   for (bool first = true; l < l_end; first = false) {
     const int ln = next_active(l + 1);   // l_end if this is the last one
     int pl, ql;
-    rr_pair(nblk, g.round, l, pl, ql);
+    g.pair(l, pl, ql);
     if (!first) __syncthreads();   // every wavefront is done with X and J_l of the pair-block before
     sub_stash(X, pk, pl, 0, 0, tid, wt[0]);
     sub_stash(X, pk, ql, 0, JAC_NB, tid, wt[1]);
@@ -844,7 +910,7 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
   const bool idk = ident[k] != 0;
   float *w = g.w32 + (int64_t)b * np * np;
   int pk, qk;
-  rr_pair(nblk, g.round, k, pk, qk);
+  g.pair(k, pk, qk);
   bool have_jk = false;
   // One 32 x 32 sub-block on its way from W to the 64 x 64 LDS tile, in two halves (global ->
   // register, register -> LDS) so that the loads of the next pair-block are in flight while
@@ -877,7 +943,7 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
   const int jr = tid >> 4, jc4 = (tid & 15) * 4;
   auto fetch = [&](int lx) {
     int pl, ql;
-    rr_pair(nblk, g.round, lx, pl, ql);
+    g.pair(lx, pl, ql);
     wx[0] = sub_fetch32(pk, pl); wx[1] = sub_fetch32(pk, ql); wx[2] = sub_fetch32(qk, pl); wx[3] = sub_fetch32(qk, ql);
     const bool idl = ident[lx] != 0;
 #pragma unroll
@@ -893,7 +959,7 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
   while (l < l_end) {
     const int ln = next_active(l + 1);                   // l_end if this is the last one
     int pl, ql;
-    rr_pair(nblk, g.round, l, pl, ql);
+    g.pair(l, pl, ql);
     __syncthreads();                                     // the tile of the pair-block before is done with
     if (!have_jk) { load_rotation(Jk, jb, k, idk, tid); have_jk = true; }
 #pragma unroll
@@ -981,7 +1047,7 @@ __device__ __forceinline__ void blockjac_apply_q_body(const BlockJacArgs &g, int
   if (g.ident[b * hp + k]) return;
   float *qt = g.qt + (int64_t)b * np * np;
   int pk, qk;
-  rr_pair(nblk, g.round, k, pk, qk);
+  g.pair(k, pk, qk);
   const int r = tid >> 4, c4 = (tid & 15) * 4;
   const int t0 = grp * APPQ_TILES, t1 = min(t0 + APPQ_TILES, ctiles);
   float4 pre0, pre1, pre2, pre3;
@@ -1022,6 +1088,165 @@ __device__ __forceinline__ void blockjac_apply_q_body(const BlockJacArgs &g, int
   }
 #undef APPQ_FETCH
 #undef APPQ_STASH
+}
+
+// The Q^T update of both rounds of a meeting of two super-columns (group == 2) in one pass:
+// the 128 rows of the four block columns a < b < c < d involved take J(a, c), J(b, d) of the
+// first round and then J(a, d), J(b, c) of the second, and are read and written once.
+//
+// On the float32 matrix cores the update of one round already takes as long as its memory
+// traffic, so one pass for two rounds would gain nothing there.  The products therefore run on
+// the fp16 matrix cores with each float32 operand split into two fp16 terms (x 2^13 = h + l up
+// to 2^-22 |x|: both operands are bounded by 1, rows and columns of orthogonal matrices) and
+// three products per result, J_h X_h + J_h X_l + J_l X_h, accumulated in float32: 3 / 16 of the
+// float32 matrix-core time, at an error of 2^-22 per update instead of 2^-24.  Q^T itself stays
+// float32 in memory; the rotation blocks arrive split (jt16, written by the pivots).
+//
+// g.round is the first of the two rounds; g.jt16 / g.ident belong to it, g.jt16_2 / g.ident2 to
+// the second.  256 threads: wavefront (piv, wi) takes pivot piv of each round and produces the
+// 32 rows of its first (wi = 0) or second (wi = 1) block column, 64 columns wide.
+// v_mfma_f32_32x32x16_f16 takes 8 consecutive k of row lane % 32 per lane, k block lane / 32, for
+// both operands, and leaves D[8 q + 4 (lane / 32) + e][lane % 32] in element 4 q + e.  The rotation
+// blocks are the A operands, straight from memory into registers (jt16 is J^T, k contiguous); the
+// tile of Q^T is the B operand and is staged in LDS column by column ([column][row], both
+// planes), which a thread fills from the 8 rows x 4 columns it loaded.  Between the rounds the
+// accumulators go back to LDS the same way (a lane holds 4 consecutive rows of one column).
+// APPQ_TILES tiles of 64 columns per workgroup, the next one on its way into registers
+// meanwhile.  grid ((np / 128) * ceil(np / 256), batch).
+constexpr int APPQ2_THREADS = 256;
+constexpr int APPQ2_ROW = 2 * JAC_PIV * 2 + 16;          // bytes of one column of the staged tile: 128 rows + padding
+constexpr int APPQ2_PLANE = JAC_PIV * APPQ2_ROW;         // one plane: 64 columns
+
+__global__ __launch_bounds__(APPQ2_THREADS, 2) void blockjac_apply_q2_kernel(const BlockJacArgs g) {
+  __shared__ __align__(16) unsigned char Xs[2 * APPQ2_PLANE];   // plane h, plane l
+  const int b = blockIdx.y;
+  if (g.failed[b]) return;
+  if (g.converged(b)) return;
+  const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2, ctiles = np / JAC_PIV;
+  const int groups = (ctiles + APPQ_TILES - 1) / APPQ_TILES;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int piv = wave >> 1, wi = wave & 1;
+  const int K = blockIdx.x / groups, grp = blockIdx.x - K * groups;
+  const bool ida0 = g.ident[b * hp + 2 * K] != 0, idb0 = g.ident[b * hp + 2 * K + 1] != 0;
+  const bool ida1 = g.ident2[b * hp + 2 * K] != 0, idb1 = g.ident2[b * hp + 2 * K + 1] != 0;
+  if (ida0 && idb0 && ida1 && idb1) return;
+  const bool id0 = piv ? idb0 : ida0, id1 = piv ? idb1 : ida1;    // this wavefront's pivot, first and second round
+  float *qt = g.qt + (int64_t)b * np * np;
+  int blk_a, blk_c;               // a, c; b = a + 1, d = c + 1
+  grouped_pair(nblk, 2, g.round, 2 * K, blk_a, blk_c);
+  // Blocks of the staged tile: 0 = a, 1 = b, 2 = c, 3 = d.  The first round pairs block piv with
+  // 2 + piv, the second with 3 - piv; this wavefront produces block out0 in the first round and
+  // out1 in the second.
+  const int xq0 = 2 + piv, xq1 = 3 - piv;
+  const int out0 = wi ? xq0 : piv, out1 = wi ? xq1 : piv;
+  // the pivot of the second round that block out0 belongs to: a, d -> 0; b, c -> 1
+  const bool out0_final = (out0 == 0 || out0 == 3) ? ida1 : idb1;   // nobody touches it again: this wavefront stores it
+  // A operands: J^T rows 32 wi + lane % 32, k = 16 s + 8 (lane / 32) .. + 7, both planes, both rounds
+  uint4 ja[2][2][4];              // [round][plane][k step]
+  {
+    const int row = 32 * wi + (lane & 31), kb = lane >> 5;
+    const uint16_t *j0 = g.jt16 + ((int64_t)b * hp + 2 * K + piv) * 2 * JAC_PIV * JAC_PIV + row * JAC_PIV + 8 * kb;
+    const uint16_t *j1 = g.jt16_2 + ((int64_t)b * hp + 2 * K + piv) * 2 * JAC_PIV * JAC_PIV + row * JAC_PIV + 8 * kb;
+#pragma unroll
+    for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        ja[0][pl][st] = *reinterpret_cast<const uint4 *>(j0 + pl * JAC_PIV * JAC_PIV + 16 * st);
+        ja[1][pl][st] = *reinterpret_cast<const uint4 *>(j1 + pl * JAC_PIV * JAC_PIV + 16 * st);
+      }
+  }
+  // thread -> rows 8 rg .. 8 rg + 7 of the 128, columns c4 .. c4 + 3 of the tile
+  const int rg = tid >> 4, c4 = (tid & 15) * 4;
+  const int t0 = grp * APPQ_TILES, t1 = min(t0 + APPQ_TILES, ctiles);
+  // offsets inside one matrix fit 32 bits (np <= 16384), which keeps addresses at one register each
+  const int src = (((rg >> 2) < 2 ? blk_a + (rg >> 2) : blk_c + (rg >> 2) - 2) * JAC_NB + 8 * (rg & 3)) * np + c4;
+  float4 pre[8];
+  auto fetch = [&](int ct) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pre[e] = *reinterpret_cast<const float4 *>(qt + (src + e * np + ct * JAC_PIV));
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      _Float16 h[8], l[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = c == 0 ? pre[e].x : c == 1 ? pre[e].y : c == 2 ? pre[e].z : pre[e].w;
+        split_scaled(x, h[e], l[e]);
+      }
+      unsigned char *dst = Xs + (c4 + c) * APPQ2_ROW + 16 * rg;
+      *reinterpret_cast<uint4 *>(dst) = make_uint4(pack_f16x2(h[0], h[1]), pack_f16x2(h[2], h[3]), pack_f16x2(h[4], h[5]), pack_f16x2(h[6], h[7]));
+      *reinterpret_cast<uint4 *>(dst + APPQ2_PLANE) = make_uint4(pack_f16x2(l[0], l[1]), pack_f16x2(l[2], l[3]), pack_f16x2(l[4], l[5]), pack_f16x2(l[6], l[7]));
+    }
+  };
+  // one round of this wavefront's pivot: acc[wj] = J^T (rows of blocks xp, xq), 32 rows x 2 x 32 columns
+  auto rotate = [&](const uint4 (&a)[2][4], int xq, floatx16 (&acc)[2]) {
+#pragma unroll
+    for (int wj = 0; wj < 2; ++wj) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[wj][v] = 0.f;
+      const unsigned char *col = Xs + (32 * wj + (lane & 31)) * APPQ2_ROW + 16 * (lane >> 5);
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        const unsigned char *p = col + (st < 2 ? piv : xq) * (JAC_NB * 2) + (st & 1) * 32;
+        const jac_f16x8 xh = __builtin_bit_cast(jac_f16x8, *reinterpret_cast<const uint4 *>(p));
+        const jac_f16x8 xl = __builtin_bit_cast(jac_f16x8, *reinterpret_cast<const uint4 *>(p + APPQ2_PLANE));
+        const jac_f16x8 jh = __builtin_bit_cast(jac_f16x8, a[0][st]), jl = __builtin_bit_cast(jac_f16x8, a[1][st]);
+        acc[wj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(jl, xh, acc[wj], 0, 0, 0);
+        acc[wj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(jh, xl, acc[wj], 0, 0, 0);
+        acc[wj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(jh, xh, acc[wj], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);     // or every operand read of the round is hoisted to its top, which costs a workgroup per CU in registers
+      }
+    }
+  };
+  constexpr float UNSCALE = 1.f / (JAC_F16_SCALE * JAC_F16_SCALE);
+  // rows of block `blk` (0 .. 3) of the tile at columns ct: the accumulators, unscaled, to Q^T
+  auto store = [&](const floatx16 (&acc)[2], int blk, int ct) {
+    int dst = ((blk < 2 ? blk_a + blk : blk_c + blk - 2) * JAC_NB + 4 * (lane >> 5)) * np + ct * JAC_PIV + (lane & 31);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        qt[dst] = acc[0][4 * q + e] * UNSCALE;
+        qt[dst + 32] = acc[1][4 * q + e] * UNSCALE;
+        dst += np;
+      }
+      dst += 4 * np;
+    }
+  };
+  fetch(t0);
+  for (int t = t0; t < t1; ++t) {
+    stage();
+    __syncthreads();
+    if (t + 1 < t1) fetch(t + 1);
+    floatx16 acc[2];
+    if (!id0) rotate(ja[0], xq0, acc);
+    __syncthreads();               // every wavefront has read what it needs of the tile
+    if (!id0) {
+      if (out0_final) store(acc, out0, t);
+      else {
+        // back into the tile for the second round: element 4 q + e is row 8 q + 4 (lane / 32) + e
+#pragma unroll
+        for (int wj = 0; wj < 2; ++wj) {
+          unsigned char *dst = Xs + (32 * wj + (lane & 31)) * APPQ2_ROW + (out0 * JAC_NB + 4 * (lane >> 5)) * 2;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            _Float16 h[4], l[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) split_scaled(acc[wj][4 * q + e] * UNSCALE, h[e], l[e]);
+            *reinterpret_cast<uint2 *>(dst + 16 * q) = make_uint2(pack_f16x2(h[0], h[1]), pack_f16x2(h[2], h[3]));
+            *reinterpret_cast<uint2 *>(dst + 16 * q + APPQ2_PLANE) = make_uint2(pack_f16x2(l[0], l[1]), pack_f16x2(l[2], l[3]));
+          }
+        }
+      }
+    }
+    __syncthreads();
+    if (!id1) {
+      rotate(ja[1], xq1, acc);
+      store(acc, out1, t);
+    }
+    __syncthreads();               // the tile is free for the next one
+  }
 }
 
 // The three updates as kernels of their own (one launch for W and Q^T together measured 3 %

@@ -361,7 +361,7 @@ constexpr int CONGRUENCE_PANEL = 256;   // columns of T = A Qt^T formed at a tim
 struct EigLayout {
   int32_t np = 0, chunk = 0;
   bool warm = false;       // block solver: room for the float64 panel of the congruence W = Qt A Qt^T
-  size_t off_w = 0, off_qt = 0, off_j = 0, off_ident = 0, off_rot = 0, off_dmax = 0, off_failed = 0, off_f = 0, off_t = 0;
+  size_t off_w = 0, off_qt = 0, off_j = 0, off_ident = 0, off_j16 = 0, off_rot = 0, off_dmax = 0, off_failed = 0, off_f = 0, off_t = 0;
   size_t bytes = 0;
 };
 
@@ -372,8 +372,11 @@ void eig_offsets(EigLayout &e) {
   e.off_w = off; off += align_up(2 * mat * e.chunk);
   e.off_qt = off; off += align_up(mat * e.chunk);
   const int hp = e.np / JAC_PIV;
-  e.off_j = off; off += align_up((size_t)e.chunk * hp * JAC_PIV * JAC_PIV * sizeof(float));
-  e.off_ident = off; off += align_up((size_t)e.chunk * hp * sizeof(int32_t));
+  // rotation blocks and flags of two rounds (the Q^T update of a meeting of two super-columns
+  // reads both): [2][chunk][hp]
+  e.off_j = off; off += align_up(2 * (size_t)e.chunk * hp * JAC_PIV * JAC_PIV * sizeof(float));
+  e.off_ident = off; off += align_up(2 * (size_t)e.chunk * hp * sizeof(int32_t));
+  e.off_j16 = off; off += align_up(2 * (size_t)e.chunk * hp * 2 * JAC_PIV * JAC_PIV * sizeof(uint16_t));   // the same blocks, transposed, as two fp16 planes
   e.off_rot = off; off += align_up((size_t)e.chunk * JAC_OUTER_SWEEPS * sizeof(int32_t));
   e.off_dmax = off; off += align_up((size_t)e.chunk * sizeof(float));
   e.off_failed = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
@@ -486,6 +489,7 @@ struct BlockSolve {
   bool warm = false, mixed = false;
   double *w = nullptr; float *w32 = nullptr, *qt = nullptr, *fv = nullptr;
   int32_t *rot = nullptr, *failed = nullptr;
+  float *jslot[2] = {nullptr, nullptr}; int32_t *islot[2] = {nullptr, nullptr}; uint16_t *hslot[2] = {nullptr, nullptr};
   BlockJacArgs ja{};
 
   int begin() {
@@ -493,8 +497,11 @@ struct BlockSolve {
     w = reinterpret_cast<double *>(ws + e->off_w) + (int64_t)slot0 * np * np;
     qt = warm_in.qt ? warm_in.qt : reinterpret_cast<float *>(ws + e->off_qt) + (int64_t)slot0 * np * np;
     warm = warm_in.qt && warm_in.start && e->warm;
-    float *jbuf = reinterpret_cast<float *>(ws + e->off_j) + (int64_t)slot0 * hp * JAC_PIV * JAC_PIV;
-    int32_t *ident = reinterpret_cast<int32_t *>(ws + e->off_ident) + (int64_t)slot0 * hp;
+    for (int k = 0; k < 2; ++k) {
+      jslot[k] = reinterpret_cast<float *>(ws + e->off_j) + ((int64_t)k * e->chunk + slot0) * hp * JAC_PIV * JAC_PIV;
+      islot[k] = reinterpret_cast<int32_t *>(ws + e->off_ident) + ((int64_t)k * e->chunk + slot0) * hp;
+      hslot[k] = reinterpret_cast<uint16_t *>(ws + e->off_j16) + ((int64_t)k * e->chunk + slot0) * hp * 2 * JAC_PIV * JAC_PIV;
+    }
     rot = reinterpret_cast<int32_t *>(ws + e->off_rot) + (int64_t)slot0 * JAC_OUTER_SWEEPS;
     float *dmax = reinterpret_cast<float *>(ws + e->off_dmax) + slot0;
     failed = reinterpret_cast<int32_t *>(ws + e->off_failed) + slot0;
@@ -520,8 +527,10 @@ struct BlockSolve {
       hipLaunchKernelGGL(blockjac_init_kernel<double>, dim3(np, cnt), dim3(256), 0, s, ia);
     }
     HIP_TRY(hipGetLastError());
-    ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jbuf; ja.ident = ident; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
+    ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
+    ja.ident2 = islot[1]; ja.jt16 = hslot[0]; ja.jt16_2 = hslot[1];
     ja.np = np;
+    ja.group = (nblk % 4 == 0) ? 2 : 1;
     ja.inner_sweeps = JAC_INNER_SWEEPS;
     sw = 0;
     return SHAMPOO_OK;
@@ -539,7 +548,15 @@ struct BlockSolve {
       ja.phase_start = f32_sweeps(); ja.tol_rel = JAC_BLOCK_TOL_REL; ja.tol_abs_rel = JAC_SMALL_TOL_ABS;
     }
     for (int rd = 0; rd < nblk - 1; ++rd) {
+      // group == 2: rounds 1 + 2 R and 2 + 2 R are the two rounds of one meeting of super-columns;
+      // the second keeps its rotation blocks apart, and Q^T takes both after it
+      const int sub = (ja.group == 2 && rd > 0) ? (rd - 1) & 1 : 0;
       ja.round = rd; ja.sweep = sw;
+      ja.jbuf = jslot[sub]; ja.ident = islot[sub]; ja.jt16 = hslot[sub];
+      // group == 2: the pairs inside a block column are rotated by the pivots of round 0 only (once
+      // per sweep, like every other pair); the pivots of the other rounds keep to the pairs across
+      // their two block columns, which halves their rounds
+      ja.cross_only = (ja.group == 2 && rd > 0) ? 1 : 0;
       if (f32) {
         hipLaunchKernelGGL(blockjac_pivot_kernel<float>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
         hipLaunchKernelGGL(blockjac_apply_w32_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
@@ -547,7 +564,12 @@ struct BlockSolve {
         hipLaunchKernelGGL(blockjac_pivot_kernel<double>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
         hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
       }
-      hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(q_blocks, cnt), dim3(JAC_THREADS), 0, s, ja);
+      if (ja.group == 1 || rd == 0) {
+        hipLaunchKernelGGL(blockjac_apply_q_kernel, dim3(q_blocks, cnt), dim3(JAC_THREADS), 0, s, ja);
+      } else if (sub == 1) {
+        ja.round = rd - 1; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.jt16 = hslot[0];
+        hipLaunchKernelGGL(blockjac_apply_q2_kernel, dim3(q_blocks / 2, cnt), dim3(APPQ2_THREADS), 0, s, ja);
+      }
     }
     HIP_TRY(hipGetLastError());
     ++sw;
@@ -2016,9 +2038,12 @@ int shampoo_root_inverse_newton(const float *a, int32_t n, int32_t batch, float 
 int shampoo_jacobi_pair(int32_t s, int32_t halves, int32_t round, int32_t k, int32_t *p, int32_t *q) {
   if (!p || !q) return SHAMPOO_ERR_NULL;
   if (s < 2 || (s & 1) || round < 0 || round >= s - 1 || k < 0 || k >= s / 2) return SHAMPOO_ERR_SHAPE;
-  if (halves && (s < 4 || ((s / 2) & (s / 2 - 1)) != 0)) return SHAMPOO_ERR_SHAPE;
+  if (halves == 1 && (s < 4 || ((s / 2) & (s / 2 - 1)) != 0)) return SHAMPOO_ERR_SHAPE;
+  if (halves == 2 && s % 4 != 0) return SHAMPOO_ERR_SHAPE;
+  if (halves < 0 || halves > 2) return SHAMPOO_ERR_SHAPE;
   int pp, qq;
-  if (halves) halves_pair(s, round, k, pp, qq); else rr_pair(s, round, k, pp, qq);
+  if (halves == 2) grouped_pair(s, 2, round, k, pp, qq);
+  else if (halves) halves_pair(s, round, k, pp, qq); else rr_pair(s, round, k, pp, qq);
   *p = pp; *q = qq;
   return SHAMPOO_OK;
 }

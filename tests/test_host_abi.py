@@ -197,7 +197,8 @@ def test_planner_merges_small_dimensions_and_blocks_tensors():
     assert B.shampoo_workspace_bytes(cfg_for([(64, 64, 9)], 128)) > 2 * 4 * (64 * 64 * 2 + 81)
 
 
-@pytest.mark.parametrize("s,halves", [(2, 0), (6, 0), (64, 0), (128, 0), (4, 1), (16, 1), (64, 1)])
+@pytest.mark.parametrize("s,halves", [(2, 0), (6, 0), (64, 0), (128, 0), (4, 1), (16, 1), (64, 1),
+                                      (4, 2), (8, 2), (12, 2), (32, 2), (64, 2), (256, 2)])
 def test_jacobi_pair_schedule_is_a_tournament(s, halves):
     """Every round of the eigensolver's sweep is a perfect matching and the s - 1 rounds meet
     every pair once; in the pivot order the first s / 2 rounds pair across the two halves."""
@@ -211,13 +212,32 @@ def test_jacobi_pair_schedule_is_a_tournament(s, halves):
             used.update((p, q))
             assert (p, q) not in seen
             seen.add((p, q))
-            if halves:
+            if halves == 1:
                 assert (p < s // 2 <= q) == (r < s // 2)
         assert len(used) == s
     assert len(seen) == s * (s - 1) // 2
 
 
+@pytest.mark.parametrize("s", [4, 12, 32, 256])
+def test_block_column_schedule_keeps_two_rounds_inside_four_columns(s):
+    """The block-column order of the blocked solver (halves = 2): round 0 pairs the members of
+    each super-column (2 S, 2 S + 1); pairs 2 K and 2 K + 1 of rounds 1 + 2 R and 2 + 2 R touch
+    the same four block columns, two whole super-columns, in the order the two-round update of
+    the eigenvector rows assumes: (a, c), (b, d), then (a, d), (b, c) with a < b < c < d."""
+    for k in range(s // 2):
+        assert B.shampoo_jacobi_pair(s, 2, 0, k) == (2 * k, 2 * k + 1)
+    for R in range(s // 2 - 1):
+        for K in range(s // 4):
+            first = [B.shampoo_jacobi_pair(s, 2, 1 + 2 * R, 2 * K + i) for i in range(2)]
+            second = [B.shampoo_jacobi_pair(s, 2, 2 + 2 * R, 2 * K + i) for i in range(2)]
+            a, c = first[0]
+            assert a % 2 == 0 and c % 2 == 0 and a < c
+            assert first[1] == (a + 1, c + 1)
+            assert second == [(a, c + 1), (a + 1, c)]
+
+
 def test_jacobi_pair_rejects_bad_arguments():
-    for args in [(3, 0, 0, 0), (64, 0, 63, 0), (64, 0, 0, 32), (12, 1, 0, 0), (2, 1, 0, 0), (64, 0, -1, 0)]:
+    for args in [(3, 0, 0, 0), (64, 0, 63, 0), (64, 0, 0, 32), (12, 1, 0, 0), (2, 1, 0, 0), (64, 0, -1, 0),
+                 (6, 2, 0, 0), (64, 3, 0, 0)]:
         with pytest.raises(B.ShampooError):
             B.shampoo_jacobi_pair(*args)
