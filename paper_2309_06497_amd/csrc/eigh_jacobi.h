@@ -490,7 +490,8 @@ struct BlockJacArgs {
   int32_t group;         // 1 or 2: see grouped_pair
   int32_t cross_only;    // the pivots rotate only pairs across their two block columns
   int32_t *rot;          // [batch][JAC_OUTER_SWEEPS]: pivots that rotated, per outer sweep
-  const float *dmax;     // [batch]
+  const float *dmax;     // [batch]: largest |diagonal entry| of the input
+  const float *wbound;   // [batch]: largest absolute row sum of the input (bounds every entry of every orthogonal transform of it)
   const int32_t *failed; // [batch]
   int32_t np;            // padded size
   int32_t round, sweep;
@@ -510,7 +511,7 @@ struct BlockInitArgs {
   const float *a; int64_t a_stride; int32_t n;
   void *w;               // float64, or float32 for a mixed-precision cold solve
   float *qt; int32_t np;
-  float *dmax; int32_t *failed; int32_t *rot;
+  float *dmax; float *wbound; int32_t *failed; int32_t *rot;
   const int32_t *only;   // optional [batch]: a matrix whose entry is 0 is marked 2 in `failed`, which
                          // every later kernel takes as "leave alone" without counting it as a failure
   int32_t warm;          // nonzero: Qt holds the eigenvectors of an earlier solve and stays; W is made
@@ -529,6 +530,7 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
     return;
   }
   int bad = 0;
+  float rowsum = 0.f;
   for (int j = threadIdx.x; j < np; j += 256) {
     double v = 0.0;
     if (i < n && j < n) {
@@ -536,12 +538,24 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
       if (!(fabsf(lo) <= 3.0e38f) || !(fabsf(up) <= 3.0e38f)) bad = 1;
       v = 0.5 * ((double)lo + (double)up);
     }
+    rowsum += fabsf((float)v);
     if (!g.warm) {
       w[j] = (T)v;
       qt[j] = (i == j) ? 1.f : 0.f;
     }
   }
   if (bad) g.failed[b] = 1;
+  {
+    __shared__ float red[4];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) rowsum += __shfl_xor(rowsum, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rowsum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const float rs = red[0] + red[1] + red[2] + red[3];
+      if (rs <= 3.0e38f) atomicMax(reinterpret_cast<int *>(g.wbound + b), __float_as_int(rs));   // rs >= 0: int order = float order
+    }
+  }
   if (i < n && threadIdx.x == 0) {
     const float d = fabsf(a[(int64_t)i * n + i]);
     if (d <= 3.0e38f) atomicMax(reinterpret_cast<int *>(g.dmax + b), __float_as_int(d));  // d >= 0: int order = float order
@@ -686,9 +700,9 @@ __device__ __forceinline__ void sub_stash(double *X, int ra, int cb, int xi, int
 constexpr int APPW_SEG = 4;   // pair-blocks of one block row handled by one workgroup
 
 // number of workgroups per matrix: row k of the lower triangle has k + 1 pair-blocks
-inline int appw_segments(int hp) {
+inline int appw_segments(int hp, int seg = APPW_SEG) {
   int s = 0;
-  for (int k = 0; k < hp; ++k) s += (k + 1 + APPW_SEG - 1) / APPW_SEG;
+  for (int k = 0; k < hp; ++k) s += (k + 1 + seg - 1) / seg;
   return s;
 }
 
@@ -883,130 +897,235 @@ __device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int
 __device__ __forceinline__ floatx16 mfma_64(const float *At, const float *B, int wi, int wj, int lane);
 
 // The same update on the float32 copy of W (the first sweeps of a mixed-precision cold solve):
-// W_kl <- J_k^T W_kl J_l on the float32 matrix cores, both products through LDS.
-// First Y^T = X^T J_k (the result's rows are the k index of the second product, so it goes back
-// to LDS as it comes out of the accumulators, over X), then C = Y J_l.  Wavefront (wi, wj) owns
-// the 32 x 32 quadrant (wi, wj) of each result, which is one stored sub-block of W.  Same grid and
-// walk as blockjac_apply_w_kernel.
+// W_kl <- J_k^T W_kl J_l on the fp16 matrix cores.  These sweeps only have to bring the
+// off-diagonal mass down to float32 level; W is formed anew in float64 afterwards, so what the
+// update needs is float32-like accuracy at fp16 speed: every operand is split into two fp16
+// terms (x s = h + l up to 2^-24 |x s|; s = 2^13 for the rotation blocks, a power of two per
+// matrix for W, from the largest absolute row sum of the input, which bounds every entry of
+// every orthogonal transform of it) and a product is three matrix-core products,
+// a_h b_h + a_h b_l + a_l b_h, accumulated in float32.  W itself stays float32 in memory.
+//
+// v_mfma_f32_16x16x32_f16 takes 8 consecutive k of row (column) lane % 16 per lane, k block
+// lane / 16, for A (B), and leaves D[4 (lane / 16) + e][lane % 16] in element e.  Wavefront w
+// owns rows 16 w .. 16 w + 15 of the result and needs no exchange with the others between the
+// two products:
+//   first   Y^T = X^T J_k as four 16 x 16 tiles a over the columns kk of X, for the wavefront's
+//           16 columns i of J_k: A is X^T, staged in LDS as [kk][m] (both planes; a thread fills
+//           it with 16-byte pieces from the 8 rows x 2 columns, or the 16 consecutive values
+//           of a sub-block kept transposed, that it loaded), B is J_k^T[i][m] straight from
+//           memory (jt16), held in registers for the whole walk.  Element e of tile a is
+//           Y^T[16 a + 4 g + e][16 w + lane % 16], g = lane / 16;
+//   second  C = Y J_l: those elements are, once split again, the A operand of a k step that
+//           covers kk = 16 a + 4 g + e for a = 2 t, 2 t + 1 (a sum may take its terms in any
+//           order as long as both operands agree); B is J_l^T[j][kk] for the same kk, two 8-byte
+//           reads from the LDS copy of jt16 of pair l.
+// The result leaves the registers straight for W; only the pair-block on the diagonal (k = l)
+// goes back through LDS, where it is completed from its lower half so that the diagonal
+// sub-blocks stay exactly symmetric.  Same grid and walk as blockjac_apply_w_kernel.
+typedef _Float16 jac_f16x8v __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+constexpr int W16_XROW = JAC_PIV * 2 + 16;        // bytes of one row of X^T in LDS (64 values of m + padding)
+constexpr int W16_XPLANE = JAC_PIV * W16_XROW;
+constexpr int W16_JROW = JAC_PIV * 2 + 8;         // bytes of one row of J_l^T in LDS
+constexpr int W16_JPLANE = JAC_PIV * W16_JROW;
+constexpr int W16_LDS_BYTES = 2 * W16_XPLANE + 2 * W16_JPLANE;
+constexpr int W16_SEG = 4;                       // pair-blocks of one block row handled by one workgroup (8: 2 % slower)
+static_assert(2 * W16_XPLANE >= JAC_PIV * APP_LD * 4, "the float32 tile of a diagonal pair-block reuses the X^T planes");
+
+// The power of two s with s * bound in [2^13, 2^14) (1 for a bound that is zero or not finite).
+__device__ __forceinline__ float jac_pow2_scale(float bound) {
+  if (!(bound > 0.f) || !(bound < 3.0e38f)) return 1.f;
+  int e;
+  (void)frexpf(bound, &e);               // bound = f 2^e with f in [0.5, 1)
+  return ldexpf(1.f, min(max(14 - e, -100), 100));
+}
+
 __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, int bx, unsigned char *smem) {
-  float *X = reinterpret_cast<float *>(smem);            // [JAC_PIV * APP_LD] W_kl, then Y^T, then (diagonal pair-block) the result
-  float *Jk = X + JAC_PIV * APP_LD;
-  float *Jl = Jk + JAC_PIV * APP_LD;
+  unsigned char *XT = smem;                              // [2 planes][64 kk][W16_XROW]
+  unsigned char *JL = smem + 2 * W16_XPLANE;             // [2 planes][64 j][W16_JROW]
+  float *Ct = reinterpret_cast<float *>(smem);           // [64][APP_LD], diagonal pair-block only
   const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wi = wave >> 1, wj = wave & 1;
+  const int li = lane & 15, lg = lane >> 4;
   const int32_t *ident = g.ident + b * hp;
-  const float *jb = g.jbuf + (int64_t)b * hp * JAC_PIV * JAC_PIV;
+  const uint16_t *jt = g.jt16 + (int64_t)b * hp * 2 * JAC_PIV * JAC_PIV;
   int seg = bx, k = 0;
   for (;;) {
-    const int ns = (k + 1 + APPW_SEG - 1) / APPW_SEG;
+    const int ns = (k + 1 + W16_SEG - 1) / W16_SEG;
     if (seg < ns) break;
     seg -= ns; ++k;
   }
-  const int l_first = seg * APPW_SEG, l_end = min(l_first + APPW_SEG, k + 1);
+  const int l_first = seg * W16_SEG, l_end = min(l_first + W16_SEG, k + 1);
   const bool idk = ident[k] != 0;
-  float *w = g.w32 + (int64_t)b * np * np;
-  int pk, qk;
-  g.pair(k, pk, qk);
-  bool have_jk = false;
-  // One 32 x 32 sub-block on its way from W to the 64 x 64 LDS tile, in two halves (global ->
-  // register, register -> LDS) so that the loads of the next pair-block are in flight while
-  // the current one is multiplied.  Thread -> row tid / 8 of the stored sub-block, 4 columns.
-  const int ii = tid >> 3, j4 = (tid & 7) * 4;
-  auto sub_fetch32 = [&](int ra, int cb) {
-    const bool tr = ra < cb;
-    const int gr0 = (tr ? cb : ra) * JAC_NB, gc0 = (tr ? ra : cb) * JAC_NB;
-    return *reinterpret_cast<const float4 *>(w + (int64_t)(gr0 + ii) * np + gc0 + j4);
-  };
-  auto sub_stash32 = [&](const float4 &v, int ra, int cb, int xi, int xj) {
-    if (ra < cb) {     // kept transposed in W
-      X[(xi + j4) * APP_LD + xj + ii] = v.x; X[(xi + j4 + 1) * APP_LD + xj + ii] = v.y;
-      X[(xi + j4 + 2) * APP_LD + xj + ii] = v.z; X[(xi + j4 + 3) * APP_LD + xj + ii] = v.w;
-    } else {
-      *reinterpret_cast<float4 *>(&X[(xi + ii) * APP_LD + xj + j4]) = v;
-    }
-  };
-  auto sub_store = [&](int ra, int cb, int xi, int xj) {   // ra >= cb: stored as it is
-    *reinterpret_cast<float4 *>(w + (int64_t)(ra * JAC_NB + ii) * np + cb * JAC_NB + j4) =
-        *reinterpret_cast<const float4 *>(&X[(xi + ii) * APP_LD + xj + j4]);
-  };
-  // the pair-blocks of this walk that rotate at all, in order (uniform across the workgroup)
   auto next_active = [&](int from) {
     int l = from;
     while (l < l_end && idk && ident[l] != 0) ++l;
     return l;
   };
-  float4 wx[4], jn[4];      // the next pair-block: its four sub-blocks and its J_l
-  const int jr = tid >> 4, jc4 = (tid & 15) * 4;
+  int l = next_active(l_first);
+  if (l >= l_end) return;
+  float *w = g.w32 + (int64_t)b * np * np;
+  int pk, qk;
+  g.pair(k, pk, qk);
+  const float sw = jac_pow2_scale(g.wbound[b]);
+  const float unscale = 1.f / (sw * JAC_F16_SCALE);
+
+  // B operands of the first product: J_k^T rows 16 wave + li, m = 32 step + 8 lg .. + 7, both planes
+  uint4 jk[2][2];                 // [plane][step]
+#pragma unroll
+  for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+      jk[pl][st] = *reinterpret_cast<const uint4 *>(jt + ((int64_t)(2 * k + pl) * JAC_PIV + 16 * wave + li) * JAC_PIV + 32 * st + 8 * lg);
+
+  // The next pair-block on its way: 16 values of W per thread and 64 bytes of jt16 of pair l.
+  // Sub-block sb = tid / 64 of the tile: (row block, column block) = (pk, pl), (pk, ql), (qk, pl), (qk, ql).
+  const int sb = tid >> 6, t6 = tid & 63;
+  float wa[8], wb[8];
+  uint4 jn0, jn1, jn2, jn3;
   auto fetch = [&](int lx) {
     int pl, ql;
     g.pair(lx, pl, ql);
-    wx[0] = sub_fetch32(pk, pl); wx[1] = sub_fetch32(pk, ql); wx[2] = sub_fetch32(qk, pl); wx[3] = sub_fetch32(qk, ql);
-    const bool idl = ident[lx] != 0;
+    const int ra = (sb & 2) ? qk : pk, cb = (sb & 1) ? ql : pl;
+    if (ra >= cb) {      // kept as it is: rows m = 8 (t6 / 16) .. + 7, columns 2 (t6 % 16), + 1
+      const float *src = w + (int64_t)(ra * JAC_NB + 8 * (t6 >> 4)) * np + cb * JAC_NB + 2 * (t6 & 15);
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const int i = jr + 16 * h;
-      if (idl) jn[h] = make_float4(i == jc4 ? 1.f : 0.f, i == jc4 + 1 ? 1.f : 0.f, i == jc4 + 2 ? 1.f : 0.f, i == jc4 + 3 ? 1.f : 0.f);
-      else jn[h] = *reinterpret_cast<const float4 *>(jb + ((int64_t)lx * JAC_PIV + i) * JAC_PIV + jc4);
+      for (int e = 0; e < 8; ++e) {
+        const float2 v = *reinterpret_cast<const float2 *>(src + (int64_t)e * np);
+        wa[e] = v.x; wb[e] = v.y;
+      }
+    } else {             // kept transposed: its row kk = t6 / 2, 16 consecutive m
+      const float *src = w + (int64_t)(cb * JAC_NB + (t6 >> 1)) * np + ra * JAC_NB + 16 * (t6 & 1);
+      const float4 v0 = *reinterpret_cast<const float4 *>(src), v1 = *reinterpret_cast<const float4 *>(src + 4);
+      const float4 v2 = *reinterpret_cast<const float4 *>(src + 8), v3 = *reinterpret_cast<const float4 *>(src + 12);
+      wa[0] = v0.x; wa[1] = v0.y; wa[2] = v0.z; wa[3] = v0.w; wa[4] = v1.x; wa[5] = v1.y; wa[6] = v1.z; wa[7] = v1.w;
+      wb[0] = v2.x; wb[1] = v2.y; wb[2] = v2.z; wb[3] = v2.w; wb[4] = v3.x; wb[5] = v3.y; wb[6] = v3.z; wb[7] = v3.w;
     }
+    // jt16 of pair lx: 2 planes x 64 rows x 128 bytes = 1024 pieces of 16 bytes, 4 per thread
+    const uint4 *js = reinterpret_cast<const uint4 *>(jt + (int64_t)(2 * lx) * JAC_PIV * JAC_PIV);
+    jn0 = js[tid]; jn1 = js[tid + 256]; jn2 = js[tid + 512]; jn3 = js[tid + 768];
   };
-  int l = next_active(l_first);
-  if (l >= l_end) return;
+  auto pack8 = [&](const float (&x)[8], unsigned char *dst) {     // the two terms of 8 values, 16 bytes per plane
+    _Float16 h[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float sx = x[e] * sw;
+      h[e] = (_Float16)sx;
+      lo[e] = (_Float16)(sx - (float)h[e]);
+    }
+    *reinterpret_cast<uint4 *>(dst) = make_uint4(pack_f16x2(h[0], h[1]), pack_f16x2(h[2], h[3]), pack_f16x2(h[4], h[5]), pack_f16x2(h[6], h[7]));
+    *reinterpret_cast<uint4 *>(dst + W16_XPLANE) = make_uint4(pack_f16x2(lo[0], lo[1]), pack_f16x2(lo[2], lo[3]), pack_f16x2(lo[4], lo[5]), pack_f16x2(lo[6], lo[7]));
+  };
+  auto stash = [&](int lx) {
+    int pl, ql;
+    g.pair(lx, pl, ql);
+    const int ra = (sb & 2) ? qk : pk, cb = (sb & 1) ? ql : pl;
+    const int m0 = (sb & 2) ? JAC_NB : 0, kk0 = (sb & 1) ? JAC_NB : 0;     // origin of the sub-block inside the tile
+    if (ra >= cb) {
+      const int mg = t6 >> 4, c2 = 2 * (t6 & 15);
+      pack8(wa, XT + (kk0 + c2) * W16_XROW + (m0 + 8 * mg) * 2);
+      pack8(wb, XT + (kk0 + c2 + 1) * W16_XROW + (m0 + 8 * mg) * 2);
+    } else {
+      const int kk = t6 >> 1, mh = 16 * (t6 & 1);
+      pack8(wa, XT + (kk0 + kk) * W16_XROW + (m0 + mh) * 2);
+      pack8(wb, XT + (kk0 + kk) * W16_XROW + (m0 + mh + 8) * 2);
+    }
+    // piece tid + 256 e: plane = e / 2, row = tid / 8 + 32 (e % 2), 16-byte column = tid % 8
+    unsigned char *jd = JL + (tid >> 3) * W16_JROW + (tid & 7) * 16;
+    *reinterpret_cast<uint4 *>(jd) = jn0;
+    *reinterpret_cast<uint4 *>(jd + 32 * W16_JROW) = jn1;
+    *reinterpret_cast<uint4 *>(jd + W16_JPLANE) = jn2;
+    *reinterpret_cast<uint4 *>(jd + W16_JPLANE + 32 * W16_JROW) = jn3;
+  };
   fetch(l);
-  while (l < l_end) {
-    const int ln = next_active(l + 1);                   // l_end if this is the last one
+  for (bool first = true; l < l_end; first = false) {
+    const int ln = next_active(l + 1);   // l_end if this is the last one
     int pl, ql;
     g.pair(l, pl, ql);
-    __syncthreads();                                     // the tile of the pair-block before is done with
-    if (!have_jk) { load_rotation(Jk, jb, k, idk, tid); have_jk = true; }
-#pragma unroll
-    for (int h = 0; h < 4; ++h) *reinterpret_cast<float4 *>(&Jl[(jr + 16 * h) * APP_LD + jc4]) = jn[h];
-    sub_stash32(wx[0], pk, pl, 0, 0);
-    sub_stash32(wx[1], pk, ql, 0, JAC_NB);
-    sub_stash32(wx[2], qk, pl, JAC_NB, 0);
-    sub_stash32(wx[3], qk, ql, JAC_NB, JAC_NB);
+    if (!first) __syncthreads();         // every wavefront is done with the tile of the pair-block before
+    stash(l);
     __syncthreads();
-    if (ln < l_end) fetch(ln);                           // in flight during the products below
-    // Y^T(kk, i) = sum_m X(m, kk) J_k(m, i)
-    const floatx16 yt = mfma_64(X, Jk, wi, wj, lane);
-    __syncthreads();                                     // every wavefront has read X
+    if (ln < l_end) fetch(ln);           // in flight during the products below
+
+    // first product: four tiles of Y^T, 2 k steps x 3 products each
+    floatx4 yt[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int a = 0; a < 4; ++a) {
+      yt[a] = (floatx4){0.f, 0.f, 0.f, 0.f};
+      const unsigned char *xr = XT + (16 * a + li) * W16_XROW + 16 * lg;
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        X[(wi * 32 + 8 * q + 4 * (lane >> 5) + e) * APP_LD + wj * 32 + (lane & 31)] = yt[4 * q + e];
-    __syncthreads();
-    // C(i, j) = sum_kk Y^T(kk, i) J_l(kk, j)
-    const floatx16 c = mfma_64(X, Jl, wi, wj, lane);
-    const int ra = wi ? qk : pk, cb = wj ? ql : pl;
-    if (k != l) {
-      const int j = lane & 31;
+      for (int st = 0; st < 2; ++st) {
+        const jac_f16x8v xh = __builtin_bit_cast(jac_f16x8v, *reinterpret_cast<const uint4 *>(xr + 64 * st));
+        const jac_f16x8v xl = __builtin_bit_cast(jac_f16x8v, *reinterpret_cast<const uint4 *>(xr + 64 * st + W16_XPLANE));
+        const jac_f16x8v jh = __builtin_bit_cast(jac_f16x8v, jk[0][st]), jl = __builtin_bit_cast(jac_f16x8v, jk[1][st]);
+        yt[a] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xl, jh, yt[a], 0, 0, 0);
+        yt[a] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh, jl, yt[a], 0, 0, 0);
+        yt[a] = __builtin_amdgcn_mfma_f32_16x16x32_f16(xh, jh, yt[a], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // the A operands of the second product: k step t takes tiles 2 t and 2 t + 1
+    jac_f16x8v ah[2], al[2];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int i0 = 8 * q + 4 * (lane >> 5);
+    for (int t = 0; t < 2; ++t) {
+      _Float16 h[8], lo[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float sx = yt[2 * t + (e >> 2)][e & 3] * unscale * sw;
+        h[e] = (_Float16)sx;
+        lo[e] = (_Float16)(sx - (float)h[e]);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { ah[t][e] = h[e]; al[t][e] = lo[e]; }
+    }
+    if (k == l) __syncthreads();         // all reads of X^T done: the result of a diagonal pair-block is completed there
+    // second product, one 16-column tile of the result at a time; each leaves as soon as it is done
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      floatx4 c = (floatx4){0.f, 0.f, 0.f, 0.f};
+      const unsigned char *jr = JL + (16 * u + li) * W16_JROW + 8 * lg;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint2 h0 = *reinterpret_cast<const uint2 *>(jr + 64 * t), h1 = *reinterpret_cast<const uint2 *>(jr + 64 * t + 32);
+        const uint2 l0 = *reinterpret_cast<const uint2 *>(jr + 64 * t + W16_JPLANE), l1 = *reinterpret_cast<const uint2 *>(jr + 64 * t + 32 + W16_JPLANE);
+        const jac_f16x8v bh = __builtin_bit_cast(jac_f16x8v, make_uint4(h0.x, h0.y, h1.x, h1.y));
+        const jac_f16x8v bl = __builtin_bit_cast(jac_f16x8v, make_uint4(l0.x, l0.y, l1.x, l1.y));
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(al[t], bh, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[t], bl, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah[t], bh, c, 0, 0, 0);
+      }
+      // element e is C[16 wave + 4 lg + e][16 u + li]
+      if (k != l) {
+        const int ra = wave < 2 ? pk : qk, cb = u < 2 ? pl : ql;
+        const int ii0 = (16 * wave & 31) + 4 * lg, jj = (16 * u & 31) + li;
         if (ra > cb) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) w[(int64_t)(ra * JAC_NB + i0 + e) * np + cb * JAC_NB + j] = c[4 * q + e];
-        } else {          // stored transposed: four consecutive floats per lane
-          *reinterpret_cast<float4 *>(w + (int64_t)(cb * JAC_NB + j) * np + ra * JAC_NB + i0) =
-              make_float4(c[4 * q], c[4 * q + 1], c[4 * q + 2], c[4 * q + 3]);
+          for (int e = 0; e < 4; ++e) w[(int64_t)(ra * JAC_NB + ii0 + e) * np + cb * JAC_NB + jj] = c[e] * unscale;
+        } else {          // kept transposed: four consecutive values per lane
+          *reinterpret_cast<float4 *>(w + (int64_t)(cb * JAC_NB + jj) * np + ra * JAC_NB + ii0) =
+              make_float4(c[0] * unscale, c[1] * unscale, c[2] * unscale, c[3] * unscale);
         }
-      }
-    } else {
-      // the diagonal pair-block is completed from its lower half, so that the sub-blocks on the
-      // diagonal of W stay exactly symmetric
-      __syncthreads();                                   // every wavefront has read Y^T
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
+      } else {
+        const int j = 16 * u + li;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int i = wi * 32 + 8 * q + 4 * (lane >> 5) + e, j = wj * 32 + (lane & 31);
-          if (j <= i) { X[i * APP_LD + j] = c[4 * q + e]; X[j * APP_LD + i] = c[4 * q + e]; }
+          const int i = 16 * wave + 4 * lg + e;
+          if (j <= i) { Ct[i * APP_LD + j] = c[e] * unscale; Ct[j * APP_LD + i] = c[e] * unscale; }
         }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (k == l) {
       __syncthreads();
+      // thread -> row tid / 8 of a stored sub-block, 4 columns
+      const int ii = tid >> 3, j4 = (tid & 7) * 4;
+      auto sub_store = [&](int ra, int cb, int xi, int xj) {   // ra >= cb: kept as it is
+        *reinterpret_cast<float4 *>(w + (int64_t)(ra * JAC_NB + ii) * np + cb * JAC_NB + j4) =
+            *reinterpret_cast<const float4 *>(&Ct[(xi + ii) * APP_LD + xj + j4]);
+      };
       sub_store(pk, pl, 0, 0);
       sub_store(qk, pl, JAC_NB, 0);                      // (pk, qk) is its mirror image and is not kept
       sub_store(qk, ql, JAC_NB, JAC_NB);
@@ -1256,7 +1375,7 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const 
   blockjac_apply_w_body(g, blockIdx.x, smem);
 }
 __global__ __launch_bounds__(JAC_THREADS, 3) void blockjac_apply_w32_kernel(const BlockJacArgs g) {
-  __shared__ __align__(32) unsigned char smem[APPLY_LDS_BYTES];
+  __shared__ __align__(32) unsigned char smem[W16_LDS_BYTES];
   blockjac_apply_w32_body(g, blockIdx.x, smem);
 }
 __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const BlockJacArgs g) {

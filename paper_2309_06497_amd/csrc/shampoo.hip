@@ -378,7 +378,7 @@ void eig_offsets(EigLayout &e) {
   e.off_ident = off; off += align_up(2 * (size_t)e.chunk * hp * sizeof(int32_t));
   e.off_j16 = off; off += align_up(2 * (size_t)e.chunk * hp * 2 * JAC_PIV * JAC_PIV * sizeof(uint16_t));   // the same blocks, transposed, as two fp16 planes
   e.off_rot = off; off += align_up((size_t)e.chunk * JAC_OUTER_SWEEPS * sizeof(int32_t));
-  e.off_dmax = off; off += align_up((size_t)e.chunk * sizeof(float));
+  e.off_dmax = off; off += align_up(2 * (size_t)e.chunk * sizeof(float));   // largest |diagonal entry|, largest absolute row sum
   e.off_failed = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
   e.off_f = off; off += align_up((size_t)e.chunk * e.np * sizeof(float));
   if (e.warm) { e.off_t = off; off += align_up((size_t)e.chunk * e.np * std::min(e.np, CONGRUENCE_PANEL) * sizeof(double)); }
@@ -506,13 +506,16 @@ struct BlockSolve {
     float *dmax = reinterpret_cast<float *>(ws + e->off_dmax) + slot0;
     failed = reinterpret_cast<int32_t *>(ws + e->off_failed) + slot0;
     fv = reinterpret_cast<float *>(ws + e->off_f) + (int64_t)slot0 * np;
+    float *wbound = reinterpret_cast<float *>(ws + e->off_dmax) + e->chunk + slot0;
     int rc = launch_fill(dmax, 0.f, cnt, s);
+    if (rc) return rc;
+    rc = launch_fill(wbound, 0.f, cnt, s);
     if (rc) return rc;
     rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, cnt, s);
     if (rc) return rc;
     BlockInitArgs ia;
     ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
-    ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.failed = failed; ia.rot = rot; ia.only = only;
+    ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.wbound = wbound; ia.failed = failed; ia.rot = rot; ia.only = only;
     // A cold solve runs its first sweeps on a float32 copy of W (twice the matrix-core and vector
     // rates, half the bytes), then continues exactly like a warm start: W = Qt A Qt^T is formed in
     // float64 from the rotations accumulated so far, and float64 sweeps finish the job.  What the
@@ -527,7 +530,7 @@ struct BlockSolve {
       hipLaunchKernelGGL(blockjac_init_kernel<double>, dim3(np, cnt), dim3(256), 0, s, ia);
     }
     HIP_TRY(hipGetLastError());
-    ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.rot = rot; ja.dmax = dmax; ja.failed = failed;
+    ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.rot = rot; ja.dmax = dmax; ja.wbound = wbound; ja.failed = failed;
     ja.ident2 = islot[1]; ja.jt16 = hslot[0]; ja.jt16_2 = hslot[1];
     ja.np = np;
     ja.group = (nblk % 4 == 0) ? 2 : 1;
@@ -559,7 +562,7 @@ struct BlockSolve {
       ja.cross_only = (ja.group == 2 && rd > 0) ? 1 : 0;
       if (f32) {
         hipLaunchKernelGGL(blockjac_pivot_kernel<float>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
-        hipLaunchKernelGGL(blockjac_apply_w32_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
+        hipLaunchKernelGGL(blockjac_apply_w32_kernel, dim3(appw_segments(hp, W16_SEG), cnt), dim3(JAC_THREADS), 0, s, ja);
       } else {
         hipLaunchKernelGGL(blockjac_pivot_kernel<double>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
         hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
