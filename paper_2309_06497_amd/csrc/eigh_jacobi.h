@@ -477,9 +477,32 @@ inline size_t rootinv_small_lds_bytes(int n) {
 // ---------------------------------------------------------------------------
 typedef double doublex4 __attribute__((ext_vector_type(4)));
 
+// The float32 copy of W keeps every 32 x 32 sub-block contiguous (4 KB, sub-block (br, bc) at
+// (br * nblk + bc) * 1024 floats, row-major inside): the updates read and write whole sub-blocks,
+// and as 128-byte row pieces 4 KB apart they reach half the memory rate that 4 KB bursts do.
+__device__ __forceinline__ int w32_sub(int br, int bc, int nblk) { return (br * nblk + bc) * (JAC_NB * JAC_NB); }
+__device__ __forceinline__ int w32_index(int i, int j, int nblk) {
+  return w32_sub(i / JAC_NB, j / JAC_NB, nblk) + (i % JAC_NB) * JAC_NB + (j % JAC_NB);
+}
+
+// Workgroups are handed to the 8 XCDs (each with an L2 of its own) round-robin in launch order.
+// The update kernels of the block solver re-number them so that every XCD works through whole
+// matrices: the rotation blocks of a matrix (256 KB at n = 1024), which all of its workgroups
+// read, then stay in one L2 instead of being fetched into all eight.  (bx, by): what the
+// workgroup takes for blockIdx.x, blockIdx.y.
+__device__ __forceinline__ void xcd_order(int &bx, int &by) {
+  constexpr int XCDS = 8;
+  const int nx = gridDim.x, total = nx * gridDim.y;
+  const int lin = blockIdx.y * nx + blockIdx.x;
+  const int xcd = lin % XCDS, pos = lin / XCDS;
+  const int q = total / XCDS, r = total % XCDS;        // XCDs 0 .. r - 1 get q + 1 workgroups, the others q
+  const int v = xcd * q + min(xcd, r) + pos;
+  by = v / nx; bx = v - by * nx;
+}
+
 struct BlockJacArgs {
   double *w;
-  float *w32;            // the float32 copy of W that the first sweeps of a cold solve work on (same layout)
+  float *w32;            // the float32 copy of W that the first sweeps of a cold solve work on (sub-blocks contiguous: w32_index)
   float *qt;
   float *jbuf;           // [batch][np/64][64][64]: rotation blocks of the current round
   int32_t *ident;        // [batch][np/64]: pivot of the current round needed no rotation
@@ -540,7 +563,8 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
     }
     rowsum += fabsf((float)v);
     if (!g.warm) {
-      w[j] = (T)v;
+      if (sizeof(T) == 4) reinterpret_cast<T *>(g.w)[(int64_t)b * np * np + w32_index(i, j, np / JAC_NB)] = (T)v;
+      else w[j] = (T)v;
       qt[j] = (i == j) ? 1.f : 0.f;
     }
   }
@@ -602,7 +626,8 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
     const int gi = (i < JAC_NB ? pb * JAC_NB + i : qb * JAC_NB + i - JAC_NB);
     const int gj = (j < JAC_NB ? pb * JAC_NB + j : qb * JAC_NB + j - JAC_NB);
     // lower triangle of W (gi >= gj when j <= i, because pb < qb), mirrored into LDS
-    const T v = (j <= i) ? w[(int64_t)gi * np + gj] : w[(int64_t)gj * np + gi];
+    const int lo_r = (j <= i) ? gi : gj, lo_c = (j <= i) ? gj : gi;
+    const T v = sizeof(T) == 4 ? w[w32_index(lo_r, lo_c, nblk)] : w[(int64_t)lo_r * np + lo_c];
     At[i * PIV_LD + j] = v;
     Js[i * PIV_LD + j] = (i == j) ? 1.f : 0.f;
   }
@@ -734,10 +759,9 @@ constexpr int APP_JLD = JAC_PIV + 4;   // LDS row stride of J_l: rows 4 apart st
 constexpr int APPLY_LDS_BYTES = JAC_PIV * APP_LD * 12;    // what each of the three update bodies below needs
 
 // bx: index of the workgroup among the appw_segments(hp) of the W update
-__device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int bx, unsigned char *smem) {
+__device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int bx, int b, unsigned char *smem) {
   double *X = reinterpret_cast<double *>(smem);                               // [JAC_PIV * APP_LD] W_kl (and the result of a diagonal pair-block)
   float *Jl = reinterpret_cast<float *>(smem + JAC_PIV * APP_LD * 8);         // [JAC_PIV * APP_JLD]
-  const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
@@ -753,10 +777,16 @@ __device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int
   }
   const int l_first = seg * APPW_SEG, l_end = min(l_first + APPW_SEG, k + 1);
   const bool idk = ident[k] != 0;
+  // the flags of the walk, read once (a load inside the walk would make every pair-block wait
+  // for the stores of the one before it: the counter of outstanding memory operations is one)
+  unsigned idbits = 0;
+#pragma unroll
+  for (int e = 0; e < APPW_SEG; ++e)
+    if (l_first + e < l_end && ident[l_first + e] != 0) idbits |= 1u << e;
   // the pair-blocks of this walk that rotate at all, in order (uniform across the workgroup)
   auto next_active = [&](int from) {
     int l = from;
-    while (l < l_end && idk && ident[l] != 0) ++l;
+    while (l < l_end && idk && ((idbits >> (l - l_first)) & 1u)) ++l;
     return l;
   };
   int l = next_active(l_first);
@@ -940,11 +970,10 @@ __device__ __forceinline__ float jac_pow2_scale(float bound) {
   return ldexpf(1.f, min(max(14 - e, -100), 100));
 }
 
-__device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, int bx, unsigned char *smem) {
+__device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, int bx, int b, unsigned char *smem) {
   unsigned char *XT = smem;                              // [2 planes][64 kk][W16_XROW]
   unsigned char *JL = smem + 2 * W16_XPLANE;             // [2 planes][64 j][W16_JROW]
   float *Ct = reinterpret_cast<float *>(smem);           // [64][APP_LD], diagonal pair-block only
-  const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2;
@@ -960,9 +989,15 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
   }
   const int l_first = seg * W16_SEG, l_end = min(l_first + W16_SEG, k + 1);
   const bool idk = ident[k] != 0;
+  // the flags of the walk, read once (a load inside the walk would make every pair-block wait
+  // for the stores of the one before it: the counter of outstanding memory operations is one)
+  unsigned idbits = 0;
+#pragma unroll
+  for (int e = 0; e < W16_SEG; ++e)
+    if (l_first + e < l_end && ident[l_first + e] != 0) idbits |= 1u << e;
   auto next_active = [&](int from) {
     int l = from;
-    while (l < l_end && idk && ident[l] != 0) ++l;
+    while (l < l_end && idk && ((idbits >> (l - l_first)) & 1u)) ++l;
     return l;
   };
   int l = next_active(l_first);
@@ -991,14 +1026,14 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
     g.pair(lx, pl, ql);
     const int ra = (sb & 2) ? qk : pk, cb = (sb & 1) ? ql : pl;
     if (ra >= cb) {      // kept as it is: rows m = 8 (t6 / 16) .. + 7, columns 2 (t6 % 16), + 1
-      const float *src = w + (int64_t)(ra * JAC_NB + 8 * (t6 >> 4)) * np + cb * JAC_NB + 2 * (t6 & 15);
+      const float *src = w + w32_sub(ra, cb, nblk) + 8 * (t6 >> 4) * JAC_NB + 2 * (t6 & 15);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float2 v = *reinterpret_cast<const float2 *>(src + (int64_t)e * np);
+        const float2 v = *reinterpret_cast<const float2 *>(src + e * JAC_NB);
         wa[e] = v.x; wb[e] = v.y;
       }
     } else {             // kept transposed: its row kk = t6 / 2, 16 consecutive m
-      const float *src = w + (int64_t)(cb * JAC_NB + (t6 >> 1)) * np + ra * JAC_NB + 16 * (t6 & 1);
+      const float *src = w + w32_sub(cb, ra, nblk) + (t6 >> 1) * JAC_NB + 16 * (t6 & 1);
       const float4 v0 = *reinterpret_cast<const float4 *>(src), v1 = *reinterpret_cast<const float4 *>(src + 4);
       const float4 v2 = *reinterpret_cast<const float4 *>(src + 8), v3 = *reinterpret_cast<const float4 *>(src + 12);
       wa[0] = v0.x; wa[1] = v0.y; wa[2] = v0.z; wa[3] = v0.w; wa[4] = v1.x; wa[5] = v1.y; wa[6] = v1.z; wa[7] = v1.w;
@@ -1103,9 +1138,9 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
         const int ii0 = (16 * wave & 31) + 4 * lg, jj = (16 * u & 31) + li;
         if (ra > cb) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) w[(int64_t)(ra * JAC_NB + ii0 + e) * np + cb * JAC_NB + jj] = c[e] * unscale;
+          for (int e = 0; e < 4; ++e) w[w32_sub(ra, cb, nblk) + (ii0 + e) * JAC_NB + jj] = c[e] * unscale;
         } else {          // kept transposed: four consecutive values per lane
-          *reinterpret_cast<float4 *>(w + (int64_t)(cb * JAC_NB + jj) * np + ra * JAC_NB + ii0) =
+          *reinterpret_cast<float4 *>(w + w32_sub(cb, ra, nblk) + jj * JAC_NB + ii0) =
               make_float4(c[0] * unscale, c[1] * unscale, c[2] * unscale, c[3] * unscale);
         }
       } else {
@@ -1123,7 +1158,7 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
       // thread -> row tid / 8 of a stored sub-block, 4 columns
       const int ii = tid >> 3, j4 = (tid & 7) * 4;
       auto sub_store = [&](int ra, int cb, int xi, int xj) {   // ra >= cb: kept as it is
-        *reinterpret_cast<float4 *>(w + (int64_t)(ra * JAC_NB + ii) * np + cb * JAC_NB + j4) =
+        *reinterpret_cast<float4 *>(w + w32_sub(ra, cb, nblk) + ii * JAC_NB + j4) =
             *reinterpret_cast<const float4 *>(&Ct[(xi + ii) * APP_LD + xj + j4]);
       };
       sub_store(pk, pl, 0, 0);
@@ -1152,10 +1187,9 @@ constexpr int APPQ_TILES = 4;   // 64-column tiles of Qt handled by one workgrou
 // Qt rows of pair k <- J_k^T (those rows), APPQ_TILES 64-column tiles per workgroup,
 // float32 MFMA.  grid (hp * ceil(np / 256), batch).
 // bx: index of the workgroup among the hp * ceil(np / 256) of the Q update
-__device__ __forceinline__ void blockjac_apply_q_body(const BlockJacArgs &g, int bx, unsigned char *smem) {
+__device__ __forceinline__ void blockjac_apply_q_body(const BlockJacArgs &g, int bx, int b, unsigned char *smem) {
   float *Jk = reinterpret_cast<float *>(smem);           // [JAC_PIV * APP_LD]
   float (*X)[JAC_PIV * APP_LD] = reinterpret_cast<float (*)[JAC_PIV * APP_LD]>(Jk + JAC_PIV * APP_LD);   // [2][...]
-  const int b = blockIdx.y;
   if (g.failed[b]) return;
   if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2, ctiles = np / JAC_PIV;
@@ -1238,14 +1272,15 @@ constexpr int APPQ2_PLANE = JAC_PIV * APPQ2_ROW;         // one plane: 64 column
 
 __global__ __launch_bounds__(APPQ2_THREADS, 2) void blockjac_apply_q2_kernel(const BlockJacArgs g) {
   __shared__ __align__(16) unsigned char Xs[2 * APPQ2_PLANE];   // plane h, plane l
-  const int b = blockIdx.y;
+  int bxo, b;
+  xcd_order(bxo, b);
   if (g.failed[b]) return;
   if (g.converged(b)) return;
   const int np = g.np, nblk = np / JAC_NB, hp = nblk / 2, ctiles = np / JAC_PIV;
   const int groups = (ctiles + APPQ_TILES - 1) / APPQ_TILES;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int piv = wave >> 1, wi = wave & 1;
-  const int K = blockIdx.x / groups, grp = blockIdx.x - K * groups;
+  const int K = bxo / groups, grp = bxo - K * groups;
   const bool ida0 = g.ident[b * hp + 2 * K] != 0, idb0 = g.ident[b * hp + 2 * K + 1] != 0;
   const bool ida1 = g.ident2[b * hp + 2 * K] != 0, idb1 = g.ident2[b * hp + 2 * K + 1] != 0;
   if (ida0 && idb0 && ida1 && idb1) return;
@@ -1372,15 +1407,21 @@ __global__ __launch_bounds__(APPQ2_THREADS, 2) void blockjac_apply_q2_kernel(con
 // slower: the two bodies then share one register allocation and one occupancy limit).
 __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_w_kernel(const BlockJacArgs g) {
   __shared__ __align__(32) unsigned char smem[APPLY_LDS_BYTES];
-  blockjac_apply_w_body(g, blockIdx.x, smem);
+  int bx, b;
+  xcd_order(bx, b);
+  blockjac_apply_w_body(g, bx, b, smem);
 }
 __global__ __launch_bounds__(JAC_THREADS, 3) void blockjac_apply_w32_kernel(const BlockJacArgs g) {
   __shared__ __align__(32) unsigned char smem[W16_LDS_BYTES];
-  blockjac_apply_w32_body(g, blockIdx.x, smem);
+  int bx, b;
+  xcd_order(bx, b);
+  blockjac_apply_w32_body(g, bx, b, smem);
 }
 __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const BlockJacArgs g) {
   __shared__ __align__(32) unsigned char smem[APPLY_LDS_BYTES];
-  blockjac_apply_q_body(g, blockIdx.x, smem);
+  int bx, b;
+  xcd_order(bx, b);
+  blockjac_apply_q_body(g, bx, b, smem);
 }
 
 struct BlockFinalArgs {
