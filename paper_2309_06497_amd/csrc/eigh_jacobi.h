@@ -172,8 +172,7 @@ __device__ __forceinline__ int tri(int i, int j) {
 // T: float64, or float32 for the first sweeps of the mixed-precision block solver.
 template <bool SQUARE, int NT, bool HALVES = false, typename T = double>
 __device__ int jacobi_sweeps(T *At, float *Js, int s, const int LD, const int LDA, int max_sweeps,
-                             T tol_rel, T tol_abs, JacScratch *sc, int n_rounds = -1) {
-  if (n_rounds < 0) n_rounds = s - 1;
+                             T tol_rel, T tol_abs, JacScratch *sc) {
   const int tid = threadIdx.x;
   const int half = s >> 1;
   auto at = [LDA](int i, int j) { return SQUARE ? i * LDA + j : tri(i, j); };
@@ -216,12 +215,12 @@ __device__ int jacobi_sweeps(T *At, float *Js, int s, const int LD, const int LD
         const T aij = jac_abs(At[at(i, j)]);
         if (aij > tol_abs && aij * aij > tol_rel * tol_rel * jac_abs(At[at(i, i)] * At[at(j, j)])) {
           const int r = HALVES ? halves_round(s, i, j) : (i == s - 1) ? j : ((i + j) * half) % (s - 1);
-          if (r < n_rounds) atomicOr(&sc->rounds[r >> 5], 1u << (r & 31));
+          atomicOr(&sc->rounds[r >> 5], 1u << (r & 31));
         }
       }
     }
     __syncthreads();
-    for (int r = 0; r < n_rounds; ++r) {
+    for (int r = 0; r < s - 1; ++r) {
       if (!((sc->rounds[r >> 5] >> (r & 31)) & 1u)) continue;      // uniform
       if (tid < half) {
         int p, q;
@@ -326,6 +325,142 @@ __device__ int jacobi_sweeps(T *At, float *Js, int s, const int LD, const int LD
     __syncthreads();   // everyone has read flag before thread 0 clears it again
   }
   return any;
+}
+
+// One sweep over the pairs ACROSS the two halves of a 64 x 64 pivot (index k of the first half
+// with index (k + r) mod 32 of the second in round r = 0 .. 31), with the matrix and the
+// accumulated rotations in registers instead of LDS.  This is what the pivots of the block
+// solver run in all rounds but the first of a sweep.
+//
+// The pairs of a round are the same for every round if the second half is thought of as moving:
+// round r pairs position k of the first half with position k of the second, where position k of
+// the second half holds index (k + r) mod 32.  In that picture a thread keeps the 2 x 2 blocks
+//   a = A[k][l]   b = A[k][32 + s(l)]   c = A[32 + s(k)][l]   d = A[32 + s(k)][32 + s(l)],   s(k) = (k + r) mod 32
+// of fixed (k, l) for the whole sweep, rotates them with the parameters of pairs k (rows) and l
+// (columns), and then lets the second half move on by one position: b comes from block
+// (k, l + 1), c from (k + 1, l), d from (k + 1, l + 1); a stays.  256 threads: lane % 32 = l,
+// q = 2 wave + lane / 32, blocks k = 4 q .. 4 q + 3 (all 1024 blocks: the symmetric half is computed
+// too, which keeps every exchange a shift).  A shift along l is a lane rotation inside 32 lanes
+// (ds_bpermute: no LDS memory involved), a shift along k is a register move for three of the
+// four blocks and goes through a small LDS array for the fourth.  The accumulated rotations
+// J (64 x 64) are held the same way: thread (l, q) keeps columns l and 32 + s(l) of rows
+// 8 q .. 8 q + 7, and only the second of them moves.  After 32 rounds every index is back at
+// its own position.  Per thread and round about 25 LDS-pipe operations and no address
+// arithmetic, where the LDS version takes 100 and a third of its vector instructions on
+// addresses.
+template <typename T> struct JacPair { T s, t; };     // sin, sin / (1 + cos)
+template <typename T> struct JacCrossScratch {
+  JacPair<T> st[JAC_PIV / 2];
+  T exc[8 * 32], exd[8 * 32];
+  int todo, rotated;
+};
+
+__device__ __forceinline__ float lane_fetch(float v, int byte_addr) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(byte_addr, __float_as_int(v)));
+}
+__device__ __forceinline__ double lane_fetch(double v, int byte_addr) {
+  const int lo = __builtin_amdgcn_ds_bpermute(byte_addr, __double2loint(v));
+  const int hi = __builtin_amdgcn_ds_bpermute(byte_addr, __double2hiint(v));
+  return __hiloint2double(hi, lo);
+}
+
+// At: the pivot, full square, row stride LDA, in LDS (read only).  Js: row stride LD, in LDS;
+// receives J if anything rotated (it must hold the identity on entry).  Returns nonzero if any
+// rotation was applied.  All 256 threads of the workgroup must call it.
+template <typename T>
+__device__ int jacobi_cross_rounds(const T *At, float *Js, const int LDA, const int LD, T tol_rel, T tol_abs,
+                                   JacCrossScratch<T> *cs) {
+  constexpr int H = JAC_PIV / 2;
+  const int tid = threadIdx.x, lane = tid & 63, l = lane & 31, q = 2 * (tid >> 6) + (lane >> 5);
+  const int nxt = 4 * ((lane & 32) | ((lane + 1) & 31));     // byte address of the lane that holds l + 1
+  T a[4], b[4], c[4], d[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int k = 4 * q + p;
+    a[p] = At[k * LDA + l]; b[p] = At[k * LDA + H + l];
+    c[p] = At[(H + k) * LDA + l]; d[p] = At[(H + k) * LDA + H + l];
+  }
+  // anything above the threshold among the pairs across the halves?  b holds all of them now.
+  {
+    const T dl = At[(H + l) * LDA + H + l];
+    int todo = 0;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int k = 4 * q + p;
+      const T aa = jac_abs(b[p]);
+      if (aa > tol_abs && aa * aa > tol_rel * tol_rel * jac_abs(At[k * LDA + k] * dl)) todo = 1;
+    }
+    if (tid == 0) { cs->todo = 0; cs->rotated = 0; }
+    __syncthreads();
+    if (todo) cs->todo = 1;
+    __syncthreads();
+    if (cs->todo == 0) return 0;
+  }
+  float x[8], y[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { x[e] = (8 * q + e == l) ? 1.f : 0.f; y[e] = (8 * q + e == H + l) ? 1.f : 0.f; }
+  const bool owner = (l >> 2) == q;      // this thread holds block (l, l), as its block l % 4
+  const int ps = l & 3;
+  for (int r = 0; r < H; ++r) {
+    if (owner) {
+      const T app = ps == 0 ? a[0] : ps == 1 ? a[1] : ps == 2 ? a[2] : a[3];
+      const T aqq = ps == 0 ? d[0] : ps == 1 ? d[1] : ps == 2 ? d[2] : d[3];
+      const T apq = ps == 0 ? c[0] : ps == 1 ? c[1] : ps == 2 ? c[2] : c[3];
+      T sn = 0, tp = 0;
+      const T aa = jac_abs(apq);
+      if (aa > tol_abs && aa * aa > tol_rel * tol_rel * jac_abs(app * aqq)) {
+        // tan of the rotation angle: the smaller root of t^2 + 2 zeta t - 1 = 0, zeta = (a_qq - a_pp) / (2 a_pq)
+        const T dd = aqq - app, hh = (T)2 * apq;
+        const T xx = dd * dd + hh * hh;
+        const T hyp = xx * rsqrt_newton(xx);
+        const T t = hh * rcp_newton(dd + jac_copysign(hyp, dd));
+        const T cc = rsqrt_newton((T)1 + t * t);
+        sn = t * cc;
+        tp = sn * rcp_newton((T)1 + cc);
+        if (!(jac_abs(sn) <= (T)1)) { sn = 0; tp = 0; }   // non-finite: leave the pair alone
+        if (sn != (T)0) cs->rotated = 1;
+      }
+      cs->st[l].s = sn; cs->st[l].t = tp;
+    }
+    __syncthreads();
+    const JacPair<T> rl = cs->st[l];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const JacPair<T> rk = cs->st[4 * q + p];
+      // rows: (a, c) and (b, d) are (x, y) pairs of rotation k
+      const T a1 = a[p] - rk.s * (c[p] + rk.t * a[p]), c1 = c[p] + rk.s * (a[p] - rk.t * c[p]);
+      const T b1 = b[p] - rk.s * (d[p] + rk.t * b[p]), d1 = d[p] + rk.s * (b[p] - rk.t * d[p]);
+      // columns: (a1, b1) and (c1, d1) are (x, y) pairs of rotation l
+      a[p] = a1 - rl.s * (b1 + rl.t * a1); b[p] = b1 + rl.s * (a1 - rl.t * b1);
+      c[p] = c1 - rl.s * (d1 + rl.t * c1); d[p] = d1 + rl.s * (c1 - rl.t * d1);
+      if (4 * q + p == l) { b[p] = (T)0; c[p] = (T)0; }   // the annihilated element
+    }
+    {
+      const float sl = (float)rl.s, tl = (float)rl.t;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xe = x[e], ye = y[e];
+        x[e] = xe - sl * (ye + tl * xe);
+        y[e] = ye + sl * (xe - tl * ye);
+      }
+    }
+    // the second half moves on by one position
+    cs->exc[q * 32 + l] = c[0]; cs->exd[q * 32 + l] = d[0];
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < 4; ++p) b[p] = lane_fetch(b[p], nxt);
+    c[0] = c[1]; c[1] = c[2]; c[2] = c[3]; c[3] = cs->exc[((q + 1) & 7) * 32 + l];
+    {
+      const T d1 = lane_fetch(d[1], nxt), d2 = lane_fetch(d[2], nxt), d3 = lane_fetch(d[3], nxt);
+      d[0] = d1; d[1] = d2; d[2] = d3; d[3] = cs->exd[((q + 1) & 7) * 32 + ((l + 1) & 31)];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y[e] = lane_fetch(y[e], nxt);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { Js[(8 * q + e) * LD + l] = x[e]; Js[(8 * q + e) * LD + H + l] = y[e]; }
+  __syncthreads();
+  return cs->rotated;
 }
 
 // ---------------------------------------------------------------------------
@@ -613,6 +748,7 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
   __shared__ T At[JAC_PIV * PIV_LD];
   __shared__ float Js[JAC_PIV * PIV_LD];
   __shared__ JacScratch sc;
+  __shared__ JacCrossScratch<T> cs;
   const int b = blockIdx.y, pair = blockIdx.x;
   if (g.failed[b]) return;
   if (g.converged(b)) return;
@@ -633,8 +769,10 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
   }
   __syncthreads();
   const double dm = (double)g.dmax[b];
-  const int any = jacobi_sweeps<true, JAC_PIV_THREADS, true, T>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps, (T)g.tol_rel,
-                                         (T)(g.tol_abs_rel * dm), &sc, g.cross_only ? JAC_PIV / 2 : -1);
+  static_assert(JAC_PIV_THREADS == 256 && JAC_PIV == 64, "thread layout of jacobi_cross_rounds");
+  const int any = g.cross_only ? jacobi_cross_rounds<T>(At, Js, PIV_LD, PIV_LD, (T)g.tol_rel, (T)(g.tol_abs_rel * dm), &cs)
+                               : jacobi_sweeps<true, JAC_PIV_THREADS, true, T>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps,
+                                                                               (T)g.tol_rel, (T)(g.tol_abs_rel * dm), &sc);
   __syncthreads();
   if (tid == 0) {
     g.ident[b * (nblk / 2) + pair] = any ? 0 : 1;
