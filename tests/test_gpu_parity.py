@@ -482,7 +482,7 @@ def test_zero_momentum_and_zero_gradient_block():
     assert rel(p.w_gpu[0].cpu().numpy().astype(np.float64) - p.w0[0], p.w_ora[0] - p.w0[0]) <= TOL_DIR
 
 
-@pytest.mark.parametrize("n", [1, 2, 19, 64, 104, 128, 129, 192, 256, 300, 512])
+@pytest.mark.parametrize("n", [1, 2, 19, 64, 104, 128, 129, 192, 256, 300, 384, 512, 640])
 def test_root_inverse_standalone(n):
     """Framed box of Sec. 3.2.1 on Wishart-like matrices, same float32 bits on both sides."""
     import torch
