@@ -620,6 +620,14 @@ __device__ __forceinline__ int w32_index(int i, int j, int nblk) {
   return w32_sub(i / JAC_NB, j / JAC_NB, nblk) + (i % JAC_NB) * JAC_NB + (j % JAC_NB);
 }
 
+// 16 bytes of a matrix that is far larger than the caches and is not touched again before the
+// next round: loaded as streaming data
+typedef float jac_floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load4(const float *p) {
+  const jac_floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const jac_floatx4 *>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+
 // Workgroups are handed to the 8 XCDs (each with an L2 of its own) round-robin in launch order.
 // The update kernels of the block solver re-number them so that every XCD works through whole
 // matrices: the rotation blocks of a matrix (256 KB at n = 1024), which all of its workgroups
@@ -847,7 +855,7 @@ __device__ __forceinline__ void sub_fetch(const double *w, int np, int ra, int c
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int idx = tid + JAC_THREADS * e;
-    r[e] = w[(int64_t)(gr0 + (idx >> 5)) * np + gc0 + (idx & 31)];
+    r[e] = __builtin_nontemporal_load(w + (int64_t)(gr0 + (idx >> 5)) * np + gc0 + (idx & 31));
   }
 }
 __device__ __forceinline__ void sub_stash(double *X, int ra, int cb, int xi, int xj, int tid, const double r[4]) {
@@ -1034,10 +1042,10 @@ __device__ __forceinline__ void blockjac_apply_w_body(const BlockJacArgs &g, int
           const int jj = (16 * u & 31) + li;
           if (ra > cb) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) w[(int64_t)(ra * JAC_NB + ii0 + 4 * v) * np + cb * JAC_NB + jj] = c2[uu][v];
+            for (int v = 0; v < 4; ++v) __builtin_nontemporal_store(c2[uu][v], w + (int64_t)(ra * JAC_NB + ii0 + 4 * v) * np + cb * JAC_NB + jj);
           } else {        // stored transposed
 #pragma unroll
-            for (int v = 0; v < 4; ++v) w[(int64_t)(cb * JAC_NB + jj) * np + ra * JAC_NB + ii0 + 4 * v] = c2[uu][v];
+            for (int v = 0; v < 4; ++v) __builtin_nontemporal_store(c2[uu][v], w + (int64_t)(cb * JAC_NB + jj) * np + ra * JAC_NB + ii0 + 4 * v);
           }
         }
       } else {
@@ -1172,8 +1180,7 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
       }
     } else {             // kept transposed: its row kk = t6 / 2, 16 consecutive m
       const float *src = w + w32_sub(cb, ra, nblk) + (t6 >> 1) * JAC_NB + 16 * (t6 & 1);
-      const float4 v0 = *reinterpret_cast<const float4 *>(src), v1 = *reinterpret_cast<const float4 *>(src + 4);
-      const float4 v2 = *reinterpret_cast<const float4 *>(src + 8), v3 = *reinterpret_cast<const float4 *>(src + 12);
+      const float4 v0 = stream_load4(src), v1 = stream_load4(src + 4), v2 = stream_load4(src + 8), v3 = stream_load4(src + 12);
       wa[0] = v0.x; wa[1] = v0.y; wa[2] = v0.z; wa[3] = v0.w; wa[4] = v1.x; wa[5] = v1.y; wa[6] = v1.z; wa[7] = v1.w;
       wb[0] = v2.x; wb[1] = v2.y; wb[2] = v2.z; wb[3] = v2.w; wb[4] = v3.x; wb[5] = v3.y; wb[6] = v3.z; wb[7] = v3.w;
     }
@@ -1276,10 +1283,9 @@ __device__ __forceinline__ void blockjac_apply_w32_body(const BlockJacArgs &g, i
         const int ii0 = (16 * wave & 31) + 4 * lg, jj = (16 * u & 31) + li;
         if (ra > cb) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) w[w32_sub(ra, cb, nblk) + (ii0 + e) * JAC_NB + jj] = c[e] * unscale;
+          for (int e = 0; e < 4; ++e) __builtin_nontemporal_store(c[e] * unscale, w + w32_sub(ra, cb, nblk) + (ii0 + e) * JAC_NB + jj);
         } else {          // kept transposed: four consecutive values per lane
-          *reinterpret_cast<float4 *>(w + w32_sub(cb, ra, nblk) + jj * JAC_NB + ii0) =
-              make_float4(c[0] * unscale, c[1] * unscale, c[2] * unscale, c[3] * unscale);
+          __builtin_nontemporal_store(c * unscale, reinterpret_cast<floatx4 *>(w + w32_sub(cb, ra, nblk) + jj * JAC_NB + ii0));
         }
       } else {
         const int j = 16 * u + li;
@@ -1455,7 +1461,7 @@ __global__ __launch_bounds__(APPQ2_THREADS, 2) void blockjac_apply_q2_kernel(con
   float4 pre[8];
   auto fetch = [&](int ct) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pre[e] = *reinterpret_cast<const float4 *>(qt + (src + e * np + ct * JAC_PIV));
+    for (int e = 0; e < 8; ++e) pre[e] = stream_load4(qt + (src + e * np + ct * JAC_PIV));
   };
   auto stage = [&]() {
 #pragma unroll
@@ -1499,8 +1505,8 @@ __global__ __launch_bounds__(APPQ2_THREADS, 2) void blockjac_apply_q2_kernel(con
     for (int q = 0; q < 4; ++q) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        qt[dst] = acc[0][4 * q + e] * UNSCALE;
-        qt[dst + 32] = acc[1][4 * q + e] * UNSCALE;
+        __builtin_nontemporal_store(acc[0][4 * q + e] * UNSCALE, qt + dst);
+        __builtin_nontemporal_store(acc[1][4 * q + e] * UNSCALE, qt + dst + 32);
         dst += np;
       }
       dst += 4 * np;

@@ -53,6 +53,17 @@ __device__ __forceinline__ void load_g4(const GT *g, bool vec, int valid, float 
 #pragma unroll
   for (int e = 0; e < 4; ++e) v[e] = e < valid ? Elem<GT>::load1(g + e) : 0.f;
 }
+// 16 bytes that this step touches once: marked as streaming, so that they do not displace what
+// the next kernel wants to find in the caches
+typedef float ew_floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float *p) {
+  const ew_floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const ew_floatx4 *>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void nt_store4(float *p, const float4 &v) {
+  const ew_floatx4 x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<ew_floatx4 *>(p));
+}
 __device__ __forceinline__ void load_f4(const float *p, bool vec, int valid, float v[4]) {
   if (vec) { Elem<float>::load4(p, v); return; }
 #pragma unroll
@@ -96,7 +107,7 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
           const int j = j0 + u * step;
           if (j < n) {
             Elem<GD>::load4(dp + (int64_t)i * ld + j, gq[u]);
-            av[u] = *reinterpret_cast<const float4 *>(ap + (int64_t)i * ld + j);
+            av[u] = nt_load4(ap + (int64_t)i * ld + j);
           }
         }
 #pragma unroll
@@ -112,7 +123,7 @@ __global__ __launch_bounds__(EW_THREADS) void graft_kernel(const EwArgs g) {
               const float pg = (gv * g.gd_scale) / (sqrtf(g.a_bc * a4[e]) + g.graft_eps);
               ss += pg * pg;
             }
-            *reinterpret_cast<float4 *>(ap + (int64_t)i * ld + j) = make_float4(a4[0], a4[1], a4[2], a4[3]);
+            nt_store4(ap + (int64_t)i * ld + j, make_float4(a4[0], a4[1], a4[2], a4[3]));
           }
         }
       }
@@ -218,9 +229,9 @@ __global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
         for (int u = 0; u < U; ++u) {
           const int j = j0 + u * step;
           if (j < n) {
-            pv[u] = *reinterpret_cast<const float4 *>(pp + (int64_t)i * n + j);
-            wv[u] = *reinterpret_cast<const float4 *>(wp + (int64_t)i * ld + j);
-            mv[u] = *reinterpret_cast<const float4 *>(mp + (int64_t)i * ld + j);
+            pv[u] = nt_load4(pp + (int64_t)i * n + j);
+            wv[u] = nt_load4(wp + (int64_t)i * ld + j);
+            mv[u] = nt_load4(mp + (int64_t)i * ld + j);
           }
         }
 #pragma unroll
@@ -236,8 +247,8 @@ __global__ __launch_bounds__(EW_THREADS) void update_kernel(const EwArgs g) {
               m4[e] = g.mu * m4[e] + p4[e];
               w4[e] += g.lr * (g.nesterov ? g.mu * m4[e] + p4[e] : m4[e]);
             }
-            *reinterpret_cast<float4 *>(mp + (int64_t)i * ld + j) = make_float4(m4[0], m4[1], m4[2], m4[3]);
-            *reinterpret_cast<float4 *>(wp + (int64_t)i * ld + j) = make_float4(w4[0], w4[1], w4[2], w4[3]);
+            nt_store4(mp + (int64_t)i * ld + j, make_float4(m4[0], m4[1], m4[2], m4[3]));
+            nt_store4(wp + (int64_t)i * ld + j, make_float4(w4[0], w4[1], w4[2], w4[3]));
           }
         }
       }

@@ -241,7 +241,7 @@ __global__ __launch_bounds__(GEMM_THREADS, ACC64 ? 2 : 3) void syrk_bf16_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int i = min(row0 + wm * 64 + mi * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), g.M - 1);
-          old[ni][v] = c[(int64_t)i * ldc + j];
+          old[ni][v] = __builtin_nontemporal_load(c + (int64_t)i * ldc + j);
         }
       }
     } else {
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(GEMM_THREADS, ACC64 ? 2 : 3) void syrk_bf16_kernel(
         double sum;
         if constexpr (ACC64) sum = acc64[mi][ni][v]; else sum = (double)acc[mi][ni][v];
         const float x = (float)(alpha * sum + g.beta * (double)old[ni][v]);
-        if (i < g.M && j < g.M) c[(int64_t)i * ldc + j] = x;
+        if (i < g.M && j < g.M) __builtin_nontemporal_store(x, c + (int64_t)i * ldc + j);
       }
     }
   }
@@ -337,7 +337,9 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeArgs
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) w[e] = (uint32_t)tile[c + 2 * e][jr] | ((uint32_t)tile[c + 2 * e + 1][jr] << 16);
-    *reinterpret_cast<uint4 *>(dst + (int64_t)j * g.m + i) = make_uint4(w[0], w[1], w[2], w[3]);
+    typedef uint32_t tr_u32x4 __attribute__((ext_vector_type(4)));
+    const tr_u32x4 packed = {w[0], w[1], w[2], w[3]};
+    __builtin_nontemporal_store(packed, reinterpret_cast<tr_u32x4 *>(dst + (int64_t)j * g.m + i));
   }
 }
 
