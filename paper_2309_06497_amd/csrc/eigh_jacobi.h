@@ -52,6 +52,7 @@ constexpr double JAC_SMALL_TOL_ABS = 1e-15;
 // resolution (pairs below 1e-6 of their diagonal entries, or below 2e-7 of the largest
 // diagonal entry, are left to the float64 sweeps that follow).
 constexpr int JAC_F32_SWEEPS = 8;
+constexpr int JAC_F32_SWEEPS_YOUNG = 10;   // for factors known to be badly conditioned (few gradient columns so far)
 constexpr double JAC_F32_TOL_REL = 1e-6;
 constexpr double JAC_F32_TOL_ABS = 2e-7;
 

@@ -473,6 +473,11 @@ struct WarmStart {
   float *qt = nullptr;          // [batch][np][np]: eigenvectors, read (start) and written
   bool start = false;
   int32_t *sweeps = nullptr;    // optional [batch]: sweeps in which anything rotated
+  bool young = false;           // the factors have seen few gradient columns (young_factor): badly conditioned, they
+                                // take three more sweeps than well-conditioned ones, and a cold solve then runs two
+                                // more of them in float32, where a sweep costs half of what it does in float64
+                                // (256 factors of a single gradient, n = 1024: 345 -> 322 ms; well-conditioned
+                                // factors would pay for the two sweeps and gain nothing: 268 -> 293 ms)
 };
 
 // One sub-chunk of a block-Jacobi solve: `cnt` matrices in workspace slots [slot0, slot0 + cnt),
@@ -538,7 +543,7 @@ struct BlockSolve {
     sw = 0;
     return SHAMPOO_OK;
   }
-  int f32_sweeps() const { return mixed ? JAC_F32_SWEEPS : 0; }
+  int f32_sweeps() const { return mixed ? (warm_in.young ? JAC_F32_SWEEPS_YOUNG : JAC_F32_SWEEPS) : 0; }
   // The next sweep: float32 while sw < f32_sweeps(), then (once) the congruence, then float64.
   int sweep() {
     const int appw_seg = appw_segments(hp);
@@ -1282,9 +1287,10 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
     // at every WARM_RESTART_PERIOD-th one (the accumulated float32 eigenvectors drift away from
     // orthogonality by about 1e-6 per solve; a cold solve resets that).
     const bool warm_now = o->n_refresh > 0 && o->n_refresh % WARM_RESTART_PERIOD != 0;
-    auto warm_of = [&](const EigLayout &lay, size_t off_qt) {
+    auto warm_of = [&](const EigLayout &lay, size_t off_qt, int cols, int dim) {
       WarmStart w;
       if (lay.warm && off_qt) { w.qt = reinterpret_cast<float *>(ws + off_qt); w.start = warm_now; }
+      w.young = young_factor(step, cols, dim);
       return w;
     };
     for (size_t i = 0; i < p.buckets.size(); ++i) {
@@ -1306,7 +1312,8 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
           } else {
             rc = root_inverse_batched(F, dim, b.count, c.epsilon, c.root_exponent, c2, Fi, nullptr, nullptr, fail_count,
                                       ws + o->off_eig, side == 0 ? o->eig_L[i] : o->eig_R[i], s, &o->aux, nullptr,
-                                      warm_of(side == 0 ? o->eig_L[i] : o->eig_R[i], side == 0 ? b.off_QtL : b.off_QtR));
+                                      warm_of(side == 0 ? o->eig_L[i] : o->eig_R[i], side == 0 ? b.off_QtL : b.off_QtR,
+                                              side == 0 ? b.n : b.m, dim));
             if (rc) return rc;
           }
         }
@@ -1346,11 +1353,11 @@ int step_impl(shampoo_opt *o, float lr, int64_t step, hipStream_t s) {
       }
       rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_L), b.m, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Linv), nullptr, nullptr, fail_count,
-                                ws + o->off_eig, o->eig_L[i], s, &o->aux, nullptr, warm_of(o->eig_L[i], b.off_QtL));
+                                ws + o->off_eig, o->eig_L[i], s, &o->aux, nullptr, warm_of(o->eig_L[i], b.off_QtL, b.n, b.m));
       if (rc) return rc;
       rc = root_inverse_batched(reinterpret_cast<float *>(ws + b.off_R), b.n, b.count, c.epsilon, c.root_exponent, c2,
                                 reinterpret_cast<float *>(ws + b.off_Rinv), nullptr, nullptr, fail_count,
-                                ws + o->off_eig, o->eig_R[i], s, &o->aux, nullptr, warm_of(o->eig_R[i], b.off_QtR));
+                                ws + o->off_eig, o->eig_R[i], s, &o->aux, nullptr, warm_of(o->eig_R[i], b.off_QtR, b.m, b.n));
       if (rc) return rc;
     }
     o->n_refresh++;
