@@ -286,6 +286,9 @@ def main():
     # update has left its float64-accumulating variant for young factors behind by then)
     base = 4 if args.skip_refresh else t_first
     for t in range(t_first):          # untimed: factors accumulate, the step is the grafted one
+        if t >= 2:                    # a fresh gradient set per step, so that the factors at the refresh are those of
+            for g in pool[t % 2]:     # t_first + 1 independent gradients (cycling two sets would leave them at rank 2 n)
+                g.copy_(torch.randn(g.shape, generator=gen, device=dev, dtype=torch.float32) * wk["sigma"])
         opt.step(params, pool[t % 2], 0.01, t)
     torch.cuda.synchronize()
     opt.get_timing()

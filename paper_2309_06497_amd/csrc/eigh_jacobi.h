@@ -51,7 +51,7 @@ constexpr double JAC_SMALL_TOL_ABS = 1e-15;
 // The float32 sweeps of a cold block solve: as many as it takes float32 to run out of
 // resolution (pairs below 1e-6 of their diagonal entries, or below 2e-7 of the largest
 // diagonal entry, are left to the float64 sweeps that follow).
-constexpr int JAC_F32_SWEEPS = 8;
+constexpr int JAC_F32_SWEEPS = 9;
 constexpr int JAC_F32_SWEEPS_YOUNG = 10;   // for factors known to be badly conditioned (few gradient columns so far)
 constexpr double JAC_F32_TOL_REL = 1e-6;
 constexpr double JAC_F32_TOL_ABS = 2e-7;
@@ -660,6 +660,7 @@ struct BlockJacArgs {
   const float *dmax;     // [batch]: largest |diagonal entry| of the input
   const float *wbound;   // [batch]: largest absolute row sum of the input (bounds every entry of every orthogonal transform of it)
   const int32_t *failed; // [batch]
+  const int32_t *done;   // [batch]: the float32 sweeps were all this matrix needed (blockjac_f32_verdict_kernel)
   int32_t np;            // padded size
   int32_t round, sweep;
   int32_t phase_start;   // index of the first sweep of the current phase (float32 or float64 sweeps): a sweep is
@@ -668,7 +669,7 @@ struct BlockJacArgs {
   double tol_rel;        // rotation threshold relative to sqrt(|a_pp a_qq|)
   double tol_abs_rel;    // ... and absolute threshold as a fraction of max |diag(input)|
   __device__ __forceinline__ bool converged(int b) const {
-    return sweep > phase_start && rot[b * JAC_OUTER_SWEEPS + sweep - 1] == 0;
+    return done[b] != 0 || (sweep > phase_start && rot[b * JAC_OUTER_SWEEPS + sweep - 1] == 0);
   }
   // block columns (p < q) of pivot k of the current round
   __device__ __forceinline__ void pair(int k, int &p, int &q) const { grouped_pair(np / JAC_NB, group, round, k, p, q); }
@@ -766,18 +767,31 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
   g.pair(pair, pb, qb);   // pb < qb
   const T *w = (sizeof(T) == 8 ? reinterpret_cast<const T *>(g.w) : reinterpret_cast<const T *>(g.w32)) + (int64_t)b * np * np;
   const int tid = threadIdx.x;
+  // A float32 pivot is solved on a copy scaled by a power of two that brings the largest diagonal
+  // entry of the matrix into [0.5, 1): the rotations do not depend on the scale, and products of
+  // two entries (the rotation threshold, the rotation itself) neither underflow nor overflow
+  // whatever the size of the gradients (factors of gradients of size 1e-15 have entries of 1e-31).
+  T psc = (T)1;
+  if (sizeof(T) == 4) {
+    const float dmx = g.dmax[b];
+    if (dmx > 0.f && dmx < 3.0e38f) {
+      int e;
+      (void)frexpf(dmx, &e);
+      psc = (T)ldexpf(1.f, min(max(-e, -120), 120));
+    }
+  }
   for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) {
     const int j = tid & 63;
     const int gi = (i < JAC_NB ? pb * JAC_NB + i : qb * JAC_NB + i - JAC_NB);
     const int gj = (j < JAC_NB ? pb * JAC_NB + j : qb * JAC_NB + j - JAC_NB);
     // lower triangle of W (gi >= gj when j <= i, because pb < qb), mirrored into LDS
     const int lo_r = (j <= i) ? gi : gj, lo_c = (j <= i) ? gj : gi;
-    const T v = sizeof(T) == 4 ? w[w32_index(lo_r, lo_c, nblk)] : w[(int64_t)lo_r * np + lo_c];
+    const T v = sizeof(T) == 4 ? w[w32_index(lo_r, lo_c, nblk)] * psc : w[(int64_t)lo_r * np + lo_c];
     At[i * PIV_LD + j] = v;
     Js[i * PIV_LD + j] = (i == j) ? 1.f : 0.f;
   }
   __syncthreads();
-  const double dm = (double)g.dmax[b];
+  const double dm = (double)g.dmax[b] * (double)psc;
   static_assert(JAC_PIV_THREADS == 256 && JAC_PIV == 64, "thread layout of jacobi_cross_rounds");
   const int any = g.cross_only ? jacobi_cross_rounds<T>(At, Js, PIV_LD, PIV_LD, (T)g.tol_rel, (T)(g.tol_abs_rel * dm), &cs)
                                : jacobi_sweeps<true, JAC_PIV_THREADS, true, T>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps,
@@ -1567,6 +1581,55 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const 
   int bx, b;
   xcd_order(bx, b);
   blockjac_apply_q_body(g, bx, b, smem);
+}
+
+// After the float32 sweeps of a cold solve: does this matrix need the float64 phase at all?
+// What float32 leaves behind is an absolute error of about 1e-7 of the largest eigenvalue, in
+// the eigenvalues and in the off-diagonal elements alike.  For a well-conditioned matrix that
+// is a relative 1e-6 of every eigenvalue, i.e. 2.5e-7 of lambda^(-1/4), below what the float32
+// eigenvectors carry anyway, and the congruence plus the float64 sweeps (a quarter of such a
+// solve: their first sweep finds every pivot above the float64 threshold and costs more than
+// a float32 one) would change nothing that can be seen in the result.  The diagonal of the
+// float32 W is the spectrum to that accuracy, so the test is min >= JAC_F32_ONLY_RATIO * max
+// on it.  A matrix that passes gets done[b] = 1 (every later kernel of the solve returns at once
+// for it) and its diagonal written into the float64 W, where the last kernel of the solve looks
+// for the eigenvalues; skip[b] = failed[b] | done[b] is what the congruence takes.
+// One workgroup of 256 threads per matrix; dynamic LDS: np floats.
+constexpr float JAC_F32_ONLY_RATIO = 0.1f;
+
+struct BlockVerdictArgs {
+  double *w; const float *w32; int32_t np, n;
+  const int32_t *failed; int32_t *done; int32_t *skip;
+};
+
+__global__ __launch_bounds__(256) void blockjac_f32_verdict_kernel(const BlockVerdictArgs g) {
+  extern __shared__ float vdiag[];
+  __shared__ float redlo[4], redhi[4];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int np = g.np, n = g.n, nblk = np / JAC_NB;
+  if (g.failed[b]) {
+    if (tid == 0) { g.done[b] = 0; g.skip[b] = 1; }
+    return;
+  }
+  const float *w32 = g.w32 + (int64_t)b * np * np;
+  float lo = 3.0e38f, hi = -3.0e38f;
+  for (int i = tid; i < np; i += 256) {
+    const float d = w32[w32_index(i, i, nblk)];
+    vdiag[i] = d;
+    if (i < n) { lo = fminf(lo, d); hi = fmaxf(hi, d); }
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { lo = fminf(lo, __shfl_xor(lo, off, 64)); hi = fmaxf(hi, __shfl_xor(hi, off, 64)); }
+  if (lane == 0) { redlo[wave] = lo; redhi[wave] = hi; }
+  __syncthreads();                 // also: every diagonal entry has been read before W is written below
+  lo = fminf(fminf(redlo[0], redlo[1]), fminf(redlo[2], redlo[3]));
+  hi = fmaxf(fmaxf(redhi[0], redhi[1]), fmaxf(redhi[2], redhi[3]));
+  const bool ok = lo > 0.f && hi < 3.0e38f && lo >= JAC_F32_ONLY_RATIO * hi;
+  if (ok) {
+    double *w = g.w + (int64_t)b * np * np;
+    for (int i = tid; i < np; i += 256) w[(int64_t)i * np + i] = (double)vdiag[i];
+  }
+  if (tid == 0) { g.done[b] = ok ? 1 : 0; g.skip[b] = ok ? 1 : 0; }
 }
 
 struct BlockFinalArgs {

@@ -379,7 +379,7 @@ void eig_offsets(EigLayout &e) {
   e.off_j16 = off; off += align_up(2 * (size_t)e.chunk * hp * 2 * JAC_PIV * JAC_PIV * sizeof(uint16_t));   // the same blocks, transposed, as two fp16 planes
   e.off_rot = off; off += align_up((size_t)e.chunk * JAC_OUTER_SWEEPS * sizeof(int32_t));
   e.off_dmax = off; off += align_up(2 * (size_t)e.chunk * sizeof(float));   // largest |diagonal entry|, largest absolute row sum
-  e.off_failed = off; off += align_up((size_t)e.chunk * sizeof(int32_t));
+  e.off_failed = off; off += align_up(3 * (size_t)e.chunk * sizeof(int32_t));   // failed, done, skip (failed | done)
   e.off_f = off; off += align_up((size_t)e.chunk * e.np * sizeof(float));
   if (e.warm) { e.off_t = off; off += align_up((size_t)e.chunk * e.np * std::min(e.np, CONGRUENCE_PANEL) * sizeof(double)); }
   e.bytes = off;
@@ -493,7 +493,7 @@ struct BlockSolve {
   int np = 0, nblk = 0, hp = 0, sw = 0;
   bool warm = false, mixed = false;
   double *w = nullptr; float *w32 = nullptr, *qt = nullptr, *fv = nullptr;
-  int32_t *rot = nullptr, *failed = nullptr;
+  int32_t *rot = nullptr, *failed = nullptr, *done = nullptr, *skipc = nullptr;
   float *jslot[2] = {nullptr, nullptr}; int32_t *islot[2] = {nullptr, nullptr}; uint16_t *hslot[2] = {nullptr, nullptr};
   BlockJacArgs ja{};
 
@@ -510,6 +510,7 @@ struct BlockSolve {
     rot = reinterpret_cast<int32_t *>(ws + e->off_rot) + (int64_t)slot0 * JAC_OUTER_SWEEPS;
     float *dmax = reinterpret_cast<float *>(ws + e->off_dmax) + slot0;
     failed = reinterpret_cast<int32_t *>(ws + e->off_failed) + slot0;
+    done = failed + e->chunk; skipc = failed + 2 * e->chunk;
     fv = reinterpret_cast<float *>(ws + e->off_f) + (int64_t)slot0 * np;
     float *wbound = reinterpret_cast<float *>(ws + e->off_dmax) + e->chunk + slot0;
     int rc = launch_fill(dmax, 0.f, cnt, s);
@@ -517,6 +518,8 @@ struct BlockSolve {
     rc = launch_fill(wbound, 0.f, cnt, s);
     if (rc) return rc;
     rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, cnt, s);
+    if (rc) return rc;
+    rc = launch_fill(reinterpret_cast<float *>(done), 0.f, cnt, s);
     if (rc) return rc;
     BlockInitArgs ia;
     ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
@@ -535,7 +538,7 @@ struct BlockSolve {
       hipLaunchKernelGGL(blockjac_init_kernel<double>, dim3(np, cnt), dim3(256), 0, s, ia);
     }
     HIP_TRY(hipGetLastError());
-    ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.rot = rot; ja.dmax = dmax; ja.wbound = wbound; ja.failed = failed;
+    ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.rot = rot; ja.dmax = dmax; ja.wbound = wbound; ja.failed = failed; ja.done = done;
     ja.ident2 = islot[1]; ja.jt16 = hslot[0]; ja.jt16_2 = hslot[1];
     ja.np = np;
     ja.group = (nblk % 4 == 0) ? 2 : 1;
@@ -552,7 +555,13 @@ struct BlockSolve {
     if (f32) {
       ja.phase_start = 0; ja.tol_rel = JAC_F32_TOL_REL; ja.tol_abs_rel = JAC_F32_TOL_ABS;
     } else {
-      if (sw == f32_sweeps() && (mixed || warm)) congruence();
+      if (sw == f32_sweeps() && (mixed || warm)) {
+        if (mixed) {     // matrices that float32 has served well enough leave here
+          BlockVerdictArgs va{w, w32, np, n, failed, done, skipc};
+          hipLaunchKernelGGL(blockjac_f32_verdict_kernel, dim3(cnt), dim3(256), (size_t)np * sizeof(float), s, va);
+        }
+        congruence(mixed ? skipc : failed);
+      }
       ja.phase_start = f32_sweeps(); ja.tol_rel = JAC_BLOCK_TOL_REL; ja.tol_abs_rel = JAC_SMALL_TOL_ABS;
     }
     for (int rd = 0; rd < nblk - 1; ++rd) {
@@ -583,7 +592,7 @@ struct BlockSolve {
     ++sw;
     return SHAMPOO_OK;
   }
-  void congruence() {
+  void congruence(const int32_t *skip) {
     // W = Qt A Qt^T, a panel of columns at a time: T = A Qt^T[:, panel], W[:, panel] = Qt T
     const int pw_max = std::min(np, CONGRUENCE_PANEL);
     double *tp = reinterpret_cast<double *>(ws + e->off_t) + (int64_t)slot0 * np * pw_max;
@@ -593,14 +602,14 @@ struct BlockSolve {
       c1.a = a; c1.a_batch = (int64_t)n * n; c1.lda = n;
       c1.b = qt + (int64_t)col0 * np; c1.b_batch = (int64_t)np * np; c1.ldb = np;
       c1.c = tp; c1.c_batch = (int64_t)np * pw_max; c1.ldc = pw_max;
-      c1.M = n; c1.N = pw; c1.K = n; c1.col0 = 0; c1.skip = failed;
+      c1.M = n; c1.N = pw; c1.K = n; c1.col0 = 0; c1.skip = skip;
       hipLaunchKernelGGL((congruence_gemm_kernel<false, false>), dim3((pw + CG_TILE - 1) / CG_TILE, (n + CG_TILE - 1) / CG_TILE, cnt),
                          dim3(CG_THREADS), 0, s, c1);
       CongruenceArgs c2{};
       c2.a = qt; c2.a_batch = (int64_t)np * np; c2.lda = np;
       c2.b = tp; c2.b_batch = (int64_t)np * pw_max; c2.ldb = pw_max;
       c2.c = w; c2.c_batch = (int64_t)np * np; c2.ldc = np;
-      c2.M = np; c2.N = pw; c2.K = n; c2.col0 = col0; c2.skip = failed;
+      c2.M = np; c2.N = pw; c2.K = n; c2.col0 = col0; c2.skip = skip;
       hipLaunchKernelGGL((congruence_gemm_kernel<true, true>), dim3((pw + CG_TILE - 1) / CG_TILE, (np + CG_TILE - 1) / CG_TILE, cnt),
                          dim3(CG_THREADS), 0, s, c2);
     }
