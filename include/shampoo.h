@@ -123,8 +123,8 @@ typedef struct {
                              accuracy); SHAMPOO_MATRIX_CORES_FP32: always the float32 MFMA          */
   int32_t warm_start_roots; /* != 0: the eigendecomposition of a refresh starts from the eigenvectors of
                              the previous one (Sec. 3.2.1, 4.3: between refreshes a factor changes
-                             little) instead of from the identity: W = Q^T L Q is formed in float64
-                             and the Jacobi sweeps begin there.  Factors of dimension <= 128 (solved
+                             little) instead of from the identity: W = Q^T L Q is formed (float64
+                             sums) and the Jacobi sweeps begin there.  Factors of dimension <= 128 (solved
                              inside one workgroup) and the coupled Newton iteration ignore it.  Costs
                              one more float32 matrix per factor in the workspace.  Every 16th refresh
                              starts cold, which bounds the drift of the accumulated float32
@@ -290,7 +290,7 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
  * qt:     device, batch x np x np float32, np = n rounded up to a multiple of 64; rows are
  *         eigenvectors.  start == 0: a cold solve (qt is overwritten).  start != 0: qt holds the
  *         result of an earlier call on matrices close to a (the same factors some steps
- *         earlier): the solve starts from W = qt a qt^T, formed in float64, and qt is updated.
+ *         earlier): the solve starts from W = qt a qt^T (float64 sums), and qt is updated.
  *         A matrix that fails (see `failed`) leaves its part of qt as it was.
  * sweeps: device int32[batch] or NULL: the number of Jacobi sweeps in which anything rotated
  *         (the last one of a solve never does: it finds every pair below the threshold).

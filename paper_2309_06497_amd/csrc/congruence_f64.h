@@ -1,5 +1,5 @@
-// W = Q^T A Q in float64 from float32 operands, for the warm start of the blocked eigensolver
-// (Sec. 3.2.1: the root inverse by symmetric eigendecomposition is recomputed every
+// W = Q^T A Q in float64 from float32 operands, between the float32 and the float64 sweeps of
+// the blocked eigensolver and (rounded to float32 at the end) for its warm start (Sec. 3.2.1: the root inverse by symmetric eigendecomposition is recomputed every
 // precondition_frequency steps from a factor that has changed little; the eigenvectors of the
 // previous refresh then nearly diagonalise the new factor).  With Qt = Q^T (rows are the
 // previous eigenvectors, float32) and the new factor A (float32):
@@ -21,6 +21,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "eigh_jacobi.h"      // w32_index: where the float32 copy of W keeps element (i, j)
 
 namespace shampoo {
 
@@ -45,7 +46,9 @@ struct CongruenceArgs {
 // LOWER: C is the solver's W: only tiles that reach the diagonal or lie below it are computed,
 // elements above the diagonal are not stored, except inside the 32 x 32 sub-blocks on the diagonal,
 // which receive the mirror image of their lower half (exactly symmetric).
-template <bool BF64, bool LOWER>
+// OUT32 (with LOWER): the result is rounded to float32 and goes into the solver's float32 copy of
+// W (c is that array, c_batch counts floats, ldc = np), sub-blocks contiguous.
+template <bool BF64, bool LOWER, bool OUT32 = false>
 __global__ __launch_bounds__(CG_THREADS, 1) void congruence_gemm_kernel(const CongruenceArgs g) {
   __shared__ float As[CG_TILE * CG_LDF];
   __shared__ __align__(16) unsigned char Bs_raw[BF64 ? CG_KS * CG_LDD * 8 : CG_TILE * CG_LDF * 4];
@@ -139,6 +142,13 @@ __global__ __launch_bounds__(CG_THREADS, 1) void congruence_gemm_kernel(const Co
         if (!LOWER) { c[(int64_t)i * g.ldc + jl] = x; continue; }
         const int j = g.col0 + jl;                  // column inside W
         if (j > i) continue;
+        if (OUT32) {
+          float *cf = reinterpret_cast<float *>(g.c) + (int64_t)bz * g.c_batch;
+          const int nblk = g.ldc / JAC_NB;
+          cf[w32_index(i, j, nblk)] = (float)x;
+          if ((i >> 5) == (j >> 5) && j < i) cf[w32_index(j, i, nblk)] = (float)x;
+          continue;
+        }
         c[(int64_t)i * g.ldc + j] = x;
         if ((i >> 5) == (j >> 5) && j < i) c[(int64_t)j * g.ldc + i] = x;
       }

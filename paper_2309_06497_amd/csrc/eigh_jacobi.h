@@ -52,6 +52,7 @@ constexpr double JAC_SMALL_TOL_ABS = 1e-15;
 // resolution (pairs below 1e-6 of their diagonal entries, or below 2e-7 of the largest
 // diagonal entry, are left to the float64 sweeps that follow).
 constexpr int JAC_F32_SWEEPS = 9;
+constexpr int JAC_F32_SWEEPS_WARM = 6;     // warm start: W = Qt A Qt^T is nearly diagonal already
 constexpr int JAC_F32_SWEEPS_YOUNG = 10;   // for factors known to be badly conditioned (few gradient columns so far)
 constexpr double JAC_F32_TOL_REL = 1e-6;
 constexpr double JAC_F32_TOL_ABS = 2e-7;
@@ -677,20 +678,18 @@ struct BlockJacArgs {
 
 struct BlockInitArgs {
   const float *a; int64_t a_stride; int32_t n;
-  void *w;               // float64, or float32 for a mixed-precision cold solve
+  float *w;              // the float32 copy of W (sub-blocks contiguous: w32_index)
   float *qt; int32_t np;
   float *dmax; float *wbound; int32_t *failed; int32_t *rot;
   const int32_t *only;   // optional [batch]: a matrix whose entry is 0 is marked 2 in `failed`, which
                          // every later kernel takes as "leave alone" without counting it as a failure
   int32_t warm;          // nonzero: Qt holds the eigenvectors of an earlier solve and stays; W is made
-                         // from it afterwards (congruence_f64.h); only the flags and dmax are set here
+                         // from it afterwards (congruence_f64.h); only the flags and bounds are set here
 };
 
 // W = pad(sym(A)), Qt = I (unless warm), dmax, failed, rot = 0.  grid (np, batch), 256 threads.
-template <typename T>
 __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs g) {
   const int b = blockIdx.y, i = blockIdx.x, np = g.np, n = g.n;
-  T *w = reinterpret_cast<T *>(g.w) + (int64_t)b * np * np + (int64_t)i * np;
   float *qt = g.qt + (int64_t)b * np * np + (int64_t)i * np;
   const float *a = g.a + (int64_t)b * g.a_stride;
   if (g.only && g.only[b] == 0) {
@@ -708,8 +707,7 @@ __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs 
     }
     rowsum += fabsf((float)v);
     if (!g.warm) {
-      if (sizeof(T) == 4) reinterpret_cast<T *>(g.w)[(int64_t)b * np * np + w32_index(i, j, np / JAC_NB)] = (T)v;
-      else w[j] = (T)v;
+      g.w[(int64_t)b * np * np + w32_index(i, j, np / JAC_NB)] = (float)v;
       qt[j] = (i == j) ? 1.f : 0.f;
     }
   }
@@ -1583,28 +1581,37 @@ __global__ __launch_bounds__(JAC_THREADS, 2) void blockjac_apply_q_kernel(const 
   blockjac_apply_q_body(g, bx, b, smem);
 }
 
-// After the float32 sweeps of a cold solve: does this matrix need the float64 phase at all?
-// What float32 leaves behind is an absolute error of about 1e-7 of the largest eigenvalue, in
-// the eigenvalues and in the off-diagonal elements alike.  For a well-conditioned matrix that
-// is a relative 1e-6 of every eigenvalue, i.e. 2.5e-7 of lambda^(-1/4), below what the float32
-// eigenvectors carry anyway, and the congruence plus the float64 sweeps (a quarter of such a
-// solve: their first sweep finds every pivot above the float64 threshold and costs more than
-// a float32 one) would change nothing that can be seen in the result.  The diagonal of the
-// float32 W is the spectrum to that accuracy, so the test is min >= JAC_F32_ONLY_RATIO * max
-// on it.  A matrix that passes gets done[b] = 1 (every later kernel of the solve returns at once
-// for it) and its diagonal written into the float64 W, where the last kernel of the solve looks
-// for the eigenvalues; skip[b] = failed[b] | done[b] is what the congruence takes.
-// One workgroup of 256 threads per matrix; dynamic LDS: np floats.
+// After the float32 sweeps: does this matrix need the float64 phase at all?
+// What converged float32 sweeps leave behind is an absolute error of about 1e-7 of the largest
+// eigenvalue, in the eigenvalues and in the off-diagonal elements alike.  For a well-conditioned
+// matrix that is a relative 1e-6 of every eigenvalue, and the congruence plus the float64 sweeps
+// (a quarter of such a solve: their first sweep finds every pivot above the float64 threshold
+// and costs more than a float32 one) would change nothing that can be seen in the result.
+// Two tests on the float32 W = D + E (D its diagonal, lo and hi the smallest and largest entry
+// of D):
+//   lo >= JAC_F32_ONLY_RATIO * hi                      the spectrum is narrow, and
+//   ||E||_F <= JAC_F32_ONLY_OFF * sqrt(n) * lo         the sweeps did converge.
+// The second bounds what stopping here costs: to first order f(D + E) - f(D) has the entries
+// E_ij (f(d_i) - f(d_j)) / (d_i - d_j), at most |f'| |E_ij| = |E_ij| f / (4 lo) for
+// f = lambda^(-1/4), so the relative error of the root in the Frobenius norm is at most
+// ||E||_F / (4 sqrt(n) lo) <= JAC_F32_ONLY_OFF / 4.
+// A matrix that passes gets done[b] = 1 (every later kernel of the solve returns at once for it)
+// and its diagonal copied to d32 (an array of its own: the float64 W of one matrix lies over the
+// float32 copies of two others, which their workgroups may not have read yet), where the last
+// kernel of the solve looks for the eigenvalues; skip[b] = failed[b] | done[b] is what the
+// congruence takes.  One workgroup of 256 threads per matrix.
 constexpr float JAC_F32_ONLY_RATIO = 0.1f;
+constexpr float JAC_F32_ONLY_OFF = 6.0e-5f;
 
 struct BlockVerdictArgs {
-  double *w; const float *w32; int32_t np, n;
+  float *d32;            // [batch][np]
+  const float *w32; int32_t np, n;
   const int32_t *failed; int32_t *done; int32_t *skip;
 };
 
 __global__ __launch_bounds__(256) void blockjac_f32_verdict_kernel(const BlockVerdictArgs g) {
-  extern __shared__ float vdiag[];
   __shared__ float redlo[4], redhi[4];
+  __shared__ double redss[4];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int np = g.np, n = g.n, nblk = np / JAC_NB;
   if (g.failed[b]) {
@@ -1612,22 +1619,50 @@ __global__ __launch_bounds__(256) void blockjac_f32_verdict_kernel(const BlockVe
     return;
   }
   const float *w32 = g.w32 + (int64_t)b * np * np;
+  float *d32 = g.d32 + (int64_t)b * np;
   float lo = 3.0e38f, hi = -3.0e38f;
   for (int i = tid; i < np; i += 256) {
     const float d = w32[w32_index(i, i, nblk)];
-    vdiag[i] = d;
+    d32[i] = d;
     if (i < n) { lo = fminf(lo, d); hi = fmaxf(hi, d); }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) { lo = fminf(lo, __shfl_xor(lo, off, 64)); hi = fmaxf(hi, __shfl_xor(hi, off, 64)); }
   if (lane == 0) { redlo[wave] = lo; redhi[wave] = hi; }
-  __syncthreads();                 // also: every diagonal entry has been read before W is written below
+  __syncthreads();
   lo = fminf(fminf(redlo[0], redlo[1]), fminf(redlo[2], redlo[3]));
   hi = fmaxf(fmaxf(redhi[0], redhi[1]), fmaxf(redhi[2], redhi[3]));
-  const bool ok = lo > 0.f && hi < 3.0e38f && lo >= JAC_F32_ONLY_RATIO * hi;
+  bool ok = lo > 0.f && hi < 3.0e38f && lo >= JAC_F32_ONLY_RATIO * hi;     // uniform over the workgroup
   if (ok) {
-    double *w = g.w + (int64_t)b * np * np;
-    for (int i = tid; i < np; i += 256) w[(int64_t)i * np + i] = (double)vdiag[i];
+    // ||E||_F^2 / hi^2: the sub-blocks below the diagonal count twice, those on it hold both halves.
+    // The elements are scaled by a power of two near 1 / hi first (their squares would leave the
+    // float32 range for factors of very small or very large gradients).
+    const float sc = jac_pow2_scale(hi);
+    double ss = 0.0;
+    for (int br = 0; br < nblk; ++br)
+      for (int bc = 0; bc <= br; ++bc) {
+        const float *sub = w32 + w32_sub(br, bc, nblk);
+        float acc = 0.f;
+        for (int e = tid; e < JAC_NB * JAC_NB / 4; e += 256) {
+          const float4 q = stream_load4(sub + 4 * e);
+          float v[4] = {q.x, q.y, q.z, q.w};
+          if (br == bc) {           // element 4 e + c is (row, col) = (e / 8, 4 (e % 8) + c)
+            const int row = e >> 3, col0 = 4 * (e & 7);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) if (col0 + c == row) v[c] = 0.f;
+          }
+#pragma unroll
+          for (int c = 0; c < 4; ++c) { v[c] *= sc; acc += v[c] * v[c]; }
+        }
+        ss += (double)acc * (br == bc ? 1.0 : 2.0);
+      }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if (lane == 0) redss[wave] = ss;
+    __syncthreads();
+    ss = redss[0] + redss[1] + redss[2] + redss[3];
+    const double bound = (double)JAC_F32_ONLY_OFF * (double)(lo * sc);
+    ok = ss <= bound * bound * (double)n;
   }
   if (tid == 0) { g.done[b] = ok ? 1 : 0; g.skip[b] = ok ? 1 : 0; }
 }
@@ -1643,6 +1678,8 @@ struct BlockFinalArgs {
   unsigned long long *fail_count;
   const int32_t *rot;    // [batch][JAC_OUTER_SWEEPS] pivots that rotated per sweep
   int32_t *sweeps_out;   // optional [batch]: number of sweeps in which anything rotated
+  const int32_t *done;   // optional [batch]: nonzero = the eigenvalues are in d32, not on the diagonal of w
+  const float *d32;      // [batch][np]
 };
 
 // One workgroup per matrix: eigenvalues, shift, f(lambda).
@@ -1660,6 +1697,8 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
   const float *qt = g.qt + (int64_t)b * np * np;
   float *fv = g.fvals + (int64_t)b * np;
   const int bad = g.failed[b];
+  const float *d32 = (g.done && g.done[b]) ? g.d32 + (int64_t)b * np : nullptr;
+  auto diag = [&](int i) { return d32 ? (double)d32[i] : w[(int64_t)i * np + i]; };
   // pass 1: fv[i] <- ||row i of Qt||^2, one wavefront per row
   if (!bad)
     for (int i = wave; i < n; i += 4) {
@@ -1675,7 +1714,7 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
   __syncthreads();
   double lmin = 1.0e300;
   if (!bad)
-    for (int i = tid; i < n; i += 256) lmin = fmin(lmin, (double)g.scale * w[(int64_t)i * np + i] / (double)fv[i]);
+    for (int i = tid; i < n; i += 256) lmin = fmin(lmin, (double)g.scale * diag(i) / (double)fv[i]);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) lmin = fmin(lmin, __shfl_xor(lmin, off, 64));
   if (lane == 0) redf[wave] = lmin;
@@ -1687,7 +1726,7 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
     float f = 0.f;
     if (i < n && !bad) {
       const double nrm2 = (double)fv[i];
-      const double lam = (double)g.scale * w[(int64_t)i * np + i] / nrm2;
+      const double lam = (double)g.scale * diag(i) / nrm2;
       f = (float)(pow(lam - shift + (double)g.epsilon, -(double)g.r) / nrm2);
       if (!(f <= 3.0e38f) || !(f >= 0.f)) badf = 1;
       if (g.lambda) g.lambda[(int64_t)b * n + i] = (float)lam;

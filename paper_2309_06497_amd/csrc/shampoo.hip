@@ -380,7 +380,7 @@ void eig_offsets(EigLayout &e) {
   e.off_rot = off; off += align_up((size_t)e.chunk * JAC_OUTER_SWEEPS * sizeof(int32_t));
   e.off_dmax = off; off += align_up(2 * (size_t)e.chunk * sizeof(float));   // largest |diagonal entry|, largest absolute row sum
   e.off_failed = off; off += align_up(3 * (size_t)e.chunk * sizeof(int32_t));   // failed, done, skip (failed | done)
-  e.off_f = off; off += align_up((size_t)e.chunk * e.np * sizeof(float));
+  e.off_f = off; off += align_up(2 * (size_t)e.chunk * e.np * sizeof(float));   // weights of the reconstruction; float32 eigenvalues of matrices that skip the float64 phase
   if (e.warm) { e.off_t = off; off += align_up((size_t)e.chunk * e.np * std::min(e.np, CONGRUENCE_PANEL) * sizeof(double)); }
   e.bytes = off;
 }
@@ -491,8 +491,8 @@ struct BlockSolve {
   const int32_t *only; WarmStart warm_in;
   // derived
   int np = 0, nblk = 0, hp = 0, sw = 0;
-  bool warm = false, mixed = false;
-  double *w = nullptr; float *w32 = nullptr, *qt = nullptr, *fv = nullptr;
+  bool warm = false;
+  double *w = nullptr; float *w32 = nullptr, *qt = nullptr, *fv = nullptr, *d32 = nullptr;
   int32_t *rot = nullptr, *failed = nullptr, *done = nullptr, *skipc = nullptr;
   float *jslot[2] = {nullptr, nullptr}; int32_t *islot[2] = {nullptr, nullptr}; uint16_t *hslot[2] = {nullptr, nullptr};
   BlockJacArgs ja{};
@@ -512,6 +512,7 @@ struct BlockSolve {
     failed = reinterpret_cast<int32_t *>(ws + e->off_failed) + slot0;
     done = failed + e->chunk; skipc = failed + 2 * e->chunk;
     fv = reinterpret_cast<float *>(ws + e->off_f) + (int64_t)slot0 * np;
+    d32 = reinterpret_cast<float *>(ws + e->off_f) + ((int64_t)e->chunk + slot0) * np;
     float *wbound = reinterpret_cast<float *>(ws + e->off_dmax) + e->chunk + slot0;
     int rc = launch_fill(dmax, 0.f, cnt, s);
     if (rc) return rc;
@@ -523,21 +524,18 @@ struct BlockSolve {
     if (rc) return rc;
     BlockInitArgs ia;
     ia.a = a; ia.a_stride = (int64_t)n * n; ia.n = n;
-    ia.w = w; ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.wbound = wbound; ia.failed = failed; ia.rot = rot; ia.only = only;
-    // A cold solve runs its first sweeps on a float32 copy of W (twice the matrix-core and vector
-    // rates, half the bytes), then continues exactly like a warm start: W = Qt A Qt^T is formed in
-    // float64 from the rotations accumulated so far, and float64 sweeps finish the job.  What the
-    // float32 sweeps cannot resolve (eigenvalues below 1e-7 of the largest) is left to them.
-    mixed = !warm;
+    ia.qt = qt; ia.np = np; ia.dmax = dmax; ia.wbound = wbound; ia.failed = failed; ia.rot = rot; ia.only = only;
+    // A solve runs its first sweeps on a float32 copy of W (twice the matrix-core and vector
+    // rates, half the bytes): W = A, Qt = I for a cold solve, W = Qt A Qt^T rounded to float32
+    // for a warm one.  Then W = Qt A Qt^T is formed in float64 from the rotations accumulated so
+    // far, and float64 sweeps finish the job.  What the float32 sweeps cannot resolve
+    // (eigenvalues below 1e-7 of the largest) is left to them.
     w32 = reinterpret_cast<float *>(w);      // shares the memory of W: it is dead when W is formed
     ia.warm = warm ? 1 : 0;
-    if (mixed) {
-      ia.w = w32;
-      hipLaunchKernelGGL(blockjac_init_kernel<float>, dim3(np, cnt), dim3(256), 0, s, ia);
-    } else {
-      hipLaunchKernelGGL(blockjac_init_kernel<double>, dim3(np, cnt), dim3(256), 0, s, ia);
-    }
+    ia.w = w32;
+    hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cnt), dim3(256), 0, s, ia);
     HIP_TRY(hipGetLastError());
+    if (warm) congruence(failed, true);
     ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.rot = rot; ja.dmax = dmax; ja.wbound = wbound; ja.failed = failed; ja.done = done;
     ja.ident2 = islot[1]; ja.jt16 = hslot[0]; ja.jt16_2 = hslot[1];
     ja.np = np;
@@ -546,7 +544,10 @@ struct BlockSolve {
     sw = 0;
     return SHAMPOO_OK;
   }
-  int f32_sweeps() const { return mixed ? (warm_in.young ? JAC_F32_SWEEPS_YOUNG : JAC_F32_SWEEPS) : 0; }
+  int f32_sweeps() const {
+    if (warm) return JAC_F32_SWEEPS_WARM;
+    return warm_in.young ? JAC_F32_SWEEPS_YOUNG : JAC_F32_SWEEPS;
+  }
   // The next sweep: float32 while sw < f32_sweeps(), then (once) the congruence, then float64.
   int sweep() {
     const int appw_seg = appw_segments(hp);
@@ -555,12 +556,11 @@ struct BlockSolve {
     if (f32) {
       ja.phase_start = 0; ja.tol_rel = JAC_F32_TOL_REL; ja.tol_abs_rel = JAC_F32_TOL_ABS;
     } else {
-      if (sw == f32_sweeps() && (mixed || warm)) {
-        if (mixed) {     // matrices that float32 has served well enough leave here
-          BlockVerdictArgs va{w, w32, np, n, failed, done, skipc};
-          hipLaunchKernelGGL(blockjac_f32_verdict_kernel, dim3(cnt), dim3(256), (size_t)np * sizeof(float), s, va);
-        }
-        congruence(mixed ? skipc : failed);
+      if (sw == f32_sweeps()) {
+        // matrices that float32 has served well enough leave here
+        BlockVerdictArgs va{d32, w32, np, n, failed, done, skipc};
+        hipLaunchKernelGGL(blockjac_f32_verdict_kernel, dim3(cnt), dim3(256), 0, s, va);
+        congruence(skipc, false);
       }
       ja.phase_start = f32_sweeps(); ja.tol_rel = JAC_BLOCK_TOL_REL; ja.tol_abs_rel = JAC_SMALL_TOL_ABS;
     }
@@ -592,8 +592,9 @@ struct BlockSolve {
     ++sw;
     return SHAMPOO_OK;
   }
-  void congruence(const int32_t *skip) {
+  void congruence(const int32_t *skip, bool out32) {
     // W = Qt A Qt^T, a panel of columns at a time: T = A Qt^T[:, panel], W[:, panel] = Qt T
+    // (out32: rounded to float32, into the float32 copy of W)
     const int pw_max = std::min(np, CONGRUENCE_PANEL);
     double *tp = reinterpret_cast<double *>(ws + e->off_t) + (int64_t)slot0 * np * pw_max;
     for (int col0 = 0; col0 < np; col0 += pw_max) {
@@ -610,8 +611,9 @@ struct BlockSolve {
       c2.b = tp; c2.b_batch = (int64_t)np * pw_max; c2.ldb = pw_max;
       c2.c = w; c2.c_batch = (int64_t)np * np; c2.ldc = np;
       c2.M = np; c2.N = pw; c2.K = n; c2.col0 = col0; c2.skip = skip;
-      hipLaunchKernelGGL((congruence_gemm_kernel<true, true>), dim3((pw + CG_TILE - 1) / CG_TILE, (np + CG_TILE - 1) / CG_TILE, cnt),
-                         dim3(CG_THREADS), 0, s, c2);
+      const dim3 grid2((pw + CG_TILE - 1) / CG_TILE, (np + CG_TILE - 1) / CG_TILE, cnt);
+      if (out32) hipLaunchKernelGGL((congruence_gemm_kernel<true, true, true>), grid2, dim3(CG_THREADS), 0, s, c2);
+      else hipLaunchKernelGGL((congruence_gemm_kernel<true, true, false>), grid2, dim3(CG_THREADS), 0, s, c2);
     }
   }
   int finish() {
@@ -619,7 +621,7 @@ struct BlockSolve {
     fa.w = w; fa.qt = qt; fa.np = np; fa.n = n; fa.epsilon = eps; fa.r = r; fa.scale = scale; fa.fvals = fv;
     fa.lambda = lambda;
     fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
-    fa.rot = rot; fa.sweeps_out = warm_in.sweeps;
+    fa.rot = rot; fa.sweeps_out = warm_in.sweeps; fa.done = done; fa.d32 = d32;
     hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);
     HIP_TRY(hipGetLastError());
     GemmArgs g{};
