@@ -687,47 +687,69 @@ struct BlockInitArgs {
                          // from it afterwards (congruence_f64.h); only the flags and bounds are set here
 };
 
-// W = pad(sym(A)), Qt = I (unless warm), dmax, failed, rot = 0.  grid (np, batch), 256 threads.
+// W = pad(sym(A)), Qt = I (unless warm), dmax, wbound, failed, rot = 0.
+// grid (np / 32, batch), 256 threads: a workgroup makes the 32 rows of one block row, sub-block by
+// sub-block: the 32 x 32 tile of A at (br, bc) and the one at (bc, br) come in along their rows
+// (128-byte pieces) and meet in LDS, so that A is read along rows only, and a sub-block of W goes
+// out as the 4 KB it occupies.  Thread t holds row t / 8, columns 4 (t % 8) .. + 3 of a tile.
 __global__ __launch_bounds__(256) void blockjac_init_kernel(const BlockInitArgs g) {
-  const int b = blockIdx.y, i = blockIdx.x, np = g.np, n = g.n;
-  float *qt = g.qt + (int64_t)b * np * np + (int64_t)i * np;
+  __shared__ float Xs[JAC_NB][JAC_NB + 1], Ys[JAC_NB][JAC_NB + 1];
+  const int b = blockIdx.y, br = blockIdx.x, np = g.np, n = g.n, nblk = np / JAC_NB;
+  const int tid = threadIdx.x, r = tid >> 3, c4 = (tid & 7) * 4;
   const float *a = g.a + (int64_t)b * g.a_stride;
   if (g.only && g.only[b] == 0) {
-    if (i == 0 && threadIdx.x == 0) g.failed[b] = 2;
+    if (br == 0 && tid == 0) g.failed[b] = 2;
     return;
   }
+  float *w = g.w + (int64_t)b * np * np;
+  float *qt = g.qt + (int64_t)b * np * np;
+  const int gi = br * JAC_NB + r;           // this thread's row of the matrix
   int bad = 0;
-  float rowsum = 0.f;
-  for (int j = threadIdx.x; j < np; j += 256) {
-    double v = 0.0;
-    if (i < n && j < n) {
-      const float lo = a[(int64_t)i * n + j], up = a[(int64_t)j * n + i];
-      if (!(fabsf(lo) <= 3.0e38f) || !(fabsf(up) <= 3.0e38f)) bad = 1;
-      v = 0.5 * ((double)lo + (double)up);
+  float rowsum = 0.f, dm = 0.f;
+  for (int bc = 0; bc < nblk; ++bc) {
+    const int yi = bc * JAC_NB + r;         // its row of the tile on the other side of the diagonal
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int xj = bc * JAC_NB + c4 + e, yj = br * JAC_NB + c4 + e;
+      const float x = (gi < n && xj < n) ? a[(int64_t)gi * n + xj] : 0.f;
+      const float y = (yi < n && yj < n) ? a[(int64_t)yi * n + yj] : 0.f;
+      if (!(fabsf(x) <= 3.0e38f) || !(fabsf(y) <= 3.0e38f)) bad = 1;
+      Xs[r][c4 + e] = x;
+      Ys[r][c4 + e] = y;
+      if (gi == xj && fabsf(x) <= 3.0e38f) dm = fmaxf(dm, fabsf(x));
     }
-    rowsum += fabsf((float)v);
+    __syncthreads();
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[e] = (float)(0.5 * ((double)Xs[r][c4 + e] + (double)Ys[c4 + e][r]));
+      rowsum += fabsf(v[e]);
+    }
     if (!g.warm) {
-      g.w[(int64_t)b * np * np + w32_index(i, j, np / JAC_NB)] = (float)v;
-      qt[j] = (i == j) ? 1.f : 0.f;
+      *reinterpret_cast<float4 *>(w + w32_sub(br, bc, nblk) + r * JAC_NB + c4) = make_float4(v[0], v[1], v[2], v[3]);
+      const int j0 = bc * JAC_NB + c4;
+      *reinterpret_cast<float4 *>(qt + (int64_t)gi * np + j0) =
+          make_float4(gi == j0 ? 1.f : 0.f, gi == j0 + 1 ? 1.f : 0.f, gi == j0 + 2 ? 1.f : 0.f, gi == j0 + 3 ? 1.f : 0.f);
     }
+    __syncthreads();
   }
   if (bad) g.failed[b] = 1;
-  {
-    __shared__ float red[4];
+  // the row sum is spread over the 8 lanes of the row; the largest of a wavefront's 8 rows goes out
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) rowsum += __shfl_xor(rowsum, off, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rowsum;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const float rs = red[0] + red[1] + red[2] + red[3];
-      if (rs <= 3.0e38f) atomicMax(reinterpret_cast<int *>(g.wbound + b), __float_as_int(rs));   // rs >= 0: int order = float order
-    }
+  for (int off = 1; off < 8; off <<= 1) rowsum += __shfl_xor(rowsum, off, 64);
+  if (!(rowsum <= 3.0e38f)) rowsum = 0.f;
+#pragma unroll
+  for (int off = 8; off < 64; off <<= 1) {
+    rowsum = fmaxf(rowsum, __shfl_xor(rowsum, off, 64));
+    dm = fmaxf(dm, __shfl_xor(dm, off, 64));
   }
-  if (i < n && threadIdx.x == 0) {
-    const float d = fabsf(a[(int64_t)i * n + i]);
-    if (d <= 3.0e38f) atomicMax(reinterpret_cast<int *>(g.dmax + b), __float_as_int(d));  // d >= 0: int order = float order
+#pragma unroll
+  for (int off = 1; off < 8; off <<= 1) dm = fmaxf(dm, __shfl_xor(dm, off, 64));
+  if ((tid & 63) == 0) {     // both are >= 0: int order = float order
+    atomicMax(reinterpret_cast<int *>(g.wbound + b), __float_as_int(rowsum));
+    atomicMax(reinterpret_cast<int *>(g.dmax + b), __float_as_int(dm));
   }
-  if (i == 0 && threadIdx.x < JAC_OUTER_SWEEPS) g.rot[b * JAC_OUTER_SWEEPS + threadIdx.x] = 0;
+  if (br == 0 && tid < JAC_OUTER_SWEEPS) g.rot[b * JAC_OUTER_SWEEPS + tid] = 0;
 }
 
 typedef _Float16 jac_f16x8 __attribute__((ext_vector_type(8)));
@@ -1682,7 +1704,27 @@ struct BlockFinalArgs {
   const float *d32;      // [batch][np]
 };
 
-// One workgroup per matrix: eigenvalues, shift, f(lambda).
+// fvals[i] <- ||row i of Qt||^2 for the n eigenvectors of every matrix that has not failed.
+// grid (ceil(n / 4), batch), 256 threads: one wavefront per row.
+struct BlockRowNormArgs {
+  const float *qt; float *fvals; const int32_t *failed; int32_t np, n;
+};
+__global__ __launch_bounds__(256) void blockjac_rownorm_kernel(const BlockRowNormArgs g) {
+  const int b = blockIdx.y, lane = threadIdx.x & 63, i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g.failed[b] || i >= g.n) return;
+  const float *row = g.qt + (int64_t)b * g.np * g.np + (int64_t)i * g.np;
+  double ss = 0.0;
+  for (int j = 4 * lane; j < g.np; j += 256) {
+    const float4 v = stream_load4(row + j);
+    ss += (double)v.x * (double)v.x + (double)v.y * (double)v.y + (double)v.z * (double)v.z + (double)v.w * (double)v.w;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+  if (lane == 0) g.fvals[(int64_t)b * g.np + i] = (float)ss;
+}
+
+// One workgroup per matrix: eigenvalues, shift, f(lambda); fvals holds the squared row norms of Qt
+// on entry (blockjac_rownorm_kernel).
 // The rotation blocks are orthogonal to float32 accuracy only, so after a few
 // hundred rounds the accumulated columns q_i have drifted off unit length by ~1e-5
 // (and the diagonal of W, q_i^T A q_i, with them).  Both are put right here: the
@@ -1694,24 +1736,11 @@ __global__ __launch_bounds__(256) void blockjac_final_kernel(const BlockFinalArg
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int np = g.np, n = g.n;
   const double *w = g.w + (int64_t)b * np * np;
-  const float *qt = g.qt + (int64_t)b * np * np;
   float *fv = g.fvals + (int64_t)b * np;
   const int bad = g.failed[b];
   const float *d32 = (g.done && g.done[b]) ? g.d32 + (int64_t)b * np : nullptr;
   auto diag = [&](int i) { return d32 ? (double)d32[i] : w[(int64_t)i * np + i]; };
-  // pass 1: fv[i] <- ||row i of Qt||^2, one wavefront per row
-  if (!bad)
-    for (int i = wave; i < n; i += 4) {
-      double ss = 0.0;
-      for (int j = lane; j < np; j += 64) {
-        const double v = (double)qt[(int64_t)i * np + j];
-        ss += v * v;
-      }
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-      if (lane == 0) fv[i] = (float)ss;
-    }
-  __syncthreads();
+  // fv[i] holds ||row i of Qt||^2 (blockjac_rownorm_kernel)
   double lmin = 1.0e300;
   if (!bad)
     for (int i = tid; i < n; i += 256) lmin = fmin(lmin, (double)g.scale * diag(i) / (double)fv[i]);

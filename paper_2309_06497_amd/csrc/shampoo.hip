@@ -533,7 +533,7 @@ struct BlockSolve {
     w32 = reinterpret_cast<float *>(w);      // shares the memory of W: it is dead when W is formed
     ia.warm = warm ? 1 : 0;
     ia.w = w32;
-    hipLaunchKernelGGL(blockjac_init_kernel, dim3(np, cnt), dim3(256), 0, s, ia);
+    hipLaunchKernelGGL(blockjac_init_kernel, dim3(nblk, cnt), dim3(256), 0, s, ia);
     HIP_TRY(hipGetLastError());
     if (warm) congruence(failed, true);
     ja.w = w; ja.w32 = w32; ja.qt = qt; ja.jbuf = jslot[0]; ja.ident = islot[0]; ja.rot = rot; ja.dmax = dmax; ja.wbound = wbound; ja.failed = failed; ja.done = done;
@@ -622,6 +622,8 @@ struct BlockSolve {
     fa.lambda = lambda;
     fa.failed = failed; fa.failed_out = failed_user; fa.fail_count = fail_count;
     fa.rot = rot; fa.sweeps_out = warm_in.sweeps; fa.done = done; fa.d32 = d32;
+    BlockRowNormArgs rn{qt, fv, failed, np, n};
+    hipLaunchKernelGGL(blockjac_rownorm_kernel, dim3((n + 3) / 4, cnt), dim3(256), 0, s, rn);
     hipLaunchKernelGGL(blockjac_final_kernel, dim3(cnt), dim3(256), 0, s, fa);
     HIP_TRY(hipGetLastError());
     GemmArgs g{};
