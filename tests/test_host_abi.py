@@ -241,3 +241,27 @@ def test_jacobi_pair_rejects_bad_arguments():
                  (6, 2, 0, 0), (64, 3, 0, 0)]:
         with pytest.raises(B.ShampooError):
             B.shampoo_jacobi_pair(*args)
+
+
+# ---------------------------------------------------------------------------
+# the bound behind the block solver's exit after its float32 sweeps
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,spread", [(96, 1.0), (96, 0.1), (257, 0.3)])
+def test_bound_on_the_root_when_small_off_diagonals_are_dropped(n, spread):
+    """The block solver lets a matrix leave after the float32 sweeps when W = D + E has
+    min(D) >= 0.1 max(D) and ||E||_F <= 6e-5 sqrt(n) min(D), and then takes D for the spectrum.
+    What that costs, for the inverse fourth root (Sec. 3.2.1 with r = 1/4), is at most
+    ||E||_F / (4 sqrt(n) min(D)) of the root in the Frobenius norm, up to second order in E.
+    Checked with the root inverse by numpy's eigendecomposition on E at the limit."""
+    rng = np.random.default_rng(n)
+    d = rng.uniform(spread, 1.0, n) * 3.7e-5
+    d[0], d[1] = d.max(), spread * d.max()                # both ends of the allowed spread
+    E = rng.standard_normal((n, n)); E = E + E.T; np.fill_diagonal(E, 0.0)
+    theta = 6.0e-5
+    E *= theta * np.sqrt(n) * d.min() / np.linalg.norm(E)
+    lam, Q = np.linalg.eigh(np.diag(d) + E)
+    exact = (Q * lam ** -0.25) @ Q.T
+    taken = np.diag(d ** -0.25)
+    err = np.linalg.norm(exact - taken) / np.linalg.norm(exact)
+    assert err <= theta / 4 * 1.01
+    assert err >= theta / 4 * 0.05        # the bound is not vacuous: the error is of that order
