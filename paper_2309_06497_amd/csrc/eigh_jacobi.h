@@ -366,9 +366,10 @@ __device__ __forceinline__ double lane_fetch(double v, int byte_addr) {
   return __hiloint2double(hi, lo);
 }
 
-// At: the pivot, full square, row stride LDA, in LDS (read only).  Js: row stride LD, in LDS;
-// receives J if anything rotated (it must hold the identity on entry).  Returns nonzero if any
-// rotation was applied.  All 256 threads of the workgroup must call it.
+// At: the pivot, full square, row stride LDA, in LDS (read only, and only before the first
+// barrier).  Js: row stride LD, in LDS; receives J if anything rotated (else it is left as it
+// was); it may share the memory of At.  Returns nonzero if any rotation was applied.  All 256
+// threads of the workgroup must call it.
 template <typename T>
 __device__ int jacobi_cross_rounds(const T *At, float *Js, const int LDA, const int LD, T tol_rel, T tol_abs,
                                    JacCrossScratch<T> *cs) {
@@ -773,12 +774,29 @@ constexpr int PIV_LD = JAC_PIV + 1;
 // its rows.  A sub-block needed "the other way round" is read transposed.
 
 // One workgroup per (pair, matrix): diagonalise the 64 x 64 pivot.
-template <typename T>
+// CROSS: only the pairs across the two block columns are rotated (g.cross_only must be set:
+// every round but the first of a sweep when the block columns are grouped in twos).  That solver
+// keeps the pivot and the rotations in registers: it reads the LDS copy of the pivot once, and J
+// comes back into the same LDS array at the end, so the kernel needs half the LDS of the general
+// one and twice as many workgroups (float64) fit a CU.
+template <typename T, bool CROSS> struct PivotLds;
+template <typename T> struct PivotLds<T, true> {
+  T At[JAC_PIV * PIV_LD];
+  JacCrossScratch<T> cs;
+  __device__ float *js() { return reinterpret_cast<float *>(At); }
+};
+template <typename T> struct PivotLds<T, false> {
+  T At[JAC_PIV * PIV_LD];
+  float Js[JAC_PIV * PIV_LD];
+  JacScratch sc;
+  __device__ float *js() { return Js; }
+};
+
+template <typename T, bool CROSS>
 __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const BlockJacArgs g) {
-  __shared__ T At[JAC_PIV * PIV_LD];
-  __shared__ float Js[JAC_PIV * PIV_LD];
-  __shared__ JacScratch sc;
-  __shared__ JacCrossScratch<T> cs;
+  __shared__ PivotLds<T, CROSS> lds;
+  T *At = lds.At;
+  float *Js = lds.js();
   const int b = blockIdx.y, pair = blockIdx.x;
   if (g.failed[b]) return;
   if (g.converged(b)) return;
@@ -808,14 +826,22 @@ __global__ __launch_bounds__(JAC_PIV_THREADS) void blockjac_pivot_kernel(const B
     const int lo_r = (j <= i) ? gi : gj, lo_c = (j <= i) ? gj : gi;
     const T v = sizeof(T) == 4 ? w[w32_index(lo_r, lo_c, nblk)] * psc : w[(int64_t)lo_r * np + lo_c];
     At[i * PIV_LD + j] = v;
-    Js[i * PIV_LD + j] = (i == j) ? 1.f : 0.f;
+    if (!CROSS) Js[i * PIV_LD + j] = (i == j) ? 1.f : 0.f;
   }
   __syncthreads();
   const double dm = (double)g.dmax[b] * (double)psc;
   static_assert(JAC_PIV_THREADS == 256 && JAC_PIV == 64, "thread layout of jacobi_cross_rounds");
-  const int any = g.cross_only ? jacobi_cross_rounds<T>(At, Js, PIV_LD, PIV_LD, (T)g.tol_rel, (T)(g.tol_abs_rel * dm), &cs)
-                               : jacobi_sweeps<true, JAC_PIV_THREADS, true, T>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps,
-                                                                               (T)g.tol_rel, (T)(g.tol_abs_rel * dm), &sc);
+  int any;
+  if constexpr (CROSS) {
+    any = jacobi_cross_rounds<T>(At, Js, PIV_LD, PIV_LD, (T)g.tol_rel, (T)(g.tol_abs_rel * dm), &lds.cs);
+    if (!any) {        // Js (the memory of At) still holds the pivot: the identity goes out instead
+      __syncthreads();
+      for (int i = tid >> 6; i < JAC_PIV; i += JAC_PIV_THREADS / 64) Js[i * PIV_LD + (tid & 63)] = (i == (tid & 63)) ? 1.f : 0.f;
+    }
+  } else {
+    any = jacobi_sweeps<true, JAC_PIV_THREADS, true, T>(At, Js, JAC_PIV, PIV_LD, PIV_LD, g.inner_sweeps,
+                                                        (T)g.tol_rel, (T)(g.tol_abs_rel * dm), &lds.sc);
+  }
   __syncthreads();
   if (tid == 0) {
     g.ident[b * (nblk / 2) + pair] = any ? 0 : 1;

@@ -575,10 +575,12 @@ struct BlockSolve {
       // their two block columns, which halves their rounds
       ja.cross_only = (ja.group == 2 && rd > 0) ? 1 : 0;
       if (f32) {
-        hipLaunchKernelGGL(blockjac_pivot_kernel<float>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+        if (ja.cross_only) hipLaunchKernelGGL((blockjac_pivot_kernel<float, true>), dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+        else hipLaunchKernelGGL((blockjac_pivot_kernel<float, false>), dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
         hipLaunchKernelGGL(blockjac_apply_w32_kernel, dim3(appw_segments(hp, W16_SEG), cnt), dim3(JAC_THREADS), 0, s, ja);
       } else {
-        hipLaunchKernelGGL(blockjac_pivot_kernel<double>, dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+        if (ja.cross_only) hipLaunchKernelGGL((blockjac_pivot_kernel<double, true>), dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
+        else hipLaunchKernelGGL((blockjac_pivot_kernel<double, false>), dim3(hp, cnt), dim3(JAC_PIV_THREADS), 0, s, ja);
         hipLaunchKernelGGL(blockjac_apply_w_kernel, dim3(appw_seg, cnt), dim3(JAC_THREADS), 0, s, ja);
       }
       if (ja.group == 1 || rd == 0) {
