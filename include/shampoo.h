@@ -287,8 +287,8 @@ int shampoo_root_inverse(const float *a, int32_t n, int32_t batch, float epsilon
 /*
  * shampoo_root_inverse with a warm start (n > 128 only, else SHAMPOO_ERR_UNSUPPORTED): the
  * eigenvectors are kept in the caller's array qt between calls.
- * qt:     device, batch x np x np float32, np = n rounded up to a multiple of 64; rows are
- *         eigenvectors.  start == 0: a cold solve (qt is overwritten).  start != 0: qt holds the
+ * qt:     device, batch x np x np float32, np = n rounded up to a multiple of 64, aligned to 16
+ *         bytes (else SHAMPOO_ERR_WORKSPACE); rows are eigenvectors.  start == 0: a cold solve (qt is overwritten).  start != 0: qt holds the
  *         result of an earlier call on matrices close to a (the same factors some steps
  *         earlier): the solve starts from W = qt a qt^T (float64 sums), and qt is updated.
  *         A matrix that fails (see `failed`) leaves its part of qt as it was.

@@ -1990,6 +1990,7 @@ int shampoo_root_inverse_warm(const float *a, int32_t n, int32_t batch, float ep
   const EigLayout e = eig_layout(n, batch, EIG_CHUNK_BYTES, 0, true);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % ALIGN) != 0 || workspace_bytes < e.bytes)
     return SHAMPOO_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(qt) % 16 != 0) return SHAMPOO_ERR_WORKSPACE;   // the kernels move it 16 bytes at a time
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (failed) {
     const int rc = launch_fill(reinterpret_cast<float *>(failed), 0.f, batch, s);

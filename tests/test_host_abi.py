@@ -243,6 +243,25 @@ def test_jacobi_pair_rejects_bad_arguments():
             B.shampoo_jacobi_pair(*args)
 
 
+def test_warm_root_inverse_rejects_bad_arguments_before_any_device_work():
+    """Argument errors of shampoo_root_inverse_warm come back before anything touches the GPU:
+    the pointers below are never dereferenced."""
+    L = B.lib()
+    ok_ptr, ws = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x100000)
+    big = 1 << 40
+
+    def call(a=ok_ptr, n=256, batch=2, eps=1e-12, r=0.25, x=ok_ptr, qt=ok_ptr, workspace=ws, nbytes=big):
+        return L.shampoo_root_inverse_warm(a, n, batch, eps, r, x, None, None, qt, 0, None, workspace, nbytes, None)
+
+    assert call(a=None) == -1 and call(x=None) == -1 and call(qt=None) == -1
+    assert call(n=0) == -2 and call(batch=0) == -2
+    assert call(n=128) == -7                      # the single-workgroup solver keeps no eigenvectors
+    assert call(eps=0.0) == -3 and call(r=-1.0) == -3
+    assert call(workspace=None) == -4 and call(workspace=ctypes.c_void_p(0x100004)) == -4
+    assert call(nbytes=1024) == -4
+    assert call(qt=ctypes.c_void_p(0x10004)) == -4   # the kernels move qt 16 bytes at a time
+
+
 # ---------------------------------------------------------------------------
 # the bound behind the block solver's exit after its float32 sweeps
 # ---------------------------------------------------------------------------
