@@ -20,6 +20,10 @@ One JSON line is printed:
   metric/value        milliseconds per (non-refresh) step, whole job, one GPU; next to it
                       `refresh_ms` (one root-inverse refresh of every factor, taken at the first
                       timed refresh) and `amortized_ms_per_step` = value + refresh_ms / f
+  later_refresh       after the timed steps the run goes on, untimed and with a fresh gradient set
+                      per step, to the next refresh (step f later) and times that one too: its
+                      factors are moving averages over many independent gradients, as at every
+                      refresh of a training run but the first (--no-later-refresh skips this)
   roofline            the dominant kernel: for blocks above 128 the second GEMM of the two-sided
                       preconditioning, P = T Rbar.  `achieved` is its ALGORITHMIC rate: 2 m n^2 flops
                       per block x blocks per launch / average launch duration, against the dense
@@ -227,6 +231,8 @@ def main():
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the short second run of the default workload on the float32 matrix cores")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-later-refresh", action="store_true",
+                    help="stop after the timed steps instead of going on to the next refresh and timing it")
     ap.add_argument("--skip-refresh", action="store_true",
                     help="number the steps from 4 so that no root refresh runs (roots stay the identity); "
                          "for counter runs of the per-step kernels only")
@@ -313,6 +319,22 @@ def main():
     stages = opt.get_timing()
     status = opt.status()
 
+    # on to the next refresh: the factors it sees are moving averages over many independent gradient sets
+    later = None
+    if not args.skip_refresh and not args.no_later_refresh:
+        t_next = base + f
+        for t in range(base + warm + args.steps, t_next + 1):
+            for g in pool[t % 2]:
+                g.copy_(torch.randn(g.shape, generator=gen, device=dev, dtype=torch.float32) * wk["sigma"])
+            if t == t_next:
+                torch.cuda.synchronize()
+                opt.get_timing()
+            opt.step(params, pool[t % 2], 0.01, t)
+        torch.cuda.synchronize()
+        later_ms = opt.get_timing()["root"][0]
+        later = {"at_step": t_next, "refresh_ms": later_ms, "amortized_ms_per_step": ms_per_step + later_ms / f,
+                 "status": opt.status()}
+
     alg_f, alg_p, exe_f, exe_p = flop_counts(table)
     st_ms = {k: v[0] / args.steps for k, v in stages.items()}
     # the dominant kernel is the second product of the preconditioning stage, P = T Rbar
@@ -394,6 +416,8 @@ def main():
         },
         "status": status,
     }
+    if later is not None:
+        out["later_refresh"] = later
     if x2 and default_shape and not args.no_secondary and not args.skip_refresh:
         out["fp32_matrix_cores"] = secondary_fp32(B, torch, wk, shapes, params, pool, alg_p2, args.steps)
     if not args.no_cpu_baseline:
